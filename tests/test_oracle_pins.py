@@ -1,0 +1,332 @@
+"""Pins for the CPU oracle: each test checks it against something that is not
+itself -- closed forms worked by hand, brute force, least-squares optimality,
+identities that follow from the objective (Sec. 2, Eq. 1 of the paper).  They
+are chosen so that a dropped term, a wrong sign or index, or a transposed
+operand in the oracle fails at least one of them."""
+import itertools
+import math
+
+import numpy as np
+import pytest
+
+from oracle import ptq_oracle as orc
+
+
+def _spd(n, rng, corr=0.9, t=None):
+    """A strongly correlated Hessian X^T X (so that compensation matters)."""
+    t = t or 3 * n
+    A = rng.standard_normal((n, n))
+    Z = rng.standard_normal((t, n))
+    X = Z @ (np.eye(n) + corr * A / math.sqrt(n))
+    X *= np.exp(rng.standard_normal(n))
+    return X.T @ X, X
+
+
+# ------------------------------------------------------------------ Hessian
+def test_hessian_brute_force():
+    rng = np.random.default_rng(1)
+    X = rng.standard_normal((37, 5))
+    H = orc.hessian(X, chunk=8)
+    for i in range(5):
+        for j in range(5):
+            s = 0.0
+            for t in range(37):
+                s += X[t, i] * X[t, j]
+            assert abs(H[i, j] - s) < 1e-12
+
+
+def test_hessian_closed_forms_and_accumulation():
+    t, n = 50, 7
+    H = orc.hessian(np.ones((t, n)))
+    assert np.array_equal(H, t * np.ones((n, n)))
+    # one-hot tokens: token k fires channel k % n with amplitude k+1
+    X = np.zeros((t, n))
+    for k in range(t):
+        X[k, k % n] = k + 1
+    H = orc.hessian(X)
+    expect = np.diag([sum((k + 1) ** 2 for k in range(t) if k % n == c) for c in range(n)])
+    assert np.array_equal(H, expect)
+    # accumulating two slabs equals one pass
+    rng = np.random.default_rng(2)
+    X = rng.standard_normal((64, 6))
+    H2 = orc.hessian(X[:40])
+    H2 = orc.hessian(X[40:], H2)
+    assert np.allclose(H2, orc.hessian(X), rtol=0, atol=1e-12)
+    # a transposed operand would give a 64x64 matrix
+    assert H2.shape == (6, 6)
+
+
+# ------------------------------------------------------------- damp + factor
+def test_damp_closed_form():
+    H = np.array([[2.0, 1.0, 0.0], [1.0, 4.0, 0.0], [0.0, 0.0, 0.0]])
+    Hd, dead = orc.damp(H, 0.5)
+    assert dead.tolist() == [False, False, True]
+    mean = (2.0 + 4.0 + 1.0) / 3.0
+    expect = np.array([[2.0, 1.0, 0.0], [1.0, 4.0, 0.0], [0.0, 0.0, 1.0]]) + 0.5 * mean * np.eye(3)
+    assert np.allclose(Hd, expect, rtol=0, atol=1e-15)
+    assert np.array_equal(H, np.array([[2.0, 1.0, 0.0], [1.0, 4.0, 0.0], [0.0, 0.0, 0.0]]))
+
+
+def test_factor_hand_worked_2x2():
+    # H = [[4,2],[2,3]], H^-1 = 1/8 [[3,-2],[-2,4]];  U^T U = H^-1, U upper:
+    # U11^2 = 3/8, U11 U12 = -1/4, U12^2 + U22^2 = 1/2.
+    U = orc.inverse_cholesky_upper(np.array([[4.0, 2.0], [2.0, 3.0]]))
+    u11 = math.sqrt(3.0 / 8.0)
+    u12 = -0.25 / u11
+    u22 = math.sqrt(0.5 - u12 * u12)
+    assert np.allclose(U, [[u11, u12], [0.0, u22]], rtol=0, atol=1e-15)
+    assert abs(u22 - 1 / math.sqrt(3.0)) < 1e-15
+
+
+def test_factor_hand_worked_3x3():
+    # H = R R^T with R upper, built from the last row upwards by hand; U = R^-1.
+    H = np.array([[4.0, 2.0, 0.0], [2.0, 5.0, 1.0], [0.0, 1.0, 3.0]])
+    r33 = math.sqrt(3.0)
+    r23 = 1.0 / r33
+    r13 = 0.0
+    r22 = math.sqrt(5.0 - r23 ** 2)
+    r12 = (2.0 - r13 * r23) / r22
+    r11 = math.sqrt(4.0 - r12 ** 2 - r13 ** 2)
+    u = np.array([[1 / r11, -r12 / (r11 * r22), (r12 * r23 - r13 * r22) / (r11 * r22 * r33)],
+                  [0.0, 1 / r22, -r23 / (r22 * r33)],
+                  [0.0, 0.0, 1 / r33]])
+    U = orc.inverse_cholesky_upper(H)
+    assert np.allclose(U, u, rtol=0, atol=1e-14)
+
+
+@pytest.mark.parametrize("n", [1, 5, 64, 200])
+def test_factor_properties_and_reversed_route(n):
+    rng = np.random.default_rng(n)
+    H, _ = _spd(n, rng)
+    Hd, _ = orc.damp(H, 0.01)
+    U = orc.inverse_cholesky_upper(Hd)
+    assert np.all(np.tril(U, -1) == 0) and np.all(np.diag(U) > 0)
+    assert np.allclose(U.T @ U @ Hd, np.eye(n), rtol=0, atol=1e-8)
+    # uniqueness: Cholesky of the index-reversed matrix, reversed back and
+    # inverted, is the same factor.
+    J = np.arange(n)[::-1]
+    Lr = np.linalg.cholesky(Hd[np.ix_(J, J)])
+    R = Lr[np.ix_(J, J)]
+    assert np.allclose(R @ R.T, Hd, rtol=0, atol=1e-12 * np.abs(Hd).max())
+    U2 = np.linalg.inv(R)
+    scale = np.abs(U).max()
+    assert np.allclose(U, U2, rtol=0, atol=1e-9 * scale)
+
+
+# ------------------------------------------------------------- quantize_layer
+def _on_grid_layer(rng, m, n, group, bits, pow2=True):
+    maxq = 2 ** bits - 1
+    codes = rng.integers(0, maxq + 1, size=(m, n))
+    ng = n // group
+    scales = 2.0 ** rng.integers(-8, -2, size=(m, ng)) if pow2 else \
+        rng.uniform(0.01, 0.1, size=(m, ng)).astype(np.float32).astype(np.float64)
+    zeros = rng.integers(1, maxq, size=(m, ng))
+    for r in range(m):                       # every group holds code 0 and maxq
+        for k in range(ng):
+            a, b = rng.choice(group, 2, replace=False)
+            codes[r, k * group + a] = 0
+            codes[r, k * group + b] = maxq
+    W = np.repeat(scales, group, axis=1) * (codes - np.repeat(zeros, group, axis=1))
+    return W, codes, scales, zeros
+
+
+@pytest.mark.parametrize("bits,group", [(2, 8), (3, 16), (4, 32), (8, 32)])
+def test_on_grid_recovery(bits, group):
+    rng = np.random.default_rng(bits * 100 + group)
+    m, n = 6, 64
+    W, codes, scales, zeros = _on_grid_layer(rng, m, n, group, bits)
+    H, _ = _spd(n, rng)
+    Hd, _ = orc.damp(H, 0.01)
+    U = orc.inverse_cholesky_upper(Hd)
+    out = orc.quantize_layer(W, U, bits, group)
+    assert np.array_equal(out["codes"], codes)
+    assert np.array_equal(out["scales"].astype(np.float64), scales)
+    assert np.array_equal(out["zeros"], zeros)
+    assert np.all(out["E"] == 0) and np.array_equal(out["Wq"], W)
+    rel, num, den = orc.layer_error(W, out["Wq"], H)
+    assert rel == 0.0 and num == 0.0 and den > 0
+
+
+def test_diagonal_hessian_is_round_to_nearest():
+    rng = np.random.default_rng(7)
+    m, n, group, bits = 9, 96, 32, 3
+    W = rng.standard_normal((m, n)) * 0.02
+    W[:, 5] *= 10
+    Hd = np.diag(rng.uniform(0.5, 50.0, n))
+    U = orc.inverse_cholesky_upper(Hd)
+    assert np.allclose(U, np.diag(1 / np.sqrt(np.diag(Hd))), rtol=1e-13, atol=0)
+    out = orc.quantize_layer(W, U, bits, group)
+    # textbook round-to-nearest written out with python scalars
+    maxq = 2 ** bits - 1
+    for r in range(m):
+        for k in range(n // group):
+            g = W[r, k * group:(k + 1) * group]
+            lo, hi = min(0.0, g.min()), max(0.0, g.max())
+            s = float(np.float32((hi - lo) / maxq))
+            z = round(-lo / s)               # python round is half-to-even
+            assert out["scales"][r, k] == np.float32(s) and out["zeros"][r, k] == z
+            for i, w in enumerate(g):
+                c = min(max(round(w / s) + z, 0), maxq)
+                assert out["codes"][r, k * group + i] == c
+    rtn = orc.round_to_nearest(W, bits, group)
+    assert np.array_equal(rtn["codes"], out["codes"])
+
+
+def test_degenerate_group_and_dead_column():
+    n, group, bits = 16, 8, 4
+    W = np.zeros((2, n))
+    W[1, 8:] = np.linspace(-0.3, 0.4, 8)
+    W[:, 3] = 5.0                                   # lives in a dead channel
+    dead = np.zeros(n, dtype=bool)
+    dead[3] = True
+    U = np.eye(n)
+    out = orc.quantize_layer(W, U, bits, group, dead=dead)
+    # all-zero group: range [-1, 1]; float32(2/15) lies above 2/15, so
+    # 1/scale is just below 7.5 and the zero-point is 7; code 7 -> q = 0
+    assert out["scales"][0, 0] == np.float32(2.0 / 15.0)
+    assert float(np.float32(2.0 / 15.0)) > 2.0 / 15.0
+    assert out["zeros"][0, 0] == 7 and np.all(out["codes"][0] == 7)
+    assert np.all(out["Wq"][0] == 0.0) and out["Wq"][1, 3] == 0.0
+
+
+def _schur_loss(Hd, d_head):
+    """min over the free tail of d^T Hd d with the head of d fixed."""
+    j = len(d_head)
+    n = Hd.shape[0]
+    if j == n:
+        return float(d_head @ Hd @ d_head)
+    Haa, Hab, Hbb = Hd[:j, :j], Hd[:j, j:], Hd[j:, j:]
+    S = Haa - Hab @ np.linalg.solve(Hbb, Hab.T)
+    return float(d_head @ S @ d_head)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_conditional_optimality(seed):
+    """Each code minimises the damped loss over its own column, given the
+    earlier codes, when the later columns are left continuous and optimal.
+    The check uses only H_d (a Schur complement), never U."""
+    rng = np.random.default_rng(100 + seed)
+    n, bits, group = 6, 3, 3
+    maxq = 2 ** bits - 1
+    H, _ = _spd(n, rng)
+    Hd, _ = orc.damp(H, 0.01)
+    U = orc.inverse_cholesky_upper(Hd)
+    W = rng.standard_normal((4, n)) * 0.05
+    out = orc.quantize_layer(W, U, bits, group)
+    for r in range(W.shape[0]):
+        for j in range(n):
+            s = float(out["scales"][r, j // group])
+            z = float(out["zeros"][r, j // group])
+            head = W[r, :j] - out["Wq"][r, :j]
+            losses = [_schur_loss(Hd, np.append(head, W[r, j] - s * (c - z)))
+                      for c in range(maxq + 1)]
+            best = int(np.argmin(losses))
+            chosen = int(out["codes"][r, j])
+            assert losses[chosen] <= losses[best] * (1 + 1e-9) + 1e-18, (r, j, chosen, best)
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 4])
+def test_brute_force_small(n):
+    rng = np.random.default_rng(40 + n)
+    bits, group = 2, n
+    maxq = 3
+    worse = 0
+    for trial in range(20):
+        H, _ = _spd(n, rng, t=n + 2)
+        Hd, _ = orc.damp(H, 0.01)
+        U = orc.inverse_cholesky_upper(Hd)
+        W = rng.standard_normal((1, n)) * 0.1
+        out = orc.quantize_layer(W, U, bits, group)
+        s = float(out["scales"][0, 0])
+        z = float(out["zeros"][0, 0])
+        d = W[0] - out["Wq"][0]
+        got = float(d @ Hd @ d)
+        best = min(float((W[0] - s * (np.array(c) - z)) @ Hd @ (W[0] - s * (np.array(c) - z)))
+                   for c in itertools.product(range(maxq + 1), repeat=n))
+        assert best <= got * (1 + 1e-12) + 1e-18
+        if n == 1:
+            assert abs(best - got) <= 1e-12 * got + 1e-18
+        # the greedy result is also never worse than plain rounding here
+        rtn = orc.round_to_nearest(W, bits, group)
+        dr = W[0] - rtn["Wq"][0]
+        worse += float(dr @ Hd @ dr) < got * (1 - 1e-12)
+    assert worse <= 2
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_error_identity(seed):
+    """(W - Wq) = E U row-wise, hence tr(D H_d D^T) = sum e^2."""
+    rng = np.random.default_rng(200 + seed)
+    m, n, bits, group = 5, 48, 4, 16
+    H, _ = _spd(n, rng)
+    Hd, _ = orc.damp(H, 0.01)
+    U = orc.inverse_cholesky_upper(Hd)
+    W = rng.standard_normal((m, n)) * 0.02
+    out = orc.quantize_layer(W, U, bits, group)
+    D = W - out["Wq"]
+    assert np.allclose(D, out["E"] @ U, rtol=0, atol=1e-12 * np.abs(W).max())
+    lhs = np.einsum("ij,ij->i", D @ Hd, D)
+    assert np.allclose(lhs, out["row_err2"], rtol=1e-9, atol=0)
+    assert np.allclose(out["Wq"], orc.dequantize(out["codes"], out["scales"], out["zeros"], group))
+    # codes do not depend on a positive rescale of H (damping is relative)
+    Hd2, _ = orc.damp(7.5 * H, 0.01)
+    out2 = orc.quantize_layer(W, orc.inverse_cholesky_upper(Hd2), bits, group)
+    assert np.array_equal(out["codes"], out2["codes"])
+
+
+def test_not_worse_than_rtn_on_correlated_layers():
+    wins = 0
+    total = 12
+    for seed in range(total):
+        rng = np.random.default_rng(300 + seed)
+        m, n, bits, group = 16, 64, 3, 32
+        H, X = _spd(n, rng, t=80)
+        Hd, dead = orc.damp(H, 0.01)
+        U = orc.inverse_cholesky_upper(Hd)
+        W = rng.standard_normal((m, n)) * 0.02
+        a = orc.layer_error(W, orc.quantize_layer(W, U, bits, group)["Wq"], H)[0]
+        b = orc.layer_error(W, orc.round_to_nearest(W, bits, group)["Wq"], H)[0]
+        wins += a <= b
+    assert wins == total
+
+
+def test_forced_decisions_are_applied():
+    rng = np.random.default_rng(5)
+    n, bits, group = 32, 4, 16
+    H, _ = _spd(n, rng)
+    U = orc.inverse_cholesky_upper(orc.damp(H, 0.01)[0])
+    W = rng.standard_normal((3, n)) * 0.02
+    base = orc.quantize_layer(W, U, bits, group, want_pre=True)
+    c = int(base["codes"][1, 5])
+    alt = c + 1 if c < 15 else c - 1
+    out = orc.quantize_layer(W, U, bits, group, forced={("code", 1, 5): alt})
+    assert out["codes"][1, 5] == alt
+    assert np.array_equal(out["codes"][[0, 2]], base["codes"][[0, 2]])
+    assert np.array_equal(out["codes"][1, :5], base["codes"][1, :5])
+    z = int(base["zeros"][2, 1])
+    out = orc.quantize_layer(W, U, bits, group, forced={("zero", 2, 1): z + 1})
+    assert out["zeros"][2, 1] == z + 1 and np.array_equal(out["codes"][2, :16], base["codes"][2, :16])
+
+
+# ------------------------------------------------------------- layer error
+def test_trace_identity_and_permutation_covariance():
+    rng = np.random.default_rng(11)
+    m, n = 7, 24
+    H, X = _spd(n, rng)
+    W = rng.standard_normal((m, n))
+    Wq = W + 0.05 * rng.standard_normal((m, n))
+    rel, num, den = orc.layer_error(W, Wq, H)
+    assert abs(rel - orc.layer_error_from_activations(W, Wq, X)) < 1e-12
+    # num is a plain quadratic form
+    D = W - Wq
+    s = sum(D[r, i] * H[i, j] * D[r, j] for r in range(m) for i in range(n) for j in range(n))
+    assert abs(num - s) < 1e-9 * abs(s)
+    # the loss is the same in a permuted / rotated basis (Sec. 3.2, Eq. 8)
+    Q, _ = np.linalg.qr(rng.standard_normal((n, n)))
+    rel2 = orc.layer_error(W @ Q, Wq @ Q, Q.T @ H @ Q)[0]
+    assert abs(rel - rel2) < 1e-10
+    p = rng.permutation(n)
+    rel3 = orc.layer_error(W[:, p], Wq[:, p], H[np.ix_(p, p)])[0]
+    assert abs(rel - rel3) < 1e-12
+    Hu = np.triu(H) + 123.0 * np.tril(np.ones((n, n)), -1)
+    assert np.array_equal(orc.symmetrize_from_upper(Hu), np.triu(H) + np.triu(H, 1).T)
