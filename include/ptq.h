@@ -1,0 +1,169 @@
+/*
+ * libptq -- layer-wise post-training weight quantization on one MI355X (gfx950).
+ *
+ * The library solves, for one linear layer with weight W (m x n, n = input
+ * channels) and calibration input X (t tokens x n channels),
+ *
+ *        min_Q || W X^T - Q X^T ||_F        (paper Sec. 2, Eq. 1; Sec. 3.2, Eq. 8)
+ *
+ * by the column-sequential quantize-and-compensate scheme the paper uses as
+ * its quantization step (Sec. 2, "Solution to O1" item (a); Algorithm 1,
+ * stage C): accumulate the proxy Hessian H = X^T X, factor the damped inverse,
+ * walk over the columns of W, and report the layer error.
+ *
+ * Conventions for every call
+ *   - All matrices are row-major with an explicit leading dimension (in
+ *     elements).  Every data pointer is a DEVICE pointer unless stated.
+ *   - The caller owns every buffer, including the workspace whose size
+ *     ptq_workspace_bytes() returns; the library allocates nothing, keeps no
+ *     state between calls and never frees anything.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
+ *     default stream) and the call returns without waiting for it.
+ *   - The return value reports errors the host can see (bad arguments, shapes,
+ *     workspace too small, a failed launch).  Conditions only the device can
+ *     see are written to a caller-provided device `info` array.
+ *   - Workspaces must be 256-byte aligned.
+ */
+#ifndef PTQ_H
+#define PTQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  PTQ_OK = 0,
+  PTQ_ERR_ARG = 1,       /* null pointer, negative damp, bits outside [2,8]  */
+  PTQ_ERR_SHAPE = 2,     /* sizes / leading dimensions / divisibility         */
+  PTQ_ERR_DTYPE = 3,     /* storage type not supported by this call           */
+  PTQ_ERR_WORKSPACE = 4, /* workspace missing, misaligned or too small        */
+  PTQ_ERR_NOT_SPD = 5,   /* only ever written to `info`, never returned       */
+  PTQ_ERR_HIP = 6        /* a HIP runtime call failed                         */
+} ptq_status;
+
+typedef enum { PTQ_F32 = 0, PTQ_BF16 = 1, PTQ_F64 = 2 } ptq_dtype;
+
+typedef enum {
+  PTQ_OP_HESSIAN = 0,
+  PTQ_OP_CHOLESKY_INV = 1,
+  PTQ_OP_QUANTIZE = 2,
+  PTQ_OP_LAYER_ERROR = 3
+} ptq_op;
+
+typedef void* ptq_stream; /* hipStream_t */
+
+/* Static, NUL-terminated description of a status code. */
+const char* ptq_status_string(ptq_status s);
+
+/*
+ * Bytes of device workspace the given call needs for these sizes
+ * (m, t, block are ignored by ops that do not use them; pass 0).
+ * `bytes` is a host pointer.
+ */
+ptq_status ptq_workspace_bytes(ptq_op op, int64_t m, int64_t n, int64_t t, int64_t block,
+                               size_t* bytes);
+
+/*
+ * Proxy Hessian accumulation (Sec. 2, Eq. 1:  H = E[x x^T], taken as the raw
+ * sum over tokens; Algorithm 1 computes it once per layer).
+ *
+ *   H[i][j] += sum_k X[k][i] * X[k][j]      for all 0 <= i <= j < n
+ *
+ * H    n x n float64, leading dimension ldh >= n.  Accumulated in place, so the
+ *      caller zeroes it before the first chunk of tokens.  Only the upper
+ *      triangle (i <= j) is defined on return; entries below the diagonal may
+ *      be left untouched or overwritten with their mirror values.
+ * X    t x n, tokens by channels, PTQ_BF16 (raw bfloat16 bits) or PTQ_F32,
+ *      leading dimension ldx >= n.  Read only.  bf16 needs n % 8 == 0 and
+ *      ldx % 8 == 0 and a 16-byte aligned X (vector loads); f32 has no such rule.
+ * t may be 0 (no-op).  Products of bf16 inputs are exact; partial sums run in
+ * float32 over at most 8192 tokens and are added to H in float64.
+ * Errors: PTQ_ERR_ARG (null), PTQ_ERR_SHAPE, PTQ_ERR_DTYPE, PTQ_ERR_WORKSPACE.
+ */
+ptq_status ptq_hessian_accumulate(double* H, int64_t ldh, const void* X, ptq_dtype xdt, int64_t t,
+                                  int64_t n, int64_t ldx, void* ws, size_t ws_bytes,
+                                  ptq_stream stream);
+
+/*
+ * Damped Cholesky factor of the inverse Hessian -- the coefficients with
+ * which a column's quantization error is pushed onto the later columns
+ * (the paper delegates this step to its quantization tool, Algorithm 1 stage C;
+ * the factor is the one of the damped inverse).
+ *
+ *   H'   = H with H_jj = 1 wherever H_jj == 0 (a channel that never fired)
+ *   H_d  = H' + damp * mean_j(H'_jj) * I
+ *   U    = the upper-triangular matrix with positive diagonal, U^T U = H_d^{-1}
+ *
+ * H          n x n float64, only its upper triangle is read.  Not modified.
+ * U          n x n float64 output, ldu >= n; the strict lower triangle is zeroed.
+ * dead_mask  n bytes output, may be NULL: 1 where H_jj == 0.
+ * info       2 x int32 device output, required: {PTQ_OK, 0}, or
+ *            {PTQ_ERR_NOT_SPD, j} when the pivot of column j (in the order of
+ *            elimination, j counted in H's own indexing) was not positive;
+ *            U is then undefined.
+ * Errors: PTQ_ERR_ARG (null, damp < 0 or not finite), PTQ_ERR_SHAPE, PTQ_ERR_WORKSPACE.
+ */
+ptq_status ptq_damped_cholesky_inv(const double* H, int64_t ldh, int64_t n, double damp, double* U,
+                                   int64_t ldu, uint8_t* dead_mask, int32_t* info, void* ws,
+                                   size_t ws_bytes, ptq_stream stream);
+
+/*
+ * Blocked column-by-column quantization with error compensation (Sec. 2,
+ * item (a): columns are quantized one after another and each column's error
+ * is compensated in the columns that follow).  For every row of W and
+ * j = 0 .. n-1, with w the row's current (already compensated) values:
+ *
+ *   when j is the first column of a group of `group` columns:
+ *       lo = min(0, min w[group]),  hi = max(0, max w[group]),
+ *       (lo, hi) = (-1, 1) if lo == hi,
+ *       scale = float32((hi - lo) / (2^bits - 1)),  zero = rne(-lo / scale)
+ *   code_j = clamp(rne(w_j / scale) + zero, 0, 2^bits - 1)
+ *   q_j    = scale * (code_j - zero)
+ *   e_j    = (w_j - q_j) / U_jj
+ *   w_k   -= e_j * U_jk            for all k > j
+ *
+ * (rne = round half to even).  The update of the columns outside the current
+ * block of `block` columns is applied lazily, once per block; `block` changes
+ * the order of summation only.
+ *
+ * W          m x n, PTQ_F32 / PTQ_BF16 / PTQ_F64, ldw >= n.  Not modified.
+ * U          n x n float64 upper-triangular factor from ptq_damped_cholesky_inv.
+ * dead_mask  n bytes or NULL; columns with mask 1 are treated as all-zero.
+ * bits       2..8.   group > 0 with n % group == 0.
+ * block      > 0, a multiple of 16, at most 256, and block % group == 0 or
+ *            group % block == 0.  n need not be a multiple of block.
+ * codes      m x n uint8 output, one code per byte, row-major, ld = n.
+ * scales     m x (n/group) float32 output.   zeros  m x (n/group) uint8 output.
+ * Wq         m x n float64 output with ld = n, or NULL: the dequantized weights.
+ * row_err2   m float64 output or NULL: sum_j e_j^2 of each row.
+ * Errors: PTQ_ERR_ARG, PTQ_ERR_SHAPE, PTQ_ERR_DTYPE, PTQ_ERR_WORKSPACE.
+ */
+ptq_status ptq_quantize_layer(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m, int64_t n,
+                              const double* U, int64_t ldu, const uint8_t* dead_mask, int bits,
+                              int group, int block, uint8_t* codes, float* scales, uint8_t* zeros,
+                              double* Wq, double* row_err2, void* ws, size_t ws_bytes,
+                              ptq_stream stream);
+
+/*
+ * Relative layer error under the proxy-Hessian loss (Sec. 2, Eq. 1):
+ *
+ *   num = tr((W - Wq) H (W - Wq)^T),  den = tr(W H W^T),  rel = sqrt(num / den)
+ *
+ * which equals ||W X^T - Wq X^T||_F / ||W X^T||_F for H = X^T X.  Pass the
+ * undamped H; only its upper triangle is read.
+ *
+ * W   m x n, PTQ_F32 / PTQ_BF16 / PTQ_F64, ldw >= n.   Wq  m x n float64, ld = n.
+ * out 3 x float64 device output: {rel, num, den}.
+ * Errors: PTQ_ERR_ARG, PTQ_ERR_SHAPE, PTQ_ERR_DTYPE, PTQ_ERR_WORKSPACE.
+ */
+ptq_status ptq_layer_error(const void* W, ptq_dtype wdt, int64_t ldw, const double* Wq, int64_t m,
+                           int64_t n, const double* H, int64_t ldh, double* out, void* ws,
+                           size_t ws_bytes, ptq_stream stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PTQ_H */

@@ -1,0 +1,6 @@
+"""MI355X-native layer-wise post-training quantization solve (libptq bindings)."""
+from .binding import (  # noqa: F401
+    PTQ_BF16, PTQ_F32, PTQ_F64, PtqError, lib_path, load_library,
+    ptq_damped_cholesky_inv, ptq_hessian_accumulate, ptq_layer_error,
+    ptq_quantize_layer, ptq_status_string, ptq_workspace_bytes,
+)

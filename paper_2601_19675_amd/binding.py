@@ -1,0 +1,168 @@
+"""Thin ctypes binding of libptq's C ABI (include/ptq.h).
+
+Argument marshalling only: every function takes torch tensors that already
+live on the GPU (torch is used for device memory and streams, nothing else),
+passes their raw pointers, sizes and the current HIP stream to the entry point
+of the same name, and raises PtqError on a non-zero status.  There is no CPU
+or PyTorch fallback: without the built library every call fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+PTQ_F32, PTQ_BF16, PTQ_F64 = 0, 1, 2
+OP_HESSIAN, OP_CHOLESKY_INV, OP_QUANTIZE, OP_LAYER_ERROR = 0, 1, 2, 3
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+
+class PtqError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {ptq_status_string(status)} (status {status})")
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libptq.so")
+
+
+def load_library() -> ctypes.CDLL:
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = lib_path()
+    if not os.path.exists(path):
+        raise RuntimeError(
+            f"{path} is missing: build it with `python -m paper_2601_19675_amd.build` "
+            "(there is no fallback path)")
+    lib = ctypes.CDLL(path)
+    c = ctypes
+    i64, vp, sz = c.c_int64, c.c_void_p, c.c_size_t
+    lib.ptq_status_string.restype = c.c_char_p
+    lib.ptq_status_string.argtypes = [c.c_int]
+    lib.ptq_workspace_bytes.restype = c.c_int
+    lib.ptq_workspace_bytes.argtypes = [c.c_int, i64, i64, i64, i64, c.POINTER(sz)]
+    lib.ptq_hessian_accumulate.restype = c.c_int
+    lib.ptq_hessian_accumulate.argtypes = [vp, i64, vp, c.c_int, i64, i64, i64, vp, sz, vp]
+    lib.ptq_damped_cholesky_inv.restype = c.c_int
+    lib.ptq_damped_cholesky_inv.argtypes = [vp, i64, i64, c.c_double, vp, i64, vp, vp, vp, sz, vp]
+    lib.ptq_quantize_layer.restype = c.c_int
+    lib.ptq_quantize_layer.argtypes = [vp, c.c_int, i64, i64, i64, vp, i64, vp, c.c_int, c.c_int,
+                                       c.c_int, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.ptq_layer_error.restype = c.c_int
+    lib.ptq_layer_error.argtypes = [vp, c.c_int, i64, vp, i64, i64, vp, i64, vp, vp, sz, vp]
+    _LIB = lib
+    return lib
+
+
+def ptq_status_string(status: int) -> str:
+    return load_library().ptq_status_string(int(status)).decode()
+
+
+def ptq_workspace_bytes(op: int, m: int = 0, n: int = 0, t: int = 0, block: int = 0) -> int:
+    out = ctypes.c_size_t(0)
+    rc = load_library().ptq_workspace_bytes(op, m, n, t, block, ctypes.byref(out))
+    if rc:
+        raise PtqError(rc, "ptq_workspace_bytes")
+    return int(out.value)
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t) -> int | None:
+    return None if t is None else t.data_ptr()
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return PTQ_F32
+    if t.dtype == torch.bfloat16:
+        return PTQ_BF16
+    if t.dtype == torch.float64:
+        return PTQ_F64
+    raise PtqError(3, f"tensor dtype {t.dtype}")
+
+
+def _check_dev(*ts):
+    for t in ts:
+        if t is not None and (not t.is_cuda):
+            raise ValueError("libptq takes device tensors only")
+
+
+def _ws(ws: torch.Tensor | None, need: int, like: torch.Tensor) -> torch.Tensor:
+    if ws is None:
+        ws = torch.empty(max(need, 256), dtype=torch.uint8, device=like.device)
+    return ws
+
+
+def ptq_hessian_accumulate(H: torch.Tensor, X: torch.Tensor, ws: torch.Tensor | None = None) -> None:
+    """H[upper] += X^T X.  H: n x n float64; X: t x n bfloat16 or float32."""
+    _check_dev(H, X)
+    t, n = X.shape
+    assert H.dtype == torch.float64 and H.shape == (n, n) and H.stride(1) == 1 and X.stride(1) == 1
+    ws = _ws(ws, ptq_workspace_bytes(OP_HESSIAN, 0, n, t), H)
+    rc = load_library().ptq_hessian_accumulate(H.data_ptr(), H.stride(0), X.data_ptr(), _dtype_code(X), t,
+                                               n, X.stride(0), ws.data_ptr(), ws.numel(), _stream())
+    if rc:
+        raise PtqError(rc, "ptq_hessian_accumulate")
+
+
+def ptq_damped_cholesky_inv(H: torch.Tensor, damp: float, U: torch.Tensor,
+                            dead_mask: torch.Tensor | None, info: torch.Tensor,
+                            ws: torch.Tensor | None = None) -> None:
+    """U <- upper factor with U^T U = (H' + damp mean(diag H') I)^-1; info: int32[2] on device."""
+    _check_dev(H, U, dead_mask, info)
+    n = H.shape[0]
+    assert H.dtype == torch.float64 and U.dtype == torch.float64 and info.dtype == torch.int32
+    assert H.stride(1) == 1 and U.stride(1) == 1 and U.shape == (n, n) and info.numel() >= 2
+    assert dead_mask is None or (dead_mask.dtype == torch.uint8 and dead_mask.numel() >= n)
+    ws = _ws(ws, ptq_workspace_bytes(OP_CHOLESKY_INV, 0, n), H)
+    rc = load_library().ptq_damped_cholesky_inv(H.data_ptr(), H.stride(0), n, float(damp), U.data_ptr(),
+                                                U.stride(0), _ptr(dead_mask), info.data_ptr(),
+                                                ws.data_ptr(), ws.numel(), _stream())
+    if rc:
+        raise PtqError(rc, "ptq_damped_cholesky_inv")
+
+
+def ptq_quantize_layer(W: torch.Tensor, U: torch.Tensor, dead_mask: torch.Tensor | None, bits: int,
+                       group: int, block: int, codes: torch.Tensor, scales: torch.Tensor,
+                       zeros: torch.Tensor, Wq: torch.Tensor | None = None,
+                       row_err2: torch.Tensor | None = None, ws: torch.Tensor | None = None) -> None:
+    """Column-sequential quantize + compensate of W (m x n) with factor U."""
+    _check_dev(W, U, dead_mask, codes, scales, zeros, Wq, row_err2)
+    m, n = W.shape
+    assert W.stride(1) == 1 and U.stride(1) == 1 and U.dtype == torch.float64
+    assert codes.dtype == torch.uint8 and codes.is_contiguous() and codes.shape == (m, n)
+    if group > 0 and n % group == 0:
+        assert scales.dtype == torch.float32 and scales.is_contiguous() and scales.shape == (m, n // group)
+        assert zeros.dtype == torch.uint8 and zeros.is_contiguous() and zeros.shape == (m, n // group)
+    assert Wq is None or (Wq.dtype == torch.float64 and Wq.is_contiguous() and Wq.shape == (m, n))
+    assert row_err2 is None or (row_err2.dtype == torch.float64 and row_err2.numel() >= m)
+    ws = _ws(ws, ptq_workspace_bytes(OP_QUANTIZE, m, n), W)
+    rc = load_library().ptq_quantize_layer(W.data_ptr(), _dtype_code(W), W.stride(0), m, n, U.data_ptr(),
+                                           U.stride(0), _ptr(dead_mask), bits, group, block,
+                                           codes.data_ptr(), scales.data_ptr(), zeros.data_ptr(), _ptr(Wq),
+                                           _ptr(row_err2), ws.data_ptr(), ws.numel(), _stream())
+    if rc:
+        raise PtqError(rc, "ptq_quantize_layer")
+
+
+def ptq_layer_error(W: torch.Tensor, Wq: torch.Tensor, H: torch.Tensor, out: torch.Tensor,
+                    ws: torch.Tensor | None = None) -> None:
+    """out[0:3] <- (rel, num, den) of the proxy-Hessian layer error."""
+    _check_dev(W, Wq, H, out)
+    m, n = W.shape
+    assert Wq.dtype == torch.float64 and Wq.is_contiguous() and Wq.shape == (m, n)
+    assert H.dtype == torch.float64 and H.stride(1) == 1 and out.dtype == torch.float64 and out.numel() >= 3
+    ws = _ws(ws, ptq_workspace_bytes(OP_LAYER_ERROR, m, n), W)
+    rc = load_library().ptq_layer_error(W.data_ptr(), _dtype_code(W), W.stride(0), Wq.data_ptr(), m, n,
+                                        H.data_ptr(), H.stride(0), out.data_ptr(), ws.data_ptr(),
+                                        ws.numel(), _stream())
+    if rc:
+        raise PtqError(rc, "ptq_layer_error")

@@ -1,0 +1,60 @@
+// Shared declarations for the gfx950 kernels of libptq (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "../../include/ptq.h"
+
+namespace ptq {
+
+typedef __attribute__((__vector_size__(4 * sizeof(double)))) double f64x4;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+
+constexpr int kWave = 64;
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) {
+  return __uint_as_float(static_cast<uint32_t>(b) << 16);
+}
+
+// Element of a stored weight / activation matrix widened exactly to float64.
+template <int DT>
+__device__ __forceinline__ double load_as_f64(const void* p, int64_t idx) {
+  if constexpr (DT == PTQ_F32) {
+    return static_cast<double>(static_cast<const float*>(p)[idx]);
+  } else if constexpr (DT == PTQ_BF16) {
+    return static_cast<double>(bf16_bits_to_f32(static_cast<const uint16_t*>(p)[idx]));
+  } else {
+    return static_cast<const double*>(p)[idx];
+  }
+}
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline size_t align_up(size_t a, size_t b) { return (a + b - 1) / b * b; }
+
+#define PTQ_HIP_CHECK_LAUNCH()                         \
+  do {                                                 \
+    if (hipGetLastError() != hipSuccess) return PTQ_ERR_HIP; \
+  } while (0)
+
+// ---- per-op host entry points (defined in the .hip files) -------------------
+size_t hessian_workspace_bytes(int64_t n, int64_t t);
+ptq_status hessian_launch(double* H, int64_t ldh, const void* X, ptq_dtype xdt, int64_t t, int64_t n,
+                          int64_t ldx, void* ws, size_t ws_bytes, hipStream_t s);
+
+size_t cholesky_workspace_bytes(int64_t n);
+ptq_status cholesky_launch(const double* H, int64_t ldh, int64_t n, double damp, double* U,
+                           int64_t ldu, uint8_t* dead_mask, int32_t* info, void* ws, size_t ws_bytes,
+                           hipStream_t s);
+
+size_t quantize_workspace_bytes(int64_t m, int64_t n);
+ptq_status quantize_launch(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m, int64_t n,
+                           const double* U, int64_t ldu, const uint8_t* dead_mask, int bits, int group,
+                           int block, uint8_t* codes, float* scales, uint8_t* zeros, double* Wq,
+                           double* row_err2, void* ws, size_t ws_bytes, hipStream_t s);
+
+size_t layer_error_workspace_bytes(int64_t m, int64_t n);
+ptq_status layer_error_launch(const void* W, ptq_dtype wdt, int64_t ldw, const double* Wq, int64_t m,
+                              int64_t n, const double* H, int64_t ldh, double* out, void* ws,
+                              size_t ws_bytes, hipStream_t s);
+
+}  // namespace ptq

@@ -1,0 +1,101 @@
+// C ABI of libptq: argument checks, then the per-step launchers.
+#include "common.h"
+
+#include <cmath>
+
+using namespace ptq;
+
+namespace {
+bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) != 0; }
+bool ws_bad(const void* ws, size_t have, size_t need) {
+  return need > 0 && (ws == nullptr || misaligned(ws, 256) || have < need);
+}
+bool dtype_ok(ptq_dtype d) { return d == PTQ_F32 || d == PTQ_BF16 || d == PTQ_F64; }
+}  // namespace
+
+extern "C" {
+
+const char* ptq_status_string(ptq_status s) {
+  switch (s) {
+    case PTQ_OK: return "ok";
+    case PTQ_ERR_ARG: return "invalid argument";
+    case PTQ_ERR_SHAPE: return "invalid shape or leading dimension";
+    case PTQ_ERR_DTYPE: return "unsupported storage type";
+    case PTQ_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case PTQ_ERR_NOT_SPD: return "matrix not positive definite";
+    case PTQ_ERR_HIP: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+ptq_status ptq_workspace_bytes(ptq_op op, int64_t m, int64_t n, int64_t t, int64_t block, size_t* bytes) {
+  (void)block;
+  if (!bytes) return PTQ_ERR_ARG;
+  if (m < 0 || n < 0 || t < 0) return PTQ_ERR_SHAPE;
+  switch (op) {
+    case PTQ_OP_HESSIAN: *bytes = hessian_workspace_bytes(n, t); return PTQ_OK;
+    case PTQ_OP_CHOLESKY_INV: *bytes = cholesky_workspace_bytes(n); return PTQ_OK;
+    case PTQ_OP_QUANTIZE: *bytes = quantize_workspace_bytes(m, n); return PTQ_OK;
+    case PTQ_OP_LAYER_ERROR: *bytes = layer_error_workspace_bytes(m, n); return PTQ_OK;
+  }
+  return PTQ_ERR_ARG;
+}
+
+ptq_status ptq_hessian_accumulate(double* H, int64_t ldh, const void* X, ptq_dtype xdt, int64_t t,
+                                  int64_t n, int64_t ldx, void* ws, size_t ws_bytes, ptq_stream stream) {
+  if (t < 0 || n < 0 || ldh < n || ldx < n || n > INT32_MAX / 2) return PTQ_ERR_SHAPE;
+  if (xdt != PTQ_F32 && xdt != PTQ_BF16) return PTQ_ERR_DTYPE;
+  if (t == 0 || n == 0) return PTQ_OK;
+  if (!H || !X) return PTQ_ERR_ARG;
+  if (xdt == PTQ_BF16) {
+    if (n % 8 != 0 || ldx % 8 != 0) return PTQ_ERR_SHAPE;
+    if (misaligned(X, 16)) return PTQ_ERR_ARG;
+  }
+  if (ws_bad(ws, ws_bytes, hessian_workspace_bytes(n, t))) return PTQ_ERR_WORKSPACE;
+  return hessian_launch(H, ldh, X, xdt, t, n, ldx, ws, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+ptq_status ptq_damped_cholesky_inv(const double* H, int64_t ldh, int64_t n, double damp, double* U,
+                                   int64_t ldu, uint8_t* dead_mask, int32_t* info, void* ws,
+                                   size_t ws_bytes, ptq_stream stream) {
+  if (n < 0 || ldh < n || ldu < n || n > INT32_MAX / 2) return PTQ_ERR_SHAPE;
+  if (!(damp >= 0.0) || !std::isfinite(damp)) return PTQ_ERR_ARG;
+  if (n == 0) return PTQ_OK;
+  if (!H || !U || !info) return PTQ_ERR_ARG;
+  if (ws_bad(ws, ws_bytes, cholesky_workspace_bytes(n))) return PTQ_ERR_WORKSPACE;
+  return cholesky_launch(H, ldh, n, damp, U, ldu, dead_mask, info, ws, ws_bytes,
+                         static_cast<hipStream_t>(stream));
+}
+
+ptq_status ptq_quantize_layer(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m, int64_t n,
+                              const double* U, int64_t ldu, const uint8_t* dead_mask, int bits, int group,
+                              int block, uint8_t* codes, float* scales, uint8_t* zeros, double* Wq,
+                              double* row_err2, void* ws, size_t ws_bytes, ptq_stream stream) {
+  if (bits < 2 || bits > 8) return PTQ_ERR_ARG;
+  if (!dtype_ok(wdt)) return PTQ_ERR_DTYPE;
+  if (m < 0 || n < 0 || ldw < n || ldu < n || m > INT32_MAX / 2 || n > INT32_MAX / 2) return PTQ_ERR_SHAPE;
+  if (group <= 0 || block <= 0 || n % group != 0) return PTQ_ERR_SHAPE;
+  if (block % 16 != 0 || block > 256) return PTQ_ERR_SHAPE;
+  if (block % group != 0 && group % block != 0) return PTQ_ERR_SHAPE;
+  // groups start on 16-column mini-block boundaries and must fit one block
+  if (group % 16 != 0 || group > 256) return PTQ_ERR_SHAPE;
+  if (m == 0 || n == 0) return PTQ_OK;
+  if (!W || !U || !codes || !scales || !zeros) return PTQ_ERR_ARG;
+  if (ws_bad(ws, ws_bytes, quantize_workspace_bytes(m, n))) return PTQ_ERR_WORKSPACE;
+  return quantize_launch(W, wdt, ldw, m, n, U, ldu, dead_mask, bits, group, block, codes, scales, zeros,
+                         Wq, row_err2, ws, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+ptq_status ptq_layer_error(const void* W, ptq_dtype wdt, int64_t ldw, const double* Wq, int64_t m,
+                           int64_t n, const double* H, int64_t ldh, double* out, void* ws,
+                           size_t ws_bytes, ptq_stream stream) {
+  if (!dtype_ok(wdt)) return PTQ_ERR_DTYPE;
+  if (m <= 0 || n <= 0 || ldw < n || ldh < n || m > INT32_MAX / 2 || n > INT32_MAX / 2)
+    return PTQ_ERR_SHAPE;
+  if (!W || !Wq || !H || !out) return PTQ_ERR_ARG;
+  if (ws_bad(ws, ws_bytes, layer_error_workspace_bytes(m, n))) return PTQ_ERR_WORKSPACE;
+  return layer_error_launch(W, wdt, ldw, Wq, m, n, H, ldh, out, ws, ws_bytes,
+                            static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

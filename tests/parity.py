@@ -1,0 +1,128 @@
+"""Helpers shared by the GPU parity tests: tensor marshalling and the
+near-tie protocol that compares GPU codes / scales / zeros with the oracle.
+
+The column recurrence is chaotic per row: one code that rounds the other way
+changes every later code of that row.  The acceptance rule is therefore
+applied decision by decision, in the order the algorithm takes them (for each
+group: scale, zero-point, then the group's codes).  At the first decision
+where GPU and oracle differ, the oracle's pre-rounding value must lie within
+`tol` of the rounding boundary and the GPU must have taken the neighbouring
+value; that decision is then forced in the oracle, the row is solved again,
+and the comparison continues.  Anything else is an unflagged mismatch.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle import ptq_oracle as orc
+from ptq_workloads import to_f64
+
+
+def to_device(a: np.ndarray) -> torch.Tensor:
+    """Stored numpy tensor (uint16 = bf16 bits, float32, float64, uint8) -> cuda tensor."""
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def hessian_errors(H_gpu: np.ndarray, H_ref: np.ndarray):
+    """(Frobenius-relative error, max entry error scaled by sqrt(H_ii H_jj)) on the upper triangle."""
+    iu = np.triu_indices_from(H_ref)
+    d = H_gpu[iu] - H_ref[iu]
+    fro = np.linalg.norm(d) / np.linalg.norm(H_ref[iu])
+    dg = np.sqrt(np.abs(np.diag(H_ref)))
+    sc = np.outer(dg, dg)[iu]
+    sc[sc == 0] = 1.0
+    return float(fro), float(np.max(np.abs(d) / sc))
+
+
+def _first_mismatch(o, g_codes, g_scales, g_zeros, group):
+    """Earliest differing decision of one row, in algorithm order, or None."""
+    best = None
+    ks = np.nonzero(o["scales"][0] != g_scales)[0]
+    if ks.size:
+        best = (int(ks[0]) * (group + 2), "scale", int(ks[0]))
+    kz = np.nonzero(o["zeros"][0] != g_zeros)[0]
+    if kz.size:
+        c = (int(kz[0]) * (group + 2) + 1, "zero", int(kz[0]))
+        best = c if best is None or c < best else best
+    jc = np.nonzero(o["codes"][0] != g_codes)[0]
+    if jc.size:
+        j = int(jc[0])
+        c = ((j // group) * (group + 2) + 2 + j % group, "code", j)
+        best = c if best is None or c < best else best
+    return best
+
+
+def _alt_round(x):
+    """The integer on the other side of the rounding boundary, and the distance to it."""
+    f = np.floor(x)
+    margin = abs((x - f) - 0.5)
+    alt = f if np.rint(x) != f else f + 1.0
+    return alt, margin
+
+
+def compare_quantization(W64, U, bits, group, dead, g_codes, g_scales, g_zeros, tol=1e-5,
+                         max_forced_per_row=64):
+    """Runs the protocol over all rows of W64.  Returns a report dict."""
+    maxq = float(2 ** bits - 1)
+    m, n = W64.shape
+    base = orc.quantize_layer(W64, U, bits, group, dead=dead, want_pre=True)
+    rep = dict(rows=m, exact_rows=0, flagged_codes=0, flagged_zeros=0, flagged_scales=0,
+               unflagged=0, max_scale_margin_ulp=0.0, details=[], oracle=base)
+    for r in range(m):
+        same = (np.array_equal(base["codes"][r], g_codes[r]) and
+                np.array_equal(base["scales"][r], g_scales[r]) and
+                np.array_equal(base["zeros"][r], g_zeros[r]))
+        if same:
+            rep["exact_rows"] += 1
+            continue
+        cur = {k: v[r:r + 1] for k, v in base.items()}
+        forced = {}
+        for _ in range(max_forced_per_row):
+            mm = _first_mismatch(cur, g_codes[r], g_scales[r], g_zeros[r], group)
+            if mm is None:
+                break
+            _, kind, idx = mm
+            ok = False
+            if kind == "code":
+                k = idx // group
+                alt, margin = _alt_round(cur["pre_x"][0, idx])
+                altc = min(max(alt + float(cur["zeros"][0, k]), 0.0), maxq)
+                ok = margin <= tol and float(g_codes[r, idx]) == altc
+                val = int(g_codes[r, idx])
+                rep["flagged_codes"] += ok
+            elif kind == "zero":
+                alt, margin = _alt_round(cur["pre_zero"][0, idx])
+                ok = margin <= tol and float(g_zeros[r, idx]) == alt
+                val = int(g_zeros[r, idx])
+                rep["flagged_zeros"] += ok
+            else:
+                ps = cur["pre_scale"][0, idx]
+                so = np.float32(ps)
+                sg = np.float32(g_scales[r, idx])
+                adjacent = sg in (np.nextafter(so, np.float32(np.inf)), np.nextafter(so, np.float32(-np.inf)))
+                mid = 0.5 * (float(so) + float(sg))
+                ulp = abs(float(sg) - float(so))
+                margin = abs(ps - mid) / ulp if ulp > 0 else np.inf
+                # the scale's pre-rounding value within relative tol of the float32 midpoint
+                ok = bool(adjacent) and abs(ps - mid) <= tol * abs(ps)
+                val = float(sg)
+                if ok:
+                    rep["flagged_scales"] += 1
+                    rep["max_scale_margin_ulp"] = max(rep["max_scale_margin_ulp"], float(margin))
+            if not ok:
+                rep["unflagged"] += 1
+                rep["details"].append((r, kind, idx))
+                break
+            forced[(kind, 0, idx)] = val
+            cur = orc.quantize_layer(W64[r:r + 1], U, bits, group, dead=dead, forced=forced, want_pre=True)
+        else:
+            rep["unflagged"] += 1
+            rep["details"].append((r, "too many forced decisions", -1))
+    return rep
+
+
+def stored_to_f64(a):
+    return to_f64(a)

@@ -1,0 +1,78 @@
+"""Host-side checks of the C-ABI library: it loads, exports every symbol the
+header declares, and turns bad arguments into status codes before touching a
+GPU (none of these calls reaches a kernel launch)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2601_19675_amd as ptq
+from paper_2601_19675_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(ptq.lib_path()):
+        from paper_2601_19675_amd import build
+        build.build(verbose=False)
+    return ptq.load_library()
+
+
+def test_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "ptq.h")).read()
+    names = sorted(set(re.findall(r"\b(ptq_[a-z_]+)\s*\(", header)))
+    assert {"ptq_hessian_accumulate", "ptq_damped_cholesky_inv", "ptq_quantize_layer",
+            "ptq_layer_error", "ptq_workspace_bytes", "ptq_status_string"} <= set(names)
+    for nm in names:
+        assert hasattr(lib, nm), nm
+
+
+def test_status_strings_and_workspace_sizes(lib):
+    assert ptq.ptq_status_string(0) == "ok"
+    assert "positive definite" in ptq.ptq_status_string(5)
+    for op in range(4):
+        assert ptq.ptq_workspace_bytes(op, 4096, 4096, 262144, 128) % 256 == 0
+    # the factorization works on one n x n float64 copy
+    assert ptq.ptq_workspace_bytes(binding.OP_CHOLESKY_INV, 0, 4096) >= 4096 * 4096 * 8
+    # the solve keeps the errors of every column: n x m float64
+    assert ptq.ptq_workspace_bytes(binding.OP_QUANTIZE, 4096, 11008) >= 4096 * 11008 * 8
+    out = ctypes.c_size_t()
+    assert lib.ptq_workspace_bytes(0, -1, 8, 8, 0, ctypes.byref(out)) == 2
+    assert lib.ptq_workspace_bytes(7, 1, 8, 8, 0, ctypes.byref(out)) == 1
+    assert lib.ptq_workspace_bytes(0, 1, 8, 8, 0, None) == 1
+
+
+def test_argument_errors_are_reported_on_the_host(lib):
+    p = 0x1000  # never dereferenced: every call below fails validation first
+    # Hessian
+    assert lib.ptq_hessian_accumulate(p, 8, p, 1, 16, 16, 8, p, 1 << 20, None) == 2   # ldx < n
+    assert lib.ptq_hessian_accumulate(p, 16, p, 2, 16, 16, 16, p, 1 << 20, None) == 3  # f64 X
+    assert lib.ptq_hessian_accumulate(p, 12, p, 1, 16, 12, 12, p, 1 << 20, None) == 2  # bf16 n % 8
+    assert lib.ptq_hessian_accumulate(None, 16, p, 1, 16, 16, 16, p, 1 << 20, None) == 1
+    assert lib.ptq_hessian_accumulate(p, 16, p, 1, 16, 16, 16, None, 0, None) == 4
+    assert lib.ptq_hessian_accumulate(p, 16, p, 1, 0, 16, 16, None, 0, None) == 0      # t == 0: no-op
+    # factor
+    assert lib.ptq_damped_cholesky_inv(p, 16, 16, -0.5, p, 16, None, p, p, 1 << 20, None) == 1
+    assert lib.ptq_damped_cholesky_inv(p, 16, 16, float("nan"), p, 16, None, p, p, 1 << 20, None) == 1
+    assert lib.ptq_damped_cholesky_inv(p, 8, 16, 0.01, p, 16, None, p, p, 1 << 20, None) == 2
+    assert lib.ptq_damped_cholesky_inv(p, 16, 16, 0.01, p, 16, None, None, p, 1 << 20, None) == 1
+    assert lib.ptq_damped_cholesky_inv(p, 16, 16, 0.01, p, 16, None, p, p, 16, None) == 4
+    # solve
+    def q(bits=4, group=16, block=16, n=32, ldw=32, ws=1 << 20, wdt=1):
+        return lib.ptq_quantize_layer(p, wdt, ldw, 4, n, p, n, None, bits, group, block, p, p, p, None, None,
+                                      p, ws, None)
+    assert q(bits=1) == 1 and q(bits=9) == 1
+    assert q(wdt=9) == 3
+    assert q(group=12) == 2            # n % group
+    assert q(group=8, block=16) == 2   # groups start on 16-column boundaries
+    assert q(block=24) == 2 and q(block=512, group=16, n=1024, ldw=1024) == 2
+    assert q(group=32, block=48, n=96, ldw=96) == 2   # neither divides the other
+    assert q(ldw=16) == 2
+    assert q(ws=64) == 4
+    # layer error
+    assert lib.ptq_layer_error(p, 1, 32, p, 4, 32, p, 16, p, p, 1 << 20, None) == 2   # ldh < n
+    assert lib.ptq_layer_error(p, 1, 32, None, 4, 32, p, 32, p, p, 1 << 20, None) == 1
+    assert lib.ptq_layer_error(p, 1, 32, p, 0, 32, p, 32, p, p, 1 << 20, None) == 2
