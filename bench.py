@@ -1,0 +1,175 @@
+#!/usr/bin/env python3
+"""Benchmark of the layer-wise quantization solve on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic layer:
+Hessian accumulation -> damped Cholesky factor of the inverse -> blocked
+column quantization -> layer error, with all inputs resident in HBM.
+Prints ONE JSON line (see README for the fields).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C2] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_F64_TFLOPS = 78.6      # MI355X float64 (vector and matrix)
+HBM_GBPS = 8000.0
+
+
+def cpu_baseline(cfg, spec, seed):
+    """The oracle, as it stands, on a bounded sample of the same layer; scaled to columns/s."""
+    import numpy as np
+    from threadpoolctl import threadpool_info
+
+    import ptq_workloads as wl
+    from oracle import ptq_oracle as orc
+
+    t_s = min(spec.t, 4096)
+    rows_s = min(spec.m, 64)
+    Ws = wl.gen_weight(spec, seed)
+    X64 = wl.to_f64(wl.gen_activations(spec, seed, 0, t_s))
+    W64 = wl.to_f64(Ws)[:rows_s]
+    t0 = time.perf_counter()
+    H = orc.hessian(X64)
+    t1 = time.perf_counter()
+    Hd, dead = orc.damp(H, cfg.damps[0])
+    U = orc.inverse_cholesky_upper(Hd)
+    t2 = time.perf_counter()
+    out = orc.quantize_layer(W64, U, cfg.bits, cfg.group, dead=dead)
+    t3 = time.perf_counter()
+    orc.layer_error(W64, out["Wq"], H)
+    t4 = time.perf_counter()
+    est = ((t1 - t0) * spec.t / t_s + (t2 - t1) + (t3 - t2) * spec.m / rows_s + (t4 - t3) * spec.m / rows_s)
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    return {
+        "value": spec.n / est, "unit": "columns/s", "cores": int(threads), "kind": "oracle",
+        "sample": (f"{t_s} of {spec.t} tokens for H, full {spec.n}x{spec.n} factor, {rows_s} of {spec.m} rows "
+                   f"for solve and error; times scaled linearly to the full layer "
+                   f"(H {t1 - t0:.2f}s, factor {t2 - t1:.2f}s, solve {t3 - t2:.2f}s, error {t4 - t3:.2f}s measured)"),
+        "est_seconds_full_layer": est,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", default="C2")
+    ap.add_argument("--layer", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on exactly one GPU (the path has no multi-GPU part); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2601_19675_amd as ptq
+    import ptq_workloads as wl
+    from paper_2601_19675_amd import binding as B
+
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from parity import to_device
+
+    if not os.path.exists(ptq.lib_path()):
+        from paper_2601_19675_amd import build
+        build.build()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+
+    cfg = wl.CONFIGS[args.config]
+    spec = cfg.layers[args.layer]
+    m, n, t = spec.m, spec.n, spec.t
+    damp = cfg.damps[0]
+    W = to_device(wl.gen_weight(spec, cfg.seed))
+    X = torch.empty((t, n), dtype=torch.bfloat16 if spec.dtype == "bf16" else torch.float32, device="cuda")
+    step_t = 32768
+    for lo in range(0, t, step_t):          # generate on the host in slabs, upload
+        X[lo:lo + step_t] = to_device(wl.gen_activations(spec, cfg.seed, lo, min(t, lo + step_t)))
+
+    dev = "cuda"
+    H = torch.zeros((n, n), dtype=torch.float64, device=dev)
+    U = torch.empty((n, n), dtype=torch.float64, device=dev)
+    dead = torch.empty((n,), dtype=torch.uint8, device=dev)
+    info = torch.empty((2,), dtype=torch.int32, device=dev)
+    codes = torch.empty((m, n), dtype=torch.uint8, device=dev)
+    scales = torch.empty((m, n // cfg.group), dtype=torch.float32, device=dev)
+    zeros = torch.empty((m, n // cfg.group), dtype=torch.uint8, device=dev)
+    Wq = torch.empty((m, n), dtype=torch.float64, device=dev)
+    err2 = torch.empty((m,), dtype=torch.float64, device=dev)
+    out = torch.zeros(3, dtype=torch.float64, device=dev)
+    ws_bytes = max(ptq.ptq_workspace_bytes(op, m, n, t, cfg.block) for op in range(4))
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+
+    n_ev = 5
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(n_ev)] for _ in range(args.steps)]
+
+    def step(ev=None):
+        H.zero_()
+        if ev: ev[0].record()
+        ptq.ptq_hessian_accumulate(H, X, ws)
+        if ev: ev[1].record()
+        ptq.ptq_damped_cholesky_inv(H, damp, U, dead, info, ws)
+        if ev: ev[2].record()
+        ptq.ptq_quantize_layer(W, U, dead, cfg.bits, cfg.group, cfg.block, codes, scales, zeros, Wq, err2, ws)
+        if ev: ev[3].record()
+        ptq.ptq_layer_error(W, Wq, H, out, ws)
+        if ev: ev[4].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(events[k])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    assert info.cpu().tolist() == [0, 0], "factorization failed"
+
+    ms = 1e3 * elapsed / args.steps
+    phase = [sum(events[k][i].elapsed_time(events[k][i + 1]) for k in range(args.steps)) / args.steps
+             for i in range(n_ev - 1)]
+    h_ms, f_ms, q_ms, e_ms = phase
+    syrk_flops = float(t) * n * (n + 1)           # algorithmic: upper triangle incl. diagonal
+    h_tflops = syrk_flops / (h_ms * 1e-3) / 1e12
+    rel = float(out[0])
+
+    result = {
+        "metric": "layer-solve columns quantized/sec + Hessian TFLOP/s (% MFMA peak), 1 GPU",
+        "value": n / (ms * 1e-3), "unit": "columns/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16,f64" if spec.dtype == "bf16" else "f64", "data": "synthetic",
+        "config": {"workload": f"{args.config}:{spec.name} W {m}x{n} {spec.dtype}, X {t}x{n} {spec.dtype}, "
+                               f"{cfg.bits}-bit asym group {cfg.group} block {cfg.block} damp {damp}"},
+        "phases_ms": {"hessian": h_ms, "factor": f_ms, "quantize": q_ms, "layer_error": e_ms},
+        "hessian_tflops_syrk": h_tflops,
+        "hessian_tflops_full_square": 2.0 * t * n * n / (h_ms * 1e-3) / 1e12,
+        "hessian_pct_mfma_peak": 100.0 * h_tflops / PEAK_BF16_TFLOPS,
+        "solve_columns_per_s": n / ((f_ms + q_ms) * 1e-3),
+        "quantize_columns_per_s": n / (q_ms * 1e-3),
+        "quantize_tflops_f64": float(m) * n * n / (q_ms * 1e-3) / 1e12,
+        "rel_layer_error": rel,
+        "roofline": {
+            "kernel": "ptq_hessian_accumulate (hessian_bf16_kernel + partial-tile reduction)",
+            "bound": "mfma", "achieved": h_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+            "frac": h_tflops / PEAK_BF16_TFLOPS, "traffic": None,
+        },
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, spec, cfg.seed)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
