@@ -173,9 +173,9 @@ struct OpPanel {
   __device__ bool active(int, int, int, int) const { return true; }
   __device__ void krange(int, int, int, int j1, int& kb, int& ke) const { kb = 0; ke = min(nd.s1, j1); }
   __device__ double a(int i, int k) const {
-    return i < nd.s2 ? nd.G[(int64_t)(nd.o + nd.s1 + i) * nd.n + nd.o + k] : 0.0;
+    return nd.G[(int64_t)(nd.o + nd.s1 + i) * nd.n + nd.o + k];
   }
-  __device__ double b(int k, int j) const { return j < nd.s1 ? nd.x(j, k) : 0.0; }
+  __device__ double b(int k, int j) const { return nd.x(j, k); }
   __device__ void store(int i, int j, double v) const {
     if (i < nd.s2 && j < nd.s1) nd.G[(int64_t)(nd.o + j) * nd.n + nd.o + nd.s1 + i] = v;
   }
@@ -190,7 +190,7 @@ struct OpSyrk {
   __device__ bool active(int, int i1, int j0, int) const { return i1 > j0; }
   __device__ void krange(int, int, int, int, int& kb, int& ke) const { kb = 0; ke = nd.s1; }
   __device__ double l21(int i, int k) const {
-    return i < nd.s2 ? nd.G[(int64_t)(nd.o + k) * nd.n + nd.o + nd.s1 + i] : 0.0;
+    return nd.G[(int64_t)(nd.o + k) * nd.n + nd.o + nd.s1 + i];
   }
   __device__ double a(int i, int k) const { return l21(i, k); }
   __device__ double b(int k, int j) const { return l21(j, k); }
@@ -208,9 +208,9 @@ struct OpT {
   __device__ bool active(int, int, int, int) const { return true; }
   __device__ void krange(int, int, int j0, int, int& kb, int& ke) const { kb = j0; ke = nd.s1; }
   __device__ double a(int i, int k) const {
-    return i < nd.s2 ? nd.G[(int64_t)(nd.o + k) * nd.n + nd.o + nd.s1 + i] : 0.0;
+    return nd.G[(int64_t)(nd.o + k) * nd.n + nd.o + nd.s1 + i];
   }
-  __device__ double b(int k, int j) const { return j < nd.s1 ? nd.x(k, j) : 0.0; }
+  __device__ double b(int k, int j) const { return nd.x(k, j); }
   __device__ void store(int i, int j, double v) const {
     if (i < nd.s2 && j < nd.s1) nd.G[(int64_t)(nd.o + nd.s1 + i) * nd.n + nd.o + j] = v;
   }
@@ -224,10 +224,8 @@ struct OpX21 {
   __device__ int N() const { return nd.s1; }
   __device__ bool active(int, int, int, int) const { return true; }
   __device__ void krange(int, int i1, int, int, int& kb, int& ke) const { kb = 0; ke = min(nd.s2, i1); }
-  __device__ double a(int i, int k) const { return i < nd.s2 ? nd.x(nd.s1 + i, nd.s1 + k) : 0.0; }
-  __device__ double b(int k, int j) const {
-    return j < nd.s1 ? nd.G[(int64_t)(nd.o + nd.s1 + k) * nd.n + nd.o + j] : 0.0;
-  }
+  __device__ double a(int i, int k) const { return nd.x(nd.s1 + i, nd.s1 + k); }
+  __device__ double b(int k, int j) const { return nd.G[(int64_t)(nd.o + nd.s1 + k) * nd.n + nd.o + j]; }
   __device__ void store(int i, int j, double v) const {
     if (i < nd.s2 && j < nd.s1)
       nd.U[(int64_t)(nd.n - 1 - (nd.o + nd.s1 + i)) * nd.ldu + (nd.n - 1 - (nd.o + j))] = -v;
@@ -247,7 +245,7 @@ __global__ __launch_bounds__(256) void node_gemm_kernel(Op op) {
   dgemm_zero(acc);
   dgemm_mainloop<TM, TN, Op::A_KFAST, Op::B_KFAST>(
       acc, [&](int i, int k) { return op.a(i0 + i, k); }, [&](int k, int j) { return op.b(k, j0 + j); },
-      kb, ke, smem);
+      i1 - i0, j1 - j0, kb, ke, smem);
   dgemm_foreach(acc, [&](int i, int j, double v) { op.store(i0 + i, j0 + j, v); });
 }
 

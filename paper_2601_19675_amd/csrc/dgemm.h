@@ -28,14 +28,16 @@ struct DgemmTile {
   static constexpr int EB = BN * kGemmBK / 256;
 };
 
-// fa(i, k): element of A for tile-local row i and absolute k (0 when outside).
-// fb(k, j): element of B for absolute k and tile-local column j.
+// fa(i, k): element of A for tile-local row i < rows and absolute k in [kbeg, kend).
+// fb(k, j): element of B for absolute k and tile-local column j < cols.
+// The functors are only ever called with indices inside those ranges (out-of-range
+// tile positions are clamped to (0, kbeg) and the value discarded), so they must be
+// plain loads without branches: every load of a k-tile is then in flight at once.
 // A_KFAST / B_KFAST say which index is contiguous in memory so that the
-// thread -> element map coalesces.  k runs over [kbeg, kend); kbeg must be a
-// multiple of 16 relative to what the functors expect (they see absolute k).
+// thread -> element map coalesces.
 template <int TM, int TN, bool A_KFAST, bool B_KFAST, class FA, class FB>
-__device__ __forceinline__ void dgemm_mainloop(f64x4 (&acc)[TM][TN], FA fa, FB fb, int kbeg, int kend,
-                                               double* smem) {
+__device__ __forceinline__ void dgemm_mainloop(f64x4 (&acc)[TM][TN], FA fa, FB fb, int rows, int cols,
+                                               int kbeg, int kend, double* smem) {
   using T = DgemmTile<TM, TN>;
   double* sa = smem;
   double* sb = smem + kGemmBK * T::PA;
@@ -51,14 +53,18 @@ __device__ __forceinline__ void dgemm_mainloop(f64x4 (&acc)[TM][TN], FA fa, FB f
       const int e = tid + 256 * p;
       const int i = A_KFAST ? e / kGemmBK : e % T::BM;
       const int k = A_KFAST ? e % kGemmBK : e / T::BM;
-      ra[p] = (k0 + k < kend) ? fa(i, k0 + k) : 0.0;
+      const bool ok = (k0 + k < kend) & (i < rows);
+      const double v = fa(ok ? i : 0, ok ? k0 + k : kbeg);
+      ra[p] = ok ? v : 0.0;
     }
 #pragma unroll
     for (int p = 0; p < T::EB; ++p) {
       const int e = tid + 256 * p;
       const int j = B_KFAST ? e / kGemmBK : e % T::BN;
       const int k = B_KFAST ? e % kGemmBK : e / T::BN;
-      rb[p] = (k0 + k < kend) ? fb(k0 + k, j) : 0.0;
+      const bool ok = (k0 + k < kend) & (j < cols);
+      const double v = fb(ok ? k0 + k : kbeg, ok ? j : 0);
+      rb[p] = ok ? v : 0.0;
     }
   };
   auto stash = [&]() {

@@ -32,10 +32,12 @@ __global__ __launch_bounds__(256) void quad_form_kernel(ErrArgs a) {
   const int z = blockIdx.z;
   const int i0 = blockIdx.y * Tile::BM, j0 = blockIdx.x * Tile::BN;
   const int j1 = min(j0 + Tile::BN, a.n);
+  const int i1 = min(i0 + Tile::BM, a.m);
+  // element of D (z == 0) or W (z == 1); indices always inside the matrix
   auto elem = [&](int i, int k) -> double {
-    if (i >= a.m || k >= a.n) return 0.0;
     const double w = load_as_f64<DT>(a.W, (int64_t)i * a.ldw + k);
-    return z == 0 ? w - a.Wq[(int64_t)i * a.n + k] : w;
+    const double q = a.Wq[(int64_t)i * a.n + k];
+    return z == 0 ? w - q : w;
   };
   f64x4 acc[TM][TN];
   dgemm_zero(acc);
@@ -43,13 +45,16 @@ __global__ __launch_bounds__(256) void quad_form_kernel(ErrArgs a) {
       acc, [&](int i, int k) { return elem(i0 + i, k); },
       [&](int k, int j) {
         const int gj = j0 + j;
-        if (gj >= a.n || k > gj) return 0.0;
-        const double h = a.H[(int64_t)k * a.ldh + gj];
-        return k == gj ? h : 2.0 * h;
+        const double h = a.H[(int64_t)k * a.ldh + gj];  // below the diagonal: read, then discarded
+        return k == gj ? h : (k < gj ? 2.0 * h : 0.0);
       },
-      0, j1, smem);
+      i1 - i0, j1 - j0, 0, j1, smem);
   double s = 0.0;
-  dgemm_foreach(acc, [&](int i, int j, double v) { s = fma(v, elem(i0 + i, j0 + j), s); });
+  dgemm_foreach(acc, [&](int i, int j, double v) {
+    const bool ok = (i0 + i < a.m) & (j0 + j < a.n);
+    const double d = elem(ok ? i0 + i : i0, ok ? j0 + j : j0);
+    s = fma(v, ok ? d : 0.0, s);
+  });
   red[threadIdx.x] = s;
   __syncthreads();
   for (int w = 128; w > 0; w >>= 1) {

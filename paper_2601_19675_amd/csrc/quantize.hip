@@ -20,7 +20,6 @@ namespace ptq {
 namespace {
 
 constexpr int kRows = 16;       // rows per workgroup
-constexpr int kMaxTiles = 16;   // block <= 256 columns
 constexpr int kThreads = 256;
 
 __global__ void inv_diag_kernel(const double* __restrict__ U, int64_t ldu, int n, double* invd) {
@@ -46,7 +45,8 @@ struct QuantArgs {
   double* row_err2;
 };
 
-template <int DT>
+// NT = number of 16-column tiles the kernel is instantiated for (>= bw / 16).
+template <int DT, int NT>
 __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
   extern __shared__ double lds[];
   const int tid = threadIdx.x;
@@ -55,38 +55,59 @@ __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
   const int row0 = blockIdx.x * kRows;
   const int nt = a.bw >> 4;
   const int sp = a.bw + 1;  // pitch of the state tile
+  const double* __restrict__ U = a.U;
+  const double* __restrict__ invd = a.invd;
 
   // LDS carve-up: partial sums of the four waves (reused as the state tile),
-  // the mini-block errors, group min / max, and the code tile.
+  // the mini-block errors, the mini-block's 16 x 16 diagonal block of U and its
+  // reciprocal pivots (double-buffered), group min / max, and the code tile.
   double* P = lds;                                  // [4][16][bw]
   double* S = lds;                                  // [16][bw + 1]   (aliases P)
   double* Em = lds + 4 * kRows * a.bw;              // [16 k][16 rows]
-  double* gmin = Em + 256;                          // [16]
+  double* Ud = Em + 256;                            // [2][16][16]
+  double* Id = Ud + 512;                            // [2][16]
+  double* gmin = Id + 32;                           // [16]
   double* gmax = gmin + 16;                         // [16]
   uint8_t* Ct = reinterpret_cast<uint8_t*>(gmax + 16);  // [16][bw]
 
-  // ---- phase 1: acc = E[rows, 0:i1] * U[0:i1, block], k split over the waves
-  f64x4 acc[kMaxTiles];
+  // ---- phase 1: acc = E[rows, 0:i1] * U[0:i1, block], k split over the waves,
+  //      operands of the next kDepth steps in flight while the MFMAs run
+  f64x4 acc[NT];
 #pragma unroll
-  for (int t = 0; t < kMaxTiles; ++t) acc[t] = f64x4{0.0, 0.0, 0.0, 0.0};
+  for (int t = 0; t < NT; ++t) acc[t] = f64x4{0.0, 0.0, 0.0, 0.0};
   {
+    constexpr int kDepth = (NT >= 16) ? 3 : 4;
     const int kl = lane >> 4, cl = lane & 15;
     const double* ep = a.errT + (int64_t)(4 * wave + kl) * a.mpad + row0 + cl;
-    const double* up = a.U + (int64_t)(4 * wave + kl) * a.ldu + a.i1 + cl;
-    for (int k0 = 4 * wave; k0 < a.i1; k0 += 16) {
-      const double av = *ep;
-      double bv[kMaxTiles];
+    const double* up = U + (int64_t)(4 * wave + kl) * a.ldu + a.i1 + cl;
+    int coff[NT];  // tiles beyond the block re-read its last tile (result unused)
 #pragma unroll
-      for (int t = 0; t < kMaxTiles; ++t) bv[t] = (t < nt) ? up[16 * t] : 0.0;
+    for (int t = 0; t < NT; ++t) coff[t] = 16 * (t < nt ? t : nt - 1);
+    const int niter = (a.i1 - 4 * wave + 15) / 16;  // i1 is a multiple of 16
+    double av[kDepth], bv[kDepth][NT];
+    auto issue = [&](int slot, int it) {
+      av[slot] = ep[(int64_t)it * 16 * a.mpad];
+      const double* u = up + (int64_t)it * 16 * a.ldu;
 #pragma unroll
-      for (int t = 0; t < kMaxTiles; ++t)
-        if (t < nt) acc[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv[t], acc[t], 0, 0, 0);
-      ep += (int64_t)16 * a.mpad;
-      up += (int64_t)16 * a.ldu;
+      for (int t = 0; t < NT; ++t) bv[slot][t] = u[coff[t]];
+    };
+#pragma unroll
+    for (int d = 0; d < kDepth; ++d)
+      if (d < niter) issue(d, d);
+    for (int it = 0; it < niter; it += kDepth) {
+#pragma unroll
+      for (int d = 0; d < kDepth; ++d) {
+        if (it + d < niter) {
+#pragma unroll
+          for (int t = 0; t < NT; ++t)
+            acc[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[d], bv[d][t], acc[t], 0, 0, 0);
+          if (it + d + kDepth < niter) issue(d, it + d + kDepth);
+        }
+      }
     }
   }
 #pragma unroll
-  for (int t = 0; t < kMaxTiles; ++t)
+  for (int t = 0; t < NT; ++t)
     if (t < nt) {
 #pragma unroll
       for (int r = 0; r < 4; ++r)
@@ -96,9 +117,9 @@ __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
 
   // ---- state tile S = W - (p0 + p1 + p2 + p3), dead channels read as zero
   {
-    double sv[kMaxTiles];
+    double sv[NT];
 #pragma unroll
-    for (int p = 0; p < kMaxTiles; ++p) {
+    for (int p = 0; p < NT; ++p) {
       const int e = tid + kThreads * p;
       sv[p] = 0.0;
       if (e < kRows * a.bw) {
@@ -113,24 +134,45 @@ __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
     }
     __syncthreads();
 #pragma unroll
-    for (int p = 0; p < kMaxTiles; ++p) {
+    for (int p = 0; p < NT; ++p) {
       const int e = tid + kThreads * p;
       if (e < kRows * a.bw) {
         const int r = e / a.bw, c = e - r * a.bw;
         S[r * sp + c] = sv[p];
       }
     }
+    // diagonal block of the first mini-block
+    Ud[tid] = U[(int64_t)(a.i1 + (tid >> 4)) * a.ldu + a.i1 + (tid & 15)];
+    if (tid < 16) Id[tid] = invd[a.i1 + tid];
   }
   __syncthreads();
 
   // ---- phase 2: 16-column mini-blocks
   const double maxq = (double)((1 << a.bits) - 1);
   const int ng = a.n / a.group;
-  double scale = 1.0, rscale = 1.0, zero = 0.0, err2 = 0.0;  // live in lanes 0..15 of wave 0
+  double scale = 1.0, rscale = 1.0, zero = 0.0, klo = 0.0, khi = 0.0, err2 = 0.0;  // lanes 0..15 of wave 0
+  constexpr int kUpd = (NT + 3) / 4;  // tiles one wave may have to update per mini-block
   for (int mb = 0; mb < nt; ++mb) {
     const int c0 = 16 * mb;           // first column of the mini-block inside the block
     const int gcol = a.i1 + c0;       // ... and in the layer
+    const int buf = mb & 1;
     const bool gstart = (gcol % a.group) == 0;
+    // operands that do not depend on this mini-block's results: the next diagonal
+    // block and the rows of U that push this mini-block's errors onto later tiles
+    double ud_next = 0.0, id_next = 0.0;
+    if (mb + 1 < nt) {
+      ud_next = U[(int64_t)(gcol + 16 + (tid >> 4)) * a.ldu + gcol + 16 + (tid & 15)];
+      if (tid < 16) id_next = invd[gcol + 16 + tid];
+    }
+    double ub[kUpd][4];
+#pragma unroll
+    for (int q = 0; q < kUpd; ++q) {
+      const int t = mb + 1 + wave + 4 * q;
+      const int tc = t < nt ? t : nt - 1;
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk)
+        ub[q][kk] = U[(int64_t)(gcol + 4 * kk + (lane >> 4)) * a.ldu + a.i1 + 16 * tc + (lane & 15)];
+    }
     if (gstart) {
       // min / max of the group's current values: 16 lanes per row
       const int r = tid >> 4, sub = tid & 15;
@@ -164,6 +206,8 @@ __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
         scale = (double)sf;
         rscale = 1.0 / scale;
         zero = rint(-lo / scale);
+        klo = -zero;
+        khi = maxq - zero;
         if (rlive) {
           a.scales[(int64_t)(row0 + r) * ng + gcol / a.group] = sf;
           a.zeros[(int64_t)(row0 + r) * ng + gcol / a.group] = (uint8_t)zero;
@@ -172,6 +216,8 @@ __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
       double w[16];
 #pragma unroll
       for (int j = 0; j < 16; ++j) w[j] = S[r * sp + c0 + j];
+      const double* ud = Ud + buf * 256;
+      const double* id = Id + buf * 16;
 #pragma unroll
       for (int j = 0; j < 16; ++j) {
         // x = w / scale, correctly rounded from the reciprocal (one Newton step
@@ -179,32 +225,38 @@ __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
         const double q0 = w[j] * rscale;
         const double rem = fma(-q0, scale, w[j]);
         const double x = fma(rem, rscale, q0);
-        const double code = fmin(fmax(rint(x) + zero, 0.0), maxq);
-        const double q = scale * (code - zero);
-        const double e = (w[j] - q) * a.invd[gcol + j];
-        const double* urow = a.U + (int64_t)(gcol + j) * a.ldu + gcol;
+        // k = code - zero, clamped; scale * k is exact (24-bit x 9-bit), so one
+        // fma gives w - q with the same single rounding as the subtraction
+        const double k = fmin(fmax(rint(x), klo), khi);
+        const double e = fma(-scale, k, w[j]) * id[j];
 #pragma unroll
-        for (int k = j + 1; k < 16; ++k) w[k] = fma(-e, urow[k], w[k]);
+        for (int c = j + 1; c < 16; ++c) w[c] = fma(-e, ud[j * 16 + c], w[c]);
         err2 = fma(e, e, err2);
-        Ct[r * a.bw + c0 + j] = (uint8_t)code;
+        Ct[r * a.bw + c0 + j] = (uint8_t)(k + zero);
         Em[j * kRows + r] = e;
         a.errT[(int64_t)(gcol + j) * a.mpad + row0 + r] = e;
-        if (a.Wq && rlive) a.Wq[(int64_t)(row0 + r) * a.n + gcol + j] = q;
+        if (a.Wq && rlive) a.Wq[(int64_t)(row0 + r) * a.n + gcol + j] = scale * k;
       }
     }
     __syncthreads();
     // push the 16 new errors onto the later tiles of the block
-    for (int t = mb + 1 + wave; t < nt; t += 4) {
-      f64x4 d = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-      for (int kk = 0; kk < 16; kk += 4) {
-        const int k = kk + (lane >> 4);
-        const double av = Em[k * kRows + (lane & 15)];
-        const double bv = a.U[(int64_t)(gcol + k) * a.ldu + a.i1 + 16 * t + (lane & 15)];
-        d = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, d, 0, 0, 0);
+    for (int q = 0; q < kUpd; ++q) {
+      const int t = mb + 1 + wave + 4 * q;
+      if (t < nt) {
+        f64x4 d = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+          const double av = Em[(4 * kk + (lane >> 4)) * kRows + (lane & 15)];
+          d = __builtin_amdgcn_mfma_f64_16x16x4f64(av, ub[q][kk], d, 0, 0, 0);
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) S[(4 * r + (lane >> 4)) * sp + 16 * t + (lane & 15)] -= d[r];
       }
-#pragma unroll
-      for (int r = 0; r < 4; ++r) S[(4 * r + (lane >> 4)) * sp + 16 * t + (lane & 15)] -= d[r];
+    }
+    if (mb + 1 < nt) {
+      Ud[(buf ^ 1) * 256 + tid] = ud_next;
+      if (tid < 16) Id[(buf ^ 1) * 16 + tid] = id_next;
     }
     __syncthreads();
   }
@@ -223,19 +275,35 @@ __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
 }
 
 size_t block_lds_bytes(int bw) {
-  return (size_t)(4 * kRows * bw + 256 + 32) * sizeof(double) + (size_t)kRows * bw;
+  return (size_t)(4 * kRows * bw + 256 + 512 + 32 + 32) * sizeof(double) + (size_t)kRows * bw;
+}
+
+template <int DT, int NT>
+ptq_status launch_block(const QuantArgs& a, hipStream_t st) {
+  static bool opted_in = false;
+  if (!opted_in) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(quant_block_kernel<DT, NT>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)block_lds_bytes(16 * NT)) != hipSuccess)
+      return PTQ_ERR_HIP;
+    opted_in = true;
+  }
+  quant_block_kernel<DT, NT><<<a.mpad / kRows, kThreads, block_lds_bytes(a.bw), st>>>(a);
+  return PTQ_OK;
 }
 
 template <int DT>
 ptq_status run_blocks(QuantArgs a, int block, hipStream_t st) {
-  const size_t max_lds = block_lds_bytes(block);
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(quant_block_kernel<DT>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)max_lds) != hipSuccess)
-    return PTQ_ERR_HIP;
   for (int i1 = 0; i1 < a.n; i1 += block) {
     a.i1 = i1;
     a.bw = (a.n - i1 < block) ? a.n - i1 : block;
-    quant_block_kernel<DT><<<a.mpad / kRows, kThreads, block_lds_bytes(a.bw), st>>>(a);
+    const int nt = a.bw / 16;
+    ptq_status rc;
+    if (nt <= 2) rc = launch_block<DT, 2>(a, st);
+    else if (nt <= 4) rc = launch_block<DT, 4>(a, st);
+    else if (nt <= 8) rc = launch_block<DT, 8>(a, st);
+    else rc = launch_block<DT, 16>(a, st);
+    if (rc != PTQ_OK) return rc;
   }
   return PTQ_OK;
 }
