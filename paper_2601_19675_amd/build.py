@@ -14,6 +14,9 @@ FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-result",
     # packed-FP32 instructions are kept out of every kernel
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # accumulators of the matrix instructions stay in ordinary VGPRs: every kernel here
+    # fits 256 registers, and the AGPR form costs copies around each MFMA
+    "-mllvm", "-amdgpu-mfma-vgpr-form",
 ]
 
 

@@ -154,13 +154,16 @@ __global__ __launch_bounds__(kLeafThreads) void leaf_kernel(const double* __rest
 }
 
 // ---- the four GEMM steps of one recursion node -------------------------------
+// Each step describes its operands as strided views for the tile at (i0, j0):
+// A(i, k) and B(k, j) with i, j tile-local and k counted from the block start.
 struct Node {
   double* G;      // work matrix, n x n, ld = n
-  double* U;      // output, X reversed
-  int64_t ldu;
+  double* U;      // output, X reversed: X(i, j) = U[n-1-i][n-1-j]
+  int ldu;
   int n, o, s1, s2;
-  __device__ __forceinline__ double x(int i, int j) const {  // X(o+i, o+j) of this block
-    return U[(int64_t)(n - 1 - (o + i)) * ldu + (n - 1 - (o + j))];
+  __device__ __forceinline__ const double* g(int i, int j) const { return G + (int64_t)i * n + j; }
+  __device__ __forceinline__ const double* x(int i, int j) const {
+    return U + (int64_t)(n - 1 - i) * ldu + (n - 1 - j);
   }
 };
 
@@ -172,10 +175,8 @@ struct OpPanel {
   __device__ int N() const { return nd.s1; }
   __device__ bool active(int, int, int, int) const { return true; }
   __device__ void krange(int, int, int, int j1, int& kb, int& ke) const { kb = 0; ke = min(nd.s1, j1); }
-  __device__ double a(int i, int k) const {
-    return nd.G[(int64_t)(nd.o + nd.s1 + i) * nd.n + nd.o + k];
-  }
-  __device__ double b(int k, int j) const { return nd.x(j, k); }
+  __device__ DView a(int i0) const { return DView{nd.g(nd.o + nd.s1 + i0, nd.o), nd.n, 1}; }
+  __device__ DView b(int j0) const { return DView{nd.x(nd.o + j0, nd.o), -nd.ldu, -1}; }  // X11(j, k)
   __device__ void store(int i, int j, double v) const {
     if (i < nd.s2 && j < nd.s1) nd.G[(int64_t)(nd.o + j) * nd.n + nd.o + nd.s1 + i] = v;
   }
@@ -189,11 +190,8 @@ struct OpSyrk {
   __device__ int N() const { return nd.s2; }
   __device__ bool active(int, int i1, int j0, int) const { return i1 > j0; }
   __device__ void krange(int, int, int, int, int& kb, int& ke) const { kb = 0; ke = nd.s1; }
-  __device__ double l21(int i, int k) const {
-    return nd.G[(int64_t)(nd.o + k) * nd.n + nd.o + nd.s1 + i];
-  }
-  __device__ double a(int i, int k) const { return l21(i, k); }
-  __device__ double b(int k, int j) const { return l21(j, k); }
+  __device__ DView a(int i0) const { return DView{nd.g(nd.o, nd.o + nd.s1 + i0), 1, nd.n}; }  // L21(i, k)
+  __device__ DView b(int j0) const { return DView{nd.g(nd.o, nd.o + nd.s1 + j0), 1, nd.n}; }  // L21(j, k)
   __device__ void store(int i, int j, double v) const {
     if (i < nd.s2 && j <= i) nd.G[(int64_t)(nd.o + nd.s1 + i) * nd.n + nd.o + nd.s1 + j] -= v;
   }
@@ -207,10 +205,8 @@ struct OpT {
   __device__ int N() const { return nd.s1; }
   __device__ bool active(int, int, int, int) const { return true; }
   __device__ void krange(int, int, int j0, int, int& kb, int& ke) const { kb = j0; ke = nd.s1; }
-  __device__ double a(int i, int k) const {
-    return nd.G[(int64_t)(nd.o + k) * nd.n + nd.o + nd.s1 + i];
-  }
-  __device__ double b(int k, int j) const { return nd.x(k, j); }
+  __device__ DView a(int i0) const { return DView{nd.g(nd.o, nd.o + nd.s1 + i0), 1, nd.n}; }
+  __device__ DView b(int j0) const { return DView{nd.x(nd.o, nd.o + j0), -1, -nd.ldu}; }  // X11(k, j)
   __device__ void store(int i, int j, double v) const {
     if (i < nd.s2 && j < nd.s1) nd.G[(int64_t)(nd.o + nd.s1 + i) * nd.n + nd.o + j] = v;
   }
@@ -224,8 +220,10 @@ struct OpX21 {
   __device__ int N() const { return nd.s1; }
   __device__ bool active(int, int, int, int) const { return true; }
   __device__ void krange(int, int i1, int, int, int& kb, int& ke) const { kb = 0; ke = min(nd.s2, i1); }
-  __device__ double a(int i, int k) const { return nd.x(nd.s1 + i, nd.s1 + k); }
-  __device__ double b(int k, int j) const { return nd.G[(int64_t)(nd.o + nd.s1 + k) * nd.n + nd.o + j]; }
+  __device__ DView a(int i0) const {  // X22(i, k)
+    return DView{nd.x(nd.o + nd.s1 + i0, nd.o + nd.s1), -nd.ldu, -1};
+  }
+  __device__ DView b(int j0) const { return DView{nd.g(nd.o + nd.s1, nd.o + j0), 1, nd.n}; }  // T(k, j)
   __device__ void store(int i, int j, double v) const {
     if (i < nd.s2 && j < nd.s1)
       nd.U[(int64_t)(nd.n - 1 - (nd.o + nd.s1 + i)) * nd.ldu + (nd.n - 1 - (nd.o + j))] = -v;
@@ -235,7 +233,7 @@ struct OpX21 {
 template <int TM, int TN, class Op>
 __global__ __launch_bounds__(256) void node_gemm_kernel(Op op) {
   using T = DgemmTile<TM, TN>;
-  __shared__ double smem[T::kSmemDoubles];
+  extern __shared__ double smem[];
   const int i0 = blockIdx.y * T::BM, j0 = blockIdx.x * T::BN;
   const int i1 = min(i0 + T::BM, op.M()), j1 = min(j0 + T::BN, op.N());
   if (!op.active(i0, i1, j0, j1)) return;
@@ -243,26 +241,36 @@ __global__ __launch_bounds__(256) void node_gemm_kernel(Op op) {
   op.krange(i0, i1, j0, j1, kb, ke);
   f64x4 acc[TM][TN];
   dgemm_zero(acc);
-  dgemm_mainloop<TM, TN, Op::A_KFAST, Op::B_KFAST>(
-      acc, [&](int i, int k) { return op.a(i0 + i, k); }, [&](int k, int j) { return op.b(k, j0 + j); },
-      i1 - i0, j1 - j0, kb, ke, smem);
+  dgemm_mainloop<TM, TN, Op::A_KFAST, Op::B_KFAST>(acc, op.a(i0), DgemmIdentity{}, op.b(j0), DgemmIdentity{},
+                                                   i1 - i0, j1 - j0, kb, ke, smem);
   dgemm_foreach(acc, [&](int i, int j, double v) { op.store(i0 + i, j0 + j, v); });
+}
+
+template <int TM, int TN, class Op>
+void launch_tiles(const Op& op, int M, int N, hipStream_t st) {
+  using T = DgemmTile<TM, TN>;
+  static bool opted_in = false;
+  constexpr int lds = T::kSmemDoubles * (int)sizeof(double);
+  if (!opted_in) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(node_gemm_kernel<TM, TN, Op>),
+                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    opted_in = true;
+  }
+  dim3 g((unsigned)ceil_div(N, T::BN), (unsigned)ceil_div(M, T::BM));
+  node_gemm_kernel<TM, TN, Op><<<g, 256, lds, st>>>(op);
 }
 
 template <class Op>
 void launch_node(const Op& op, int M, int N, hipStream_t st) {
-  // 128 x 128 tiles once there are enough of them to fill the chip, else 64 x 64
-  const int64_t big = ceil_div(M, 128) * ceil_div(N, 128);
-  if (big >= 512) {
-    dim3 g((unsigned)ceil_div(N, 128), (unsigned)ceil_div(M, 128));
-    node_gemm_kernel<4, 4, Op><<<g, 256, 0, st>>>(op);
-  } else {
-    dim3 g((unsigned)ceil_div(N, 64), (unsigned)ceil_div(M, 64));
-    node_gemm_kernel<2, 2, Op><<<g, 256, 0, st>>>(op);
-  }
+  // 64 x 128 tiles once there are enough of them to fill the chip, else 64 x 64
+  const int64_t big = ceil_div(M, 64) * ceil_div(N, 128);
+  if (big >= 1024)
+    launch_tiles<2, 4, Op>(op, M, N, st);
+  else
+    launch_tiles<2, 2, Op>(op, M, N, st);
 }
 
-void recurse(double* G, double* U, int64_t ldu, int n, int o, int s, int32_t* info, hipStream_t st) {
+void recurse(double* G, double* U, int ldu, int n, int o, int s, int32_t* info, hipStream_t st) {
   if (s <= kLeaf) {
     const size_t lds = (size_t)(kLeaf * kLeafPitch + kLeaf) * sizeof(double);
     leaf_kernel<<<1, kLeafThreads, lds, st>>>(G, n, o, s, U, ldu, info);
@@ -307,7 +315,7 @@ ptq_status cholesky_launch(const double* H, int64_t ldh, int64_t n, double damp,
   dim3 g((unsigned)ceil_div(n, 256), (unsigned)n);
   build_work_kernel<<<g, 256, 0, st>>>(H, ldh, (int)n, scal, G, U, ldu);
   PTQ_HIP_CHECK_LAUNCH();
-  recurse(G, U, ldu, (int)n, 0, (int)n, info, st);
+  recurse(G, U, (int)ldu, (int)n, 0, (int)n, info, st);
   PTQ_HIP_CHECK_LAUNCH();
   return PTQ_OK;
 }

@@ -28,6 +28,21 @@ __device__ __forceinline__ double load_as_f64(const void* p, int64_t idx) {
   }
 }
 
+// The same in two steps, so that a kernel can keep the raw stored value in a
+// register while the load is in flight and widen it only when it is consumed.
+template <int DT> struct StoredType { using type = double; };
+template <> struct StoredType<PTQ_F32> { using type = float; };
+template <> struct StoredType<PTQ_BF16> { using type = uint16_t; };
+template <int DT>
+__device__ __forceinline__ typename StoredType<DT>::type load_stored(const void* p, int64_t idx) {
+  return static_cast<const typename StoredType<DT>::type*>(p)[idx];
+}
+template <int DT>
+__device__ __forceinline__ double stored_to_f64(typename StoredType<DT>::type v) {
+  if constexpr (DT == PTQ_BF16) return static_cast<double>(bf16_bits_to_f32(v));
+  else return static_cast<double>(v);
+}
+
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline size_t align_up(size_t a, size_t b) { return (a + b - 1) / b * b; }
 

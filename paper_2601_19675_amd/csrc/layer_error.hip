@@ -12,47 +12,50 @@
 namespace ptq {
 namespace {
 
-constexpr int TM = 4, TN = 4;
+constexpr int TM = 2, TN = 4;  // 64 x 128 tile: two workgroups (8 waves) per CU keep the f64 matrix pipe fuller
 using Tile = DgemmTile<TM, TN>;
 
 struct ErrArgs {
-  const void* W;
-  int64_t ldw;
-  const double* Wq;
+  const double* A2;  // [2][m][n]: D = W - Wq, then W, both widened to float64
   int m, n;
   const double* H;
-  int64_t ldh;
+  int ldh;
   double* partial;  // [2][tiles]
 };
 
+// D = W - Wq and W itself as float64, so that the GEMM streams plain doubles.
 template <int DT>
+__global__ __launch_bounds__(256) void widen_kernel(const void* __restrict__ W, int64_t ldw,
+                                                    const double* __restrict__ Wq, int m, int n,
+                                                    double* __restrict__ A2) {
+  const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (e >= (int64_t)m * n) return;
+  const int i = (int)(e / n), k = (int)(e - (int64_t)i * n);
+  const double w = load_as_f64<DT>(W, (int64_t)i * ldw + k);
+  A2[e] = w - Wq[e];
+  A2[(int64_t)m * n + e] = w;
+}
+
 __global__ __launch_bounds__(256) void quad_form_kernel(ErrArgs a) {
-  __shared__ double smem[Tile::kSmemDoubles];
+  extern __shared__ double smem[];
   __shared__ double red[256];
   const int z = blockIdx.z;
   const int i0 = blockIdx.y * Tile::BM, j0 = blockIdx.x * Tile::BN;
   const int j1 = min(j0 + Tile::BN, a.n);
   const int i1 = min(i0 + Tile::BM, a.m);
-  // element of D (z == 0) or W (z == 1); indices always inside the matrix
-  auto elem = [&](int i, int k) -> double {
-    const double w = load_as_f64<DT>(a.W, (int64_t)i * a.ldw + k);
-    const double q = a.Wq[(int64_t)i * a.n + k];
-    return z == 0 ? w - q : w;
-  };
+  const double* Az = a.A2 + (int64_t)z * a.m * a.n;
   f64x4 acc[TM][TN];
   dgemm_zero(acc);
   dgemm_mainloop<TM, TN, true, false>(
-      acc, [&](int i, int k) { return elem(i0 + i, k); },
-      [&](int k, int j) {
-        const int gj = j0 + j;
-        const double h = a.H[(int64_t)k * a.ldh + gj];  // below the diagonal: read, then discarded
-        return k == gj ? h : (k < gj ? 2.0 * h : 0.0);
-      },
+      acc, DView{Az + (int64_t)i0 * a.n, a.n, 1}, DgemmIdentity{},
+      // H below the diagonal is read (it is valid memory) and discarded
+      DView{a.H + j0, 1, a.ldh},
+      [&](double h, int k, int j) { return k == j0 + j ? h : (k < j0 + j ? 2.0 * h : 0.0); },
       i1 - i0, j1 - j0, 0, j1, smem);
   double s = 0.0;
   dgemm_foreach(acc, [&](int i, int j, double v) {
     const bool ok = (i0 + i < a.m) & (j0 + j < a.n);
-    const double d = elem(ok ? i0 + i : i0, ok ? j0 + j : j0);
+    const double d = Az[ok ? (int64_t)(i0 + i) * a.n + j0 + j : 0];
     s = fma(v, ok ? d : 0.0, s);
   });
   red[threadIdx.x] = s;
@@ -91,25 +94,41 @@ __global__ __launch_bounds__(256) void finish_kernel(const double* __restrict__ 
 
 }  // namespace
 
-size_t layer_error_workspace_bytes(int64_t m, int64_t n) {
+static size_t partial_bytes(int64_t m, int64_t n) {
   const size_t tiles = (size_t)ceil_div(m, Tile::BM) * (size_t)ceil_div(n, Tile::BN);
   return align_up(2 * tiles * sizeof(double), 256);
+}
+
+size_t layer_error_workspace_bytes(int64_t m, int64_t n) {
+  return partial_bytes(m, n) + align_up(2 * (size_t)m * (size_t)n * sizeof(double), 256);
 }
 
 ptq_status layer_error_launch(const void* W, ptq_dtype wdt, int64_t ldw, const double* Wq, int64_t m,
                               int64_t n, const double* H, int64_t ldh, double* out, void* ws,
                               size_t ws_bytes, hipStream_t st) {
   if (ws_bytes < layer_error_workspace_bytes(m, n)) return PTQ_ERR_WORKSPACE;
-  ErrArgs a{W, ldw, Wq, (int)m, (int)n, H, ldh, static_cast<double*>(ws)};
-  dim3 g((unsigned)ceil_div(n, Tile::BN), (unsigned)ceil_div(m, Tile::BM), 2);
-  const int tiles = (int)(g.x * g.y);
+  double* partial = static_cast<double*>(ws);
+  double* A2 = reinterpret_cast<double*>(static_cast<char*>(ws) + partial_bytes(m, n));
+  const unsigned wg = (unsigned)ceil_div(m * n, 256);
   switch (wdt) {
-    case PTQ_F32: quad_form_kernel<PTQ_F32><<<g, 256, 0, st>>>(a); break;
-    case PTQ_BF16: quad_form_kernel<PTQ_BF16><<<g, 256, 0, st>>>(a); break;
-    case PTQ_F64: quad_form_kernel<PTQ_F64><<<g, 256, 0, st>>>(a); break;
+    case PTQ_F32: widen_kernel<PTQ_F32><<<wg, 256, 0, st>>>(W, ldw, Wq, (int)m, (int)n, A2); break;
+    case PTQ_BF16: widen_kernel<PTQ_BF16><<<wg, 256, 0, st>>>(W, ldw, Wq, (int)m, (int)n, A2); break;
+    case PTQ_F64: widen_kernel<PTQ_F64><<<wg, 256, 0, st>>>(W, ldw, Wq, (int)m, (int)n, A2); break;
     default: return PTQ_ERR_DTYPE;
   }
-  finish_kernel<<<1, 256, 0, st>>>(a.partial, tiles, out);
+  ErrArgs a{A2, (int)m, (int)n, H, (int)ldh, partial};
+  dim3 g((unsigned)ceil_div(n, Tile::BN), (unsigned)ceil_div(m, Tile::BM), 2);
+  const int tiles = (int)(g.x * g.y);
+  constexpr int lds = Tile::kSmemDoubles * (int)sizeof(double);
+  static bool opted_in = false;
+  if (!opted_in) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(quad_form_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
+      return PTQ_ERR_HIP;
+    opted_in = true;
+  }
+  quad_form_kernel<<<g, 256, lds, st>>>(a);
+  finish_kernel<<<1, 256, 0, st>>>(partial, tiles, out);
   PTQ_HIP_CHECK_LAUNCH();
   return PTQ_OK;
 }
