@@ -25,8 +25,6 @@ namespace ptq {
 namespace {
 
 constexpr int kLeaf = 128;          // largest block factored inside one workgroup
-constexpr int kLeafPitch = kLeaf + 1;
-constexpr int kLeafThreads = 1024;
 
 // ---- diagonal statistics: dead channels, mean of the fixed diagonal ---------
 __global__ __launch_bounds__(1024) void diag_stats_kernel(const double* __restrict__ H, int64_t ldh,
@@ -76,80 +74,156 @@ __global__ __launch_bounds__(256) void build_work_kernel(const double* __restric
 }
 
 // ---- leaf: X = inverse of the Cholesky factor of G[o:o+s, o:o+s], s <= 128 ---
-__global__ __launch_bounds__(kLeafThreads) void leaf_kernel(const double* __restrict__ G, int n, int o,
-                                                            int s, double* __restrict__ U, int64_t ldu,
-                                                            int32_t* info) {
+// The block lives in LDS and is processed in 16 x 16 sub-blocks.  For each
+// diagonal sub-block one wave factors it and inverts the factor in registers
+// (lane = row, pivots and multipliers passed around with v_readlane, no
+// barriers); the sub-blocks below and the trailing sub-blocks are then updated
+// with 16x16x4 float64 MFMAs by all four waves.  The inverse is built the same
+// way, one wave per block column.  X is parked in the upper sub-blocks.
+__device__ __forceinline__ double lane_bcast(double v, int src) {
+  const int lo = __builtin_amdgcn_readlane(__double2loint(v), src);
+  const int hi = __builtin_amdgcn_readlane(__double2hiint(v), src);
+  return __hiloint2double(hi, lo);
+}
+
+constexpr int kLeafP = kLeaf + 1;   // pitch of the LDS block
+constexpr int kXdP = 17;            // pitch of a stored 16 x 16 diagonal inverse
+constexpr size_t kLeafLdsBytes = (size_t)(kLeaf * kLeafP + (kLeaf / 16) * 16 * kXdP) * sizeof(double);
+
+__global__ __launch_bounds__(256) void leaf_kernel(const double* __restrict__ G, int n, int o, int s,
+                                                   double* __restrict__ U, int64_t ldu, int32_t* info) {
   extern __shared__ double lds[];
-  double* S = lds;                          // s x s, pitch 129: lower = L, strict upper = X^T
-  double* invd = lds + kLeaf * kLeafPitch;  // 1 / L_jj
-  const int tid = threadIdx.x;
+  double* S = lds;                      // [128][129]
+  double* XD = lds + kLeaf * kLeafP;    // [8][16][17] inverses of the diagonal sub-blocks
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int nb = (s + 15) >> 4, sp = nb << 4;
+  const int l16 = lane & 15, lq = lane >> 4;
 
-  for (int e = tid; e < s * s; e += kLeafThreads) {
-    const int i = e / s, j = e % s;
-    S[i * kLeafPitch + j] = (j <= i) ? G[(int64_t)(o + i) * n + o + j] : 0.0;
+  for (int e = tid; e < sp * sp; e += 256) {
+    const int i = e / sp, j = e - i * sp;
+    double v = 0.0;
+    if (i < s && j <= i) v = G[(int64_t)(o + i) * n + o + j];
+    if (i >= s && i == j) v = 1.0;   // padding: identity
+    S[i * kLeafP + j] = v;
   }
   __syncthreads();
 
-  // right-looking factorization, one column at a time
-  const int ti = tid >> 5, tk = tid & 31;
-  for (int j = 0; j < s; ++j) {
-    if (tid == 0) {
-      double p = S[j * kLeafPitch + j];
-      if (!(p > 0.0)) {
-        if (info[0] == PTQ_OK) {
-          info[0] = PTQ_ERR_NOT_SPD;
-          info[1] = n - 1 - (o + j);
+  for (int d = 0; d < nb; ++d) {
+    const int b0 = 16 * d;
+    if (wave == 0) {
+      // ---- factor the diagonal sub-block and invert its factor (lanes 0..15)
+      double a[16], id[16];
+#pragma unroll
+      for (int c = 0; c < 16; ++c) a[c] = S[(b0 + l16) * kLeafP + b0 + c];
+      int bad = -1;
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        double p = lane_bcast(a[j], j);
+        if (!(p > 0.0)) {
+          if (bad < 0) bad = j;
+          p = 1.0;
         }
-        p = 1.0;
+        const double r = sqrt(p);
+        id[j] = 1.0 / r;
+        a[j] = (l16 == j) ? r : a[j] * id[j];
+#pragma unroll
+        for (int k = j + 1; k < 16; ++k) a[k] = fma(-a[j], lane_bcast(a[j], k), a[k]);
       }
-      const double r = sqrt(p);
-      S[j * kLeafPitch + j] = r;
-      invd[j] = 1.0 / r;
+      if (bad >= 0 && b0 + bad < s && tid == 0 && info[0] == PTQ_OK) {
+        info[0] = PTQ_ERR_NOT_SPD;
+        info[1] = n - 1 - (o + b0 + bad);
+      }
+      // column l16 of the inverse: x[i] = -(sum_{k<i} L_ik x[k]) / L_ii, x[l16] = 1 / L_ii
+      double x[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        double sum = 0.0;
+#pragma unroll
+        for (int k = 0; k < i; ++k) sum = fma(lane_bcast(a[k], i), x[k], sum);
+        x[i] = (l16 == i) ? id[i] : (l16 < i ? -sum * id[i] : 0.0);
+      }
+      if (lane < 16) {
+#pragma unroll
+        for (int c = 0; c < 16; ++c) {
+          if (c <= lane) S[(b0 + lane) * kLeafP + b0 + c] = a[c];
+          XD[(d * 16 + c) * kXdP + lane] = x[c];
+        }
+      }
     }
     __syncthreads();
-    const double rinv = invd[j];
-    for (int i = j + 1 + tid; i < s; i += kLeafThreads) S[i * kLeafPitch + j] *= rinv;
-    __syncthreads();
-    for (int i = j + 1 + ti; i < s; i += 32) {
-      const double lij = S[i * kLeafPitch + j];
-      for (int k = j + 1 + tk; k <= i; k += 32) S[i * kLeafPitch + k] -= lij * S[k * kLeafPitch + j];
+    // ---- sub-blocks below the diagonal one: L_id = G_id X_dd^T
+    for (int ib = d + 1 + wave; ib < nb; ib += 4) {
+      f64x4 acc = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        const double av = S[(16 * ib + l16) * kLeafP + b0 + 4 * kk + lq];
+        const double bv = XD[(d * 16 + l16) * kXdP + 4 * kk + lq];
+        acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) S[(16 * ib + 4 * r + lq) * kLeafP + b0 + l16] = acc[r];
     }
-    // the next pivot is written by this loop; the barrier at the top of the
-    // next iteration (after thread 0's section) is not enough for thread 0 itself
+    __syncthreads();
+    // ---- trailing sub-blocks (ib >= jb > d): G_ij -= L_id L_jd^T
+    {
+      const int T = nb - 1 - d;
+      const int cnt = T * (T + 1) / 2;
+      for (int q = wave; q < cnt; q += 4) {
+        int ii = 0, rem = q;
+        while (rem > ii) {
+          rem -= ii + 1;
+          ++ii;
+        }
+        const int ib = d + 1 + ii, jb = d + 1 + rem;
+        f64x4 acc = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+          const double av = S[(16 * ib + l16) * kLeafP + b0 + 4 * kk + lq];
+          const double bv = S[(16 * jb + l16) * kLeafP + b0 + 4 * kk + lq];
+          acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) S[(16 * ib + 4 * r + lq) * kLeafP + 16 * jb + l16] -= acc[r];
+      }
+    }
     __syncthreads();
   }
 
-  // inverse by forward substitution, eight threads per column c:
-  //   x_c[c] = 1/L_cc,   x_c[i] = -(sum_{k=c}^{i-1} L_ik x_c[k]) / L_ii
-  // x_c[k] (k > c) is kept at S[c][k]; columns are independent of each other.
-  const int c = tid >> 3, q = tid & 7;
-  const bool live = c < s;
-  const double xcc = live ? invd[c] : 0.0;
-  for (int i = 1; i < s; ++i) {
-    double sum = 0.0;
-    if (live && i > c) {
-      for (int k = c + q; k < i; k += 8) {
-        const double x = (k == c) ? xcc : S[c * kLeafPitch + k];
-        sum += S[i * kLeafPitch + k] * x;
+  // ---- inverse, one wave per block column jb:
+  //   X_ij = -X_ii * sum_{k=jb}^{ib-1} L_ik X_kj ;  X_kj (k > jb) is kept in sub-block (jb, k)
+  for (int jb = wave; jb < nb; jb += 4) {
+    for (int ib = jb + 1; ib < nb; ++ib) {
+      f64x4 t = {0.0, 0.0, 0.0, 0.0};
+      for (int k = jb; k < ib; ++k) {
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+          const double av = S[(16 * ib + l16) * kLeafP + 16 * k + 4 * kk + lq];
+          const double bv = (k == jb) ? XD[(jb * 16 + 4 * kk + lq) * kXdP + l16]
+                                      : S[(16 * jb + 4 * kk + lq) * kLeafP + 16 * k + l16];
+          t = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, t, 0, 0, 0);
+        }
       }
+      // the accumulator layout (row 4r + lane/16) is the B-fragment layout of k-step r
+      f64x4 xo = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        const double av = -XD[(ib * 16 + l16) * kXdP + 4 * kk + lq];
+        xo = __builtin_amdgcn_mfma_f64_16x16x4f64(av, t[kk], xo, 0, 0, 0);
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) S[(16 * jb + 4 * r + lq) * kLeafP + 16 * ib + l16] = xo[r];
     }
-    sum += __shfl_xor(sum, 1);
-    sum += __shfl_xor(sum, 2);
-    sum += __shfl_xor(sum, 4);
-    if (live && i > c && q == 0) S[c * kLeafPitch + i] = -sum * invd[i];
-    // the eight threads of a column sit in one wavefront, whose LDS accesses
-    // complete in program order, so the value is visible to them on the next i
-    __builtin_amdgcn_wave_barrier();
   }
   __syncthreads();
 
-  // X(i,j), i >= j, goes to U[n-1-(o+i)][n-1-(o+j)]
-  for (int e = tid; e < s * s; e += kLeafThreads) {
-    const int i = e / s, j = e % s;
-    if (j <= i) {
-      const double x = (i == j) ? invd[i] : S[j * kLeafPitch + i];
-      U[(int64_t)(n - 1 - (o + i)) * ldu + (n - 1 - (o + j))] = x;
-    }
+  // X(i, j), i >= j, goes to U[n-1-(o+i)][n-1-(o+j)]
+  for (int e = tid; e < sp * sp; e += 256) {
+    const int i = e / sp, j = e - i * sp;
+    if (i >= s || j > i) continue;
+    const int ib = i >> 4, jb = j >> 4;
+    const double x = (ib == jb) ? XD[(ib * 16 + (i & 15)) * kXdP + (j & 15)]
+                                : S[(16 * jb + (i & 15)) * kLeafP + 16 * ib + (j & 15)];
+    U[(int64_t)(n - 1 - (o + i)) * ldu + (n - 1 - (o + j))] = x;
   }
 }
 
@@ -169,7 +243,7 @@ struct Node {
 
 // L21 = G21 X11^T, stored transposed in the mirror block of G.
 struct OpPanel {
-  static constexpr bool A_KFAST = true, B_KFAST = true;
+  static constexpr bool A_KFAST = true, B_KFAST = true, REV_I = false, REV_J = true;
   Node nd;
   __device__ int M() const { return nd.s2; }
   __device__ int N() const { return nd.s1; }
@@ -184,7 +258,7 @@ struct OpPanel {
 
 // G22 -= L21 L21^T on the lower triangle.
 struct OpSyrk {
-  static constexpr bool A_KFAST = false, B_KFAST = false;
+  static constexpr bool A_KFAST = false, B_KFAST = false, REV_I = false, REV_J = false;
   Node nd;
   __device__ int M() const { return nd.s2; }
   __device__ int N() const { return nd.s2; }
@@ -199,7 +273,7 @@ struct OpSyrk {
 
 // T = L21 X11, stored in the dead G21 block.
 struct OpT {
-  static constexpr bool A_KFAST = false, B_KFAST = false;
+  static constexpr bool A_KFAST = false, B_KFAST = false, REV_I = false, REV_J = false;
   Node nd;
   __device__ int M() const { return nd.s2; }
   __device__ int N() const { return nd.s1; }
@@ -214,7 +288,7 @@ struct OpT {
 
 // X21 = -X22 T.
 struct OpX21 {
-  static constexpr bool A_KFAST = true, B_KFAST = false;
+  static constexpr bool A_KFAST = true, B_KFAST = false, REV_I = true, REV_J = false;
   Node nd;
   __device__ int M() const { return nd.s2; }
   __device__ int N() const { return nd.s1; }
@@ -234,7 +308,10 @@ template <int TM, int TN, class Op>
 __global__ __launch_bounds__(256) void node_gemm_kernel(Op op) {
   using T = DgemmTile<TM, TN>;
   extern __shared__ double smem[];
-  const int i0 = blockIdx.y * T::BM, j0 = blockIdx.x * T::BN;
+  // tiles with the longest k range first (triangular operands make them uneven)
+  const int bi = Op::REV_I ? gridDim.y - 1 - blockIdx.y : blockIdx.y;
+  const int bj = Op::REV_J ? gridDim.x - 1 - blockIdx.x : blockIdx.x;
+  const int i0 = bi * T::BM, j0 = bj * T::BN;
   const int i1 = min(i0 + T::BM, op.M()), j1 = min(j0 + T::BN, op.N());
   if (!op.active(i0, i1, j0, j1)) return;
   int kb, ke;
@@ -272,8 +349,7 @@ void launch_node(const Op& op, int M, int N, hipStream_t st) {
 
 void recurse(double* G, double* U, int ldu, int n, int o, int s, int32_t* info, hipStream_t st) {
   if (s <= kLeaf) {
-    const size_t lds = (size_t)(kLeaf * kLeafPitch + kLeaf) * sizeof(double);
-    leaf_kernel<<<1, kLeafThreads, lds, st>>>(G, n, o, s, U, ldu, info);
+    leaf_kernel<<<1, 256, kLeafLdsBytes, st>>>(G, n, o, s, U, ldu, info);
     return;
   }
   const int nb = (int)ceil_div(s, kLeaf);
@@ -304,9 +380,8 @@ ptq_status cholesky_launch(const double* H, int64_t ldh, int64_t n, double damp,
                                            align_up((size_t)n * (size_t)n * sizeof(double), 256));
   static bool lds_opt_in = false;
   if (!lds_opt_in) {
-    const int lds = (kLeaf * kLeafPitch + kLeaf) * (int)sizeof(double);
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(leaf_kernel),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLeafLdsBytes) != hipSuccess)
       return PTQ_ERR_HIP;
     lds_opt_in = true;
   }

@@ -39,8 +39,13 @@ __global__ __launch_bounds__(256) void widen_kernel(const void* __restrict__ W, 
 __global__ __launch_bounds__(256) void quad_form_kernel(ErrArgs a) {
   extern __shared__ double smem[];
   __shared__ double red[256];
-  const int z = blockIdx.z;
-  const int i0 = blockIdx.y * Tile::BM, j0 = blockIdx.x * Tile::BN;
+  // column tiles have k ranges proportional to their index: the widest are dispatched
+  // first (blockIdx.y is the slow grid index), the two quadratic forms share blockIdx.x
+  const int nrt = gridDim.x >> 1;
+  const int z = blockIdx.x / nrt;
+  const int rt = blockIdx.x - z * nrt;
+  const int ct = gridDim.y - 1 - blockIdx.y;
+  const int i0 = rt * Tile::BM, j0 = ct * Tile::BN;
   const int j1 = min(j0 + Tile::BN, a.n);
   const int i1 = min(i0 + Tile::BM, a.m);
   const double* Az = a.A2 + (int64_t)z * a.m * a.n;
@@ -65,7 +70,7 @@ __global__ __launch_bounds__(256) void quad_form_kernel(ErrArgs a) {
     __syncthreads();
   }
   if (threadIdx.x == 0)
-    a.partial[(int64_t)z * gridDim.x * gridDim.y + blockIdx.y * gridDim.x + blockIdx.x] = red[0];
+    a.partial[((int64_t)z * nrt + rt) * gridDim.y + ct] = red[0];
 }
 
 __global__ __launch_bounds__(256) void finish_kernel(const double* __restrict__ partial, int tiles,
@@ -117,8 +122,8 @@ ptq_status layer_error_launch(const void* W, ptq_dtype wdt, int64_t ldw, const d
     default: return PTQ_ERR_DTYPE;
   }
   ErrArgs a{A2, (int)m, (int)n, H, (int)ldh, partial};
-  dim3 g((unsigned)ceil_div(n, Tile::BN), (unsigned)ceil_div(m, Tile::BM), 2);
-  const int tiles = (int)(g.x * g.y);
+  dim3 g(2 * (unsigned)ceil_div(m, Tile::BM), (unsigned)ceil_div(n, Tile::BN));
+  const int tiles = (int)(g.x / 2 * g.y);
   constexpr int lds = Tile::kSmemDoubles * (int)sizeof(double);
   static bool opted_in = false;
   if (!opted_in) {
