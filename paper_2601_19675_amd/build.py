@@ -14,10 +14,12 @@ FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-result",
     # packed-FP32 instructions are kept out of every kernel
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    # accumulators of the matrix instructions stay in ordinary VGPRs: every kernel here
-    # fits 256 registers, and the AGPR form costs copies around each MFMA
-    "-mllvm", "-amdgpu-mfma-vgpr-form",
 ]
+# Accumulators of the float64 matrix instructions stay in ordinary VGPRs (those kernels fit
+# 256 registers, and the AGPR form costs copies around each MFMA).  The bf16 Hessian kernel
+# needs all 256 AGPRs for its accumulators and is compiled without the option.
+VGPR_FORM = ["-mllvm", "-amdgpu-mfma-vgpr-form"]
+NO_VGPR_FORM = {"hessian.hip"}
 
 
 def _hipcc() -> str:
@@ -34,7 +36,8 @@ def build(verbose: bool = True) -> str:
 
     def compile_one(src):
         obj = os.path.join(CSRC, src.replace(".hip", ".o"))
-        cmd = [hipcc, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        extra = [] if src in NO_VGPR_FORM else VGPR_FORM
+        cmd = [hipcc, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
             raise RuntimeError(f"hipcc failed for {src}:\n{r.stdout}\n{r.stderr}")

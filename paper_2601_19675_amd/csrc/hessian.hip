@@ -24,7 +24,8 @@ namespace {
 constexpr int kTile = 128;      // bf16 macro tile (channels x channels)
 constexpr int kKT = 32;         // tokens per LDS stage
 constexpr int kPitch = kTile + 8;  // bf16 elements; 272-byte rows
-constexpr int kMaxChunk = 8192;
+constexpr int kMaxChunk = 8192;      // tokens summed in float32 before the float64 reduction
+constexpr int kMaxChunkBig = 20480;  // ... in the 256 x 256-tile kernel (fewer, larger partial tiles)
 
 constexpr int kTile32 = 64;     // f32-path tile
 constexpr int kKT32 = 16;
@@ -137,6 +138,143 @@ __global__ __launch_bounds__(256) void hessian_bf16_kernel(const uint16_t* __res
       }
 }
 
+// ---- large layers: 256 x 256 tile, each wave 128 x 128 (4 x 4 MFMA tiles) ------
+// Same transposition trick with 8-byte LDS reads: a lane gets channels 4p..4p+3
+// for eight tokens, four byte-permutes per token pair give the fragments of the
+// channel classes c % 4 = 0..3, one class per MFMA tile.  A wave then issues 16
+// MFMAs (512 matrix-pipe cycles) per 16 LDS reads, so LDS sits at about half of
+// its bandwidth; accumulators fill the 256 AGPRs.  LDS is double-buffered with
+// one barrier per 32 tokens, and the global loads of tile t+2 are issued before
+// the MFMAs of tile t.
+constexpr int kBT = 256;
+constexpr int kBP = kBT + 8;                       // 528-byte rows
+constexpr int kBStage = 2 * kKT * kBP;             // A and B, bf16 elements
+constexpr size_t kBigLdsBytes = 2 * kBStage * sizeof(uint16_t);
+
+template <bool diag>
+__device__ __forceinline__ void big_tile(const uint16_t* __restrict__ X, int64_t ldx, int64_t t, int n,
+                                         int64_t tok0, int chunk, int I, int J, float* __restrict__ partial,
+                                         uint16_t* hs) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wi = wave >> 1, wj = wave & 1;
+  const int64_t kbeg = tok0 + (int64_t)blockIdx.y * chunk;
+  const int64_t kend = (kbeg + chunk < t) ? kbeg + chunk : t;
+
+  f32x16 acc[4][4];
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+
+  if (kbeg < kend) {
+    // global -> LDS map: 32 threads cover one token row (8 channels = 16 bytes each)
+    const int lrow = tid >> 5, lcol = (tid & 31) * 8;
+    const bool a_in = (I * kBT + lcol) < n, b_in = (J * kBT + lcol) < n;
+    const uint16_t* ga = X + (kbeg + lrow) * ldx + (a_in ? I * kBT + lcol : 0);
+    const uint16_t* gb = X + (kbeg + lrow) * ldx + (b_in ? J * kBT + lcol : 0);
+    const int64_t rstep = 8 * ldx;
+    typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
+    u32x4 ra[4], rb[4];
+    auto fetch = [&](int64_t k0) {
+      if (k0 + kKT <= kend) {
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+          ra[p] = *reinterpret_cast<const u32x4*>(ga + p * rstep);
+          if (!diag) rb[p] = *reinterpret_cast<const u32x4*>(gb + p * rstep);
+        }
+      } else {  // last, partial stage: rows beyond the chunk re-read its last token
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+          const int64_t over = k0 + lrow + 8 * p - (kend - 1);
+          const int64_t back = (over > 0 ? over : 0) * ldx;
+          ra[p] = *reinterpret_cast<const u32x4*>(ga + p * rstep - back);
+          if (!diag) rb[p] = *reinterpret_cast<const u32x4*>(gb + p * rstep - back);
+        }
+      }
+      ga += kKT * ldx;
+      gb += kKT * ldx;
+    };
+    auto stash = [&](int64_t k0, uint16_t* st) {
+#pragma unroll
+      for (int p = 0; p < 4; ++p) {
+        const bool kin = k0 + lrow + 8 * p < kend;
+        const uint32_t ma = (kin && a_in) ? 0xffffffffu : 0u, mb = (kin && b_in) ? 0xffffffffu : 0u;
+        *reinterpret_cast<u32x4*>(&st[(lrow + 8 * p) * kBP + lcol]) = ra[p] & ma;
+        if (!diag) *reinterpret_cast<u32x4*>(&st[kKT * kBP + (lrow + 8 * p) * kBP + lcol]) = rb[p] & mb;
+      }
+    };
+    // fragments of the channel classes c % 4 of a 128-channel strip, tokens ks*16 + kg*8 .. +7
+    auto fragments = [&](const uint16_t* T, int strip, int ks, bf16x8 (&f)[4]) {
+      const int p = lane & 31, kg = lane >> 5;
+      const uint16_t* src = T + (ks * 16 + kg * 8) * kBP + strip * 128 + 4 * p;
+      uint2 d[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) d[i] = *reinterpret_cast<const uint2*>(src + i * kBP);
+      u32x4 v[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        v[0][i] = __builtin_amdgcn_perm(d[2 * i + 1].x, d[2 * i].x, 0x05040100u);
+        v[1][i] = __builtin_amdgcn_perm(d[2 * i + 1].x, d[2 * i].x, 0x07060302u);
+        v[2][i] = __builtin_amdgcn_perm(d[2 * i + 1].y, d[2 * i].y, 0x05040100u);
+        v[3][i] = __builtin_amdgcn_perm(d[2 * i + 1].y, d[2 * i].y, 0x07060302u);
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) f[q] = __builtin_bit_cast(bf16x8, v[q]);
+    };
+
+    fetch(kbeg);
+    stash(kbeg, hs);
+    if (kbeg + kKT < kend) fetch(kbeg + kKT);
+    __syncthreads();
+    int cur = 0;
+    for (int64_t k0 = kbeg; k0 < kend; k0 += kKT) {
+      const uint16_t* As = hs + cur * kBStage;
+      const uint16_t* Bs = diag ? As : As + kKT * kBP;
+      if (k0 + kKT < kend) stash(k0 + kKT, hs + (cur ^ 1) * kBStage);
+      if (k0 + 2 * kKT < kend) fetch(k0 + 2 * kKT);
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        bf16x8 fa[4], fb[4];
+        fragments(As, wi, ks, fa);
+        fragments(Bs, wj, ks, fb);
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+          for (int b = 0; b < 4; ++b)
+            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+      }
+      __syncthreads();
+      cur ^= 1;
+    }
+  }
+
+  float* out = partial + ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * (kBT * kBT);
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int il = (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+        const int jl = lane & 31;
+        out[(wi * 128 + 4 * il + a) * kBT + wj * 128 + 4 * jl + b] = acc[a][b][r];
+      }
+}
+
+__global__ __launch_bounds__(256) void hessian_bf16_big_kernel(const uint16_t* __restrict__ X, int64_t ldx,
+                                                               int64_t t, int n, int64_t tok0, int chunk,
+                                                               int ntb, float* __restrict__ partial) {
+  extern __shared__ __attribute__((aligned(16))) uint16_t hs[];
+  int I, J;
+  tile_from_linear(blockIdx.x, ntb, I, J);
+  if (I == J)
+    big_tile<true>(X, ldx, t, n, tok0, chunk, I, J, partial, hs);
+  else
+    big_tile<false>(X, ldx, t, n, tok0, chunk, I, J, partial, hs);
+}
+
 // float32 activations: float64 FMAs, 64 x 64 tile, 4 x 4 outputs per thread.
 __global__ __launch_bounds__(256) void hessian_f32_kernel(const float* __restrict__ X, int64_t ldx,
                                                           int64_t t, int n, int64_t tok0, int chunk,
@@ -204,24 +342,41 @@ struct Plan {
   size_t tile_bytes;
 };
 
+constexpr int64_t kBigFrom = 2048;                   // layers at least this wide use the 256-tile kernel
+constexpr size_t kMaxPartialBytes = (size_t)1 << 30;  // partial tiles in flight per launch
+
 Plan make_plan(int64_t n, int64_t t, ptq_dtype dt) {
   Plan p;
-  p.tile = (dt == PTQ_BF16) ? kTile : kTile32;
+  const bool big = (dt == PTQ_BF16) && n >= kBigFrom;
+  p.tile = (dt == PTQ_BF16) ? (big ? kBT : kTile) : kTile32;
   const int kt = (dt == PTQ_BF16) ? kKT : kKT32;
   p.ntb = (int)ceil_div(n, p.tile);
   p.ntiles = p.ntb * (p.ntb + 1) / 2;
-  // enough workgroups to fill 256 CUs several times, at most 8192 tokens each
-  int64_t chunk = ceil_div(t * p.ntiles, 4096);
-  chunk = ceil_div(chunk, kt) * kt;
-  if (chunk < 256) chunk = 256;
-  if (chunk > kMaxChunk) chunk = kMaxChunk;
+  // Split the tokens so that the workgroups fill 256 CUs in whole rounds, with at most
+  // max_chunk tokens summed in float32 by one workgroup: pick the split count with the
+  // least (rounds x work per split).
+  const int64_t max_chunk = big ? kMaxChunkBig : kMaxChunk;
+  const int64_t s_min = ceil_div(t > 0 ? t : 1, max_chunk);
+  int64_t best_s = s_min, best_cost = -1;
+  for (int64_t sp = s_min; sp < s_min + 64; ++sp) {
+    int64_t ch = ceil_div(ceil_div(t > 0 ? t : 1, sp), kt) * kt;
+    if (ch < 256 && sp > s_min) break;
+    // + 1024: writing and re-reading a partial tile costs about as much as 1024 tokens
+    const int64_t cost = ceil_div(p.ntiles * sp, 256) * (ch + 1024);
+    if (best_cost < 0 || cost < best_cost) {
+      best_cost = cost;
+      best_s = sp;
+    }
+  }
+  int64_t chunk = ceil_div(ceil_div(t > 0 ? t : 1, best_s), kt) * kt;
+  if (chunk < kt) chunk = kt;
   p.chunk = (int)chunk;
   p.splits_total = (int)ceil_div(t > 0 ? t : 1, chunk);
-  int sl = (int)ceil_div(2048, p.ntiles);
+  p.tile_bytes = (size_t)p.tile * p.tile * ((dt == PTQ_BF16) ? sizeof(float) : sizeof(double));
+  int64_t sl = big ? (int64_t)(kMaxPartialBytes / (p.tile_bytes * p.ntiles)) : ceil_div(2048, p.ntiles);
   if (sl > p.splits_total) sl = p.splits_total;
   if (sl < 1) sl = 1;
-  p.splits_launch = sl;
-  p.tile_bytes = (size_t)p.tile * p.tile * ((dt == PTQ_BF16) ? sizeof(float) : sizeof(double));
+  p.splits_launch = (int)sl;
   return p;
 }
 
@@ -245,7 +400,19 @@ ptq_status hessian_launch(double* H, int64_t ldh, const void* X, ptq_dtype xdt, 
     const int64_t tok0 = (int64_t)s0 * p.chunk;
     dim3 g((unsigned)p.ntiles, (unsigned)ns);
     dim3 gr((unsigned)p.ntiles, (unsigned)(p.tile * p.tile / 256));
-    if (xdt == PTQ_BF16) {
+    if (xdt == PTQ_BF16 && p.tile == kBT) {
+      static bool opted_in = false;
+      if (!opted_in) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(hessian_bf16_big_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kBigLdsBytes) != hipSuccess)
+          return PTQ_ERR_HIP;
+        opted_in = true;
+      }
+      hessian_bf16_big_kernel<<<g, 256, kBigLdsBytes, st>>>(static_cast<const uint16_t*>(X), ldx, t, (int)n,
+                                                            tok0, p.chunk, p.ntb, static_cast<float*>(ws));
+      hessian_reduce_kernel<float, kBT><<<gr, 256, 0, st>>>(static_cast<const float*>(ws), ns, p.ntiles,
+                                                            p.ntb, (int)n, H, ldh);
+    } else if (xdt == PTQ_BF16) {
       hessian_bf16_kernel<<<g, 256, 0, st>>>(static_cast<const uint16_t*>(X), ldx, t, (int)n, tok0, p.chunk,
                                              p.ntb, static_cast<float*>(ws));
       hessian_reduce_kernel<float, kTile><<<gr, 256, 0, st>>>(static_cast<const float*>(ws), ns, p.ntiles,
