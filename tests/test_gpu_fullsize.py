@@ -1,0 +1,237 @@
+"""GPU parity at the benchmark configurations' own sizes (Llama-2-7B-shaped
+layers), in the launch configuration bench.py times.
+
+The oracle cannot solve 262144 tokens x 11008 channels in seconds, so:
+  * the stage-wise checks use the oracle's own chain on a token prefix
+    (H and U from the oracle, fed to the GPU stage under test), with the
+    column solve compared on a random sample of rows (rows are independent
+    given U, so the oracle solves exactly those rows);
+  * the Hessian over ALL tokens is compared on a sampled sub-block of
+    channels whose Gram matrix the oracle computes directly;
+  * one test runs the second configuration end to end on all tokens
+    against the full oracle chain.
+Progress lines are printed as the slow CPU parts finish.
+"""
+import sys
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2601_19675_amd as ptq
+import ptq_workloads as wl
+from oracle import ptq_oracle as orc
+from parity import compare_quantization, hessian_errors, to_device
+
+pytestmark = pytest.mark.gpu
+
+_T0 = time.time()
+
+
+def say(capsys, msg):
+    with capsys.disabled():
+        print(f"  [{time.time() - _T0:6.1f}s] {msg}", flush=True)
+
+
+class GpuLayer:
+    """Device buffers of one layer and the four calls of the path."""
+
+    def __init__(self, Ws, n, group):
+        self.W = to_device(Ws)
+        self.m, self.n, self.group = self.W.shape[0], n, group
+        d = "cuda"
+        self.H = torch.zeros((n, n), dtype=torch.float64, device=d)
+        self.U = torch.empty((n, n), dtype=torch.float64, device=d)
+        self.dead = torch.empty((n,), dtype=torch.uint8, device=d)
+        self.info = torch.empty((2,), dtype=torch.int32, device=d)
+        self.codes = torch.empty((self.m, n), dtype=torch.uint8, device=d)
+        self.scales = torch.empty((self.m, n // group), dtype=torch.float32, device=d)
+        self.zeros = torch.empty((self.m, n // group), dtype=torch.uint8, device=d)
+        self.Wq = torch.empty((self.m, n), dtype=torch.float64, device=d)
+        self.err2 = torch.empty((self.m,), dtype=torch.float64, device=d)
+        self.out = torch.zeros(3, dtype=torch.float64, device=d)
+
+    def hessian(self, Xs, slab=65536):
+        self.H.zero_()
+        for lo in range(0, Xs.shape[0], slab):
+            ptq.ptq_hessian_accumulate(self.H, to_device(Xs[lo:lo + slab]))
+        torch.cuda.synchronize()
+
+    def factor(self, damp, H=None):
+        ptq.ptq_damped_cholesky_inv(self.H if H is None else H, damp, self.U, self.dead, self.info)
+        torch.cuda.synchronize()
+        assert self.info.cpu().tolist() == [0, 0]
+
+    def quantize(self, bits, block, U=None, dead=None):
+        ptq.ptq_quantize_layer(self.W, self.U if U is None else U, dead, bits, self.group, block, self.codes,
+                               self.scales, self.zeros, self.Wq, self.err2)
+        torch.cuda.synchronize()
+
+    def error(self, H=None):
+        ptq.ptq_layer_error(self.W, self.Wq, self.H if H is None else H, self.out)
+        torch.cuda.synchronize()
+        return self.out.cpu().numpy()
+
+
+def stagewise(capsys, spec, bits, group, block, damps, t_test, n_rows=48, seed=wl.BASE_SEED):
+    """Every stage on the GPU at the layer's full m x n, each fed the oracle's
+    upstream result computed from the first t_test tokens."""
+    m, n = spec.m, spec.n
+    sub = wl.scaled(spec, t=t_test)
+    Ws, Xs = wl.gen_weight(sub, seed), wl.gen_activations(sub, seed)
+    W64 = wl.to_f64(Ws)
+    Href = orc.hessian(wl.to_f64(Xs))
+    say(capsys, f"{spec.name} {m}x{n}: oracle H from {t_test} tokens done")
+    g = GpuLayer(Ws, n, group)
+    g.hessian(Xs)
+    fro, ent = hessian_errors(g.H.cpu().numpy(), Href)
+    assert fro <= 1e-5 and ent <= 1e-5, (fro, ent)
+    Hdev = torch.from_numpy(np.triu(Href)).cuda()
+    rng = np.random.default_rng(n + m + bits)
+    rows = np.sort(rng.choice(m, n_rows, replace=False))
+    rows[0], rows[-1] = 0, m - 1
+    for damp in damps:
+        Hd, dead = orc.damp(Href, damp)
+        Uref = orc.inverse_cholesky_upper(Hd)
+        say(capsys, f"  damp {damp}: oracle factor done")
+        g.factor(damp, Hdev)
+        du = np.max(np.abs(g.U.cpu().numpy() - Uref)) / np.max(np.abs(Uref))
+        assert du <= 1e-9, du
+        Udev = torch.from_numpy(Uref).cuda()
+        g.quantize(bits, block, U=Udev)
+        codes, scales, zeros = g.codes.cpu().numpy(), g.scales.cpu().numpy(), g.zeros.cpu().numpy()
+        rep = compare_quantization(W64[rows], Uref, bits, group, None, codes[rows], scales[rows], zeros[rows])
+        say(capsys, f"  damp {damp}: H err {fro:.1e}, U err {du:.1e}, sampled rows exact {rep['exact_rows']}/{n_rows}, "
+                    f"flagged c/z/s {rep['flagged_codes']}/{rep['flagged_zeros']}/{rep['flagged_scales']}, "
+                    f"unflagged {rep['unflagged']}")
+        assert rep["unflagged"] == 0, rep["details"][:5]
+        assert rep["flagged_codes"] + rep["flagged_zeros"] + rep["flagged_scales"] <= 2
+        # every row, not just the sample: outputs are a valid quantization of something
+        assert codes.max() <= 2 ** bits - 1 and zeros.max() <= 2 ** bits - 1 and np.all(scales > 0)
+        Wq = g.Wq.cpu().numpy()
+        assert np.array_equal(Wq, orc.dequantize(codes, scales, zeros, group))
+        # sum e^2 = tr(D H_d D^T) holds for all rows at any size
+        D = W64 - Wq
+        lhs = np.einsum("ij,ij->i", D @ Hd, D)
+        assert np.allclose(lhs, g.err2.cpu().numpy(), rtol=1e-7, atol=0)
+        rel, num, den = g.error(Hdev)
+        r0, n0, d0 = orc.layer_error(W64, Wq, Href)
+        say(capsys, f"  damp {damp}: rel layer error gpu {rel:.6f} oracle {r0:.6f}")
+        assert abs(rel - r0) <= 1e-4 and abs(num - n0) <= 1e-9 * n0 and abs(den - d0) <= 1e-9 * d0
+    del g
+    torch.cuda.empty_cache()
+
+
+def test_config2_attention_projection_stagewise(capsys):
+    cfg = wl.CONFIGS["C2"]
+    stagewise(capsys, cfg.layers[0], cfg.bits, cfg.group, cfg.block, cfg.damps, t_test=8192)
+
+
+def test_config4_two_bit_damp_sweep(capsys):
+    cfg = wl.CONFIGS["C4"]
+    stagewise(capsys, cfg.layers[0], cfg.bits, cfg.group, cfg.block, cfg.damps, t_test=8192)
+
+
+def test_config3_up_proj_stagewise(capsys):
+    cfg = wl.CONFIGS["C3"]
+    stagewise(capsys, cfg.layers[0], cfg.bits, cfg.group, cfg.block, cfg.damps, t_test=8192)
+
+
+def test_config3_down_proj_stagewise(capsys):
+    cfg = wl.CONFIGS["C3"]
+    stagewise(capsys, cfg.layers[1], cfg.bits, cfg.group, cfg.block, cfg.damps, t_test=12288, n_rows=24)
+
+
+def test_config5_decoder_block(capsys):
+    """The seven linears one after another.  The six with 4096 input channels
+    go through the stage-wise protocol; down_proj (whose shape the test above
+    covers against the oracle) runs the whole GPU chain and is checked through
+    the identities that hold at any size."""
+    cfg = wl.CONFIGS["C5"]
+    for spec in cfg.layers[:6]:
+        stagewise(capsys, spec, cfg.bits, cfg.group, cfg.block, cfg.damps, t_test=4096, n_rows=16)
+    spec = wl.scaled(cfg.layers[6], t=16384)
+    Ws, Xs = wl.gen_weight(spec), wl.gen_activations(spec)
+    g = GpuLayer(Ws, spec.n, cfg.group)
+    g.hessian(Xs)
+    g.factor(cfg.damps[0])
+    g.quantize(cfg.bits, cfg.block, dead=g.dead)
+    rel = g.error()[0]
+    say(capsys, f"down_proj GPU chain: rel layer error {rel:.6f}")
+    # the factor: U upper, positive diagonal, U^T U H_d v = v for random v
+    U = g.U.cpu().numpy()
+    H = orc.symmetrize_from_upper(g.H.cpu().numpy())
+    Hd, _ = orc.damp(H, cfg.damps[0])
+    assert np.all(np.diag(U) > 0)
+    v = np.random.default_rng(0).standard_normal((spec.n, 4))
+    w = U.T @ (U @ (Hd @ v))
+    assert np.max(np.abs(w - v)) <= 1e-8 * np.max(np.abs(v))
+    Wq = g.Wq.cpu().numpy()
+    D = wl.to_f64(Ws) - Wq
+    lhs = np.einsum("ij,ij->i", D @ Hd, D)
+    assert np.allclose(lhs, g.err2.cpu().numpy(), rtol=1e-7, atol=0)
+    assert 0 < rel < 1
+
+
+def test_hessian_all_tokens_sampled_channels(capsys):
+    """H over all 262144 tokens of the second configuration, in one call as
+    bench.py issues it, against the directly computed Gram matrix of 40 channels."""
+    spec = wl.CONFIGS["C2"].layers[0]
+    Xs = wl.gen_activations(spec)
+    say(capsys, "generated X 262144 x 4096")
+    X = to_device(Xs)
+    H = torch.zeros((spec.n, spec.n), dtype=torch.float64, device="cuda")
+    ptq.ptq_hessian_accumulate(H, X)
+    torch.cuda.synchronize()
+    Hg = H.cpu().numpy()
+    ch = np.sort(np.random.default_rng(1).choice(spec.n, 40, replace=False))
+    ch[0], ch[-1] = 0, spec.n - 1
+    Xc = wl.to_f64(np.ascontiguousarray(Xs[:, ch]))
+    Gref = Xc.T @ Xc
+    fro, ent = hessian_errors(Hg[np.ix_(ch, ch)], Gref)
+    say(capsys, f"H over all tokens, 40 sampled channels: frobenius {fro:.2e}, scaled entry-wise {ent:.2e}")
+    assert fro <= 1e-5 and ent <= 1e-5
+    # and the run is reproducible bit for bit
+    H2 = torch.zeros_like(H)
+    ptq.ptq_hessian_accumulate(H2, X)
+    torch.cuda.synchronize()
+    assert torch.equal(torch.triu(H), torch.triu(H2))
+
+
+def test_config2_end_to_end_all_tokens(capsys):
+    """Whole path on the GPU from X and W only, against the whole oracle chain."""
+    cfg = wl.CONFIGS["C2"]
+    spec = cfg.layers[0]
+    Ws, Xs = wl.gen_weight(spec), wl.gen_activations(spec)
+    W64 = wl.to_f64(Ws)
+    g = GpuLayer(Ws, spec.n, cfg.group)
+    g.hessian(Xs, slab=spec.t)
+    g.factor(cfg.damps[0])
+    g.quantize(cfg.bits, cfg.block, dead=g.dead)
+    rel_gpu = g.error()[0]
+    say(capsys, f"GPU chain done, rel layer error {rel_gpu:.6f}")
+    Href = np.zeros((spec.n, spec.n))
+    for lo in range(0, spec.t, 32768):
+        orc.hessian(wl.to_f64(Xs[lo:lo + 32768]), Href)
+    say(capsys, "oracle H over all tokens done")
+    fro, ent = hessian_errors(g.H.cpu().numpy(), Href)
+    assert fro <= 1e-5 and ent <= 1e-5, (fro, ent)
+    Hd, dead = orc.damp(Href, cfg.damps[0])
+    Uref = orc.inverse_cholesky_upper(Hd)
+    du = np.max(np.abs(g.U.cpu().numpy() - Uref)) / np.max(np.abs(Uref))
+    say(capsys, f"oracle factor done; H err {fro:.1e}/{ent:.1e}, U (from GPU H) vs oracle U {du:.1e}")
+    assert du <= 1e-5
+    o = orc.quantize_layer(W64, Uref, cfg.bits, cfg.group)
+    rel_ref = orc.layer_error(W64, o["Wq"], Href)[0]
+    codes = g.codes.cpu().numpy()
+    agree = float(np.mean(codes == o["codes"]))
+    rows_same = int(np.sum(np.all(codes == o["codes"], axis=1)))
+    # the GPU's own quantized weights judged by the oracle's error routine and Hessian
+    rel_gpu_by_oracle = orc.layer_error(W64, g.Wq.cpu().numpy(), Href)[0]
+    say(capsys, f"rel layer error: gpu {rel_gpu:.6f}, gpu result judged by oracle {rel_gpu_by_oracle:.6f}, "
+                f"oracle chain {rel_ref:.6f}; codes equal {100 * agree:.4f}% ({rows_same}/{spec.m} rows identical)")
+    assert abs(rel_gpu - rel_ref) <= 1e-4 and abs(rel_gpu_by_oracle - rel_gpu) <= 1e-6
+    # H differs from the oracle's by ~1e-7, so a small share of near-tie decisions may fall
+    # the other way; the stage-wise tests hold the bit-exact bar, this one bounds the drift
+    assert agree >= 0.999
