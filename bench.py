@@ -67,6 +67,9 @@ def main():
     ap.add_argument("--config", default="C2")
     ap.add_argument("--layer", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run plain 1 GiB device copies and exit (reference reading for the "
+                         "FETCH_SIZE / WRITE_SIZE counters under rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (the path has no multi-GPU part); use --gpus 1",
@@ -77,7 +80,6 @@ def main():
 
     import paper_2601_19675_amd as ptq
     import ptq_workloads as wl
-    from paper_2601_19675_amd import binding as B
 
     sys.path.insert(0, os.path.join(ROOT, "tests"))
     from parity import to_device
@@ -87,6 +89,15 @@ def main():
         build.build()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")   # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": 1 << 30, "copy_bytes_written": 1 << 30, "copies": 3}))
+        return
 
     cfg = wl.CONFIGS[args.config]
     spec = cfg.layers[args.layer]

@@ -144,21 +144,24 @@ __global__ __launch_bounds__(256) void hessian_bf16_kernel(const uint16_t* __res
 // channel classes c % 4 = 0..3, one class per MFMA tile.  A wave then issues 16
 // MFMAs (512 matrix-pipe cycles) per 16 LDS reads, so LDS sits at about half of
 // its bandwidth; accumulators fill the 256 AGPRs.  LDS is double-buffered with
-// one barrier per 32 tokens, and the global loads of tile t+2 are issued before
-// the MFMAs of tile t.
+// one barrier per 64 tokens; the global loads of tile t+2, the LDS stores of
+// tile t+1 and the fragments of the next 16 tokens are issued between the MFMAs
+// of the current 16 tokens.
 constexpr int kBT = 256;
 constexpr int kBP = kBT + 8;                       // 528-byte rows
-constexpr int kBStage = 2 * kKT * kBP;             // A and B, bf16 elements
+constexpr int kBKT = 64;                           // tokens per LDS stage
+constexpr int kBStage = 2 * kBKT * kBP;            // A and B, bf16 elements
 constexpr size_t kBigLdsBytes = 2 * kBStage * sizeof(uint16_t);
 
 template <bool diag>
 __device__ __forceinline__ void big_tile(const uint16_t* __restrict__ X, int64_t ldx, int64_t t, int n,
-                                         int64_t tok0, int chunk, int I, int J, float* __restrict__ partial,
-                                         uint16_t* hs) {
+                                         int64_t tok0, int chunk, int I, int J, int split,
+                                         float* __restrict__ out, uint16_t* hs) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wi = wave >> 1, wj = wave & 1;
-  const int64_t kbeg = tok0 + (int64_t)blockIdx.y * chunk;
+  const int64_t kbeg = tok0 + (int64_t)split * chunk;
   const int64_t kend = (kbeg + chunk < t) ? kbeg + chunk : t;
+  typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
 
   f32x16 acc[4][4];
 #pragma unroll
@@ -169,40 +172,38 @@ __device__ __forceinline__ void big_tile(const uint16_t* __restrict__ X, int64_t
       for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
   if (kbeg < kend) {
-    // global -> LDS map: 32 threads cover one token row (8 channels = 16 bytes each)
+    // global -> LDS map: 32 threads cover one token row (8 channels = 16 bytes each),
+    // eight rows per pass.  Rows past the end of the chunk re-read its last token
+    // (pointer clamp, no branch) and are zeroed on the way into LDS.
+    constexpr int kPass = kBKT / 8;
     const int lrow = tid >> 5, lcol = (tid & 31) * 8;
     const bool a_in = (I * kBT + lcol) < n, b_in = (J * kBT + lcol) < n;
     const uint16_t* ga = X + (kbeg + lrow) * ldx + (a_in ? I * kBT + lcol : 0);
     const uint16_t* gb = X + (kbeg + lrow) * ldx + (b_in ? J * kBT + lcol : 0);
+    const uint16_t* la = X + (kend - 1) * ldx + (a_in ? I * kBT + lcol : 0);
+    const uint16_t* lb = X + (kend - 1) * ldx + (b_in ? J * kBT + lcol : 0);
     const int64_t rstep = 8 * ldx;
-    typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
-    u32x4 ra[4], rb[4];
-    auto fetch = [&](int64_t k0) {
-      if (k0 + kKT <= kend) {
+    u32x4 ra[kPass], rb[kPass];
+    auto fetch = [&]() {
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
-          ra[p] = *reinterpret_cast<const u32x4*>(ga + p * rstep);
-          if (!diag) rb[p] = *reinterpret_cast<const u32x4*>(gb + p * rstep);
-        }
-      } else {  // last, partial stage: rows beyond the chunk re-read its last token
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-          const int64_t over = k0 + lrow + 8 * p - (kend - 1);
-          const int64_t back = (over > 0 ? over : 0) * ldx;
-          ra[p] = *reinterpret_cast<const u32x4*>(ga + p * rstep - back);
-          if (!diag) rb[p] = *reinterpret_cast<const u32x4*>(gb + p * rstep - back);
+      for (int p = 0; p < kPass; ++p) {
+        const uint16_t* pa = ga + p * rstep;
+        ra[p] = *reinterpret_cast<const u32x4*>(pa < la ? pa : la);
+        if (!diag) {
+          const uint16_t* pb = gb + p * rstep;
+          rb[p] = *reinterpret_cast<const u32x4*>(pb < lb ? pb : lb);
         }
       }
-      ga += kKT * ldx;
-      gb += kKT * ldx;
+      ga += kBKT * ldx;
+      gb += kBKT * ldx;
     };
     auto stash = [&](int64_t k0, uint16_t* st) {
 #pragma unroll
-      for (int p = 0; p < 4; ++p) {
+      for (int p = 0; p < kPass; ++p) {
         const bool kin = k0 + lrow + 8 * p < kend;
         const uint32_t ma = (kin && a_in) ? 0xffffffffu : 0u, mb = (kin && b_in) ? 0xffffffffu : 0u;
         *reinterpret_cast<u32x4*>(&st[(lrow + 8 * p) * kBP + lcol]) = ra[p] & ma;
-        if (!diag) *reinterpret_cast<u32x4*>(&st[kKT * kBP + (lrow + 8 * p) * kBP + lcol]) = rb[p] & mb;
+        if (!diag) *reinterpret_cast<u32x4*>(&st[kBKT * kBP + (lrow + 8 * p) * kBP + lcol]) = rb[p] & mb;
       }
     };
     // fragments of the channel classes c % 4 of a 128-channel strip, tokens ks*16 + kg*8 .. +7
@@ -223,34 +224,57 @@ __device__ __forceinline__ void big_tile(const uint16_t* __restrict__ X, int64_t
 #pragma unroll
       for (int q = 0; q < 4; ++q) f[q] = __builtin_bit_cast(bf16x8, v[q]);
     };
+    auto mfma16 = [&](const bf16x8 (&fa)[4], const bf16x8 (&fb)[4]) {
+#pragma unroll
+      for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+    };
 
-    fetch(kbeg);
+    // stage s holds tile s; registers hold tile s+1 until it is stored
+    fetch();
     stash(kbeg, hs);
-    if (kbeg + kKT < kend) fetch(kbeg + kKT);
+    fetch();
     __syncthreads();
     int cur = 0;
-    for (int64_t k0 = kbeg; k0 < kend; k0 += kKT) {
+    for (int64_t k0 = kbeg; k0 < kend; k0 += kBKT) {
       const uint16_t* As = hs + cur * kBStage;
-      const uint16_t* Bs = diag ? As : As + kKT * kBP;
-      if (k0 + kKT < kend) stash(k0 + kKT, hs + (cur ^ 1) * kBStage);
-      if (k0 + 2 * kKT < kend) fetch(k0 + 2 * kKT);
+      const uint16_t* Bs = diag ? As : As + kBKT * kBP;
+      bf16x8 fa[2][4], fb[2][4];
+      fragments(As, wi, 0, fa[0]);
+      fragments(Bs, wj, 0, fb[0]);
+      // the next tile goes to the other stage, the one after that is requested;
+      // past the end of the chunk both are harmless (clamped loads, zeroed rows)
+      stash(k0 + kBKT, hs + (cur ^ 1) * kBStage);
+      fetch();
 #pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
-        bf16x8 fa[4], fb[4];
-        fragments(As, wi, ks, fa);
-        fragments(Bs, wj, ks, fb);
+      for (int ks = 0; ks < kBKT / 16; ++ks) {
+        if (ks + 1 < kBKT / 16) {
+          fragments(As, wi, ks + 1, fa[(ks + 1) & 1]);
+          fragments(Bs, wj, ks + 1, fb[(ks + 1) & 1]);
+        }
+        mfma16(fa[ks & 1], fb[ks & 1]);
+        // interleave: LDS reads of the next fragments first, then their permutes,
+        // each group behind one MFMA so that the matrix pipe never waits for them
 #pragma unroll
-        for (int a = 0; a < 4; ++a)
+        for (int g = 0; g < 8; ++g) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
+          __builtin_amdgcn_sched_group_barrier(0x200, 2, 0);  // DS write (tile t+1)
+          __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);  // VMEM read (tile t+2)
+        }
 #pragma unroll
-          for (int b = 0; b < 4; ++b)
-            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+        for (int g = 0; g < 8; ++g) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+          __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);  // VALU (permutes)
+        }
       }
       __syncthreads();
       cur ^= 1;
     }
   }
 
-  float* out = partial + ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * (kBT * kBT);
 #pragma unroll
   for (int a = 0; a < 4; ++a)
 #pragma unroll
@@ -263,16 +287,62 @@ __device__ __forceinline__ void big_tile(const uint16_t* __restrict__ X, int64_t
       }
 }
 
+// Work order.  Workgroups are handed to the eight XCDs (each with its own L2)
+// round-robin by workgroup id, so workgroup id = 8 * k + x is the k-th one of
+// XCD x.  All (split, tile) items are laid out in one locality order -- split by
+// split, and inside a split by super-tiles of 8 x 8 tiles -- and every XCD takes
+// a contiguous eighth of that sequence: the 32 workgroups an XCD runs at a time
+// then work on the same tokens of at most 16 channel strips, which its L2 serves.
+constexpr int kSuper = 8;
+
+__device__ __forceinline__ void tile_in_locality_order(int r, int ntb, int& I, int& J) {
+  const int ns = (ntb + kSuper - 1) / kSuper;
+  for (int a = 0; a < ns; ++a) {
+    const int ha = min(kSuper, ntb - a * kSuper);
+    for (int b = a; b < ns; ++b) {
+      const int hb = min(kSuper, ntb - b * kSuper);
+      const int cnt = (a == b) ? ha * (ha + 1) / 2 : ha * hb;
+      if (r < cnt) {
+        int i, j;
+        if (a == b) {
+          i = 0;
+          while (r >= ha - i) {
+            r -= ha - i;
+            ++i;
+          }
+          j = i + r;
+        } else {
+          i = r / hb;
+          j = r - i * hb;
+        }
+        I = a * kSuper + i;
+        J = b * kSuper + j;
+        return;
+      }
+      r -= cnt;
+    }
+  }
+  I = J = 0;  // not reached
+}
+
 __global__ __launch_bounds__(256) void hessian_bf16_big_kernel(const uint16_t* __restrict__ X, int64_t ldx,
                                                                int64_t t, int n, int64_t tok0, int chunk,
-                                                               int ntb, float* __restrict__ partial) {
+                                                               int ntb, int ntiles, int nsplits,
+                                                               float* __restrict__ partial) {
   extern __shared__ __attribute__((aligned(16))) uint16_t hs[];
+  const int total = ntiles * nsplits;
+  const int per_xcd = (total + 7) / 8;
+  const int q = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (q >= total || (blockIdx.x >> 3) >= per_xcd) return;
+  const int split = q / ntiles;
   int I, J;
-  tile_from_linear(blockIdx.x, ntb, I, J);
+  tile_in_locality_order(q - split * ntiles, ntb, I, J);
+  const int lin = I * ntb - I * (I - 1) / 2 + (J - I);  // index in the row-major upper-triangular tile list
+  float* out = partial + ((int64_t)split * ntiles + lin) * (kBT * kBT);
   if (I == J)
-    big_tile<true>(X, ldx, t, n, tok0, chunk, I, J, partial, hs);
+    big_tile<true>(X, ldx, t, n, tok0, chunk, I, J, split, out, hs);
   else
-    big_tile<false>(X, ldx, t, n, tok0, chunk, I, J, partial, hs);
+    big_tile<false>(X, ldx, t, n, tok0, chunk, I, J, split, out, hs);
 }
 
 // float32 activations: float64 FMAs, 64 x 64 tile, 4 x 4 outputs per thread.
@@ -408,8 +478,10 @@ ptq_status hessian_launch(double* H, int64_t ldh, const void* X, ptq_dtype xdt, 
           return PTQ_ERR_HIP;
         opted_in = true;
       }
-      hessian_bf16_big_kernel<<<g, 256, kBigLdsBytes, st>>>(static_cast<const uint16_t*>(X), ldx, t, (int)n,
-                                                            tok0, p.chunk, p.ntb, static_cast<float*>(ws));
+      const unsigned nwg = 8u * (unsigned)ceil_div((int64_t)p.ntiles * ns, 8);
+      hessian_bf16_big_kernel<<<nwg, 256, kBigLdsBytes, st>>>(static_cast<const uint16_t*>(X), ldx, t, (int)n,
+                                                              tok0, p.chunk, p.ntb, p.ntiles, ns,
+                                                              static_cast<float*>(ws));
       hessian_reduce_kernel<float, kBT><<<gr, 256, 0, st>>>(static_cast<const float*>(ws), ns, p.ntiles,
                                                             p.ntb, (int)n, H, ldh);
     } else if (xdt == PTQ_BF16) {
