@@ -24,6 +24,15 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_F64_TFLOPS = 78.6      # MI355X float64 (vector and matrix)
 HBM_GBPS = 8000.0
 
+# HBM bytes per launch of the dominant kernel (Hessian main kernel), from two rocprofv3 --pmc
+# runs of this file (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter reads
+# for a plain 1 GiB device copy (--copy-calibration): FETCH_SIZE reads 524288 per GiB read
+# (factor 2 KiB per count), WRITE_SIZE 1048576 per GiB written (1 KiB per count).
+# See profiles/hessian_C2_hbm_traffic.txt.  None for workloads that were not profiled.
+MEASURED_TRAFFIC_BYTES = {
+    "C2:attn_proj": 5.786e6 * 2048 + 4.8e5 * 1024,
+}
+
 
 def cpu_baseline(cfg, spec, seed):
     """The oracle, as it stands, on a bounded sample of the same layer; scaled to columns/s."""
@@ -172,9 +181,11 @@ def main():
         "quantize_tflops_f64": float(m) * n * n / (q_ms * 1e-3) / 1e12,
         "rel_layer_error": rel,
         "roofline": {
-            "kernel": "ptq_hessian_accumulate (hessian_bf16_kernel + partial-tile reduction)",
+            "kernel": "ptq_hessian_accumulate (Hessian MFMA kernel + partial-tile reduction)",
             "bound": "mfma", "achieved": h_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-            "frac": h_tflops / PEAK_BF16_TFLOPS, "traffic": None,
+            "frac": h_tflops / PEAK_BF16_TFLOPS,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(f"{args.config}:{spec.name}"),
+            "algorithmic_flops_per_launch": syrk_flops, "algorithmic_bytes_per_launch": 2.0 * t * n,
         },
     }
     if not args.no_cpu_baseline:
