@@ -99,12 +99,23 @@ __global__ __launch_bounds__(256) void leaf_kernel(const double* __restrict__ G,
   const int nb = (s + 15) >> 4, sp = nb << 4;
   const int l16 = lane & 15, lq = lane >> 4;
 
-  for (int e = tid; e < sp * sp; e += 256) {
-    const int i = e / sp, j = e - i * sp;
-    double v = 0.0;
-    if (i < s && j <= i) v = G[(int64_t)(o + i) * n + o + j];
-    if (i >= s && i == j) v = 1.0;   // padding: identity
-    S[i * kLeafP + j] = v;
+  // load the lower triangle, sixteen independent loads per thread in flight
+  for (int base = 0; base < sp * sp; base += 256 * 16) {
+    double v[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const int e = base + tid + 256 * u;
+      const int i = e / sp, j = e - i * sp;
+      const bool ld = (e < sp * sp) & (i < s) & (j <= i);
+      v[u] = G[ld ? (int64_t)(o + i) * n + o + j : (int64_t)o * n + o];
+    }
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const int e = base + tid + 256 * u;
+      const int i = e / sp, j = e - i * sp;
+      const bool ld = (i < s) & (j <= i);
+      if (e < sp * sp) S[i * kLeafP + j] = ld ? v[u] : ((i >= s && i == j) ? 1.0 : 0.0);  // padding: identity
+    }
   }
   __syncthreads();
 
@@ -123,9 +134,17 @@ __global__ __launch_bounds__(256) void leaf_kernel(const double* __restrict__ G,
           if (bad < 0) bad = j;
           p = 1.0;
         }
-        const double r = sqrt(p);
-        id[j] = 1.0 / r;
-        a[j] = (l16 == j) ? r : a[j] * id[j];
+        // 1/sqrt(p) by two Newton steps on the hardware estimate, then one
+        // correction each for sqrt(p) and its reciprocal (no division, no sqrt call)
+        const double h = 0.5 * p;
+        double r = __builtin_amdgcn_rsq(p);
+        r = r * fma(-h * r, r, 1.5);
+        r = r * fma(-h * r, r, 1.5);
+        double sq = p * r;
+        sq = fma(fma(-sq, sq, p), 0.5 * r, sq);
+        r = fma(fma(-sq, r, 1.0), r, r);
+        id[j] = r;
+        a[j] = (l16 == j) ? sq : a[j] * r;
 #pragma unroll
         for (int k = j + 1; k < 16; ++k) a[k] = fma(-a[j], lane_bcast(a[j], k), a[k]);
       }
@@ -191,7 +210,21 @@ __global__ __launch_bounds__(256) void leaf_kernel(const double* __restrict__ G,
 
   // ---- inverse, one wave per block column jb:
   //   X_ij = -X_ii * sum_{k=jb}^{ib-1} L_ik X_kj ;  X_kj (k > jb) is kept in sub-block (jb, k)
-  for (int jb = wave; jb < nb; jb += 4) {
+  // block column jb costs about (nb - jb)^2 / 2 sub-block products: deal the columns to
+  // the waves longest first, each to the least loaded wave
+  int mine = 0;
+  {
+    int load[4] = {0, 0, 0, 0};
+    for (int jb = 0; jb < nb; ++jb) {
+      int w = 0;
+      for (int c = 1; c < 4; ++c)
+        if (load[c] < load[w]) w = c;
+      load[w] += (nb - jb) * (nb - jb + 1);
+      if (w == wave) mine |= 1 << jb;
+    }
+  }
+  for (int jb = 0; jb < nb; ++jb) {
+    if (!((mine >> jb) & 1)) continue;
     for (int ib = jb + 1; ib < nb; ++ib) {
       f64x4 t = {0.0, 0.0, 0.0, 0.0};
       for (int k = jb; k < ib; ++k) {
