@@ -139,29 +139,70 @@ __global__ __launch_bounds__(256) void hessian_bf16_kernel(const uint16_t* __res
 }
 
 // ---- large layers: 256 x 256 tile, each wave 128 x 128 (4 x 4 MFMA tiles) ------
-// Same transposition trick with 8-byte LDS reads: a lane gets channels 4p..4p+3
-// for eight tokens, four byte-permutes per token pair give the fragments of the
-// channel classes c % 4 = 0..3, one class per MFMA tile.  A wave then issues 16
-// MFMAs (512 matrix-pipe cycles) per 16 LDS reads, so LDS sits at about half of
-// its bandwidth; accumulators fill the 256 AGPRs.  LDS is double-buffered with
-// one barrier per 64 tokens; the global loads of tile t+2, the LDS stores of
-// tile t+1 and the fragments of the next 16 tokens are issued between the MFMAs
-// of the current 16 tokens.
+// The tile's operands go from global memory straight into LDS (buffer_load ... lds,
+// 16 bytes per lane, no staging registers) as they lie in memory, [token][channel], into
+// a ring of four 32-token stages.  The transposition to "eight consecutive tokens of one
+// channel per lane" is done by the LDS itself: ds_read_b64_tr_b16 hands a lane four tokens
+// of its channel, two such reads make one MFMA operand.  Per 16 tokens a wave issues 16
+// of these reads and 16 MFMAs (32 cycles each), accumulators fill the 256 AGPRs.
+//
+// LDS layout of a stage: A part (32 token rows x 512 bytes) then B part.  A row holds 32
+// chunks of 16 bytes (8 channels); chunk c of token row r sits at position c ^ swz(r & 3),
+// which spreads the 16 chunks a half-wave reads (four token rows x 64 bytes) over all
+// banks.  A DMA instruction writes 64 consecutive chunks (two token rows) in lane order, so
+// the swizzle is applied on the global side: lane j of the instruction fetches the chunk
+// that belongs at position j & 31.
+//
+// Tokens past the end of the chunk are never fetched: the buffer descriptor ends with the
+// chunk and out-of-range lanes deliver zeros.  Channels past n (last tile row / column
+// only) fetch some valid channel instead; the outputs they feed lie outside the matrix and
+// are dropped by the reduction.
+//
+// The DMA requests are issued by inline assembly and tracked with explicit vmcnt waits:
+// the compiler would otherwise wait for every outstanding request before each LDS read.
 constexpr int kBT = 256;
-constexpr int kBP = kBT + 8;                       // 528-byte rows
-constexpr int kBKT = 64;                           // tokens per LDS stage
-constexpr int kBStage = 2 * kBKT * kBP;            // A and B, bf16 elements
-constexpr size_t kBigLdsBytes = 2 * kBStage * sizeof(uint16_t);
+constexpr int kBKS = 32;                          // tokens per stage
+constexpr int kBRing = 4;                         // stages in LDS
+constexpr int kBRow = kBT * 2;                    // bytes per token row of a part
+constexpr int kBPart = kBKS * kBRow;              // 16 KB
+constexpr int kBStage = 2 * kBPart;               // 32 KB
+constexpr size_t kBigLdsBytes = (size_t)kBRing * kBStage;  // 128 KB
+
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short i16x4;
+typedef __attribute__((__vector_size__(4 * sizeof(int)))) int i32x4;
+
+__device__ __forceinline__ int swz(int row) { return ((row & 1) * 10) | ((row & 2) * 2); }
+
+// One request: 64 lanes x 16 bytes from (descriptor base + voff) to LDS address ldsaddr + 16 * lane.
+// (m0 is not otherwise used in this kernel: no indirect register indexing, no other LDS DMA.)
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ __forceinline__ void dma16(i32x4 rsrc, uint32_t voff, uint32_t ldsaddr) {
+  asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(ldsaddr), "v"(voff), "s"(rsrc)
+               : "memory", "m0");
+}
+#pragma clang diagnostic pop
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  // s_waitcnt vmcnt(N); the other counters at their maximum (no wait)
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0f70);
+}
 
 template <bool diag>
 __device__ __forceinline__ void big_tile(const uint16_t* __restrict__ X, int64_t ldx, int64_t t, int n,
                                          int64_t tok0, int chunk, int I, int J, int split,
                                          float* __restrict__ out, uint16_t* hs) {
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  typedef __attribute__((address_space(3))) char lds_char;
+  typedef __attribute__((address_space(3))) i16x4 lds_i16x4;
+  lds_char* lds = (lds_char*)hs;
+  const uint32_t lbase = (uint32_t)(uintptr_t)lds;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wi = wave >> 1, wj = wave & 1;
   const int64_t kbeg = tok0 + (int64_t)split * chunk;
   const int64_t kend = (kbeg + chunk < t) ? kbeg + chunk : t;
-  typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
+  const int64_t len = kend - kbeg;
 
   f32x16 acc[4][4];
 #pragma unroll
@@ -171,108 +212,125 @@ __device__ __forceinline__ void big_tile(const uint16_t* __restrict__ X, int64_t
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-  if (kbeg < kend) {
-    // global -> LDS map: 32 threads cover one token row (8 channels = 16 bytes each),
-    // eight rows per pass.  Rows past the end of the chunk re-read its last token
-    // (pointer clamp, no branch) and are zeroed on the way into LDS.
-    constexpr int kPass = kBKT / 8;
-    const int lrow = tid >> 5, lcol = (tid & 31) * 8;
-    const bool a_in = (I * kBT + lcol) < n, b_in = (J * kBT + lcol) < n;
-    const uint16_t* ga = X + (kbeg + lrow) * ldx + (a_in ? I * kBT + lcol : 0);
-    const uint16_t* gb = X + (kbeg + lrow) * ldx + (b_in ? J * kBT + lcol : 0);
-    const uint16_t* la = X + (kend - 1) * ldx + (a_in ? I * kBT + lcol : 0);
-    const uint16_t* lb = X + (kend - 1) * ldx + (b_in ? J * kBT + lcol : 0);
-    const int64_t rstep = 8 * ldx;
-    u32x4 ra[kPass], rb[kPass];
-    auto fetch = [&]() {
-#pragma unroll
-      for (int p = 0; p < kPass; ++p) {
-        const uint16_t* pa = ga + p * rstep;
-        ra[p] = *reinterpret_cast<const u32x4*>(pa < la ? pa : la);
-        if (!diag) {
-          const uint16_t* pb = gb + p * rstep;
-          rb[p] = *reinterpret_cast<const u32x4*>(pb < lb ? pb : lb);
-        }
-      }
-      ga += kBKT * ldx;
-      gb += kBKT * ldx;
-    };
-    auto stash = [&](int64_t k0, uint16_t* st) {
-#pragma unroll
-      for (int p = 0; p < kPass; ++p) {
-        const bool kin = k0 + lrow + 8 * p < kend;
-        const uint32_t ma = (kin && a_in) ? 0xffffffffu : 0u, mb = (kin && b_in) ? 0xffffffffu : 0u;
-        *reinterpret_cast<u32x4*>(&st[(lrow + 8 * p) * kBP + lcol]) = ra[p] & ma;
-        if (!diag) *reinterpret_cast<u32x4*>(&st[kBKT * kBP + (lrow + 8 * p) * kBP + lcol]) = rb[p] & mb;
-      }
-    };
-    // fragments of the channel classes c % 4 of a 128-channel strip, tokens ks*16 + kg*8 .. +7
-    auto fragments = [&](const uint16_t* T, int strip, int ks, bf16x8 (&f)[4]) {
-      const int p = lane & 31, kg = lane >> 5;
-      const uint16_t* src = T + (ks * 16 + kg * 8) * kBP + strip * 128 + 4 * p;
-      uint2 d[8];
-#pragma unroll
-      for (int i = 0; i < 8; ++i) d[i] = *reinterpret_cast<const uint2*>(src + i * kBP);
-      u32x4 v[4];
+  if (len > 0) {
+    const int nstage = (int)((len + kBKS - 1) / kBKS);
+    constexpr int L = diag ? 4 : 8;  // DMA instructions per stage and wave
+
+    // descriptor over the chunk's tokens (uniform, kept in scalar registers)
+    const uint64_t gb0 = (uint64_t)(X + kbeg * ldx);
+    const i32x4 rs = {(int)__builtin_amdgcn_readfirstlane((uint32_t)gb0),
+                      (int)__builtin_amdgcn_readfirstlane((uint32_t)(gb0 >> 32)),
+                      (int)__builtin_amdgcn_readfirstlane((uint32_t)(len * ldx * 2)),  // bytes, < 2^32 (host)
+                      0x00020000};
+    const uint32_t stage_step = (uint32_t)(kBKS * ldx * 2);
+
+    // per-lane byte offsets of the four DMA instructions of a part; they advance by a stage
+    uint32_t voA[4], voB[4];
+    {
+      const int pos = lane & 31;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        v[0][i] = __builtin_amdgcn_perm(d[2 * i + 1].x, d[2 * i].x, 0x05040100u);
-        v[1][i] = __builtin_amdgcn_perm(d[2 * i + 1].x, d[2 * i].x, 0x07060302u);
-        v[2][i] = __builtin_amdgcn_perm(d[2 * i + 1].y, d[2 * i].y, 0x05040100u);
-        v[3][i] = __builtin_amdgcn_perm(d[2 * i + 1].y, d[2 * i].y, 0x07060302u);
+        const int row = 8 * i + 2 * wave + (lane >> 5);
+        const int c = pos ^ swz(row);
+        int colA = I * kBT + 8 * c, colB = J * kBT + 8 * c;
+        if (colA >= n) colA = I * kBT;
+        if (colB >= n) colB = J * kBT;
+        voA[i] = (uint32_t)((row * ldx + colA) * 2);
+        voB[i] = (uint32_t)((row * ldx + colB) * 2);
       }
+    }
+    // per-lane LDS read addresses inside a stage, one per MFMA tile of the wave's strips
+    uint32_t adA[4], adB[4];
+    {
+      const int g = lane >> 4, h = g & 1, kg = g >> 1, j = lane & 15, r = j >> 2, q = j & 3;
+      const int row = kg * 8 + r;
 #pragma unroll
-      for (int q = 0; q < 4; ++q) f[q] = __builtin_bit_cast(bf16x8, v[q]);
+      for (int T = 0; T < 4; ++T) {
+        const int cA = wi * 16 + T * 4 + 2 * h + (q >> 1);
+        const int cB = wj * 16 + T * 4 + 2 * h + (q >> 1);
+        adA[T] = row * kBRow + ((cA ^ swz(r)) * 16) + (q & 1) * 8;
+        adB[T] = (diag ? 0 : kBPart) + row * kBRow + ((cB ^ swz(r)) * 16) + (q & 1) * 8;
+      }
+    }
+    // fragment of eight tokens: rows +0..3 and +4..7 relative to the lane's row
+    auto read_one = [&](uint32_t addr) -> bf16x8 {
+      const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(lds + addr));
+      const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(lds + addr + 4 * kBRow));
+      return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
     };
-    auto mfma16 = [&](const bf16x8 (&fa)[4], const bf16x8 (&fb)[4]) {
+    // DMA instruction q of a stage (A rows first, then B rows) into the slot at dst
+    auto dma_q = [&](int q, uint32_t dst) {
+      if (q < 4) dma16(rs, voA[q], dst + q * 4096);
+      else dma16(rs, voB[q - 4], dst + kBPart + (q - 4) * 4096);
+    };
+    auto dma_advance = [&]() {
 #pragma unroll
-      for (int a = 0; a < 4; ++a)
+      for (int i = 0; i < 4; ++i) {
+        voA[i] += stage_step;
+        voB[i] += stage_step;
+      }
+    };
+    // 16 MFMAs on (fa, fb) while the next fragments (na, nb) are read at `so`.  L/2 DMA
+    // instructions, q0 onwards, go between the four groups of four MFMAs: issued in one
+    // burst they fill the memory pipeline's queue and the wave (hence its MFMAs) stalls.
+    auto half = [&](const bf16x8 (&fa)[4], const bf16x8 (&fb)[4], bf16x8 (&na)[4], bf16x8 (&nb)[4], uint32_t so,
+                    int q0, uint32_t dst) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        na[g] = read_one(so + adA[g]);
+        nb[g] = read_one(so + adB[g]);
 #pragma unroll
         for (int b = 0; b < 4; ++b)
-          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+          acc[g][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[g], fb[b], acc[g][b], 0, 0, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);  // DS read
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (L == 8) dma_q(q0 + g, dst);
+        else if (g & 1) dma_q(q0 + (g >> 1), dst);
+        __builtin_amdgcn_sched_barrier(0);
+      }
     };
 
-    // stage s holds tile s; registers hold tile s+1 until it is stored
-    fetch();
-    stash(kbeg, hs);
-    fetch();
-    __syncthreads();
-    int cur = 0;
-    for (int64_t k0 = kbeg; k0 < kend; k0 += kBKT) {
-      const uint16_t* As = hs + cur * kBStage;
-      const uint16_t* Bs = diag ? As : As + kBKT * kBP;
-      bf16x8 fa[2][4], fb[2][4];
-      fragments(As, wi, 0, fa[0]);
-      fragments(Bs, wj, 0, fb[0]);
-      // the next tile goes to the other stage, the one after that is requested;
-      // past the end of the chunk both are harmless (clamped loads, zeroed rows)
-      stash(k0 + kBKT, hs + (cur ^ 1) * kBStage);
-      fetch();
+    // prologue: stages 0, 1, 2 and the first half of stage 3 are requested; stage 0 must have
+    // landed.  Stages past the end of the chunk are requested like the others and deliver zeros.
 #pragma unroll
-      for (int ks = 0; ks < kBKT / 16; ++ks) {
-        if (ks + 1 < kBKT / 16) {
-          fragments(As, wi, ks + 1, fa[(ks + 1) & 1]);
-          fragments(Bs, wj, ks + 1, fb[(ks + 1) & 1]);
-        }
-        mfma16(fa[ks & 1], fb[ks & 1]);
-        // interleave: LDS reads of the next fragments first, then their permutes,
-        // each group behind one MFMA so that the matrix pipe never waits for them
+    for (int s = 0; s < kBRing - 1; ++s) {
 #pragma unroll
-        for (int g = 0; g < 8; ++g) {
-          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
-          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
-          __builtin_amdgcn_sched_group_barrier(0x200, 2, 0);  // DS write (tile t+1)
-          __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);  // VMEM read (tile t+2)
-        }
-#pragma unroll
-        for (int g = 0; g < 8; ++g) {
-          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
-          __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);  // VALU (permutes)
-        }
-      }
-      __syncthreads();
-      cur ^= 1;
+      for (int q = 0; q < L; ++q) dma_q(q, lbase + s * kBStage + wave * 1024);
+      dma_advance();
     }
+#pragma unroll
+    for (int q = 0; q < L / 2; ++q) dma_q(q, lbase + (kBRing - 1) * kBStage + wave * 1024);
+    wait_vmcnt<2 * L + L / 2>();
+    __builtin_amdgcn_s_barrier();
+    bf16x8 fa0[4], fb0[4], fa1[4], fb1[4];
+#pragma unroll
+    for (int T = 0; T < 4; ++T) {
+      fa0[T] = read_one(adA[T]);
+      fb0[T] = read_one(adB[T]);
+    }
+
+    // Iteration s: tokens 0..15 of stage s | barrier | tokens 16..31.  At the barrier every wave
+    // has finished reading stage s, so its slot is refilled with stage s + 4: the first half of
+    // those DMA instructions is spread over the second half of iteration s, the rest over the
+    // first half of iteration s + 1.  In issue order the requests outstanding at the barrier are
+    // those of stages s+1, s+2, s+3, and stage s+1 is the one that must have landed.
+    for (int s = 0; s < nstage; ++s) {
+      const uint32_t slot_off = (s & (kBRing - 1)) * kBStage;
+      const uint32_t pend_off = ((s + kBRing - 1) & (kBRing - 1)) * kBStage;
+      const uint32_t next_off = ((s + 1) & (kBRing - 1)) * kBStage;
+      half(fa0, fb0, fa1, fb1, slot_off + 16 * kBRow, L / 2, lbase + pend_off + wave * 1024);
+      dma_advance();
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      wait_vmcnt<2 * L>();
+      __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_sched_barrier(0);
+      half(fa1, fb1, fa0, fb0, next_off, 0, lbase + slot_off + wave * 1024);
+    }
+    wait_vmcnt<0>();  // nothing may still be landing in LDS when the workgroup ends
   }
 
 #pragma unroll
@@ -283,16 +341,16 @@ __device__ __forceinline__ void big_tile(const uint16_t* __restrict__ X, int64_t
       for (int r = 0; r < 16; ++r) {
         const int il = (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
         const int jl = lane & 31;
-        out[(wi * 128 + 4 * il + a) * kBT + wj * 128 + 4 * jl + b] = acc[a][b][r];
+        out[(wi * 128 + 32 * a + il) * kBT + wj * 128 + 32 * b + jl] = acc[a][b][r];
       }
 }
 
-// Work order.  Workgroups are handed to the eight XCDs (each with its own L2)
-// round-robin by workgroup id, so workgroup id = 8 * k + x is the k-th one of
-// XCD x.  All (split, tile) items are laid out in one locality order -- split by
-// split, and inside a split by super-tiles of 8 x 8 tiles -- and every XCD takes
-// a contiguous eighth of that sequence: the 32 workgroups an XCD runs at a time
-// then work on the same tokens of at most 16 channel strips, which its L2 serves.
+// Work order.  Workgroups are handed to the eight XCDs (each with its own L2) round-robin by
+// workgroup id.  All (split, tile) items are laid out in one locality order -- split by split,
+// and inside a split by super-tiles of 8 x 8 tiles.  The 256 workgroups in flight take 256
+// consecutive items, and of those XCD x (ids = x mod 8) takes 32 consecutive ones: its L2 then
+// serves a few channel strips over the same tokens, and the memory-side cache serves what the
+// XCDs share (the same one or two splits, at most two slabs of tokens x n).
 constexpr int kSuper = 8;
 
 __device__ __forceinline__ void tile_in_locality_order(int r, int ntb, int& I, int& J) {
@@ -331,9 +389,8 @@ __global__ __launch_bounds__(256) void hessian_bf16_big_kernel(const uint16_t* _
                                                                float* __restrict__ partial) {
   extern __shared__ __attribute__((aligned(16))) uint16_t hs[];
   const int total = ntiles * nsplits;
-  const int per_xcd = (total + 7) / 8;
-  const int q = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-  if (q >= total || (blockIdx.x >> 3) >= per_xcd) return;
+  const int q = 256 * (blockIdx.x >> 8) + 32 * (blockIdx.x & 7) + ((blockIdx.x & 255) >> 3);
+  if (q >= total) return;
   const int split = q / ntiles;
   int I, J;
   tile_in_locality_order(q - split * ntiles, ntb, I, J);
@@ -415,9 +472,15 @@ struct Plan {
 constexpr int64_t kBigFrom = 2048;                   // layers at least this wide use the 256-tile kernel
 constexpr size_t kMaxPartialBytes = (size_t)1 << 30;  // partial tiles in flight per launch
 
-Plan make_plan(int64_t n, int64_t t, ptq_dtype dt) {
+// The 256-tile kernel addresses a chunk of tokens (and the ring's read-ahead past it) with
+// 32-bit byte offsets, which bounds the row pitch.
+bool big_kernel_fits(int64_t ldx) {
+  return (kMaxChunkBig + (kBRing + 1) * kBKS) * ldx * 2 < ((int64_t)1 << 32);
+}
+
+Plan make_plan(int64_t n, int64_t t, ptq_dtype dt, bool allow_big) {
   Plan p;
-  const bool big = (dt == PTQ_BF16) && n >= kBigFrom;
+  const bool big = allow_big && (dt == PTQ_BF16) && n >= kBigFrom;
   p.tile = (dt == PTQ_BF16) ? (big ? kBT : kTile) : kTile32;
   const int kt = (dt == PTQ_BF16) ? kKT : kKT32;
   p.ntb = (int)ceil_div(n, p.tile);
@@ -453,17 +516,20 @@ Plan make_plan(int64_t n, int64_t t, ptq_dtype dt) {
 }  // namespace
 
 size_t hessian_workspace_bytes(int64_t n, int64_t t) {
-  // sized for either input type
-  const Plan a = make_plan(n, t, PTQ_BF16), b = make_plan(n, t, PTQ_F32);
-  const size_t sa = a.tile_bytes * a.ntiles * a.splits_launch;
-  const size_t sb = b.tile_bytes * b.ntiles * b.splits_launch;
-  return align_up(sa > sb ? sa : sb, 256);
+  // sized for either input type and either bf16 kernel
+  size_t need = 0;
+  for (int v = 0; v < 3; ++v) {
+    const Plan p = make_plan(n, t, v == 2 ? PTQ_F32 : PTQ_BF16, v == 0);
+    const size_t b = p.tile_bytes * p.ntiles * p.splits_launch;
+    if (b > need) need = b;
+  }
+  return align_up(need, 256);
 }
 
 ptq_status hessian_launch(double* H, int64_t ldh, const void* X, ptq_dtype xdt, int64_t t, int64_t n,
                           int64_t ldx, void* ws, size_t ws_bytes, hipStream_t st) {
   if (t == 0 || n == 0) return PTQ_OK;
-  const Plan p = make_plan(n, t, xdt);
+  const Plan p = make_plan(n, t, xdt, big_kernel_fits(ldx));
   if (ws_bytes < p.tile_bytes * p.ntiles * p.splits_launch) return PTQ_ERR_WORKSPACE;
   for (int s0 = 0; s0 < p.splits_total; s0 += p.splits_launch) {
     const int ns = (p.splits_total - s0 < p.splits_launch) ? p.splits_total - s0 : p.splits_launch;
@@ -478,7 +544,7 @@ ptq_status hessian_launch(double* H, int64_t ldh, const void* X, ptq_dtype xdt, 
           return PTQ_ERR_HIP;
         opted_in = true;
       }
-      const unsigned nwg = 8u * (unsigned)ceil_div((int64_t)p.ntiles * ns, 8);
+      const unsigned nwg = 256u * (unsigned)ceil_div((int64_t)p.ntiles * ns, 256);
       hessian_bf16_big_kernel<<<nwg, 256, kBigLdsBytes, st>>>(static_cast<const uint16_t*>(X), ldx, t, (int)n,
                                                               tok0, p.chunk, p.ntb, p.ntiles, ns,
                                                               static_cast<float*>(ws));

@@ -70,6 +70,7 @@ def _correlated_x(rng, t, n, corr=0.8):
 @pytest.mark.parametrize("dtype,t,n", [
     ("bf16", 1000, 384), ("bf16", 4096 + 17, 200), ("bf16", 300, 8), ("bf16", 9000, 136),
     ("bf16", 3000, 2304), ("bf16", 20000 + 5, 2056),      # wide layers: the 256 x 256-tile kernel
+    ("bf16", 50, 2048), ("bf16", 1, 2048), ("bf16", 129, 2560),   # ... with fewer tokens than its LDS ring holds
     ("f32", 2048, 512), ("f32", 333, 70), ("f32", 5, 1),
 ])
 def test_hessian_matches_oracle(dtype, t, n):
@@ -106,6 +107,25 @@ def test_hessian_accumulates_over_calls_and_is_reproducible():
     # empty chunk is a no-op
     ptq.ptq_hessian_accumulate(H, Xw[:0])
     assert np.array_equal(np.triu(H.cpu().numpy()), np.triu(a))
+
+
+def test_hessian_wide_layer_strided_and_chunked():
+    # the 256 x 256-tile kernel on a view with a leading dimension larger than n, fed in two calls
+    t, n, ld = 2100, 2048, 2048 + 72
+    spec = wl.LayerSpec("h", 16, n, t, dtype="bf16", x_sigma=1.5, layer_id=902)
+    Xs = wl.gen_activations(spec)
+    wide = np.zeros((t, ld), dtype=np.uint16)
+    wide[:, 8:8 + n] = Xs
+    Xw = to_device(wide)[:, 8:8 + n]
+    H = torch.zeros((n, n), dtype=torch.float64, device="cuda")
+    ptq.ptq_hessian_accumulate(H, Xw[:1037])
+    ptq.ptq_hessian_accumulate(H, Xw[1037:])
+    Href = orc.hessian(wl.to_f64(Xs))
+    fro, ent = hessian_errors(H.cpu().numpy(), Href)
+    assert fro <= 1e-5 and ent <= 1e-5, (fro, ent)
+    a = _gpu_hessian(Xs).cpu().numpy()
+    b = _gpu_hessian(Xs).cpu().numpy()
+    assert np.array_equal(np.triu(a), np.triu(b))
 
 
 # ------------------------------------------------------------------ factor
