@@ -76,6 +76,9 @@ def main():
     ap.add_argument("--config", default="C2")
     ap.add_argument("--layer", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--device-x", action="store_true",
+                    help="draw the activations on the GPU (same distribution family, torch generator) instead of "
+                         "the seeded host generator: for timing the widest layers, whose host generation takes minutes")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run plain 1 GiB device copies and exit (reference reading for the "
                          "FETCH_SIZE / WRITE_SIZE counters under rocprofv3 --pmc)")
@@ -115,8 +118,22 @@ def main():
     W = to_device(wl.gen_weight(spec, cfg.seed))
     X = torch.empty((t, n), dtype=torch.bfloat16 if spec.dtype == "bf16" else torch.float32, device="cuda")
     step_t = 32768
-    for lo in range(0, t, step_t):          # generate on the host in slabs, upload
-        X[lo:lo + step_t] = to_device(wl.gen_activations(spec, cfg.seed, lo, min(t, lo + step_t)))
+    if args.device_x:
+        gen = torch.Generator(device="cuda").manual_seed(cfg.seed)
+        if spec.x_kind == "student_t":
+            ch_scale = torch.ones(n, device="cuda")
+        else:
+            ch_scale = torch.exp(spec.x_sigma * torch.randn(n, device="cuda", generator=gen))
+        for lo in range(0, t, step_t):
+            z = torch.randn((min(t, lo + step_t) - lo, n), device="cuda", generator=gen)
+            if spec.x_kind == "student_t":
+                chi = sum(torch.randn_like(z).square_() for _ in range(3)) / 3.0
+                z = z / chi.sqrt_()
+            X[lo:lo + step_t] = (z * ch_scale).to(X.dtype)
+        del z
+    else:
+        for lo in range(0, t, step_t):          # generate on the host in slabs, upload
+            X[lo:lo + step_t] = to_device(wl.gen_activations(spec, cfg.seed, lo, min(t, lo + step_t)))
 
     dev = "cuda"
     H = torch.zeros((n, n), dtype=torch.float64, device=dev)
@@ -169,7 +186,7 @@ def main():
         "metric": "layer-solve columns quantized/sec + Hessian TFLOP/s (% MFMA peak), 1 GPU",
         "value": n / (ms * 1e-3), "unit": "columns/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16,f64" if spec.dtype == "bf16" else "f64", "data": "synthetic",
+        "vs_baseline": None, "dtype": "bf16,f64" if spec.dtype == "bf16" else "f64", "data": "synthetic (device-drawn activations)" if args.device_x else "synthetic",
         "config": {"workload": f"{args.config}:{spec.name} W {m}x{n} {spec.dtype}, X {t}x{n} {spec.dtype}, "
                                f"{cfg.bits}-bit asym group {cfg.group} block {cfg.block} damp {damp}"},
         "phases_ms": {"hessian": h_ms, "factor": f_ms, "quantize": q_ms, "layer_error": e_ms},

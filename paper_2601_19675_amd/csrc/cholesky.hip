@@ -10,9 +10,10 @@
 //     split s = s1 + s2
 //     X11           = rec(G11)
 //     L21           = G21 X11^T                       (GEMM, X11 triangular)
-//     G22          -= L21 L21^T                       (SYRK, lower tiles)
+//     G22          -= L21 L21^T                       (SYRK, lower tiles)  } one launch
+//     T             = L21 X11                                              }
 //     X22           = rec(G22)
-//     X21           = -X22 (L21 X11)                  (two GEMMs)
+//     X21           = -X22 T
 //
 // Every off-diagonal step is a float64 MFMA GEMM; only blocks of at most 128
 // columns are factored and inverted inside one workgroup (in LDS).  L itself
@@ -338,12 +339,11 @@ struct OpX21 {
 };
 
 template <int TM, int TN, class Op>
-__global__ __launch_bounds__(256) void node_gemm_kernel(Op op) {
+__device__ __forceinline__ void node_gemm_tile(const Op& op, int bx, int by, int gx, int gy, double* smem) {
   using T = DgemmTile<TM, TN>;
-  extern __shared__ double smem[];
   // tiles with the longest k range first (triangular operands make them uneven)
-  const int bi = Op::REV_I ? gridDim.y - 1 - blockIdx.y : blockIdx.y;
-  const int bj = Op::REV_J ? gridDim.x - 1 - blockIdx.x : blockIdx.x;
+  const int bi = Op::REV_I ? gy - 1 - by : by;
+  const int bj = Op::REV_J ? gx - 1 - bx : bx;
   const int i0 = bi * T::BM, j0 = bj * T::BN;
   const int i1 = min(i0 + T::BM, op.M()), j1 = min(j0 + T::BN, op.N());
   if (!op.active(i0, i1, j0, j1)) return;
@@ -354,6 +354,23 @@ __global__ __launch_bounds__(256) void node_gemm_kernel(Op op) {
   dgemm_mainloop<TM, TN, Op::A_KFAST, Op::B_KFAST>(acc, op.a(i0), DgemmIdentity{}, op.b(j0), DgemmIdentity{},
                                                    i1 - i0, j1 - j0, kb, ke, smem);
   dgemm_foreach(acc, [&](int i, int j, double v) { op.store(i0 + i, j0 + j, v); });
+}
+
+template <int TM, int TN, class Op>
+__global__ __launch_bounds__(256) void node_gemm_kernel(Op op) {
+  extern __shared__ double smem[];
+  node_gemm_tile<TM, TN>(op, blockIdx.x, blockIdx.y, gridDim.x, gridDim.y, smem);
+}
+
+// Two independent steps in one launch: workgroups [0, gx1*gy1) take the tiles of the first.
+template <int TM, int TN, class Op1, class Op2>
+__global__ __launch_bounds__(256) void node_gemm2_kernel(Op1 op1, Op2 op2, int gx1, int gy1, int gx2, int gy2) {
+  extern __shared__ double smem[];
+  const int b = blockIdx.x, n1 = gx1 * gy1;
+  if (b < n1)
+    node_gemm_tile<TM, TN>(op1, b % gx1, b / gx1, gx1, gy1, smem);
+  else
+    node_gemm_tile<TM, TN>(op2, (b - n1) % gx2, (b - n1) / gx2, gx2, gy2, smem);
 }
 
 template <int TM, int TN, class Op>
@@ -370,14 +387,47 @@ void launch_tiles(const Op& op, int M, int N, hipStream_t st) {
   node_gemm_kernel<TM, TN, Op><<<g, 256, lds, st>>>(op);
 }
 
+template <int TM, int TN, class Op1, class Op2>
+void launch_tiles2(const Op1& op1, int M1, int N1, const Op2& op2, int M2, int N2, hipStream_t st) {
+  using T = DgemmTile<TM, TN>;
+  static bool opted_in = false;
+  constexpr int lds = T::kSmemDoubles * (int)sizeof(double);
+  if (!opted_in) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(node_gemm2_kernel<TM, TN, Op1, Op2>),
+                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    opted_in = true;
+  }
+  const int gx1 = (int)ceil_div(N1, T::BN), gy1 = (int)ceil_div(M1, T::BM);
+  const int gx2 = (int)ceil_div(N2, T::BN), gy2 = (int)ceil_div(M2, T::BM);
+  node_gemm2_kernel<TM, TN, Op1, Op2><<<(unsigned)(gx1 * gy1 + gx2 * gy2), 256, lds, st>>>(op1, op2, gx1, gy1, gx2, gy2);
+}
+
+// Tile shape by problem size: 64 x 128 once there are enough tiles to fill the chip several
+// times over, 32 x 32 for the small nodes deep in the recursion (more workgroups, each with a
+// short k loop: those launches are bound by latency, not by the matrix pipe), else 64 x 64.
+inline int tile_class(int M, int N) {
+  if (ceil_div(M, 64) * ceil_div(N, 128) >= 1024) return 2;
+  if (ceil_div(M, 64) * ceil_div(N, 64) <= 64) return 0;
+  return 1;
+}
+
 template <class Op>
 void launch_node(const Op& op, int M, int N, hipStream_t st) {
-  // 64 x 128 tiles once there are enough of them to fill the chip, else 64 x 64
-  const int64_t big = ceil_div(M, 64) * ceil_div(N, 128);
-  if (big >= 1024)
-    launch_tiles<2, 4, Op>(op, M, N, st);
-  else
-    launch_tiles<2, 2, Op>(op, M, N, st);
+  switch (tile_class(M, N)) {
+    case 2: launch_tiles<2, 4, Op>(op, M, N, st); break;
+    case 1: launch_tiles<2, 2, Op>(op, M, N, st); break;
+    default: launch_tiles<1, 1, Op>(op, M, N, st); break;
+  }
+}
+
+template <class Op1, class Op2>
+void launch_node2(const Op1& op1, int M1, int N1, const Op2& op2, int M2, int N2, hipStream_t st) {
+  const int c1 = tile_class(M1, N1), c2 = tile_class(M2, N2);
+  switch (c1 < c2 ? c1 : c2) {
+    case 2: launch_tiles2<2, 4, Op1, Op2>(op1, M1, N1, op2, M2, N2, st); break;
+    case 1: launch_tiles2<2, 2, Op1, Op2>(op1, M1, N1, op2, M2, N2, st); break;
+    default: launch_tiles2<1, 1, Op1, Op2>(op1, M1, N1, op2, M2, N2, st); break;
+  }
 }
 
 void recurse(double* G, double* U, int ldu, int n, int o, int s, int32_t* info, hipStream_t st) {
@@ -391,9 +441,9 @@ void recurse(double* G, double* U, int ldu, int n, int o, int s, int32_t* info, 
   Node nd{G, U, ldu, n, o, s1, s2};
   recurse(G, U, ldu, n, o, s1, info, st);
   launch_node(OpPanel{nd}, s2, s1, st);
-  launch_node(OpSyrk{nd}, s2, s2, st);
+  // the trailing update and T = L21 X11 both need only L21 and touch different blocks
+  launch_node2(OpSyrk{nd}, s2, s2, OpT{nd}, s2, s1, st);
   recurse(G, U, ldu, n, o + s1, s2, info, st);
-  launch_node(OpT{nd}, s2, s1, st);
   launch_node(OpX21{nd}, s2, s1, st);
 }
 
