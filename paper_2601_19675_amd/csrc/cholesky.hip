@@ -75,12 +75,21 @@ __global__ __launch_bounds__(256) void build_work_kernel(const double* __restric
 }
 
 // ---- leaf: X = inverse of the Cholesky factor of G[o:o+s, o:o+s], s <= 128 ---
-// The block lives in LDS and is processed in 16 x 16 sub-blocks.  For each
-// diagonal sub-block one wave factors it and inverts the factor in registers
-// (lane = row, pivots and multipliers passed around with v_readlane, no
-// barriers); the sub-blocks below and the trailing sub-blocks are then updated
-// with 16x16x4 float64 MFMAs by all four waves.  The inverse is built the same
-// way, one wave per block column.  X is parked in the upper sub-blocks.
+// The block lives in LDS and is processed in 16 x 16 sub-blocks, right-looking.  Factoring a
+// diagonal sub-block and inverting its factor is a chain of dependent operations that one
+// wave does in registers (lane = row, pivots and multipliers passed around with v_readlane,
+// no barriers); everything else is 16x16x4 float64 MFMA work on sub-blocks.  The chain is the
+// critical path, so the steps are skewed: while wave 0 factors diagonal block d+1 (after
+// applying step d's update to it itself), the other waves apply the rest of step d's trailing
+// update and pre-compute row d+1 of the inverse.
+//
+//   P1(d)  all waves   L_id = G_id X_dd^T  (i > d);   X_dj = -X_dd T_dj  (j < d)
+//   P2(d)  wave 0      G_{d+1,d+1} -= L_{d+1,d} L_{d+1,d}^T ;  factor + invert it -> X_{d+1,d+1}
+//          waves 1-3   G_ij -= L_id L_jd^T  (i >= j > d, all but (d+1,d+1));
+//                      T_{d+1,j} = sum_{k=j..d} L_{d+1,k} X_kj  (j <= d)
+//
+// X_ij (i > j) and before it T_ij are parked in the unused upper sub-block (j, i); the
+// inverses of the diagonal sub-blocks have their own array.
 __device__ __forceinline__ double lane_bcast(double v, int src) {
   const int lo = __builtin_amdgcn_readlane(__double2loint(v), src);
   const int hi = __builtin_amdgcn_readlane(__double2hiint(v), src);
@@ -120,17 +129,49 @@ __global__ __launch_bounds__(256) void leaf_kernel(const double* __restrict__ G,
   }
   __syncthreads();
 
-  for (int d = 0; d < nb; ++d) {
+  // Factor diagonal sub-block d and invert its factor, one wave, all 64 lanes.  The symmetric
+  // 16 x 16 block M sits in four registers per lane in the accumulator layout of the MFMA read
+  // through the symmetry: lane (lq, l16), register r holds M(l16, 4 r + lq).  Column group g
+  // (columns 4g .. 4g+3) is then register g, and that register is at once the A and the B
+  // fragment of the 16 x 4 panel, so the rank-4 update of the later column groups is one MFMA
+  // with no data movement.  Inside a group the pivots go one by one: the pivot column is
+  // handed to the other lane groups with two lane permutes.  With `update`, step d-1's
+  // contribution L_{d,d-1} L_{d,d-1}^T is taken off the block first.
+  // The inverse follows by block forward substitution with 4 x 4 blocks: the four diagonal
+  // 4 x 4 inverses are computed from broadcast entries, then per block row two MFMAs:
+  // X_h = D_h - Dinv_h (T_h),  T += L(:, h) X_h.
+  auto factor_diag = [&](int d, bool update) {
     const int b0 = 16 * d;
-    if (wave == 0) {
-      // ---- factor the diagonal sub-block and invert its factor (lanes 0..15)
-      double a[16], id[16];
+    double m[4];
 #pragma unroll
-      for (int c = 0; c < 16; ++c) a[c] = S[(b0 + l16) * kLeafP + b0 + c];
-      int bad = -1;
+    for (int r = 0; r < 4; ++r) {
+      const int c = 4 * r + lq;
+      const int hi = l16 > c ? l16 : c, lo = l16 > c ? c : l16;
+      m[r] = S[(b0 + hi) * kLeafP + b0 + lo];
+    }
+    if (update) {
+      f64x4 acc = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-      for (int j = 0; j < 16; ++j) {
-        double p = lane_bcast(a[j], j);
+      for (int kk = 0; kk < 4; ++kk) {
+        const double lv = S[(b0 + l16) * kLeafP + b0 - 16 + 4 * kk + lq];
+        acc = __builtin_amdgcn_mfma_f64_16x16x4f64(lv, lv, acc, 0, 0, 0);
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) m[r] -= acc[r];
+    }
+    auto lane_fetch = [&](double v, int src_lane) -> double {  // per-lane source (ds_bpermute)
+      const int lo = __builtin_amdgcn_ds_bpermute(src_lane << 2, __double2loint(v));
+      const int hi = __builtin_amdgcn_ds_bpermute(src_lane << 2, __double2hiint(v));
+      return __hiloint2double(hi, lo);
+    };
+    int bad = -1;
+    double rinv[16];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int j = 4 * g + k;
+        double p = lane_bcast(m[g], 16 * k + j);
         if (!(p > 0.0)) {
           if (bad < 0) bad = j;
           p = 1.0;
@@ -144,111 +185,157 @@ __global__ __launch_bounds__(256) void leaf_kernel(const double* __restrict__ G,
         double sq = p * r;
         sq = fma(fma(-sq, sq, p), 0.5 * r, sq);
         r = fma(fma(-sq, r, 1.0), r, r);
-        id[j] = r;
-        a[j] = (l16 == j) ? sq : a[j] * r;
-#pragma unroll
-        for (int k = j + 1; k < 16; ++k) a[k] = fma(-a[j], lane_bcast(a[j], k), a[k]);
-      }
-      if (bad >= 0 && b0 + bad < s && tid == 0 && info[0] == PTQ_OK) {
-        info[0] = PTQ_ERR_NOT_SPD;
-        info[1] = n - 1 - (o + b0 + bad);
-      }
-      // column l16 of the inverse: x[i] = -(sum_{k<i} L_ik x[k]) / L_ii, x[l16] = 1 / L_ii
-      double x[16];
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        double sum = 0.0;
-#pragma unroll
-        for (int k = 0; k < i; ++k) sum = fma(lane_bcast(a[k], i), x[k], sum);
-        x[i] = (l16 == i) ? id[i] : (l16 < i ? -sum * id[i] : 0.0);
-      }
-      if (lane < 16) {
-#pragma unroll
-        for (int c = 0; c < 16; ++c) {
-          if (c <= lane) S[(b0 + lane) * kLeafP + b0 + c] = a[c];
-          XD[(d * 16 + c) * kXdP + lane] = x[c];
+        rinv[j] = r;
+        const double colv = (l16 == j) ? sq : (l16 > j ? m[g] * r : 0.0);
+        m[g] = (lq == k) ? colv : m[g];
+        if (k < 3) {
+          const double cj = lane_fetch(m[g], 16 * k + l16);          // L(own row, j)
+          const double mu = lane_fetch(m[g], 16 * k + 4 * g + lq);   // L(own column, j)
+          m[g] = (lq > k) ? fma(-cj, mu, m[g]) : m[g];
         }
       }
-    }
-    __syncthreads();
-    // ---- sub-blocks below the diagonal one: L_id = G_id X_dd^T
-    for (int ib = d + 1 + wave; ib < nb; ib += 4) {
-      f64x4 acc = {0.0, 0.0, 0.0, 0.0};
+      if (g < 3) {
+        const f64x4 acc = __builtin_amdgcn_mfma_f64_16x16x4f64(m[g], m[g], f64x4{0.0, 0.0, 0.0, 0.0}, 0, 0, 0);
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        const double av = S[(16 * ib + l16) * kLeafP + b0 + 4 * kk + lq];
-        const double bv = XD[(d * 16 + l16) * kXdP + 4 * kk + lq];
-        acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
-      }
-#pragma unroll
-      for (int r = 0; r < 4; ++r) S[(16 * ib + 4 * r + lq) * kLeafP + b0 + l16] = acc[r];
-    }
-    __syncthreads();
-    // ---- trailing sub-blocks (ib >= jb > d): G_ij -= L_id L_jd^T
-    {
-      const int T = nb - 1 - d;
-      const int cnt = T * (T + 1) / 2;
-      for (int q = wave; q < cnt; q += 4) {
-        int ii = 0, rem = q;
-        while (rem > ii) {
-          rem -= ii + 1;
-          ++ii;
-        }
-        const int ib = d + 1 + ii, jb = d + 1 + rem;
-        f64x4 acc = {0.0, 0.0, 0.0, 0.0};
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-          const double av = S[(16 * ib + l16) * kLeafP + b0 + 4 * kk + lq];
-          const double bv = S[(16 * jb + l16) * kLeafP + b0 + 4 * kk + lq];
-          acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
-        }
-#pragma unroll
-        for (int r = 0; r < 4; ++r) S[(16 * ib + 4 * r + lq) * kLeafP + 16 * jb + l16] -= acc[r];
+        for (int r = g + 1; r < 4; ++r) m[r] -= acc[r];
       }
     }
-    __syncthreads();
-  }
+    if (bad >= 0 && b0 + bad < s && lane == 0 && info[0] == PTQ_OK) {
+      info[0] = PTQ_ERR_NOT_SPD;
+      info[1] = n - 1 - (o + b0 + bad);
+    }
+    // diagonal 4 x 4 inverses: dA[h] = Dinv(:, 4h..4h+3) as an A fragment (lane (lq, l16) holds
+    // x_ab with a = l16 - 4h, b = lq), dD[h] the same block in the accumulator layout
+    double dA[4], dD[4];
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+      const double l10 = lane_bcast(m[h], 4 * h + 1), l20 = lane_bcast(m[h], 4 * h + 2);
+      const double l30 = lane_bcast(m[h], 4 * h + 3), l21 = lane_bcast(m[h], 16 + 4 * h + 2);
+      const double l31 = lane_bcast(m[h], 16 + 4 * h + 3), l32 = lane_bcast(m[h], 32 + 4 * h + 3);
+      const double r0 = rinv[4 * h], r1 = rinv[4 * h + 1], r2 = rinv[4 * h + 2], r3 = rinv[4 * h + 3];
+      const double x10 = -r1 * (l10 * r0);
+      const double x21 = -r2 * (l21 * r1);
+      const double x32 = -r3 * (l32 * r2);
+      const double x20 = -r2 * fma(l21, x10, l20 * r0);
+      const double x31 = -r3 * fma(l32, x21, l31 * r1);
+      const double x30 = -r3 * fma(l32, x20, fma(l31, x10, l30 * r0));
+      const int a = l16 - 4 * h, bq = lq;
+      double v = 0.0;
+      v = (a == 0 && bq == 0) ? r0 : v;
+      v = (a == 1 && bq == 1) ? r1 : v;
+      v = (a == 2 && bq == 2) ? r2 : v;
+      v = (a == 3 && bq == 3) ? r3 : v;
+      v = (a == 1 && bq == 0) ? x10 : v;
+      v = (a == 2 && bq == 1) ? x21 : v;
+      v = (a == 3 && bq == 2) ? x32 : v;
+      v = (a == 2 && bq == 0) ? x20 : v;
+      v = (a == 3 && bq == 1) ? x31 : v;
+      v = (a == 3 && bq == 0) ? x30 : v;
+      dA[h] = v;
+      // accumulator layout: lane (lq = a', l16 = 4h + b') wants x_{a'b'}, held by lane (b', 4h + a')
+      const int bp = l16 - 4 * h;
+      const bool in = (bp >= 0) & (bp < 4);
+      const double t = lane_fetch(v, in ? 16 * bp + 4 * h + lq : lane);
+      dD[h] = in ? t : 0.0;
+    }
+    f64x4 T = {0.0, 0.0, 0.0, 0.0};
+    double X[4];
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+      if (h > 0) {
+        const f64x4 o = __builtin_amdgcn_mfma_f64_16x16x4f64(dA[h], T[h], f64x4{0.0, 0.0, 0.0, 0.0}, 0, 0, 0);
+        X[h] = dD[h] - o[h];
+      } else {
+        X[h] = dD[h];
+      }
+      if (h < 3) T = __builtin_amdgcn_mfma_f64_16x16x4f64(m[h], X[h], T, 0, 0, 0);
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) XD[(d * 16 + 4 * r + lq) * kXdP + l16] = X[r];
+  };
+  auto fragA = [&](const double* blk, int kk) { return blk[l16 * kLeafP + 4 * kk + lq]; };
 
-  // ---- inverse, one wave per block column jb:
-  //   X_ij = -X_ii * sum_{k=jb}^{ib-1} L_ik X_kj ;  X_kj (k > jb) is kept in sub-block (jb, k)
-  // block column jb costs about (nb - jb)^2 / 2 sub-block products: deal the columns to
-  // the waves longest first, each to the least loaded wave
-  int mine = 0;
-  {
-    int load[4] = {0, 0, 0, 0};
-    for (int jb = 0; jb < nb; ++jb) {
-      int w = 0;
-      for (int c = 1; c < 4; ++c)
-        if (load[c] < load[w]) w = c;
-      load[w] += (nb - jb) * (nb - jb + 1);
-      if (w == wave) mine |= 1 << jb;
-    }
-  }
-  for (int jb = 0; jb < nb; ++jb) {
-    if (!((mine >> jb) & 1)) continue;
-    for (int ib = jb + 1; ib < nb; ++ib) {
-      f64x4 t = {0.0, 0.0, 0.0, 0.0};
-      for (int k = jb; k < ib; ++k) {
+  if (wave == 0) factor_diag(0, false);
+  __syncthreads();
+
+  for (int d = 0; d < nb; ++d) {
+    const int b0 = 16 * d;
+    // ---- P1: column d of L below the diagonal, row d of the inverse left of it
+    {
+      const int nB = nb - 1 - d, nItems = nB + d;
+      for (int q = wave; q < nItems; q += 4) {
+        f64x4 acc = {0.0, 0.0, 0.0, 0.0};
+        if (q < nB) {
+          const int ib = d + 1 + q;  // wave 0 gets ib = d + 1, which it needs first in P2
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-          const double av = S[(16 * ib + l16) * kLeafP + 16 * k + 4 * kk + lq];
-          const double bv = (k == jb) ? XD[(jb * 16 + 4 * kk + lq) * kXdP + l16]
-                                      : S[(16 * jb + 4 * kk + lq) * kLeafP + 16 * k + l16];
-          t = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, t, 0, 0, 0);
+          for (int kk = 0; kk < 4; ++kk) {
+            const double av = fragA(S + (16 * ib) * kLeafP + b0, kk);
+            const double bv = XD[(d * 16 + l16) * kXdP + 4 * kk + lq];
+            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
+          }
+#pragma unroll
+          for (int r = 0; r < 4; ++r) S[(16 * ib + 4 * r + lq) * kLeafP + b0 + l16] = acc[r];
+        } else {
+          const int jb = q - nB;  // X_dj = -X_dd T_dj, in place in the parked block (jb, d)
+          double* blk = S + (16 * jb) * kLeafP + b0;
+#pragma unroll
+          for (int kk = 0; kk < 4; ++kk) {
+            const double av = -XD[(d * 16 + l16) * kXdP + 4 * kk + lq];
+            const double bv = blk[(4 * kk + lq) * kLeafP + l16];
+            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
+          }
+#pragma unroll
+          for (int r = 0; r < 4; ++r) blk[(4 * r + lq) * kLeafP + l16] = acc[r];
         }
       }
-      // the accumulator layout (row 4r + lane/16) is the B-fragment layout of k-step r
-      f64x4 xo = {0.0, 0.0, 0.0, 0.0};
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        const double av = -XD[(ib * 16 + l16) * kXdP + 4 * kk + lq];
-        xo = __builtin_amdgcn_mfma_f64_16x16x4f64(av, t[kk], xo, 0, 0, 0);
-      }
-#pragma unroll
-      for (int r = 0; r < 4; ++r) S[(16 * jb + 4 * r + lq) * kLeafP + 16 * ib + l16] = xo[r];
     }
+    __syncthreads();
+    if (d + 1 >= nb) break;
+    // ---- P2
+    if (wave == 0) {
+      factor_diag(d + 1, true);
+    } else {
+      // row d+1 of the inverse, longest sums first: T_{d+1,j} = sum_{k=j..d} L_{d+1,k} X_kj
+      const int ib = d + 1;
+      const int T = nb - 1 - d;
+      const int cnt = T * (T + 1) / 2;           // trailing sub-blocks, index 0 = (d+1, d+1): wave 0's
+      const int nItems = (d + 1) + (cnt - 1);
+      for (int q = wave - 1; q < nItems; q += 3) {
+        if (q <= d) {
+          const int jb = q;
+          f64x4 t = {0.0, 0.0, 0.0, 0.0};
+          for (int k = jb; k <= d; ++k) {
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+              const double av = fragA(S + (16 * ib) * kLeafP + 16 * k, kk);
+              const double bv = (k == jb) ? XD[(jb * 16 + 4 * kk + lq) * kXdP + l16]
+                                          : S[(16 * jb + 4 * kk + lq) * kLeafP + 16 * k + l16];
+              t = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, t, 0, 0, 0);
+            }
+          }
+#pragma unroll
+          for (int r = 0; r < 4; ++r) S[(16 * jb + 4 * r + lq) * kLeafP + 16 * ib + l16] = t[r];
+        } else {
+          int ii = 0, rem = q - d;   // q - d = 1 .. cnt-1: triangular index of (ii, rem), rem <= ii
+          while (rem > ii) {
+            rem -= ii + 1;
+            ++ii;
+          }
+          const int i2 = d + 1 + ii, j2 = d + 1 + rem;
+          f64x4 acc = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+          for (int kk = 0; kk < 4; ++kk) {
+            const double av = fragA(S + (16 * i2) * kLeafP + b0, kk);
+            const double bv = fragA(S + (16 * j2) * kLeafP + b0, kk);
+            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
+          }
+#pragma unroll
+          for (int r = 0; r < 4; ++r) S[(16 * i2 + 4 * r + lq) * kLeafP + 16 * j2 + l16] -= acc[r];
+        }
+      }
+    }
+    __syncthreads();
   }
-  __syncthreads();
 
   // X(i, j), i >= j, goes to U[n-1-(o+i)][n-1-(o+j)]
   for (int e = tid; e < sp * sp; e += 256) {
