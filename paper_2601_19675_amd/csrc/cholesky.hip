@@ -109,22 +109,21 @@ __global__ __launch_bounds__(256) void leaf_kernel(const double* __restrict__ G,
   const int nb = (s + 15) >> 4, sp = nb << 4;
   const int l16 = lane & 15, lq = lane >> 4;
 
-  // load the lower triangle, sixteen independent loads per thread in flight
-  for (int base = 0; base < sp * sp; base += 256 * 16) {
-    double v[16];
+  // load the lower triangle: thread = (column j, row parity), all its loads in flight at once
+  // (padding rows / columns beyond s: identity)
+  {
+    const int j = tid & 127, i0 = tid >> 7;
+    double v[kLeaf / 2];
 #pragma unroll
-    for (int u = 0; u < 16; ++u) {
-      const int e = base + tid + 256 * u;
-      const int i = e / sp, j = e - i * sp;
-      const bool ld = (e < sp * sp) & (i < s) & (j <= i);
-      v[u] = G[ld ? (int64_t)(o + i) * n + o + j : (int64_t)o * n + o];
+    for (int u = 0; u < kLeaf / 2; ++u) {
+      const int i = i0 + 2 * u;
+      const bool ld = (i < s) & (j <= i);
+      v[u] = ld ? G[(int64_t)(o + i) * n + o + j] : ((i == j) ? 1.0 : 0.0);
     }
 #pragma unroll
-    for (int u = 0; u < 16; ++u) {
-      const int e = base + tid + 256 * u;
-      const int i = e / sp, j = e - i * sp;
-      const bool ld = (i < s) & (j <= i);
-      if (e < sp * sp) S[i * kLeafP + j] = ld ? v[u] : ((i >= s && i == j) ? 1.0 : 0.0);  // padding: identity
+    for (int u = 0; u < kLeaf / 2; ++u) {
+      const int i = i0 + 2 * u;
+      if (i < sp && j < sp) S[i * kLeafP + j] = v[u];
     }
   }
   __syncthreads();
@@ -296,55 +295,93 @@ __global__ __launch_bounds__(256) void leaf_kernel(const double* __restrict__ G,
       factor_diag(d + 1, true);
     } else {
       // row d+1 of the inverse, longest sums first: T_{d+1,j} = sum_{k=j..d} L_{d+1,k} X_kj
+      // (two accumulators, so that consecutive k blocks do not wait for each other)
       const int ib = d + 1;
-      const int T = nb - 1 - d;
-      const int cnt = T * (T + 1) / 2;           // trailing sub-blocks, index 0 = (d+1, d+1): wave 0's
-      const int nItems = (d + 1) + (cnt - 1);
-      for (int q = wave - 1; q < nItems; q += 3) {
-        if (q <= d) {
-          const int jb = q;
-          f64x4 t = {0.0, 0.0, 0.0, 0.0};
-          for (int k = jb; k <= d; ++k) {
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-              const double av = fragA(S + (16 * ib) * kLeafP + 16 * k, kk);
-              const double bv = (k == jb) ? XD[(jb * 16 + 4 * kk + lq) * kXdP + l16]
-                                          : S[(16 * jb + 4 * kk + lq) * kLeafP + 16 * k + l16];
-              t = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, t, 0, 0, 0);
-            }
-          }
-#pragma unroll
-          for (int r = 0; r < 4; ++r) S[(16 * jb + 4 * r + lq) * kLeafP + 16 * ib + l16] = t[r];
-        } else {
-          int ii = 0, rem = q - d;   // q - d = 1 .. cnt-1: triangular index of (ii, rem), rem <= ii
-          while (rem > ii) {
-            rem -= ii + 1;
-            ++ii;
-          }
-          const int i2 = d + 1 + ii, j2 = d + 1 + rem;
-          f64x4 acc = {0.0, 0.0, 0.0, 0.0};
+      for (int jb = wave - 1; jb <= d; jb += 3) {
+        f64x4 t0 = {0.0, 0.0, 0.0, 0.0}, t1 = {0.0, 0.0, 0.0, 0.0};
+        for (int k = jb; k <= d; k += 2) {
+          const bool two = k + 1 <= d;
+          const int k1 = two ? k + 1 : k;
+          double av0[4], bv0[4], av1[4], bv1[4];
 #pragma unroll
           for (int kk = 0; kk < 4; ++kk) {
-            const double av = fragA(S + (16 * i2) * kLeafP + b0, kk);
-            const double bv = fragA(S + (16 * j2) * kLeafP + b0, kk);
-            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
+            av0[kk] = fragA(S + (16 * ib) * kLeafP + 16 * k, kk);
+            bv0[kk] = (k == jb) ? XD[(jb * 16 + 4 * kk + lq) * kXdP + l16]
+                                : S[(16 * jb + 4 * kk + lq) * kLeafP + 16 * k + l16];
+            av1[kk] = fragA(S + (16 * ib) * kLeafP + 16 * k1, kk);
+            bv1[kk] = S[(16 * jb + 4 * kk + lq) * kLeafP + 16 * k1 + l16];
           }
 #pragma unroll
-          for (int r = 0; r < 4; ++r) S[(16 * i2 + 4 * r + lq) * kLeafP + 16 * j2 + l16] -= acc[r];
+          for (int kk = 0; kk < 4; ++kk) {
+            t0 = __builtin_amdgcn_mfma_f64_16x16x4f64(av0[kk], bv0[kk], t0, 0, 0, 0);
+            t1 = __builtin_amdgcn_mfma_f64_16x16x4f64(av1[kk], two ? bv1[kk] : 0.0, t1, 0, 0, 0);
+          }
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) S[(16 * jb + 4 * r + lq) * kLeafP + 16 * ib + l16] = t0[r] + t1[r];
+      }
+      // trailing sub-blocks (i2 >= j2 > d), triangular index 1 .. cnt-1 (index 0 = (d+1, d+1) is
+      // wave 0's), dealt round-robin after the d+1 sums above and processed two at a time
+      const int T = nb - 1 - d;
+      const int cnt = T * (T + 1) / 2;
+      int c0 = (wave - 1 - d) % 3;
+      if (c0 < 0) c0 += 3;
+      if (c0 == 0) c0 = 3;
+      auto decode = [&](int idx, int& i2, int& j2) {
+        int ii = 0, rem = idx;
+        while (rem > ii) {
+          rem -= ii + 1;
+          ++ii;
+        }
+        i2 = d + 1 + ii;
+        j2 = d + 1 + rem;
+      };
+      for (int c = c0; c < cnt; c += 6) {
+        const bool two = c + 3 < cnt;
+        int ia, ja, ib2, jb2;
+        decode(c, ia, ja);
+        decode(two ? c + 3 : c, ib2, jb2);
+        double a0[4], b0v[4], a1[4], b1[4], cur0[4], cur1[4];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+          a0[kk] = fragA(S + (16 * ia) * kLeafP + b0, kk);
+          b0v[kk] = fragA(S + (16 * ja) * kLeafP + b0, kk);
+          a1[kk] = fragA(S + (16 * ib2) * kLeafP + b0, kk);
+          b1[kk] = fragA(S + (16 * jb2) * kLeafP + b0, kk);
+          cur0[kk] = S[(16 * ia + 4 * kk + lq) * kLeafP + 16 * ja + l16];
+          cur1[kk] = S[(16 * ib2 + 4 * kk + lq) * kLeafP + 16 * jb2 + l16];
+        }
+        f64x4 acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+          acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64(a0[kk], b0v[kk], acc0, 0, 0, 0);
+          acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a1[kk], b1[kk], acc1, 0, 0, 0);
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) S[(16 * ia + 4 * r + lq) * kLeafP + 16 * ja + l16] = cur0[r] - acc0[r];
+        if (two) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) S[(16 * ib2 + 4 * r + lq) * kLeafP + 16 * jb2 + l16] = cur1[r] - acc1[r];
         }
       }
     }
     __syncthreads();
   }
 
-  // X(i, j), i >= j, goes to U[n-1-(o+i)][n-1-(o+j)]
-  for (int e = tid; e < sp * sp; e += 256) {
-    const int i = e / sp, j = e - i * sp;
-    if (i >= s || j > i) continue;
-    const int ib = i >> 4, jb = j >> 4;
-    const double x = (ib == jb) ? XD[(ib * 16 + (i & 15)) * kXdP + (j & 15)]
-                                : S[(16 * jb + (i & 15)) * kLeafP + 16 * ib + (j & 15)];
-    U[(int64_t)(n - 1 - (o + i)) * ldu + (n - 1 - (o + j))] = x;
+  // X(i, j), i >= j, goes to U[n-1-(o+i)][n-1-(o+j)]: thread = (column j, row parity)
+  {
+    const int j = tid & 127, i0 = tid >> 7, jb = j >> 4;
+    double* urow = U + (int64_t)(n - 1 - o) * ldu + (n - 1 - (o + j));
+#pragma unroll 8
+    for (int u = 0; u < kLeaf / 2; ++u) {
+      const int i = i0 + 2 * u;
+      if (i < s && j <= i) {
+        const int ib = i >> 4;
+        const double x = (ib == jb) ? XD[(ib * 16 + (i & 15)) * kXdP + (j & 15)]
+                                    : S[(16 * jb + (i & 15)) * kLeafP + 16 * ib + (j & 15)];
+        urow[-(int64_t)i * ldu] = x;
+      }
+    }
   }
 }
 
