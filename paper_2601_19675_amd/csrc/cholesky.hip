@@ -105,7 +105,8 @@ __global__ __launch_bounds__(256) void leaf_kernel(const double* __restrict__ G,
   extern __shared__ double lds[];
   double* S = lds;                      // [128][129]
   double* XD = lds + kLeaf * kLeafP;    // [8][16][17] inverses of the diagonal sub-blocks
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: keeps the work-list arithmetic scalar
   const int nb = (s + 15) >> 4, sp = nb << 4;
   const int l16 = lane & 15, lq = lane >> 4;
 
@@ -327,20 +328,26 @@ __global__ __launch_bounds__(256) void leaf_kernel(const double* __restrict__ G,
       int c0 = (wave - 1 - d) % 3;
       if (c0 < 0) c0 += 3;
       if (c0 == 0) c0 = 3;
-      auto decode = [&](int idx, int& i2, int& j2) {
-        int ii = 0, rem = idx;
+      // (ii, rem) = row / column of triangular index c, advanced incrementally (index += 3)
+      int ii = 0, rem = c0;
+      auto settle = [&]() {
         while (rem > ii) {
           rem -= ii + 1;
           ++ii;
         }
-        i2 = d + 1 + ii;
-        j2 = d + 1 + rem;
       };
       for (int c = c0; c < cnt; c += 6) {
         const bool two = c + 3 < cnt;
-        int ia, ja, ib2, jb2;
-        decode(c, ia, ja);
-        decode(two ? c + 3 : c, ib2, jb2);
+        settle();
+        const int ia = d + 1 + ii, ja = d + 1 + rem;
+        int ib2 = ia, jb2 = ja;
+        rem += 3;
+        if (two) {
+          settle();
+          ib2 = d + 1 + ii;
+          jb2 = d + 1 + rem;
+        }
+        rem += 3;
         double a0[4], b0v[4], a1[4], b1[4], cur0[4], cur1[4];
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
