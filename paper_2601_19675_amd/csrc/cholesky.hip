@@ -533,12 +533,12 @@ void launch_tiles2(const Op1& op1, int M1, int N1, const Op2& op2, int M2, int N
   node_gemm2_kernel<TM, TN, Op1, Op2><<<(unsigned)(gx1 * gy1 + gx2 * gy2), 256, lds, st>>>(op1, op2, gx1, gy1, gx2, gy2);
 }
 
-// Tile shape by problem size: 64 x 128 once there are enough tiles to fill the chip several
-// times over, 32 x 32 for the small nodes deep in the recursion (more workgroups, each with a
-// short k loop: those launches are bound by latency, not by the matrix pipe), else 64 x 64.
+// Tile shape by problem size, as measured: 64 x 128 once there are enough tiles to fill the
+// chip several times over; up to a 2048-wide node 32 x 32 tiles (many small workgroups per CU
+// hide the load latency of the short k loops better than few large ones); 64 x 64 between.
 inline int tile_class(int M, int N) {
   if (ceil_div(M, 64) * ceil_div(N, 128) >= 1024) return 2;
-  if (ceil_div(M, 64) * ceil_div(N, 64) <= 64) return 0;
+  if (ceil_div(M, 64) * ceil_div(N, 64) <= 1024) return 0;
   return 1;
 }
 
