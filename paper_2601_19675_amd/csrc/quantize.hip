@@ -20,7 +20,8 @@ namespace ptq {
 namespace {
 
 constexpr int kRows = 16;       // rows per workgroup
-constexpr int kThreads = 256;
+constexpr int kThreads = 512;   // eight waves: one wave per SIMD cannot keep the float64 matrix pipe busy
+constexpr int kWaves = kThreads / 64;
 
 __global__ void inv_diag_kernel(const double* __restrict__ U, int64_t ldu, int n, double* invd) {
   const int j = blockIdx.x * blockDim.x + threadIdx.x;
@@ -58,7 +59,7 @@ __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
   const double* __restrict__ U = a.U;
   const double* __restrict__ invd = a.invd;
 
-  // LDS carve-up: partial sums of the four waves (reused as the state tile),
+  // LDS carve-up: partial sums of four waves at a time (reused as the state tile),
   // the mini-block errors, the mini-block's 16 x 16 diagonal block of U and its
   // reciprocal pivots (double-buffered), group min / max, and the code tile.
   double* P = lds;                                  // [4][16][bw]
@@ -76,18 +77,18 @@ __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
 #pragma unroll
   for (int t = 0; t < NT; ++t) acc[t] = f64x4{0.0, 0.0, 0.0, 0.0};
   {
-    constexpr int kDepth = (NT >= 16) ? 3 : 4;
+    constexpr int kDepth = (NT >= 16) ? 2 : 4;
     const int kl = lane >> 4, cl = lane & 15;
     const double* ep = a.errT + (int64_t)(4 * wave + kl) * a.mpad + row0 + cl;
     const double* up = U + (int64_t)(4 * wave + kl) * a.ldu + a.i1 + cl;
     int coff[NT];  // tiles beyond the block re-read its last tile (result unused)
 #pragma unroll
     for (int t = 0; t < NT; ++t) coff[t] = 16 * (t < nt ? t : nt - 1);
-    const int niter = (a.i1 - 4 * wave + 15) / 16;  // i1 is a multiple of 16
+    const int niter = (a.i1 - 4 * wave + 4 * kWaves - 1) / (4 * kWaves);  // k = 32 it + 4 wave + kl < i1 (a multiple of 16)
     double av[kDepth], bv[kDepth][NT];
     auto issue = [&](int slot, int it) {
-      av[slot] = ep[(int64_t)it * 16 * a.mpad];
-      const double* u = up + (int64_t)it * 16 * a.ldu;
+      av[slot] = ep[(int64_t)it * (4 * kWaves) * a.mpad];
+      const double* u = up + (int64_t)it * (4 * kWaves) * a.ldu;
 #pragma unroll
       for (int t = 0; t < NT; ++t) bv[slot][t] = u[coff[t]];
     };
@@ -106,20 +107,34 @@ __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
       }
     }
   }
+  // the eight partial sums are folded in two rounds through four LDS slots
+  if (wave >= 4) {
 #pragma unroll
-  for (int t = 0; t < NT; ++t)
-    if (t < nt) {
+    for (int t = 0; t < NT; ++t)
+      if (t < nt) {
 #pragma unroll
-      for (int r = 0; r < 4; ++r)
-        P[(wave * kRows + 4 * r + (lane >> 4)) * a.bw + 16 * t + (lane & 15)] = acc[t][r];
-    }
+        for (int r = 0; r < 4; ++r)
+          P[((wave - 4) * kRows + 4 * r + (lane >> 4)) * a.bw + 16 * t + (lane & 15)] = acc[t][r];
+      }
+  }
+  __syncthreads();
+  if (wave < 4) {
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+      if (t < nt) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          P[(wave * kRows + 4 * r + (lane >> 4)) * a.bw + 16 * t + (lane & 15)] += acc[t][r];
+      }
+  }
   __syncthreads();
 
   // ---- state tile S = W - (p0 + p1 + p2 + p3), dead channels read as zero
   {
-    double sv[NT];
+    constexpr int NP = (kRows * 16 * NT + kThreads - 1) / kThreads;
+    double sv[NP];
 #pragma unroll
-    for (int p = 0; p < NT; ++p) {
+    for (int p = 0; p < NP; ++p) {
       const int e = tid + kThreads * p;
       sv[p] = 0.0;
       if (e < kRows * a.bw) {
@@ -134,7 +149,7 @@ __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
     }
     __syncthreads();
 #pragma unroll
-    for (int p = 0; p < NT; ++p) {
+    for (int p = 0; p < NP; ++p) {
       const int e = tid + kThreads * p;
       if (e < kRows * a.bw) {
         const int r = e / a.bw, c = e - r * a.bw;
@@ -142,7 +157,7 @@ __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
       }
     }
     // diagonal block of the first mini-block
-    Ud[tid] = U[(int64_t)(a.i1 + (tid >> 4)) * a.ldu + a.i1 + (tid & 15)];
+    if (tid < 256) Ud[tid] = U[(int64_t)(a.i1 + (tid >> 4)) * a.ldu + a.i1 + (tid & 15)];
     if (tid < 16) Id[tid] = invd[a.i1 + tid];
   }
   __syncthreads();
@@ -151,7 +166,7 @@ __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
   const double maxq = (double)((1 << a.bits) - 1);
   const int ng = a.n / a.group;
   double scale = 1.0, rscale = 1.0, zero = 0.0, klo = 0.0, khi = 0.0, err2 = 0.0;  // lanes 0..15 of wave 0
-  constexpr int kUpd = (NT + 3) / 4;  // tiles one wave may have to update per mini-block
+  constexpr int kUpd = (NT + kWaves - 1) / kWaves;  // tiles one wave may have to update per mini-block
   for (int mb = 0; mb < nt; ++mb) {
     const int c0 = 16 * mb;           // first column of the mini-block inside the block
     const int gcol = a.i1 + c0;       // ... and in the layer
@@ -161,35 +176,37 @@ __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
     // block and the rows of U that push this mini-block's errors onto later tiles
     double ud_next = 0.0, id_next = 0.0;
     if (mb + 1 < nt) {
-      ud_next = U[(int64_t)(gcol + 16 + (tid >> 4)) * a.ldu + gcol + 16 + (tid & 15)];
+      if (tid < 256) ud_next = U[(int64_t)(gcol + 16 + (tid >> 4)) * a.ldu + gcol + 16 + (tid & 15)];
       if (tid < 16) id_next = invd[gcol + 16 + tid];
     }
     double ub[kUpd][4];
 #pragma unroll
     for (int q = 0; q < kUpd; ++q) {
-      const int t = mb + 1 + wave + 4 * q;
+      const int t = mb + 1 + wave + kWaves * q;
       const int tc = t < nt ? t : nt - 1;
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk)
         ub[q][kk] = U[(int64_t)(gcol + 4 * kk + (lane >> 4)) * a.ldu + a.i1 + 16 * tc + (lane & 15)];
     }
     if (gstart) {
-      // min / max of the group's current values: 16 lanes per row
-      const int r = tid >> 4, sub = tid & 15;
-      double lo = 0.0, hi = 0.0;
-      for (int c = sub; c < a.group; c += 16) {
-        const double v = S[r * sp + c0 + c];
-        lo = fmin(lo, v);
-        hi = fmax(hi, v);
-      }
+      // min / max of the group's current values: 16 lanes per row (first four waves)
+      if (tid < 256) {
+        const int r = tid >> 4, sub = tid & 15;
+        double lo = 0.0, hi = 0.0;
+        for (int c = sub; c < a.group; c += 16) {
+          const double v = S[r * sp + c0 + c];
+          lo = fmin(lo, v);
+          hi = fmax(hi, v);
+        }
 #pragma unroll
-      for (int x = 8; x > 0; x >>= 1) {
-        lo = fmin(lo, __shfl_xor(lo, x));
-        hi = fmax(hi, __shfl_xor(hi, x));
-      }
-      if (sub == 0) {
-        gmin[r] = lo;
-        gmax[r] = hi;
+        for (int x = 8; x > 0; x >>= 1) {
+          lo = fmin(lo, __shfl_xor(lo, x));
+          hi = fmax(hi, __shfl_xor(hi, x));
+        }
+        if (sub == 0) {
+          gmin[r] = lo;
+          gmax[r] = hi;
+        }
       }
       __syncthreads();
     }
@@ -242,7 +259,7 @@ __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
     // push the 16 new errors onto the later tiles of the block
 #pragma unroll
     for (int q = 0; q < kUpd; ++q) {
-      const int t = mb + 1 + wave + 4 * q;
+      const int t = mb + 1 + wave + kWaves * q;
       if (t < nt) {
         f64x4 d = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
@@ -255,7 +272,7 @@ __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
       }
     }
     if (mb + 1 < nt) {
-      Ud[(buf ^ 1) * 256 + tid] = ud_next;
+      if (tid < 256) Ud[(buf ^ 1) * 256 + tid] = ud_next;
       if (tid < 16) Id[(buf ^ 1) * 16 + tid] = id_next;
     }
     __syncthreads();
