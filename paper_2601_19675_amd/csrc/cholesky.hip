@@ -487,15 +487,16 @@ __device__ __forceinline__ void node_gemm_tile(const Op& op, int bx, int by, int
   dgemm_foreach(acc, [&](int i, int j, double v) { op.store(i0 + i, j0 + j, v); });
 }
 
+// (64 x 128 tiles: three workgroups per CU fit in LDS, so the registers are capped for three)
 template <int TM, int TN, class Op>
-__global__ __launch_bounds__(256) void node_gemm_kernel(Op op) {
+__global__ __launch_bounds__(256, (TM * TN >= 8) ? 3 : 1) void node_gemm_kernel(Op op) {
   extern __shared__ double smem[];
   node_gemm_tile<TM, TN>(op, blockIdx.x, blockIdx.y, gridDim.x, gridDim.y, smem);
 }
 
 // Two independent steps in one launch: workgroups [0, gx1*gy1) take the tiles of the first.
 template <int TM, int TN, class Op1, class Op2>
-__global__ __launch_bounds__(256) void node_gemm2_kernel(Op1 op1, Op2 op2, int gx1, int gy1, int gx2, int gy2) {
+__global__ __launch_bounds__(256, (TM * TN >= 8) ? 3 : 1) void node_gemm2_kernel(Op1 op1, Op2 op2, int gx1, int gy1, int gx2, int gy2) {
   extern __shared__ double smem[];
   const int b = blockIdx.x, n1 = gx1 * gy1;
   if (b < n1)

@@ -144,19 +144,28 @@ __device__ __forceinline__ void dgemm_mainloop(f64x4 (&acc)[TM][TN], DView A, FA
     // next tile: registers -> the other LDS stage; tile after next: issue loads
     if (k0 + kGemmBK < kend) stash(k0 + kGemmBK, smem + (cur ^ 1) * T::kStageDoubles);
     if (k0 + 2 * kGemmBK < kend) fetch(k0 + 2 * kGemmBK);
-#pragma unroll
-    for (int kk = 0; kk < kGemmBK; kk += 4) {
-      double a[TM], b[TN];
+    // fragments of k-step kk+1 are read while the MFMAs of k-step kk run (two register sets):
+    // with few waves per SIMD nothing else would cover the LDS latency
+    double a[2][TM], b[2][TN];
+    auto frags = [&](int kk, int slot) {
       const int kr = kk + (lane >> 4);
 #pragma unroll
-      for (int tm = 0; tm < TM; ++tm) a[tm] = sa[kr * T::PA + wm * 16 * TM + tm * 16 + (lane & 15)];
+      for (int tm = 0; tm < TM; ++tm) a[slot][tm] = sa[kr * T::PA + wm * 16 * TM + tm * 16 + (lane & 15)];
 #pragma unroll
-      for (int tn = 0; tn < TN; ++tn) b[tn] = sb[kr * T::PB + wn * 16 * TN + tn * 16 + (lane & 15)];
+      for (int tn = 0; tn < TN; ++tn) b[slot][tn] = sb[kr * T::PB + wn * 16 * TN + tn * 16 + (lane & 15)];
+    };
+    frags(0, 0);
+#pragma unroll
+    for (int kk = 0; kk < kGemmBK; kk += 4) {
+      const int slot = (kk >> 2) & 1;
+      if (kk + 4 < kGemmBK) frags(kk + 4, slot ^ 1);
 #pragma unroll
       for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn)
-          acc[tm][tn] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[tm], b[tn], acc[tm][tn], 0, 0, 0);
+          acc[tm][tn] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[slot][tm], b[slot][tn], acc[tm][tn], 0, 0, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);   // the reads of the next k-step first
+      __builtin_amdgcn_sched_group_barrier(0x008, TM * TN, 0);   // then this k-step's MFMAs
     }
     __syncthreads();  // stage cur free for the tile after next, stage cur^1 complete
     cur ^= 1;

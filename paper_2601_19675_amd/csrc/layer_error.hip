@@ -36,7 +36,7 @@ __global__ __launch_bounds__(256) void widen_kernel(const void* __restrict__ W, 
   A2[(int64_t)m * n + e] = w;
 }
 
-__global__ __launch_bounds__(256) void quad_form_kernel(ErrArgs a) {
+__global__ __launch_bounds__(256, 3) void quad_form_kernel(ErrArgs a) {   // three workgroups per CU fit in LDS
   extern __shared__ double smem[];
   __shared__ double red[256];
   // column tiles have k ranges proportional to their index: the widest are dispatched
