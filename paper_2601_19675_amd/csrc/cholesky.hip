@@ -408,7 +408,8 @@ struct Node {
 
 // L21 = G21 X11^T, stored transposed in the mirror block of G.
 struct OpPanel {
-  static constexpr bool A_KFAST = true, B_KFAST = true, REV_I = false, REV_J = true;
+  static constexpr bool A_KFAST = true, B_KFAST = true;
+  static constexpr int K_ORDER = +2;  // k range grows with the column tile: last column tile first
   Node nd;
   __device__ int M() const { return nd.s2; }
   __device__ int N() const { return nd.s1; }
@@ -423,7 +424,8 @@ struct OpPanel {
 
 // G22 -= L21 L21^T on the lower triangle.
 struct OpSyrk {
-  static constexpr bool A_KFAST = false, B_KFAST = false, REV_I = false, REV_J = false;
+  static constexpr bool A_KFAST = false, B_KFAST = false;
+  static constexpr int K_ORDER = 0;   // every active tile has the full k range
   Node nd;
   __device__ int M() const { return nd.s2; }
   __device__ int N() const { return nd.s2; }
@@ -438,7 +440,8 @@ struct OpSyrk {
 
 // T = L21 X11, stored in the dead G21 block.
 struct OpT {
-  static constexpr bool A_KFAST = false, B_KFAST = false, REV_I = false, REV_J = false;
+  static constexpr bool A_KFAST = false, B_KFAST = false;
+  static constexpr int K_ORDER = -2;  // k range shrinks with the column tile: first column tile first
   Node nd;
   __device__ int M() const { return nd.s2; }
   __device__ int N() const { return nd.s1; }
@@ -453,7 +456,8 @@ struct OpT {
 
 // X21 = -X22 T.
 struct OpX21 {
-  static constexpr bool A_KFAST = true, B_KFAST = false, REV_I = true, REV_J = false;
+  static constexpr bool A_KFAST = true, B_KFAST = false;
+  static constexpr int K_ORDER = +1;  // k range grows with the row tile: last row tile first
   Node nd;
   __device__ int M() const { return nd.s2; }
   __device__ int N() const { return nd.s1; }
@@ -469,12 +473,22 @@ struct OpX21 {
   }
 };
 
+// Tile `lin` of the gx x gy tile grid of a step.  Triangular operands make the k ranges uneven, so
+// the tiles are handed out longest first, over the whole grid: the index the k range depends on
+// (K_ORDER: +-1 row tile, +-2 column tile; sign = which end is longest) is the slow one.
 template <int TM, int TN, class Op>
-__device__ __forceinline__ void node_gemm_tile(const Op& op, int bx, int by, int gx, int gy, double* smem) {
+__device__ __forceinline__ void node_gemm_tile(const Op& op, int lin, int gx, int gy, double* smem) {
   using T = DgemmTile<TM, TN>;
-  // tiles with the longest k range first (triangular operands make them uneven)
-  const int bi = Op::REV_I ? gy - 1 - by : by;
-  const int bj = Op::REV_J ? gx - 1 - bx : bx;
+  int bi, bj;
+  if (Op::K_ORDER == 2 || Op::K_ORDER == -2) {
+    const int q = lin / gy;
+    bi = lin - q * gy;
+    bj = Op::K_ORDER > 0 ? gx - 1 - q : q;
+  } else {
+    const int q = lin / gx;
+    bj = lin - q * gx;
+    bi = Op::K_ORDER > 0 ? gy - 1 - q : q;
+  }
   const int i0 = bi * T::BM, j0 = bj * T::BN;
   const int i1 = min(i0 + T::BM, op.M()), j1 = min(j0 + T::BN, op.N());
   if (!op.active(i0, i1, j0, j1)) return;
@@ -489,9 +503,9 @@ __device__ __forceinline__ void node_gemm_tile(const Op& op, int bx, int by, int
 
 // (64 x 128 tiles: three workgroups per CU fit in LDS, so the registers are capped for three)
 template <int TM, int TN, class Op>
-__global__ __launch_bounds__(256, (TM * TN >= 8) ? 3 : 1) void node_gemm_kernel(Op op) {
+__global__ __launch_bounds__(256, (TM * TN >= 8) ? 3 : 1) void node_gemm_kernel(Op op, int gx, int gy) {
   extern __shared__ double smem[];
-  node_gemm_tile<TM, TN>(op, blockIdx.x, blockIdx.y, gridDim.x, gridDim.y, smem);
+  node_gemm_tile<TM, TN>(op, blockIdx.x, gx, gy, smem);
 }
 
 // Two independent steps in one launch: workgroups [0, gx1*gy1) take the tiles of the first.
@@ -500,9 +514,9 @@ __global__ __launch_bounds__(256, (TM * TN >= 8) ? 3 : 1) void node_gemm2_kernel
   extern __shared__ double smem[];
   const int b = blockIdx.x, n1 = gx1 * gy1;
   if (b < n1)
-    node_gemm_tile<TM, TN>(op1, b % gx1, b / gx1, gx1, gy1, smem);
+    node_gemm_tile<TM, TN>(op1, b, gx1, gy1, smem);
   else
-    node_gemm_tile<TM, TN>(op2, (b - n1) % gx2, (b - n1) / gx2, gx2, gy2, smem);
+    node_gemm_tile<TM, TN>(op2, b - n1, gx2, gy2, smem);
 }
 
 template <int TM, int TN, class Op>
@@ -515,8 +529,8 @@ void launch_tiles(const Op& op, int M, int N, hipStream_t st) {
                         hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     opted_in = true;
   }
-  dim3 g((unsigned)ceil_div(N, T::BN), (unsigned)ceil_div(M, T::BM));
-  node_gemm_kernel<TM, TN, Op><<<g, 256, lds, st>>>(op);
+  const int gx = (int)ceil_div(N, T::BN), gy = (int)ceil_div(M, T::BM);
+  node_gemm_kernel<TM, TN, Op><<<(unsigned)(gx * gy), 256, lds, st>>>(op, gx, gy);
 }
 
 template <int TM, int TN, class Op1, class Op2>
