@@ -26,6 +26,7 @@ constexpr int kKT = 32;         // tokens per LDS stage
 constexpr int kPitch = kTile + 8;  // bf16 elements; 272-byte rows
 constexpr int kMaxChunk = 8192;      // tokens summed in float32 before the float64 reduction
 constexpr int kMaxChunkBig = 20480;  // ... in the 256 x 256-tile kernel (fewer, larger partial tiles)
+constexpr int kMaxChunkHuge = 65536; // ... and once a split alone fills the chip several times over
 
 constexpr int kTile32 = 64;     // f32-path tile
 constexpr int kKT32 = 16;
@@ -447,21 +448,30 @@ __global__ __launch_bounds__(256) void hessian_f32_kernel(const float* __restric
     for (int j = 0; j < 4; ++j) out[(ty * 4 + i) * kTile32 + tx * 4 + j] = acc[i][j];
 }
 
-// H[upper] += sum over splits of the partial tiles, in float64, fixed order.
+// H[upper] += sum over splits of the partial tiles, in float64, fixed order.  Four consecutive
+// elements of a tile row per thread (TILE is a multiple of 4, so they share the row).
 template <class PT, int TILE>
 __global__ __launch_bounds__(256) void hessian_reduce_kernel(const PT* __restrict__ partial, int splits,
                                                              int ntiles, int ntb, int n,
                                                              double* __restrict__ H, int64_t ldh) {
   int I, J;
   tile_from_linear(blockIdx.x, ntb, I, J);
-  const int e = blockIdx.y * 256 + threadIdx.x;
+  const int e = (blockIdx.y * 256 + threadIdx.x) * 4;
   const int r = e / TILE, c = e % TILE;
   const int gi = I * TILE + r, gj = J * TILE + c;
-  if (gi >= n || gj >= n || gi > gj) return;
-  double s = 0.0;
-  for (int sp = 0; sp < splits; ++sp)
-    s += (double)partial[((int64_t)sp * ntiles + blockIdx.x) * (TILE * TILE) + e];
-  H[(int64_t)gi * ldh + gj] += s;
+  if (gi >= n || gj >= n || gi > gj + 3) return;
+  double s[4] = {0.0, 0.0, 0.0, 0.0};
+  for (int sp = 0; sp < splits; ++sp) {
+    const PT* src = partial + ((int64_t)sp * ntiles + blockIdx.x) * (TILE * TILE) + e;
+    PT v[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) v[q] = src[q];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) s[q] += (double)v[q];
+  }
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+    if (gj + q < n && gi <= gj + q) H[(int64_t)gi * ldh + gj + q] += s[q];
 }
 
 struct Plan {
@@ -475,7 +485,7 @@ constexpr size_t kMaxPartialBytes = (size_t)1 << 30;  // partial tiles in flight
 // The 256-tile kernel addresses a chunk of tokens (and the ring's read-ahead past it) with
 // 32-bit byte offsets, which bounds the row pitch.
 bool big_kernel_fits(int64_t ldx) {
-  return (kMaxChunkBig + (kBRing + 1) * kBKS) * ldx * 2 < ((int64_t)1 << 32);
+  return (kMaxChunkHuge + (kBRing + 1) * kBKS) * ldx * 2 < ((int64_t)1 << 32);
 }
 
 Plan make_plan(int64_t n, int64_t t, ptq_dtype dt, bool allow_big) {
@@ -488,7 +498,8 @@ Plan make_plan(int64_t n, int64_t t, ptq_dtype dt, bool allow_big) {
   // Split the tokens so that the workgroups fill 256 CUs in whole rounds, with at most
   // max_chunk tokens summed in float32 by one workgroup: pick the split count with the
   // least (rounds x work per split).
-  const int64_t max_chunk = big ? kMaxChunkBig : kMaxChunk;
+  // (with >= 512 tiles the rounds are full for any split count, so longer float32 sums buy fewer partial tiles)
+  const int64_t max_chunk = big ? (p.ntiles >= 512 ? kMaxChunkHuge : kMaxChunkBig) : kMaxChunk;
   const int64_t s_min = ceil_div(t > 0 ? t : 1, max_chunk);
   int64_t best_s = s_min, best_cost = -1;
   for (int64_t sp = s_min; sp < s_min + 64; ++sp) {
@@ -535,7 +546,7 @@ ptq_status hessian_launch(double* H, int64_t ldh, const void* X, ptq_dtype xdt, 
     const int ns = (p.splits_total - s0 < p.splits_launch) ? p.splits_total - s0 : p.splits_launch;
     const int64_t tok0 = (int64_t)s0 * p.chunk;
     dim3 g((unsigned)p.ntiles, (unsigned)ns);
-    dim3 gr((unsigned)p.ntiles, (unsigned)(p.tile * p.tile / 256));
+    dim3 gr((unsigned)p.ntiles, (unsigned)(p.tile * p.tile / 1024));
     if (xdt == PTQ_BF16 && p.tile == kBT) {
       static bool opted_in = false;
       if (!opted_in) {
