@@ -410,6 +410,7 @@ struct Node {
 struct OpPanel {
   static constexpr bool A_KFAST = true, B_KFAST = true;
   static constexpr int K_ORDER = +2;  // k range grows with the column tile: last column tile first
+  static constexpr bool LOWER_ONLY = false;
   Node nd;
   __device__ int M() const { return nd.s2; }
   __device__ int N() const { return nd.s1; }
@@ -426,6 +427,7 @@ struct OpPanel {
 struct OpSyrk {
   static constexpr bool A_KFAST = false, B_KFAST = false;
   static constexpr int K_ORDER = 0;   // every active tile has the full k range
+  static constexpr bool LOWER_ONLY = true;  // only tiles that touch the lower triangle are launched
   Node nd;
   __device__ int M() const { return nd.s2; }
   __device__ int N() const { return nd.s2; }
@@ -442,6 +444,7 @@ struct OpSyrk {
 struct OpT {
   static constexpr bool A_KFAST = false, B_KFAST = false;
   static constexpr int K_ORDER = -2;  // k range shrinks with the column tile: first column tile first
+  static constexpr bool LOWER_ONLY = false;
   Node nd;
   __device__ int M() const { return nd.s2; }
   __device__ int N() const { return nd.s1; }
@@ -458,6 +461,7 @@ struct OpT {
 struct OpX21 {
   static constexpr bool A_KFAST = true, B_KFAST = false;
   static constexpr int K_ORDER = +1;  // k range grows with the row tile: last row tile first
+  static constexpr bool LOWER_ONLY = false;
   Node nd;
   __device__ int M() const { return nd.s2; }
   __device__ int N() const { return nd.s1; }
@@ -473,6 +477,19 @@ struct OpX21 {
   }
 };
 
+// Column tiles of row tile bi that reach the lower triangle (square matrix, tile BM x BN).
+template <int TM, int TN>
+__host__ __device__ inline int lower_tiles_in_row(int bi, int gx) {
+  const int c = ((bi + 1) * 32 * TM - 1) / (32 * TN) + 1;
+  return c < gx ? c : gx;
+}
+template <int TM, int TN>
+inline int lower_tiles(int gx, int gy) {
+  int s = 0;
+  for (int bi = 0; bi < gy; ++bi) s += lower_tiles_in_row<TM, TN>(bi, gx);
+  return s;
+}
+
 // Tile `lin` of the gx x gy tile grid of a step.  Triangular operands make the k ranges uneven, so
 // the tiles are handed out longest first, over the whole grid: the index the k range depends on
 // (K_ORDER: +-1 row tile, +-2 column tile; sign = which end is longest) is the slow one.
@@ -480,7 +497,17 @@ template <int TM, int TN, class Op>
 __device__ __forceinline__ void node_gemm_tile(const Op& op, int lin, int gx, int gy, double* smem) {
   using T = DgemmTile<TM, TN>;
   int bi, bj;
-  if (Op::K_ORDER == 2 || Op::K_ORDER == -2) {
+  if (Op::LOWER_ONLY) {
+    // row tile bi has lower_tiles_in_row(bi) tiles (bj = 0 ..); rows from the last one up
+    bi = gy - 1;
+    int c = lower_tiles_in_row<TM, TN>(bi, gx);
+    while (lin >= c) {
+      lin -= c;
+      --bi;
+      c = lower_tiles_in_row<TM, TN>(bi, gx);
+    }
+    bj = lin;
+  } else if (Op::K_ORDER == 2 || Op::K_ORDER == -2) {
     const int q = lin / gy;
     bi = lin - q * gy;
     bj = Op::K_ORDER > 0 ? gx - 1 - q : q;
@@ -508,11 +535,11 @@ __global__ __launch_bounds__(256, (TM * TN >= 8) ? 3 : 1) void node_gemm_kernel(
   node_gemm_tile<TM, TN>(op, blockIdx.x, gx, gy, smem);
 }
 
-// Two independent steps in one launch: workgroups [0, gx1*gy1) take the tiles of the first.
+// Two independent steps in one launch: workgroups [0, n1) take the tiles of the first.
 template <int TM, int TN, class Op1, class Op2>
-__global__ __launch_bounds__(256, (TM * TN >= 8) ? 3 : 1) void node_gemm2_kernel(Op1 op1, Op2 op2, int gx1, int gy1, int gx2, int gy2) {
+__global__ __launch_bounds__(256, (TM * TN >= 8) ? 3 : 1) void node_gemm2_kernel(Op1 op1, Op2 op2, int n1, int gx1, int gy1, int gx2, int gy2) {
   extern __shared__ double smem[];
-  const int b = blockIdx.x, n1 = gx1 * gy1;
+  const int b = blockIdx.x;
   if (b < n1)
     node_gemm_tile<TM, TN>(op1, b, gx1, gy1, smem);
   else
@@ -530,7 +557,8 @@ void launch_tiles(const Op& op, int M, int N, hipStream_t st) {
     opted_in = true;
   }
   const int gx = (int)ceil_div(N, T::BN), gy = (int)ceil_div(M, T::BM);
-  node_gemm_kernel<TM, TN, Op><<<(unsigned)(gx * gy), 256, lds, st>>>(op, gx, gy);
+  const int nwg = Op::LOWER_ONLY ? lower_tiles<TM, TN>(gx, gy) : gx * gy;
+  node_gemm_kernel<TM, TN, Op><<<(unsigned)nwg, 256, lds, st>>>(op, gx, gy);
 }
 
 template <int TM, int TN, class Op1, class Op2>
@@ -545,7 +573,9 @@ void launch_tiles2(const Op1& op1, int M1, int N1, const Op2& op2, int M2, int N
   }
   const int gx1 = (int)ceil_div(N1, T::BN), gy1 = (int)ceil_div(M1, T::BM);
   const int gx2 = (int)ceil_div(N2, T::BN), gy2 = (int)ceil_div(M2, T::BM);
-  node_gemm2_kernel<TM, TN, Op1, Op2><<<(unsigned)(gx1 * gy1 + gx2 * gy2), 256, lds, st>>>(op1, op2, gx1, gy1, gx2, gy2);
+  const int n1 = Op1::LOWER_ONLY ? lower_tiles<TM, TN>(gx1, gy1) : gx1 * gy1;
+  const int n2 = Op2::LOWER_ONLY ? lower_tiles<TM, TN>(gx2, gy2) : gx2 * gy2;
+  node_gemm2_kernel<TM, TN, Op1, Op2><<<(unsigned)(n1 + n2), 256, lds, st>>>(op1, op2, n1, gx1, gy1, gx2, gy2);
 }
 
 // Tile shape by problem size, as measured: 64 x 128 once there are enough tiles to fill the
