@@ -16,6 +16,8 @@
 // fixed order, so the result is bit-reproducible from run to run.
 //
 // f32 path (small layers): float64 FMAs on a 64 x 64 tile, same partial scheme.
+#include <type_traits>
+
 #include "common.h"
 
 namespace ptq {
@@ -274,20 +276,26 @@ __device__ __forceinline__ void big_tile(const uint16_t* __restrict__ X, int64_t
     // 16 MFMAs on (fa, fb) while the next fragments (na, nb) are read at `so`.  L/2 DMA
     // instructions, q0 onwards, go between the four groups of four MFMAs: issued in one
     // burst they fill the memory pipeline's queue and the wave (hence its MFMAs) stalls.
-    auto half = [&](const bf16x8 (&fa)[4], const bf16x8 (&fb)[4], bf16x8 (&na)[4], bf16x8 (&nb)[4], uint32_t so,
-                    int q0, uint32_t dst) {
+    // ROLE: 0 = the wave's whole 128 x 128 quadrant; on a diagonal tile 1 = only the MFMA
+    // tiles on or above the diagonal (the quadrant is itself a diagonal block of H),
+    // 2 = nothing (the quadrant lies below the diagonal; the wave only moves data).
+    auto half = [&](auto role, const bf16x8 (&fa)[4], const bf16x8 (&fb)[4], bf16x8 (&na)[4], bf16x8 (&nb)[4],
+                    uint32_t so, int q0, uint32_t dst) {
+      constexpr int ROLE = decltype(role)::value;
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        na[g] = read_one(so + adA[g]);
-        nb[g] = read_one(so + adB[g]);
+        if (ROLE != 2) {
+          na[g] = read_one(so + adA[g]);
+          nb[g] = read_one(so + adB[g]);
 #pragma unroll
-        for (int b = 0; b < 4; ++b)
-          acc[g][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[g], fb[b], acc[g][b], 0, 0, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
-        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);  // DS read
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+          for (int b = (ROLE == 1 ? g : 0); b < 4; ++b)
+            acc[g][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[g], fb[b], acc[g][b], 0, 0, 0);
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+          __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);  // DS read
+          if (ROLE == 0 || g < 3) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+          if (ROLE == 0 || g < 2) __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+        }
         __builtin_amdgcn_sched_barrier(0);
         if (L == 8) dma_q(q0 + g, dst);
         else if (g & 1) dma_q(q0 + (g >> 1), dst);
@@ -307,30 +315,41 @@ __device__ __forceinline__ void big_tile(const uint16_t* __restrict__ X, int64_t
     for (int q = 0; q < L / 2; ++q) dma_q(q, lbase + (kBRing - 1) * kBStage + wave * 1024);
     wait_vmcnt<2 * L + L / 2>();
     __builtin_amdgcn_s_barrier();
-    bf16x8 fa0[4], fb0[4], fa1[4], fb1[4];
-#pragma unroll
-    for (int T = 0; T < 4; ++T) {
-      fa0[T] = read_one(adA[T]);
-      fb0[T] = read_one(adB[T]);
-    }
 
     // Iteration s: tokens 0..15 of stage s | barrier | tokens 16..31.  At the barrier every wave
     // has finished reading stage s, so its slot is refilled with stage s + 4: the first half of
     // those DMA instructions is spread over the second half of iteration s, the rest over the
     // first half of iteration s + 1.  In issue order the requests outstanding at the barrier are
     // those of stages s+1, s+2, s+3, and stage s+1 is the one that must have landed.
-    for (int s = 0; s < nstage; ++s) {
-      const uint32_t slot_off = (s & (kBRing - 1)) * kBStage;
-      const uint32_t pend_off = ((s + kBRing - 1) & (kBRing - 1)) * kBStage;
-      const uint32_t next_off = ((s + 1) & (kBRing - 1)) * kBStage;
-      half(fa0, fb0, fa1, fb1, slot_off + 16 * kBRow, L / 2, lbase + pend_off + wave * 1024);
-      dma_advance();
-      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-      wait_vmcnt<2 * L>();
-      __builtin_amdgcn_s_barrier();
-      __builtin_amdgcn_sched_barrier(0);
-      half(fa1, fb1, fa0, fb0, next_off, 0, lbase + slot_off + wave * 1024);
-    }
+    auto main_loop = [&](auto role) {
+      constexpr int ROLE = decltype(role)::value;
+      bf16x8 fa0[4], fb0[4], fa1[4], fb1[4];
+      if (ROLE != 2) {
+#pragma unroll
+        for (int T = 0; T < 4; ++T) {
+          fa0[T] = read_one(adA[T]);
+          fb0[T] = read_one(adB[T]);
+        }
+      }
+      for (int s = 0; s < nstage; ++s) {
+        const uint32_t slot_off = (s & (kBRing - 1)) * kBStage;
+        const uint32_t pend_off = ((s + kBRing - 1) & (kBRing - 1)) * kBStage;
+        const uint32_t next_off = ((s + 1) & (kBRing - 1)) * kBStage;
+        half(role, fa0, fb0, fa1, fb1, slot_off + 16 * kBRow, L / 2, lbase + pend_off + wave * 1024);
+        dma_advance();
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        wait_vmcnt<2 * L>();
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        half(role, fa1, fb1, fa0, fb0, next_off, 0, lbase + slot_off + wave * 1024);
+      }
+    };
+    if (!diag || wave == 1)
+      main_loop(std::integral_constant<int, 0>{});
+    else if (wave == 2)
+      main_loop(std::integral_constant<int, 2>{});
+    else
+      main_loop(std::integral_constant<int, 1>{});
     wait_vmcnt<0>();  // nothing may still be landing in LDS when the workgroup ends
   }
 
