@@ -30,7 +30,7 @@ HBM_GBPS = 8000.0
 # (factor 2 KiB per count), WRITE_SIZE 1048576 per GiB written (1 KiB per count).
 # See profiles/hessian_C2_hbm_traffic.txt.  None for workloads that were not profiled.
 MEASURED_TRAFFIC_BYTES = {
-    "C2:attn_proj": 3.464e6 * 2048 + 5.222e5 * 1024,
+    "C2:attn_proj": 3.655e6 * 2048 + 5.222e5 * 1024,
 }
 
 
