@@ -50,7 +50,9 @@ typedef enum {
   PTQ_OP_HESSIAN = 0,
   PTQ_OP_CHOLESKY_INV = 1,
   PTQ_OP_QUANTIZE = 2,
-  PTQ_OP_LAYER_ERROR = 3
+  PTQ_OP_LAYER_ERROR = 3,
+  PTQ_OP_LOPRO_ORDER = 4,
+  PTQ_OP_LOPRO_ROTATE_HESSIAN = 5
 } ptq_op;
 
 typedef void* ptq_stream; /* hipStream_t */
@@ -80,7 +82,8 @@ ptq_status ptq_workspace_bytes(ptq_op op, int64_t m, int64_t n, int64_t t, int64
  *      leading dimension ldx >= n.  Read only.  bf16 needs n % 8 == 0 and
  *      ldx % 8 == 0 and a 16-byte aligned X (vector loads); f32 has no such rule.
  * t may be 0 (no-op).  Products of bf16 inputs are exact; partial sums run in
- * float32 over at most 8192 tokens and are added to H in float64.
+ * float32 over at most 20480 tokens (65536 for layers wider than about 8000
+ * channels) and are added to H in float64 in a fixed order.
  * Errors: PTQ_ERR_ARG (null), PTQ_ERR_SHAPE, PTQ_ERR_DTYPE, PTQ_ERR_WORKSPACE.
  */
 ptq_status ptq_hessian_accumulate(double* H, int64_t ldh, const void* X, ptq_dtype xdt, int64_t t,
@@ -162,6 +165,62 @@ ptq_status ptq_quantize_layer(const void* W, ptq_dtype wdt, int64_t ldw, int64_t
 ptq_status ptq_layer_error(const void* W, ptq_dtype wdt, int64_t ldw, const double* Wq, int64_t m,
                            int64_t n, const double* H, int64_t ldh, double* out, void* ws,
                            size_t ws_bytes, ptq_stream stream);
+
+/* ---------------------------------------------------------------------------
+ * LoPRo's pre-conditioning of the same solve (Sec. 3.2): the residual R and the
+ * proxy Hessian are taken to a permuted, partially rotated basis, the solve
+ * above runs there unchanged on (R', H'), and its result is taken back.
+ *
+ *   perm  orders the columns by  diag(H) / amean(R, axis=0)            (Eq. 5)
+ *   P     applies perm as a gather: column c of (R P) is column perm[c] of R
+ *   Q     = blockdiag(I_{b_I}, H_wal, .., H_wal), H_wal the b_H x b_H Sylvester
+ *         Hadamard matrix times 1/sqrt(b_H)                            (Eq. 6)
+ *   R'    = R P Q        H' = Q^T P^T H P Q        W = W_r + Q(R') Q^T P^T   (Eq. 6-8)
+ *
+ * b_H is a power of two, 16 <= b_H <= 256; b_I >= 0 is a multiple of 4; (n - b_I) is a
+ * multiple of b_H; n is a multiple of 4.  Violations: PTQ_ERR_SHAPE.
+ * ------------------------------------------------------------------------- */
+
+/*
+ * Column order (Eq. 5).  key_j = H_jj / mean_i |R_ij|; a column whose residual is all zero
+ * gets +inf if H_jj > 0 and 0 otherwise.  perm lists the columns by descending key
+ * (descending != 0: the columns the paper calls important come first, which is what the
+ * identity block of Q is for) or by ascending key (descending == 0: Eq. 5 read literally);
+ * equal keys keep the lower column index first.
+ *
+ * R     m x n, PTQ_F32 / PTQ_BF16 / PTQ_F64, ldr >= n.    H   n x n float64, diagonal read.
+ * perm  n int32 output.     keys  n float64 output or NULL.
+ * Errors: PTQ_ERR_ARG, PTQ_ERR_SHAPE, PTQ_ERR_DTYPE, PTQ_ERR_WORKSPACE.
+ */
+ptq_status ptq_lopro_column_order(const void* R, ptq_dtype rdt, int64_t ldr, int64_t m, int64_t n,
+                                  const double* H, int64_t ldh, int descending, int32_t* perm,
+                                  double* keys, void* ws, size_t ws_bytes, ptq_stream stream);
+
+/*
+ * R' = R P Q (Eq. 6).   Rout  m x n float64, ldo >= n, 32-byte aligned rows (ldo % 4 == 0).
+ * For bf16 / f32 inputs of moderate dynamic range and b_H = 16, 64 or 256 every sum is exact.
+ * perm must be a permutation of 0..n-1 (not checked).  No workspace.
+ */
+ptq_status ptq_lopro_rotate_weight(const void* R, ptq_dtype rdt, int64_t ldr, int64_t m, int64_t n,
+                                   const int32_t* perm, int b_I, int b_H, double* Rout, int64_t ldo,
+                                   ptq_stream stream);
+
+/*
+ * Wout = Rq Q^T P^T (Eq. 7): a matrix given in the rotated basis, e.g. the dequantized
+ * result of the solve, back in the layer's own column order.  Rq, Wout m x n float64;
+ * Rq needs ldq % 4 == 0 and a 32-byte aligned base.  Wout must not alias Rq.
+ */
+ptq_status ptq_lopro_unrotate_weight(const double* Rq, int64_t ldq, int64_t m, int64_t n,
+                                     const int32_t* perm, int b_I, int b_H, double* Wout, int64_t ldo,
+                                     ptq_stream stream);
+
+/*
+ * H' = Q^T P^T H P Q (Eq. 8).  Only the upper triangle of H is read; Hout (n x n float64,
+ * ldo >= n, ldo % 4 == 0, must not alias H) receives the full symmetric matrix.
+ */
+ptq_status ptq_lopro_rotate_hessian(const double* H, int64_t ldh, int64_t n, const int32_t* perm,
+                                    int b_I, int b_H, double* Hout, int64_t ldo, void* ws,
+                                    size_t ws_bytes, ptq_stream stream);
 
 #ifdef __cplusplus
 }

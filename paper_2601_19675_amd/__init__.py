@@ -2,5 +2,6 @@
 from .binding import (  # noqa: F401
     PTQ_BF16, PTQ_F32, PTQ_F64, PtqError, lib_path, load_library,
     ptq_damped_cholesky_inv, ptq_hessian_accumulate, ptq_layer_error,
+    ptq_lopro_column_order, ptq_lopro_rotate_hessian, ptq_lopro_rotate_weight, ptq_lopro_unrotate_weight,
     ptq_quantize_layer, ptq_status_string, ptq_workspace_bytes,
 )

@@ -15,6 +15,7 @@ import torch
 
 PTQ_F32, PTQ_BF16, PTQ_F64 = 0, 1, 2
 OP_HESSIAN, OP_CHOLESKY_INV, OP_QUANTIZE, OP_LAYER_ERROR = 0, 1, 2, 3
+OP_LOPRO_ORDER, OP_LOPRO_ROTATE_HESSIAN = 4, 5
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
@@ -55,6 +56,14 @@ def load_library() -> ctypes.CDLL:
                                        c.c_int, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.ptq_layer_error.restype = c.c_int
     lib.ptq_layer_error.argtypes = [vp, c.c_int, i64, vp, i64, i64, vp, i64, vp, vp, sz, vp]
+    lib.ptq_lopro_column_order.restype = c.c_int
+    lib.ptq_lopro_column_order.argtypes = [vp, c.c_int, i64, i64, i64, vp, i64, c.c_int, vp, vp, vp, sz, vp]
+    lib.ptq_lopro_rotate_weight.restype = c.c_int
+    lib.ptq_lopro_rotate_weight.argtypes = [vp, c.c_int, i64, i64, i64, vp, c.c_int, c.c_int, vp, i64, vp]
+    lib.ptq_lopro_unrotate_weight.restype = c.c_int
+    lib.ptq_lopro_unrotate_weight.argtypes = [vp, i64, i64, i64, vp, c.c_int, c.c_int, vp, i64, vp]
+    lib.ptq_lopro_rotate_hessian.restype = c.c_int
+    lib.ptq_lopro_rotate_hessian.argtypes = [vp, i64, i64, vp, c.c_int, c.c_int, vp, i64, vp, sz, vp]
     _LIB = lib
     return lib
 
@@ -166,3 +175,58 @@ def ptq_layer_error(W: torch.Tensor, Wq: torch.Tensor, H: torch.Tensor, out: tor
                                         ws.numel(), _stream())
     if rc:
         raise PtqError(rc, "ptq_layer_error")
+
+
+def ptq_lopro_column_order(R: torch.Tensor, H: torch.Tensor, perm: torch.Tensor, descending: bool = True,
+                           keys: torch.Tensor | None = None, ws: torch.Tensor | None = None) -> None:
+    """perm <- columns ordered by diag(H) / mean|R| (int32[n]); keys (float64[n]) optional."""
+    _check_dev(R, H, perm, keys)
+    m, n = R.shape
+    assert R.stride(1) == 1 and H.dtype == torch.float64 and H.stride(1) == 1
+    assert perm.dtype == torch.int32 and perm.is_contiguous() and perm.numel() >= n
+    assert keys is None or (keys.dtype == torch.float64 and keys.is_contiguous() and keys.numel() >= n)
+    ws = _ws(ws, ptq_workspace_bytes(OP_LOPRO_ORDER, m, n), R)
+    rc = load_library().ptq_lopro_column_order(R.data_ptr(), _dtype_code(R), R.stride(0), m, n, H.data_ptr(),
+                                               H.stride(0), int(bool(descending)), perm.data_ptr(),
+                                               _ptr(keys), ws.data_ptr(), ws.numel(), _stream())
+    if rc:
+        raise PtqError(rc, "ptq_lopro_column_order")
+
+
+def ptq_lopro_rotate_weight(R: torch.Tensor, perm: torch.Tensor, b_I: int, b_H: int, Rout: torch.Tensor) -> None:
+    """Rout <- R P Q (float64)."""
+    _check_dev(R, perm, Rout)
+    m, n = R.shape
+    assert R.stride(1) == 1 and perm.dtype == torch.int32 and perm.is_contiguous()
+    assert Rout.dtype == torch.float64 and Rout.stride(1) == 1 and Rout.shape == (m, n)
+    rc = load_library().ptq_lopro_rotate_weight(R.data_ptr(), _dtype_code(R), R.stride(0), m, n, perm.data_ptr(),
+                                                b_I, b_H, Rout.data_ptr(), Rout.stride(0), _stream())
+    if rc:
+        raise PtqError(rc, "ptq_lopro_rotate_weight")
+
+
+def ptq_lopro_unrotate_weight(Rq: torch.Tensor, perm: torch.Tensor, b_I: int, b_H: int, Wout: torch.Tensor) -> None:
+    """Wout <- Rq Q^T P^T (float64)."""
+    _check_dev(Rq, perm, Wout)
+    m, n = Rq.shape
+    assert Rq.dtype == torch.float64 and Rq.stride(1) == 1 and perm.dtype == torch.int32 and perm.is_contiguous()
+    assert Wout.dtype == torch.float64 and Wout.stride(1) == 1 and Wout.shape == (m, n)
+    rc = load_library().ptq_lopro_unrotate_weight(Rq.data_ptr(), Rq.stride(0), m, n, perm.data_ptr(), b_I, b_H,
+                                                  Wout.data_ptr(), Wout.stride(0), _stream())
+    if rc:
+        raise PtqError(rc, "ptq_lopro_unrotate_weight")
+
+
+def ptq_lopro_rotate_hessian(H: torch.Tensor, perm: torch.Tensor, b_I: int, b_H: int, Hout: torch.Tensor,
+                             ws: torch.Tensor | None = None) -> None:
+    """Hout <- Q^T P^T H P Q (full symmetric, float64); only H's upper triangle is read."""
+    _check_dev(H, perm, Hout)
+    n = H.shape[0]
+    assert H.dtype == torch.float64 and H.stride(1) == 1 and perm.dtype == torch.int32 and perm.is_contiguous()
+    assert Hout.dtype == torch.float64 and Hout.stride(1) == 1 and Hout.shape == (n, n)
+    ws = _ws(ws, ptq_workspace_bytes(OP_LOPRO_ROTATE_HESSIAN, 0, n), H)
+    rc = load_library().ptq_lopro_rotate_hessian(H.data_ptr(), H.stride(0), n, perm.data_ptr(), b_I, b_H,
+                                                 Hout.data_ptr(), Hout.stride(0), ws.data_ptr(), ws.numel(),
+                                                 _stream())
+    if rc:
+        raise PtqError(rc, "ptq_lopro_rotate_hessian")

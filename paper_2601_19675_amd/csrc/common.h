@@ -72,4 +72,19 @@ ptq_status layer_error_launch(const void* W, ptq_dtype wdt, int64_t ldw, const d
                               int64_t n, const double* H, int64_t ldh, double* out, void* ws,
                               size_t ws_bytes, hipStream_t s);
 
+
+size_t lopro_order_workspace_bytes(int64_t n);
+size_t lopro_hessian_workspace_bytes(int64_t n);
+ptq_status lopro_order_launch(const void* R, ptq_dtype rdt, int64_t ldr, int64_t m, int64_t n, const double* H,
+                              int64_t ldh, int descending, int32_t* perm, double* keys, void* ws,
+                              hipStream_t s);
+ptq_status lopro_rotate_weight_launch(const void* R, ptq_dtype rdt, int64_t ldr, int64_t m, int64_t n,
+                                      const int32_t* perm, int b_I, int b_H, double* Rout, int64_t ldo,
+                                      hipStream_t s);
+ptq_status lopro_unrotate_weight_launch(const double* Rq, int64_t ldq, int64_t m, int64_t n,
+                                        const int32_t* perm, int b_I, int b_H, double* Wout, int64_t ldo,
+                                        hipStream_t s);
+ptq_status lopro_rotate_hessian_launch(const double* H, int64_t ldh, int64_t n, const int32_t* perm, int b_I,
+                                       int b_H, double* Hout, int64_t ldo, void* ws, hipStream_t s);
+
 }  // namespace ptq

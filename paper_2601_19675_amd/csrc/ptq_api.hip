@@ -11,6 +11,12 @@ bool ws_bad(const void* ws, size_t have, size_t need) {
   return need > 0 && (ws == nullptr || misaligned(ws, 256) || have < need);
 }
 bool dtype_ok(ptq_dtype d) { return d == PTQ_F32 || d == PTQ_BF16 || d == PTQ_F64; }
+// shape rules shared by the rotation calls
+bool rotation_shape_bad(int64_t n, int b_I, int b_H) {
+  if (b_H < 16 || b_H > 256 || (b_H & (b_H - 1)) != 0) return true;
+  if (b_I < 0 || b_I > n || b_I % 4 != 0 || n % 4 != 0) return true;
+  return (n - b_I) % b_H != 0;
+}
 }  // namespace
 
 extern "C" {
@@ -37,6 +43,8 @@ ptq_status ptq_workspace_bytes(ptq_op op, int64_t m, int64_t n, int64_t t, int64
     case PTQ_OP_CHOLESKY_INV: *bytes = cholesky_workspace_bytes(n); return PTQ_OK;
     case PTQ_OP_QUANTIZE: *bytes = quantize_workspace_bytes(m, n); return PTQ_OK;
     case PTQ_OP_LAYER_ERROR: *bytes = layer_error_workspace_bytes(m, n); return PTQ_OK;
+    case PTQ_OP_LOPRO_ORDER: *bytes = lopro_order_workspace_bytes(n); return PTQ_OK;
+    case PTQ_OP_LOPRO_ROTATE_HESSIAN: *bytes = lopro_hessian_workspace_bytes(n); return PTQ_OK;
   }
   return PTQ_ERR_ARG;
 }
@@ -96,6 +104,54 @@ ptq_status ptq_layer_error(const void* W, ptq_dtype wdt, int64_t ldw, const doub
   if (ws_bad(ws, ws_bytes, layer_error_workspace_bytes(m, n))) return PTQ_ERR_WORKSPACE;
   return layer_error_launch(W, wdt, ldw, Wq, m, n, H, ldh, out, ws, ws_bytes,
                             static_cast<hipStream_t>(stream));
+}
+
+ptq_status ptq_lopro_column_order(const void* R, ptq_dtype rdt, int64_t ldr, int64_t m, int64_t n,
+                                  const double* H, int64_t ldh, int descending, int32_t* perm, double* keys,
+                                  void* ws, size_t ws_bytes, ptq_stream stream) {
+  if (!dtype_ok(rdt)) return PTQ_ERR_DTYPE;
+  if (m <= 0 || n < 0 || ldr < n || ldh < n || m > INT32_MAX / 2 || n > INT32_MAX / 2) return PTQ_ERR_SHAPE;
+  if (n == 0) return PTQ_OK;
+  if (!R || !H || !perm) return PTQ_ERR_ARG;
+  if (ws_bad(ws, ws_bytes, lopro_order_workspace_bytes(n))) return PTQ_ERR_WORKSPACE;
+  return lopro_order_launch(R, rdt, ldr, m, n, H, ldh, descending, perm, keys, ws,
+                            static_cast<hipStream_t>(stream));
+}
+
+ptq_status ptq_lopro_rotate_weight(const void* R, ptq_dtype rdt, int64_t ldr, int64_t m, int64_t n,
+                                   const int32_t* perm, int b_I, int b_H, double* Rout, int64_t ldo,
+                                   ptq_stream stream) {
+  if (!dtype_ok(rdt)) return PTQ_ERR_DTYPE;
+  if (m < 0 || n < 0 || ldr < n || ldo < n || ldo % 4 != 0 || m > INT32_MAX / 2 || n > INT32_MAX / 2)
+    return PTQ_ERR_SHAPE;
+  if (rotation_shape_bad(n, b_I, b_H)) return PTQ_ERR_SHAPE;
+  if (m == 0 || n == 0) return PTQ_OK;
+  if (!R || !perm || !Rout || misaligned(Rout, 32) || misaligned(perm, 16)) return PTQ_ERR_ARG;
+  return lopro_rotate_weight_launch(R, rdt, ldr, m, n, perm, b_I, b_H, Rout, ldo,
+                                    static_cast<hipStream_t>(stream));
+}
+
+ptq_status ptq_lopro_unrotate_weight(const double* Rq, int64_t ldq, int64_t m, int64_t n, const int32_t* perm,
+                                     int b_I, int b_H, double* Wout, int64_t ldo, ptq_stream stream) {
+  if (m < 0 || n < 0 || ldq < n || ldq % 4 != 0 || ldo < n || m > INT32_MAX / 2 || n > INT32_MAX / 2)
+    return PTQ_ERR_SHAPE;
+  if (rotation_shape_bad(n, b_I, b_H)) return PTQ_ERR_SHAPE;
+  if (m == 0 || n == 0) return PTQ_OK;
+  if (!Rq || !perm || !Wout || Rq == Wout || misaligned(Rq, 32) || misaligned(perm, 16)) return PTQ_ERR_ARG;
+  return lopro_unrotate_weight_launch(Rq, ldq, m, n, perm, b_I, b_H, Wout, ldo,
+                                      static_cast<hipStream_t>(stream));
+}
+
+ptq_status ptq_lopro_rotate_hessian(const double* H, int64_t ldh, int64_t n, const int32_t* perm, int b_I,
+                                    int b_H, double* Hout, int64_t ldo, void* ws, size_t ws_bytes,
+                                    ptq_stream stream) {
+  if (n < 0 || ldh < n || ldo < n || ldo % 4 != 0 || n > INT32_MAX / 2) return PTQ_ERR_SHAPE;
+  if (rotation_shape_bad(n, b_I, b_H)) return PTQ_ERR_SHAPE;
+  if (n == 0) return PTQ_OK;
+  if (!H || !perm || !Hout || H == Hout || misaligned(Hout, 32) || misaligned(perm, 16)) return PTQ_ERR_ARG;
+  if (ws_bad(ws, ws_bytes, lopro_hessian_workspace_bytes(n))) return PTQ_ERR_WORKSPACE;
+  return lopro_rotate_hessian_launch(H, ldh, n, perm, b_I, b_H, Hout, ldo, ws,
+                                     static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

@@ -33,7 +33,7 @@ def test_exports_every_declared_symbol(lib):
 def test_status_strings_and_workspace_sizes(lib):
     assert ptq.ptq_status_string(0) == "ok"
     assert "positive definite" in ptq.ptq_status_string(5)
-    for op in range(4):
+    for op in range(6):
         assert ptq.ptq_workspace_bytes(op, 4096, 4096, 262144, 128) % 256 == 0
     # the factorization works on one n x n float64 copy
     assert ptq.ptq_workspace_bytes(binding.OP_CHOLESKY_INV, 0, 4096) >= 4096 * 4096 * 8
@@ -76,3 +76,27 @@ def test_argument_errors_are_reported_on_the_host(lib):
     assert lib.ptq_layer_error(p, 1, 32, p, 4, 32, p, 16, p, p, 1 << 20, None) == 2   # ldh < n
     assert lib.ptq_layer_error(p, 1, 32, None, 4, 32, p, 32, p, p, 1 << 20, None) == 1
     assert lib.ptq_layer_error(p, 1, 32, p, 0, 32, p, 32, p, p, 1 << 20, None) == 2
+
+
+def test_lopro_argument_errors_are_reported_on_the_host(lib):
+    p = 0x1000  # 32-byte aligned, never dereferenced
+    big = 1 << 30
+    # rotation shape rules: b_H a power of two in [16, 256], b_I % 4 == 0, (n - b_I) % b_H == 0
+    assert lib.ptq_lopro_rotate_weight(p, 1, 512, 4, 512, p, 256, 96, p, 512, None) == 2    # b_H not a power of two
+    assert lib.ptq_lopro_rotate_weight(p, 1, 512, 4, 512, p, 256, 512, p, 512, None) == 2   # b_H > 256
+    assert lib.ptq_lopro_rotate_weight(p, 1, 512, 4, 512, p, 250, 64, p, 512, None) == 2    # b_I % 4
+    assert lib.ptq_lopro_rotate_weight(p, 1, 512, 4, 512, p, 128, 256, p, 512, None) == 2   # (n - b_I) % b_H
+    assert lib.ptq_lopro_rotate_weight(p, 1, 512, 4, 512, p, 256, 256, p, 510, None) == 2   # ldo
+    assert lib.ptq_lopro_rotate_weight(p, 5, 512, 4, 512, p, 256, 256, p, 512, None) == 3   # dtype
+    assert lib.ptq_lopro_rotate_weight(p, 1, 512, 4, 512, None, 256, 256, p, 512, None) == 1
+    assert lib.ptq_lopro_rotate_weight(p, 1, 512, 4, 512, p, 256, 256, p + 8, 512, None) == 1  # misaligned output
+    assert lib.ptq_lopro_rotate_weight(p, 1, 512, 0, 512, p, 256, 256, p, 512, None) == 0   # m == 0: no-op
+    assert lib.ptq_lopro_unrotate_weight(p, 512, 4, 512, p, 256, 256, p, 512, None) == 1    # in place
+    assert lib.ptq_lopro_unrotate_weight(p, 510, 4, 512, p, 256, 256, p + 64, 512, None) == 2
+    assert lib.ptq_lopro_rotate_hessian(p, 512, 512, p, 256, 256, p + 64, 512, None, 0, None) == 4
+    assert lib.ptq_lopro_rotate_hessian(p, 512, 512, p, 256, 256, p, 512, p, big, None) == 1   # in place
+    assert lib.ptq_lopro_rotate_hessian(p, 256, 512, p, 256, 256, p + 64, 512, p, big, None) == 2
+    assert lib.ptq_lopro_column_order(p, 1, 512, 4, 512, p, 512, 1, p, None, None, 0, None) == 4
+    assert lib.ptq_lopro_column_order(p, 1, 256, 4, 512, p, 512, 1, p, None, p, big, None) == 2
+    assert lib.ptq_lopro_column_order(p, 1, 512, 4, 512, p, 512, 1, None, None, p, big, None) == 1
+    assert lib.ptq_lopro_column_order(p, 1, 512, 0, 512, p, 512, 1, p, None, p, big, None) == 2  # no rows: keys undefined
