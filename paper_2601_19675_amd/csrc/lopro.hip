@@ -64,26 +64,23 @@ __global__ __launch_bounds__(256) void keys_kernel(const double* __restrict__ pa
   keys[c] = (a != 0.0) ? d / a : (d > 0.0 ? __builtin_inf() : 0.0);
 }
 
-// perm[rank] = column, rank = number of columns that come before it (ties: lower index first)
+// perm[rank] = column, rank = number of columns that come before it (ties: lower index first).
+// A workgroup ranks 32 columns; the comparisons against all n keys are split over eight lanes
+// per column and the eight counts are added with shuffles.
 __global__ __launch_bounds__(256) void rank_kernel(const double* __restrict__ keys, int n, int descending,
                                                    int32_t* __restrict__ perm) {
-  __shared__ double kbuf[256];
-  const int i = blockIdx.x * 256 + threadIdx.x;
+  const int i = blockIdx.x * 32 + (threadIdx.x >> 3), sl = threadIdx.x & 7;
   const double ki = i < n ? keys[i] : 0.0;
   int rank = 0;
-  for (int j0 = 0; j0 < n; j0 += 256) {
-    __syncthreads();
-    if (j0 + threadIdx.x < n) kbuf[threadIdx.x] = keys[j0 + threadIdx.x];
-    __syncthreads();
-    const int cnt = min(256, n - j0);
-    for (int jj = 0; jj < cnt; ++jj) {
-      const double kj = kbuf[jj];
-      const int j = j0 + jj;
-      const bool first = descending ? (kj > ki) : (kj < ki);
-      rank += (first || (kj == ki && j < i)) ? 1 : 0;
-    }
+  for (int j = sl; j < n; j += 8) {
+    const double kj = keys[j];
+    const bool first = descending ? (kj > ki) : (kj < ki);
+    rank += (first || (kj == ki && j < i)) ? 1 : 0;
   }
-  if (i < n) perm[rank] = i;
+  rank += __shfl_xor(rank, 1);
+  rank += __shfl_xor(rank, 2);
+  rank += __shfl_xor(rank, 4);
+  if (i < n && sl == 0) perm[rank] = i;
 }
 
 // ---- row transforms ----------------------------------------------------------------------
@@ -91,14 +88,16 @@ __global__ __launch_bounds__(256) void rank_kernel(const double* __restrict__ ke
 // MODE 1:  out[row, perm[c]] = sum_c' in[row, c'] Q[c, c']          (rotate, then scatter)
 // One workgroup per row; the row is staged in LDS in its storage type (MODE 0) resp. as float64
 // (MODE 1).  row_perm (MODE 0 only, may be null) picks the source row.
+// (256 threads, or 1024 when the staged row is so large that only one workgroup fits a CU.)
 template <int DT, int MODE>
-__global__ __launch_bounds__(256) void row_rotate_kernel(const void* __restrict__ in, int64_t ldi, int n,
+__global__ __launch_bounds__(1024) void row_rotate_kernel(const void* __restrict__ in, int64_t ldi, int n,
                                                          const int32_t* __restrict__ perm,
                                                          const int32_t* __restrict__ row_perm, int b_I, int b_H,
                                                          double* __restrict__ out, int64_t ldo) {
   extern __shared__ __attribute__((aligned(16))) char rowbuf[];
   using ST = typename StoredType<DT>::type;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int nthr = blockDim.x, nwave = nthr >> 6;
   const int row = blockIdx.x;
   const int lg = ilog2(b_H);
   const double scale = 1.0 / sqrt((double)b_H);
@@ -107,9 +106,9 @@ __global__ __launch_bounds__(256) void row_rotate_kernel(const void* __restrict_
   if (MODE == 0) {
     const int64_t src = row_perm ? row_perm[row] : row;
     ST* buf = reinterpret_cast<ST*>(rowbuf);
-    for (int c = tid; c < n; c += 256) buf[c] = load_stored<DT>(in, src * ldi + c);
+    for (int c = tid; c < n; c += nthr) buf[c] = load_stored<DT>(in, src * ldi + c);
     __syncthreads();
-    for (int k = wave; k < nchunk; k += 4) {
+    for (int k = wave; k < nchunk; k += nwave) {
       const bool ident = k < nchunk_id;
       const int cs = ident ? 256 * k : b_I + 256 * (k - nchunk_id);
       const int ce = ident ? b_I : n;
@@ -136,7 +135,7 @@ __global__ __launch_bounds__(256) void row_rotate_kernel(const void* __restrict_
   } else {
     double* buf = reinterpret_cast<double*>(rowbuf);
     const double* irow = static_cast<const double*>(in) + (int64_t)row * ldi;
-    for (int k = wave; k < nchunk; k += 4) {
+    for (int k = wave; k < nchunk; k += nwave) {
       const bool ident = k < nchunk_id;
       const int cs = ident ? 256 * k : b_I + 256 * (k - nchunk_id);
       const int ce = ident ? b_I : n;
@@ -164,7 +163,7 @@ __global__ __launch_bounds__(256) void row_rotate_kernel(const void* __restrict_
       }
     }
     __syncthreads();
-    for (int c = tid; c < n; c += 256) out[(int64_t)row * ldo + c] = buf[c];
+    for (int c = tid; c < n; c += nthr) out[(int64_t)row * ldo + c] = buf[c];
   }
 }
 
@@ -210,7 +209,7 @@ __device__ __forceinline__ void fwht16(double (&x)[16], int lg) {
   }
 }
 
-__global__ __launch_bounds__(256) void col_rotate_kernel(double* __restrict__ A, int64_t lda, int n, int b_I,
+__global__ __launch_bounds__(512) void col_rotate_kernel(double* __restrict__ A, int64_t lda, int n, int b_I,
                                                          int b_H) {
   extern __shared__ double tile[];   // [b_H][33]
   const int tid = threadIdx.x;
@@ -218,12 +217,12 @@ __global__ __launch_bounds__(256) void col_rotate_kernel(double* __restrict__ A,
   const int lg = ilog2(b_H);
   const double scale = 1.0 / sqrt((double)b_H);
   const int cx = tid & 31;
-  for (int r = tid >> 5; r < b_H; r += 8)
+  for (int r = tid >> 5; r < b_H; r += 16)
     tile[r * 33 + cx] = (c0 + cx < n) ? A[(int64_t)(r0 + r) * lda + c0 + cx] : 0.0;
   __syncthreads();
   const int groups = b_H / 16;   // 1 .. 16
   // pass 1: over b (bits 0..3 of the row index), groups x 32 column vectors
-  for (int g = tid >> 5; g < groups; g += 8) {
+  for (int g = tid >> 5; g < groups; g += 16) {
     double x[16];
 #pragma unroll
     for (int b = 0; b < 16; ++b) x[b] = tile[(16 * g + b) * 33 + cx];
@@ -233,7 +232,7 @@ __global__ __launch_bounds__(256) void col_rotate_kernel(double* __restrict__ A,
   }
   __syncthreads();
   // pass 2: over a (bits 4.. of the row index), 16 x 32 column vectors of `groups` points
-  for (int b = tid >> 5; b < 16; b += 8) {
+  for (int b = tid >> 5; b < 16; b += 16) {
     double x[16];
 #pragma unroll
     for (int a = 0; a < 16; ++a) x[a] = a < groups ? tile[(16 * a + b) * 33 + cx] : 0.0;
@@ -243,7 +242,7 @@ __global__ __launch_bounds__(256) void col_rotate_kernel(double* __restrict__ A,
       if (a < groups) tile[(16 * a + b) * 33 + cx] = x[a] * scale;
   }
   __syncthreads();
-  for (int r = tid >> 5; r < b_H; r += 8)
+  for (int r = tid >> 5; r < b_H; r += 16)
     if (c0 + cx < n) A[(int64_t)(r0 + r) * lda + c0 + cx] = tile[r * 33 + cx];
 }
 
@@ -264,8 +263,8 @@ ptq_status launch_row_rotate(const void* in, ptq_dtype dt, int64_t ldi, int64_t 
         return PTQ_ERR_HIP;                                                                                \
       opted_in = true;                                                                                     \
     }                                                                                                      \
-    row_rotate_kernel<DT, MODE><<<(unsigned)rows, 256, lds, st>>>(in, ldi, (int)n, perm, row_perm, b_I,     \
-                                                                  b_H, out, ldo);                          \
+    row_rotate_kernel<DT, MODE><<<(unsigned)rows, lds > 40 * 1024 ? 1024 : 256, lds, st>>>(                \
+        in, ldi, (int)n, perm, row_perm, b_I, b_H, out, ldo);                                              \
   }
   switch (dt) {
     case PTQ_F32: PTQ_ROW_CASE(PTQ_F32) break;
@@ -301,7 +300,7 @@ ptq_status lopro_order_launch(const void* R, ptq_dtype rdt, int64_t ldr, int64_t
     default: return PTQ_ERR_DTYPE;
   }
   keys_kernel<<<(unsigned)ceil_div(n, 256), 256, 0, st>>>(partial, H, ldh, (int)m, (int)n, k);
-  rank_kernel<<<(unsigned)ceil_div(n, 256), 256, 0, st>>>(k, (int)n, descending, perm);
+  rank_kernel<<<(unsigned)ceil_div(n, 32), 256, 0, st>>>(k, (int)n, descending, perm);
   PTQ_HIP_CHECK_LAUNCH();
   return PTQ_OK;
 }
@@ -336,7 +335,7 @@ ptq_status lopro_rotate_hessian_launch(const double* H, int64_t ldh, int64_t n, 
       opted_in = true;
     }
     dim3 gc((unsigned)ceil_div(n, 32), (unsigned)((n - b_I) / b_H));
-    col_rotate_kernel<<<gc, 256, (size_t)b_H * 33 * sizeof(double), st>>>(Hout, ldo, (int)n, b_I, b_H);
+    col_rotate_kernel<<<gc, 512, (size_t)b_H * 33 * sizeof(double), st>>>(Hout, ldo, (int)n, b_I, b_H);
   }
   PTQ_HIP_CHECK_LAUNCH();
   return PTQ_OK;
