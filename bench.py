@@ -68,6 +68,41 @@ def cpu_baseline(cfg, spec, seed):
     }
 
 
+def lopro_timings(ptq, W, H, m, n, ws, b_I=256, b_H=256, reps=10):
+    """LoPRo's pre-conditioning kernels on the benchmark layer: all memory-bound; GB/s are algorithmic
+    bytes (each operand read once, each result written once) over the event-bracketed call."""
+    import torch
+    perm = torch.empty(n, dtype=torch.int32, device="cuda")
+    Rr = torch.empty((m, n), dtype=torch.float64, device="cuda")
+    back = torch.empty_like(Rr)
+    Hr = torch.empty((n, n), dtype=torch.float64, device="cuda")
+    esz = W.element_size()
+
+    def timed(f):
+        for _ in range(2):
+            f()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            f()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    calls = {
+        "column_order": (lambda: ptq.ptq_lopro_column_order(W, H, perm, True, None, ws), m * n * esz),
+        "rotate_weight": (lambda: ptq.ptq_lopro_rotate_weight(W, perm, b_I, b_H, Rr), m * n * (esz + 8)),
+        "rotate_hessian": (lambda: ptq.ptq_lopro_rotate_hessian(H, perm, b_I, b_H, Hr, ws), n * n * (4 + 8)),
+        "unrotate_weight": (lambda: ptq.ptq_lopro_unrotate_weight(Rr, perm, b_I, b_H, back), m * n * 16),
+    }
+    out = {"b_I": b_I, "b_H": b_H}
+    for name, (f, nbytes) in calls.items():
+        ms = timed(f)
+        out[name] = {"ms": ms, "algorithmic_GBps": nbytes / ms / 1e6, "frac_of_hbm_peak": nbytes / ms / 1e6 / HBM_GBPS}
+    out["total_ms"] = sum(v["ms"] for v in out.values() if isinstance(v, dict))
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -76,6 +111,9 @@ def main():
     ap.add_argument("--config", default="C2")
     ap.add_argument("--layer", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--lopro", action="store_true",
+                    help="also time LoPRo's pre-conditioning of the same layer (column order, rotation of W and H, "
+                         "way back; b_I = b_H = 256) and report it under \"lopro\"; the step itself is unchanged")
     ap.add_argument("--device-x", action="store_true",
                     help="draw the activations on the GPU (same distribution family, torch generator) instead of "
                          "the seeded host generator: for timing the widest layers, whose host generation takes minutes")
@@ -146,7 +184,7 @@ def main():
     Wq = torch.empty((m, n), dtype=torch.float64, device=dev)
     err2 = torch.empty((m,), dtype=torch.float64, device=dev)
     out = torch.zeros(3, dtype=torch.float64, device=dev)
-    ws_bytes = max(ptq.ptq_workspace_bytes(op, m, n, t, cfg.block) for op in range(4))
+    ws_bytes = max(ptq.ptq_workspace_bytes(op, m, n, t, cfg.block) for op in range(6))
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
 
     n_ev = 5
@@ -205,6 +243,8 @@ def main():
             "algorithmic_flops_per_launch": syrk_flops, "algorithmic_bytes_per_launch": 2.0 * t * n,
         },
     }
+    if args.lopro:
+        result["lopro"] = lopro_timings(ptq, W, H, m, n, ws)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, spec, cfg.seed)
     print(json.dumps(result))

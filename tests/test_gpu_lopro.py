@@ -160,3 +160,41 @@ def test_solve_in_the_rotated_basis_end_to_end():
     assert abs(float(e_orig[0]) - rel_ref) <= 1e-4
     # rotation helps or at least does not hurt much on this layer: report, do not assert a theorem
     print(f"rel layer error rotated solve {float(e_orig[0]):.5f} (oracle {rel_ref:.5f})")
+
+
+def test_full_size_rotation_sampled(capsys):
+    # the C2 layer's own size (4096 x 4096 bf16, b_I = b_H = 256): rows of R' and entries of H' sampled
+    # against the definition (the dense oracle at n = 4096 would take minutes)
+    spec = wl.CONFIGS["C2"].layers[0]
+    n, m, bI, bH = spec.n, spec.m, 256, 256
+    Ws = wl.gen_weight(spec, wl.CONFIGS["C2"].seed)
+    W64, Wd = wl.to_f64(Ws), to_device(Ws)
+    rng = np.random.default_rng(12)
+    A = rng.standard_normal((n + 64, n)) * np.exp(0.5 * rng.standard_normal(n))
+    H = A.T @ A
+    Hd = _dev(H)
+    perm = torch.empty(n, dtype=torch.int32, device="cuda")
+    ptq.ptq_lopro_column_order(Wd, Hd, perm)
+    pg = perm.cpu().numpy().astype(np.int64)
+    kref = lo.column_keys(H, W64)
+    assert sorted(pg.tolist()) == list(range(n))
+    ks = kref[pg]
+    assert np.all(ks[:-1] >= ks[1:] * (1 - 1e-12))                 # descending up to ties to rounding
+    Rr = torch.empty((m, n), dtype=torch.float64, device="cuda")
+    Hr = torch.empty((n, n), dtype=torch.float64, device="cuda")
+    ptq.ptq_lopro_rotate_weight(Wd, perm, bI, bH, Rr)
+    ptq.ptq_lopro_rotate_hessian(Hd, perm, bI, bH, Hr)
+    Q = lo.rotation_matrix(n, bI, bH)
+    rows = rng.choice(m, 12, replace=False)
+    ref_rows = W64[rows][:, pg] @ Q
+    assert np.array_equal(Rr[torch.from_numpy(rows).cuda()].cpu().numpy(), ref_rows)
+    Hp = H[np.ix_(pg, pg)]
+    got = Hr.cpu().numpy()
+    ia, ib = rng.choice(n, 40, replace=False), rng.choice(n, 40, replace=False)
+    ref = Q[:, ia].T @ Hp @ Q[:, ib]
+    sc = np.sqrt(np.outer(np.diag(got)[ia], np.diag(got)[ib]))
+    assert np.max(np.abs(got[np.ix_(ia, ib)] - ref) / sc) <= 1e-13
+    assert abs(np.trace(got) - np.trace(H)) <= 1e-12 * np.trace(H)  # orthogonal similarity keeps the trace
+    back = torch.empty_like(Rr)
+    ptq.ptq_lopro_unrotate_weight(Rr, perm, bI, bH, back)
+    assert np.array_equal(back.cpu().numpy(), W64)                  # exact: bf16 inputs, scale 1/16 twice
