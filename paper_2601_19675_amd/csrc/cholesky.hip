@@ -547,35 +547,27 @@ __global__ __launch_bounds__(256, (TM * TN >= 8) ? 3 : 1) void node_gemm2_kernel
 }
 
 template <int TM, int TN, class Op>
-void launch_tiles(const Op& op, int M, int N, hipStream_t st) {
+bool launch_tiles(const Op& op, int M, int N, hipStream_t st) {
   using T = DgemmTile<TM, TN>;
-  static bool opted_in = false;
   constexpr int lds = T::kSmemDoubles * (int)sizeof(double);
-  if (!opted_in) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(node_gemm_kernel<TM, TN, Op>),
-                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    opted_in = true;
-  }
+  if (!lds_opt_in<node_gemm_kernel<TM, TN, Op>>(lds)) return false;
   const int gx = (int)ceil_div(N, T::BN), gy = (int)ceil_div(M, T::BM);
   const int nwg = Op::LOWER_ONLY ? lower_tiles<TM, TN>(gx, gy) : gx * gy;
   node_gemm_kernel<TM, TN, Op><<<(unsigned)nwg, 256, lds, st>>>(op, gx, gy);
+  return true;
 }
 
 template <int TM, int TN, class Op1, class Op2>
-void launch_tiles2(const Op1& op1, int M1, int N1, const Op2& op2, int M2, int N2, hipStream_t st) {
+bool launch_tiles2(const Op1& op1, int M1, int N1, const Op2& op2, int M2, int N2, hipStream_t st) {
   using T = DgemmTile<TM, TN>;
-  static bool opted_in = false;
   constexpr int lds = T::kSmemDoubles * (int)sizeof(double);
-  if (!opted_in) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(node_gemm2_kernel<TM, TN, Op1, Op2>),
-                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    opted_in = true;
-  }
+  if (!lds_opt_in<node_gemm2_kernel<TM, TN, Op1, Op2>>(lds)) return false;
   const int gx1 = (int)ceil_div(N1, T::BN), gy1 = (int)ceil_div(M1, T::BM);
   const int gx2 = (int)ceil_div(N2, T::BN), gy2 = (int)ceil_div(M2, T::BM);
   const int n1 = Op1::LOWER_ONLY ? lower_tiles<TM, TN>(gx1, gy1) : gx1 * gy1;
   const int n2 = Op2::LOWER_ONLY ? lower_tiles<TM, TN>(gx2, gy2) : gx2 * gy2;
   node_gemm2_kernel<TM, TN, Op1, Op2><<<(unsigned)(n1 + n2), 256, lds, st>>>(op1, op2, n1, gx1, gy1, gx2, gy2);
+  return true;
 }
 
 // Tile shape by problem size, as measured: 64 x 128 once there are enough tiles to fill the
@@ -588,39 +580,37 @@ inline int tile_class(int M, int N) {
 }
 
 template <class Op>
-void launch_node(const Op& op, int M, int N, hipStream_t st) {
+bool launch_node(const Op& op, int M, int N, hipStream_t st) {
   switch (tile_class(M, N)) {
-    case 2: launch_tiles<2, 4, Op>(op, M, N, st); break;
-    case 1: launch_tiles<2, 2, Op>(op, M, N, st); break;
-    default: launch_tiles<1, 1, Op>(op, M, N, st); break;
+    case 2: return launch_tiles<2, 4, Op>(op, M, N, st);
+    case 1: return launch_tiles<2, 2, Op>(op, M, N, st);
+    default: return launch_tiles<1, 1, Op>(op, M, N, st);
   }
 }
 
 template <class Op1, class Op2>
-void launch_node2(const Op1& op1, int M1, int N1, const Op2& op2, int M2, int N2, hipStream_t st) {
+bool launch_node2(const Op1& op1, int M1, int N1, const Op2& op2, int M2, int N2, hipStream_t st) {
   const int c1 = tile_class(M1, N1), c2 = tile_class(M2, N2);
   switch (c1 < c2 ? c1 : c2) {
-    case 2: launch_tiles2<2, 4, Op1, Op2>(op1, M1, N1, op2, M2, N2, st); break;
-    case 1: launch_tiles2<2, 2, Op1, Op2>(op1, M1, N1, op2, M2, N2, st); break;
-    default: launch_tiles2<1, 1, Op1, Op2>(op1, M1, N1, op2, M2, N2, st); break;
+    case 2: return launch_tiles2<2, 4, Op1, Op2>(op1, M1, N1, op2, M2, N2, st);
+    case 1: return launch_tiles2<2, 2, Op1, Op2>(op1, M1, N1, op2, M2, N2, st);
+    default: return launch_tiles2<1, 1, Op1, Op2>(op1, M1, N1, op2, M2, N2, st);
   }
 }
 
-void recurse(double* G, double* U, int ldu, int n, int o, int s, int32_t* info, hipStream_t st) {
+bool recurse(double* G, double* U, int ldu, int n, int o, int s, int32_t* info, hipStream_t st) {
   if (s <= kLeaf) {
     leaf_kernel<<<1, 256, kLeafLdsBytes, st>>>(G, n, o, s, U, ldu, info);
-    return;
+    return true;
   }
   const int nb = (int)ceil_div(s, kLeaf);
   const int s1 = (nb / 2) * kLeaf;
   const int s2 = s - s1;
   Node nd{G, U, ldu, n, o, s1, s2};
-  recurse(G, U, ldu, n, o, s1, info, st);
-  launch_node(OpPanel{nd}, s2, s1, st);
   // the trailing update and T = L21 X11 both need only L21 and touch different blocks
-  launch_node2(OpSyrk{nd}, s2, s2, OpT{nd}, s2, s1, st);
-  recurse(G, U, ldu, n, o + s1, s2, info, st);
-  launch_node(OpX21{nd}, s2, s1, st);
+  return recurse(G, U, ldu, n, o, s1, info, st) && launch_node(OpPanel{nd}, s2, s1, st) &&
+         launch_node2(OpSyrk{nd}, s2, s2, OpT{nd}, s2, s1, st) && recurse(G, U, ldu, n, o + s1, s2, info, st) &&
+         launch_node(OpX21{nd}, s2, s1, st);
 }
 
 }  // namespace
@@ -637,19 +627,13 @@ ptq_status cholesky_launch(const double* H, int64_t ldh, int64_t n, double damp,
   double* G = static_cast<double*>(ws);
   double* scal = reinterpret_cast<double*>(static_cast<char*>(ws) +
                                            align_up((size_t)n * (size_t)n * sizeof(double), 256));
-  static bool lds_opt_in = false;
-  if (!lds_opt_in) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(leaf_kernel),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLeafLdsBytes) != hipSuccess)
-      return PTQ_ERR_HIP;
-    lds_opt_in = true;
-  }
+  if (!lds_opt_in<leaf_kernel>((int)kLeafLdsBytes)) return PTQ_ERR_HIP;
   diag_stats_kernel<<<1, 1024, 0, st>>>(H, ldh, (int)n, damp, dead_mask, scal, info);
   PTQ_HIP_CHECK_LAUNCH();
   dim3 g((unsigned)ceil_div(n, 256), (unsigned)n);
   build_work_kernel<<<g, 256, 0, st>>>(H, ldh, (int)n, scal, G, U, ldu);
   PTQ_HIP_CHECK_LAUNCH();
-  recurse(G, U, (int)ldu, (int)n, 0, (int)n, info, st);
+  if (!recurse(G, U, (int)ldu, (int)n, 0, (int)n, info, st)) return PTQ_ERR_HIP;
   PTQ_HIP_CHECK_LAUNCH();
   return PTQ_OK;
 }

@@ -2,6 +2,8 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include <atomic>
 #include "../../include/ptq.h"
 
 namespace ptq {
@@ -45,6 +47,22 @@ __device__ __forceinline__ double stored_to_f64(typename StoredType<DT>::type v)
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline size_t align_up(size_t a, size_t b) { return (a + b - 1) / b * b; }
+
+// Lets `Kernel` use up to `bytes` of dynamic LDS (more than the 64 KB default needs the
+// attribute).  Done once per kernel and device; safe to call from several host threads.
+template <auto Kernel>
+inline bool lds_opt_in(int bytes) {
+  static std::atomic<uint64_t> done{0};  // one bit per device
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return false;
+  const uint64_t bit = uint64_t{1} << (dev & 63);
+  if (done.load(std::memory_order_acquire) & bit) return true;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(Kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                          bytes) != hipSuccess)
+    return false;
+  done.fetch_or(bit, std::memory_order_release);
+  return true;
+}
 
 #define PTQ_HIP_CHECK_LAUNCH()                         \
   do {                                                 \

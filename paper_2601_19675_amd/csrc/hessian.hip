@@ -567,13 +567,7 @@ ptq_status hessian_launch(double* H, int64_t ldh, const void* X, ptq_dtype xdt, 
     dim3 g((unsigned)p.ntiles, (unsigned)ns);
     dim3 gr((unsigned)p.ntiles, (unsigned)(p.tile * p.tile / 1024));
     if (xdt == PTQ_BF16 && p.tile == kBT) {
-      static bool opted_in = false;
-      if (!opted_in) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(hessian_bf16_big_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kBigLdsBytes) != hipSuccess)
-          return PTQ_ERR_HIP;
-        opted_in = true;
-      }
+      if (!lds_opt_in<hessian_bf16_big_kernel>((int)kBigLdsBytes)) return PTQ_ERR_HIP;
       const unsigned nwg = 256u * (unsigned)ceil_div((int64_t)p.ntiles * ns, 256);
       hessian_bf16_big_kernel<<<nwg, 256, kBigLdsBytes, st>>>(static_cast<const uint16_t*>(X), ldx, t, (int)n,
                                                               tok0, p.chunk, p.ntb, p.ntiles, ns,

@@ -125,13 +125,7 @@ ptq_status layer_error_launch(const void* W, ptq_dtype wdt, int64_t ldw, const d
   dim3 g(2 * (unsigned)ceil_div(m, Tile::BM), (unsigned)ceil_div(n, Tile::BN));
   const int tiles = (int)(g.x / 2 * g.y);
   constexpr int lds = Tile::kSmemDoubles * (int)sizeof(double);
-  static bool opted_in = false;
-  if (!opted_in) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(quad_form_kernel),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
-      return PTQ_ERR_HIP;
-    opted_in = true;
-  }
+  if (!lds_opt_in<quad_form_kernel>(lds)) return PTQ_ERR_HIP;
   quad_form_kernel<<<g, 256, lds, st>>>(a);
   finish_kernel<<<1, 256, 0, st>>>(partial, tiles, out);
   PTQ_HIP_CHECK_LAUNCH();

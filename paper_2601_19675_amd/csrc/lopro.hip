@@ -256,13 +256,7 @@ ptq_status launch_row_rotate(const void* in, ptq_dtype dt, int64_t ldi, int64_t 
   if (lds > 160 * 1024) return PTQ_ERR_SHAPE;
 #define PTQ_ROW_CASE(DT)                                                                                   \
   {                                                                                                        \
-    static bool opted_in = false;                                                                          \
-    if (!opted_in) {                                                                                       \
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(row_rotate_kernel<DT, MODE>),                  \
-                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)       \
-        return PTQ_ERR_HIP;                                                                                \
-      opted_in = true;                                                                                     \
-    }                                                                                                      \
+    if (!lds_opt_in<row_rotate_kernel<DT, MODE>>(160 * 1024)) return PTQ_ERR_HIP;                          \
     row_rotate_kernel<DT, MODE><<<(unsigned)rows, lds > 40 * 1024 ? 1024 : 256, lds, st>>>(                \
         in, ldi, (int)n, perm, row_perm, b_I, b_H, out, ldo);                                              \
   }
@@ -327,13 +321,7 @@ ptq_status lopro_rotate_hessian_launch(const double* H, int64_t ldh, int64_t n, 
   if (rc != PTQ_OK) return rc;
   // columns: H' = Q^T (that)
   if (n > b_I) {
-    static bool opted_in = false;
-    if (!opted_in) {
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(col_rotate_kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, 256 * 33 * 8) != hipSuccess)
-        return PTQ_ERR_HIP;
-      opted_in = true;
-    }
+    if (!lds_opt_in<col_rotate_kernel>(256 * 33 * 8)) return PTQ_ERR_HIP;
     dim3 gc((unsigned)ceil_div(n, 32), (unsigned)((n - b_I) / b_H));
     col_rotate_kernel<<<gc, 512, (size_t)b_H * 33 * sizeof(double), st>>>(Hout, ldo, (int)n, b_I, b_H);
   }

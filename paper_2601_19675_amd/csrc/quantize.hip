@@ -297,14 +297,7 @@ size_t block_lds_bytes(int bw) {
 
 template <int DT, int NT>
 ptq_status launch_block(const QuantArgs& a, hipStream_t st) {
-  static bool opted_in = false;
-  if (!opted_in) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(quant_block_kernel<DT, NT>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)block_lds_bytes(16 * NT)) != hipSuccess)
-      return PTQ_ERR_HIP;
-    opted_in = true;
-  }
+  if (!lds_opt_in<quant_block_kernel<DT, NT>>((int)block_lds_bytes(16 * NT))) return PTQ_ERR_HIP;
   quant_block_kernel<DT, NT><<<a.mpad / kRows, kThreads, block_lds_bytes(a.bw), st>>>(a);
   return PTQ_OK;
 }
