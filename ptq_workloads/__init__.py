@@ -33,6 +33,8 @@ _TENSOR_W = 1
 _TENSOR_X = 2
 _TENSOR_SCALE = 3
 _TENSOR_OUTLIER = 4
+_TENSOR_SKETCH = 5
+_TENSOR_LOWRANK = 6
 
 
 # ----------------------------------------------------------------------------
@@ -159,6 +161,30 @@ def gen_weight(spec: LayerSpec, seed: int = BASE_SEED) -> np.ndarray:
         cols = _rng(seed, spec.layer_id, _TENSOR_OUTLIER).choice(spec.n, n_out, replace=False)
         w[:, cols] *= spec.outlier_mul
     return store(w, spec.dtype)
+
+
+def gen_weight_with_low_rank_part(spec: LayerSpec, seed: int = BASE_SEED, rank: int = 8,
+                                  strength: float = 6.0) -> np.ndarray:
+    """gen_weight plus a few strong directions: sum_k c_k a_k b_k^T with unit-norm Gaussian
+    a_k, b_k and c_k = strength * w_sigma * sqrt(max(m, n)) / (k + 1), i.e. `strength` times
+    the largest singular value of the Gaussian part for k = 0, then decaying.  Trained
+    weights have such leading directions; pure Gaussian noise gives a low-rank step
+    nothing to find."""
+    w = to_f64(gen_weight(spec, seed))
+    rng = _rng(seed, spec.layer_id, _TENSOR_LOWRANK)
+    for k in range(rank):
+        a = rng.standard_normal(spec.m)
+        b = rng.standard_normal(spec.n)
+        c = strength * spec.w_sigma * np.sqrt(max(spec.m, spec.n)) / (k + 1)
+        w += c * np.outer(a / np.linalg.norm(a), b / np.linalg.norm(b))
+    return store(w, spec.dtype)
+
+
+def gen_sketch_vectors(spec: LayerSpec, r: int, seed: int = BASE_SEED) -> np.ndarray:
+    """r x n float32 standard normal draws: the random vectors a sketching method asks for,
+    drawn here so that every implementation under test sees the same ones."""
+    rng = _rng(seed, spec.layer_id, _TENSOR_SKETCH)
+    return rng.standard_normal((r, spec.n), dtype=np.float32)
 
 
 def channel_scales(spec: LayerSpec, seed: int = BASE_SEED) -> np.ndarray:
