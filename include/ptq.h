@@ -52,7 +52,9 @@ typedef enum {
   PTQ_OP_QUANTIZE = 2,
   PTQ_OP_LAYER_ERROR = 3,
   PTQ_OP_LOPRO_ORDER = 4,
-  PTQ_OP_LOPRO_ROTATE_HESSIAN = 5
+  PTQ_OP_LOPRO_ROTATE_HESSIAN = 5,
+  PTQ_OP_ACTIVATION_ABS_SUM = 6,
+  PTQ_OP_SCALED_R1SVD = 7
 } ptq_op;
 
 typedef void* ptq_stream; /* hipStream_t */
@@ -221,6 +223,62 @@ ptq_status ptq_lopro_unrotate_weight(const double* Rq, int64_t ldq, int64_t m, i
 ptq_status ptq_lopro_rotate_hessian(const double* H, int64_t ldh, int64_t n, const int32_t* perm,
                                     int b_I, int b_H, double* Hout, int64_t ldo, void* ws,
                                     size_t ws_bytes, ptq_stream stream);
+
+/* ---------------------------------------------------------------------------
+ * The low-rank step that produces the residual R (Sec. 3.1, Eq. 4: W = W_r + R with
+ * W_r from a decomposition of the activation-scaled weight; Sec. 3.3: the rank-one
+ * randomized sketch "R1SVD"; Algorithm 1, the lines before the permutation).
+ * ------------------------------------------------------------------------- */
+
+/*
+ * Per-channel activation magnitude (Algorithm 1: Xbar = mean(|X|, axis 0)), kept as a raw
+ * sum so that calibration batches can be streamed:
+ *
+ *   asum[j] += sum_k |X[k][j]|
+ *
+ * asum  n float64, accumulated in place (zero it before the first batch).
+ * X     t x n, PTQ_F32 or PTQ_BF16, ldx >= n; n and ldx multiples of 8, base 16-byte aligned.
+ * Sums are float64 and taken in a fixed order.  Workspace: PTQ_OP_ACTIVATION_ABS_SUM.
+ * Errors: PTQ_ERR_ARG, PTQ_ERR_SHAPE, PTQ_ERR_DTYPE, PTQ_ERR_WORKSPACE.
+ */
+ptq_status ptq_activation_abs_sum(double* asum, const void* X, ptq_dtype xdt, int64_t t, int64_t n,
+                                  int64_t ldx, void* ws, size_t ws_bytes, ptq_stream stream);
+
+/*
+ * The scale of Algorithm 1 from the accumulated sums:  Xbar = asum / tokens,
+ *   s_j = Xbar_j^2.5 / sqrt(max(Xbar) * min(Xbar)).
+ * max and min run over the channels with Xbar_j > 0; a channel that was never active gets
+ * s_j = 1 (the printed formula has no value there).   s  n float64 output.  No workspace.
+ */
+ptq_status ptq_activation_scale(const double* asum, int64_t tokens, int64_t n, double* s,
+                                ptq_stream stream);
+
+/*
+ * Scaled rank-one sketching (Sec. 3.3, Eq. 9-11; Algorithm 1).  With A = W diag(s), for
+ * k = 0 .. r-1:
+ *     y = (A A^T)^it A S[k],   p = A^T y,
+ *     U[k] = e4m3(y / ||y||),  V[k] = e4m3(p / ||p||),  sigma[k] = fp16(||p|| / ||y||),
+ *     A <- A - sigma[k] U[k] V[k]^T      (with the stored, rounded values)
+ * and finally  R = A diag(s)^-1, so that  W = (U^T diag(sigma) V) diag(s)^-1 + R  holds for
+ * what is stored.  If y or p is zero the rank stores zeros.
+ *
+ * W      m x n, PTQ_F32 / PTQ_BF16 / PTQ_F64, ldw >= n.      s  n float64, all entries nonzero.
+ * S      r x n float32 with leading dimension lds >= n: the random vector of each rank
+ *        (the caller draws them; standard normal in the paper's prototype).
+ * U, V   r x m and r x n bytes, dense: OCP e4m3 codes (bias 7, no infinities), conversion
+ *        rounds to nearest, ties to even.      sigma  r IEEE binary16 bit patterns.
+ * R      m x n float32 output, ldr >= n, ldr % 4 == 0, 16-byte aligned.  May not alias W.
+ * r, it  rank and number of power iterations (the paper uses 16 and 8); r = 0 gives R = W.
+ * n % 4 == 0 and n <= 32768.
+ * The running matrix is held in float32, every product and sum is float64 in a fixed
+ * order: results are reproducible run to run.
+ * Workspace: PTQ_OP_SCALED_R1SVD (m, n).
+ * Errors: PTQ_ERR_ARG, PTQ_ERR_SHAPE, PTQ_ERR_DTYPE, PTQ_ERR_WORKSPACE, PTQ_ERR_HIP.
+ */
+ptq_status ptq_scaled_r1svd(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m, int64_t n,
+                            const double* s, const float* S, int64_t lds, int r, int it, uint8_t* U,
+                            uint8_t* V, uint16_t* sigma, float* R, int64_t ldr, void* ws,
+                            size_t ws_bytes, ptq_stream stream);
 
 #ifdef __cplusplus
 }

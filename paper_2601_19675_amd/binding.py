@@ -16,6 +16,7 @@ import torch
 PTQ_F32, PTQ_BF16, PTQ_F64 = 0, 1, 2
 OP_HESSIAN, OP_CHOLESKY_INV, OP_QUANTIZE, OP_LAYER_ERROR = 0, 1, 2, 3
 OP_LOPRO_ORDER, OP_LOPRO_ROTATE_HESSIAN = 4, 5
+OP_ACTIVATION_ABS_SUM, OP_SCALED_R1SVD = 6, 7
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
@@ -64,6 +65,13 @@ def load_library() -> ctypes.CDLL:
     lib.ptq_lopro_unrotate_weight.argtypes = [vp, i64, i64, i64, vp, c.c_int, c.c_int, vp, i64, vp]
     lib.ptq_lopro_rotate_hessian.restype = c.c_int
     lib.ptq_lopro_rotate_hessian.argtypes = [vp, i64, i64, vp, c.c_int, c.c_int, vp, i64, vp, sz, vp]
+    lib.ptq_activation_abs_sum.restype = c.c_int
+    lib.ptq_activation_abs_sum.argtypes = [vp, vp, c.c_int, i64, i64, i64, vp, sz, vp]
+    lib.ptq_activation_scale.restype = c.c_int
+    lib.ptq_activation_scale.argtypes = [vp, i64, i64, vp, vp]
+    lib.ptq_scaled_r1svd.restype = c.c_int
+    lib.ptq_scaled_r1svd.argtypes = [vp, c.c_int, i64, i64, i64, vp, vp, i64, c.c_int, c.c_int, vp, vp, vp, vp,
+                                     i64, vp, sz, vp]
     _LIB = lib
     return lib
 
@@ -230,3 +238,48 @@ def ptq_lopro_rotate_hessian(H: torch.Tensor, perm: torch.Tensor, b_I: int, b_H:
                                                  _stream())
     if rc:
         raise PtqError(rc, "ptq_lopro_rotate_hessian")
+
+
+def ptq_activation_abs_sum(asum: torch.Tensor, X: torch.Tensor, ws: torch.Tensor | None = None) -> None:
+    """asum[j] += sum_k |X[k, j]| (float64[n], accumulated in place)."""
+    _check_dev(asum, X)
+    t, n = X.shape
+    assert X.stride(1) == 1 and asum.dtype == torch.float64 and asum.is_contiguous() and asum.numel() >= n
+    ws = _ws(ws, ptq_workspace_bytes(OP_ACTIVATION_ABS_SUM, 0, n), X)
+    rc = load_library().ptq_activation_abs_sum(asum.data_ptr(), X.data_ptr(), _dtype_code(X), t, n, X.stride(0),
+                                               ws.data_ptr(), ws.numel(), _stream())
+    if rc:
+        raise PtqError(rc, "ptq_activation_abs_sum")
+
+
+def ptq_activation_scale(asum: torch.Tensor, tokens: int, s: torch.Tensor) -> None:
+    """s <- Xbar^2.5 / sqrt(max(Xbar) min(Xbar)), Xbar = asum / tokens (float64[n])."""
+    _check_dev(asum, s)
+    n = asum.numel()
+    assert asum.dtype == torch.float64 and asum.is_contiguous()
+    assert s.dtype == torch.float64 and s.is_contiguous() and s.numel() >= n
+    rc = load_library().ptq_activation_scale(asum.data_ptr(), int(tokens), n, s.data_ptr(), _stream())
+    if rc:
+        raise PtqError(rc, "ptq_activation_scale")
+
+
+def ptq_scaled_r1svd(W: torch.Tensor, s: torch.Tensor, S: torch.Tensor, it: int, U: torch.Tensor, V: torch.Tensor,
+                     sigma: torch.Tensor, R: torch.Tensor, ws: torch.Tensor | None = None) -> None:
+    """Rank-by-rank sketch of W diag(s): U (uint8 r x m), V (uint8 r x n) e4m3 codes, sigma (float16 r),
+    R (float32 m x n) the residual; S (float32 r x n) holds the random vector of each rank."""
+    _check_dev(W, s, S, U, V, sigma, R)
+    m, n = W.shape
+    r = S.shape[0]
+    assert W.stride(1) == 1 and s.dtype == torch.float64 and s.is_contiguous() and s.numel() == n
+    assert S.dtype == torch.float32 and S.shape == (r, n) and (r == 0 or S.stride(1) == 1)
+    assert U.dtype == torch.uint8 and U.is_contiguous() and U.shape == (r, m)
+    assert V.dtype == torch.uint8 and V.is_contiguous() and V.shape == (r, n)
+    assert sigma.dtype == torch.float16 and sigma.is_contiguous() and sigma.numel() == r
+    assert R.dtype == torch.float32 and R.stride(1) == 1 and R.shape == (m, n)
+    ws = _ws(ws, ptq_workspace_bytes(OP_SCALED_R1SVD, m, n), W)
+    rc = load_library().ptq_scaled_r1svd(W.data_ptr(), _dtype_code(W), W.stride(0), m, n, s.data_ptr(),
+                                         S.data_ptr(), S.stride(0) if r else n, r, int(it), U.data_ptr(),
+                                         V.data_ptr(), sigma.data_ptr(), R.data_ptr(), R.stride(0),
+                                         ws.data_ptr(), ws.numel(), _stream())
+    if rc:
+        raise PtqError(rc, "ptq_scaled_r1svd")

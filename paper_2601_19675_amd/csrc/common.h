@@ -105,4 +105,15 @@ ptq_status lopro_unrotate_weight_launch(const double* Rq, int64_t ldq, int64_t m
 ptq_status lopro_rotate_hessian_launch(const double* H, int64_t ldh, int64_t n, const int32_t* perm, int b_I,
                                        int b_H, double* Hout, int64_t ldo, void* ws, hipStream_t s);
 
+
+size_t abs_sum_workspace_bytes(int64_t n);
+ptq_status abs_sum_launch(double* asum, const void* X, ptq_dtype xdt, int64_t t, int64_t n, int64_t ldx, void* ws,
+                          hipStream_t s);
+ptq_status activation_scale_launch(const double* asum, int64_t tokens, int64_t n, double* s, hipStream_t st);
+size_t r1svd_workspace_bytes(int64_t m, int64_t n);
+int64_t r1svd_max_columns();
+ptq_status r1svd_launch(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m, int64_t n, const double* s,
+                        const float* S, int64_t lds, int r, int it, uint8_t* U, uint8_t* V, uint16_t* sigma16,
+                        float* Rout, int64_t ldr, void* ws, hipStream_t st);
+
 }  // namespace ptq

@@ -45,6 +45,8 @@ ptq_status ptq_workspace_bytes(ptq_op op, int64_t m, int64_t n, int64_t t, int64
     case PTQ_OP_LAYER_ERROR: *bytes = layer_error_workspace_bytes(m, n); return PTQ_OK;
     case PTQ_OP_LOPRO_ORDER: *bytes = lopro_order_workspace_bytes(n); return PTQ_OK;
     case PTQ_OP_LOPRO_ROTATE_HESSIAN: *bytes = lopro_hessian_workspace_bytes(n); return PTQ_OK;
+    case PTQ_OP_ACTIVATION_ABS_SUM: *bytes = abs_sum_workspace_bytes(n); return PTQ_OK;
+    case PTQ_OP_SCALED_R1SVD: *bytes = r1svd_workspace_bytes(m, n); return PTQ_OK;
   }
   return PTQ_ERR_ARG;
 }
@@ -152,6 +154,39 @@ ptq_status ptq_lopro_rotate_hessian(const double* H, int64_t ldh, int64_t n, con
   if (ws_bad(ws, ws_bytes, lopro_hessian_workspace_bytes(n))) return PTQ_ERR_WORKSPACE;
   return lopro_rotate_hessian_launch(H, ldh, n, perm, b_I, b_H, Hout, ldo, ws,
                                      static_cast<hipStream_t>(stream));
+}
+
+ptq_status ptq_activation_abs_sum(double* asum, const void* X, ptq_dtype xdt, int64_t t, int64_t n, int64_t ldx,
+                                  void* ws, size_t ws_bytes, ptq_stream stream) {
+  if (xdt != PTQ_F32 && xdt != PTQ_BF16) return PTQ_ERR_DTYPE;
+  if (t < 0 || n < 0 || ldx < n || n % 8 != 0 || ldx % 8 != 0 || n > INT32_MAX / 2) return PTQ_ERR_SHAPE;
+  if (t == 0 || n == 0) return PTQ_OK;
+  if (!asum || !X || misaligned(X, 16)) return PTQ_ERR_ARG;
+  if (ws_bad(ws, ws_bytes, abs_sum_workspace_bytes(n))) return PTQ_ERR_WORKSPACE;
+  return abs_sum_launch(asum, X, xdt, t, n, ldx, ws, static_cast<hipStream_t>(stream));
+}
+
+ptq_status ptq_activation_scale(const double* asum, int64_t tokens, int64_t n, double* s, ptq_stream stream) {
+  if (tokens <= 0 || n < 0 || n > INT32_MAX / 2) return PTQ_ERR_SHAPE;
+  if (n == 0) return PTQ_OK;
+  if (!asum || !s) return PTQ_ERR_ARG;
+  return activation_scale_launch(asum, tokens, n, s, static_cast<hipStream_t>(stream));
+}
+
+ptq_status ptq_scaled_r1svd(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m, int64_t n, const double* s,
+                            const float* S, int64_t lds, int r, int it, uint8_t* U, uint8_t* V,
+                            uint16_t* sigma, float* R, int64_t ldr, void* ws, size_t ws_bytes,
+                            ptq_stream stream) {
+  if (!dtype_ok(wdt)) return PTQ_ERR_DTYPE;
+  if (m <= 0 || n <= 0 || ldw < n || ldr < n || ldr % 4 != 0 || n % 4 != 0 || lds < n || m > INT32_MAX / 2 ||
+      n > r1svd_max_columns())
+    return PTQ_ERR_SHAPE;
+  if (r < 0 || r > 1024 || it < 0 || it > 1024) return PTQ_ERR_ARG;
+  if (!W || !s || !R || misaligned(R, 16) || static_cast<const void*>(R) == W) return PTQ_ERR_ARG;
+  if (r > 0 && (!S || !U || !V || !sigma)) return PTQ_ERR_ARG;
+  if (ws_bad(ws, ws_bytes, r1svd_workspace_bytes(m, n))) return PTQ_ERR_WORKSPACE;
+  return r1svd_launch(W, wdt, ldw, m, n, s, S, lds, r, it, U, V, sigma, R, ldr, ws,
+                      static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

@@ -33,7 +33,7 @@ def test_exports_every_declared_symbol(lib):
 def test_status_strings_and_workspace_sizes(lib):
     assert ptq.ptq_status_string(0) == "ok"
     assert "positive definite" in ptq.ptq_status_string(5)
-    for op in range(6):
+    for op in range(8):
         assert ptq.ptq_workspace_bytes(op, 4096, 4096, 262144, 128) % 256 == 0
     # the factorization works on one n x n float64 copy
     assert ptq.ptq_workspace_bytes(binding.OP_CHOLESKY_INV, 0, 4096) >= 4096 * 4096 * 8
@@ -41,7 +41,7 @@ def test_status_strings_and_workspace_sizes(lib):
     assert ptq.ptq_workspace_bytes(binding.OP_QUANTIZE, 4096, 11008) >= 4096 * 11008 * 8
     out = ctypes.c_size_t()
     assert lib.ptq_workspace_bytes(0, -1, 8, 8, 0, ctypes.byref(out)) == 2
-    assert lib.ptq_workspace_bytes(7, 1, 8, 8, 0, ctypes.byref(out)) == 1
+    assert lib.ptq_workspace_bytes(8, 1, 8, 8, 0, ctypes.byref(out)) == 1
     assert lib.ptq_workspace_bytes(0, 1, 8, 8, 0, None) == 1
 
 
@@ -100,3 +100,39 @@ def test_lopro_argument_errors_are_reported_on_the_host(lib):
     assert lib.ptq_lopro_column_order(p, 1, 256, 4, 512, p, 512, 1, p, None, p, big, None) == 2
     assert lib.ptq_lopro_column_order(p, 1, 512, 4, 512, p, 512, 1, None, None, p, big, None) == 1
     assert lib.ptq_lopro_column_order(p, 1, 512, 0, 512, p, 512, 1, p, None, p, big, None) == 2  # no rows: keys undefined
+
+
+def test_low_rank_step_argument_errors_are_reported_on_the_host(lib):
+    p = 0x1000
+    big = 1 << 34
+    # activation sums
+    assert lib.ptq_activation_abs_sum(p, p, 2, 16, 16, 16, p, big, None) == 3        # f64 X
+    assert lib.ptq_activation_abs_sum(p, p, 1, 16, 12, 16, p, big, None) == 2        # n % 8
+    assert lib.ptq_activation_abs_sum(p, p, 1, 16, 16, 8, p, big, None) == 2         # ldx < n
+    assert lib.ptq_activation_abs_sum(None, p, 1, 16, 16, 16, p, big, None) == 1
+    assert lib.ptq_activation_abs_sum(p, p + 2, 1, 16, 16, 16, p, big, None) == 1    # misaligned X
+    assert lib.ptq_activation_abs_sum(p, p, 1, 16, 16, 16, None, 0, None) == 4
+    assert lib.ptq_activation_abs_sum(p, p, 1, 0, 16, 16, None, 0, None) == 0        # no tokens: no-op
+    assert lib.ptq_activation_scale(p, 0, 16, p, None) == 2                          # tokens must be positive
+    assert lib.ptq_activation_scale(None, 4, 16, p, None) == 1
+    # the sketch:              W  dt ldw  m   n   s  S  lds r  it U  V  sg R  ldr ws  bytes
+    ok = (p, 0, 64, 8, 64, p, p, 64, 2, 2, p, p, p, p + 64, 64, p, big, None)
+    def call(**kw):
+        a = list(ok)
+        names = ["W", "dt", "ldw", "m", "n", "s", "S", "lds", "r", "it", "U", "V", "sg", "R", "ldr", "ws", "bytes"]
+        for k, v in kw.items():
+            a[names.index(k)] = v
+        return lib.ptq_scaled_r1svd(*a)
+    assert call(dt=7) == 3
+    assert call(n=62, ldw=62, ldr=64) == 2           # n % 4
+    assert call(ldr=66) == 2                         # ldr % 4
+    assert call(ldw=32) == 2
+    assert call(lds=32) == 2
+    assert call(n=32772, ldw=32772, ldr=32772, lds=32772) == 2   # more columns than the kernels hold
+    assert call(r=-1) == 1
+    assert call(it=-1) == 1
+    assert call(S=None) == 1
+    assert call(R=p) == 1                            # in place
+    assert call(R=p + 4) == 1                        # misaligned
+    assert call(ws=None, bytes=0) == 4
+    assert call(bytes=1024) == 4

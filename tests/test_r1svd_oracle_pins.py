@@ -218,3 +218,32 @@ def test_forced_codes_replace_single_entries():
     assert not np.array_equal(forced["A"], base["A"])
     none = ro.r1svd(A, S, 2, U_force=np.full((2, 16), -1, dtype=np.int16))
     assert np.array_equal(none["A"], base["A"])
+
+
+def test_follow_adopts_only_legitimate_roundings():
+    rng = np.random.default_rng(26)
+    A = rng.standard_normal((16, 12))
+    S = rng.standard_normal((2, 12))
+    base = ro.r1svd(A, S, 2)
+    exact = ro.r1svd(A, S, 2, rounded=False)
+    # the other neighbour of the entry closest to a tie is adopted with a tolerance above its
+    # margin, and refused with a tolerance below it; a far-off code is never adopted
+    i = int(np.argmin(base["U_margin"][0]))
+    mg = base["U_margin"][0, i]
+    x = exact["U"][0, i]
+    own = base["U"][0, i]
+    q = 2.0 ** (max(np.frexp(abs(x))[1] - 1, -6) - 3)
+    other = own + q if x > own else own - q
+    theirs = {"U_code": base["U_code"].copy(), "V_code": base["V_code"].copy(), "sigma": base["sigma"].copy()}
+    theirs["U_code"][0, i] = ro.e4m3_encode(np.array([other]))[0]
+    yes = ro.r1svd(A, S, 2, follow=theirs, follow_tol=mg * 1.01 + 1e-12)
+    assert yes["followed"] >= 1 and yes["U_code"][0, i] == theirs["U_code"][0, i]
+    no = ro.r1svd(A, S, 2, follow=theirs, follow_tol=mg * 0.5)
+    assert no["U_code"][0, i] == base["U_code"][0, i]
+    far = {k: v.copy() for k, v in theirs.items()}
+    far["U_code"][0, i] = base["U_code"][0, i] ^ 0x20
+    assert ro.r1svd(A, S, 2, follow=far, follow_tol=0.01)["U_code"][0, i] == base["U_code"][0, i]
+    # following one's own results changes nothing
+    same = ro.r1svd(A, S, 2, follow={"U_code": base["U_code"], "V_code": base["V_code"], "sigma": base["sigma"]},
+                    follow_tol=0.01)
+    assert same["followed"] == 0 and np.array_equal(same["A"], base["A"])
