@@ -19,13 +19,12 @@
 namespace ptq {
 namespace {
 
-constexpr int kPassThreads = 1024;
-constexpr int kPassWaves = kPassThreads / kWave;
-constexpr int kColsPerSweep = 4 * kPassThreads;   // a thread owns 4 adjacent columns per sweep
-constexpr int kMaxSweeps = 8;
-constexpr int kReduceCols = 64;                   // columns per workgroup of the partial-vector sum
-constexpr int kReduceGroups = 16;
-constexpr int kMaxNormParts = kMaxSweeps * kColsPerSweep / kReduceCols;   // 512
+constexpr int kComputeUnits = 256;
+constexpr int kMaxColumns = 32768;
+constexpr int kReduceCols = 16;                   // columns per workgroup of the partial-vector sum
+constexpr int kReduceGroups = 64;                 // partial vectors in flight per column
+constexpr int kMaxNormParts = kMaxColumns / kReduceCols;
+static_assert(kReduceCols * 4 == kWave, "the last step of the sum pairs four lanes per column");
 
 // ---- small floating point formats --------------------------------------------------------
 // Nearest value with MANT explicit mantissa bits and smallest normal exponent EMIN, ties to
@@ -130,7 +129,7 @@ __global__ __launch_bounds__(256) void abs_sum_finish_kernel(const double* __res
 // s_j = Xbar_j^2.5 / sqrt(max Xbar * min Xbar) over the channels with Xbar > 0; 1 elsewhere.
 __global__ __launch_bounds__(1024) void scale_kernel(const double* __restrict__ asum, double tokens, int n,
                                                      double* __restrict__ s) {
-  __shared__ double shi[kPassWaves], slo[kPassWaves];
+  __shared__ double shi[16], slo[16];
   double hi = 0.0, lo = __builtin_inf();
   for (int c = threadIdx.x; c < n; c += 1024) {
     const double x = asum[c] / tokens;
@@ -144,7 +143,7 @@ __global__ __launch_bounds__(1024) void scale_kernel(const double* __restrict__ 
   if ((threadIdx.x & 63) == 0) { shi[threadIdx.x >> 6] = hi; slo[threadIdx.x >> 6] = lo; }
   __syncthreads();
   hi = shi[0]; lo = slo[0];
-  for (int w = 1; w < kPassWaves; ++w) { hi = fmax(hi, shi[w]); lo = fmin(lo, slo[w]); }
+  for (int w = 1; w < 16; ++w) { hi = fmax(hi, shi[w]); lo = fmin(lo, slo[w]); }
   const double den = sqrt(hi * lo);
   for (int c = threadIdx.x; c < n; c += 1024) {
     const double x = asum[c] / tokens;
@@ -181,114 +180,152 @@ struct PassArgs {
   const double* rescale;    // power of two applied to vin (null: 1)
   double* u;                // m
   double* unrm2;            // per workgroup: sum of squares of its entries of u
-  double* zpart;            // (number of workgroups) x n
+  double* zpart;            // one partial z per workgroup, see the end of the kernel for the layout
   // deflation by the previous rank's stored triplet, applied to A while it is loaded
   const double* sigma;      // null: none
   const double* ud;         // m
   const double* vd;         // n
 };
 
-template <int NS, int R, bool DEFLATE>
-__global__ __launch_bounds__(kPassThreads) void pass_kernel(PassArgs a) {
+// T threads; a thread owns 4 adjacent columns in each of NS sweeps of 4 T columns; R rows per block.
+template <int T, int NS, int R, bool DEFLATE>
+__global__ __launch_bounds__(T, (T == 512 && NS <= 2) ? 4 : 2) void pass_kernel(PassArgs a) {
+  constexpr int kPassThreads = T, kPassWaves = T / kWave;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int row0 = blockIdx.x * R;
   const int n = a.n;
   __shared__ double red[kPassWaves][R];
   __shared__ double ush[R];
 
-  float w[NS][R][4];
-#pragma unroll
-  for (int s = 0; s < NS; ++s) {
-    const int col = 4 * (tid + kPassThreads * s);
-    double dv[4] = {0.0, 0.0, 0.0, 0.0};
-    if (DEFLATE && col < n) {
-      const double sg = *a.sigma;
-#pragma unroll
-      for (int c = 0; c < 4; ++c) dv[c] = sg * a.vd[col + c];
-    }
-#pragma unroll
-    for (int i = 0; i < R; ++i) {
-      const int row = row0 + i;
-      float4 q = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (col < n && row < a.m) {
-        float4* p = reinterpret_cast<float4*>(a.A + (int64_t)row * n + col);
-        q = *p;
-        if (DEFLATE) {
-          const double ui = a.ud[row];
-          q.x = (float)((double)q.x - ui * dv[0]);
-          q.y = (float)((double)q.y - ui * dv[1]);
-          q.z = (float)((double)q.z - ui * dv[2]);
-          q.w = (float)((double)q.w - ui * dv[3]);
-          *p = q;
-        }
-      }
-      w[s][i][0] = q.x; w[s][i][1] = q.y; w[s][i][2] = q.z; w[s][i][3] = q.w;
-    }
-  }
-
-  // u = A v for the R rows of this workgroup
-  double us[R];
-#pragma unroll
-  for (int i = 0; i < R; ++i) us[i] = 0.0;
-  const double rs = a.rescale ? *a.rescale : 1.0;
-#pragma unroll
-  for (int s = 0; s < NS; ++s) {
-    const int col = 4 * (tid + kPassThreads * s);
-    double v[4] = {0.0, 0.0, 0.0, 0.0};
-    if (col < n) {
-#pragma unroll
-      for (int c = 0; c < 4; ++c) v[c] = (a.vin32 ? (double)a.vin32[col + c] : a.vin[col + c]) * rs;
-    }
-#pragma unroll
-    for (int i = 0; i < R; ++i)
-#pragma unroll
-      for (int c = 0; c < 4; ++c) us[i] = fma((double)w[s][i][c], v[c], us[i]);
-  }
-#pragma unroll
-  for (int i = 0; i < R; ++i) {
-    const double t = wave_sum(us[i]);
-    if (lane == 0) red[wave][i] = t;
-  }
-  __syncthreads();
-  if (tid < R) {
-    double t = 0.0;
-#pragma unroll
-    for (int wv = 0; wv < kPassWaves; ++wv) t += red[wv][tid];
-    ush[tid] = t;
-    if (row0 + tid < a.m) a.u[row0 + tid] = t;
-  }
-  __syncthreads();
-  if (tid == 0) {
-    double t = 0.0;
-#pragma unroll
-    for (int i = 0; i < R; ++i) t = fma(ush[i], ush[i], t);
-    a.unrm2[blockIdx.x] = t;
-  }
-
-  // (the float32 values are what stays in registers between the two products: without this
-  // the compiler keeps their 64 float64 conversions alive instead and spills)
+  double zacc[NS][4];
 #pragma unroll
   for (int s = 0; s < NS; ++s)
 #pragma unroll
-    for (int i = 0; i < R; ++i)
-#pragma unroll
-      for (int c = 0; c < 4; ++c) asm volatile("" : "+v"(w[s][i][c]));
+    for (int c = 0; c < 4; ++c) zacc[s][c] = 0.0;
+  double unrm2 = 0.0;   // thread 0 only
+  const double rs = a.rescale ? *a.rescale : 1.0;
+  const int tiles = (a.m + R - 1) / R;
 
-  // this workgroup's share of z = A^T u
+  // a workgroup walks over row blocks and keeps adding to the same partial z, so that the
+  // number of partial vectors is the number of workgroups, whatever the number of rows
+  for (int tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+    const int row0 = tile * R;
+    // the vectors are re-read (from cache) for every row block: kept in registers across the
+    // loop they would take 8 per sweep and push the block's own data out
+    const double* vin = a.vin;
+    const float* vin32 = a.vin32;
+    const double* vd = a.vd;
+    asm volatile("" : "+s"(vin), "+s"(vin32), "+s"(vd));
+    float w[NS][R][4];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      const int col = 4 * (tid + kPassThreads * s);
+      double dv[4] = {0.0, 0.0, 0.0, 0.0};
+      if (DEFLATE && col < n) {
+        const double sg = *a.sigma;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) dv[c] = sg * vd[col + c];
+      }
+#pragma unroll
+      for (int i = 0; i < R; ++i) {
+        const int row = row0 + i;
+        float4 q = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (col < n && row < a.m) {
+          float4* p = reinterpret_cast<float4*>(a.A + (int64_t)row * n + col);
+          q = *p;
+          if (DEFLATE) {
+            const double ui = a.ud[row];
+            q.x = (float)((double)q.x - ui * dv[0]);
+            q.y = (float)((double)q.y - ui * dv[1]);
+            q.z = (float)((double)q.z - ui * dv[2]);
+            q.w = (float)((double)q.w - ui * dv[3]);
+            *p = q;
+          }
+        }
+        w[s][i][0] = q.x; w[s][i][1] = q.y; w[s][i][2] = q.z; w[s][i][3] = q.w;
+      }
+    }
+
+    // u = A v for the R rows of this block
+    double us[R];
+#pragma unroll
+    for (int i = 0; i < R; ++i) us[i] = 0.0;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      const int col = 4 * (tid + kPassThreads * s);
+      double v[4] = {0.0, 0.0, 0.0, 0.0};
+      if (col < n) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) v[c] = (vin32 ? (double)vin32[col + c] : vin[col + c]) * rs;
+      }
+#pragma unroll
+      for (int i = 0; i < R; ++i)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) us[i] = fma((double)w[s][i][c], v[c], us[i]);
+    }
+    // R sums over the 64 lanes at once: each exchange halves the number of values a lane
+    // carries (the lane keeps the rows its bit selects and hands over the others), so R = 16
+    // takes 8 + 4 + 2 + 1 exchanges and two plain ones instead of 16 x 6
+    {
+      int width = 32;
+#pragma unroll
+      for (int cnt = R; cnt > 1; cnt >>= 1, width >>= 1) {
+        const bool upper = (lane & width) != 0;
+#pragma unroll
+        for (int j = 0; j < cnt / 2; ++j) {
+          const double send = upper ? us[j] : us[j + cnt / 2];
+          const double keep = upper ? us[j + cnt / 2] : us[j];
+          us[j] = keep + __shfl_xor(send, width);
+        }
+      }
+#pragma unroll
+      for (; width >= 1; width >>= 1) us[0] += __shfl_xor(us[0], width);
+      constexpr int kLanesPerRow = kWave / R;
+      if ((lane & (kLanesPerRow - 1)) == 0) red[wave][lane / kLanesPerRow] = us[0];
+    }
+    __syncthreads();
+    if (tid < R) {
+      double t = 0.0;
+#pragma unroll
+      for (int wv = 0; wv < kPassWaves; ++wv) t += red[wv][tid];
+      ush[tid] = t;
+      if (row0 + tid < a.m) a.u[row0 + tid] = t;
+    }
+    __syncthreads();
+    if (tid == 0) {
+#pragma unroll
+      for (int i = 0; i < R; ++i) unrm2 = fma(ush[i], ush[i], unrm2);
+    }
+
+    // (the float32 values are what stays in registers between the two products: without this
+    // the compiler keeps their float64 conversions alive instead and spills)
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+#pragma unroll
+      for (int i = 0; i < R; ++i)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) asm volatile("" : "+v"(w[s][i][c]));
+
+    // this block's share of z = A^T u
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+#pragma unroll
+      for (int i = 0; i < R; ++i) {
+        const double ui = ush[i];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) zacc[s][c] = fma((double)w[s][i][c], ui, zacc[s][c]);
+      }
+  }
+
+  if (tid == 0) a.unrm2[blockIdx.x] = unrm2;
+  // partial vectors are stored in blocks of kReduceCols columns, [column block][workgroup][column],
+  // so that the sum over workgroups reads contiguous memory
 #pragma unroll
   for (int s = 0; s < NS; ++s) {
     const int col = 4 * (tid + kPassThreads * s);
-    double z[4] = {0.0, 0.0, 0.0, 0.0};
-#pragma unroll
-    for (int i = 0; i < R; ++i) {
-      const double ui = ush[i];
-#pragma unroll
-      for (int c = 0; c < 4; ++c) z[c] = fma((double)w[s][i][c], ui, z[c]);
-    }
     if (col < n) {
-      double* o = a.zpart + (int64_t)blockIdx.x * n + col;
-      *reinterpret_cast<double2*>(o) = make_double2(z[0], z[1]);
-      *reinterpret_cast<double2*>(o + 2) = make_double2(z[2], z[3]);
+      double* o = a.zpart + ((int64_t)(col / kReduceCols) * gridDim.x + blockIdx.x) * kReduceCols + col % kReduceCols;
+      *reinterpret_cast<double2*>(o) = make_double2(zacc[s][0], zacc[s][1]);
+      *reinterpret_cast<double2*>(o + 2) = make_double2(zacc[s][2], zacc[s][3]);
     }
   }
 }
@@ -310,18 +347,31 @@ __global__ __launch_bounds__(kReduceCols * kReduceGroups) void reduce_kernel(Red
   const int col = blockIdx.x * kReduceCols + cl;
   __shared__ double red[kReduceGroups][kReduceCols];
   __shared__ bool last;
+  // the block of this workgroup is contiguous: parts x kReduceCols doubles
+  const double* src = a.zpart + (int64_t)blockIdx.x * a.parts * kReduceCols + cl;
   double t = 0.0;
-  if (col < a.n)
-    for (int p = g; p < a.parts; p += kReduceGroups) t += a.zpart[(int64_t)p * a.n + col];
+  for (int p0 = g; p0 < a.parts; p0 += 8 * kReduceGroups) {
+    double x[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {   // all loads first: eight in flight per thread
+      const int p = p0 + j * kReduceGroups;
+      x[j] = p < a.parts ? src[(int64_t)p * kReduceCols] : 0.0;
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) t += x[j];
+  }
   red[g][cl] = t;
   __syncthreads();
-  if (g == 0) {
+  if (threadIdx.x < kWave) {   // the first wave: four lanes per column, sixteen groups each
+    const int quarter = threadIdx.x / kReduceCols;
     double zz = 0.0;
 #pragma unroll
-    for (int k = 0; k < kReduceGroups; ++k) zz += red[k][cl];
-    if (col < a.n) a.z[col] = zz;
-    const double q = wave_sum(col < a.n ? zz * zz : 0.0);
-    if (cl == 0) {
+    for (int k = 0; k < kReduceGroups / 4; ++k) zz += red[quarter * (kReduceGroups / 4) + k][cl];
+    zz += __shfl_xor(zz, 16);
+    zz += __shfl_xor(zz, 32);
+    if (threadIdx.x < kReduceCols && col < a.n) a.z[col] = zz;
+    const double q = wave_sum((threadIdx.x < kReduceCols && col < a.n) ? zz * zz : 0.0);
+    if (threadIdx.x == 0) {
       a.normpart[blockIdx.x] = q;
       __threadfence();
       last = atomicAdd(a.counter, 1u) == gridDim.x - 1;
@@ -405,13 +455,17 @@ __global__ __launch_bounds__(256) void residual_kernel(const float* __restrict__
 
 // ---- host side -----------------------------------------------------------------------------------
 // rows per workgroup by number of column sweeps (registers: 4 * sweeps * rows floats per thread)
-struct PassShape { int ns, rows; };
+// Shape of a pass by number of columns.  The registers of a thread hold 4 * sweeps * rows
+// floats of A plus 4 * sweeps float64 sums.  Up to 4096 columns two workgroups share a compute
+// unit, so that one loads while the other computes; beyond that one workgroup takes all registers.
+struct PassShape { int threads, ns, rows, groups; };
 inline PassShape pass_shape(int64_t n) {
-  const int ns = (int)ceil_div(n, kColsPerSweep);
-  if (ns <= 1) return {1, 16};
-  if (ns == 2) return {2, 8};
-  if (ns <= 4) return {4, 4};
-  return {8, 2};
+  if (n <= 2048) return {512, 1, 16, 2 * kComputeUnits};
+  if (n <= 4096) return {512, 2, 8, 2 * kComputeUnits};
+  if (n <= 8192) return {512, 4, 4, kComputeUnits};
+  if (n <= 12288) return {512, 6, 2, kComputeUnits};
+  if (n <= 16384) return {512, 8, 1, kComputeUnits};
+  return {512, 16, 1, kComputeUnits};
 }
 
 struct Layout {
@@ -421,11 +475,12 @@ struct Layout {
 inline Layout layout(int64_t m, int64_t n) {
   Layout L{};
   const PassShape ps = pass_shape(n);
-  L.parts = (int)ceil_div(m, ps.rows);
+  const int64_t tiles = ceil_div(m, ps.rows);
+  L.parts = (int)(tiles < ps.groups ? tiles : ps.groups);
   size_t o = 0;
   auto take = [&](size_t bytes) { const size_t at = o; o += align_up(bytes, 256); return at; };
   L.A = take((size_t)m * n * sizeof(float));
-  L.zpart = take((size_t)L.parts * n * sizeof(double));
+  L.zpart = take((size_t)ceil_div(n, kReduceCols) * L.parts * kReduceCols * sizeof(double));
   L.z = take((size_t)n * sizeof(double));
   L.u = take((size_t)m * sizeof(double));
   L.unrm2 = take((size_t)L.parts * sizeof(double));
@@ -437,12 +492,12 @@ inline Layout layout(int64_t m, int64_t n) {
   return L;
 }
 
-template <int NS, int R>
+template <int T, int NS, int R>
 void launch_pass(const PassArgs& a, int parts, hipStream_t st) {
   if (a.sigma)
-    pass_kernel<NS, R, true><<<(unsigned)parts, kPassThreads, 0, st>>>(a);
+    pass_kernel<T, NS, R, true><<<(unsigned)parts, T, 0, st>>>(a);
   else
-    pass_kernel<NS, R, false><<<(unsigned)parts, kPassThreads, 0, st>>>(a);
+    pass_kernel<T, NS, R, false><<<(unsigned)parts, T, 0, st>>>(a);
 }
 
 }  // namespace
@@ -469,7 +524,7 @@ ptq_status activation_scale_launch(const double* asum, int64_t tokens, int64_t n
 }
 
 size_t r1svd_workspace_bytes(int64_t m, int64_t n) { return layout(m, n).total; }
-int64_t r1svd_max_columns() { return (int64_t)kMaxSweeps * kColsPerSweep; }
+int64_t r1svd_max_columns() { return kMaxColumns; }
 
 ptq_status r1svd_launch(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m, int64_t n, const double* s,
                         const float* S, int64_t lds, int r, int it, uint8_t* U, uint8_t* V, uint16_t* sigma16,
@@ -502,12 +557,12 @@ ptq_status r1svd_launch(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m, in
     for (int i = 0; i <= it; ++i) {
       PassArgs pa{A, (int)m, (int)n, i == 0 ? S + (int64_t)k * lds : nullptr, z, i == 0 ? nullptr : scal + 1,
                   u, unrm2, zpart, (i == 0 && k > 0) ? scal + 2 : nullptr, ud, vd};
-      switch (ps.ns) {
-        case 1: launch_pass<1, 16>(pa, L.parts, st); break;
-        case 2: launch_pass<2, 8>(pa, L.parts, st); break;
-        case 4: launch_pass<4, 4>(pa, L.parts, st); break;
-        default: launch_pass<8, 2>(pa, L.parts, st); break;
-      }
+      if (ps.ns == 16) launch_pass<512, 16, 1>(pa, L.parts, st);
+      else if (ps.ns == 1) launch_pass<512, 1, 16>(pa, L.parts, st);
+      else if (ps.ns == 2) launch_pass<512, 2, 8>(pa, L.parts, st);
+      else if (ps.ns == 4) launch_pass<512, 4, 4>(pa, L.parts, st);
+      else if (ps.ns == 6) launch_pass<512, 6, 2>(pa, L.parts, st);
+      else launch_pass<512, 8, 1>(pa, L.parts, st);
       ReduceArgs ra{zpart, L.parts, (int)n, z, normpart, scal, scal + 1, counter};
       reduce_kernel<<<reduce_grid, kReduceCols * kReduceGroups, 0, st>>>(ra);
     }
