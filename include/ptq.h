@@ -263,8 +263,9 @@ ptq_status ptq_activation_scale(const double* asum, int64_t tokens, int64_t n, d
  * what is stored.  If y or p is zero the rank stores zeros.
  *
  * W      m x n, PTQ_F32 / PTQ_BF16 / PTQ_F64, ldw >= n.      s  n float64, all entries nonzero.
- * S      r x n float32 with leading dimension lds >= n: the random vector of each rank
- *        (the caller draws them; standard normal in the paper's prototype).
+ * S      r x n float32 with leading dimension lds >= n, lds % 4 == 0, 16-byte aligned: the
+ *        random vector of each rank (the caller draws them; standard normal in the paper's
+ *        prototype).
  * U, V   r x m and r x n bytes, dense: OCP e4m3 codes (bias 7, no infinities), conversion
  *        rounds to nearest, ties to even.      sigma  r IEEE binary16 bit patterns.
  * R      m x n float32 output, ldr >= n, ldr % 4 == 0, 16-byte aligned.  May not alias W.

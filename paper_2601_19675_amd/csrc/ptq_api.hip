@@ -183,7 +183,8 @@ ptq_status ptq_scaled_r1svd(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m
     return PTQ_ERR_SHAPE;
   if (r < 0 || r > 1024 || it < 0 || it > 1024) return PTQ_ERR_ARG;
   if (!W || !s || !R || misaligned(R, 16) || static_cast<const void*>(R) == W) return PTQ_ERR_ARG;
-  if (r > 0 && (!S || !U || !V || !sigma)) return PTQ_ERR_ARG;
+  if (r > 0 && (!S || !U || !V || !sigma || misaligned(S, 16))) return PTQ_ERR_ARG;
+  if (lds % 4 != 0) return PTQ_ERR_SHAPE;
   if (ws_bad(ws, ws_bytes, r1svd_workspace_bytes(m, n))) return PTQ_ERR_WORKSPACE;
   return r1svd_launch(W, wdt, ldw, m, n, s, S, lds, r, it, U, V, sigma, R, ldr, ws,
                       static_cast<hipStream_t>(stream));

@@ -11,15 +11,23 @@
 // every sum has a fixed order (results are reproducible), and the chain is bound by the rate
 // at which A (float32, rewritten once per rank by the deflation) streams from memory.
 //
-// Arithmetic: A is stored in float32; every product and sum is float64.  Vectors grow by
-// sigma_1^2 per application; they are rescaled by a power of two (exact) taken from the norm
-// of the previous result, so the printed formula is evaluated as it stands.
+// Arithmetic: A and the vector v of an application are float32, and so are the products and
+// the short sums a thread forms from its own 4 * sweeps columns (for u) or its R rows (for z);
+// everything that is added across threads, workgroups or row blocks is float64, as are the
+// norms and the values that get rounded to e4m3 / fp16.  That keeps the noise at the level the
+// float32 storage of A sets anyway.  Vectors grow by sigma_1^2 per application; v is z times a
+// power of two (exact) taken from the size of z, so the printed formula is evaluated as it stands.
 #include "common.h"
+
+#include <climits>
+#include <cstdlib>
+#include <cstring>
 
 namespace ptq {
 namespace {
 
 constexpr int kComputeUnits = 256;
+constexpr int kChainThreads = 512;
 constexpr int kMaxColumns = 32768;
 constexpr int kReduceCols = 16;                   // columns per workgroup of the partial-vector sum
 constexpr int kReduceGroups = 64;                 // partial vectors in flight per column
@@ -71,6 +79,37 @@ __device__ __forceinline__ double wave_sum(double v) {
 #pragma unroll
   for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
   return v;
+}
+
+// Loads and stores that are coherent across the whole device without cache maintenance: the
+// workgroups of one launch use them for everything they hand to each other (each compute die
+// has an L2 of its own; an ordinary store may sit there, an ordinary load may find an old line).
+__device__ __forceinline__ double load_dev(const double* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void store_dev(double* p, double v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float load_dev(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void store_dev(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// four adjacent floats, 16-byte aligned, as two 8-byte accesses
+__device__ __forceinline__ float4 load_dev4(const float* p) {
+  const unsigned long long* q = reinterpret_cast<const unsigned long long*>(p);
+  const unsigned long long a = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  const unsigned long long b = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return make_float4(__uint_as_float((unsigned)a), __uint_as_float((unsigned)(a >> 32)),
+                     __uint_as_float((unsigned)b), __uint_as_float((unsigned)(b >> 32)));
+}
+__device__ __forceinline__ void store_dev4(float* p, float x, float y, float z, float w) {
+  unsigned long long* q = reinterpret_cast<unsigned long long*>(p);
+  __hip_atomic_store(q, (unsigned long long)__float_as_uint(x) | ((unsigned long long)__float_as_uint(y) << 32),
+                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store(q + 1, (unsigned long long)__float_as_uint(z) | ((unsigned long long)__float_as_uint(w) << 32),
+                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // ---- activation magnitude and scale (Algorithm 1) ------------------------------------------
@@ -175,65 +214,49 @@ __global__ __launch_bounds__(256) void scale_weight_kernel(const void* __restric
 struct PassArgs {
   float* A;                 // m x n, leading dimension n
   int m, n;
-  const float* vin32;       // first application of a rank: the sketch vector ...
-  const double* vin;        // ... afterwards the previous z
+  const float* vin;         // the sketch vector (first application of a rank) or the previous z
   const double* rescale;    // power of two applied to vin (null: 1)
   double* u;                // m
   double* unrm2;            // per workgroup: sum of squares of its entries of u
-  double* zpart;            // one partial z per workgroup, see the end of the kernel for the layout
+  float* zpart;             // one partial z per workgroup, see store_partial for the layout
   // deflation by the previous rank's stored triplet, applied to A while it is loaded
   const double* sigma;      // null: none
   const double* ud;         // m
   const double* vd;         // n
 };
 
-// T threads; a thread owns 4 adjacent columns in each of NS sweeps of 4 T columns; R rows per block.
-template <int T, int NS, int R, bool DEFLATE>
-__global__ __launch_bounds__(T, (T == 512 && NS <= 2) ? 4 : 2) void pass_kernel(PassArgs a) {
-  constexpr int kPassThreads = T, kPassWaves = T / kWave;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int n = a.n;
-  __shared__ double red[kPassWaves][R];
-  __shared__ double ush[R];
+// A block of R rows of A in the registers of a workgroup of T threads: a thread owns 4 adjacent
+// columns in each of NS sweeps of 4 T columns.
+// COH: the vectors come from other workgroups of the same launch (see load_dev).
+template <int T, int NS, int R, bool COH = false>
+struct RowBlock {
+  float w[NS][R][4];
 
-  double zacc[NS][4];
-#pragma unroll
-  for (int s = 0; s < NS; ++s)
-#pragma unroll
-    for (int c = 0; c < 4; ++c) zacc[s][c] = 0.0;
-  double unrm2 = 0.0;   // thread 0 only
-  const double rs = a.rescale ? *a.rescale : 1.0;
-  const int tiles = (a.m + R - 1) / R;
+  static __device__ __forceinline__ double vec(const double* p) { return COH ? load_dev(p) : *p; }
 
-  // a workgroup walks over row blocks and keeps adding to the same partial z, so that the
-  // number of partial vectors is the number of workgroups, whatever the number of rows
-  for (int tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
-    const int row0 = tile * R;
-    // the vectors are re-read (from cache) for every row block: kept in registers across the
-    // loop they would take 8 per sweep and push the block's own data out
-    const double* vin = a.vin;
-    const float* vin32 = a.vin32;
-    const double* vd = a.vd;
-    asm volatile("" : "+s"(vin), "+s"(vin32), "+s"(vd));
-    float w[NS][R][4];
+  // Loads rows row0 .. row0+R-1 (zeros outside the matrix).  With `deflate` the previous rank's
+  // stored triplet (sg, ud, vd) is subtracted on the way (float64 arithmetic, one rounding to
+  // float32) and the result is stored back.
+  __device__ __forceinline__ void load(float* A, int m, int n, int row0, bool deflate, double sg, const double* ud,
+                                       const double* vd) {
+    const int tid = threadIdx.x;
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
-      const int col = 4 * (tid + kPassThreads * s);
+      const int col = 4 * (tid + T * s);
       double dv[4] = {0.0, 0.0, 0.0, 0.0};
-      if (DEFLATE && col < n) {
-        const double sg = *a.sigma;
+      if (deflate && col < n) {
 #pragma unroll
-        for (int c = 0; c < 4; ++c) dv[c] = sg * vd[col + c];
+        for (int c = 0; c < 4; ++c) dv[c] = sg * vec(vd + col + c);
       }
 #pragma unroll
       for (int i = 0; i < R; ++i) {
         const int row = row0 + i;
         float4 q = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (col < n && row < a.m) {
-          float4* p = reinterpret_cast<float4*>(a.A + (int64_t)row * n + col);
+        if (col < n && row < m) {
+          float4* p = reinterpret_cast<float4*>(A + (int64_t)row * n + col);
           q = *p;
-          if (DEFLATE) {
-            const double ui = a.ud[row];
+          if (deflate) {
+            const double ui = vec(ud + row);
             q.x = (float)((double)q.x - ui * dv[0]);
             q.y = (float)((double)q.y - ui * dv[1]);
             q.z = (float)((double)q.z - ui * dv[2]);
@@ -244,98 +267,172 @@ __global__ __launch_bounds__(T, (T == 512 && NS <= 2) ? 4 : 2) void pass_kernel(
         w[s][i][0] = q.x; w[s][i][1] = q.y; w[s][i][2] = q.z; w[s][i][3] = q.w;
       }
     }
+  }
 
-    // u = A v for the R rows of this block
-    double us[R];
-#pragma unroll
-    for (int i = 0; i < R; ++i) us[i] = 0.0;
+  // The same subtraction on a block that is already in registers.
+  __device__ __forceinline__ void deflate(int m, int n, int row0, double sg, const double* ud, const double* vd) {
+    const int tid = threadIdx.x;
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
-      const int col = 4 * (tid + kPassThreads * s);
-      double v[4] = {0.0, 0.0, 0.0, 0.0};
-      if (col < n) {
+      const int col = 4 * (tid + T * s);
+      if (col >= n) continue;
+      double dv[4];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) v[c] = (vin32 ? (double)vin32[col + c] : vin[col + c]) * rs;
+      for (int c = 0; c < 4; ++c) dv[c] = sg * vec(vd + col + c);
+#pragma unroll
+      for (int i = 0; i < R; ++i) {
+        if (row0 + i >= m) continue;
+        const double ui = vec(ud + row0 + i);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) w[s][i][c] = (float)((double)w[s][i][c] - ui * dv[c]);
       }
+    }
+  }
+
+  __device__ __forceinline__ void store(float* A, int m, int n, int row0) const {
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      const int col = 4 * (tid + T * s);
 #pragma unroll
       for (int i = 0; i < R; ++i)
-#pragma unroll
-        for (int c = 0; c < 4; ++c) us[i] = fma((double)w[s][i][c], v[c], us[i]);
+        if (col < n && row0 + i < m)
+          *reinterpret_cast<float4*>(A + (int64_t)(row0 + i) * n + col) =
+              make_float4(w[s][i][0], w[s][i][1], w[s][i][2], w[s][i][3]);
     }
-    // R sums over the 64 lanes at once: each exchange halves the number of values a lane
-    // carries (the lane keeps the rows its bit selects and hands over the others), so R = 16
-    // takes 8 + 4 + 2 + 1 exchanges and two plain ones instead of 16 x 6
-    {
+  }
+
+  // u = (block) v for the R rows, left in ush[0..R) (and in u_out, if not null); then
+  // zacc += (block)^T u.  v is vin times the power of two rs.
+  // Returns the sum of squares of the R entries of u (valid in thread 0).
+  // red: T/64 x R doubles, ush: R doubles of LDS.  Contains two workgroup barriers.
+  __device__ __forceinline__ double apply(const float* vin, float rs, int m, int n, int row0, double* u_out,
+                                          double (&zacc)[NS][4], double* red, double* ush) {
+    constexpr int kWaves = T / kWave;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    float us[R];
+#pragma unroll
+    for (int i = 0; i < R; ++i) us[i] = 0.f;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      const int col = 4 * (tid + T * s);
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (col < n) v = COH ? load_dev4(vin + col) : *reinterpret_cast<const float4*>(vin + col);
+      v.x *= rs; v.y *= rs; v.z *= rs; v.w *= rs;
+#pragma unroll
+      for (int i = 0; i < R; ++i)
+        us[i] = fmaf(w[s][i][3], v.w, fmaf(w[s][i][2], v.z, fmaf(w[s][i][1], v.y, fmaf(w[s][i][0], v.x, us[i]))));
+    }
+    // rows in chunks of at most 8: C float64 sums over the 64 lanes at once.  Each exchange
+    // halves the number of values a lane carries (the lane keeps the rows its bit selects and
+    // hands over the others), so C = 8 takes 4 + 2 + 1 exchanges and three plain ones instead
+    // of 8 x 6
+    constexpr int C = R < 8 ? R : 8;
+#pragma unroll
+    for (int h = 0; h < R / C; ++h) {
+      double ud[C];
+#pragma unroll
+      for (int i = 0; i < C; ++i) ud[i] = (double)us[h * C + i];
       int width = 32;
 #pragma unroll
-      for (int cnt = R; cnt > 1; cnt >>= 1, width >>= 1) {
+      for (int cnt = C; cnt > 1; cnt >>= 1, width >>= 1) {
         const bool upper = (lane & width) != 0;
 #pragma unroll
         for (int j = 0; j < cnt / 2; ++j) {
-          const double send = upper ? us[j] : us[j + cnt / 2];
-          const double keep = upper ? us[j + cnt / 2] : us[j];
-          us[j] = keep + __shfl_xor(send, width);
+          const double send = upper ? ud[j] : ud[j + cnt / 2];
+          const double keep = upper ? ud[j + cnt / 2] : ud[j];
+          ud[j] = keep + __shfl_xor(send, width);
         }
       }
 #pragma unroll
-      for (; width >= 1; width >>= 1) us[0] += __shfl_xor(us[0], width);
-      constexpr int kLanesPerRow = kWave / R;
-      if ((lane & (kLanesPerRow - 1)) == 0) red[wave][lane / kLanesPerRow] = us[0];
+      for (; width >= 1; width >>= 1) ud[0] += __shfl_xor(ud[0], width);
+      constexpr int kLanesPerRow = kWave / C;
+      if ((lane & (kLanesPerRow - 1)) == 0) red[wave * R + h * C + lane / kLanesPerRow] = ud[0];
     }
     __syncthreads();
     if (tid < R) {
       double t = 0.0;
 #pragma unroll
-      for (int wv = 0; wv < kPassWaves; ++wv) t += red[wv][tid];
+      for (int wv = 0; wv < kWaves; ++wv) t += red[wv * R + tid];
       ush[tid] = t;
-      if (row0 + tid < a.m) a.u[row0 + tid] = t;
+      if (u_out && row0 + tid < m) u_out[row0 + tid] = t;
     }
     __syncthreads();
+    double nrm2 = 0.0;
     if (tid == 0) {
 #pragma unroll
-      for (int i = 0; i < R; ++i) unrm2 = fma(ush[i], ush[i], unrm2);
+      for (int i = 0; i < R; ++i) nrm2 = fma(ush[i], ush[i], nrm2);
     }
-
-    // (the float32 values are what stays in registers between the two products: without this
-    // the compiler keeps their float64 conversions alive instead and spills)
+    float uf[R];
 #pragma unroll
-    for (int s = 0; s < NS; ++s)
+    for (int i = 0; i < R; ++i) uf[i] = (float)ush[i];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      float zt[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int i = 0; i < R; ++i)
 #pragma unroll
-        for (int c = 0; c < 4; ++c) asm volatile("" : "+v"(w[s][i][c]));
-
-    // this block's share of z = A^T u
+        for (int c = 0; c < 4; ++c) zt[c] = fmaf(w[s][i][c], uf[i], zt[c]);
 #pragma unroll
-    for (int s = 0; s < NS; ++s)
-#pragma unroll
-      for (int i = 0; i < R; ++i) {
-        const double ui = ush[i];
-#pragma unroll
-        for (int c = 0; c < 4; ++c) zacc[s][c] = fma((double)w[s][i][c], ui, zacc[s][c]);
-      }
+      for (int c = 0; c < 4; ++c) zacc[s][c] += (double)zt[c];
+    }
+    return nrm2;
   }
+};
 
-  if (tid == 0) a.unrm2[blockIdx.x] = unrm2;
-  // partial vectors are stored in blocks of kReduceCols columns, [column block][workgroup][column],
-  // so that the sum over workgroups reads contiguous memory
+// Partial vectors are stored as float32 in blocks of kReduceCols columns, [column block][workgroup]
+// [column], so that the sum over workgroups reads contiguous memory.
+template <int T, int NS, bool COH = false>
+__device__ __forceinline__ void store_partial(const double (&zacc)[NS][4], float* zpart, int n, int part,
+                                              int parts) {
 #pragma unroll
   for (int s = 0; s < NS; ++s) {
-    const int col = 4 * (tid + kPassThreads * s);
+    const int col = 4 * ((int)threadIdx.x + T * s);
     if (col < n) {
-      double* o = a.zpart + ((int64_t)(col / kReduceCols) * gridDim.x + blockIdx.x) * kReduceCols + col % kReduceCols;
-      *reinterpret_cast<double2*>(o) = make_double2(zacc[s][0], zacc[s][1]);
-      *reinterpret_cast<double2*>(o + 2) = make_double2(zacc[s][2], zacc[s][3]);
+      float* o = zpart + ((int64_t)(col / kReduceCols) * parts + part) * kReduceCols + col % kReduceCols;
+      const float x = (float)zacc[s][0], y = (float)zacc[s][1], z = (float)zacc[s][2], w = (float)zacc[s][3];
+      if (COH) store_dev4(o, x, y, z, w);
+      else *reinterpret_cast<float4*>(o) = make_float4(x, y, z, w);
     }
   }
+}
+
+template <int T, int NS, int R, bool DEFLATE>
+__global__ __launch_bounds__(T) void pass_kernel(PassArgs a) {
+  __shared__ double red[T / kWave * R];
+  __shared__ double ush[R];
+  double zacc[NS][4];
+#pragma unroll
+  for (int s = 0; s < NS; ++s)
+#pragma unroll
+    for (int c = 0; c < 4; ++c) zacc[s][c] = 0.0;
+  double unrm2 = 0.0;   // thread 0 only
+  const float rs = a.rescale ? (float)*a.rescale : 1.f;
+  const int tiles = (a.m + R - 1) / R;
+
+  // a workgroup walks over row blocks and keeps adding to the same partial z, so that the
+  // number of partial vectors is the number of workgroups, whatever the number of rows
+  for (int tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+    // the vectors are re-read (from cache) for every row block: kept in registers across the
+    // loop they would take 8 per sweep and push the block's own data out
+    const float* vin = a.vin;
+    const double* vd = a.vd;
+    asm volatile("" : "+s"(vin), "+s"(vd));
+    RowBlock<T, NS, R> blk;
+    blk.load(a.A, a.m, a.n, tile * R, DEFLATE, DEFLATE ? *a.sigma : 0.0, a.ud, vd);
+    unrm2 += blk.apply(vin, rs, a.m, a.n, tile * R, a.u, zacc, red, ush);
+  }
+  if (threadIdx.x == 0) a.unrm2[blockIdx.x] = unrm2;
+  store_partial<T, NS>(zacc, a.zpart, a.n, blockIdx.x, gridDim.x);
 }
 
 // z = sum of the partial vectors, in a fixed order; the workgroup that finishes last adds up
 // the squared norm and derives the power of two that brings z back to unit magnitude.
 struct ReduceArgs {
-  const double* zpart;
+  const float* zpart;
   int parts, n;
-  double* z;
+  double* z;             // the sum ...
+  float* z32;            // ... and the same rounded to float32, the next application's input
   double* normpart;      // one entry per workgroup
   double* nrm2;          // out: ||z||^2
   double* rescale;       // out: 2^-ilogb(||z||)
@@ -347,18 +444,18 @@ __global__ __launch_bounds__(kReduceCols * kReduceGroups) void reduce_kernel(Red
   const int col = blockIdx.x * kReduceCols + cl;
   __shared__ double red[kReduceGroups][kReduceCols];
   __shared__ bool last;
-  // the block of this workgroup is contiguous: parts x kReduceCols doubles
-  const double* src = a.zpart + (int64_t)blockIdx.x * a.parts * kReduceCols + cl;
+  // the block of this workgroup is contiguous: parts x kReduceCols floats
+  const float* src = a.zpart + (int64_t)blockIdx.x * a.parts * kReduceCols + cl;
   double t = 0.0;
   for (int p0 = g; p0 < a.parts; p0 += 8 * kReduceGroups) {
-    double x[8];
+    float x[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {   // all loads first: eight in flight per thread
       const int p = p0 + j * kReduceGroups;
-      x[j] = p < a.parts ? src[(int64_t)p * kReduceCols] : 0.0;
+      x[j] = p < a.parts ? src[(int64_t)p * kReduceCols] : 0.f;
     }
 #pragma unroll
-    for (int j = 0; j < 8; ++j) t += x[j];
+    for (int j = 0; j < 8; ++j) t += (double)x[j];
   }
   red[g][cl] = t;
   __syncthreads();
@@ -369,7 +466,7 @@ __global__ __launch_bounds__(kReduceCols * kReduceGroups) void reduce_kernel(Red
     for (int k = 0; k < kReduceGroups / 4; ++k) zz += red[quarter * (kReduceGroups / 4) + k][cl];
     zz += __shfl_xor(zz, 16);
     zz += __shfl_xor(zz, 32);
-    if (threadIdx.x < kReduceCols && col < a.n) a.z[col] = zz;
+    if (threadIdx.x < kReduceCols && col < a.n) { a.z[col] = zz; a.z32[col] = (float)zz; }
     const double q = wave_sum((threadIdx.x < kReduceCols && col < a.n) ? zz * zz : 0.0);
     if (threadIdx.x == 0) {
       a.normpart[blockIdx.x] = q;
@@ -387,7 +484,9 @@ __global__ __launch_bounds__(kReduceCols * kReduceGroups) void reduce_kernel(Red
     if (threadIdx.x == 0) {
       *a.nrm2 = q;
       const double nz = sqrt(q);
-      *a.rescale = (nz > 0.0 && nz < __builtin_inf()) ? scalbn(1.0, -ilogb(nz)) : 1.0;
+      int e = (nz > 0.0 && nz < __builtin_inf()) ? ilogb(nz) : 0;
+      e = e > 126 ? 126 : (e < -126 ? -126 : e);   // v = z * 2^-e is formed in float32
+      *a.rescale = scalbn(1.0, -e);
       *a.counter = 0u;
     }
   }
@@ -430,6 +529,222 @@ __global__ __launch_bounds__(256) void finish_kernel(FinishArgs a) {
   }
 }
 
+// ---- the whole loop in one launch ------------------------------------------------------------
+// All ranks and applications in one cooperative launch: the workgroups meet at a barrier
+// between the steps that the separate kernels above end with.  If every row block has a
+// workgroup of its own, the block never leaves the registers: A is then read once and written
+// once, and the loop runs at the speed of the barriers and the partial-vector exchange.
+//
+// The barrier is a counter in global memory that only grows.  A waiting workgroup gives up
+// after spin_limit polls and raises `abort`, which makes every later wait return at once: the
+// kernel always terminates, and the caller finds NaN in every sigma.
+struct ChainArgs {
+  float* A; int m, n;
+  const float* S; int64_t lds; int r, it;
+  uint8_t* U; uint8_t* V; uint16_t* sigma16;
+  float* zpart; double* z; float* z32; double* u; double* unrm2; double* normpart; double* ud; double* vd;
+  double* sigma;        // the last rank's decoded sigma, for the residual kernel
+  int* expo;            // r * (it + 1) entries preset to INT_MIN: largest exponent in each z
+  unsigned* bar;        // kBarrierWords words preset to 0
+  int* abort;           // preset to 0
+  unsigned spin_limit;
+};
+
+// Barrier state: one arrival counter per group of 16 workgroups, one for the groups, and one
+// release word per group, each in a 128-byte line of its own.
+constexpr int kBarrierGroup = 16;
+constexpr int kBarrierLine = 32;   // words
+constexpr int kBarrierWords = (2 * (kComputeUnits / kBarrierGroup) + 1) * kBarrierLine;
+
+__global__ void chain_init_kernel(int* expo, int count, unsigned* bar, int* abort) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < count) expo[i] = INT_MIN;
+  if (i < kBarrierWords) bar[i] = 0u;
+  if (i == 0) *abort = 0;
+}
+
+// What the workgroups exchange goes through load_dev / store_dev, so the barrier needs no cache
+// write-back or invalidation (a device-wide fence walks the whole L2 and, issued by every
+// workgroup at every barrier, costs more than the loop's arithmetic): every wave waits for its
+// own stores to be acknowledged, the workgroup meets, and one thread counts it as arrived.
+// Arrivals are counted in two levels, because read-modify-writes of ONE word are served one
+// after the other and 256 of them take longer than everything else in an application: the last
+// of a group of 16 reports for the group, the last group releases all groups.  All words only
+// grow; `phase` is the number of this barrier, counted from 1.
+__device__ __forceinline__ void grid_barrier(unsigned* bar, unsigned phase, int* abort, unsigned spin_limit) {
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int G = gridDim.x, g = blockIdx.x / kBarrierGroup;
+    const int groups = (G + kBarrierGroup - 1) / kBarrierGroup;
+    const int members = G - g * kBarrierGroup < kBarrierGroup ? G - g * kBarrierGroup : kBarrierGroup;
+    unsigned* top = bar + (kComputeUnits / kBarrierGroup) * kBarrierLine;
+    unsigned* release = top + kBarrierLine;
+    if (atomicAdd(bar + g * kBarrierLine, 1u) + 1u == (unsigned)members * phase)
+      if (atomicAdd(top, 1u) + 1u == (unsigned)groups * phase)
+        for (int j = 0; j < groups; ++j)
+          __hip_atomic_store(release + j * kBarrierLine, phase, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    unsigned spins = 0;
+    while (__hip_atomic_load(release + g * kBarrierLine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < phase) {
+      if ((spins & 255u) == 0 && __hip_atomic_load(abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) break;
+      if (++spins > spin_limit) {
+        __hip_atomic_store(abort, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        break;
+      }
+      __builtin_amdgcn_s_sleep(1);
+    }
+  }
+  __syncthreads();
+}
+
+// Sum of ptr[0..count) over the workgroup in a fixed order; the same value in every thread.
+template <int T>
+__device__ __forceinline__ double block_sum(const double* ptr, int count, double* scratch) {
+  double t = 0.0;
+  for (int j = threadIdx.x; j < count; j += T) t += load_dev(ptr + j);
+  t = wave_sum(t);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = t;
+  __syncthreads();
+  double total = 0.0;
+#pragma unroll
+  for (int wv = 0; wv < T / kWave; ++wv) total += scratch[wv];
+  return total;
+}
+
+// RESIDENT: every row block has a workgroup of its own (number of blocks <= grid size) and stays
+// in that workgroup's registers from the first application to the last.
+template <int NS, int R, bool RESIDENT>
+__global__ __launch_bounds__(kChainThreads) void chain_kernel(ChainArgs a) {
+  constexpr int T = kChainThreads;
+  constexpr int kGroups = T / kReduceCols;   // 32 partial vectors in flight per column
+  __shared__ double red[T / kWave * R];
+  __shared__ double ush[R];
+  __shared__ double sred[kGroups][kReduceCols];
+  __shared__ double fin[T / kWave];
+  const int tid = threadIdx.x, b = blockIdx.x, G = gridDim.x;
+  const int m = a.m, n = a.n;
+  const int tiles = (m + R - 1) / R;
+  const int ncb = (n + kReduceCols - 1) / kReduceCols;
+  unsigned phase = 0;
+  int app = 0;
+  double sg_prev = 0.0;
+  RowBlock<T, NS, R, true> own;
+  if (RESIDENT) own.load(a.A, m, n, b * R, false, 0.0, a.ud, a.vd);   // all zeros for b >= tiles
+
+  for (int k = 0; k < a.r; ++k) {
+    for (int i = 0; i <= a.it; ++i, ++app) {
+      double zacc[NS][4];
+#pragma unroll
+      for (int s = 0; s < NS; ++s)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) zacc[s][c] = 0.0;
+      double unrm2 = 0.0;
+      float rs = 1.f;
+      if (i > 0) {
+        int e = __hip_atomic_load(a.expo + app - 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        e = e == INT_MIN ? 0 : (e > 126 ? 126 : (e < -126 ? -126 : e));
+        rs = scalbnf(1.f, -e);
+      }
+      // the sketch vector is read like z (the same load instructions; it never changes)
+      const float* v_in = i == 0 ? a.S + (int64_t)k * a.lds : a.z32;
+      if constexpr (RESIDENT) {
+        if (b < tiles) {
+          if (i == 0 && k > 0) own.deflate(m, n, b * R, sg_prev, a.ud, a.vd);
+          unrm2 = own.apply(v_in, rs, m, n, b * R, a.u, zacc, red, ush);
+        }
+      } else {
+        for (int tile = b; tile < tiles; tile += G) {
+          const float* vin = v_in;
+          const double* vd = a.vd;
+          asm volatile("" : "+s"(vin), "+s"(vd));
+          RowBlock<T, NS, R, true> blk;
+          blk.load(a.A, m, n, tile * R, i == 0 && k > 0, sg_prev, a.ud, vd);
+          unrm2 += blk.apply(vin, rs, m, n, tile * R, a.u, zacc, red, ush);
+        }
+      }
+      store_partial<T, NS, true>(zacc, a.zpart, n, b, G);
+      if (tid == 0) store_dev(a.unrm2 + b, unrm2);
+      grid_barrier(a.bar, ++phase, a.abort, a.spin_limit);
+
+      // this workgroup's column blocks of z = sum of the partial vectors
+      const bool last_app = i == a.it;
+      for (int cb = b; cb < ncb; cb += G) {
+        const int cl = tid & (kReduceCols - 1), g = tid / kReduceCols;
+        const int col = cb * kReduceCols + cl;
+        const float* src = a.zpart + (int64_t)cb * G * kReduceCols + cl;
+        double t = 0.0;
+        for (int p0 = g; p0 < G; p0 += 8 * kGroups) {
+          float x[8];
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            const int p = p0 + j * kGroups;
+            x[j] = p < G ? load_dev(src + (int64_t)p * kReduceCols) : 0.f;
+          }
+#pragma unroll
+          for (int j = 0; j < 8; ++j) t += (double)x[j];
+        }
+        sred[g][cl] = t;
+        __syncthreads();
+        if (tid < kWave) {
+          const int quarter = tid / kReduceCols;
+          double zz = 0.0;
+#pragma unroll
+          for (int q = 0; q < kGroups / 4; ++q) zz += sred[quarter * (kGroups / 4) + q][cl];
+          zz += __shfl_xor(zz, 16);
+          zz += __shfl_xor(zz, 32);
+          const bool mine = tid < kReduceCols && col < n;
+          if (mine) {
+            store_dev(a.z32 + col, (float)zz);
+            a.z[col] = zz;   // read back by this workgroup only
+          }
+          if (!last_app) {
+            int e = (mine && zz != 0.0 && fabs(zz) < __builtin_inf()) ? ilogb(zz) : INT_MIN;
+#pragma unroll
+            for (int o = 32; o >= 1; o >>= 1) e = max(e, __shfl_xor(e, o));
+            if (tid == 0 && e != INT_MIN) atomicMax(a.expo + app, e);
+          } else {
+            const double q2 = wave_sum(mine ? zz * zz : 0.0);
+            if (tid == 0) store_dev(a.normpart + cb, q2);
+          }
+        }
+        __syncthreads();
+      }
+      grid_barrier(a.bar, ++phase, a.abort, a.spin_limit);
+    }
+
+    // the stored triplet of rank k: every workgroup derives the same norms and sigma, and
+    // encodes the entries of U and V it produced itself
+    const double ny = sqrt(block_sum<T>(a.unrm2, G, fin));
+    const double np = sqrt(block_sum<T>(a.normpart, ncb, fin));
+    const bool dead = !(ny > 0.0) || !(np > 0.0);
+    const uint16_t h = dead ? 0 : fp16_encode_pos(np / ny);
+    sg_prev = fp16_decode_pos(h);
+    if (b == 0 && tid == 0) { a.sigma16[k] = h; *a.sigma = sg_prev; }
+    for (int tile = b; tile < tiles; tile += G) {
+      const int row = tile * R + tid;
+      if (tid < R && row < m) {
+        const uint8_t c = dead ? 0 : e4m3_encode(a.u[row] / ny);
+        a.U[(int64_t)k * m + row] = c;
+        store_dev(a.ud + row, e4m3_decode(c));
+      }
+    }
+    for (int cb = b; cb < ncb; cb += G) {
+      const int col = cb * kReduceCols + tid;
+      if (tid < kReduceCols && col < n) {
+        const uint8_t c = dead ? 0 : e4m3_encode(a.z[col] / np);
+        a.V[(int64_t)k * n + col] = c;
+        store_dev(a.vd + col, e4m3_decode(c));
+      }
+    }
+    grid_barrier(a.bar, ++phase, a.abort, a.spin_limit);
+  }
+
+  if (RESIDENT && b < tiles) own.store(a.A, m, n, b * R);
+  if (b == 0 && __hip_atomic_load(a.abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)
+    for (int k = tid; k < a.r; k += T) a.sigma16[k] = 0x7e00;
+}
+
 // R = (A - sigma u v^T) diag(s)^-1: the last rank's deflation and the way back from the scaled
 // matrix (Algorithm 1).
 __global__ __launch_bounds__(256) void residual_kernel(const float* __restrict__ A, int m, int n,
@@ -455,49 +770,89 @@ __global__ __launch_bounds__(256) void residual_kernel(const float* __restrict__
 
 // ---- host side -----------------------------------------------------------------------------------
 // rows per workgroup by number of column sweeps (registers: 4 * sweeps * rows floats per thread)
-// Shape of a pass by number of columns.  The registers of a thread hold 4 * sweeps * rows
-// floats of A plus 4 * sweeps float64 sums.  Up to 4096 columns two workgroups share a compute
-// unit, so that one loads while the other computes; beyond that one workgroup takes all registers.
-struct PassShape { int threads, ns, rows, groups; };
+// Shape of a pass by number of columns: 512 threads and one workgroup per compute unit, which
+// gives a thread 256 registers; they hold 4 * sweeps * rows floats of A, 4 * sweeps float64
+// sums of z and `rows` float64 sums of u.
+constexpr int kPassThreads = 512;
+struct PassShape { int ns, rows; };
 inline PassShape pass_shape(int64_t n) {
-  if (n <= 2048) return {512, 1, 16, 2 * kComputeUnits};
-  if (n <= 4096) return {512, 2, 8, 2 * kComputeUnits};
-  if (n <= 8192) return {512, 4, 4, kComputeUnits};
-  if (n <= 12288) return {512, 6, 2, kComputeUnits};
-  if (n <= 16384) return {512, 8, 1, kComputeUnits};
-  return {512, 16, 1, kComputeUnits};
+  if (n <= 2048) return {1, 16};
+  if (n <= 4096) return {2, 16};
+  if (n <= 8192) return {4, 8};
+  if (n <= 12288) return {6, 4};
+  if (n <= 16384) return {8, 2};
+  return {16, 1};
 }
 
+constexpr int kMaxChainApps = 16384;   // applications (rank x iteration) one cooperative launch can hold
+
 struct Layout {
-  size_t A, zpart, z, u, unrm2, normpart, ud, vd, scalars, total;
-  int parts;
+  size_t A, zpart, z, z32, u, unrm2, normpart, ud, vd, scalars, barrier, expo, total;
+  int parts;    // workgroups of a pass when every step is a launch of its own
+  int groups;   // workgroups of the single cooperative launch
 };
 inline Layout layout(int64_t m, int64_t n) {
   Layout L{};
   const PassShape ps = pass_shape(n);
   const int64_t tiles = ceil_div(m, ps.rows);
-  L.parts = (int)(tiles < ps.groups ? tiles : ps.groups);
+  L.parts = (int)(tiles < kComputeUnits ? tiles : kComputeUnits);
+  const int64_t want = tiles > ceil_div(n, kReduceCols) ? tiles : ceil_div(n, kReduceCols);
+  L.groups = (int)(want < kComputeUnits ? want : kComputeUnits);
   size_t o = 0;
   auto take = [&](size_t bytes) { const size_t at = o; o += align_up(bytes, 256); return at; };
   L.A = take((size_t)m * n * sizeof(float));
-  L.zpart = take((size_t)ceil_div(n, kReduceCols) * L.parts * kReduceCols * sizeof(double));
+  L.zpart = take((size_t)ceil_div(n, kReduceCols) * L.groups * kReduceCols * sizeof(float));
   L.z = take((size_t)n * sizeof(double));
+  L.z32 = take((size_t)n * sizeof(float));
   L.u = take((size_t)m * sizeof(double));
-  L.unrm2 = take((size_t)L.parts * sizeof(double));
+  L.unrm2 = take((size_t)L.groups * sizeof(double));
   L.normpart = take((size_t)kMaxNormParts * sizeof(double));
   L.ud = take((size_t)m * sizeof(double));
   L.vd = take((size_t)n * sizeof(double));
   L.scalars = take(256);
+  L.barrier = take((size_t)kBarrierWords * sizeof(unsigned));
+  L.expo = take((size_t)kMaxChainApps * sizeof(int));
   L.total = o;
   return L;
 }
 
-template <int T, int NS, int R>
+template <int NS, int R>
 void launch_pass(const PassArgs& a, int parts, hipStream_t st) {
   if (a.sigma)
-    pass_kernel<T, NS, R, true><<<(unsigned)parts, T, 0, st>>>(a);
+    pass_kernel<kPassThreads, NS, R, true><<<(unsigned)parts, kPassThreads, 0, st>>>(a);
   else
-    pass_kernel<T, NS, R, false><<<(unsigned)parts, T, 0, st>>>(a);
+    pass_kernel<kPassThreads, NS, R, false><<<(unsigned)parts, kPassThreads, 0, st>>>(a);
+}
+
+// Whether `groups` workgroups of the chain kernel can be resident at once on the current device.
+template <int NS, int R, bool RESIDENT>
+bool chain_fits(int groups) {
+  int dev = 0, coop = 0, cus = 0, per_cu = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return false;
+  if (hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev) != hipSuccess || !coop) return false;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return false;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, chain_kernel<NS, R, RESIDENT>, kChainThreads, 0) !=
+      hipSuccess)
+    return false;
+  return (int64_t)per_cu * cus >= groups;
+}
+
+template <int NS, int R, bool RESIDENT>
+bool launch_chain_as(ChainArgs& a, int groups, hipStream_t st) {
+  if (!chain_fits<NS, R, RESIDENT>(groups)) return false;
+  void* params[] = {&a};
+  if (hipLaunchCooperativeKernel(reinterpret_cast<const void*>(chain_kernel<NS, R, RESIDENT>),
+                                 dim3((unsigned)groups), dim3(kChainThreads), params, 0, st) != hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  return true;
+}
+
+template <int NS, int R>
+bool launch_chain(ChainArgs& a, int groups, hipStream_t st) {
+  return ceil_div(a.m, R) <= groups ? launch_chain_as<NS, R, true>(a, groups, st)
+                                    : launch_chain_as<NS, R, false>(a, groups, st);
 }
 
 }  // namespace
@@ -533,8 +888,9 @@ ptq_status r1svd_launch(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m, in
   const PassShape ps = pass_shape(n);
   char* base = static_cast<char*>(ws);
   float* A = reinterpret_cast<float*>(base + L.A);
-  double* zpart = reinterpret_cast<double*>(base + L.zpart);
+  float* zpart = reinterpret_cast<float*>(base + L.zpart);
   double* z = reinterpret_cast<double*>(base + L.z);
+  float* z32 = reinterpret_cast<float*>(base + L.z32);
   double* u = reinterpret_cast<double*>(base + L.u);
   double* unrm2 = reinterpret_cast<double*>(base + L.unrm2);
   double* normpart = reinterpret_cast<double*>(base + L.normpart);
@@ -552,18 +908,44 @@ ptq_status r1svd_launch(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m, in
     default: return PTQ_ERR_DTYPE;
   }
 
+  // One cooperative launch for the whole loop where the device can hold it; PTQ_R1SVD_LAUNCH=steps
+  // in the environment selects the launch-per-step form (same arithmetic, for comparison).
+  const char* mode = std::getenv("PTQ_R1SVD_LAUNCH");
+  bool chained = false;
+  if (r > 0 && (int64_t)r * (it + 1) <= kMaxChainApps && !(mode && std::strcmp(mode, "steps") == 0)) {
+    int* expo = reinterpret_cast<int*>(base + L.expo);
+    int* abort_flag = reinterpret_cast<int*>(counter + 1);
+    const int apps = r * (it + 1);
+    unsigned* bar = reinterpret_cast<unsigned*>(base + L.barrier);
+    const int init = apps > kBarrierWords ? apps : kBarrierWords;
+    chain_init_kernel<<<(unsigned)ceil_div(init, 256), 256, 0, st>>>(expo, apps, bar, abort_flag);
+    ChainArgs ca{A, (int)m, (int)n, S, lds, r, it, U, V, sigma16, zpart, z, z32, u, unrm2, normpart, ud, vd,
+                 scal + 2, expo, bar, abort_flag, 1u << 21};
+    switch (ps.ns) {
+      case 1: chained = launch_chain<1, 16>(ca, L.groups, st); break;
+      case 2: chained = launch_chain<2, 16>(ca, L.groups, st); break;
+      case 4: chained = launch_chain<4, 8>(ca, L.groups, st); break;
+      case 6: chained = launch_chain<6, 4>(ca, L.groups, st); break;
+      case 8: chained = launch_chain<8, 2>(ca, L.groups, st); break;
+      default: chained = launch_chain<16, 1>(ca, L.groups, st); break;
+    }
+    if (!chained) clear_counter_kernel<<<1, kWave, 0, st>>>(counter);
+  }
+
   const unsigned reduce_grid = (unsigned)ceil_div(n, kReduceCols);
-  for (int k = 0; k < r; ++k) {
+  for (int k = 0; k < r && !chained; ++k) {
     for (int i = 0; i <= it; ++i) {
-      PassArgs pa{A, (int)m, (int)n, i == 0 ? S + (int64_t)k * lds : nullptr, z, i == 0 ? nullptr : scal + 1,
+      PassArgs pa{A, (int)m, (int)n, i == 0 ? S + (int64_t)k * lds : z32, i == 0 ? nullptr : scal + 1,
                   u, unrm2, zpart, (i == 0 && k > 0) ? scal + 2 : nullptr, ud, vd};
-      if (ps.ns == 16) launch_pass<512, 16, 1>(pa, L.parts, st);
-      else if (ps.ns == 1) launch_pass<512, 1, 16>(pa, L.parts, st);
-      else if (ps.ns == 2) launch_pass<512, 2, 8>(pa, L.parts, st);
-      else if (ps.ns == 4) launch_pass<512, 4, 4>(pa, L.parts, st);
-      else if (ps.ns == 6) launch_pass<512, 6, 2>(pa, L.parts, st);
-      else launch_pass<512, 8, 1>(pa, L.parts, st);
-      ReduceArgs ra{zpart, L.parts, (int)n, z, normpart, scal, scal + 1, counter};
+      switch (ps.ns) {
+        case 1: launch_pass<1, 16>(pa, L.parts, st); break;
+        case 2: launch_pass<2, 16>(pa, L.parts, st); break;
+        case 4: launch_pass<4, 8>(pa, L.parts, st); break;
+        case 6: launch_pass<6, 4>(pa, L.parts, st); break;
+        case 8: launch_pass<8, 2>(pa, L.parts, st); break;
+        default: launch_pass<16, 1>(pa, L.parts, st); break;
+      }
+      ReduceArgs ra{zpart, L.parts, (int)n, z, z32, normpart, scal, scal + 1, counter};
       reduce_kernel<<<reduce_grid, kReduceCols * kReduceGroups, 0, st>>>(ra);
     }
     FinishArgs fa{u, unrm2, L.parts, (int)m, z, scal, (int)n, U + (int64_t)k * m, V + (int64_t)k * n,

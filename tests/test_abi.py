@@ -128,6 +128,8 @@ def test_low_rank_step_argument_errors_are_reported_on_the_host(lib):
     assert call(ldr=66) == 2                         # ldr % 4
     assert call(ldw=32) == 2
     assert call(lds=32) == 2
+    assert call(lds=66) == 2                         # lds % 4
+    assert call(S=p + 4) == 1                        # misaligned sketch vectors
     assert call(n=32772, ldw=32772, ldr=32772, lds=32772) == 2   # more columns than the kernels hold
     assert call(r=-1) == 1
     assert call(it=-1) == 1

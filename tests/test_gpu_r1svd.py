@@ -24,6 +24,17 @@ pytestmark = pytest.mark.gpu
 FOLLOW_TOL = 2e-3
 
 
+@pytest.fixture(params=["single", "steps"])
+def launch_mode(request, monkeypatch):
+    """The loop runs as one cooperative launch (default) or as one launch per step; the library
+    reads PTQ_R1SVD_LAUNCH at every call.  Both forms are held to the oracle."""
+    if request.param == "steps":
+        monkeypatch.setenv("PTQ_R1SVD_LAUNCH", "steps")
+    else:
+        monkeypatch.delenv("PTQ_R1SVD_LAUNCH", raising=False)
+    return request.param
+
+
 def _dev(a, dtype=None):
     t = torch.from_numpy(np.ascontiguousarray(a)).cuda()
     return t if dtype is None else t.to(dtype)
@@ -74,8 +85,9 @@ def _case(m, n, dtype, layer_id, r, seed_s=0):
     ("f32", 21, 8200, 2, 1),      # four-sweep shape
     ("bf16", 7, 16400, 2, 1),     # eight-sweep shape
     ("f32", 16, 64, 5, 0),        # no power iteration
+    ("bf16", 4100, 256, 2, 2),    # more row blocks than workgroups: blocks are streamed, not resident
 ])
-def test_r1svd_matches_oracle(dtype, m, n, r, it):
+def test_r1svd_matches_oracle(dtype, m, n, r, it, launch_mode):
     Ws, W64, s, S = _case(m, n, dtype, 900 + n, r)
     got = _run_gpu(to_device(Ws), s, S, it)
     ref = _check(W64, s, S, it, got)
@@ -101,7 +113,7 @@ def test_r1svd_float64_weight_and_strided_views():
                           Rbig[:, :n].cpu().numpy().astype(np.float64)))
 
 
-def test_r1svd_is_reproducible_and_rank_zero_is_identity():
+def test_r1svd_is_reproducible_and_rank_zero_is_identity(launch_mode):
     Ws, W64, s, S = _case(130, 1024, "bf16", 960, 4)
     a = _run_gpu(to_device(Ws), s, S, 4)
     b = _run_gpu(to_device(Ws), s, S, 4)
@@ -112,7 +124,7 @@ def test_r1svd_is_reproducible_and_rank_zero_is_identity():
     assert np.allclose(none[3], W64, rtol=3 * 2.0 ** -24, atol=0)
 
 
-def test_r1svd_zero_matrix_stores_zeros():
+def test_r1svd_zero_matrix_stores_zeros(launch_mode):
     m, n, r = 20, 256, 2
     S = np.random.default_rng(1).standard_normal((r, n)).astype(np.float32)
     got = _run_gpu(torch.zeros((m, n), dtype=torch.float32, device="cuda"), np.ones(n), S, 2)
