@@ -97,13 +97,6 @@ __device__ __forceinline__ void store_dev(float* p, float v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 // four adjacent floats, 16-byte aligned, as two 8-byte accesses
-__device__ __forceinline__ float4 load_dev4(const float* p) {
-  const unsigned long long* q = reinterpret_cast<const unsigned long long*>(p);
-  const unsigned long long a = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  const unsigned long long b = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  return make_float4(__uint_as_float((unsigned)a), __uint_as_float((unsigned)(a >> 32)),
-                     __uint_as_float((unsigned)b), __uint_as_float((unsigned)(b >> 32)));
-}
 __device__ __forceinline__ void store_dev4(float* p, float x, float y, float z, float w) {
   unsigned long long* q = reinterpret_cast<unsigned long long*>(p);
   __hip_atomic_store(q, (unsigned long long)__float_as_uint(x) | ((unsigned long long)__float_as_uint(y) << 32),
@@ -317,7 +310,7 @@ struct RowBlock {
     for (int s = 0; s < NS; ++s) {
       const int col = 4 * (tid + T * s);
       float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (col < n) v = COH ? load_dev4(vin + col) : *reinterpret_cast<const float4*>(vin + col);
+      if (col < n) v = *reinterpret_cast<const float4*>(vin + col);
       v.x *= rs; v.y *= rs; v.z *= rs; v.w *= rs;
 #pragma unroll
       for (int i = 0; i < R; ++i)
@@ -542,7 +535,9 @@ struct ChainArgs {
   float* A; int m, n;
   const float* S; int64_t lds; int r, it;
   uint8_t* U; uint8_t* V; uint16_t* sigma16;
-  float* zpart; double* z; float* z32; double* u; double* unrm2; double* normpart; double* ud; double* vd;
+  float* zpart; double* z; double* u; double* unrm2; double* normpart; double* ud; double* vd;
+  float* zapp;          // one float32 copy of z per application, zstride floats apart
+  int64_t zstride;
   double* sigma;        // the last rank's decoded sigma, for the residual kernel
   int* expo;            // r * (it + 1) entries preset to INT_MIN: largest exponent in each z
   unsigned* bar;        // kBarrierWords words preset to 0
@@ -646,8 +641,11 @@ __global__ __launch_bounds__(kChainThreads) void chain_kernel(ChainArgs a) {
         e = e == INT_MIN ? 0 : (e > 126 ? 126 : (e < -126 ? -126 : e));
         rs = scalbnf(1.f, -e);
       }
-      // the sketch vector is read like z (the same load instructions; it never changes)
-      const float* v_in = i == 0 ? a.S + (int64_t)k * a.lds : a.z32;
+      // Every workgroup reads all of v.  Coherent loads of the same few lines from 256 places
+      // are served one after the other by the memory side; ordinary loads are served by the L2
+      // of each die after its first miss, and they are safe here because each application's z
+      // has an address of its own that no cache can hold an older copy of.
+      const float* v_in = i == 0 ? a.S + (int64_t)k * a.lds : a.zapp + (int64_t)(app - 1) * a.zstride;
       if constexpr (RESIDENT) {
         if (b < tiles) {
           if (i == 0 && k > 0) own.deflate(m, n, b * R, sg_prev, a.ud, a.vd);
@@ -695,7 +693,7 @@ __global__ __launch_bounds__(kChainThreads) void chain_kernel(ChainArgs a) {
           zz += __shfl_xor(zz, 32);
           const bool mine = tid < kReduceCols && col < n;
           if (mine) {
-            store_dev(a.z32 + col, (float)zz);
+            store_dev(a.zapp + (int64_t)app * a.zstride + col, (float)zz);
             a.z[col] = zz;   // read back by this workgroup only
           }
           if (!last_app) {
@@ -785,9 +783,10 @@ inline PassShape pass_shape(int64_t n) {
 }
 
 constexpr int kMaxChainApps = 16384;   // applications (rank x iteration) one cooperative launch can hold
+constexpr size_t kChainVectorBytes = size_t{16} << 20;   // room for their float32 copies of z
 
 struct Layout {
-  size_t A, zpart, z, z32, u, unrm2, normpart, ud, vd, scalars, barrier, expo, total;
+  size_t A, zpart, z, z32, u, unrm2, normpart, ud, vd, scalars, barrier, expo, zapp, total;
   int parts;    // workgroups of a pass when every step is a launch of its own
   int groups;   // workgroups of the single cooperative launch
 };
@@ -812,6 +811,7 @@ inline Layout layout(int64_t m, int64_t n) {
   L.scalars = take(256);
   L.barrier = take((size_t)kBarrierWords * sizeof(unsigned));
   L.expo = take((size_t)kMaxChainApps * sizeof(int));
+  L.zapp = take(kChainVectorBytes);
   L.total = o;
   return L;
 }
@@ -912,15 +912,18 @@ ptq_status r1svd_launch(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m, in
   // in the environment selects the launch-per-step form (same arithmetic, for comparison).
   const char* mode = std::getenv("PTQ_R1SVD_LAUNCH");
   bool chained = false;
-  if (r > 0 && (int64_t)r * (it + 1) <= kMaxChainApps && !(mode && std::strcmp(mode, "steps") == 0)) {
+  const int64_t zstride = (int64_t)align_up((size_t)n * sizeof(float), 256) / (int64_t)sizeof(float);
+  if (r > 0 && (int64_t)r * (it + 1) <= kMaxChainApps &&
+      (size_t)r * (it + 1) * zstride * sizeof(float) <= kChainVectorBytes &&
+      !(mode && std::strcmp(mode, "steps") == 0)) {
     int* expo = reinterpret_cast<int*>(base + L.expo);
     int* abort_flag = reinterpret_cast<int*>(counter + 1);
     const int apps = r * (it + 1);
     unsigned* bar = reinterpret_cast<unsigned*>(base + L.barrier);
     const int init = apps > kBarrierWords ? apps : kBarrierWords;
     chain_init_kernel<<<(unsigned)ceil_div(init, 256), 256, 0, st>>>(expo, apps, bar, abort_flag);
-    ChainArgs ca{A, (int)m, (int)n, S, lds, r, it, U, V, sigma16, zpart, z, z32, u, unrm2, normpart, ud, vd,
-                 scal + 2, expo, bar, abort_flag, 1u << 21};
+    ChainArgs ca{A, (int)m, (int)n, S, lds, r, it, U, V, sigma16, zpart, z, u, unrm2, normpart, ud, vd,
+                 reinterpret_cast<float*>(base + L.zapp), zstride, scal + 2, expo, bar, abort_flag, 1u << 21};
     switch (ps.ns) {
       case 1: chained = launch_chain<1, 16>(ca, L.groups, st); break;
       case 2: chained = launch_chain<2, 16>(ca, L.groups, st); break;
