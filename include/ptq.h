@@ -267,7 +267,9 @@ ptq_status ptq_activation_scale(const double* asum, int64_t tokens, int64_t n, d
  *        random vector of each rank (the caller draws them; standard normal in the paper's
  *        prototype).
  * U, V   r x m and r x n bytes, dense: OCP e4m3 codes (bias 7, no infinities), conversion
- *        rounds to nearest, ties to even.      sigma  r IEEE binary16 bit patterns.
+ *        rounds to nearest, ties to even.      sigma  r IEEE binary16 bit patterns; a value
+ *        beyond the format's range is stored as 65504 (the deflation then removes part of
+ *        that direction and later ranks find the rest).
  * R      m x n float32 output, ldr >= n, ldr % 4 == 0, 16-byte aligned.  May not alias W.
  * r, it  rank and number of power iterations (the paper uses 16 and 8); r = 0 gives R = W.
  * n % 4 == 0 and n <= 32768.

@@ -30,6 +30,10 @@ Readings (the text leaves these open):
   * Scaling y between the products would change nothing (U_1, V_1 and sigma are ratios);
     the oracle applies the printed formula as it stands.
   * If y or p is the zero vector the step stores U_1 = V_1 = 0 and sigma = 0.
+  * sigma can exceed the fp16 range (65504) when the activation scale is large; an IEEE
+    conversion would store infinity and destroy the matrix at the deflation.  The conversion
+    saturates at 65504: the deflation then removes only part of that direction and the next
+    ranks find the rest, which is the compensation mechanism the paper relies on anyway.
   * A channel that is never active (Xbar_j = 0) would make the printed scale 0/0 or
     divide by zero for every channel: max and min run over the positive entries and such
     a channel gets s_j = 1.
@@ -111,8 +115,12 @@ def e4m3_decode(code: np.ndarray) -> np.ndarray:
     return np.where(c & 0x80, -mag, mag)
 
 
+FP16_MAX = 65504.0
+
+
 def fp16_round(x: float) -> float:
-    return float(np.float16(x))
+    """Nearest fp16 value, ties to even; beyond the format's range the largest finite value."""
+    return float(np.float16(min(x, FP16_MAX)))
 
 
 def _quantum(x: np.ndarray, min_exp: int, mant_bits: int) -> np.ndarray:

@@ -63,10 +63,10 @@ __device__ __forceinline__ double e4m3_decode(uint8_t c) {
   const double mag = ef == 0 ? scalbn((double)mt, -9) : scalbn((double)(8 + mt), ef - 10);
   return (c & 0x80) ? -mag : mag;
 }
-// IEEE binary16 bits of a non-negative double (overflow gives infinity).
+// IEEE binary16 bits of a non-negative double; saturates at the largest finite value, 65504.
 __device__ __forceinline__ uint16_t fp16_encode_pos(double a) {
   if (!(a == a)) return 0x7e00;
-  if (a >= 65520.0) return 0x7c00;
+  if (a >= 65504.0) return 0x7bff;
   return (uint16_t)small_float_code<10, -14>(a);
 }
 __device__ __forceinline__ double fp16_decode_pos(uint16_t h) {

@@ -247,3 +247,19 @@ def test_follow_adopts_only_legitimate_roundings():
     same = ro.r1svd(A, S, 2, follow={"U_code": base["U_code"], "V_code": base["V_code"], "sigma": base["sigma"]},
                     follow_tol=0.01)
     assert same["followed"] == 0 and np.array_equal(same["A"], base["A"])
+
+
+def test_sigma_beyond_fp16_saturates_and_later_ranks_take_the_rest():
+    # a rank-one matrix with singular value 150000 > 65504: three ranks of (about) 65504,
+    # 65504 and the remainder rebuild it; an infinite sigma would have left NaN everywhere
+    rng = np.random.default_rng(27)
+    a = rng.standard_normal(24); a /= np.linalg.norm(a)
+    b = rng.standard_normal(20); b /= np.linalg.norm(b)
+    A = 150000.0 * np.outer(a, b)
+    out = ro.r1svd(A, rng.standard_normal((4, 20)), 2)
+    assert out["sigma"][0] == 65504.0 and np.all(np.isfinite(out["A"]))
+    # the e4m3 factors are a little short of unit norm, so the first two ranks remove a little less
+    assert out["sigma"][1] == 65504.0 and 0 < out["sigma"][2] < 65504.0
+    assert np.linalg.norm(out["A"]) < 0.02 * 150000.0
+    assert ro.fp16_round(65519.9) == 65504.0 and ro.fp16_round(1e9) == 65504.0
+    assert ro.fp16_round(65503.0) == float(np.float16(65503.0))
