@@ -103,6 +103,57 @@ def lopro_timings(ptq, W, H, m, n, ws, b_I=256, b_H=256, reps=10):
     return out
 
 
+def r1svd_timings(ptq, W, X, m, n, t, rank=16, it=8, reps=5):
+    """The low-rank step that precedes the solve in LoPRo: per-channel activation magnitude over all of X
+    (memory-bound, one read of X), the scale, and the scaled rank-one sketching loop in the paper's setting
+    (rank 16, 8 power iterations: 16 x 9 applications of "u = A v, z = A^T u" to the float32 matrix)."""
+    import torch
+    from paper_2601_19675_amd import binding
+    dev = "cuda"
+    asum = torch.zeros(n, dtype=torch.float64, device=dev)
+    s = torch.empty(n, dtype=torch.float64, device=dev)
+    g = torch.Generator(device=dev)
+    g.manual_seed(19675)
+    S = torch.randn((rank, n), generator=g, device=dev, dtype=torch.float32)
+    U = torch.empty((rank, m), dtype=torch.uint8, device=dev)
+    V = torch.empty((rank, n), dtype=torch.uint8, device=dev)
+    sg = torch.empty(rank, dtype=torch.float16, device=dev)
+    R = torch.empty((m, n), dtype=torch.float32, device=dev)
+    ws = torch.empty(max(ptq.ptq_workspace_bytes(binding.OP_ACTIVATION_ABS_SUM, 0, n),
+                         ptq.ptq_workspace_bytes(binding.OP_SCALED_R1SVD, m, n)), dtype=torch.uint8, device=dev)
+
+    def timed(f):
+        f()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            f()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    def magnitude():
+        asum.zero_()
+        ptq.ptq_activation_abs_sum(asum, X, ws)
+        ptq.ptq_activation_scale(asum, t, s)
+
+    a_ms = timed(magnitude)
+    r_ms = timed(lambda: ptq.ptq_scaled_r1svd(W, s, S, it, U, V, sg, R, ws))
+    apps = rank * (it + 1)
+    xbytes = float(t) * n * X.element_size()
+    return {
+        "rank": rank, "iterations": it,
+        "activation_scale": {"ms": a_ms, "algorithmic_GBps": xbytes / a_ms / 1e6,
+                             "frac_of_hbm_peak": xbytes / a_ms / 1e6 / HBM_GBPS},
+        "sketch": {"ms": r_ms, "applications": apps, "us_per_application": 1e3 * r_ms / apps,
+                   "matrix_bytes_f32": 4.0 * m * n,
+                   # what a pass-per-product implementation would stream: (2 it + 2) reads of A per rank
+                   "equivalent_GBps_of_unfused_gemvs": rank * (2 * it + 2) * 4.0 * m * n / r_ms / 1e6},
+        "sigma_first": [float(x) for x in sg[:4].float().cpu()],
+        "total_ms": a_ms + r_ms,
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -114,6 +165,9 @@ def main():
     ap.add_argument("--lopro", action="store_true",
                     help="also time LoPRo's pre-conditioning of the same layer (column order, rotation of W and H, "
                          "way back; b_I = b_H = 256) and report it under \"lopro\"; the step itself is unchanged")
+    ap.add_argument("--r1svd", action="store_true",
+                    help="also time the low-rank step on the same layer (activation scale from X, then the scaled "
+                         "rank-one sketch with rank 16 and 8 iterations) and report it under \"r1svd\"")
     ap.add_argument("--device-x", action="store_true",
                     help="draw the activations on the GPU (same distribution family, torch generator) instead of "
                          "the seeded host generator: for timing the widest layers, whose host generation takes minutes")
@@ -245,6 +299,8 @@ def main():
     }
     if args.lopro:
         result["lopro"] = lopro_timings(ptq, W, H, m, n, ws)
+    if args.r1svd:
+        result["r1svd"] = r1svd_timings(ptq, W, X, m, n, t)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, spec, cfg.seed)
     print(json.dumps(result))
