@@ -54,7 +54,8 @@ typedef enum {
   PTQ_OP_LOPRO_ORDER = 4,
   PTQ_OP_LOPRO_ROTATE_HESSIAN = 5,
   PTQ_OP_ACTIVATION_ABS_SUM = 6,
-  PTQ_OP_SCALED_R1SVD = 7
+  PTQ_OP_SCALED_R1SVD = 7,
+  PTQ_OP_LINEAR_FORWARD = 8 /* t = tokens, block = rank r */
 } ptq_op;
 
 typedef void* ptq_stream; /* hipStream_t */
@@ -282,6 +283,60 @@ ptq_status ptq_scaled_r1svd(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m
                             const double* s, const float* S, int64_t lds, int r, int it, uint8_t* U,
                             uint8_t* V, uint16_t* sigma, float* R, int64_t ldr, void* ws,
                             size_t ws_bytes, ptq_stream stream);
+
+/* ---------------------------------------------------------------------------
+ * What is stored for a layer and the form it is applied in (Algorithm 1, last lines: the
+ * quantized residual, U, Sigma, V, the scale vector and the permutation; Sec. 3.4, Eq. 12:
+ * its size; Sec. 3.2, Eq. 7 and the time-complexity appendix: its use).
+ * ------------------------------------------------------------------------- */
+
+/*
+ * Eq. 12, host arithmetic only: average bits per weight of an m x n layer quantized to d_q
+ * bits with one d_o-bit scale per group of g columns, rank-r factors in d_r bits, the scale
+ * vector, the permutation and Sigma:
+ *   d_q + d_o/g + r d_r/n + r d_r/m + 2 d_o/n + r d_o/(m n).     Returns -1 on bad arguments.
+ */
+double ptq_average_bits(int64_t m, int64_t n, double d_q, double d_o, int64_t g, int64_t r, double d_r);
+
+/*
+ * Bit packing.  Code j of a row occupies bits [j bits, (j+1) bits) of the row's bit stream,
+ * stored in little-endian 32-bit words, rows dense: packed is m x (n bits / 32) words.
+ * codes m x n bytes (values < 2^bits; higher bits are ignored), ldc >= n, ldc % 16 == 0,
+ * 16-byte aligned.  bits in {2, 3, 4, 8}; n % 32 == 0.
+ */
+ptq_status ptq_pack_codes(const uint8_t* codes, int64_t ldc, int64_t m, int64_t n, int bits,
+                          uint32_t* packed, ptq_stream stream);
+
+/*
+ * The inverse with dequantization:  Wq[i][j] = scale[i][j/group] * (code[i][j] - zero[i][j/group])
+ * in float64 (exact: a float32 times a small integer), the value ptq_quantize_layer wrote.
+ * scales m x n/group float32, zeros m x n/group bytes, Wq m x n float64, ldq >= n.
+ */
+ptq_status ptq_unpack_dequantize(const uint32_t* packed, int64_t m, int64_t n, int bits,
+                                 const float* scales, const uint8_t* zeros, int group, double* Wq,
+                                 int64_t ldq, ptq_stream stream);
+
+/*
+ * The stored layer applied to a few tokens (Eq. 7, rows = tokens):
+ *     X~ = X P Q,      O = X~ Dequant(packed)^T + ((X diag(s)^-1) V^T diag(sigma)) U.
+ * The residual stays in the rotated basis it was quantized in; the input is permuted and
+ * rotated once (same perm, b_I, b_H and their restrictions as the rotation calls above).
+ *
+ * X      tokens x n, PTQ_F32 / PTQ_BF16 / PTQ_F64, ldx >= n.       O  tokens x m float32, ldo >= m.
+ * packed, scales, zeros, bits, group: as above; group % 32 == 0.
+ * U, V   r x m and r x n e4m3 codes, sigma r fp16 bit patterns, s n float64: the output of
+ *        ptq_scaled_r1svd; r = 0 applies the residual alone (U, V, sigma, s may be NULL).
+ * X~ and the low-rank coefficients are formed in float64 and rounded to float32; the products
+ * with the codes accumulate in float32.  tokens <= 4096 (meant for a handful: the call reads
+ * the packed codes once per four tokens).
+ * Workspace: PTQ_OP_LINEAR_FORWARD with t = tokens and block = r.
+ */
+ptq_status ptq_lopro_linear_forward(const void* X, ptq_dtype xdt, int64_t ldx, int64_t tokens, int64_t m,
+                                    int64_t n, const uint32_t* packed, int bits, const float* scales,
+                                    const uint8_t* zeros, int group, const int32_t* perm, int b_I,
+                                    int b_H, const uint8_t* U, const uint8_t* V, const uint16_t* sigma,
+                                    int r, const double* s, float* O, int64_t ldo, void* ws,
+                                    size_t ws_bytes, ptq_stream stream);
 
 #ifdef __cplusplus
 }

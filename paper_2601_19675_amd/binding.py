@@ -16,7 +16,7 @@ import torch
 PTQ_F32, PTQ_BF16, PTQ_F64 = 0, 1, 2
 OP_HESSIAN, OP_CHOLESKY_INV, OP_QUANTIZE, OP_LAYER_ERROR = 0, 1, 2, 3
 OP_LOPRO_ORDER, OP_LOPRO_ROTATE_HESSIAN = 4, 5
-OP_ACTIVATION_ABS_SUM, OP_SCALED_R1SVD = 6, 7
+OP_ACTIVATION_ABS_SUM, OP_SCALED_R1SVD, OP_LINEAR_FORWARD = 6, 7, 8
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
@@ -69,6 +69,15 @@ def load_library() -> ctypes.CDLL:
     lib.ptq_activation_abs_sum.argtypes = [vp, vp, c.c_int, i64, i64, i64, vp, sz, vp]
     lib.ptq_activation_scale.restype = c.c_int
     lib.ptq_activation_scale.argtypes = [vp, i64, i64, vp, vp]
+    lib.ptq_average_bits.restype = c.c_double
+    lib.ptq_average_bits.argtypes = [i64, i64, c.c_double, c.c_double, i64, i64, c.c_double]
+    lib.ptq_pack_codes.restype = c.c_int
+    lib.ptq_pack_codes.argtypes = [vp, i64, i64, i64, c.c_int, vp, vp]
+    lib.ptq_unpack_dequantize.restype = c.c_int
+    lib.ptq_unpack_dequantize.argtypes = [vp, i64, i64, c.c_int, vp, vp, c.c_int, vp, i64, vp]
+    lib.ptq_lopro_linear_forward.restype = c.c_int
+    lib.ptq_lopro_linear_forward.argtypes = [vp, c.c_int, i64, i64, i64, i64, vp, c.c_int, vp, vp, c.c_int, vp,
+                                             c.c_int, c.c_int, vp, vp, vp, c.c_int, vp, vp, i64, vp, sz, vp]
     lib.ptq_scaled_r1svd.restype = c.c_int
     lib.ptq_scaled_r1svd.argtypes = [vp, c.c_int, i64, i64, i64, vp, vp, i64, c.c_int, c.c_int, vp, vp, vp, vp,
                                      i64, vp, sz, vp]
@@ -283,3 +292,63 @@ def ptq_scaled_r1svd(W: torch.Tensor, s: torch.Tensor, S: torch.Tensor, it: int,
                                          ws.data_ptr(), ws.numel(), _stream())
     if rc:
         raise PtqError(rc, "ptq_scaled_r1svd")
+
+
+def ptq_average_bits(m: int, n: int, d_q: float, d_o: float, g: int, r: int, d_r: float) -> float:
+    """Eq. 12: average bits per weight of a stored layer (host arithmetic)."""
+    return float(load_library().ptq_average_bits(m, n, d_q, d_o, g, r, d_r))
+
+
+def ptq_pack_codes(codes: torch.Tensor, bits: int, packed: torch.Tensor) -> None:
+    """packed (int32 m x n*bits/32) <- bit stream of codes (uint8 m x n)."""
+    _check_dev(codes, packed)
+    m, n = codes.shape
+    assert codes.dtype == torch.uint8 and codes.stride(1) == 1
+    assert packed.dtype == torch.int32 and packed.is_contiguous() and packed.shape == (m, n * bits // 32)
+    rc = load_library().ptq_pack_codes(codes.data_ptr(), codes.stride(0), m, n, bits, packed.data_ptr(), _stream())
+    if rc:
+        raise PtqError(rc, "ptq_pack_codes")
+
+
+def ptq_unpack_dequantize(packed: torch.Tensor, n: int, bits: int, scales: torch.Tensor, zeros: torch.Tensor,
+                          group: int, Wq: torch.Tensor) -> None:
+    """Wq (float64 m x n) <- scale * (code - zero) from the packed codes."""
+    _check_dev(packed, scales, zeros, Wq)
+    m = packed.shape[0]
+    assert packed.dtype == torch.int32 and packed.is_contiguous() and packed.shape == (m, n * bits // 32)
+    assert scales.dtype == torch.float32 and scales.is_contiguous() and scales.shape == (m, n // group)
+    assert zeros.dtype == torch.uint8 and zeros.is_contiguous() and zeros.shape == (m, n // group)
+    assert Wq.dtype == torch.float64 and Wq.stride(1) == 1 and Wq.shape == (m, n)
+    rc = load_library().ptq_unpack_dequantize(packed.data_ptr(), m, n, bits, scales.data_ptr(), zeros.data_ptr(),
+                                              group, Wq.data_ptr(), Wq.stride(0), _stream())
+    if rc:
+        raise PtqError(rc, "ptq_unpack_dequantize")
+
+
+def ptq_lopro_linear_forward(X: torch.Tensor, packed: torch.Tensor, bits: int, scales: torch.Tensor,
+                             zeros: torch.Tensor, group: int, perm: torch.Tensor, b_I: int, b_H: int,
+                             U: torch.Tensor | None, V: torch.Tensor | None, sigma: torch.Tensor | None,
+                             s: torch.Tensor | None, O: torch.Tensor, ws: torch.Tensor | None = None) -> None:
+    """O (float32 tokens x m) <- the stored layer applied to X (tokens x n) in the rotated-input form."""
+    _check_dev(X, packed, scales, zeros, perm, U, V, sigma, s, O)
+    tokens, n = X.shape
+    m = packed.shape[0]
+    r = 0 if U is None else U.shape[0]
+    assert X.stride(1) == 1 and packed.dtype == torch.int32 and packed.is_contiguous()
+    assert packed.shape == (m, n * bits // 32)
+    assert scales.dtype == torch.float32 and scales.is_contiguous() and scales.shape == (m, n // group)
+    assert zeros.dtype == torch.uint8 and zeros.is_contiguous() and zeros.shape == (m, n // group)
+    assert perm.dtype == torch.int32 and perm.is_contiguous() and perm.numel() == n
+    if r:
+        assert U.dtype == torch.uint8 and U.is_contiguous() and U.shape == (r, m)
+        assert V.dtype == torch.uint8 and V.is_contiguous() and V.shape == (r, n)
+        assert sigma.dtype == torch.float16 and sigma.is_contiguous() and sigma.numel() == r
+        assert s.dtype == torch.float64 and s.is_contiguous() and s.numel() == n
+    assert O.dtype == torch.float32 and O.stride(1) == 1 and O.shape == (tokens, m)
+    ws = _ws(ws, ptq_workspace_bytes(OP_LINEAR_FORWARD, m, n, tokens, r), X)
+    rc = load_library().ptq_lopro_linear_forward(
+        X.data_ptr(), _dtype_code(X), X.stride(0), tokens, m, n, packed.data_ptr(), bits, scales.data_ptr(),
+        zeros.data_ptr(), group, perm.data_ptr(), b_I, b_H, _ptr(U), _ptr(V), _ptr(sigma), r, _ptr(s),
+        O.data_ptr(), O.stride(0), ws.data_ptr(), ws.numel(), _stream())
+    if rc:
+        raise PtqError(rc, "ptq_lopro_linear_forward")

@@ -116,4 +116,16 @@ ptq_status r1svd_launch(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m, in
                         const float* S, int64_t lds, int r, int it, uint8_t* U, uint8_t* V, uint16_t* sigma16,
                         float* Rout, int64_t ldr, void* ws, hipStream_t st);
 
+
+ptq_status pack_codes_launch(const uint8_t* codes, int64_t ldc, int64_t m, int64_t n, int bits, uint32_t* packed,
+                             hipStream_t st);
+ptq_status unpack_dequant_launch(const uint32_t* packed, int64_t m, int64_t n, int bits, const float* scales,
+                                 const uint8_t* zeros, int group, double* Wq, int64_t ldq, hipStream_t st);
+size_t linear_forward_workspace_bytes(int64_t tokens, int64_t n, int64_t r);
+ptq_status linear_forward_launch(const void* X, ptq_dtype xdt, int64_t ldx, int64_t tokens, int64_t m, int64_t n,
+                                 const uint32_t* packed, int bits, const float* scales, const uint8_t* zeros,
+                                 int group, const int32_t* perm, int b_I, int b_H, const uint8_t* U,
+                                 const uint8_t* V, const uint16_t* sigma, int r, const double* s, float* O,
+                                 int64_t ldo, void* ws, hipStream_t st);
+
 }  // namespace ptq

@@ -35,7 +35,6 @@ const char* ptq_status_string(ptq_status s) {
 }
 
 ptq_status ptq_workspace_bytes(ptq_op op, int64_t m, int64_t n, int64_t t, int64_t block, size_t* bytes) {
-  (void)block;
   if (!bytes) return PTQ_ERR_ARG;
   if (m < 0 || n < 0 || t < 0) return PTQ_ERR_SHAPE;
   switch (op) {
@@ -47,6 +46,7 @@ ptq_status ptq_workspace_bytes(ptq_op op, int64_t m, int64_t n, int64_t t, int64
     case PTQ_OP_LOPRO_ROTATE_HESSIAN: *bytes = lopro_hessian_workspace_bytes(n); return PTQ_OK;
     case PTQ_OP_ACTIVATION_ABS_SUM: *bytes = abs_sum_workspace_bytes(n); return PTQ_OK;
     case PTQ_OP_SCALED_R1SVD: *bytes = r1svd_workspace_bytes(m, n); return PTQ_OK;
+    case PTQ_OP_LINEAR_FORWARD: *bytes = linear_forward_workspace_bytes(t, n, block); return PTQ_OK;
   }
   return PTQ_ERR_ARG;
 }
@@ -188,6 +188,53 @@ ptq_status ptq_scaled_r1svd(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m
   if (ws_bad(ws, ws_bytes, r1svd_workspace_bytes(m, n))) return PTQ_ERR_WORKSPACE;
   return r1svd_launch(W, wdt, ldw, m, n, s, S, lds, r, it, U, V, sigma, R, ldr, ws,
                       static_cast<hipStream_t>(stream));
+}
+
+double ptq_average_bits(int64_t m, int64_t n, double d_q, double d_o, int64_t g, int64_t r, double d_r) {
+  if (m <= 0 || n <= 0 || g <= 0 || r < 0) return -1.0;
+  return d_q + d_o / (double)g + (double)r * d_r / (double)n + (double)r * d_r / (double)m + 2.0 * d_o / (double)n +
+         (double)r * d_o / ((double)m * (double)n);
+}
+
+ptq_status ptq_pack_codes(const uint8_t* codes, int64_t ldc, int64_t m, int64_t n, int bits, uint32_t* packed,
+                          ptq_stream stream) {
+  if (bits != 2 && bits != 3 && bits != 4 && bits != 8) return PTQ_ERR_ARG;
+  if (m < 0 || n < 0 || n % 32 != 0 || ldc < n || ldc % 16 != 0 || m > INT32_MAX / 2 || n > INT32_MAX / 2)
+    return PTQ_ERR_SHAPE;
+  if (m == 0 || n == 0) return PTQ_OK;
+  if (!codes || !packed || misaligned(codes, 16) || misaligned(packed, 4)) return PTQ_ERR_ARG;
+  return pack_codes_launch(codes, ldc, m, n, bits, packed, static_cast<hipStream_t>(stream));
+}
+
+ptq_status ptq_unpack_dequantize(const uint32_t* packed, int64_t m, int64_t n, int bits, const float* scales,
+                                 const uint8_t* zeros, int group, double* Wq, int64_t ldq, ptq_stream stream) {
+  if (bits != 2 && bits != 3 && bits != 4 && bits != 8) return PTQ_ERR_ARG;
+  if (m < 0 || n < 0 || n % 32 != 0 || group <= 0 || n % group != 0 || ldq < n || m > INT32_MAX / 2 ||
+      n > INT32_MAX / 2)
+    return PTQ_ERR_SHAPE;
+  if (m == 0 || n == 0) return PTQ_OK;
+  if (!packed || !scales || !zeros || !Wq) return PTQ_ERR_ARG;
+  return unpack_dequant_launch(packed, m, n, bits, scales, zeros, group, Wq, ldq, static_cast<hipStream_t>(stream));
+}
+
+ptq_status ptq_lopro_linear_forward(const void* X, ptq_dtype xdt, int64_t ldx, int64_t tokens, int64_t m, int64_t n,
+                                    const uint32_t* packed, int bits, const float* scales, const uint8_t* zeros,
+                                    int group, const int32_t* perm, int b_I, int b_H, const uint8_t* U,
+                                    const uint8_t* V, const uint16_t* sigma, int r, const double* s, float* O,
+                                    int64_t ldo, void* ws, size_t ws_bytes, ptq_stream stream) {
+  if (!dtype_ok(xdt)) return PTQ_ERR_DTYPE;
+  if (bits != 2 && bits != 3 && bits != 4 && bits != 8) return PTQ_ERR_ARG;
+  if (tokens < 0 || tokens > 4096 || m <= 0 || n <= 0 || n % 32 != 0 || group <= 0 || group % 32 != 0 ||
+      n % group != 0 || ldx < n || ldo < m || m > INT32_MAX / 2 || n > INT32_MAX / 2)
+    return PTQ_ERR_SHAPE;
+  if (rotation_shape_bad(n, b_I, b_H)) return PTQ_ERR_SHAPE;
+  if (r < 0 || r > 1024) return PTQ_ERR_ARG;
+  if (tokens == 0) return PTQ_OK;
+  if (!X || !packed || !scales || !zeros || !perm || !O || misaligned(perm, 16)) return PTQ_ERR_ARG;
+  if (r > 0 && (!U || !V || !sigma || !s)) return PTQ_ERR_ARG;
+  if (ws_bad(ws, ws_bytes, linear_forward_workspace_bytes(tokens, n, r))) return PTQ_ERR_WORKSPACE;
+  return linear_forward_launch(X, xdt, ldx, tokens, m, n, packed, bits, scales, zeros, group, perm, b_I, b_H, U, V,
+                               sigma, r, s, O, ldo, ws, static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

@@ -33,7 +33,7 @@ def test_exports_every_declared_symbol(lib):
 def test_status_strings_and_workspace_sizes(lib):
     assert ptq.ptq_status_string(0) == "ok"
     assert "positive definite" in ptq.ptq_status_string(5)
-    for op in range(8):
+    for op in range(9):
         assert ptq.ptq_workspace_bytes(op, 4096, 4096, 262144, 128) % 256 == 0
     # the factorization works on one n x n float64 copy
     assert ptq.ptq_workspace_bytes(binding.OP_CHOLESKY_INV, 0, 4096) >= 4096 * 4096 * 8
@@ -41,7 +41,7 @@ def test_status_strings_and_workspace_sizes(lib):
     assert ptq.ptq_workspace_bytes(binding.OP_QUANTIZE, 4096, 11008) >= 4096 * 11008 * 8
     out = ctypes.c_size_t()
     assert lib.ptq_workspace_bytes(0, -1, 8, 8, 0, ctypes.byref(out)) == 2
-    assert lib.ptq_workspace_bytes(8, 1, 8, 8, 0, ctypes.byref(out)) == 1
+    assert lib.ptq_workspace_bytes(9, 1, 8, 8, 0, ctypes.byref(out)) == 1
     assert lib.ptq_workspace_bytes(0, 1, 8, 8, 0, None) == 1
 
 
@@ -138,3 +138,42 @@ def test_low_rank_step_argument_errors_are_reported_on_the_host(lib):
     assert call(R=p + 4) == 1                        # misaligned
     assert call(ws=None, bytes=0) == 4
     assert call(bytes=1024) == 4
+
+
+def test_stored_form_argument_errors_and_average_bits(lib):
+    p = 0x1000
+    big = 1 << 34
+    # Eq. 12 on the host: 2 bits, group 128, 16-bit originals, rank 16 in 8 bits, 4096 x 4096
+    want = 2 + 16 / 128 + 2 * (16 * 8 / 4096) + 2 * 16 / 4096 + 16 * 16 / 4096 ** 2
+    assert abs(ptq.ptq_average_bits(4096, 4096, 2, 16, 128, 16, 8) - want) < 1e-15
+    assert ptq.ptq_average_bits(0, 4096, 2, 16, 128, 16, 8) == -1.0
+    # packing
+    assert lib.ptq_pack_codes(p, 64, 4, 64, 5, p, None) == 1          # bits
+    assert lib.ptq_pack_codes(p, 64, 4, 48, 4, p, None) == 2          # n % 32
+    assert lib.ptq_pack_codes(p, 72, 4, 64, 4, p, None) == 2          # ldc % 16
+    assert lib.ptq_pack_codes(p + 8, 64, 4, 64, 4, p, None) == 1      # misaligned codes
+    assert lib.ptq_pack_codes(None, 64, 4, 64, 4, p, None) == 1
+    assert lib.ptq_pack_codes(p, 64, 0, 64, 4, p, None) == 0
+    assert lib.ptq_unpack_dequantize(p, 4, 64, 4, p, p, 48, p, 64, None) == 2   # n % group
+    assert lib.ptq_unpack_dequantize(p, 4, 64, 4, p, p, 32, p, 32, None) == 2   # ldq < n
+    assert lib.ptq_unpack_dequantize(p, 4, 64, 4, None, p, 32, p, 64, None) == 1
+    # forward:                  X  dt ldx tok m  n    packed bits sc z  grp perm bI  bH  U  V  sg r  s  O  ldo ws bytes
+    ok = [p, 0, 256, 2, 8, 256, p, 4, p, p, 64, p, 128, 128, p, p, p, 4, p, p, 8, p, big, None]
+    names = ["X", "dt", "ldx", "tok", "m", "n", "packed", "bits", "sc", "z", "grp", "perm", "bI", "bH", "U", "V",
+             "sg", "r", "s", "O", "ldo", "ws", "bytes"]
+    def call(**kw):
+        a = list(ok)
+        for k, v in kw.items():
+            a[names.index(k)] = v
+        return lib.ptq_lopro_linear_forward(*a)
+    assert call(dt=9) == 3
+    assert call(bits=5) == 1
+    assert call(grp=48) == 2                     # group % 32
+    assert call(ldo=4) == 2
+    assert call(ldx=128) == 2
+    assert call(bH=96) == 2                      # rotation shape rules
+    assert call(tok=5000) == 2
+    assert call(U=None) == 1
+    assert call(perm=None) == 1
+    assert call(ws=None, bytes=0) == 4
+    assert call(tok=0) == 0
