@@ -154,6 +154,45 @@ def r1svd_timings(ptq, W, X, m, n, t, rank=16, it=8, reps=5):
     }
 
 
+def forward_timings(ptq, codes, scales, zeros, m, n, bits, group, rank=16, reps=20):
+    """The stored layer applied to 1 and to 4 tokens in the rotated-input form (packed codes of the step just
+    run, a random permutation, random rank-16 e4m3 factors): bound by the packed codes streaming from memory."""
+    import torch
+    from paper_2601_19675_amd import binding
+    dev = "cuda"
+    g = torch.Generator(device=dev)
+    g.manual_seed(7)
+    packed = torch.empty((n // 32, m, bits), dtype=torch.int32, device=dev)
+    st = torch.empty((n // group, m), dtype=torch.float32, device=dev)
+    zt = torch.empty((n // group, m), dtype=torch.uint8, device=dev)
+    ptq.ptq_pack_codes(codes, bits, packed, scales, zeros, group, st, zt)
+    perm = torch.randperm(n, generator=g, device=dev).to(torch.int32)
+    U = torch.randint(0x20, 0x38, (rank, m), generator=g, device=dev, dtype=torch.uint8)
+    V = torch.randint(0x20, 0x38, (rank, n), generator=g, device=dev, dtype=torch.uint8)
+    sg = torch.rand(rank, generator=g, device=dev).to(torch.float16)
+    s = torch.ones(n, dtype=torch.float64, device=dev)
+    out = {"bits": bits, "group": group, "rank": rank, "packed_bytes": packed.numel() * 4}
+    nbytes = packed.numel() * 4 + scales.numel() * 4 + zeros.numel() + rank * (m + n)
+    for tokens in (1, 4):
+        X = torch.randn((tokens, n), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        O = torch.empty((tokens, m), dtype=torch.float32, device=dev)
+        ws = torch.empty(ptq.ptq_workspace_bytes(binding.OP_LINEAR_FORWARD, m, n, tokens, rank), dtype=torch.uint8,
+                         device=dev)
+        f = lambda: ptq.ptq_lopro_linear_forward(X, packed, bits, st, zt, group, perm, 256, 256, U, V, sg, s, O, ws)
+        for _ in range(3):
+            f()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            f()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        out[f"tokens_{tokens}"] = {"ms_per_call": ms, "algorithmic_GBps": nbytes / ms / 1e6,
+                                   "frac_of_hbm_peak": nbytes / ms / 1e6 / HBM_GBPS}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -168,6 +207,9 @@ def main():
     ap.add_argument("--r1svd", action="store_true",
                     help="also time the low-rank step on the same layer (activation scale from X, then the scaled "
                          "rank-one sketch with rank 16 and 8 iterations) and report it under \"r1svd\"")
+    ap.add_argument("--forward", action="store_true",
+                    help="also time the stored layer applied to 1 and 4 tokens (packed codes, rotated input, "
+                         "rank-16 low-rank part) and report it under \"forward\"")
     ap.add_argument("--device-x", action="store_true",
                     help="draw the activations on the GPU (same distribution family, torch generator) instead of "
                          "the seeded host generator: for timing the widest layers, whose host generation takes minutes")
@@ -301,6 +343,8 @@ def main():
         result["lopro"] = lopro_timings(ptq, W, H, m, n, ws)
     if args.r1svd:
         result["r1svd"] = r1svd_timings(ptq, W, X, m, n, t)
+    if args.forward:
+        result["forward"] = forward_timings(ptq, codes, scales, zeros, m, n, cfg.bits, cfg.group)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, spec, cfg.seed)
     print(json.dumps(result))

@@ -299,21 +299,27 @@ ptq_status ptq_scaled_r1svd(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m
 double ptq_average_bits(int64_t m, int64_t n, double d_q, double d_o, int64_t g, int64_t r, double d_r);
 
 /*
- * Bit packing.  Code j of a row occupies bits [j bits, (j+1) bits) of the row's bit stream,
- * stored in little-endian 32-bit words, rows dense: packed is m x (n bits / 32) words.
+ * Bit packing.  32 consecutive codes of a row (a chunk) form a little-endian bit stream of
+ * exactly `bits` 32-bit words, code j of the chunk in bits [j bits, (j+1) bits); chunks are
+ * stored chunk-major: packed is (n / 32) x m x bits words (consecutive rows of a chunk are
+ * adjacent, which is the order the forward kernel reads them in); 16-byte aligned.
  * codes m x n bytes (values < 2^bits; higher bits are ignored), ldc >= n, ldc % 16 == 0,
  * 16-byte aligned.  bits in {2, 3, 4, 8}; n % 32 == 0.
+ * The grids are brought into the matching group-major order on the way: scales, zeros
+ * (m x n/group, as ptq_quantize_layer wrote them) -> scales_t, zeros_t (n/group x m); pass
+ * NULL for all four to pack the codes only.
  */
 ptq_status ptq_pack_codes(const uint8_t* codes, int64_t ldc, int64_t m, int64_t n, int bits,
-                          uint32_t* packed, ptq_stream stream);
+                          uint32_t* packed, const float* scales, const uint8_t* zeros, int group,
+                          float* scales_t, uint8_t* zeros_t, ptq_stream stream);
 
 /*
- * The inverse with dequantization:  Wq[i][j] = scale[i][j/group] * (code[i][j] - zero[i][j/group])
+ * The inverse with dequantization:  Wq[i][j] = scale_t[j/group][i] * (code[i][j] - zero_t[j/group][i])
  * in float64 (exact: a float32 times a small integer), the value ptq_quantize_layer wrote.
- * scales m x n/group float32, zeros m x n/group bytes, Wq m x n float64, ldq >= n.
+ * scales_t n/group x m float32, zeros_t n/group x m bytes, Wq m x n float64, ldq >= n.
  */
 ptq_status ptq_unpack_dequantize(const uint32_t* packed, int64_t m, int64_t n, int bits,
-                                 const float* scales, const uint8_t* zeros, int group, double* Wq,
+                                 const float* scales_t, const uint8_t* zeros_t, int group, double* Wq,
                                  int64_t ldq, ptq_stream stream);
 
 /*
@@ -323,17 +329,17 @@ ptq_status ptq_unpack_dequantize(const uint32_t* packed, int64_t m, int64_t n, i
  * rotated once (same perm, b_I, b_H and their restrictions as the rotation calls above).
  *
  * X      tokens x n, PTQ_F32 / PTQ_BF16 / PTQ_F64, ldx >= n.       O  tokens x m float32, ldo >= m.
- * packed, scales, zeros, bits, group: as above; group % 32 == 0.
+ * packed, scales_t, zeros_t (group-major), bits, group: as above; group % 32 == 0.
  * U, V   r x m and r x n e4m3 codes, sigma r fp16 bit patterns, s n float64: the output of
  *        ptq_scaled_r1svd; r = 0 applies the residual alone (U, V, sigma, s may be NULL).
  * X~ and the low-rank coefficients are formed in float64 and rounded to float32; the products
  * with the codes accumulate in float32.  tokens <= 4096 (meant for a handful: the call reads
  * the packed codes once per four tokens).
- * Workspace: PTQ_OP_LINEAR_FORWARD with t = tokens and block = r.
+ * Workspace: PTQ_OP_LINEAR_FORWARD with m, n, t = tokens and block = r.
  */
 ptq_status ptq_lopro_linear_forward(const void* X, ptq_dtype xdt, int64_t ldx, int64_t tokens, int64_t m,
-                                    int64_t n, const uint32_t* packed, int bits, const float* scales,
-                                    const uint8_t* zeros, int group, const int32_t* perm, int b_I,
+                                    int64_t n, const uint32_t* packed, int bits, const float* scales_t,
+                                    const uint8_t* zeros_t, int group, const int32_t* perm, int b_I,
                                     int b_H, const uint8_t* U, const uint8_t* V, const uint16_t* sigma,
                                     int r, const double* s, float* O, int64_t ldo, void* ws,
                                     size_t ws_bytes, ptq_stream stream);

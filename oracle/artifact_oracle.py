@@ -14,9 +14,10 @@ What the paper fixes (LoPRo, arXiv 2601.19675):
     V' = V diag(s)^-1 (Eq. 3).
 
 Readings:
-  * Bit packing is not specified: code j of a row occupies bits [j d_q, (j+1) d_q) of the
-    row's bit stream, stored in little-endian 32-bit words (for d_q = 3, 32 codes fill exactly
-    three words).  Any packing has the same size; this one is what the GPU kernels read.
+  * Bit packing is not specified: 32 consecutive codes of a row (a chunk) form a little-endian
+    bit stream of exactly d_q 32-bit words, code j in bits [j d_q, (j+1) d_q); chunks are stored
+    chunk-major, packed[chunk, row, word].  Any packing has the same size; this one is what the
+    GPU kernels read (consecutive rows of a chunk are adjacent in memory).
   * Activations are handled as tokens x channels (rows are tokens), so X~ = X P Q and
     O = X~ Dequant(W_q)^T + ((X diag(s)^-1) V^T diag(sigma)) U.
   * Eq. 12 counts one d_o-bit scale per group and nothing for the zero-point of an
@@ -58,32 +59,35 @@ def stored_bits(m: int, n: int, d_q: int, g: int, r: int) -> float:
 
 
 def pack_codes(codes: np.ndarray, bits: int) -> np.ndarray:
-    """uint8 codes (m x n) -> uint32 words (m x ceil(n bits / 32)), little-endian bit stream."""
+    """uint8 codes (m x n, n % 32 == 0) -> uint32 words (n/32 x m x bits)."""
     m, n = codes.shape
-    words = -(-n * bits // 32)
-    out = np.zeros((m, words), dtype=np.uint64)
-    for j in range(n):
-        pos = j * bits
-        wi, sh = pos // 32, pos % 32
-        v = codes[:, j].astype(np.uint64) << np.uint64(sh)
-        out[:, wi] |= v & np.uint64(0xFFFFFFFF)
-        if sh + bits > 32:
-            out[:, wi + 1] |= v >> np.uint64(32)
+    assert n % 32 == 0
+    out = np.zeros((n // 32, m, bits), dtype=np.uint64)
+    for c in range(n // 32):
+        for j in range(32):
+            pos = j * bits
+            wi, sh = pos // 32, pos % 32
+            v = codes[:, c * 32 + j].astype(np.uint64) << np.uint64(sh)
+            out[c, :, wi] |= v & np.uint64(0xFFFFFFFF)
+            if sh + bits > 32:
+                out[c, :, wi + 1] |= v >> np.uint64(32)
     return out.astype(np.uint32)
 
 
 def unpack_codes(packed: np.ndarray, bits: int, n: int) -> np.ndarray:
-    m = packed.shape[0]
+    chunks, m, _ = packed.shape
+    assert chunks * 32 == n
     out = np.zeros((m, n), dtype=np.uint8)
     p64 = packed.astype(np.uint64)
     mask = np.uint64((1 << bits) - 1)
-    for j in range(n):
-        pos = j * bits
-        wi, sh = pos // 32, pos % 32
-        v = p64[:, wi] >> np.uint64(sh)
-        if sh + bits > 32:
-            v |= p64[:, wi + 1] << np.uint64(32 - sh)
-        out[:, j] = (v & mask).astype(np.uint8)
+    for c in range(chunks):
+        for j in range(32):
+            pos = j * bits
+            wi, sh = pos // 32, pos % 32
+            v = p64[c, :, wi] >> np.uint64(sh)
+            if sh + bits > 32:
+                v |= p64[c, :, wi + 1] << np.uint64(32 - sh)
+            out[:, c * 32 + j] = (v & mask).astype(np.uint8)
     return out
 
 

@@ -72,7 +72,7 @@ def load_library() -> ctypes.CDLL:
     lib.ptq_average_bits.restype = c.c_double
     lib.ptq_average_bits.argtypes = [i64, i64, c.c_double, c.c_double, i64, i64, c.c_double]
     lib.ptq_pack_codes.restype = c.c_int
-    lib.ptq_pack_codes.argtypes = [vp, i64, i64, i64, c.c_int, vp, vp]
+    lib.ptq_pack_codes.argtypes = [vp, i64, i64, i64, c.c_int, vp, vp, vp, c.c_int, vp, vp, vp]
     lib.ptq_unpack_dequantize.restype = c.c_int
     lib.ptq_unpack_dequantize.argtypes = [vp, i64, i64, c.c_int, vp, vp, c.c_int, vp, i64, vp]
     lib.ptq_lopro_linear_forward.restype = c.c_int
@@ -299,45 +299,57 @@ def ptq_average_bits(m: int, n: int, d_q: float, d_o: float, g: int, r: int, d_r
     return float(load_library().ptq_average_bits(m, n, d_q, d_o, g, r, d_r))
 
 
-def ptq_pack_codes(codes: torch.Tensor, bits: int, packed: torch.Tensor) -> None:
-    """packed (int32 m x n*bits/32) <- bit stream of codes (uint8 m x n)."""
-    _check_dev(codes, packed)
+def ptq_pack_codes(codes: torch.Tensor, bits: int, packed: torch.Tensor, scales: torch.Tensor | None = None,
+                   zeros: torch.Tensor | None = None, group: int = 0, scales_t: torch.Tensor | None = None,
+                   zeros_t: torch.Tensor | None = None) -> None:
+    """packed (int32 n/32 x m x bits, chunk-major) <- bit stream of codes (uint8 m x n); with the grids given,
+    scales_t / zeros_t (n/group x m) <- scales / zeros (m x n/group)."""
+    _check_dev(codes, packed, scales, zeros, scales_t, zeros_t)
     m, n = codes.shape
     assert codes.dtype == torch.uint8 and codes.stride(1) == 1
-    assert packed.dtype == torch.int32 and packed.is_contiguous() and packed.shape == (m, n * bits // 32)
-    rc = load_library().ptq_pack_codes(codes.data_ptr(), codes.stride(0), m, n, bits, packed.data_ptr(), _stream())
+    assert packed.dtype == torch.int32 and packed.is_contiguous() and packed.shape == (n // 32, m, bits)
+    if scales is not None:
+        ng = n // group
+        assert scales.dtype == torch.float32 and scales.is_contiguous() and scales.shape == (m, ng)
+        assert zeros.dtype == torch.uint8 and zeros.is_contiguous() and zeros.shape == (m, ng)
+        assert scales_t.dtype == torch.float32 and scales_t.is_contiguous() and scales_t.shape == (ng, m)
+        assert zeros_t.dtype == torch.uint8 and zeros_t.is_contiguous() and zeros_t.shape == (ng, m)
+    rc = load_library().ptq_pack_codes(codes.data_ptr(), codes.stride(0), m, n, bits, packed.data_ptr(), _ptr(scales),
+                                       _ptr(zeros), group, _ptr(scales_t), _ptr(zeros_t), _stream())
     if rc:
         raise PtqError(rc, "ptq_pack_codes")
 
 
-def ptq_unpack_dequantize(packed: torch.Tensor, n: int, bits: int, scales: torch.Tensor, zeros: torch.Tensor,
+def ptq_unpack_dequantize(packed: torch.Tensor, n: int, bits: int, scales_t: torch.Tensor, zeros_t: torch.Tensor,
                           group: int, Wq: torch.Tensor) -> None:
-    """Wq (float64 m x n) <- scale * (code - zero) from the packed codes."""
-    _check_dev(packed, scales, zeros, Wq)
-    m = packed.shape[0]
-    assert packed.dtype == torch.int32 and packed.is_contiguous() and packed.shape == (m, n * bits // 32)
-    assert scales.dtype == torch.float32 and scales.is_contiguous() and scales.shape == (m, n // group)
-    assert zeros.dtype == torch.uint8 and zeros.is_contiguous() and zeros.shape == (m, n // group)
+    """Wq (float64 m x n) <- scale * (code - zero) from the packed codes and group-major grids."""
+    _check_dev(packed, scales_t, zeros_t, Wq)
+    m = packed.shape[1]
+    assert packed.dtype == torch.int32 and packed.is_contiguous() and packed.shape == (n // 32, m, bits)
+    assert scales_t.dtype == torch.float32 and scales_t.is_contiguous() and scales_t.shape == (n // group, m)
+    assert zeros_t.dtype == torch.uint8 and zeros_t.is_contiguous() and zeros_t.shape == (n // group, m)
     assert Wq.dtype == torch.float64 and Wq.stride(1) == 1 and Wq.shape == (m, n)
-    rc = load_library().ptq_unpack_dequantize(packed.data_ptr(), m, n, bits, scales.data_ptr(), zeros.data_ptr(),
+    rc = load_library().ptq_unpack_dequantize(packed.data_ptr(), m, n, bits, scales_t.data_ptr(), zeros_t.data_ptr(),
                                               group, Wq.data_ptr(), Wq.stride(0), _stream())
     if rc:
         raise PtqError(rc, "ptq_unpack_dequantize")
 
 
-def ptq_lopro_linear_forward(X: torch.Tensor, packed: torch.Tensor, bits: int, scales: torch.Tensor,
-                             zeros: torch.Tensor, group: int, perm: torch.Tensor, b_I: int, b_H: int,
+def ptq_lopro_linear_forward(X: torch.Tensor, packed: torch.Tensor, bits: int, scales_t: torch.Tensor,
+                             zeros_t: torch.Tensor, group: int, perm: torch.Tensor, b_I: int, b_H: int,
                              U: torch.Tensor | None, V: torch.Tensor | None, sigma: torch.Tensor | None,
                              s: torch.Tensor | None, O: torch.Tensor, ws: torch.Tensor | None = None) -> None:
-    """O (float32 tokens x m) <- the stored layer applied to X (tokens x n) in the rotated-input form."""
+    """O (float32 tokens x m) <- the stored layer applied to X (tokens x n) in the rotated-input form;
+    scales_t / zeros_t are the group-major grids ptq_pack_codes writes."""
+    scales, zeros = scales_t, zeros_t
     _check_dev(X, packed, scales, zeros, perm, U, V, sigma, s, O)
     tokens, n = X.shape
-    m = packed.shape[0]
+    m = packed.shape[1]
     r = 0 if U is None else U.shape[0]
     assert X.stride(1) == 1 and packed.dtype == torch.int32 and packed.is_contiguous()
-    assert packed.shape == (m, n * bits // 32)
-    assert scales.dtype == torch.float32 and scales.is_contiguous() and scales.shape == (m, n // group)
-    assert zeros.dtype == torch.uint8 and zeros.is_contiguous() and zeros.shape == (m, n // group)
+    assert packed.shape == (n // 32, m, bits)
+    assert scales.dtype == torch.float32 and scales.is_contiguous() and scales.shape == (n // group, m)
+    assert zeros.dtype == torch.uint8 and zeros.is_contiguous() and zeros.shape == (n // group, m)
     assert perm.dtype == torch.int32 and perm.is_contiguous() and perm.numel() == n
     if r:
         assert U.dtype == torch.uint8 and U.is_contiguous() and U.shape == (r, m)

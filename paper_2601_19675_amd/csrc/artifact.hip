@@ -4,13 +4,19 @@
 //   * the layer applied to a few tokens:  O = X~ Dequant(W_q)^T + ((X diag(s)^-1) V^T diag(sigma)) U,
 //     X~ = X P Q  (the input is permuted and rotated once, the residual is never rotated back).
 //
-// Packing: code j of a row occupies bits [j d, (j+1) d) of the row's bit stream, stored in
-// little-endian 32-bit words; 32 codes fill exactly d words, which is the unit a lane works on.
+// Packing: 32 consecutive codes of a row (a chunk) form a little-endian bit stream of exactly d
+// 32-bit words, code j in bits [j d, (j+1) d); the chunks are stored chunk-major,
+// packed[chunk][row][d], and the grids group-major, scale[group][row] and zero[group][row], so
+// that lanes that work on consecutive rows read consecutive memory.
 //
 // The product with the packed residual is bound by the rate at which the codes stream from
-// memory (m n d / 8 bytes; the vectors and grids are a few percent of that).  A wave takes a
-// few rows; each lane takes 32-column chunks, keeps that chunk of X~ for all tokens in
-// registers and reuses it for the wave's rows, so that nothing but the codes is read per row.
+// memory (m n d / 8 bytes; the vectors and grids are a few percent of that).  A lane is a row;
+// a workgroup takes 256 rows and a run of eight chunks (256 columns), whose piece of X~ it
+// stages in LDS (all lanes read the same address: a broadcast), requests its eight chunks at
+// once, and writes one partial sum per row and token; a second small kernel adds the partial
+// sums of a row in a fixed order together with the low-rank part.  Splitting the columns rather
+// than the rows keeps the staged piece of X~ tiny, so that the grid can be large enough to fill
+// the chip without every workgroup re-reading all of X~.
 #include "common.h"
 
 namespace ptq {
@@ -18,21 +24,20 @@ namespace {
 
 constexpr int kChunk = 32;   // codes per lane and step: d words
 
-// The 32 codes of a chunk from its d words.
+// Code j of a chunk from its d words; j and d are compile-time constants, so this is one
+// bit-field extract, or two shifts and a mask where a 3-bit code straddles two words.
+template <int BITS>
+__device__ __forceinline__ uint32_t chunk_code(const uint32_t* __restrict__ words, int j) {
+  const int pos = j * BITS, wi = pos >> 5, sh = pos & 31;
+  constexpr uint32_t mask = (1u << BITS) - 1u;
+  if (sh + BITS <= 32) return (words[wi] >> sh) & mask;
+  return ((words[wi] >> sh) | (words[wi + 1] << (32 - sh))) & mask;
+}
+
 template <int BITS>
 __device__ __forceinline__ void unpack_chunk(const uint32_t* __restrict__ words, uint8_t (&code)[kChunk]) {
-  uint64_t acc = 0;
-  int have = 0, w = 0;
 #pragma unroll
-  for (int j = 0; j < kChunk; ++j) {
-    if (have < BITS) {
-      acc |= (uint64_t)words[w++] << have;
-      have += 32;
-    }
-    code[j] = (uint8_t)(acc & ((1u << BITS) - 1u));
-    acc >>= BITS;
-    have -= BITS;
-  }
+  for (int j = 0; j < kChunk; ++j) code[j] = (uint8_t)chunk_code<BITS>(words, j);
 }
 
 template <int BITS>
@@ -41,11 +46,11 @@ __global__ __launch_bounds__(256) void pack_kernel(const uint8_t* __restrict__ c
   const int chunks = n / kChunk;
   const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (e >= (int64_t)m * chunks) return;
-  const int row = (int)(e / chunks), c = (int)(e - (int64_t)row * chunks);
+  const int c = (int)(e / m), row = (int)(e - (int64_t)c * m);   // rows fastest: the stores are contiguous
   const uint4* src = reinterpret_cast<const uint4*>(codes + (int64_t)row * ldc + c * kChunk);
   const uint4 lo = src[0], hi = src[1];
   const uint32_t raw[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-  uint32_t* dst = packed + ((int64_t)row * chunks + c) * BITS;
+  uint32_t* dst = packed + ((int64_t)c * m + row) * BITS;
   uint64_t acc = 0;
   int have = 0, w = 0;
 #pragma unroll
@@ -69,21 +74,40 @@ __global__ __launch_bounds__(256) void unpack_dequant_kernel(const uint32_t* __r
   const int chunks = n / kChunk;
   const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (e >= (int64_t)m * chunks) return;
-  const int row = (int)(e / chunks), c = (int)(e - (int64_t)row * chunks);
-  const uint32_t* src = packed + ((int64_t)row * chunks + c) * BITS;
+  const int c = (int)(e / m), row = (int)(e - (int64_t)c * m);
+  const uint32_t* src = packed + ((int64_t)c * m + row) * BITS;
   uint32_t words[BITS];
 #pragma unroll
   for (int w = 0; w < BITS; ++w) words[w] = src[w];
   uint8_t code[kChunk];
   unpack_chunk<BITS>(words, code);
-  const int ng = n / group;
   double* dst = Wq + (int64_t)row * ldq + c * kChunk;
 #pragma unroll
   for (int j = 0; j < kChunk; ++j) {
     const int g = (c * kChunk + j) / group;   // a group may be as small as 16 columns
-    const double sc = (double)scales[(int64_t)row * ng + g];
-    const double z = (double)zeros[(int64_t)row * ng + g];
+    const double sc = (double)scales[(int64_t)g * m + row];
+    const double z = (double)zeros[(int64_t)g * m + row];
     dst[j] = sc * ((double)code[j] - z);
+  }
+}
+
+// scale[row][group] -> scale[group][row], the same for the zero-points (32 x 32 tiles through LDS)
+__global__ __launch_bounds__(256) void transpose_grids_kernel(const float* __restrict__ scales,
+                                                              const uint8_t* __restrict__ zeros, int m, int ng,
+                                                              float* __restrict__ scales_t,
+                                                              uint8_t* __restrict__ zeros_t) {
+  __shared__ float ts[32][33];
+  __shared__ uint8_t tz[32][33];
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  const int r0 = blockIdx.x * 32, g0 = blockIdx.y * 32;
+  for (int k = ty; k < 32; k += 8) {
+    const int row = r0 + k, g = g0 + tx;
+    if (row < m && g < ng) { ts[k][tx] = scales[(int64_t)row * ng + g]; tz[k][tx] = zeros[(int64_t)row * ng + g]; }
+  }
+  __syncthreads();
+  for (int k = ty; k < 32; k += 8) {
+    const int g = g0 + k, row = r0 + tx;
+    if (row < m && g < ng) { scales_t[(int64_t)g * m + row] = ts[tx][k]; zeros_t[(int64_t)g * m + row] = tz[tx][k]; }
   }
 }
 
@@ -131,103 +155,140 @@ __global__ __launch_bounds__(256) void low_rank_coeff_kernel(const void* __restr
 }
 
 struct ForwardArgs {
-  const uint32_t* packed;   // m x (n / 32) x BITS words
-  const float* scales;      // m x n / group
-  const uint8_t* zeros;     // m x n / group
+  const uint32_t* packed;   // (n / 32) x m x BITS words
+  const float* scales;      // n / group x m
+  const uint8_t* zeros;     // n / group x m
   int m, n, group;
   const float* xt;          // tokens x n: X~
   const float* y;           // tokens x r
   const uint8_t* U;         // r x m, e4m3
   int r;
+  float* partial;           // splits x B x m
   float* O;                 // tokens x m
   int64_t ldo;
 };
 
-constexpr int kFwdWaves = 4;
-constexpr int kFwdRows = 4;   // rows of W per wave
+constexpr int kFwdRun = 8;   // chunks per workgroup: 256 columns
 
-// B tokens per launch.  A lane's chunks are c = lane, lane + 64, ...; requires group % 32 == 0.
+template <int BITS>
+struct alignas(BITS == 3 ? 4 : (BITS == 2 ? 8 : 16)) Words { uint32_t w[BITS]; };
+
+// grid: (row blocks of 256, runs of kFwdRun chunks); B tokens.  Requires group % 32 == 0.
 template <int BITS, int B>
-__global__ __launch_bounds__(64 * kFwdWaves) void forward_kernel(ForwardArgs a) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int row0 = (blockIdx.x * kFwdWaves + wave) * kFwdRows;
-  if (row0 >= a.m) return;
-  const int chunks = a.n / kChunk, ng = a.n / a.group;
-  float acc[kFwdRows][B];
-#pragma unroll
-  for (int i = 0; i < kFwdRows; ++i)
-#pragma unroll
-    for (int t = 0; t < B; ++t) acc[i][t] = 0.f;
+__global__ __launch_bounds__(256) void forward_partial_kernel(ForwardArgs a) {
+  __shared__ float xs[B][kFwdRun * kChunk];
+  __shared__ float xsum[B][kFwdRun];
+  const int tid = threadIdx.x;
+  const int m = a.m, n = a.n, chunks = n / kChunk;
+  const int row = blockIdx.x * 256 + tid;
+  const bool live = row < m;
+  const int c0 = blockIdx.y * kFwdRun;
+  const int nc = min(kFwdRun, chunks - c0);
 
-  for (int c = lane; c < chunks; c += 64) {
-    float x[B][kChunk];
+  // the eight chunks of this row first: they are the long latency
+  Words<BITS> wd[kFwdRun];
 #pragma unroll
-    for (int t = 0; t < B; ++t) {
-      const float4* px = reinterpret_cast<const float4*>(a.xt + (int64_t)t * a.n + c * kChunk);
+  for (int k = 0; k < kFwdRun; ++k) {
 #pragma unroll
-      for (int q = 0; q < kChunk / 4; ++q) {
-        const float4 v = px[q];
-        x[t][4 * q] = v.x; x[t][4 * q + 1] = v.y; x[t][4 * q + 2] = v.z; x[t][4 * q + 3] = v.w;
-      }
-    }
-    const int g = c * kChunk / a.group;
-#pragma unroll
-    for (int i = 0; i < kFwdRows; ++i) {
-      const int row = row0 + i;
-      if (row >= a.m) break;
-      const uint32_t* src = a.packed + ((int64_t)row * chunks + c) * BITS;
-      uint32_t words[BITS];
-#pragma unroll
-      for (int w = 0; w < BITS; ++w) words[w] = src[w];
-      uint8_t code[kChunk];
-      unpack_chunk<BITS>(words, code);
-      const float sc = a.scales[(int64_t)row * ng + g];
-      const float z = (float)a.zeros[(int64_t)row * ng + g];
-#pragma unroll
-      for (int j = 0; j < kChunk; ++j) {
-        const float wq = sc * ((float)code[j] - z);
-#pragma unroll
-        for (int t = 0; t < B; ++t) acc[i][t] = fmaf(wq, x[t][j], acc[i][t]);
-      }
-    }
+    for (int w = 0; w < BITS; ++w) wd[k].w[w] = 0u;
+    if (live && k < nc) wd[k] = *reinterpret_cast<const Words<BITS>*>(a.packed + ((int64_t)(c0 + k) * m + row) * BITS);
   }
-  // the low-rank part rides on the same reduction: lane k adds  U[k][row] * y[t][k]
+  // sum_j scale (code_j - zero) x_j = scale (sum_j code_j x_j - zero sum_j x_j): the second sum does
+  // not depend on the row, so a weight costs an extract, a conversion and one multiply-add per token
+  for (int e = tid; e < B * kFwdRun * (kChunk / 4); e += 256) {
+    const int t = e / (kFwdRun * (kChunk / 4)), q = e - t * (kFwdRun * (kChunk / 4));   // q: float4 index in the run
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (q < nc * (kChunk / 4)) v = *reinterpret_cast<const float4*>(a.xt + (int64_t)t * n + c0 * kChunk + 4 * q);
+    *reinterpret_cast<float4*>(&xs[t][4 * q]) = v;
+    float sum = (v.x + v.y) + (v.z + v.w);     // eight consecutive threads hold one chunk
+    sum += __shfl_xor(sum, 1);
+    sum += __shfl_xor(sum, 2);
+    sum += __shfl_xor(sum, 4);
+    if ((q & 7) == 0) xsum[t][q >> 3] = sum;
+  }
+  __syncthreads();
+
+  float acc[B];
 #pragma unroll
-  for (int i = 0; i < kFwdRows; ++i) {
-    const int row = row0 + i;
-    if (row >= a.m) break;
-    for (int k = lane; k < a.r; k += 64) {
-      const float u = e4m3_to_float(a.U[(int64_t)k * a.m + row]);
+  for (int t = 0; t < B; ++t) acc[t] = 0.f;
 #pragma unroll
-      for (int t = 0; t < B; ++t) acc[i][t] = fmaf(u, a.y[(int64_t)t * a.r + k], acc[i][t]);
+  for (int k = 0; k < kFwdRun; ++k) {
+    if (k >= nc) break;
+    const int g = (c0 + k) * kChunk / a.group;
+    const float sc = live ? a.scales[(int64_t)g * m + row] : 0.f;
+    const float z = live ? (float)a.zeros[(int64_t)g * m + row] : 0.f;
+    float raw[B];
+#pragma unroll
+    for (int t = 0; t < B; ++t) raw[t] = 0.f;
+#pragma unroll
+    for (int q = 0; q < kChunk / 4; ++q) {
+      float cf[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) cf[j] = (float)chunk_code<BITS>(wd[k].w, 4 * q + j);
+#pragma unroll
+      for (int t = 0; t < B; ++t) {
+        const float4 x = *reinterpret_cast<const float4*>(&xs[t][k * kChunk + 4 * q]);
+        raw[t] = fmaf(cf[3], x.w, fmaf(cf[2], x.z, fmaf(cf[1], x.y, fmaf(cf[0], x.x, raw[t]))));
+      }
     }
 #pragma unroll
-    for (int t = 0; t < B; ++t) {
-      float v = acc[i][t];
+    for (int t = 0; t < B; ++t) acc[t] = fmaf(sc, fmaf(-z, xsum[t][k], raw[t]), acc[t]);
+  }
+  if (live) {
 #pragma unroll
-      for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
-      if (lane == 0) a.O[(int64_t)t * a.ldo + row] = v;
-    }
+    for (int t = 0; t < B; ++t) a.partial[((int64_t)blockIdx.y * B + t) * m + row] = acc[t];
   }
 }
 
+// O[t][row] = sum over the column runs, in order, + sum_k U[k][row] y[t][k]
+template <int B>
+__global__ __launch_bounds__(64) void forward_finish_kernel(ForwardArgs a, int splits) {
+  const int row = blockIdx.x * 64 + threadIdx.x;
+  if (row >= a.m) return;
+  float acc[B];
+#pragma unroll
+  for (int t = 0; t < B; ++t) acc[t] = 0.f;
+  for (int sp0 = 0; sp0 < splits; sp0 += 8) {   // eight loads in flight per token, added in order
+    float v[8][B];
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+#pragma unroll
+      for (int t = 0; t < B; ++t)
+        v[k][t] = sp0 + k < splits ? a.partial[((int64_t)(sp0 + k) * B + t) * a.m + row] : 0.f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+#pragma unroll
+      for (int t = 0; t < B; ++t) acc[t] += v[k][t];
+  }
+  for (int k = 0; k < a.r; ++k) {
+    const float u = e4m3_to_float(a.U[(int64_t)k * a.m + row]);
+#pragma unroll
+    for (int t = 0; t < B; ++t) acc[t] = fmaf(u, a.y[(int64_t)t * a.r + k], acc[t]);
+  }
+#pragma unroll
+  for (int t = 0; t < B; ++t) a.O[(int64_t)t * a.ldo + row] = acc[t];
+}
+
+template <int BITS, int B>
+void launch_forward_b(const ForwardArgs& a, hipStream_t st) {
+  const int splits = (int)ceil_div(a.n / kChunk, kFwdRun);
+  dim3 g((unsigned)ceil_div(a.m, 256), (unsigned)splits);
+  forward_partial_kernel<BITS, B><<<g, 256, 0, st>>>(a);
+  forward_finish_kernel<B><<<(unsigned)ceil_div(a.m, 64), 64, 0, st>>>(a, splits);
+}
+
+// four, two or one token per pass over the codes
 template <int BITS>
 void launch_forward(const ForwardArgs& a, int tokens, hipStream_t st) {
-  const unsigned grid = (unsigned)ceil_div(a.m, kFwdWaves * kFwdRows);
   ForwardArgs b = a;
   int done = 0;
   while (done < tokens) {
     const int left = tokens - done;
-    if (left >= 4) {
-      forward_kernel<BITS, 4><<<grid, 64 * kFwdWaves, 0, st>>>(b);
-      done += 4;
-    } else if (left >= 2) {
-      forward_kernel<BITS, 2><<<grid, 64 * kFwdWaves, 0, st>>>(b);
-      done += 2;
-    } else {
-      forward_kernel<BITS, 1><<<grid, 64 * kFwdWaves, 0, st>>>(b);
-      done += 1;
-    }
+    int step;
+    if (left >= 4) { step = 4; launch_forward_b<BITS, 4>(b, st); }
+    else if (left >= 2) { step = 2; launch_forward_b<BITS, 2>(b, st); }
+    else { step = 1; launch_forward_b<BITS, 1>(b, st); }
+    done += step;
     b.xt = a.xt + (int64_t)done * a.n;
     b.y = a.y + (int64_t)done * a.r;
     b.O = a.O + (int64_t)done * a.ldo;
@@ -235,6 +296,14 @@ void launch_forward(const ForwardArgs& a, int tokens, hipStream_t st) {
 }
 
 }  // namespace
+
+ptq_status pack_grids_launch(const float* scales, const uint8_t* zeros, int64_t m, int64_t ng, float* scales_t,
+                             uint8_t* zeros_t, hipStream_t st) {
+  dim3 g((unsigned)ceil_div(m, 32), (unsigned)ceil_div(ng, 32));
+  transpose_grids_kernel<<<g, 256, 0, st>>>(scales, zeros, (int)m, (int)ng, scales_t, zeros_t);
+  PTQ_HIP_CHECK_LAUNCH();
+  return PTQ_OK;
+}
 
 ptq_status pack_codes_launch(const uint8_t* codes, int64_t ldc, int64_t m, int64_t n, int bits, uint32_t* packed,
                              hipStream_t st) {
@@ -264,9 +333,13 @@ ptq_status unpack_dequant_launch(const uint32_t* packed, int64_t m, int64_t n, i
   return PTQ_OK;
 }
 
-size_t linear_forward_workspace_bytes(int64_t tokens, int64_t n, int64_t r) {
+static size_t forward_partial_bytes(int64_t m, int64_t n) {
+  return align_up((size_t)ceil_div(n / kChunk, kFwdRun) * 4 * (size_t)m * sizeof(float), 256);
+}
+
+size_t linear_forward_workspace_bytes(int64_t tokens, int64_t m, int64_t n, int64_t r) {
   return align_up((size_t)tokens * n * sizeof(double), 256) + align_up((size_t)tokens * n * sizeof(float), 256) +
-         align_up((size_t)tokens * (r > 0 ? r : 1) * sizeof(float), 256);
+         align_up((size_t)tokens * (r > 0 ? r : 1) * sizeof(float), 256) + forward_partial_bytes(m, n);
 }
 
 ptq_status linear_forward_launch(const void* X, ptq_dtype xdt, int64_t ldx, int64_t tokens, int64_t m, int64_t n,
@@ -278,6 +351,8 @@ ptq_status linear_forward_launch(const void* X, ptq_dtype xdt, int64_t ldx, int6
   double* xt64 = reinterpret_cast<double*>(base);
   float* xt = reinterpret_cast<float*>(base + align_up((size_t)tokens * n * sizeof(double), 256));
   float* y = reinterpret_cast<float*>(reinterpret_cast<char*>(xt) + align_up((size_t)tokens * n * sizeof(float), 256));
+  float* partial = reinterpret_cast<float*>(reinterpret_cast<char*>(y) +
+                                            align_up((size_t)tokens * (r > 0 ? r : 1) * sizeof(float), 256));
   // X~ = X P Q: the rows of X go through the same transform as the rows of the residual
   ptq_status rc = lopro_rotate_weight_launch(X, xdt, ldx, tokens, n, perm, b_I, b_H, xt64, n, st);
   if (rc != PTQ_OK) return rc;
@@ -291,7 +366,7 @@ ptq_status linear_forward_launch(const void* X, ptq_dtype xdt, int64_t ldx, int6
       default: return PTQ_ERR_DTYPE;
     }
   }
-  ForwardArgs a{packed, scales, zeros, (int)m, (int)n, group, xt, y, U, r, O, ldo};
+  ForwardArgs a{packed, scales, zeros, (int)m, (int)n, group, xt, y, U, r, partial, O, ldo};
   switch (bits) {
     case 2: launch_forward<2>(a, (int)tokens, st); break;
     case 3: launch_forward<3>(a, (int)tokens, st); break;

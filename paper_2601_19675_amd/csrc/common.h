@@ -121,7 +121,9 @@ ptq_status pack_codes_launch(const uint8_t* codes, int64_t ldc, int64_t m, int64
                              hipStream_t st);
 ptq_status unpack_dequant_launch(const uint32_t* packed, int64_t m, int64_t n, int bits, const float* scales,
                                  const uint8_t* zeros, int group, double* Wq, int64_t ldq, hipStream_t st);
-size_t linear_forward_workspace_bytes(int64_t tokens, int64_t n, int64_t r);
+ptq_status pack_grids_launch(const float* scales, const uint8_t* zeros, int64_t m, int64_t ng, float* scales_t,
+                             uint8_t* zeros_t, hipStream_t st);
+size_t linear_forward_workspace_bytes(int64_t tokens, int64_t m, int64_t n, int64_t r);
 ptq_status linear_forward_launch(const void* X, ptq_dtype xdt, int64_t ldx, int64_t tokens, int64_t m, int64_t n,
                                  const uint32_t* packed, int bits, const float* scales, const uint8_t* zeros,
                                  int group, const int32_t* perm, int b_I, int b_H, const uint8_t* U,

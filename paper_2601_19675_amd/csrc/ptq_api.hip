@@ -46,7 +46,7 @@ ptq_status ptq_workspace_bytes(ptq_op op, int64_t m, int64_t n, int64_t t, int64
     case PTQ_OP_LOPRO_ROTATE_HESSIAN: *bytes = lopro_hessian_workspace_bytes(n); return PTQ_OK;
     case PTQ_OP_ACTIVATION_ABS_SUM: *bytes = abs_sum_workspace_bytes(n); return PTQ_OK;
     case PTQ_OP_SCALED_R1SVD: *bytes = r1svd_workspace_bytes(m, n); return PTQ_OK;
-    case PTQ_OP_LINEAR_FORWARD: *bytes = linear_forward_workspace_bytes(t, n, block); return PTQ_OK;
+    case PTQ_OP_LINEAR_FORWARD: *bytes = linear_forward_workspace_bytes(t, m, n, block); return PTQ_OK;
   }
   return PTQ_ERR_ARG;
 }
@@ -197,13 +197,20 @@ double ptq_average_bits(int64_t m, int64_t n, double d_q, double d_o, int64_t g,
 }
 
 ptq_status ptq_pack_codes(const uint8_t* codes, int64_t ldc, int64_t m, int64_t n, int bits, uint32_t* packed,
+                          const float* scales, const uint8_t* zeros, int group, float* scales_t, uint8_t* zeros_t,
                           ptq_stream stream) {
   if (bits != 2 && bits != 3 && bits != 4 && bits != 8) return PTQ_ERR_ARG;
   if (m < 0 || n < 0 || n % 32 != 0 || ldc < n || ldc % 16 != 0 || m > INT32_MAX / 2 || n > INT32_MAX / 2)
     return PTQ_ERR_SHAPE;
+  const bool grids = scales || zeros || scales_t || zeros_t;
+  if (grids && (group <= 0 || n % group != 0)) return PTQ_ERR_SHAPE;
   if (m == 0 || n == 0) return PTQ_OK;
-  if (!codes || !packed || misaligned(codes, 16) || misaligned(packed, 4)) return PTQ_ERR_ARG;
-  return pack_codes_launch(codes, ldc, m, n, bits, packed, static_cast<hipStream_t>(stream));
+  if (!codes || !packed || misaligned(codes, 16) || misaligned(packed, 16)) return PTQ_ERR_ARG;
+  if (grids && (!scales || !zeros || !scales_t || !zeros_t || scales == scales_t || zeros == zeros_t))
+    return PTQ_ERR_ARG;
+  ptq_status rc = pack_codes_launch(codes, ldc, m, n, bits, packed, static_cast<hipStream_t>(stream));
+  if (rc != PTQ_OK || !grids) return rc;
+  return pack_grids_launch(scales, zeros, m, n / group, scales_t, zeros_t, static_cast<hipStream_t>(stream));
 }
 
 ptq_status ptq_unpack_dequantize(const uint32_t* packed, int64_t m, int64_t n, int bits, const float* scales,
@@ -213,7 +220,7 @@ ptq_status ptq_unpack_dequantize(const uint32_t* packed, int64_t m, int64_t n, i
       n > INT32_MAX / 2)
     return PTQ_ERR_SHAPE;
   if (m == 0 || n == 0) return PTQ_OK;
-  if (!packed || !scales || !zeros || !Wq) return PTQ_ERR_ARG;
+  if (!packed || !scales || !zeros || !Wq || misaligned(packed, 16)) return PTQ_ERR_ARG;
   return unpack_dequant_launch(packed, m, n, bits, scales, zeros, group, Wq, ldq, static_cast<hipStream_t>(stream));
 }
 
@@ -230,9 +237,10 @@ ptq_status ptq_lopro_linear_forward(const void* X, ptq_dtype xdt, int64_t ldx, i
   if (rotation_shape_bad(n, b_I, b_H)) return PTQ_ERR_SHAPE;
   if (r < 0 || r > 1024) return PTQ_ERR_ARG;
   if (tokens == 0) return PTQ_OK;
-  if (!X || !packed || !scales || !zeros || !perm || !O || misaligned(perm, 16)) return PTQ_ERR_ARG;
+  if (!X || !packed || !scales || !zeros || !perm || !O || misaligned(perm, 16) || misaligned(packed, 16))
+    return PTQ_ERR_ARG;
   if (r > 0 && (!U || !V || !sigma || !s)) return PTQ_ERR_ARG;
-  if (ws_bad(ws, ws_bytes, linear_forward_workspace_bytes(tokens, n, r))) return PTQ_ERR_WORKSPACE;
+  if (ws_bad(ws, ws_bytes, linear_forward_workspace_bytes(tokens, m, n, r))) return PTQ_ERR_WORKSPACE;
   return linear_forward_launch(X, xdt, ldx, tokens, m, n, packed, bits, scales, zeros, group, perm, b_I, b_H, U, V,
                                sigma, r, s, O, ldo, ws, static_cast<hipStream_t>(stream));
 }

@@ -148,12 +148,16 @@ def test_stored_form_argument_errors_and_average_bits(lib):
     assert abs(ptq.ptq_average_bits(4096, 4096, 2, 16, 128, 16, 8) - want) < 1e-15
     assert ptq.ptq_average_bits(0, 4096, 2, 16, 128, 16, 8) == -1.0
     # packing
-    assert lib.ptq_pack_codes(p, 64, 4, 64, 5, p, None) == 1          # bits
-    assert lib.ptq_pack_codes(p, 64, 4, 48, 4, p, None) == 2          # n % 32
-    assert lib.ptq_pack_codes(p, 72, 4, 64, 4, p, None) == 2          # ldc % 16
-    assert lib.ptq_pack_codes(p + 8, 64, 4, 64, 4, p, None) == 1      # misaligned codes
-    assert lib.ptq_pack_codes(None, 64, 4, 64, 4, p, None) == 1
-    assert lib.ptq_pack_codes(p, 64, 0, 64, 4, p, None) == 0
+    g0 = (None, None, 0, None, None, None)                                # codes only
+    assert lib.ptq_pack_codes(p, 64, 4, 64, 5, p, *g0) == 1          # bits
+    assert lib.ptq_pack_codes(p, 64, 4, 48, 4, p, *g0) == 2          # n % 32
+    assert lib.ptq_pack_codes(p, 72, 4, 64, 4, p, *g0) == 2          # ldc % 16
+    assert lib.ptq_pack_codes(p + 8, 64, 4, 64, 4, p, *g0) == 1      # misaligned codes
+    assert lib.ptq_pack_codes(None, 64, 4, 64, 4, p, *g0) == 1
+    assert lib.ptq_pack_codes(p, 64, 0, 64, 4, p, *g0) == 0
+    assert lib.ptq_pack_codes(p, 64, 4, 64, 4, p, p, p, 48, p + 64, p + 128, None) == 2   # n % group
+    assert lib.ptq_pack_codes(p, 64, 4, 64, 4, p, p, p, 32, None, p + 128, None) == 1    # grids: all or none
+    assert lib.ptq_pack_codes(p, 64, 4, 64, 4, p, p, p, 32, p, p + 128, None) == 1       # in place
     assert lib.ptq_unpack_dequantize(p, 4, 64, 4, p, p, 48, p, 64, None) == 2   # n % group
     assert lib.ptq_unpack_dequantize(p, 4, 64, 4, p, p, 32, p, 32, None) == 2   # ldq < n
     assert lib.ptq_unpack_dequantize(p, 4, 64, 4, None, p, 32, p, 64, None) == 1

@@ -37,21 +37,29 @@ def test_eq12_term_by_term_on_a_square_layer():
 
 
 def test_packing_hand_worked_words():
-    # 2 bits: codes 1,2,3,0 -> 0b00_11_10_01 = 0x39 in the low byte
-    c = np.zeros((1, 16), dtype=np.uint8)
+    # 2 bits: codes 1,2,3,0 -> 0b00_11_10_01 = 0x39 in the low byte of the chunk's first word
+    c = np.zeros((1, 32), dtype=np.uint8)
     c[0, :4] = [1, 2, 3, 0]
-    assert ao.pack_codes(c, 2)[0, 0] == 0x39
+    p = ao.pack_codes(c, 2)
+    assert p.shape == (1, 1, 2) and p[0, 0, 0] == 0x39 and p[0, 0, 1] == 0
+    c[0, 16] = 2                                   # the 17th code opens the second word
+    assert ao.pack_codes(c, 2)[0, 0, 1] == 2
     # 4 bits: codes 0xA, 0xB, 0xC -> 0xCBA
-    c = np.zeros((1, 8), dtype=np.uint8)
+    c = np.zeros((1, 32), dtype=np.uint8)
     c[0, :3] = [0xA, 0xB, 0xC]
-    assert ao.pack_codes(c, 4)[0, 0] == 0xCBA
+    assert ao.pack_codes(c, 4)[0, 0, 0] == 0xCBA
     # 3 bits: code 10 occupies bits 30..32 and straddles the first two words
     c = np.zeros((1, 32), dtype=np.uint8)
     c[0, 10] = 0b101
     p = ao.pack_codes(c, 3)
-    assert p.shape == (1, 3) and p[0, 0] == (0b01 << 30) and p[0, 1] == 0b1 and p[0, 2] == 0
+    assert p.shape == (1, 1, 3) and p[0, 0, 0] == (0b01 << 30) and p[0, 0, 1] == 0b1 and p[0, 0, 2] == 0
     c[0, 31] = 0b111
-    assert ao.pack_codes(c, 3)[0, 2] == (0b111 << 29)
+    assert ao.pack_codes(c, 3)[0, 0, 2] == (0b111 << 29)
+    # chunk-major: the second chunk of every row comes after the first chunk of all rows
+    c = np.zeros((3, 64), dtype=np.uint8)
+    c[2, 32] = 3
+    p = ao.pack_codes(c, 2)
+    assert p.shape == (2, 3, 2) and p[1, 2, 0] == 3 and p.sum() == 3
 
 
 @pytest.mark.parametrize("bits", [2, 3, 4, 8])
@@ -59,7 +67,7 @@ def test_packing_round_trip_and_size(bits):
     rng = np.random.default_rng(bits)
     codes = rng.integers(0, 2 ** bits, size=(7, 160), dtype=np.uint8)
     p = ao.pack_codes(codes, bits)
-    assert p.dtype == np.uint32 and p.shape == (7, 160 * bits // 32)
+    assert p.dtype == np.uint32 and p.shape == (5, 7, bits) and p.size * 32 == codes.size * bits
     assert np.array_equal(ao.unpack_codes(p, bits, 160), codes)
 
 

@@ -96,6 +96,29 @@ def test_one_layer_through_every_stage(bits, capsys):
                                scales.cpu().numpy(), zeros.cpu().numpy())
     assert rep["unflagged"] == 0, rep["details"][:3]
 
+    # ---- the stored layer applied to a few tokens (Eq. 7 as inference runs it) -------------------
+    from oracle import artifact_oracle as ao
+    packed = _t((n // 32, m, bits), torch.int32)
+    st_, zt_ = _t((n // group, m), torch.float32), _t((n // group, m), torch.uint8)
+    ptq.ptq_pack_codes(codes, bits, packed, scales, zeros, group, st_, zt_)
+    tok = 6
+    O = _t((tok, m), torch.float32)
+    ptq.ptq_lopro_linear_forward(Xd[:tok], packed, bits, st_, zt_, group, perm, bI, bH, U8, V8, sg, s, O)
+    torch.cuda.synchronize()
+    O_g = O.cpu().numpy().astype(np.float64)
+    O_hat = X64[:tok] @ W_hat.T                     # the dense layer built from the same stored parts
+    O_true = X64[:tok] @ W64.T
+    sc_ = np.repeat(scales.cpu().numpy().astype(np.float64), group, axis=1)
+    cz_ = codes.cpu().numpy().astype(np.float64) + np.repeat(zeros.cpu().numpy().astype(np.float64), group, axis=1)
+    mag = np.abs(lo.rotate_weight(X64[:tok], pg, bI, bH)) @ (sc_ * cz_).T \
+        + (np.abs(X64[:tok] / s_g) @ np.abs(out["V"]).T * out["sigma"]) @ np.abs(out["U"])
+    assert np.all(np.abs(O_g - O_hat) <= (120 + n // 256) * 2.0 ** -24 * mag + 1e-30)
+    # and it approximates the original layer about as well as the layer error says
+    rel_out = np.linalg.norm(O_g - O_true) / np.linalg.norm(O_true)
+    assert rel_out < 3 * rel_layer
+    assert ptq.ptq_average_bits(m, n, bits, 16, group, r, 8) == pytest.approx(
+        ao.average_bits(m, n, bits, 16, group, r, 8), rel=1e-15)
+
     # ---- context (printed, not asserted: the paper's claim is about trained weights) -------------
     Hd_, dm = orc.damp(H_ref, 0.01)
     plain = orc.quantize_layer(W64, orc.inverse_cholesky_upper(Hd_), bits, group, dead=dm)

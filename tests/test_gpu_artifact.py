@@ -11,10 +11,10 @@ from oracle import r1svd_oracle as ro
 
 pytestmark = pytest.mark.gpu
 
-# float32 sums: a lane adds at most n/64 products in sequence, the wave six more levels, plus one
-# rounding each for X~, the dequantized weight and the low-rank coefficient
+# float32 sums: a lane adds the 32 products of a chunk in sequence, the chunk sums of a run, then the
+# runs and the low-rank terms in sequence, plus one rounding each for X~, the grid and the coefficients
 def _gamma(n):
-    return (n // 64 + 16) * 2.0 ** -24
+    return (32 + 8 + n // 256 + 80) * 2.0 ** -24
 
 
 def _dev(a, dtype=None):
@@ -27,15 +27,21 @@ def _dev(a, dtype=None):
 def test_pack_matches_oracle_and_unpacks(bits, m, n):
     rng = np.random.default_rng(bits * 100 + m)
     codes = rng.integers(0, 2 ** bits, size=(m, n), dtype=np.uint8)
-    packed = torch.full((m, n * bits // 32), -1, dtype=torch.int32, device="cuda")
-    ptq.ptq_pack_codes(_dev(codes), bits, packed)
-    got = packed.cpu().numpy().view(np.uint32)
-    assert np.array_equal(got, ao.pack_codes(codes, bits))
     group = 32
     scales = rng.uniform(0.001, 0.2, size=(m, n // group)).astype(np.float32)
     zeros = rng.integers(0, 2 ** bits, size=(m, n // group), dtype=np.uint8)
+    packed = torch.full((n // 32, m, bits), -1, dtype=torch.int32, device="cuda")
+    st = torch.full((n // group, m), float("nan"), dtype=torch.float32, device="cuda")
+    zt = torch.full((n // group, m), 0xEE, dtype=torch.uint8, device="cuda")
+    ptq.ptq_pack_codes(_dev(codes), bits, packed, _dev(scales), _dev(zeros), group, st, zt)
+    got = packed.cpu().numpy().view(np.uint32)
+    assert np.array_equal(got, ao.pack_codes(codes, bits))
+    assert np.array_equal(st.cpu().numpy(), scales.T) and np.array_equal(zt.cpu().numpy(), zeros.T)
+    only = torch.full_like(packed, -1)
+    ptq.ptq_pack_codes(_dev(codes), bits, only)           # codes alone
+    assert torch.equal(only, packed)
     Wq = torch.full((m, n), float("nan"), dtype=torch.float64, device="cuda")
-    ptq.ptq_unpack_dequantize(packed, n, bits, _dev(scales), _dev(zeros), group, Wq)
+    ptq.ptq_unpack_dequantize(packed, n, bits, st, zt, group, Wq)
     assert np.array_equal(Wq.cpu().numpy(), ao.dequantize(codes, scales, zeros, group))
 
 
@@ -56,12 +62,14 @@ def test_unpack_reproduces_what_the_solve_wrote():
     zeros = torch.empty((m, n // group), dtype=torch.uint8, device="cuda")
     Wq = torch.empty((m, n), dtype=torch.float64, device="cuda")
     ptq.ptq_quantize_layer(to_device(Ws), U, dead, bits, group, 128, codes, scales, zeros, Wq, None)
-    packed = torch.empty((m, n * bits // 32), dtype=torch.int32, device="cuda")
-    ptq.ptq_pack_codes(codes, bits, packed)
+    packed = torch.empty((n // 32, m, bits), dtype=torch.int32, device="cuda")
+    st = torch.empty((n // group, m), dtype=torch.float32, device="cuda")
+    zt = torch.empty((n // group, m), dtype=torch.uint8, device="cuda")
+    ptq.ptq_pack_codes(codes, bits, packed, scales, zeros, group, st, zt)
     back = torch.empty_like(Wq)
-    ptq.ptq_unpack_dequantize(packed, n, bits, scales, zeros, group, back)
+    ptq.ptq_unpack_dequantize(packed, n, bits, st, zt, group, back)
     assert torch.equal(back, Wq)
-    assert packed.numel() * 4 * 8 == m * n * bits
+    assert packed.numel() * 32 == m * n * bits
 
 
 def _random_layer(rng, m, n, r, bits, group):
@@ -80,11 +88,13 @@ def _random_layer(rng, m, n, r, bits, group):
 def _forward(X_t, codes, scales, zeros, perm, Uc, Vc, sigma, s, bits, group, bI, bH):
     m, n = codes.shape
     tokens = X_t.shape[0]
-    packed = torch.empty((m, n * bits // 32), dtype=torch.int32, device="cuda")
-    ptq.ptq_pack_codes(_dev(codes), bits, packed)
+    packed = torch.empty((n // 32, m, bits), dtype=torch.int32, device="cuda")
+    st = torch.empty((n // group, m), dtype=torch.float32, device="cuda")
+    zt = torch.empty((n // group, m), dtype=torch.uint8, device="cuda")
+    ptq.ptq_pack_codes(_dev(codes), bits, packed, _dev(scales), _dev(zeros), group, st, zt)
     O = torch.full((tokens, m), float("nan"), dtype=torch.float32, device="cuda")
     r = Uc.shape[0]
-    ptq.ptq_lopro_linear_forward(X_t, packed, bits, _dev(scales), _dev(zeros), group, _dev(perm), bI, bH,
+    ptq.ptq_lopro_linear_forward(X_t, packed, bits, st, zt, group, _dev(perm), bI, bH,
                                  _dev(Uc) if r else None, _dev(Vc) if r else None,
                                  torch.from_numpy(sigma.copy()).cuda() if r else None, _dev(s) if r else None, O)
     torch.cuda.synchronize()
@@ -97,8 +107,10 @@ def _check_forward(X64, got, packed, codes, scales, zeros, perm, Uc, Vc, sigma, 
     sig = sigma.astype(np.float64)
     ref = ao.linear_forward(X64, packed, bits, scales, zeros, group, p64, bI, bH, Uc, Vc, sig, s)
     Xt = lo.rotate_weight(X64, p64, bI, bH)
-    Wq = ao.dequantize(codes, scales, zeros, group)
-    mag = np.abs(Xt) @ np.abs(Wq).T
+    # the kernel sums scale * code * x and scale * zero * x separately (the second does not depend on the row)
+    sc = np.repeat(scales.astype(np.float64), group, axis=1)
+    zz = np.repeat(zeros.astype(np.float64), group, axis=1)
+    mag = np.abs(Xt) @ (sc * (codes.astype(np.float64) + zz)).T
     if Uc.shape[0]:
         mag += (np.abs(X64 / s) @ np.abs(ro.e4m3_decode(Vc)).T * sig) @ np.abs(ro.e4m3_decode(Uc))
     err = np.abs(got - ref)
@@ -128,7 +140,7 @@ def test_forward_without_rotation_or_low_rank_is_a_plain_dequantized_product():
     X_t = _dev(rng.standard_normal((2, n)).astype(np.float32))
     got, _ = _forward(X_t, codes, scales, zeros, perm, Uc, Vc, sigma, s, bits, group, n, 256)
     ref = X_t.to(torch.float64).cpu().numpy() @ ao.dequantize(codes, scales, zeros, group).T
-    assert np.allclose(got, ref, rtol=0, atol=_gamma(n) * np.max(np.abs(ref)) * 40)
+    assert np.allclose(got, ref, rtol=0, atol=_gamma(n) * np.max(np.abs(ref)) * 100)
 
 
 def test_forward_full_size_attention_projection(capsys):
