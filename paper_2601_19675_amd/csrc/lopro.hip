@@ -65,21 +65,33 @@ __global__ __launch_bounds__(256) void keys_kernel(const double* __restrict__ pa
 }
 
 // perm[rank] = column, rank = number of columns that come before it (ties: lower index first).
-// A workgroup ranks 32 columns; the comparisons against all n keys are split over eight lanes
-// per column and the eight counts are added with shuffles.
+// A workgroup ranks 16 columns; the comparisons against all n keys are split over sixteen lanes
+// per column and the sixteen counts are added with shuffles.  The keys are staged in LDS in
+// pieces of kRankStage (every lane reads all of them; from global memory the loop is a chain of
+// load latencies).
+constexpr int kRankStage = 4096;
 __global__ __launch_bounds__(256) void rank_kernel(const double* __restrict__ keys, int n, int descending,
                                                    int32_t* __restrict__ perm) {
-  const int i = blockIdx.x * 32 + (threadIdx.x >> 3), sl = threadIdx.x & 7;
+  __shared__ double ks[kRankStage];
+  const int i = blockIdx.x * 16 + (threadIdx.x >> 4), sl = threadIdx.x & 15;
   const double ki = i < n ? keys[i] : 0.0;
   int rank = 0;
-  for (int j = sl; j < n; j += 8) {
-    const double kj = keys[j];
-    const bool first = descending ? (kj > ki) : (kj < ki);
-    rank += (first || (kj == ki && j < i)) ? 1 : 0;
+  for (int j0 = 0; j0 < n; j0 += kRankStage) {
+    const int cnt = min(kRankStage, n - j0);
+    __syncthreads();
+    for (int j = threadIdx.x; j < cnt; j += 256) ks[j] = keys[j0 + j];
+    __syncthreads();
+#pragma unroll 8
+    for (int j = sl; j < cnt; j += 16) {
+      const double kj = ks[j];
+      const bool first = descending ? (kj > ki) : (kj < ki);
+      rank += (first || (kj == ki && j0 + j < i)) ? 1 : 0;
+    }
   }
   rank += __shfl_xor(rank, 1);
   rank += __shfl_xor(rank, 2);
   rank += __shfl_xor(rank, 4);
+  rank += __shfl_xor(rank, 8);
   if (i < n && sl == 0) perm[rank] = i;
 }
 
@@ -294,7 +306,7 @@ ptq_status lopro_order_launch(const void* R, ptq_dtype rdt, int64_t ldr, int64_t
     default: return PTQ_ERR_DTYPE;
   }
   keys_kernel<<<(unsigned)ceil_div(n, 256), 256, 0, st>>>(partial, H, ldh, (int)m, (int)n, k);
-  rank_kernel<<<(unsigned)ceil_div(n, 32), 256, 0, st>>>(k, (int)n, descending, perm);
+  rank_kernel<<<(unsigned)ceil_div(n, 16), 256, 0, st>>>(k, (int)n, descending, perm);
   PTQ_HIP_CHECK_LAUNCH();
   return PTQ_OK;
 }
