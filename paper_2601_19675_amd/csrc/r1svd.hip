@@ -96,6 +96,12 @@ __device__ __forceinline__ float load_dev(const float* p) {
 __device__ __forceinline__ void store_dev(float* p, float v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+__device__ __forceinline__ int load_dev(const int* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void store_dev(int* p, int v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 // four adjacent floats, 16-byte aligned, as two 8-byte accesses
 __device__ __forceinline__ void store_dev4(float* p, float x, float y, float z, float w) {
   unsigned long long* q = reinterpret_cast<unsigned long long*>(p);
@@ -743,6 +749,288 @@ __global__ __launch_bounds__(kChainThreads) void chain_kernel(ChainArgs a) {
     for (int k = tid; k < a.r; k += T) a.sigma16[k] = 0x7e00;
 }
 
+// ---- the whole loop on a matrix that fits the registers of the chip ---------------------------
+// When the matrix has at most 256 tiles of 256 x 256 (64 MB of float32: the attention
+// projections of a 7B model), a workgroup keeps ONE TILE, not a block of rows, for the whole
+// loop.  Tile (p, q) then exchanges 256 partial sums per product instead of a whole partial
+// vector: its share of u = A v goes to the Q tiles of its row of tiles, its share of z = A^T u
+// to the P tiles of its column, and each tile adds up the partial sums it needs itself.  So
+// an application moves 1/8 of the data of the row-block form, has no separate summation step,
+// and its two barriers involve Q resp. P workgroups instead of all of them; only the norms of
+// a rank's last vectors need everybody (once per rank).
+//
+// The power of two that keeps the vectors in range travels with the data: every tile attaches
+// the largest exponent of its piece of v to its partial u; the tiles of a row of tiles see
+// all pieces, take the maximum and scale u instead of v (the same thing, A being linear).
+// Partial sums alternate between two buffers, so that a tile may write those of the next
+// application while a slower tile of its group still reads the last ones.
+constexpr int kTile = 256;
+constexpr int kTilePart = kTile + 32;   // 256 partial sums and, in the next word, the exponent
+
+struct TileArgs {
+  float* A; int m, n;
+  const float* S; int64_t lds; int r, it;
+  uint8_t* U; uint8_t* V; uint16_t* sigma16;
+  int P, Q;             // tiles down and across; the grid has P * Q workgroups
+  float* upart;         // [2][P][Q][kTilePart]
+  float* zpart;         // [2][P][Q][kTilePart]
+  double* normy;        // [2][P]: sum of squares of a rank's y by row of tiles
+  double* normp;        // [2][Q]: the same for p by column of tiles
+  double* ud; double* vd; double* sigma;   // the last rank's decoded triplet, for the residual kernel
+  unsigned* rowbar;     // P words, kBarrierLine apart, preset to 0
+  unsigned* colbar;     // Q words, kBarrierLine apart, preset to 0
+  unsigned* bar;        // the two-level barrier of all workgroups
+  int* abort;
+  unsigned spin_limit;
+};
+
+__global__ void tile_init_kernel(unsigned* words, int count, int* abort) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < count) words[i] = 0u;
+  if (i == 0) *abort = 0;
+}
+
+// Barrier of the `members` workgroups that share `word` (same rules as grid_barrier).
+__device__ __forceinline__ void group_barrier(unsigned* word, unsigned members, unsigned phase, int* abort,
+                                              unsigned spin_limit) {
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    atomicAdd(word, 1u);
+    const unsigned target = members * phase;
+    unsigned spins = 0;
+    while (__hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+      if ((spins & 255u) == 0 && __hip_atomic_load(abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) break;
+      if (++spins > spin_limit) {
+        __hip_atomic_store(abort, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        break;
+      }
+      __builtin_amdgcn_s_sleep(1);
+    }
+  }
+  __syncthreads();
+}
+
+// 2^-e as a double for the exponent that travels with the data (INT_MIN: nothing to scale).
+__device__ __forceinline__ double unscale(int e) {
+  if (e == INT_MIN) return 1.0;
+  return scalbn(1.0, -(e > 126 ? 126 : (e < -126 ? -126 : e)));
+}
+
+// Sum of squares of an LDS array over the workgroup, fixed order; the same value in every thread.
+template <int T>
+__device__ __forceinline__ double block_sum_squares(const double* x, int count, double* scratch) {
+  double t = 0.0;
+  for (int j = threadIdx.x; j < count; j += T) t = fma(x[j], x[j], t);
+  t = wave_sum(t);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = t;
+  __syncthreads();
+  double total = 0.0;
+#pragma unroll
+  for (int wv = 0; wv < T / kWave; ++wv) total += scratch[wv];
+  return total;
+}
+
+// Entry (threadIdx.x & 255) of the sum of `count` partial vectors `stride` floats apart, for a
+// workgroup of 512 threads: each half of the workgroup takes every other vector, eight loads in
+// flight per thread (one after the other they are a chain of round trips to memory), the two
+// halves meet in `tmp` (2 x 256 doubles).  Valid in threads 0..255 after the call.
+__device__ __forceinline__ double sum_partials(const float* base, int count, int64_t stride, double* tmp) {
+  const int e = threadIdx.x & (kTile - 1), half = threadIdx.x >> 8;
+  double t = 0.0;
+  for (int j0 = half; j0 < count; j0 += 16) {
+    float x[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) x[k] = j0 + 2 * k < count ? load_dev(base + (int64_t)(j0 + 2 * k) * stride + e) : 0.f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) t += (double)x[k];
+  }
+  __syncthreads();
+  tmp[half * kTile + e] = t;
+  __syncthreads();
+  return tmp[e] + tmp[kTile + e];
+}
+
+__global__ __launch_bounds__(512) void tile_chain_kernel(TileArgs a) {
+  constexpr int T = 512, kWaves = T / kWave, kRowsPerWave = kTile / kWaves;   // 8 waves x 32 rows
+  __shared__ double zsum[kTile];        // this column of tiles' piece of z (= v of the next application, p at the end)
+  __shared__ float vsh[kTile];          // ... as the float32 vector the products use
+  __shared__ double ush[kTile];         // this row of tiles' piece of u, scaled
+  __shared__ float red2[kWaves][kTile];
+  __shared__ double udsh[kTile], vdsh[kTile];
+  __shared__ double tmp[2 * kTile];
+  __shared__ double fin[kWaves];
+  __shared__ int esh[kWaves];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int m = a.m, n = a.n, P = a.P, Q = a.Q;
+  const int p = blockIdx.x / Q, q = blockIdx.x - p * Q;
+  const int row_base = p * kTile, col_base = q * kTile;
+  const int my_row0 = row_base + w * kRowsPerWave;   // this wave's 32 rows
+  const int my_col = col_base + lane * 4;            // this lane's 4 columns
+  const int64_t part_stride = (int64_t)P * Q * kTilePart;
+
+  float wt[kRowsPerWave][4];
+#pragma unroll
+  for (int i = 0; i < kRowsPerWave; ++i) {
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (my_row0 + i < m && my_col < n) v = *reinterpret_cast<const float4*>(a.A + (int64_t)(my_row0 + i) * n + my_col);
+    wt[i][0] = v.x; wt[i][1] = v.y; wt[i][2] = v.z; wt[i][3] = v.w;
+  }
+
+  unsigned rphase = 0, cphase = 0, gphase = 0;
+  int app = 0;
+  for (int k = 0; k < a.r; ++k) {
+    for (int i = 0; i <= a.it; ++i, ++app) {
+      const int buf = app & 1;
+      // ---- v for this column of tiles: the sketch vector, or the sum of the partial z of the tiles above and below
+      int e_loc = INT_MIN;
+      if (i == 0) {
+        const int col = col_base + tid;
+        if (tid < kTile) vsh[tid] = col < n ? a.S[(int64_t)k * a.lds + col] : 0.f;
+      } else {
+        const double t = sum_partials(a.zpart + (int64_t)(buf ^ 1) * part_stride + (int64_t)q * kTilePart, P,
+                                      (int64_t)Q * kTilePart, tmp);
+        if (tid < kTile) {
+          vsh[tid] = (float)t;
+          if (t != 0.0 && fabs(t) < __builtin_inf()) e_loc = ilogb(t);
+        }
+      }
+      if (i > 0) {   // largest exponent of the piece: wave maximum, then over the waves that hold data
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) e_loc = max(e_loc, __shfl_xor(e_loc, o));
+        if (lane == 0) esh[w] = e_loc;
+      }
+      __syncthreads();
+      if (i > 0) e_loc = max(max(esh[0], esh[1]), max(esh[2], esh[3]));
+
+      // ---- this tile's share of u = A v: 32 rows per wave, reduced over the 64 lanes
+      {
+        const float4 v = *reinterpret_cast<const float4*>(&vsh[lane * 4]);
+#pragma unroll
+        for (int h = 0; h < kRowsPerWave / 16; ++h) {
+          double us[16];
+#pragma unroll
+          for (int j = 0; j < 16; ++j) {
+            const float* wr = wt[h * 16 + j];
+            us[j] = (double)fmaf(wr[3], v.w, fmaf(wr[2], v.z, fmaf(wr[1], v.y, wr[0] * v.x)));
+          }
+          int width = 32;
+#pragma unroll
+          for (int cnt = 16; cnt > 1; cnt >>= 1, width >>= 1) {
+            const bool upper = (lane & width) != 0;
+#pragma unroll
+            for (int j = 0; j < cnt / 2; ++j) {
+              const double send = upper ? us[j] : us[j + cnt / 2];
+              const double keep = upper ? us[j + cnt / 2] : us[j];
+              us[j] = keep + __shfl_xor(send, width);
+            }
+          }
+          us[0] += __shfl_xor(us[0], 2);
+          us[0] += __shfl_xor(us[0], 1);
+          if ((lane & 3) == 0)
+            store_dev(a.upart + (int64_t)buf * part_stride + ((int64_t)p * Q + q) * kTilePart + w * kRowsPerWave +
+                          h * 16 + (lane >> 2),
+                      (float)us[0]);
+        }
+        if (tid == 0)
+          store_dev(reinterpret_cast<int*>(a.upart + (int64_t)buf * part_stride + ((int64_t)p * Q + q) * kTilePart +
+                                           kTile),
+                    e_loc);
+      }
+      group_barrier(a.rowbar + p * kBarrierLine, (unsigned)Q, ++rphase, a.abort, a.spin_limit);
+
+      // ---- u for this row of tiles: the partial sums of the tiles to the left and right, scaled
+      {
+        const float* row_parts = a.upart + (int64_t)buf * part_stride + (int64_t)p * Q * kTilePart;
+        int e = tid < Q ? load_dev(reinterpret_cast<const int*>(row_parts + (int64_t)tid * kTilePart + kTile)) : INT_MIN;
+        const double t = sum_partials(row_parts, Q, kTilePart, tmp);
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) e = max(e, __shfl_xor(e, o));
+        if (lane == 0) esh[w] = e;
+        __syncthreads();
+        e = max(max(esh[0], esh[1]), max(esh[2], esh[3]));   // Q <= 256: the first four waves
+        if (tid < kTile) ush[tid] = t * unscale(e);
+      }
+      __syncthreads();
+
+      // ---- this tile's share of z = A^T u: 4 columns per lane, reduced over the 8 waves
+      {
+        float zs[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < kRowsPerWave; ++j) {
+          const float uf = (float)ush[w * kRowsPerWave + j];
+#pragma unroll
+          for (int c = 0; c < 4; ++c) zs[c] = fmaf(wt[j][c], uf, zs[c]);
+        }
+        *reinterpret_cast<float4*>(&red2[w][lane * 4]) = make_float4(zs[0], zs[1], zs[2], zs[3]);
+      }
+      __syncthreads();
+      if (tid < kTile) {
+        double t = 0.0;
+#pragma unroll
+        for (int wv = 0; wv < kWaves; ++wv) t += (double)red2[wv][tid];
+        store_dev(a.zpart + (int64_t)buf * part_stride + ((int64_t)p * Q + q) * kTilePart + tid, (float)t);
+      }
+      group_barrier(a.colbar + q * kBarrierLine, (unsigned)P, ++cphase, a.abort, a.spin_limit);
+    }
+
+    // ---- the stored triplet of rank k.  y is ush (every tile of the row of tiles has it), p is the sum of the last
+    // partial z of this column of tiles; their norms need all rows resp. columns of tiles.
+    const int last = (app - 1) & 1, nb = k & 1;
+    {
+      const double t = sum_partials(a.zpart + (int64_t)last * part_stride + (int64_t)q * kTilePart, P,
+                                    (int64_t)Q * kTilePart, tmp);
+      if (tid < kTile) zsum[tid] = t;
+    }
+    __syncthreads();
+    const double y2 = block_sum_squares<T>(ush, kTile, fin);     // rows and columns outside the matrix hold zeros
+    const double p2 = block_sum_squares<T>(zsum, kTile, fin);
+    if (tid == 0) {
+      if (q == 0) store_dev(a.normy + nb * P + p, y2);
+      if (p == 0) store_dev(a.normp + nb * Q + q, p2);
+    }
+    grid_barrier(a.bar, ++gphase, a.abort, a.spin_limit);
+    const double ny = sqrt(block_sum<T>(a.normy + nb * P, P, fin));
+    const double np = sqrt(block_sum<T>(a.normp + nb * Q, Q, fin));
+    const bool dead = !(ny > 0.0) || !(np > 0.0);
+    const uint16_t h = dead ? 0 : fp16_encode_pos(np / ny);
+    const double sg = fp16_decode_pos(h);
+    if (blockIdx.x == 0 && tid == 0) { a.sigma16[k] = h; *a.sigma = sg; }
+    if (tid < kTile) {
+      const int row = row_base + tid, col = col_base + tid;
+      const uint8_t cu = dead ? 0 : e4m3_encode(ush[tid] / ny);
+      const uint8_t cv = dead ? 0 : e4m3_encode(zsum[tid] / np);
+      udsh[tid] = e4m3_decode(cu);
+      vdsh[tid] = e4m3_decode(cv);
+      if (q == 0 && row < m) { a.U[(int64_t)k * m + row] = cu; a.ud[row] = udsh[tid]; }
+      if (p == 0 && col < n) { a.V[(int64_t)k * n + col] = cv; a.vd[col] = vdsh[tid]; }
+    }
+    __syncthreads();
+    // the deflation by this rank, in registers (the last rank's is left to the residual kernel)
+    if (k + 1 < a.r) {
+      double dv[4];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) dv[c] = sg * vdsh[lane * 4 + c];
+#pragma unroll
+      for (int j = 0; j < kRowsPerWave; ++j) {
+        const double uj = udsh[w * kRowsPerWave + j];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) wt[j][c] = (float)((double)wt[j][c] - uj * dv[c]);
+      }
+    }
+    __syncthreads();
+  }
+
+#pragma unroll
+  for (int i = 0; i < kRowsPerWave; ++i)
+    if (my_row0 + i < m && my_col < n)
+      *reinterpret_cast<float4*>(a.A + (int64_t)(my_row0 + i) * n + my_col) =
+          make_float4(wt[i][0], wt[i][1], wt[i][2], wt[i][3]);
+  if (blockIdx.x == 0 && __hip_atomic_load(a.abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)
+    for (int k = tid; k < a.r; k += T) a.sigma16[k] = 0x7e00;
+}
+
 // R = (A - sigma u v^T) diag(s)^-1: the last rank's deflation and the way back from the scaled
 // matrix (Algorithm 1).
 __global__ __launch_bounds__(256) void residual_kernel(const float* __restrict__ A, int m, int n,
@@ -782,11 +1070,17 @@ inline PassShape pass_shape(int64_t n) {
   return {16, 1};
 }
 
+// workspace of the tile form: partial sums (two buffers each), norms, group barriers
+constexpr size_t kTilePartBytes = (size_t)2 * kComputeUnits * kTilePart * sizeof(float);
+constexpr size_t kTileNormBytes = (size_t)2 * kComputeUnits * sizeof(double);
+constexpr size_t kTileBarBytes = (size_t)kComputeUnits * kBarrierLine * sizeof(unsigned);
+constexpr size_t kTileWorkspaceBytes = 2 * kTilePartBytes + 2 * kTileNormBytes + 2 * kTileBarBytes;
+
 constexpr int kMaxChainApps = 16384;   // applications (rank x iteration) one cooperative launch can hold
 constexpr size_t kChainVectorBytes = size_t{16} << 20;   // room for their float32 copies of z
 
 struct Layout {
-  size_t A, zpart, z, z32, u, unrm2, normpart, ud, vd, scalars, barrier, expo, zapp, total;
+  size_t A, zpart, z, z32, u, unrm2, normpart, ud, vd, scalars, barrier, expo, zapp, tile, total;
   int parts;    // workgroups of a pass when every step is a launch of its own
   int groups;   // workgroups of the single cooperative launch
 };
@@ -812,6 +1106,7 @@ inline Layout layout(int64_t m, int64_t n) {
   L.barrier = take((size_t)kBarrierWords * sizeof(unsigned));
   L.expo = take((size_t)kMaxChainApps * sizeof(int));
   L.zapp = take(kChainVectorBytes);
+  L.tile = take(kTileWorkspaceBytes);
   L.total = o;
   return L;
 }
@@ -853,6 +1148,22 @@ template <int NS, int R>
 bool launch_chain(ChainArgs& a, int groups, hipStream_t st) {
   return ceil_div(a.m, R) <= groups ? launch_chain_as<NS, R, true>(a, groups, st)
                                     : launch_chain_as<NS, R, false>(a, groups, st);
+}
+
+bool launch_tile_chain(TileArgs& a, hipStream_t st) {
+  int dev = 0, coop = 0, cus = 0, per_cu = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return false;
+  if (hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev) != hipSuccess || !coop) return false;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return false;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, tile_chain_kernel, 512, 0) != hipSuccess) return false;
+  if ((int64_t)per_cu * cus < (int64_t)a.P * a.Q) return false;
+  void* params[] = {&a};
+  if (hipLaunchCooperativeKernel(reinterpret_cast<const void*>(tile_chain_kernel), dim3((unsigned)(a.P * a.Q)),
+                                 dim3(512), params, 0, st) != hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  return true;
 }
 
 }  // namespace
@@ -908,12 +1219,33 @@ ptq_status r1svd_launch(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m, in
     default: return PTQ_ERR_DTYPE;
   }
 
-  // One cooperative launch for the whole loop where the device can hold it; PTQ_R1SVD_LAUNCH=steps
-  // in the environment selects the launch-per-step form (same arithmetic, for comparison).
+  // One cooperative launch for the whole loop where the device can hold it.  PTQ_R1SVD_LAUNCH in the
+  // environment selects another form of the same loop, for comparison and tests: "rows" the single
+  // launch over row blocks even where the tile form applies, "steps" one launch per step.
   const char* mode = std::getenv("PTQ_R1SVD_LAUNCH");
   bool chained = false;
+  // a matrix of at most 256 tiles stays in registers, a tile per workgroup
+  const int64_t TP = ceil_div(m, kTile), TQ = ceil_div(n, kTile);
+  if (r > 0 && TP * TQ <= kComputeUnits && !(mode && (std::strcmp(mode, "steps") == 0 || std::strcmp(mode, "rows") == 0))) {
+    char* tw = base + L.tile;
+    float* upart = reinterpret_cast<float*>(tw);
+    float* zp2 = reinterpret_cast<float*>(tw + kTilePartBytes);
+    double* normy = reinterpret_cast<double*>(tw + 2 * kTilePartBytes);
+    double* normp = reinterpret_cast<double*>(tw + 2 * kTilePartBytes + kTileNormBytes);
+    unsigned* rowbar = reinterpret_cast<unsigned*>(tw + 2 * kTilePartBytes + 2 * kTileNormBytes);
+    unsigned* colbar = reinterpret_cast<unsigned*>(tw + 2 * kTilePartBytes + 2 * kTileNormBytes + kTileBarBytes);
+    unsigned* bar = reinterpret_cast<unsigned*>(base + L.barrier);
+    int* abort_flag = reinterpret_cast<int*>(counter + 1);
+    // rowbar and colbar are adjacent: one fill for both, one for the barrier of all workgroups
+    const int words = (int)(2 * kTileBarBytes / sizeof(unsigned));
+    tile_init_kernel<<<(unsigned)ceil_div(words, 256), 256, 0, st>>>(rowbar, words, abort_flag);
+    tile_init_kernel<<<(unsigned)ceil_div(kBarrierWords, 256), 256, 0, st>>>(bar, kBarrierWords, abort_flag);
+    TileArgs ta{A, (int)m, (int)n, S, lds, r, it, U, V, sigma16, (int)TP, (int)TQ, upart, zp2, normy, normp,
+                ud, vd, scal + 2, rowbar, colbar, bar, abort_flag, 1u << 21};
+    chained = launch_tile_chain(ta, st);
+  }
   const int64_t zstride = (int64_t)align_up((size_t)n * sizeof(float), 256) / (int64_t)sizeof(float);
-  if (r > 0 && (int64_t)r * (it + 1) <= kMaxChainApps &&
+  if (!chained && r > 0 && (int64_t)r * (it + 1) <= kMaxChainApps &&
       (size_t)r * (it + 1) * zstride * sizeof(float) <= kChainVectorBytes &&
       !(mode && std::strcmp(mode, "steps") == 0)) {
     int* expo = reinterpret_cast<int*>(base + L.expo);

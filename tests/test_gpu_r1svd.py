@@ -24,14 +24,15 @@ pytestmark = pytest.mark.gpu
 FOLLOW_TOL = 2e-3
 
 
-@pytest.fixture(params=["single", "steps"])
+@pytest.fixture(params=["single", "rows", "steps"])
 def launch_mode(request, monkeypatch):
-    """The loop runs as one cooperative launch (default) or as one launch per step; the library
-    reads PTQ_R1SVD_LAUNCH at every call.  Both forms are held to the oracle."""
-    if request.param == "steps":
-        monkeypatch.setenv("PTQ_R1SVD_LAUNCH", "steps")
-    else:
+    """The loop runs as one cooperative launch -- over tiles where the matrix fits the chip's registers
+    (default), or over row blocks ("rows") -- or as one launch per step ("steps"); the library reads
+    PTQ_R1SVD_LAUNCH at every call.  All forms are held to the oracle."""
+    if request.param == "single":
         monkeypatch.delenv("PTQ_R1SVD_LAUNCH", raising=False)
+    else:
+        monkeypatch.setenv("PTQ_R1SVD_LAUNCH", request.param)
     return request.param
 
 
