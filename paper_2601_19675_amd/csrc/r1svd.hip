@@ -96,12 +96,6 @@ __device__ __forceinline__ float load_dev(const float* p) {
 __device__ __forceinline__ void store_dev(float* p, float v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ int load_dev(const int* p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void store_dev(int* p, int v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
 // four adjacent floats, 16-byte aligned, as two 8-byte accesses
 __device__ __forceinline__ void store_dev4(float* p, float x, float y, float z, float w) {
   unsigned long long* q = reinterpret_cast<unsigned long long*>(p);
@@ -755,15 +749,23 @@ __global__ __launch_bounds__(kChainThreads) void chain_kernel(ChainArgs a) {
 // loop.  Tile (p, q) then exchanges 256 partial sums per product instead of a whole partial
 // vector: its share of u = A v goes to the Q tiles of its row of tiles, its share of z = A^T u
 // to the P tiles of its column, and each tile adds up the partial sums it needs itself.  So
-// an application moves 1/8 of the data of the row-block form, has no separate summation step,
-// and its two barriers involve Q resp. P workgroups instead of all of them; only the norms of
-// a rank's last vectors need everybody (once per rank).
+// an application moves 1/8 of the data of the row-block form and has no separate summation
+// step; only the norms of a rank's last vectors need everybody (once per rank).
+//
+// There is no barrier between the steps of an application.  Every exchanged number is an
+// 8-byte word, the float in the low half and the number of the application in the high half,
+// written with one device-coherent store; a reader loads the words it needs and loads them
+// again until their high halves show the application it is waiting for.  Store, signal and
+// load thus cost one trip to memory instead of three (wait for the store, arrive and poll,
+// load).  A reader gives up after spin_limit rounds and raises `abort`, like the barriers.
 //
 // The power of two that keeps the vectors in range travels with the data: every tile attaches
 // the largest exponent of its piece of v to its partial u; the tiles of a row of tiles see
 // all pieces, take the maximum and scale u instead of v (the same thing, A being linear).
 // Partial sums alternate between two buffers, so that a tile may write those of the next
-// application while a slower tile of its group still reads the last ones.
+// application while a slower tile of its group still reads the last ones: a tile writes
+// application i + 2 only after it has seen application i + 1 from every tile of the group, and
+// each of those published it after it had read application i.
 constexpr int kTile = 256;
 constexpr int kTilePart = kTile + 32;   // 256 partial sums and, in the next word, the exponent
 
@@ -772,13 +774,11 @@ struct TileArgs {
   const float* S; int64_t lds; int r, it;
   uint8_t* U; uint8_t* V; uint16_t* sigma16;
   int P, Q;             // tiles down and across; the grid has P * Q workgroups
-  float* upart;         // [2][P][Q][kTilePart]
-  float* zpart;         // [2][P][Q][kTilePart]
+  unsigned long long* upart;   // [2][P][Q][kTilePart] tagged words, preset to 0 (tags start at 1)
+  unsigned long long* zpart;   // [2][P][Q][kTilePart]
   double* normy;        // [2][P]: sum of squares of a rank's y by row of tiles
   double* normp;        // [2][Q]: the same for p by column of tiles
   double* ud; double* vd; double* sigma;   // the last rank's decoded triplet, for the residual kernel
-  unsigned* rowbar;     // P words, kBarrierLine apart, preset to 0
-  unsigned* colbar;     // Q words, kBarrierLine apart, preset to 0
   unsigned* bar;        // the two-level barrier of all workgroups
   int* abort;
   unsigned spin_limit;
@@ -790,25 +790,22 @@ __global__ void tile_init_kernel(unsigned* words, int count, int* abort) {
   if (i == 0) *abort = 0;
 }
 
-// Barrier of the `members` workgroups that share `word` (same rules as grid_barrier).
-__device__ __forceinline__ void group_barrier(unsigned* word, unsigned members, unsigned phase, int* abort,
-                                              unsigned spin_limit) {
-  __builtin_amdgcn_s_waitcnt(0);
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    atomicAdd(word, 1u);
-    const unsigned target = members * phase;
-    unsigned spins = 0;
-    while (__hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
-      if ((spins & 255u) == 0 && __hip_atomic_load(abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) break;
-      if (++spins > spin_limit) {
-        __hip_atomic_store(abort, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        break;
-      }
-      __builtin_amdgcn_s_sleep(1);
-    }
+__device__ __forceinline__ void store_tagged(unsigned long long* p, unsigned bits, unsigned tag) {
+  __hip_atomic_store(p, (unsigned long long)bits | ((unsigned long long)tag << 32), __ATOMIC_RELAXED,
+                     __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned long long load_tagged(const unsigned long long* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// One round of waiting for tagged words: false when the wait is to be abandoned.
+__device__ __forceinline__ bool keep_waiting(unsigned& spins, int* abort, unsigned spin_limit) {
+  if ((spins & 63u) == 63u && __hip_atomic_load(abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return false;
+  if (++spins > spin_limit) {
+    __hip_atomic_store(abort, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return false;
   }
-  __syncthreads();
+  __builtin_amdgcn_s_sleep(1);
+  return true;
 }
 
 // 2^-e as a double for the exponent that travels with the data (INT_MIN: nothing to scale).
@@ -832,19 +829,30 @@ __device__ __forceinline__ double block_sum_squares(const double* x, int count, 
   return total;
 }
 
-// Entry (threadIdx.x & 255) of the sum of `count` partial vectors `stride` floats apart, for a
-// workgroup of 512 threads: each half of the workgroup takes every other vector, eight loads in
-// flight per thread (one after the other they are a chain of round trips to memory), the two
-// halves meet in `tmp` (2 x 256 doubles).  Valid in threads 0..255 after the call.
-__device__ __forceinline__ double sum_partials(const float* base, int count, int64_t stride, double* tmp) {
+// Entry (threadIdx.x & 255) of the sum of `count` partial vectors `stride` words apart, each word
+// tagged `tag`, for a workgroup of 512 threads: each half of the workgroup takes every other
+// vector, eight loads in flight per thread (one after the other they are a chain of trips to
+// memory), repeated until all eight carry the tag; the two halves meet in `tmp` (2 x 256
+// doubles).  Valid in threads 0..255 after the call.
+__device__ __forceinline__ double sum_partials(const unsigned long long* base, int count, int64_t stride,
+                                               unsigned tag, double* tmp, int* abort, unsigned spin_limit) {
   const int e = threadIdx.x & (kTile - 1), half = threadIdx.x >> 8;
   double t = 0.0;
+  unsigned spins = 0;
   for (int j0 = half; j0 < count; j0 += 16) {
-    float x[8];
+    unsigned long long x[8];
+    bool ready;
+    do {
+      ready = true;
 #pragma unroll
-    for (int k = 0; k < 8; ++k) x[k] = j0 + 2 * k < count ? load_dev(base + (int64_t)(j0 + 2 * k) * stride + e) : 0.f;
+      for (int k = 0; k < 8; ++k) {
+        x[k] = (unsigned long long)tag << 32;
+        if (j0 + 2 * k < count) x[k] = load_tagged(base + (int64_t)(j0 + 2 * k) * stride + e);
+        ready = ready && (unsigned)(x[k] >> 32) == tag;
+      }
+    } while (!ready && keep_waiting(spins, abort, spin_limit));
 #pragma unroll
-    for (int k = 0; k < 8; ++k) t += (double)x[k];
+    for (int k = 0; k < 8; ++k) t += (double)__uint_as_float((unsigned)x[k]);
   }
   __syncthreads();
   tmp[half * kTile + e] = t;
@@ -878,11 +886,12 @@ __global__ __launch_bounds__(512) void tile_chain_kernel(TileArgs a) {
     wt[i][0] = v.x; wt[i][1] = v.y; wt[i][2] = v.z; wt[i][3] = v.w;
   }
 
-  unsigned rphase = 0, cphase = 0, gphase = 0;
+  unsigned gphase = 0;
   int app = 0;
   for (int k = 0; k < a.r; ++k) {
     for (int i = 0; i <= a.it; ++i, ++app) {
       const int buf = app & 1;
+      const unsigned tag = (unsigned)app + 1u;   // what this application writes; it reads z tagged `app`
       // ---- v for this column of tiles: the sketch vector, or the sum of the partial z of the tiles above and below
       int e_loc = INT_MIN;
       if (i == 0) {
@@ -890,7 +899,7 @@ __global__ __launch_bounds__(512) void tile_chain_kernel(TileArgs a) {
         if (tid < kTile) vsh[tid] = col < n ? a.S[(int64_t)k * a.lds + col] : 0.f;
       } else {
         const double t = sum_partials(a.zpart + (int64_t)(buf ^ 1) * part_stride + (int64_t)q * kTilePart, P,
-                                      (int64_t)Q * kTilePart, tmp);
+                                      (int64_t)Q * kTilePart, (unsigned)app, tmp, a.abort, a.spin_limit);
         if (tid < kTile) {
           vsh[tid] = (float)t;
           if (t != 0.0 && fabs(t) < __builtin_inf()) e_loc = ilogb(t);
@@ -929,22 +938,27 @@ __global__ __launch_bounds__(512) void tile_chain_kernel(TileArgs a) {
           us[0] += __shfl_xor(us[0], 2);
           us[0] += __shfl_xor(us[0], 1);
           if ((lane & 3) == 0)
-            store_dev(a.upart + (int64_t)buf * part_stride + ((int64_t)p * Q + q) * kTilePart + w * kRowsPerWave +
-                          h * 16 + (lane >> 2),
-                      (float)us[0]);
+            store_tagged(a.upart + (int64_t)buf * part_stride + ((int64_t)p * Q + q) * kTilePart + w * kRowsPerWave +
+                             h * 16 + (lane >> 2),
+                         __float_as_uint((float)us[0]), tag);
         }
         if (tid == 0)
-          store_dev(reinterpret_cast<int*>(a.upart + (int64_t)buf * part_stride + ((int64_t)p * Q + q) * kTilePart +
-                                           kTile),
-                    e_loc);
+          store_tagged(a.upart + (int64_t)buf * part_stride + ((int64_t)p * Q + q) * kTilePart + kTile,
+                       (unsigned)e_loc, tag);
       }
-      group_barrier(a.rowbar + p * kBarrierLine, (unsigned)Q, ++rphase, a.abort, a.spin_limit);
 
       // ---- u for this row of tiles: the partial sums of the tiles to the left and right, scaled
       {
-        const float* row_parts = a.upart + (int64_t)buf * part_stride + (int64_t)p * Q * kTilePart;
-        int e = tid < Q ? load_dev(reinterpret_cast<const int*>(row_parts + (int64_t)tid * kTilePart + kTile)) : INT_MIN;
-        const double t = sum_partials(row_parts, Q, kTilePart, tmp);
+        const unsigned long long* row_parts = a.upart + (int64_t)buf * part_stride + (int64_t)p * Q * kTilePart;
+        int e = INT_MIN;
+        if (tid < Q) {
+          unsigned spins = 0;
+          unsigned long long hw;
+          do hw = load_tagged(row_parts + (int64_t)tid * kTilePart + kTile);
+          while ((unsigned)(hw >> 32) != tag && keep_waiting(spins, a.abort, a.spin_limit));
+          e = (int)(unsigned)hw;
+        }
+        const double t = sum_partials(row_parts, Q, kTilePart, tag, tmp, a.abort, a.spin_limit);
 #pragma unroll
         for (int o = 32; o >= 1; o >>= 1) e = max(e, __shfl_xor(e, o));
         if (lane == 0) esh[w] = e;
@@ -970,9 +984,9 @@ __global__ __launch_bounds__(512) void tile_chain_kernel(TileArgs a) {
         double t = 0.0;
 #pragma unroll
         for (int wv = 0; wv < kWaves; ++wv) t += (double)red2[wv][tid];
-        store_dev(a.zpart + (int64_t)buf * part_stride + ((int64_t)p * Q + q) * kTilePart + tid, (float)t);
+        store_tagged(a.zpart + (int64_t)buf * part_stride + ((int64_t)p * Q + q) * kTilePart + tid,
+                     __float_as_uint((float)t), tag);
       }
-      group_barrier(a.colbar + q * kBarrierLine, (unsigned)P, ++cphase, a.abort, a.spin_limit);
     }
 
     // ---- the stored triplet of rank k.  y is ush (every tile of the row of tiles has it), p is the sum of the last
@@ -980,7 +994,7 @@ __global__ __launch_bounds__(512) void tile_chain_kernel(TileArgs a) {
     const int last = (app - 1) & 1, nb = k & 1;
     {
       const double t = sum_partials(a.zpart + (int64_t)last * part_stride + (int64_t)q * kTilePart, P,
-                                    (int64_t)Q * kTilePart, tmp);
+                                    (int64_t)Q * kTilePart, (unsigned)app, tmp, a.abort, a.spin_limit);
       if (tid < kTile) zsum[tid] = t;
     }
     __syncthreads();
@@ -1070,11 +1084,10 @@ inline PassShape pass_shape(int64_t n) {
   return {16, 1};
 }
 
-// workspace of the tile form: partial sums (two buffers each), norms, group barriers
-constexpr size_t kTilePartBytes = (size_t)2 * kComputeUnits * kTilePart * sizeof(float);
+// workspace of the tile form: tagged partial sums (two buffers each) and norms
+constexpr size_t kTilePartBytes = (size_t)2 * kComputeUnits * kTilePart * sizeof(unsigned long long);
 constexpr size_t kTileNormBytes = (size_t)2 * kComputeUnits * sizeof(double);
-constexpr size_t kTileBarBytes = (size_t)kComputeUnits * kBarrierLine * sizeof(unsigned);
-constexpr size_t kTileWorkspaceBytes = 2 * kTilePartBytes + 2 * kTileNormBytes + 2 * kTileBarBytes;
+constexpr size_t kTileWorkspaceBytes = 2 * kTilePartBytes + 2 * kTileNormBytes;
 
 constexpr int kMaxChainApps = 16384;   // applications (rank x iteration) one cooperative launch can hold
 constexpr size_t kChainVectorBytes = size_t{16} << 20;   // room for their float32 copies of z
@@ -1228,20 +1241,18 @@ ptq_status r1svd_launch(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m, in
   const int64_t TP = ceil_div(m, kTile), TQ = ceil_div(n, kTile);
   if (r > 0 && TP * TQ <= kComputeUnits && !(mode && (std::strcmp(mode, "steps") == 0 || std::strcmp(mode, "rows") == 0))) {
     char* tw = base + L.tile;
-    float* upart = reinterpret_cast<float*>(tw);
-    float* zp2 = reinterpret_cast<float*>(tw + kTilePartBytes);
+    unsigned long long* upart = reinterpret_cast<unsigned long long*>(tw);
+    unsigned long long* zp2 = reinterpret_cast<unsigned long long*>(tw + kTilePartBytes);
     double* normy = reinterpret_cast<double*>(tw + 2 * kTilePartBytes);
     double* normp = reinterpret_cast<double*>(tw + 2 * kTilePartBytes + kTileNormBytes);
-    unsigned* rowbar = reinterpret_cast<unsigned*>(tw + 2 * kTilePartBytes + 2 * kTileNormBytes);
-    unsigned* colbar = reinterpret_cast<unsigned*>(tw + 2 * kTilePartBytes + 2 * kTileNormBytes + kTileBarBytes);
     unsigned* bar = reinterpret_cast<unsigned*>(base + L.barrier);
     int* abort_flag = reinterpret_cast<int*>(counter + 1);
-    // rowbar and colbar are adjacent: one fill for both, one for the barrier of all workgroups
-    const int words = (int)(2 * kTileBarBytes / sizeof(unsigned));
-    tile_init_kernel<<<(unsigned)ceil_div(words, 256), 256, 0, st>>>(rowbar, words, abort_flag);
+    // tags of an earlier call must not be mistaken for this one's: the tagged words start at zero
+    const int words = (int)(2 * kTilePartBytes / sizeof(unsigned));
+    tile_init_kernel<<<(unsigned)ceil_div(words, 256), 256, 0, st>>>(reinterpret_cast<unsigned*>(tw), words, abort_flag);
     tile_init_kernel<<<(unsigned)ceil_div(kBarrierWords, 256), 256, 0, st>>>(bar, kBarrierWords, abort_flag);
     TileArgs ta{A, (int)m, (int)n, S, lds, r, it, U, V, sigma16, (int)TP, (int)TQ, upart, zp2, normy, normp,
-                ud, vd, scal + 2, rowbar, colbar, bar, abort_flag, 1u << 21};
+                ud, vd, scal + 2, bar, abort_flag, 1u << 21};
     chained = launch_tile_chain(ta, st);
   }
   const int64_t zstride = (int64_t)align_up((size_t)n * sizeof(float), 256) / (int64_t)sizeof(float);
