@@ -262,39 +262,6 @@ struct RowBlock {
     }
   }
 
-  // The same subtraction on a block that is already in registers.
-  __device__ __forceinline__ void deflate(int m, int n, int row0, double sg, const double* ud, const double* vd) {
-    const int tid = threadIdx.x;
-#pragma unroll
-    for (int s = 0; s < NS; ++s) {
-      const int col = 4 * (tid + T * s);
-      if (col >= n) continue;
-      double dv[4];
-#pragma unroll
-      for (int c = 0; c < 4; ++c) dv[c] = sg * vec(vd + col + c);
-#pragma unroll
-      for (int i = 0; i < R; ++i) {
-        if (row0 + i >= m) continue;
-        const double ui = vec(ud + row0 + i);
-#pragma unroll
-        for (int c = 0; c < 4; ++c) w[s][i][c] = (float)((double)w[s][i][c] - ui * dv[c]);
-      }
-    }
-  }
-
-  __device__ __forceinline__ void store(float* A, int m, int n, int row0) const {
-    const int tid = threadIdx.x;
-#pragma unroll
-    for (int s = 0; s < NS; ++s) {
-      const int col = 4 * (tid + T * s);
-#pragma unroll
-      for (int i = 0; i < R; ++i)
-        if (col < n && row0 + i < m)
-          *reinterpret_cast<float4*>(A + (int64_t)(row0 + i) * n + col) =
-              make_float4(w[s][i][0], w[s][i][1], w[s][i][2], w[s][i][3]);
-    }
-  }
-
   // u = (block) v for the R rows, left in ush[0..R) (and in u_out, if not null); then
   // zacc += (block)^T u.  v is vin times the power of two rs.
   // Returns the sum of squares of the R entries of u (valid in thread 0).
@@ -522,11 +489,11 @@ __global__ __launch_bounds__(256) void finish_kernel(FinishArgs a) {
   }
 }
 
-// ---- the whole loop in one launch ------------------------------------------------------------
+// ---- the whole loop in one launch, row blocks streamed -----------------------------------------
 // All ranks and applications in one cooperative launch: the workgroups meet at a barrier
-// between the steps that the separate kernels above end with.  If every row block has a
-// workgroup of its own, the block never leaves the registers: A is then read once and written
-// once, and the loop runs at the speed of the barriers and the partial-vector exchange.
+// between the steps that the separate kernels above end with, and stream their row blocks from
+// memory in every application.  This is the form for matrices too large for the tile form
+// further down (the MLP layers).
 //
 // The barrier is a counter in global memory that only grows.  A waiting workgroup gives up
 // after spin_limit polls and raises `abort`, which makes every later wait return at once: the
@@ -607,9 +574,7 @@ __device__ __forceinline__ double block_sum(const double* ptr, int count, double
   return total;
 }
 
-// RESIDENT: every row block has a workgroup of its own (number of blocks <= grid size) and stays
-// in that workgroup's registers from the first application to the last.
-template <int NS, int R, bool RESIDENT>
+template <int NS, int R>
 __global__ __launch_bounds__(kChainThreads) void chain_kernel(ChainArgs a) {
   constexpr int T = kChainThreads;
   constexpr int kGroups = T / kReduceCols;   // 32 partial vectors in flight per column
@@ -624,8 +589,6 @@ __global__ __launch_bounds__(kChainThreads) void chain_kernel(ChainArgs a) {
   unsigned phase = 0;
   int app = 0;
   double sg_prev = 0.0;
-  RowBlock<T, NS, R, true> own;
-  if (RESIDENT) own.load(a.A, m, n, b * R, false, 0.0, a.ud, a.vd);   // all zeros for b >= tiles
 
   for (int k = 0; k < a.r; ++k) {
     for (int i = 0; i <= a.it; ++i, ++app) {
@@ -646,20 +609,13 @@ __global__ __launch_bounds__(kChainThreads) void chain_kernel(ChainArgs a) {
       // of each die after its first miss, and they are safe here because each application's z
       // has an address of its own that no cache can hold an older copy of.
       const float* v_in = i == 0 ? a.S + (int64_t)k * a.lds : a.zapp + (int64_t)(app - 1) * a.zstride;
-      if constexpr (RESIDENT) {
-        if (b < tiles) {
-          if (i == 0 && k > 0) own.deflate(m, n, b * R, sg_prev, a.ud, a.vd);
-          unrm2 = own.apply(v_in, rs, m, n, b * R, a.u, zacc, red, ush);
-        }
-      } else {
-        for (int tile = b; tile < tiles; tile += G) {
-          const float* vin = v_in;
-          const double* vd = a.vd;
-          asm volatile("" : "+s"(vin), "+s"(vd));
-          RowBlock<T, NS, R, true> blk;
-          blk.load(a.A, m, n, tile * R, i == 0 && k > 0, sg_prev, a.ud, vd);
-          unrm2 += blk.apply(vin, rs, m, n, tile * R, a.u, zacc, red, ush);
-        }
+      for (int tile = b; tile < tiles; tile += G) {
+        const float* vin = v_in;
+        const double* vd = a.vd;
+        asm volatile("" : "+s"(vin), "+s"(vd));
+        RowBlock<T, NS, R, true> blk;
+        blk.load(a.A, m, n, tile * R, i == 0 && k > 0, sg_prev, a.ud, vd);
+        unrm2 += blk.apply(vin, rs, m, n, tile * R, a.u, zacc, red, ush);
       }
       store_partial<T, NS, true>(zacc, a.zpart, n, b, G);
       if (tid == 0) store_dev(a.unrm2 + b, unrm2);
@@ -738,7 +694,6 @@ __global__ __launch_bounds__(kChainThreads) void chain_kernel(ChainArgs a) {
     grid_barrier(a.bar, ++phase, a.abort, a.spin_limit);
   }
 
-  if (RESIDENT && b < tiles) own.store(a.A, m, n, b * R);
   if (b == 0 && __hip_atomic_load(a.abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)
     for (int k = tid; k < a.r; k += T) a.sigma16[k] = 0x7e00;
 }
@@ -1133,34 +1088,27 @@ void launch_pass(const PassArgs& a, int parts, hipStream_t st) {
 }
 
 // Whether `groups` workgroups of the chain kernel can be resident at once on the current device.
-template <int NS, int R, bool RESIDENT>
+template <int NS, int R>
 bool chain_fits(int groups) {
   int dev = 0, coop = 0, cus = 0, per_cu = 0;
   if (hipGetDevice(&dev) != hipSuccess) return false;
   if (hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev) != hipSuccess || !coop) return false;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return false;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, chain_kernel<NS, R, RESIDENT>, kChainThreads, 0) !=
-      hipSuccess)
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, chain_kernel<NS, R>, kChainThreads, 0) != hipSuccess)
     return false;
   return (int64_t)per_cu * cus >= groups;
 }
 
-template <int NS, int R, bool RESIDENT>
-bool launch_chain_as(ChainArgs& a, int groups, hipStream_t st) {
-  if (!chain_fits<NS, R, RESIDENT>(groups)) return false;
+template <int NS, int R>
+bool launch_chain(ChainArgs& a, int groups, hipStream_t st) {
+  if (!chain_fits<NS, R>(groups)) return false;
   void* params[] = {&a};
-  if (hipLaunchCooperativeKernel(reinterpret_cast<const void*>(chain_kernel<NS, R, RESIDENT>),
-                                 dim3((unsigned)groups), dim3(kChainThreads), params, 0, st) != hipSuccess) {
+  if (hipLaunchCooperativeKernel(reinterpret_cast<const void*>(chain_kernel<NS, R>), dim3((unsigned)groups),
+                                 dim3(kChainThreads), params, 0, st) != hipSuccess) {
     (void)hipGetLastError();
     return false;
   }
   return true;
-}
-
-template <int NS, int R>
-bool launch_chain(ChainArgs& a, int groups, hipStream_t st) {
-  return ceil_div(a.m, R) <= groups ? launch_chain_as<NS, R, true>(a, groups, st)
-                                    : launch_chain_as<NS, R, false>(a, groups, st);
 }
 
 bool launch_tile_chain(TileArgs& a, hipStream_t st) {
