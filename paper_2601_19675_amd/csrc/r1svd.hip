@@ -1184,6 +1184,9 @@ ptq_status r1svd_launch(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m, in
   // environment selects another form of the same loop, for comparison and tests: "rows" the single
   // launch over row blocks even where the tile form applies, "steps" one launch per step.
   const char* mode = std::getenv("PTQ_R1SVD_LAUNCH");
+  // rounds a workgroup waits for another before it gives up (PTQ_R1SVD_SPIN_LIMIT: for tests of that path)
+  unsigned spin_limit = 1u << 21;
+  if (const char* lim = std::getenv("PTQ_R1SVD_SPIN_LIMIT")) spin_limit = (unsigned)std::strtoul(lim, nullptr, 10);
   bool chained = false;
   // a matrix of at most 256 tiles stays in registers, a tile per workgroup
   const int64_t TP = ceil_div(m, kTile), TQ = ceil_div(n, kTile);
@@ -1200,7 +1203,7 @@ ptq_status r1svd_launch(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m, in
     tile_init_kernel<<<(unsigned)ceil_div(words, 256), 256, 0, st>>>(reinterpret_cast<unsigned*>(tw), words, abort_flag);
     tile_init_kernel<<<(unsigned)ceil_div(kBarrierWords, 256), 256, 0, st>>>(bar, kBarrierWords, abort_flag);
     TileArgs ta{A, (int)m, (int)n, S, lds, r, it, U, V, sigma16, (int)TP, (int)TQ, upart, zp2, normy, normp,
-                ud, vd, scal + 2, bar, abort_flag, 1u << 21};
+                ud, vd, scal + 2, bar, abort_flag, spin_limit};
     chained = launch_tile_chain(ta, st);
   }
   const int64_t zstride = (int64_t)align_up((size_t)n * sizeof(float), 256) / (int64_t)sizeof(float);
@@ -1214,7 +1217,7 @@ ptq_status r1svd_launch(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m, in
     const int init = apps > kBarrierWords ? apps : kBarrierWords;
     chain_init_kernel<<<(unsigned)ceil_div(init, 256), 256, 0, st>>>(expo, apps, bar, abort_flag);
     ChainArgs ca{A, (int)m, (int)n, S, lds, r, it, U, V, sigma16, zpart, z, u, unrm2, normpart, ud, vd,
-                 reinterpret_cast<float*>(base + L.zapp), zstride, scal + 2, expo, bar, abort_flag, 1u << 21};
+                 reinterpret_cast<float*>(base + L.zapp), zstride, scal + 2, expo, bar, abort_flag, spin_limit};
     switch (ps.ns) {
       case 1: chained = launch_chain<1, 16>(ca, L.groups, st); break;
       case 2: chained = launch_chain<2, 16>(ca, L.groups, st); break;

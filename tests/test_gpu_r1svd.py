@@ -223,6 +223,22 @@ def test_r1svd_sigma_beyond_fp16_range(launch_mode):
     _check(W.astype(np.float64), np.ones(n), S, 3, got)
 
 
+@pytest.mark.parametrize("mode", ["single", "rows"])
+def test_r1svd_gives_up_cleanly_when_the_wait_limit_is_reached(mode, monkeypatch):
+    # a wait limit of zero rounds: the first workgroup that finds a partial sum not there yet raises the
+    # abort flag, everybody stops waiting, the kernel runs to its end on whatever it has and marks every
+    # sigma as NaN; the next ordinary call is unaffected
+    Ws, W64, s, S = _case(1024, 1024, "f32", 1300, 3)
+    if mode == "rows":
+        monkeypatch.setenv("PTQ_R1SVD_LAUNCH", "rows")
+    monkeypatch.setenv("PTQ_R1SVD_SPIN_LIMIT", "0")
+    bad = _run_gpu(to_device(Ws), s, S, 2)
+    assert np.all(np.isnan(bad[2]))
+    monkeypatch.delenv("PTQ_R1SVD_SPIN_LIMIT")
+    good = _run_gpu(to_device(Ws), s, S, 2)
+    _check(W64, s, S, 2, good)
+
+
 def test_activation_abs_sum_many_tokens():
     spec = wl.scaled(wl.CONFIGS["C2"].layers[0], t=65536)
     Xs = wl.gen_activations(spec)
