@@ -339,3 +339,60 @@ def test_end_to_end_small_fp32_layer():
     rel = float(out[0])
     assert abs(rel - rel_ref) <= 1e-4
     assert rel <= rel_rtn
+
+
+def test_step_can_be_captured_in_a_graph_and_replayed():
+    """The four calls of the path enqueue kernels only (no allocation, no memset, no synchronization), so a
+    whole step can be captured in a HIP graph.  Replays with new activations in the same buffer must match
+    the eager calls exactly."""
+    m, n, t, bits, group, block = 64, 512, 1536, 4, 128, 128
+    spec = wl.LayerSpec("graph", m, n, t, dtype="bf16", x_sigma=1.0, layer_id=1400)
+    Wd = to_device(wl.gen_weight(spec))
+    Xs = [to_device(wl.gen_activations(wl.LayerSpec("graph", m, n, t, dtype="bf16", x_sigma=1.0, layer_id=1400 + k)))
+          for k in range(3)]
+    d = "cuda"
+    X = torch.empty_like(Xs[0])
+    H = torch.zeros((n, n), dtype=torch.float64, device=d)
+    U = torch.empty((n, n), dtype=torch.float64, device=d)
+    dead = torch.empty(n, dtype=torch.uint8, device=d)
+    info = torch.empty(2, dtype=torch.int32, device=d)
+    codes = torch.empty((m, n), dtype=torch.uint8, device=d)
+    scales = torch.empty((m, n // group), dtype=torch.float32, device=d)
+    zeros = torch.empty((m, n // group), dtype=torch.uint8, device=d)
+    Wq = torch.empty((m, n), dtype=torch.float64, device=d)
+    out = torch.zeros(3, dtype=torch.float64, device=d)
+    ws = torch.empty(max(ptq.ptq_workspace_bytes(op, m, n, t, block) for op in range(4)), dtype=torch.uint8, device=d)
+
+    def step():
+        H.zero_()
+        ptq.ptq_hessian_accumulate(H, X, ws)
+        ptq.ptq_damped_cholesky_inv(H, 0.01, U, dead, info, ws)
+        ptq.ptq_quantize_layer(Wd, U, dead, bits, group, block, codes, scales, zeros, Wq, None, ws)
+        ptq.ptq_layer_error(Wd, Wq, H, out, ws)
+
+    eager = []
+    for Xk in Xs:                       # eager results first (this also warms every kernel up)
+        X.copy_(Xk)
+        step()
+        torch.cuda.synchronize()
+        eager.append((codes.clone(), scales.clone(), zeros.clone(), out.clone()))
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        X.copy_(Xs[0])
+        step()
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.current_stream().wait_stream(side)
+    for k in (1, 2, 0, 1):              # replays, with eager work and synchronization in between
+        X.copy_(Xs[k])
+        codes.zero_()
+        out.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert info.cpu().tolist() == [0, 0]
+        assert torch.equal(codes, eager[k][0]) and torch.equal(scales, eager[k][1])
+        assert torch.equal(zeros, eager[k][2]) and torch.equal(out, eager[k][3])
