@@ -211,6 +211,25 @@ def test_r1svd_full_size_attention_projection(capsys):
     assert np.all(np.isfinite(ref["sigma"])) and ref["sigma"][0] > 0
 
 
+def test_r1svd_full_size_mlp_projection(capsys):
+    """A Llama-7B-shaped down projection (4096 x 11008, 172 MB in float32): too large for the tile form, the
+    row blocks are streamed from memory in every application.  The paper's setting, everything compared."""
+    import time
+    spec = wl.LayerSpec("down_proj", 4096, 11008, 2048, x_sigma=1.0, layer_id=31)
+    r, it = 16, 8
+    Ws = wl.gen_weight_with_low_rank_part(spec, rank=8)
+    W64 = wl.to_f64(Ws)
+    S = wl.gen_sketch_vectors(spec, r)
+    s = ro.activation_scale(wl.channel_scales(spec) * np.sqrt(2.0 / np.pi))
+    t0 = time.time()
+    got = _run_gpu(to_device(Ws), s, S, it)
+    t1 = time.time()
+    ref = _check(W64, s, S, it, got)
+    with capsys.disabled():
+        print(f"  [r1svd 4096x11008 r=16 it=8: gpu call {t1 - t0:.2f}s incl. transfers, oracle {time.time() - t1:.1f}s, "
+              f"followed {ref['followed']} near-ties, sigma {ref['sigma'][:3]}...]", flush=True)
+
+
 def test_r1svd_sigma_beyond_fp16_range(launch_mode):
     rng = np.random.default_rng(31)
     m, n = 64, 256
