@@ -218,6 +218,37 @@ struct PassArgs {
   const double* vd;         // n
 };
 
+// Sums over the 64 lanes of a wave of R per-lane values, in float64, left in red[wave * R + row].
+// Rows go in chunks of at most 8: C sums over the 64 lanes at once.  Each exchange halves the
+// number of values a lane carries (the lane keeps the rows its bit selects and hands over the
+// others), so C = 8 takes 4 + 2 + 1 exchanges and three plain ones instead of 8 x 6.
+template <int R>
+__device__ __forceinline__ void wave_row_sums(const float (&us)[R], double* red) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  constexpr int C = R < 8 ? R : 8;
+#pragma unroll
+  for (int h = 0; h < R / C; ++h) {
+    double ud[C];
+#pragma unroll
+    for (int i = 0; i < C; ++i) ud[i] = (double)us[h * C + i];
+    int width = 32;
+#pragma unroll
+    for (int cnt = C; cnt > 1; cnt >>= 1, width >>= 1) {
+      const bool upper = (lane & width) != 0;
+#pragma unroll
+      for (int j = 0; j < cnt / 2; ++j) {
+        const double send = upper ? ud[j] : ud[j + cnt / 2];
+        const double keep = upper ? ud[j + cnt / 2] : ud[j];
+        ud[j] = keep + __shfl_xor(send, width);
+      }
+    }
+#pragma unroll
+    for (; width >= 1; width >>= 1) ud[0] += __shfl_xor(ud[0], width);
+    constexpr int kLanesPerRow = kWave / C;
+    if ((lane & (kLanesPerRow - 1)) == 0) red[wave * R + h * C + lane / kLanesPerRow] = ud[0];
+  }
+}
+
 // A block of R rows of A in the registers of a workgroup of T threads: a thread owns 4 adjacent
 // columns in each of NS sweeps of 4 T columns.
 // COH: the vectors come from other workgroups of the same launch (see load_dev).
@@ -269,7 +300,7 @@ struct RowBlock {
   __device__ __forceinline__ double apply(const float* vin, float rs, int m, int n, int row0, double* u_out,
                                           double (&zacc)[NS][4], double* red, double* ush) {
     constexpr int kWaves = T / kWave;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x;
     float us[R];
 #pragma unroll
     for (int i = 0; i < R; ++i) us[i] = 0.f;
@@ -283,32 +314,7 @@ struct RowBlock {
       for (int i = 0; i < R; ++i)
         us[i] = fmaf(w[s][i][3], v.w, fmaf(w[s][i][2], v.z, fmaf(w[s][i][1], v.y, fmaf(w[s][i][0], v.x, us[i]))));
     }
-    // rows in chunks of at most 8: C float64 sums over the 64 lanes at once.  Each exchange
-    // halves the number of values a lane carries (the lane keeps the rows its bit selects and
-    // hands over the others), so C = 8 takes 4 + 2 + 1 exchanges and three plain ones instead
-    // of 8 x 6
-    constexpr int C = R < 8 ? R : 8;
-#pragma unroll
-    for (int h = 0; h < R / C; ++h) {
-      double ud[C];
-#pragma unroll
-      for (int i = 0; i < C; ++i) ud[i] = (double)us[h * C + i];
-      int width = 32;
-#pragma unroll
-      for (int cnt = C; cnt > 1; cnt >>= 1, width >>= 1) {
-        const bool upper = (lane & width) != 0;
-#pragma unroll
-        for (int j = 0; j < cnt / 2; ++j) {
-          const double send = upper ? ud[j] : ud[j + cnt / 2];
-          const double keep = upper ? ud[j + cnt / 2] : ud[j];
-          ud[j] = keep + __shfl_xor(send, width);
-        }
-      }
-#pragma unroll
-      for (; width >= 1; width >>= 1) ud[0] += __shfl_xor(ud[0], width);
-      constexpr int kLanesPerRow = kWave / C;
-      if ((lane & (kLanesPerRow - 1)) == 0) red[wave * R + h * C + lane / kLanesPerRow] = ud[0];
-    }
+    wave_row_sums<R>(us, red);
     __syncthreads();
     if (tid < R) {
       double t = 0.0;
@@ -698,6 +704,381 @@ __global__ __launch_bounds__(kChainThreads) void chain_kernel(ChainArgs a) {
     for (int k = tid; k < a.r; k += T) a.sigma16[k] = 0x7e00;
 }
 
+// ---- the loop on a bfloat16 weight that is never rewritten ------------------------------------
+// The running matrix of rank k is  A_k = W diag(s) - sum_{j<k} sigma_j U_j V_j^T  with the STORED
+// factors.  Instead of keeping A_k in memory (float32, rewritten at every rank) the products are
+// taken from the weight as it was handed over:
+//     u = A_k v   = W (s o v)     - sum_j sigma_j U_j (V_j . v)
+//     z = A_k^T u = s o (W^T u)   - sum_j sigma_j V_j (U_j . u)
+// so that an application streams 2 bytes per entry instead of 4, nothing is ever written back,
+// and the first pass that builds W diag(s) disappears.  The corrections are small: a workgroup
+// owns a contiguous range of rows and every 256th block of 16 columns, keeps the decoded entries
+// of all U_j for its rows and of all V_j for its columns in LDS, and
+//   * the k numbers V_j . v are summed over the columns as they are produced (each workgroup adds
+//     its columns' share when it finishes them; the partial sums cross the grid barrier that ends
+//     the application anyway),
+//   * the k numbers U_j . u are summed over a workgroup's rows while it streams them and cross
+//     the barrier that precedes the summation of the partial z vectors.
+// Every sum has a fixed order.  The float32 scale fl(s) is used on both sides, so the matrix the
+// loop sees is W diag(fl(s)): a relative change of 2^-24 per column, the size of the rounding
+// the float32 copy of A makes in the other forms.
+constexpr int kMaxStreamRank = 16;
+
+struct StreamArgs {
+  const uint16_t* W; int64_t ldw; int m, n;
+  const float* sf;          // n: the activation scale rounded to float32
+  const float* S; int64_t lds; int r, it;
+  uint8_t* U; uint8_t* V; uint16_t* sigma16;
+  float* zpart; double* z; double* u; double* unrm2; double* normpart;
+  double* cpart;            // [kMaxStreamRank][kComputeUnits]: shares of V_j . v
+  double* dpart;            // [kMaxStreamRank][kComputeUnits]: shares of U_j . u
+  float* zapp; int64_t zstride;
+  int* expo; unsigned* bar; int* abort; unsigned spin_limit;
+  int rows_own, cols_own;   // row lengths of the two LDS tables
+};
+
+__device__ __forceinline__ float bf16_lo(unsigned x) { return __uint_as_float(x << 16); }
+__device__ __forceinline__ float bf16_hi(unsigned x) { return __uint_as_float(x & 0xffff0000u); }
+
+// R rows of W, 8 adjacent columns per thread in each of NS sweeps of 8 T columns, two bfloat16 per
+// register.
+template <int T, int NS, int R>
+struct PackedRowBlock {
+  unsigned w[NS][R][4];
+
+  // rows row0 .. row0+R-1 below row_end (zeros beyond, and beyond column n)
+  __device__ __forceinline__ void load(const uint16_t* W, int64_t ldw, int n, int row0, int row_end) {
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      const int col = 8 * ((int)threadIdx.x + T * s);
+#pragma unroll
+      for (int i = 0; i < R; ++i) {
+        uint4 q = make_uint4(0u, 0u, 0u, 0u);
+        if (col < n && row0 + i < row_end) q = *reinterpret_cast<const uint4*>(W + (int64_t)(row0 + i) * ldw + col);
+        w[s][i][0] = q.x; w[s][i][1] = q.y; w[s][i][2] = q.z; w[s][i][3] = q.w;
+      }
+    }
+  }
+
+  // us[i] = this thread's share of (row i) . (s o v),  v = vin * rs
+  __device__ __forceinline__ void times_vector(const float* vin, const float* sf, float rs, int n, float (&us)[R]) const {
+#pragma unroll
+    for (int i = 0; i < R; ++i) us[i] = 0.f;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      const int col = 8 * ((int)threadIdx.x + T * s);
+      float sv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      if (col < n) {
+        const float4 v0 = *reinterpret_cast<const float4*>(vin + col), v1 = *reinterpret_cast<const float4*>(vin + col + 4);
+        const float4 s0 = *reinterpret_cast<const float4*>(sf + col), s1 = *reinterpret_cast<const float4*>(sf + col + 4);
+        sv[0] = v0.x * rs * s0.x; sv[1] = v0.y * rs * s0.y; sv[2] = v0.z * rs * s0.z; sv[3] = v0.w * rs * s0.w;
+        sv[4] = v1.x * rs * s1.x; sv[5] = v1.y * rs * s1.y; sv[6] = v1.z * rs * s1.z; sv[7] = v1.w * rs * s1.w;
+      }
+#pragma unroll
+      for (int i = 0; i < R; ++i)
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+          us[i] = fmaf(bf16_hi(w[s][i][c]), sv[2 * c + 1], fmaf(bf16_lo(w[s][i][c]), sv[2 * c], us[i]));
+    }
+  }
+
+  // zacc += (block)^T uf
+  __device__ __forceinline__ void transposed_times(const float (&uf)[R], double (&zacc)[NS][8]) {
+    // the packed words are unpacked again here: kept from times_vector, the unpacked floats would
+    // take twice the registers of the block for the whole reduction in between
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+#pragma unroll
+      for (int i = 0; i < R; ++i)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) asm volatile("" : "+v"(w[s][i][c]));
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      float zt[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int i = 0; i < R; ++i)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          zt[2 * c] = fmaf(bf16_lo(w[s][i][c]), uf[i], zt[2 * c]);
+          zt[2 * c + 1] = fmaf(bf16_hi(w[s][i][c]), uf[i], zt[2 * c + 1]);
+        }
+#pragma unroll
+      for (int c = 0; c < 8; ++c) zacc[s][c] += (double)zt[c];
+    }
+  }
+};
+
+// sum over the workgroups of one row of a [kMaxStreamRank][kComputeUnits] table, by one wave
+__device__ __forceinline__ double share_sum(const double* row, int G) {
+  double x[kComputeUnits / kWave];
+#pragma unroll
+  for (int q = 0; q < kComputeUnits / kWave; ++q) {
+    const int p = (int)(threadIdx.x & 63) + q * kWave;
+    x[q] = p < G ? load_dev(row + p) : 0.0;
+  }
+  double t = 0.0;
+#pragma unroll
+  for (int q = 0; q < kComputeUnits / kWave; ++q) t += x[q];
+  return wave_sum(t);
+}
+
+template <int NS, int R>
+__global__ __launch_bounds__(kChainThreads) void stream_chain_kernel(StreamArgs a) {
+  constexpr int T = kChainThreads;
+  constexpr int kWaves = T / kWave;
+  constexpr int kGroups = T / kReduceCols;
+  constexpr int KR = kMaxStreamRank;
+  extern __shared__ float own[];          // decoded U_j for the own rows, then V_j for the own columns
+  __shared__ double red[kWaves * R];
+  __shared__ double ush[R];
+  __shared__ double sred[kGroups][kReduceCols];
+  __shared__ double fin[kWaves];
+  __shared__ double sc[KR], sd[KR], sig[KR];
+  __shared__ double cacc[KR][kReduceCols];
+  float* Uown = own;
+  float* Vown = own + (size_t)KR * a.rows_own;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, b = blockIdx.x, G = gridDim.x;
+  const int m = a.m, n = a.n;
+  const int r0 = (int)((int64_t)b * m / G), r1 = (int)((int64_t)(b + 1) * m / G);
+  const int ncb = (n + kReduceCols - 1) / kReduceCols;
+  unsigned phase = 0;
+  int app = 0;
+
+  for (int k = 0; k < a.r; ++k) {
+    for (int i = 0; i <= a.it; ++i, ++app) {
+      double zacc[NS][8];
+#pragma unroll
+      for (int s = 0; s < NS; ++s)
+#pragma unroll
+        for (int c = 0; c < 8; ++c) zacc[s][c] = 0.0;
+      double unrm2 = 0.0, dacc = 0.0;
+      float rs = 1.f;
+      if (i > 0) {
+        int e = __hip_atomic_load(a.expo + app - 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        e = e == INT_MIN ? 0 : (e > 126 ? 126 : (e < -126 ? -126 : e));
+        rs = scalbnf(1.f, -e);
+      }
+      // sigma_j (V_j . v) for the stored ranks, v being the scaled input of this application
+      for (int j = wave; j < k; j += kWaves) {
+        const double t = share_sum(a.cpart + (size_t)j * kComputeUnits, G);
+        if (lane == 0) sc[j] = sig[j] * t * (double)rs;
+      }
+      __syncthreads();
+      // ordinary loads of v are safe: each application's z has an address of its own
+      const float* v_in = i == 0 ? a.S + (int64_t)k * a.lds : a.zapp + (int64_t)(app - 1) * a.zstride;
+      for (int row0 = r0; row0 < r1; row0 += R) {
+        const float* vin = v_in;
+        const float* sf = a.sf;
+        asm volatile("" : "+s"(vin), "+s"(sf));
+        PackedRowBlock<T, NS, R> blk;
+        blk.load(a.W, a.ldw, n, row0, r1);
+        float us[R];
+        blk.times_vector(vin, sf, rs, n, us);
+        wave_row_sums<R>(us, red);
+        __syncthreads();
+        if (tid < R) {
+          double t = 0.0;
+          if (row0 + tid < r1) {
+#pragma unroll
+            for (int wv = 0; wv < kWaves; ++wv) t += red[wv * R + tid];
+            const float* uo = Uown + (row0 - r0 + tid);
+            for (int j = 0; j < k; ++j) t -= sc[j] * (double)uo[(size_t)j * a.rows_own];
+            a.u[row0 + tid] = t;
+          }
+          ush[tid] = t;
+        }
+        __syncthreads();
+        if (tid == 0) {
+#pragma unroll
+          for (int q = 0; q < R; ++q) unrm2 = fma(ush[q], ush[q], unrm2);
+        }
+        if (tid < k) {
+          const float* uo = Uown + (size_t)tid * a.rows_own + (row0 - r0);
+          const int cnt = r1 - row0 < R ? r1 - row0 : R;
+          for (int q = 0; q < cnt; ++q) dacc = fma((double)uo[q], ush[q], dacc);
+        }
+        float uf[R];
+#pragma unroll
+        for (int q = 0; q < R; ++q) uf[q] = (float)ush[q];
+        blk.transposed_times(uf, zacc);
+      }
+#pragma unroll
+      for (int s = 0; s < NS; ++s) {
+        const int col = 8 * (tid + T * s);
+        if (col < n) {
+          float* o = a.zpart + ((int64_t)(col / kReduceCols) * G + b) * kReduceCols + col % kReduceCols;
+          store_dev4(o, (float)zacc[s][0], (float)zacc[s][1], (float)zacc[s][2], (float)zacc[s][3]);
+          store_dev4(o + 4, (float)zacc[s][4], (float)zacc[s][5], (float)zacc[s][6], (float)zacc[s][7]);
+        }
+      }
+      if (tid == 0) store_dev(a.unrm2 + b, unrm2);
+      if (tid < k) store_dev(a.dpart + (size_t)tid * kComputeUnits + b, dacc);
+      grid_barrier(a.bar, ++phase, a.abort, a.spin_limit);
+
+      // this workgroup's column blocks of z = s o (sum of the partial vectors) - correction
+      const bool last_app = i == a.it;
+      for (int j = wave; j < k; j += kWaves) {
+        const double t = share_sum(a.dpart + (size_t)j * kComputeUnits, G);
+        if (lane == 0) sd[j] = sig[j] * t;
+      }
+      if (tid < KR * kReduceCols) cacc[tid / kReduceCols][tid % kReduceCols] = 0.0;
+      __syncthreads();
+      int lc0 = 0;
+      for (int cb = b; cb < ncb; cb += G, lc0 += kReduceCols) {
+        const int cl = tid & (kReduceCols - 1), g = tid / kReduceCols;
+        const int col = cb * kReduceCols + cl;
+        const float* src = a.zpart + (int64_t)cb * G * kReduceCols + cl;
+        double t = 0.0;
+        for (int p0 = g; p0 < G; p0 += 8 * kGroups) {
+          float x[8];
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            const int p = p0 + j * kGroups;
+            x[j] = p < G ? load_dev(src + (int64_t)p * kReduceCols) : 0.f;
+          }
+#pragma unroll
+          for (int j = 0; j < 8; ++j) t += (double)x[j];
+        }
+        sred[g][cl] = t;
+        __syncthreads();
+        if (tid < kWave) {
+          const int quarter = tid / kReduceCols;
+          double zz = 0.0;
+#pragma unroll
+          for (int q = 0; q < kGroups / 4; ++q) zz += sred[quarter * (kGroups / 4) + q][cl];
+          zz += __shfl_xor(zz, 16);
+          zz += __shfl_xor(zz, 32);
+          const bool mine = tid < kReduceCols && col < n;
+          if (mine) {
+            zz *= (double)a.sf[col];
+            const float* vo = Vown + lc0 + cl;
+            for (int j = 0; j < k; ++j) zz -= sd[j] * (double)vo[(size_t)j * a.cols_own];
+            const float zf = (float)zz;
+            store_dev(a.zapp + (int64_t)app * a.zstride + col, zf);
+            a.z[col] = zz;   // read back by this workgroup only
+            if (!last_app)
+              for (int j = 0; j < k; ++j) cacc[j][cl] = fma((double)vo[(size_t)j * a.cols_own], (double)zf, cacc[j][cl]);
+          }
+          if (!last_app) {
+            int e = (mine && zz != 0.0 && fabs(zz) < __builtin_inf()) ? ilogb(zz) : INT_MIN;
+#pragma unroll
+            for (int o = 32; o >= 1; o >>= 1) e = max(e, __shfl_xor(e, o));
+            if (tid == 0 && e != INT_MIN) atomicMax(a.expo + app, e);
+          } else {
+            const double q2 = wave_sum(mine ? zz * zz : 0.0);
+            if (tid == 0) store_dev(a.normpart + cb, q2);
+          }
+        }
+        __syncthreads();
+      }
+      if (!last_app && tid < k) {
+        double t = 0.0;
+#pragma unroll
+        for (int c = 0; c < kReduceCols; ++c) t += cacc[tid][c];
+        store_dev(a.cpart + (size_t)tid * kComputeUnits + b, t);
+      }
+      grid_barrier(a.bar, ++phase, a.abort, a.spin_limit);
+    }
+
+    // the stored triplet of rank k: every workgroup derives the same norms and sigma, encodes the
+    // entries of U and V it produced itself and keeps their decoded values
+    const double ny = sqrt(block_sum<T>(a.unrm2, G, fin));
+    const double np = sqrt(block_sum<T>(a.normpart, ncb, fin));
+    const bool dead = !(ny > 0.0) || !(np > 0.0);
+    const uint16_t h = dead ? 0 : fp16_encode_pos(np / ny);
+    if (tid == 0) sig[k] = fp16_decode_pos(h);
+    if (b == 0 && tid == 0) a.sigma16[k] = h;
+    for (int row = r0 + tid; row < r1; row += T) {
+      const uint8_t c = dead ? 0 : e4m3_encode(a.u[row] / ny);
+      a.U[(int64_t)k * m + row] = c;
+      Uown[(size_t)k * a.rows_own + row - r0] = (float)e4m3_decode(c);
+    }
+    if (tid < kReduceCols) {
+      int lc0 = 0;
+      for (int cb = b; cb < ncb; cb += G, lc0 += kReduceCols) {
+        const int col = cb * kReduceCols + tid;
+        uint8_t c = 0;
+        if (col < n) {
+          c = dead ? 0 : e4m3_encode(a.z[col] / np);
+          a.V[(int64_t)k * n + col] = c;
+        }
+        Vown[(size_t)k * a.cols_own + lc0 + tid] = (float)e4m3_decode(c);
+      }
+    }
+    __syncthreads();
+    // shares of V_j . S_{k+1}, the first input of the next rank: 32 lanes per stored rank
+    if (k + 1 < a.r) {
+      const int j = tid / 32, part = tid % 32;
+      const float* Sn = a.S + (int64_t)(k + 1) * a.lds;
+      double t = 0.0;
+      if (j <= k) {
+        int lc0 = 0;
+        for (int cb = b; cb < ncb; cb += G, lc0 += kReduceCols) {
+          const int col = cb * kReduceCols + part;
+          if (part < kReduceCols && col < n)
+            t = fma((double)Vown[(size_t)j * a.cols_own + lc0 + part], (double)Sn[col], t);
+        }
+      }
+#pragma unroll
+      for (int o = 8; o >= 1; o >>= 1) t += __shfl_xor(t, o);
+      if (part == 0 && j <= k) store_dev(a.cpart + (size_t)j * kComputeUnits + b, t);
+    }
+    grid_barrier(a.bar, ++phase, a.abort, a.spin_limit);
+  }
+
+  if (b == 0 && __hip_atomic_load(a.abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)
+    for (int k = tid; k < a.r; k += T) a.sigma16[k] = 0x7e00;
+}
+
+// R = W - (sum_k sigma_k U_k V_k^T) diag(s)^-1 from the stored factors (Algorithm 1; float64
+// arithmetic, one rounding): what the stream form hands to the quantizer.  One workgroup per
+// 4 rows x 1024 columns.
+__global__ __launch_bounds__(256) void stream_residual_kernel(const uint16_t* __restrict__ W, int64_t ldw, int m,
+                                                             int n, int r, const uint8_t* __restrict__ U,
+                                                             const uint8_t* __restrict__ V,
+                                                             const uint16_t* __restrict__ sigma16,
+                                                             const double* __restrict__ s, float* __restrict__ Rout,
+                                                             int64_t ldr) {
+  __shared__ double su[4][kMaxStreamRank];
+  const int nb = (n + 1023) / 1024;
+  const int c = ((int)(blockIdx.x % nb) * 256 + threadIdx.x) * 4;
+  const int row0 = (int)(blockIdx.x / nb) * 4;
+  if (threadIdx.x < 4 * kMaxStreamRank) {
+    const int i = threadIdx.x / kMaxStreamRank, k = threadIdx.x % kMaxStreamRank;
+    su[i][k] = (k < r && row0 + i < m) ? fp16_decode_pos(sigma16[k]) * e4m3_decode(U[(int64_t)k * m + row0 + i]) : 0.0;
+  }
+  __syncthreads();
+  if (c >= n) return;
+  double low[4][4] = {};
+  for (int k = 0; k < r; ++k) {
+    const unsigned codes = *reinterpret_cast<const unsigned*>(V + (int64_t)k * n + c);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const double v = e4m3_decode((uint8_t)(codes >> (8 * q)));
+#pragma unroll
+      for (int i = 0; i < 4; ++i) low[i][q] = fma(su[i][k], v, low[i][q]);
+    }
+  }
+  double sc4[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) sc4[q] = s[c + q];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    if (row0 + i >= m) break;
+    const uint2 wv = *reinterpret_cast<const uint2*>(W + (int64_t)(row0 + i) * ldw + c);
+    const double w4[4] = {(double)bf16_lo(wv.x), (double)bf16_hi(wv.x), (double)bf16_lo(wv.y), (double)bf16_hi(wv.y)};
+    float o[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) o[q] = (float)(w4[q] - low[i][q] / sc4[q]);
+    *reinterpret_cast<float4*>(Rout + (int64_t)(row0 + i) * ldr + c) = make_float4(o[0], o[1], o[2], o[3]);
+  }
+}
+
+__global__ __launch_bounds__(256) void narrow_scale_kernel(const double* __restrict__ s, int n, float* __restrict__ sf) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c < n) sf[c] = (float)s[c];
+}
+
 // ---- the whole loop on a matrix that fits the registers of the chip ---------------------------
 // When the matrix has at most 256 tiles of 256 x 256 (64 MB of float32: the attention
 // projections of a 7B model), a workgroup keeps ONE TILE, not a block of rows, for the whole
@@ -1048,7 +1429,7 @@ constexpr int kMaxChainApps = 16384;   // applications (rank x iteration) one co
 constexpr size_t kChainVectorBytes = size_t{16} << 20;   // room for their float32 copies of z
 
 struct Layout {
-  size_t A, zpart, z, z32, u, unrm2, normpart, ud, vd, scalars, barrier, expo, zapp, tile, total;
+  size_t A, zpart, z, z32, u, unrm2, normpart, ud, vd, scalars, barrier, expo, zapp, tile, sf, shares, total;
   int parts;    // workgroups of a pass when every step is a launch of its own
   int groups;   // workgroups of the single cooperative launch
 };
@@ -1062,11 +1443,11 @@ inline Layout layout(int64_t m, int64_t n) {
   size_t o = 0;
   auto take = [&](size_t bytes) { const size_t at = o; o += align_up(bytes, 256); return at; };
   L.A = take((size_t)m * n * sizeof(float));
-  L.zpart = take((size_t)ceil_div(n, kReduceCols) * L.groups * kReduceCols * sizeof(float));
+  L.zpart = take((size_t)ceil_div(n, kReduceCols) * kComputeUnits * kReduceCols * sizeof(float));
   L.z = take((size_t)n * sizeof(double));
   L.z32 = take((size_t)n * sizeof(float));
   L.u = take((size_t)m * sizeof(double));
-  L.unrm2 = take((size_t)L.groups * sizeof(double));
+  L.unrm2 = take((size_t)kComputeUnits * sizeof(double));
   L.normpart = take((size_t)kMaxNormParts * sizeof(double));
   L.ud = take((size_t)m * sizeof(double));
   L.vd = take((size_t)n * sizeof(double));
@@ -1075,6 +1456,8 @@ inline Layout layout(int64_t m, int64_t n) {
   L.expo = take((size_t)kMaxChainApps * sizeof(int));
   L.zapp = take(kChainVectorBytes);
   L.tile = take(kTileWorkspaceBytes);
+  L.sf = take((size_t)n * sizeof(float));
+  L.shares = take((size_t)2 * kMaxStreamRank * kComputeUnits * sizeof(double));
   L.total = o;
   return L;
 }
@@ -1105,6 +1488,42 @@ bool launch_chain(ChainArgs& a, int groups, hipStream_t st) {
   void* params[] = {&a};
   if (hipLaunchCooperativeKernel(reinterpret_cast<const void*>(chain_kernel<NS, R>), dim3((unsigned)groups),
                                  dim3(kChainThreads), params, 0, st) != hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  return true;
+}
+
+// Shape of the stream form by number of columns: 8 * sweeps * rows bfloat16 of W per thread.
+struct StreamShape { int ns, rows; };
+inline StreamShape stream_shape(int64_t n) {
+  if (n <= 4096) return {1, 16};
+  if (n <= 8192) return {2, 8};
+  if (n <= 12288) return {3, 4};
+  return {4, 4};
+}
+constexpr int kMaxStreamColumns = 16384;
+
+template <int NS, int R>
+bool launch_stream(StreamArgs& a, hipStream_t st) {
+  const int64_t ncb = ceil_div((int64_t)a.n, kReduceCols);
+  const int64_t want = ceil_div((int64_t)a.m, R) > ncb ? ceil_div((int64_t)a.m, R) : ncb;
+  const int groups = (int)(want < kComputeUnits ? want : kComputeUnits);
+  a.rows_own = (int)ceil_div((int64_t)a.m, groups);
+  a.cols_own = (int)ceil_div(ncb, groups) * kReduceCols;
+  const size_t lds = (size_t)kMaxStreamRank * (a.rows_own + a.cols_own) * sizeof(float);
+  constexpr size_t kMaxLds = 96 * 1024;
+  if (lds > kMaxLds || !lds_opt_in<stream_chain_kernel<NS, R>>((int)kMaxLds)) return false;
+  int dev = 0, coop = 0, cus = 0, per_cu = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return false;
+  if (hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev) != hipSuccess || !coop) return false;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return false;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, stream_chain_kernel<NS, R>, kChainThreads, lds) != hipSuccess)
+    return false;
+  if ((int64_t)per_cu * cus < groups) return false;
+  void* params[] = {&a};
+  if (hipLaunchCooperativeKernel(reinterpret_cast<const void*>(stream_chain_kernel<NS, R>), dim3((unsigned)groups),
+                                 dim3(kChainThreads), params, (unsigned)lds, st) != hipSuccess) {
     (void)hipGetLastError();
     return false;
   }
@@ -1172,6 +1591,53 @@ ptq_status r1svd_launch(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m, in
   unsigned* counter = reinterpret_cast<unsigned*>(scal + 3);
   clear_counter_kernel<<<1, kWave, 0, st>>>(counter);   // a kernel, so that the call can be captured in a graph
 
+  // rounds a workgroup waits for another before it gives up (PTQ_R1SVD_SPIN_LIMIT: for tests of that path)
+  unsigned spin_limit = 1u << 21;
+  if (const char* lim = std::getenv("PTQ_R1SVD_SPIN_LIMIT")) spin_limit = (unsigned)std::strtoul(lim, nullptr, 10);
+  // One cooperative launch for the whole loop where the device can hold it.  PTQ_R1SVD_LAUNCH in the
+  // environment selects another form of the same loop, for comparison and tests: "stream" the launch
+  // that streams a bfloat16 weight even where the tile form applies, "rows" the launch over row blocks
+  // of the float32 running matrix, "steps" one launch per step.
+  const char* mode = std::getenv("PTQ_R1SVD_LAUNCH");
+  const auto mode_is = [&](const char* name) { return mode && std::strcmp(mode, name) == 0; };
+  const int64_t TP = ceil_div(m, kTile), TQ = ceil_div(n, kTile);
+  const bool tile_form = r > 0 && TP * TQ <= kComputeUnits && !mode_is("steps") && !mode_is("rows") && !mode_is("stream");
+  const int64_t zstride = (int64_t)align_up((size_t)n * sizeof(float), 256) / (int64_t)sizeof(float);
+  const bool one_launch_holds = r > 0 && (int64_t)r * (it + 1) <= kMaxChainApps &&
+                                (size_t)r * (it + 1) * zstride * sizeof(float) <= kChainVectorBytes;
+  int* abort_flag = reinterpret_cast<int*>(counter + 1);
+  unsigned* bar = reinterpret_cast<unsigned*>(base + L.barrier);
+
+  // a bfloat16 weight too large for the tile form is streamed as it is, never copied or rewritten
+  if (wdt == PTQ_BF16 && !tile_form && !mode_is("steps") && !mode_is("rows") && one_launch_holds &&
+      r <= kMaxStreamRank && n <= kMaxStreamColumns && n % 8 == 0 && ldw % 8 == 0 && reinterpret_cast<uintptr_t>(W) % 16 == 0) {
+    float* sf = reinterpret_cast<float*>(base + L.sf);
+    double* shares = reinterpret_cast<double*>(base + L.shares);
+    int* expo = reinterpret_cast<int*>(base + L.expo);
+    const int apps = r * (it + 1);
+    const int init = apps > kBarrierWords ? apps : kBarrierWords;
+    narrow_scale_kernel<<<(unsigned)ceil_div(n, 256), 256, 0, st>>>(s, (int)n, sf);
+    chain_init_kernel<<<(unsigned)ceil_div(init, 256), 256, 0, st>>>(expo, apps, bar, abort_flag);
+    StreamArgs sa{static_cast<const uint16_t*>(W), ldw, (int)m, (int)n, sf, S, lds, r, it, U, V, sigma16,
+                  zpart, z, u, unrm2, normpart, shares, shares + (size_t)kMaxStreamRank * kComputeUnits,
+                  reinterpret_cast<float*>(base + L.zapp), zstride, expo, bar, abort_flag, spin_limit, 0, 0};
+    bool streamed = false;
+    const StreamShape ss = stream_shape(n);
+    switch (ss.ns) {
+      case 1: streamed = launch_stream<1, 16>(sa, st); break;
+      case 2: streamed = launch_stream<2, 8>(sa, st); break;
+      case 3: streamed = launch_stream<3, 4>(sa, st); break;
+      default: streamed = launch_stream<4, 4>(sa, st); break;
+    }
+    if (streamed) {
+      const unsigned gr = (unsigned)(ceil_div(n, 1024) * ceil_div(m, 4));
+      stream_residual_kernel<<<gr, 256, 0, st>>>(static_cast<const uint16_t*>(W), ldw, (int)m, (int)n, r, U, V,
+                                                 sigma16, s, Rout, ldr);
+      PTQ_HIP_CHECK_LAUNCH();
+      return PTQ_OK;
+    }
+  }
+
   const unsigned ge = (unsigned)(ceil_div(n, 1024) * m);   // one workgroup per 1024 columns of a row
   switch (wdt) {
     case PTQ_F32: scale_weight_kernel<PTQ_F32><<<ge, 256, 0, st>>>(W, ldw, (int)m, (int)n, s, A); break;
@@ -1180,24 +1646,14 @@ ptq_status r1svd_launch(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m, in
     default: return PTQ_ERR_DTYPE;
   }
 
-  // One cooperative launch for the whole loop where the device can hold it.  PTQ_R1SVD_LAUNCH in the
-  // environment selects another form of the same loop, for comparison and tests: "rows" the single
-  // launch over row blocks even where the tile form applies, "steps" one launch per step.
-  const char* mode = std::getenv("PTQ_R1SVD_LAUNCH");
-  // rounds a workgroup waits for another before it gives up (PTQ_R1SVD_SPIN_LIMIT: for tests of that path)
-  unsigned spin_limit = 1u << 21;
-  if (const char* lim = std::getenv("PTQ_R1SVD_SPIN_LIMIT")) spin_limit = (unsigned)std::strtoul(lim, nullptr, 10);
   bool chained = false;
   // a matrix of at most 256 tiles stays in registers, a tile per workgroup
-  const int64_t TP = ceil_div(m, kTile), TQ = ceil_div(n, kTile);
-  if (r > 0 && TP * TQ <= kComputeUnits && !(mode && (std::strcmp(mode, "steps") == 0 || std::strcmp(mode, "rows") == 0))) {
+  if (tile_form) {
     char* tw = base + L.tile;
     unsigned long long* upart = reinterpret_cast<unsigned long long*>(tw);
     unsigned long long* zp2 = reinterpret_cast<unsigned long long*>(tw + kTilePartBytes);
     double* normy = reinterpret_cast<double*>(tw + 2 * kTilePartBytes);
     double* normp = reinterpret_cast<double*>(tw + 2 * kTilePartBytes + kTileNormBytes);
-    unsigned* bar = reinterpret_cast<unsigned*>(base + L.barrier);
-    int* abort_flag = reinterpret_cast<int*>(counter + 1);
     // tags of an earlier call must not be mistaken for this one's: the tagged words start at zero
     const int words = (int)(2 * kTilePartBytes / sizeof(unsigned));
     tile_init_kernel<<<(unsigned)ceil_div(words, 256), 256, 0, st>>>(reinterpret_cast<unsigned*>(tw), words, abort_flag);
@@ -1206,14 +1662,9 @@ ptq_status r1svd_launch(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m, in
                 ud, vd, scal + 2, bar, abort_flag, spin_limit};
     chained = launch_tile_chain(ta, st);
   }
-  const int64_t zstride = (int64_t)align_up((size_t)n * sizeof(float), 256) / (int64_t)sizeof(float);
-  if (!chained && r > 0 && (int64_t)r * (it + 1) <= kMaxChainApps &&
-      (size_t)r * (it + 1) * zstride * sizeof(float) <= kChainVectorBytes &&
-      !(mode && std::strcmp(mode, "steps") == 0)) {
+  if (!chained && one_launch_holds && !mode_is("steps")) {
     int* expo = reinterpret_cast<int*>(base + L.expo);
-    int* abort_flag = reinterpret_cast<int*>(counter + 1);
     const int apps = r * (it + 1);
-    unsigned* bar = reinterpret_cast<unsigned*>(base + L.barrier);
     const int init = apps > kBarrierWords ? apps : kBarrierWords;
     chain_init_kernel<<<(unsigned)ceil_div(init, 256), 256, 0, st>>>(expo, apps, bar, abort_flag);
     ChainArgs ca{A, (int)m, (int)n, S, lds, r, it, U, V, sigma16, zpart, z, u, unrm2, normpart, ud, vd,

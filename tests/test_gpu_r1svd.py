@@ -24,11 +24,13 @@ pytestmark = pytest.mark.gpu
 FOLLOW_TOL = 2e-3
 
 
-@pytest.fixture(params=["single", "rows", "steps"])
+@pytest.fixture(params=["single", "stream", "rows", "steps"])
 def launch_mode(request, monkeypatch):
     """The loop runs as one cooperative launch -- over tiles where the matrix fits the chip's registers
-    (default), or over row blocks ("rows") -- or as one launch per step ("steps"); the library reads
-    PTQ_R1SVD_LAUNCH at every call.  All forms are held to the oracle."""
+    (default), over row blocks of a bfloat16 weight that is streamed as it is ("stream"; other types
+    take the next form), or over row blocks of the float32 running matrix ("rows") -- or as one launch
+    per step ("steps"); the library reads PTQ_R1SVD_LAUNCH at every call.  All forms are held to the
+    oracle."""
     if request.param == "single":
         monkeypatch.delenv("PTQ_R1SVD_LAUNCH", raising=False)
     else:
@@ -94,6 +96,20 @@ def test_r1svd_matches_oracle(dtype, m, n, r, it, launch_mode):
     ref = _check(W64, s, S, it, got)
     # the low-rank part did its job: the scaled residual is smaller than the scaled weight
     assert np.linalg.norm(ref["A"]) < np.linalg.norm(W64 * s)
+
+
+@pytest.mark.parametrize("m,n,r,it", [
+    (300, 4104, 5, 3),     # two column sweeps, more rows than workgroups
+    (21, 8200, 16, 2),     # three sweeps, the largest rank the form takes
+    (9, 12296, 3, 2),      # four sweeps
+    (1031, 64, 4, 4),      # a prime number of rows over 256 workgroups, 4 column blocks
+])
+def test_r1svd_stream_form_shapes(m, n, r, it, monkeypatch):
+    """The form that streams the bfloat16 weight and applies the stored ranks as corrections."""
+    monkeypatch.setenv("PTQ_R1SVD_LAUNCH", "stream")
+    Ws, W64, s, S = _case(m, n, "bf16", 930 + n, r)
+    got = _run_gpu(to_device(Ws), s, S, it)
+    _check(W64, s, S, it, got)
 
 
 def test_r1svd_float64_weight_and_strided_views():
