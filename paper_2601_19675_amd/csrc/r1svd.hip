@@ -1079,6 +1079,395 @@ __global__ __launch_bounds__(256) void narrow_scale_kernel(const double* __restr
   if (c < n) sf[c] = (float)s[c];
 }
 
+// ---- the loop on a bfloat16 weight that fits the registers and LDS of the chip -----------------
+// The same products as the stream form, but the weight is read ONCE: the matrix is cut into
+// P x Q tiles (P Q <= 256), workgroup (p, q) keeps its tile for the whole loop -- 8 waves, a
+// band of rows per wave, the first RR rows of a band packed in registers (128 per thread), the
+// others in LDS -- and an application is
+//   A  partial u of the tile from v (the tile's columns)            -> upart, grid barrier
+//   B  u of the tile's rows = sum over the Q tiles of the row group - corrections
+//   C  partial z of the tile from u                                  -> zpart, grid barrier
+//   D  z of the tile's columns = s o (sum over the P tiles of the column group) - corrections
+// so what crosses the chip is P n + Q m numbers per application instead of 256 n, and nothing
+// is streamed.  Every tile of a row group derives the same u, every tile of a column group the
+// same z (same loads, same order); the dot products with the stored ranks, the norms and the
+// largest exponent are shared out: tile (p, q) takes the q-th part of its rows and the p-th
+// part of its columns.  The power of two that keeps the vectors in range is applied to u
+// (A is linear).  7B-sized MLP projections (90 MB) just fit: 352 KB per compute unit.
+struct ResidentArgs {
+  const uint16_t* W; int64_t ldw; int m, n;
+  const float* sf; const float* S; int64_t lds; int r, it;
+  uint8_t* U; uint8_t* V; uint16_t* sigma16;
+  double* upart;            // [workgroup][8 RW]
+  double* zpart;            // [workgroup][TC]
+  double* unrm2; double* normpart;   // per workgroup
+  double* cpart; double* dpart;      // [kMaxStreamRank][kComputeUnits]
+  int* emax;                // per workgroup: largest exponent in its share of z
+  unsigned* bar; int* abort; unsigned spin_limit;
+  int P, Q, RW;             // row groups, column groups, rows per wave
+};
+
+// LDS of the resident form by tile shape; `shared` holds, at different times, the per-wave row
+// sums of step A, the per-wave column sums of step C and the float32 copy of z of step D.
+struct ResidentLds {
+  size_t tile, ush, shared, small, svsh, uf, lut, ucode, vcode, total;
+};
+__host__ __device__ inline ResidentLds resident_lds(int nsw, int rr, int rw) {
+  const int tc = nsw * 512, tr = 8 * rw, rl = rw > rr ? rw - rr : 0;
+  const int chunks = rr / 8 + (rl + 7) / 8;
+  ResidentLds L{};
+  size_t off = 0;
+  auto take = [&](size_t bytes) { const size_t at = off; off += (bytes + 15) & ~size_t{15}; return at; };
+  L.tile = take((size_t)8 * rl * tc * 2);
+  L.ush = take((size_t)tr * 8);
+  size_t sh = (size_t)8 * 512 * 4;
+  if ((size_t)chunks * 64 * 8 > sh) sh = (size_t)chunks * 64 * 8;
+  if ((size_t)tc * 4 > sh) sh = (size_t)tc * 4;
+  L.shared = take(sh);
+  L.small = take(64 * 8 + 16 * 4);
+  L.svsh = take((size_t)tc * 4);
+  L.uf = take((size_t)(tr + rr) * 4);
+  L.lut = take(256 * 4);
+  L.ucode = take((size_t)kMaxStreamRank * tr);
+  L.vcode = take((size_t)kMaxStreamRank * tc);
+  L.total = off;
+  return L;
+}
+
+// shares of (decoded code row j) . vec over [lo, hi): 32 lanes per stored rank j < k
+template <typename VT>
+__device__ __forceinline__ void dot_shares(const uint8_t* codes, int stride, const float* lut, const VT* vec, int lo,
+                                           int hi, int k, double* out) {
+  const int j = threadIdx.x / 32, part = threadIdx.x % 32;
+  double t = 0.0;
+  if (j < k)
+    for (int x = lo + part; x < hi; x += 32) t = fma((double)lut[codes[(size_t)j * stride + x]], (double)vec[x], t);
+#pragma unroll
+  for (int o = 16; o >= 1; o >>= 1) t += __shfl_xor(t, o);
+  if (part == 0 && j < k) store_dev(out + (size_t)j * kComputeUnits + blockIdx.x, t);
+}
+
+template <int NSW, int RR>
+__global__ __launch_bounds__(kChainThreads) void resident_chain_kernel(ResidentArgs a) {
+  constexpr int T = kChainThreads, KR = kMaxStreamRank, TC = NSW * 512;
+  static_assert(T == 512 && KR * 32 == T, "32 lanes per stored rank");
+  extern __shared__ __align__(16) unsigned char lds_raw[];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, b = blockIdx.x, G = gridDim.x;
+  const int p = b / a.Q, q = b % a.Q, P = a.P, Q = a.Q;
+  const int m = a.m, n = a.n, RW = a.RW, TR = 8 * RW, RL = RW > RR ? RW - RR : 0;
+  const ResidentLds L = resident_lds(NSW, RR, RW);
+  uint4* tile = reinterpret_cast<uint4*>(lds_raw + L.tile);
+  double* ush = reinterpret_cast<double*>(lds_raw + L.ush);
+  double* ustage = reinterpret_cast<double*>(lds_raw + L.shared);
+  float* zred = reinterpret_cast<float*>(lds_raw + L.shared);
+  float* vsh = reinterpret_cast<float*>(lds_raw + L.shared);
+  double* sc = reinterpret_cast<double*>(lds_raw + L.small);
+  double* sd = sc + 16; double* sig = sc + 32; double* fin = sc + 48;
+  int* esh = reinterpret_cast<int*>(sc + 64);
+  float* svsh = reinterpret_cast<float*>(lds_raw + L.svsh);
+  float* uf = reinterpret_cast<float*>(lds_raw + L.uf);
+  float* lut = reinterpret_cast<float*>(lds_raw + L.lut);
+  uint8_t* ucode = lds_raw + L.ucode;
+  uint8_t* vcode = lds_raw + L.vcode;
+
+  // ---- the tile, once
+  unsigned wreg[RR][NSW][4];
+#pragma unroll
+  for (int rr = 0; rr < RR; ++rr)
+#pragma unroll
+    for (int s = 0; s < NSW; ++s) {
+      const int row = p * TR + w * RW + rr, col = q * TC + s * 512 + lane * 8;
+      uint4 x = make_uint4(0u, 0u, 0u, 0u);
+      if (rr < RW && row < m && col < n) x = *reinterpret_cast<const uint4*>(a.W + (int64_t)row * a.ldw + col);
+      wreg[rr][s][0] = x.x; wreg[rr][s][1] = x.y; wreg[rr][s][2] = x.z; wreg[rr][s][3] = x.w;
+    }
+  for (int rl = 0; rl < RL; ++rl)
+#pragma unroll
+    for (int s = 0; s < NSW; ++s) {
+      const int row = p * TR + w * RW + RR + rl, col = q * TC + s * 512 + lane * 8;
+      uint4 x = make_uint4(0u, 0u, 0u, 0u);
+      if (row < m && col < n) x = *reinterpret_cast<const uint4*>(a.W + (int64_t)row * a.ldw + col);
+      tile[(size_t)(w * RL + rl) * (TC / 8) + s * 64 + lane] = x;
+    }
+  if (tid < 256) lut[tid] = (float)e4m3_decode((uint8_t)tid);
+  for (int x = tid; x < TR + RR; x += T) uf[x] = 0.f;
+  float sfc[NSW];
+#pragma unroll
+  for (int s = 0; s < NSW; ++s) {
+    const int gcol = q * TC + s * 512 + tid;
+    sfc[s] = gcol < n ? a.sf[gcol] : 0.f;
+    svsh[s * 512 + tid] = gcol < n ? a.S[gcol] * sfc[s] : 0.f;
+  }
+  __syncthreads();
+
+  const int row_lo = (int)((int64_t)q * TR / Q), row_hi = (int)((int64_t)(q + 1) * TR / Q);
+  const int col_lo = (int)((int64_t)p * TC / P), col_hi = (int)((int64_t)(p + 1) * TC / P);
+  unsigned phase = 0;
+
+  for (int k = 0; k < a.r; ++k) {
+    double zcur[NSW];
+    for (int i = 0; i <= a.it; ++i) {
+      const bool last_app = i == a.it;
+      // ---- A: partial u of the tile
+      {
+        float sv[NSW][8];
+#pragma unroll
+        for (int s = 0; s < NSW; ++s) {
+          const float4 x = *reinterpret_cast<const float4*>(svsh + s * 512 + lane * 8);
+          const float4 y = *reinterpret_cast<const float4*>(svsh + s * 512 + lane * 8 + 4);
+          sv[s][0] = x.x; sv[s][1] = x.y; sv[s][2] = x.z; sv[s][3] = x.w;
+          sv[s][4] = y.x; sv[s][5] = y.y; sv[s][6] = y.z; sv[s][7] = y.w;
+        }
+#pragma unroll
+        for (int c8 = 0; c8 < RR / 8; ++c8) {
+          if (c8 * 8 < RW) {
+            float us[8];
+#pragma unroll
+            for (int x = 0; x < 8; ++x) {
+              us[x] = 0.f;
+#pragma unroll
+              for (int s = 0; s < NSW; ++s)
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                  us[x] = fmaf(bf16_hi(wreg[c8 * 8 + x][s][c]), sv[s][2 * c + 1],
+                               fmaf(bf16_lo(wreg[c8 * 8 + x][s][c]), sv[s][2 * c], us[x]));
+            }
+            wave_row_sums<8>(us, ustage + c8 * 64);
+          }
+        }
+        for (int c8 = RR / 8; c8 * 8 < RW; ++c8) {
+          float us[8];
+#pragma unroll
+          for (int x = 0; x < 8; ++x) {
+            us[x] = 0.f;
+            const int rl = c8 * 8 - RR + x;
+            if (rl < RL) {
+#pragma unroll
+              for (int s = 0; s < NSW; ++s) {
+                const uint4 t4 = tile[(size_t)(w * RL + rl) * (TC / 8) + s * 64 + lane];
+                const unsigned wd[4] = {t4.x, t4.y, t4.z, t4.w};
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                  us[x] = fmaf(bf16_hi(wd[c]), sv[s][2 * c + 1], fmaf(bf16_lo(wd[c]), sv[s][2 * c], us[x]));
+              }
+            }
+          }
+          wave_row_sums<8>(us, ustage + c8 * 64);
+        }
+      }
+      __syncthreads();
+      if (tid < TR) {
+        const int wv = tid / RW, x = tid - wv * RW;
+        store_dev(a.upart + (size_t)b * TR + tid, ustage[(x >> 3) * 64 + wv * 8 + (x & 7)]);
+      }
+      grid_barrier(a.bar, ++phase, a.abort, a.spin_limit);
+
+      // ---- B: u of the row group
+      if (i > 0 && w == 0) {
+        int e = INT_MIN;
+#pragma unroll
+        for (int x = 0; x < kComputeUnits / kWave; ++x) {
+          const int o = lane + x * kWave;
+          if (o < G) e = max(e, __hip_atomic_load(a.emax + o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        }
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) e = max(e, __shfl_xor(e, o));
+        if (lane == 0) esh[0] = e;
+      }
+      for (int j = w; j < k; j += T / kWave) {
+        const double t = share_sum(a.cpart + (size_t)j * kComputeUnits, G);
+        if (lane == 0) sc[j] = sig[j] * t;
+      }
+      double usum = 0.0;
+      if (tid < TR) {
+        const double* src = a.upart + (size_t)p * Q * TR + tid;
+        for (int q0 = 0; q0 < Q; q0 += 8) {
+          double x[8];
+#pragma unroll
+          for (int j = 0; j < 8; ++j) x[j] = q0 + j < Q ? load_dev(src + (size_t)(q0 + j) * TR) : 0.0;
+#pragma unroll
+          for (int j = 0; j < 8; ++j) usum += x[j];
+        }
+      }
+      __syncthreads();
+      double rs = 1.0;
+      if (i > 0) {
+        int e = esh[0];
+        e = e == INT_MIN ? 0 : (e > 126 ? 126 : (e < -126 ? -126 : e));
+        rs = scalbn(1.0, -e);
+      }
+      if (tid < TR) {
+        double t = usum;
+        for (int j = 0; j < k; ++j) t -= sc[j] * (double)lut[ucode[(size_t)j * TR + tid]];
+        t *= rs;
+        ush[tid] = t;
+        uf[tid] = (float)t;
+      }
+      __syncthreads();
+      dot_shares(ucode, TR, lut, ush, row_lo, row_hi, k, a.dpart);
+      if (last_app) {
+        const double x = (tid >= row_lo && tid < row_hi) ? ush[tid] * ush[tid] : 0.0;
+        const double t = wave_sum(x);
+        if (lane == 0) fin[w] = t;
+        __syncthreads();
+        if (tid == 0) {
+          double total = 0.0;
+#pragma unroll
+          for (int wv = 0; wv < T / kWave; ++wv) total += fin[wv];
+          store_dev(a.unrm2 + b, total);
+        }
+      }
+
+      // ---- C: partial z of the tile
+      {
+        float zt[NSW][8];
+#pragma unroll
+        for (int s = 0; s < NSW; ++s)
+#pragma unroll
+          for (int c = 0; c < 8; ++c) zt[s][c] = 0.f;
+        // the packed words are unpacked again: unpacked floats kept from step A, or hoisted out of
+        // the loop, would need twice the registers of the tile
+#pragma unroll
+        for (int rr = 0; rr < RR; ++rr)
+#pragma unroll
+          for (int s = 0; s < NSW; ++s)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) asm volatile("" : "+v"(wreg[rr][s][c]));
+#pragma unroll
+        for (int rr = 0; rr < RR; ++rr) {
+          const float ufv = uf[w * RW + rr];   // rows past the band hold zeros in wreg
+#pragma unroll
+          for (int s = 0; s < NSW; ++s)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+              zt[s][2 * c] = fmaf(bf16_lo(wreg[rr][s][c]), ufv, zt[s][2 * c]);
+              zt[s][2 * c + 1] = fmaf(bf16_hi(wreg[rr][s][c]), ufv, zt[s][2 * c + 1]);
+            }
+        }
+        for (int rl = 0; rl < RL; ++rl) {
+          const float ufv = uf[w * RW + RR + rl];
+#pragma unroll
+          for (int s = 0; s < NSW; ++s) {
+            const uint4 t4 = tile[(size_t)(w * RL + rl) * (TC / 8) + s * 64 + lane];
+            const unsigned wd[4] = {t4.x, t4.y, t4.z, t4.w};
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+              zt[s][2 * c] = fmaf(bf16_lo(wd[c]), ufv, zt[s][2 * c]);
+              zt[s][2 * c + 1] = fmaf(bf16_hi(wd[c]), ufv, zt[s][2 * c + 1]);
+            }
+          }
+        }
+#pragma unroll
+        for (int s = 0; s < NSW; ++s) {
+          __syncthreads();   // the shared region: step A's sums were read before the barrier, sweep s - 1 just above
+          *reinterpret_cast<float4*>(zred + w * 512 + lane * 8) = make_float4(zt[s][0], zt[s][1], zt[s][2], zt[s][3]);
+          *reinterpret_cast<float4*>(zred + w * 512 + lane * 8 + 4) = make_float4(zt[s][4], zt[s][5], zt[s][6], zt[s][7]);
+          __syncthreads();
+          double t = 0.0;
+#pragma unroll
+          for (int wv = 0; wv < T / kWave; ++wv) t += (double)zred[wv * 512 + tid];
+          store_dev(a.zpart + (size_t)b * TC + s * 512 + tid, t);
+        }
+      }
+      grid_barrier(a.bar, ++phase, a.abort, a.spin_limit);
+
+      // ---- D: z of the column group, the next input
+      for (int j = w; j < k; j += T / kWave) {
+        const double t = share_sum(a.dpart + (size_t)j * kComputeUnits, G);
+        if (lane == 0) sd[j] = sig[j] * t;
+      }
+      double zsum[NSW];
+#pragma unroll
+      for (int s = 0; s < NSW; ++s) {
+        zsum[s] = 0.0;
+        const double* src = a.zpart + (size_t)q * TC + s * 512 + tid;
+        for (int p0 = 0; p0 < P; p0 += 8) {
+          double x[8];
+#pragma unroll
+          for (int j = 0; j < 8; ++j) x[j] = p0 + j < P ? load_dev(src + (size_t)(p0 + j) * Q * TC) : 0.0;
+#pragma unroll
+          for (int j = 0; j < 8; ++j) zsum[s] += x[j];
+        }
+      }
+      __syncthreads();
+      int e = INT_MIN;
+      double q2 = 0.0;
+#pragma unroll
+      for (int s = 0; s < NSW; ++s) {
+        const int cl = s * 512 + tid;
+        double zz = zsum[s] * (double)sfc[s];
+        for (int j = 0; j < k; ++j) zz -= sd[j] * (double)lut[vcode[(size_t)j * TC + cl]];
+        if (q * TC + cl >= n) zz = 0.0;
+        zcur[s] = zz;
+        const float zf = (float)zz;
+        vsh[cl] = zf;
+        svsh[cl] = zf * sfc[s];
+        if (cl >= col_lo && cl < col_hi) {
+          if (zz != 0.0 && fabs(zz) < __builtin_inf()) e = max(e, ilogb(zz));
+          q2 = fma(zz, zz, q2);
+        }
+      }
+      __syncthreads();
+      if (!last_app) {
+        dot_shares(vcode, TC, lut, vsh, col_lo, col_hi, k, a.cpart);
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) e = max(e, __shfl_xor(e, o));
+        if (lane == 0) esh[1 + w] = e;
+        __syncthreads();
+        if (tid == 0) {
+          int em = INT_MIN;
+#pragma unroll
+          for (int wv = 0; wv < T / kWave; ++wv) em = max(em, esh[1 + wv]);
+          __hip_atomic_store(a.emax + b, em, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+      } else {
+        const double t = wave_sum(q2);
+        if (lane == 0) fin[w] = t;
+        __syncthreads();
+        if (tid == 0) {
+          double total = 0.0;
+#pragma unroll
+          for (int wv = 0; wv < T / kWave; ++wv) total += fin[wv];
+          store_dev(a.normpart + b, total);
+        }
+      }
+    }
+    grid_barrier(a.bar, ++phase, a.abort, a.spin_limit);
+
+    // ---- the stored triplet of rank k
+    const double ny = sqrt(block_sum<T>(a.unrm2, G, fin));
+    const double np = sqrt(block_sum<T>(a.normpart, G, fin));
+    const bool dead = !(ny > 0.0) || !(np > 0.0);
+    const uint16_t h = dead ? 0 : fp16_encode_pos(np / ny);
+    if (tid == 0) sig[k] = fp16_decode_pos(h);
+    if (b == 0 && tid == 0) a.sigma16[k] = h;
+    if (tid < TR) {
+      const int row = p * TR + tid;
+      const uint8_t c = (dead || row >= m) ? 0 : e4m3_encode(ush[tid] / ny);
+      ucode[(size_t)k * TR + tid] = c;
+      if (q == 0 && row < m) a.U[(int64_t)k * m + row] = c;
+    }
+#pragma unroll
+    for (int s = 0; s < NSW; ++s) {
+      const int cl = s * 512 + tid, gcol = q * TC + cl;
+      const uint8_t c = (dead || gcol >= n) ? 0 : e4m3_encode(zcur[s] / np);
+      vcode[(size_t)k * TC + cl] = c;
+      if (p == 0 && gcol < n) a.V[(int64_t)k * n + gcol] = c;
+      if (k + 1 < a.r) {
+        const float x = gcol < n ? a.S[(int64_t)(k + 1) * a.lds + gcol] : 0.f;
+        vsh[cl] = x;
+        svsh[cl] = x * sfc[s];
+      }
+    }
+    __syncthreads();
+    if (k + 1 < a.r) dot_shares(vcode, TC, lut, vsh, col_lo, col_hi, k + 1, a.cpart);
+    __syncthreads();   // vsh shares its memory with step A's sums
+  }
+
+  if (b == 0 && __hip_atomic_load(a.abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)
+    for (int k = tid; k < a.r; k += T) a.sigma16[k] = 0x7e00;
+}
+
 // ---- the whole loop on a matrix that fits the registers of the chip ---------------------------
 // When the matrix has at most 256 tiles of 256 x 256 (64 MB of float32: the attention
 // projections of a 7B model), a workgroup keeps ONE TILE, not a block of rows, for the whole
@@ -1428,8 +1817,14 @@ constexpr size_t kTileWorkspaceBytes = 2 * kTilePartBytes + 2 * kTileNormBytes;
 constexpr int kMaxChainApps = 16384;   // applications (rank x iteration) one cooperative launch can hold
 constexpr size_t kChainVectorBytes = size_t{16} << 20;   // room for their float32 copies of z
 
+// resident form: partial u (at most 512 rows per tile) and partial z (at most 1024 columns), float64,
+// and the exponents
+constexpr size_t kResidentUpartBytes = (size_t)kComputeUnits * 512 * sizeof(double);
+constexpr size_t kResidentZpartBytes = (size_t)kComputeUnits * 1024 * sizeof(double);
+constexpr size_t kResidentWorkspaceBytes = kResidentUpartBytes + kResidentZpartBytes + kComputeUnits * sizeof(int);
+
 struct Layout {
-  size_t A, zpart, z, z32, u, unrm2, normpart, ud, vd, scalars, barrier, expo, zapp, tile, sf, shares, total;
+  size_t A, zpart, z, z32, u, unrm2, normpart, ud, vd, scalars, barrier, expo, zapp, tile, sf, shares, resident, total;
   int parts;    // workgroups of a pass when every step is a launch of its own
   int groups;   // workgroups of the single cooperative launch
 };
@@ -1458,6 +1853,7 @@ inline Layout layout(int64_t m, int64_t n) {
   L.tile = take(kTileWorkspaceBytes);
   L.sf = take((size_t)n * sizeof(float));
   L.shares = take((size_t)2 * kMaxStreamRank * kComputeUnits * sizeof(double));
+  L.resident = take(kResidentWorkspaceBytes);
   L.total = o;
   return L;
 }
@@ -1530,6 +1926,47 @@ bool launch_stream(StreamArgs& a, hipStream_t st) {
   return true;
 }
 
+// Tile shape of the resident form: column sweeps per tile (512 columns each), rows per wave, groups.
+constexpr size_t kResidentMaxLds = 160 * 1024;
+struct ResidentPlan { int nsw, rr, rw, P, Q; size_t lds; bool ok; };
+inline ResidentPlan resident_plan(int64_t m, int64_t n) {
+  ResidentPlan best{};
+  for (int nsw = 1; nsw <= 2; ++nsw) {
+    const int rr = 32 / nsw;
+    const int64_t Q = ceil_div(n, (int64_t)512 * nsw);
+    if (Q > kComputeUnits) continue;
+    int64_t P = kComputeUnits / Q;
+    const int64_t rw = ceil_div(m, 8 * P);
+    P = ceil_div(m, 8 * rw);
+    if (8 * rw > kChainThreads) continue;
+    const size_t lds = resident_lds(nsw, rr, (int)rw).total;
+    if (lds > kResidentMaxLds) continue;
+    if (!best.ok || rw * nsw < (int64_t)best.rw * best.nsw) best = {nsw, rr, (int)rw, (int)P, (int)Q, lds, true};
+  }
+  return best;
+}
+
+template <int NSW, int RR>
+bool launch_resident(ResidentArgs& a, const ResidentPlan& plan, hipStream_t st) {
+  if (!lds_opt_in<resident_chain_kernel<NSW, RR>>((int)kResidentMaxLds)) return false;
+  int dev = 0, coop = 0, cus = 0, per_cu = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return false;
+  if (hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev) != hipSuccess || !coop) return false;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return false;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, resident_chain_kernel<NSW, RR>, kChainThreads, plan.lds) !=
+      hipSuccess)
+    return false;
+  const int groups = plan.P * plan.Q;
+  if ((int64_t)per_cu * cus < groups) return false;
+  void* params[] = {&a};
+  if (hipLaunchCooperativeKernel(reinterpret_cast<const void*>(resident_chain_kernel<NSW, RR>), dim3((unsigned)groups),
+                                 dim3(kChainThreads), params, (unsigned)plan.lds, st) != hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  return true;
+}
+
 bool launch_tile_chain(TileArgs& a, hipStream_t st) {
   int dev = 0, coop = 0, cus = 0, per_cu = 0;
   if (hipGetDevice(&dev) != hipSuccess) return false;
@@ -1595,22 +2032,26 @@ ptq_status r1svd_launch(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m, in
   unsigned spin_limit = 1u << 21;
   if (const char* lim = std::getenv("PTQ_R1SVD_SPIN_LIMIT")) spin_limit = (unsigned)std::strtoul(lim, nullptr, 10);
   // One cooperative launch for the whole loop where the device can hold it.  PTQ_R1SVD_LAUNCH in the
-  // environment selects another form of the same loop, for comparison and tests: "stream" the launch
-  // that streams a bfloat16 weight even where the tile form applies, "rows" the launch over row blocks
-  // of the float32 running matrix, "steps" one launch per step.
+  // environment selects another form of the same loop, for comparison and tests: "resident" and
+  // "stream" the two launches that work on a bfloat16 weight as it is even where the tile form
+  // applies, "rows" the launch over row blocks of the float32 running matrix, "steps" one launch
+  // per step.
   const char* mode = std::getenv("PTQ_R1SVD_LAUNCH");
   const auto mode_is = [&](const char* name) { return mode && std::strcmp(mode, name) == 0; };
   const int64_t TP = ceil_div(m, kTile), TQ = ceil_div(n, kTile);
-  const bool tile_form = r > 0 && TP * TQ <= kComputeUnits && !mode_is("steps") && !mode_is("rows") && !mode_is("stream");
+  const bool tile_form = r > 0 && TP * TQ <= kComputeUnits && !mode_is("steps") && !mode_is("rows") &&
+                         !mode_is("stream") && !mode_is("resident");
   const int64_t zstride = (int64_t)align_up((size_t)n * sizeof(float), 256) / (int64_t)sizeof(float);
   const bool one_launch_holds = r > 0 && (int64_t)r * (it + 1) <= kMaxChainApps &&
                                 (size_t)r * (it + 1) * zstride * sizeof(float) <= kChainVectorBytes;
   int* abort_flag = reinterpret_cast<int*>(counter + 1);
   unsigned* bar = reinterpret_cast<unsigned*>(base + L.barrier);
 
-  // a bfloat16 weight too large for the tile form is streamed as it is, never copied or rewritten
+  // A bfloat16 weight too large for the tile form is used as it is, never copied or rewritten: kept
+  // on the chip if it fits there (resident form), else streamed in every application.
   if (wdt == PTQ_BF16 && !tile_form && !mode_is("steps") && !mode_is("rows") && one_launch_holds &&
-      r <= kMaxStreamRank && n <= kMaxStreamColumns && n % 8 == 0 && ldw % 8 == 0 && reinterpret_cast<uintptr_t>(W) % 16 == 0) {
+      r <= kMaxStreamRank && n <= kMaxStreamColumns && n % 8 == 0 && ldw % 8 == 0 &&
+      reinterpret_cast<uintptr_t>(W) % 16 == 0) {
     float* sf = reinterpret_cast<float*>(base + L.sf);
     double* shares = reinterpret_cast<double*>(base + L.shares);
     int* expo = reinterpret_cast<int*>(base + L.expo);
@@ -1618,18 +2059,29 @@ ptq_status r1svd_launch(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m, in
     const int init = apps > kBarrierWords ? apps : kBarrierWords;
     narrow_scale_kernel<<<(unsigned)ceil_div(n, 256), 256, 0, st>>>(s, (int)n, sf);
     chain_init_kernel<<<(unsigned)ceil_div(init, 256), 256, 0, st>>>(expo, apps, bar, abort_flag);
-    StreamArgs sa{static_cast<const uint16_t*>(W), ldw, (int)m, (int)n, sf, S, lds, r, it, U, V, sigma16,
-                  zpart, z, u, unrm2, normpart, shares, shares + (size_t)kMaxStreamRank * kComputeUnits,
-                  reinterpret_cast<float*>(base + L.zapp), zstride, expo, bar, abort_flag, spin_limit, 0, 0};
-    bool streamed = false;
-    const StreamShape ss = stream_shape(n);
-    switch (ss.ns) {
-      case 1: streamed = launch_stream<1, 16>(sa, st); break;
-      case 2: streamed = launch_stream<2, 8>(sa, st); break;
-      case 3: streamed = launch_stream<3, 4>(sa, st); break;
-      default: streamed = launch_stream<4, 4>(sa, st); break;
+    bool launched = false;
+    const ResidentPlan plan = resident_plan(m, n);
+    if (plan.ok && !mode_is("stream")) {
+      char* rw = base + L.resident;
+      ResidentArgs ra{static_cast<const uint16_t*>(W), ldw, (int)m, (int)n, sf, S, lds, r, it, U, V, sigma16,
+                      reinterpret_cast<double*>(rw), reinterpret_cast<double*>(rw + kResidentUpartBytes),
+                      unrm2, normpart, shares, shares + (size_t)kMaxStreamRank * kComputeUnits,
+                      reinterpret_cast<int*>(rw + kResidentUpartBytes + kResidentZpartBytes),
+                      bar, abort_flag, spin_limit, plan.P, plan.Q, plan.rw};
+      launched = plan.nsw == 1 ? launch_resident<1, 32>(ra, plan, st) : launch_resident<2, 16>(ra, plan, st);
     }
-    if (streamed) {
+    if (!launched) {
+      StreamArgs sa{static_cast<const uint16_t*>(W), ldw, (int)m, (int)n, sf, S, lds, r, it, U, V, sigma16,
+                    zpart, z, u, unrm2, normpart, shares, shares + (size_t)kMaxStreamRank * kComputeUnits,
+                    reinterpret_cast<float*>(base + L.zapp), zstride, expo, bar, abort_flag, spin_limit, 0, 0};
+      switch (stream_shape(n).ns) {
+        case 1: launched = launch_stream<1, 16>(sa, st); break;
+        case 2: launched = launch_stream<2, 8>(sa, st); break;
+        case 3: launched = launch_stream<3, 4>(sa, st); break;
+        default: launched = launch_stream<4, 4>(sa, st); break;
+      }
+    }
+    if (launched) {
       const unsigned gr = (unsigned)(ceil_div(n, 1024) * ceil_div(m, 4));
       stream_residual_kernel<<<gr, 256, 0, st>>>(static_cast<const uint16_t*>(W), ldw, (int)m, (int)n, r, U, V,
                                                  sigma16, s, Rout, ldr);

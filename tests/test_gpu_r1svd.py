@@ -24,13 +24,13 @@ pytestmark = pytest.mark.gpu
 FOLLOW_TOL = 2e-3
 
 
-@pytest.fixture(params=["single", "stream", "rows", "steps"])
+@pytest.fixture(params=["single", "resident", "stream", "rows", "steps"])
 def launch_mode(request, monkeypatch):
     """The loop runs as one cooperative launch -- over tiles where the matrix fits the chip's registers
-    (default), over row blocks of a bfloat16 weight that is streamed as it is ("stream"; other types
-    take the next form), or over row blocks of the float32 running matrix ("rows") -- or as one launch
-    per step ("steps"); the library reads PTQ_R1SVD_LAUNCH at every call.  All forms are held to the
-    oracle."""
+    (default), over a bfloat16 weight used as it is, kept on the chip in two-dimensional tiles ("resident")
+    or streamed in row blocks ("stream"; other types take the next form), or over row blocks of the
+    float32 running matrix ("rows") -- or as one launch per step ("steps"); the library reads
+    PTQ_R1SVD_LAUNCH at every call.  All forms are held to the oracle."""
     if request.param == "single":
         monkeypatch.delenv("PTQ_R1SVD_LAUNCH", raising=False)
     else:
@@ -103,10 +103,12 @@ def test_r1svd_matches_oracle(dtype, m, n, r, it, launch_mode):
     (21, 8200, 16, 2),     # three sweeps, the largest rank the form takes
     (9, 12296, 3, 2),      # four sweeps
     (1031, 64, 4, 4),      # a prime number of rows over 256 workgroups, 4 column blocks
+    (12000, 520, 3, 2),    # resident: two column groups, 128 row groups, rows of a band in registers and LDS
 ])
-def test_r1svd_stream_form_shapes(m, n, r, it, monkeypatch):
-    """The form that streams the bfloat16 weight and applies the stored ranks as corrections."""
-    monkeypatch.setenv("PTQ_R1SVD_LAUNCH", "stream")
+@pytest.mark.parametrize("form", ["resident", "stream"])
+def test_r1svd_bfloat16_forms_shapes(m, n, r, it, form, monkeypatch):
+    """The forms that use the bfloat16 weight as it is and apply the stored ranks as corrections."""
+    monkeypatch.setenv("PTQ_R1SVD_LAUNCH", form)
     Ws, W64, s, S = _case(m, n, "bf16", 930 + n, r)
     got = _run_gpu(to_device(Ws), s, S, it)
     _check(W64, s, S, it, got)
