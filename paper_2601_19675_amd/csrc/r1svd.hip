@@ -814,7 +814,8 @@ __device__ __forceinline__ double share_sum(const double* row, int G) {
 #pragma unroll
   for (int q = 0; q < kComputeUnits / kWave; ++q) {
     const int p = (int)(threadIdx.x & 63) + q * kWave;
-    x[q] = p < G ? load_dev(row + p) : 0.0;
+    const double v = load_dev(row + (p < G ? p : G - 1));   // issued whatever p: loads under a condition wait for each other
+    x[q] = p < G ? v : 0.0;
   }
   double t = 0.0;
 #pragma unroll
@@ -1099,7 +1100,7 @@ struct ResidentArgs {
   const float* sf; const float* S; int64_t lds; int r, it;
   uint8_t* U; uint8_t* V; uint16_t* sigma16;
   double* upart;            // [workgroup][8 RW]
-  double* zpart;            // [workgroup][TC]
+  float* zpart;             // [workgroup][TC]
   double* unrm2; double* normpart;   // per workgroup
   double* cpart; double* dpart;      // [kMaxStreamRank][kComputeUnits]
   int* emax;                // per workgroup: largest exponent in its share of z
@@ -1107,10 +1108,11 @@ struct ResidentArgs {
   int P, Q, RW;             // row groups, column groups, rows per wave
 };
 
-// LDS of the resident form by tile shape; `shared` holds, at different times, the per-wave row
-// sums of step A, the per-wave column sums of step C and the float32 copy of z of step D.
+// LDS of the resident form by tile shape; `shared` (8 x 512 floats) holds, at different times, the
+// per-wave staging of step A's row sums, the per-wave column sums of step C and the float32 copy
+// of z of step D.
 struct ResidentLds {
-  size_t tile, ush, shared, small, svsh, uf, lut, ucode, vcode, total;
+  size_t tile, ush, ustage, shared, small, svsh, uf, lut, ucode, vcode, total;
 };
 __host__ __device__ inline ResidentLds resident_lds(int nsw, int rr, int rw) {
   const int tc = nsw * 512, tr = 8 * rw, rl = rw > rr ? rw - rr : 0;
@@ -1120,10 +1122,8 @@ __host__ __device__ inline ResidentLds resident_lds(int nsw, int rr, int rw) {
   auto take = [&](size_t bytes) { const size_t at = off; off += (bytes + 15) & ~size_t{15}; return at; };
   L.tile = take((size_t)8 * rl * tc * 2);
   L.ush = take((size_t)tr * 8);
-  size_t sh = (size_t)8 * 512 * 4;
-  if ((size_t)chunks * 64 * 8 > sh) sh = (size_t)chunks * 64 * 8;
-  if ((size_t)tc * 4 > sh) sh = (size_t)tc * 4;
-  L.shared = take(sh);
+  L.ustage = take((size_t)chunks * 64 * 8);
+  L.shared = take((size_t)8 * 512 * 4);
   L.small = take(64 * 8 + 16 * 4);
   L.svsh = take((size_t)tc * 4);
   L.uf = take((size_t)(tr + rr) * 4);
@@ -1134,17 +1134,91 @@ __host__ __device__ inline ResidentLds resident_lds(int nsw, int rr, int rw) {
   return L;
 }
 
-// shares of (decoded code row j) . vec over [lo, hi): 32 lanes per stored rank j < k
+// Lane exchanges inside a row of 16 lanes by data-parallel primitives (no LDS traffic): after the
+// four steps every lane of a row holds the sum over the row, added in a fixed order.
+template <int CTRL>
+__device__ __forceinline__ double dpp_move(double v) {
+  const unsigned long long bits = __double_as_longlong(v);
+  const int lo = __builtin_amdgcn_update_dpp(0, (int)(unsigned)bits, CTRL, 0xf, 0xf, false);
+  const int hi = __builtin_amdgcn_update_dpp(0, (int)(unsigned)(bits >> 32), CTRL, 0xf, 0xf, false);
+  return __longlong_as_double((long long)(((unsigned long long)(unsigned)hi << 32) | (unsigned)lo));
+}
+constexpr int kDppSwapPairs = 0xB1;      // quad_perm [1, 0, 3, 2]
+constexpr int kDppSwapHalfQuads = 0x4E;  // quad_perm [2, 3, 0, 1]
+constexpr int kDppHalfMirror = 0x141;    // lane i of 8 <- lane 7 - i
+constexpr int kDppMirror = 0x140;        // lane i of 16 <- lane 15 - i
+__device__ __forceinline__ double sum8(double t) {
+  t += dpp_move<kDppSwapPairs>(t);
+  t += dpp_move<kDppSwapHalfQuads>(t);
+  t += dpp_move<kDppHalfMirror>(t);
+  return t;
+}
+__device__ __forceinline__ double sum32(double t) {
+  t = sum8(t);
+  t += dpp_move<kDppMirror>(t);
+  t += __shfl_xor(t, 16);
+  return t;
+}
+
+// Sums over the 64 lanes of a wave of 8 per-lane values, in float64: the values go through
+// `stage` (8 x 64 floats of this wave's own), 8 lanes add up a row (each 8 values, then among
+// themselves).  Every lane returns the sum of row lane / 8.
+__device__ __forceinline__ double wave_row_sums_staged(const float (&us)[8], float* stage) {
+  const int lane = threadIdx.x & 63;
+  __builtin_amdgcn_wave_barrier();   // the reads of the previous call precede these writes
+#pragma unroll
+  for (int x = 0; x < 8; ++x) stage[x * 64 + lane] = us[x];
+  __builtin_amdgcn_wave_barrier();   // a wave's LDS accesses complete in order
+  const float4 v0 = *reinterpret_cast<const float4*>(stage + (lane >> 3) * 64 + (lane & 7) * 8);
+  const float4 v1 = *reinterpret_cast<const float4*>(stage + (lane >> 3) * 64 + (lane & 7) * 8 + 4);
+  const double t = (((double)v0.x + (double)v0.y) + ((double)v0.z + (double)v0.w)) +
+                   (((double)v1.x + (double)v1.y) + ((double)v1.z + (double)v1.w));
+  return sum8(t);
+}
+
+// out[j] = scale_j * (sum over the workgroups of row j of a [kMaxStreamRank][kComputeUnits] table),
+// j < k: 32 lanes per row, all loads in flight at once
+__device__ __forceinline__ void all_share_sums(const double* table, int G, int k, const double* sig, double* out) {
+  const int j = threadIdx.x / 32, part = threadIdx.x % 32;
+  double x[kComputeUnits / 32];
+#pragma unroll
+  for (int i = 0; i < kComputeUnits / 32; ++i) {
+    // every load is issued (a load under a condition would wait for the one before it)
+    const int o = part + 32 * i;
+    const double v = load_dev(table + (size_t)j * kComputeUnits + (o < G ? o : G - 1));
+    x[i] = (j < k && o < G) ? v : 0.0;
+  }
+  double t = 0.0;
+#pragma unroll
+  for (int i = 0; i < kComputeUnits / 32; ++i) t += x[i];
+  t = sum32(t);
+  if (part == 0 && j < k) out[j] = sig[j] * t;
+}
+
+// shares of (decoded code row j) . vec over [lo, hi): 32 lanes per stored rank j < k; the codes
+// of an entry's 16 ranks are adjacent
 template <typename VT>
-__device__ __forceinline__ void dot_shares(const uint8_t* codes, int stride, const float* lut, const VT* vec, int lo,
-                                           int hi, int k, double* out) {
+__device__ __forceinline__ void dot_shares(const uint8_t* codes, const float* lut, const VT* vec, int lo, int hi,
+                                           int k, double* out) {
   const int j = threadIdx.x / 32, part = threadIdx.x % 32;
   double t = 0.0;
   if (j < k)
-    for (int x = lo + part; x < hi; x += 32) t = fma((double)lut[codes[(size_t)j * stride + x]], (double)vec[x], t);
-#pragma unroll
-  for (int o = 16; o >= 1; o >>= 1) t += __shfl_xor(t, o);
+    for (int x = lo + part; x < hi; x += 32) t = fma((double)lut[codes[(size_t)x * kMaxStreamRank + j]], (double)vec[x], t);
+  t = sum32(t);
   if (part == 0 && j < k) store_dev(out + (size_t)j * kComputeUnits + blockIdx.x, t);
+}
+
+// sum_j coef[j] * (decoded code j of the 16 adjacent codes at `codes`), j < k
+__device__ __forceinline__ double stored_ranks_dot(const uint8_t* codes, const float* lut, const double* coef, int k) {
+  const uint4 cw = *reinterpret_cast<const uint4*>(codes);
+  const unsigned wd[4] = {cw.x, cw.y, cw.z, cw.w};
+  double t = 0.0;
+#pragma unroll
+  for (int j = 0; j < kMaxStreamRank; ++j) {
+    const float v = lut[(wd[j >> 2] >> (8 * (j & 3))) & 0xffu];
+    t += j < k ? coef[j] * (double)v : 0.0;
+  }
+  return t;
 }
 
 template <int NSW, int RR>
@@ -1158,7 +1232,8 @@ __global__ __launch_bounds__(kChainThreads) void resident_chain_kernel(ResidentA
   const ResidentLds L = resident_lds(NSW, RR, RW);
   uint4* tile = reinterpret_cast<uint4*>(lds_raw + L.tile);
   double* ush = reinterpret_cast<double*>(lds_raw + L.ush);
-  double* ustage = reinterpret_cast<double*>(lds_raw + L.shared);
+  double* ustage = reinterpret_cast<double*>(lds_raw + L.ustage);
+  float* stage = reinterpret_cast<float*>(lds_raw + L.shared) + w * 512;
   float* zred = reinterpret_cast<float*>(lds_raw + L.shared);
   float* vsh = reinterpret_cast<float*>(lds_raw + L.shared);
   double* sc = reinterpret_cast<double*>(lds_raw + L.small);
@@ -1232,7 +1307,8 @@ __global__ __launch_bounds__(kChainThreads) void resident_chain_kernel(ResidentA
                   us[x] = fmaf(bf16_hi(wreg[c8 * 8 + x][s][c]), sv[s][2 * c + 1],
                                fmaf(bf16_lo(wreg[c8 * 8 + x][s][c]), sv[s][2 * c], us[x]));
             }
-            wave_row_sums<8>(us, ustage + c8 * 64);
+            const double t = wave_row_sums_staged(us, stage);
+            if ((lane & 7) == 0) ustage[c8 * 64 + w * 8 + (lane >> 3)] = t;
           }
         }
         for (int c8 = RR / 8; c8 * 8 < RW; ++c8) {
@@ -1252,7 +1328,8 @@ __global__ __launch_bounds__(kChainThreads) void resident_chain_kernel(ResidentA
               }
             }
           }
-          wave_row_sums<8>(us, ustage + c8 * 64);
+          const double t = wave_row_sums_staged(us, stage);
+          if ((lane & 7) == 0) ustage[c8 * 64 + w * 8 + (lane >> 3)] = t;
         }
       }
       __syncthreads();
@@ -1268,27 +1345,28 @@ __global__ __launch_bounds__(kChainThreads) void resident_chain_kernel(ResidentA
 #pragma unroll
         for (int x = 0; x < kComputeUnits / kWave; ++x) {
           const int o = lane + x * kWave;
-          if (o < G) e = max(e, __hip_atomic_load(a.emax + o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+          const int v = __hip_atomic_load(a.emax + (o < G ? o : G - 1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          e = max(e, v);
         }
 #pragma unroll
         for (int o = 32; o >= 1; o >>= 1) e = max(e, __shfl_xor(e, o));
         if (lane == 0) esh[0] = e;
       }
-      for (int j = w; j < k; j += T / kWave) {
-        const double t = share_sum(a.cpart + (size_t)j * kComputeUnits, G);
-        if (lane == 0) sc[j] = sig[j] * t;
-      }
       double usum = 0.0;
       if (tid < TR) {
         const double* src = a.upart + (size_t)p * Q * TR + tid;
-        for (int q0 = 0; q0 < Q; q0 += 8) {
-          double x[8];
+        for (int q0 = 0; q0 < Q; q0 += 16) {
+          double x[16];
 #pragma unroll
-          for (int j = 0; j < 8; ++j) x[j] = q0 + j < Q ? load_dev(src + (size_t)(q0 + j) * TR) : 0.0;
+          for (int j = 0; j < 16; ++j) {
+            const double v = load_dev(src + (size_t)(q0 + j < Q ? q0 + j : Q - 1) * TR);
+            x[j] = q0 + j < Q ? v : 0.0;
+          }
 #pragma unroll
-          for (int j = 0; j < 8; ++j) usum += x[j];
+          for (int j = 0; j < 16; ++j) usum += x[j];
         }
       }
+      all_share_sums(a.cpart, G, k, sig, sc);
       __syncthreads();
       double rs = 1.0;
       if (i > 0) {
@@ -1297,14 +1375,12 @@ __global__ __launch_bounds__(kChainThreads) void resident_chain_kernel(ResidentA
         rs = scalbn(1.0, -e);
       }
       if (tid < TR) {
-        double t = usum;
-        for (int j = 0; j < k; ++j) t -= sc[j] * (double)lut[ucode[(size_t)j * TR + tid]];
-        t *= rs;
+        const double t = (usum - stored_ranks_dot(ucode + (size_t)tid * KR, lut, sc, k)) * rs;
         ush[tid] = t;
         uf[tid] = (float)t;
       }
       __syncthreads();
-      dot_shares(ucode, TR, lut, ush, row_lo, row_hi, k, a.dpart);
+      dot_shares(ucode, lut, ush, row_lo, row_hi, k, a.dpart);
       if (last_app) {
         const double x = (tid >= row_lo && tid < row_hi) ? ush[tid] * ush[tid] : 0.0;
         const double t = wave_sum(x);
@@ -1366,37 +1442,36 @@ __global__ __launch_bounds__(kChainThreads) void resident_chain_kernel(ResidentA
           double t = 0.0;
 #pragma unroll
           for (int wv = 0; wv < T / kWave; ++wv) t += (double)zred[wv * 512 + tid];
-          store_dev(a.zpart + (size_t)b * TC + s * 512 + tid, t);
+          store_dev(a.zpart + (size_t)b * TC + s * 512 + tid, (float)t);
         }
       }
       grid_barrier(a.bar, ++phase, a.abort, a.spin_limit);
 
       // ---- D: z of the column group, the next input
-      for (int j = w; j < k; j += T / kWave) {
-        const double t = share_sum(a.dpart + (size_t)j * kComputeUnits, G);
-        if (lane == 0) sd[j] = sig[j] * t;
-      }
       double zsum[NSW];
 #pragma unroll
       for (int s = 0; s < NSW; ++s) {
         zsum[s] = 0.0;
-        const double* src = a.zpart + (size_t)q * TC + s * 512 + tid;
-        for (int p0 = 0; p0 < P; p0 += 8) {
-          double x[8];
+        const float* src = a.zpart + (size_t)q * TC + s * 512 + tid;
+        for (int p0 = 0; p0 < P; p0 += 32) {
+          float x[32];
 #pragma unroll
-          for (int j = 0; j < 8; ++j) x[j] = p0 + j < P ? load_dev(src + (size_t)(p0 + j) * Q * TC) : 0.0;
+          for (int j = 0; j < 32; ++j) {
+            const float v = load_dev(src + (size_t)(p0 + j < P ? p0 + j : P - 1) * Q * TC);
+            x[j] = p0 + j < P ? v : 0.f;
+          }
 #pragma unroll
-          for (int j = 0; j < 8; ++j) zsum[s] += x[j];
+          for (int j = 0; j < 32; ++j) zsum[s] += (double)x[j];
         }
       }
+      all_share_sums(a.dpart, G, k, sig, sd);
       __syncthreads();
       int e = INT_MIN;
       double q2 = 0.0;
 #pragma unroll
       for (int s = 0; s < NSW; ++s) {
         const int cl = s * 512 + tid;
-        double zz = zsum[s] * (double)sfc[s];
-        for (int j = 0; j < k; ++j) zz -= sd[j] * (double)lut[vcode[(size_t)j * TC + cl]];
+        double zz = zsum[s] * (double)sfc[s] - stored_ranks_dot(vcode + (size_t)cl * KR, lut, sd, k);
         if (q * TC + cl >= n) zz = 0.0;
         zcur[s] = zz;
         const float zf = (float)zz;
@@ -1409,7 +1484,7 @@ __global__ __launch_bounds__(kChainThreads) void resident_chain_kernel(ResidentA
       }
       __syncthreads();
       if (!last_app) {
-        dot_shares(vcode, TC, lut, vsh, col_lo, col_hi, k, a.cpart);
+        dot_shares(vcode, lut, vsh, col_lo, col_hi, k, a.cpart);
 #pragma unroll
         for (int o = 32; o >= 1; o >>= 1) e = max(e, __shfl_xor(e, o));
         if (lane == 0) esh[1 + w] = e;
@@ -1444,14 +1519,14 @@ __global__ __launch_bounds__(kChainThreads) void resident_chain_kernel(ResidentA
     if (tid < TR) {
       const int row = p * TR + tid;
       const uint8_t c = (dead || row >= m) ? 0 : e4m3_encode(ush[tid] / ny);
-      ucode[(size_t)k * TR + tid] = c;
+      ucode[(size_t)tid * KR + k] = c;
       if (q == 0 && row < m) a.U[(int64_t)k * m + row] = c;
     }
 #pragma unroll
     for (int s = 0; s < NSW; ++s) {
       const int cl = s * 512 + tid, gcol = q * TC + cl;
       const uint8_t c = (dead || gcol >= n) ? 0 : e4m3_encode(zcur[s] / np);
-      vcode[(size_t)k * TC + cl] = c;
+      vcode[(size_t)cl * KR + k] = c;
       if (p == 0 && gcol < n) a.V[(int64_t)k * n + gcol] = c;
       if (k + 1 < a.r) {
         const float x = gcol < n ? a.S[(int64_t)(k + 1) * a.lds + gcol] : 0.f;
@@ -1460,7 +1535,7 @@ __global__ __launch_bounds__(kChainThreads) void resident_chain_kernel(ResidentA
       }
     }
     __syncthreads();
-    if (k + 1 < a.r) dot_shares(vcode, TC, lut, vsh, col_lo, col_hi, k + 1, a.cpart);
+    if (k + 1 < a.r) dot_shares(vcode, lut, vsh, col_lo, col_hi, k + 1, a.cpart);
     __syncthreads();   // vsh shares its memory with step A's sums
   }
 
@@ -1817,10 +1892,10 @@ constexpr size_t kTileWorkspaceBytes = 2 * kTilePartBytes + 2 * kTileNormBytes;
 constexpr int kMaxChainApps = 16384;   // applications (rank x iteration) one cooperative launch can hold
 constexpr size_t kChainVectorBytes = size_t{16} << 20;   // room for their float32 copies of z
 
-// resident form: partial u (at most 512 rows per tile) and partial z (at most 1024 columns), float64,
-// and the exponents
+// resident form: partial u (at most 512 rows per tile, float64), partial z (at most 1024 columns,
+// float32) and the exponents
 constexpr size_t kResidentUpartBytes = (size_t)kComputeUnits * 512 * sizeof(double);
-constexpr size_t kResidentZpartBytes = (size_t)kComputeUnits * 1024 * sizeof(double);
+constexpr size_t kResidentZpartBytes = (size_t)kComputeUnits * 1024 * sizeof(float);
 constexpr size_t kResidentWorkspaceBytes = kResidentUpartBytes + kResidentZpartBytes + kComputeUnits * sizeof(int);
 
 struct Layout {
@@ -2064,7 +2139,7 @@ ptq_status r1svd_launch(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m, in
     if (plan.ok && !mode_is("stream")) {
       char* rw = base + L.resident;
       ResidentArgs ra{static_cast<const uint16_t*>(W), ldw, (int)m, (int)n, sf, S, lds, r, it, U, V, sigma16,
-                      reinterpret_cast<double*>(rw), reinterpret_cast<double*>(rw + kResidentUpartBytes),
+                      reinterpret_cast<double*>(rw), reinterpret_cast<float*>(rw + kResidentUpartBytes),
                       unrm2, normpart, shares, shares + (size_t)kMaxStreamRank * kComputeUnits,
                       reinterpret_cast<int*>(rw + kResidentUpartBytes + kResidentZpartBytes),
                       bar, abort_flag, spin_limit, plan.P, plan.Q, plan.rw};
