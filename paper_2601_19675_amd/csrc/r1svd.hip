@@ -1091,10 +1091,11 @@ __global__ __launch_bounds__(256) void narrow_scale_kernel(const double* __restr
 //   D  z of the tile's columns = s o (sum over the P tiles of the column group) - corrections
 // so what crosses the chip is P n + Q m numbers per application instead of 256 n, and nothing
 // is streamed.  Every tile of a row group derives the same u, every tile of a column group the
-// same z (same loads, same order); the dot products with the stored ranks, the norms and the
-// largest exponent are shared out: tile (p, q) takes the q-th part of its rows and the p-th
-// part of its columns.  The power of two that keeps the vectors in range is applied to u
-// (A is linear).  7B-sized MLP projections (90 MB) just fit: 352 KB per compute unit.
+// same z (same loads, same order), so the small jobs are shared out: of the dot products with
+// the stored ranks tile (p, q) takes rank j = q (mod Q) for its row group and j = p (mod P) for
+// its column group; of the norms and the largest exponent it takes the q-th part of its rows
+// and the p-th part of its columns.  The power of two that keeps the vectors in range is
+// applied to u (A is linear).  7B-sized MLP projections (90 MB) just fit: 352 KB per compute unit.
 struct ResidentArgs {
   const uint16_t* W; int64_t ldw; int m, n;
   const float* sf; const float* S; int64_t lds; int r, it;
@@ -1102,15 +1103,15 @@ struct ResidentArgs {
   double* upart;            // [workgroup][8 RW]
   float* zpart;             // [workgroup][TC]
   double* unrm2; double* normpart;   // per workgroup
-  double* cpart; double* dpart;      // [kMaxStreamRank][kComputeUnits]
+  double* cpart; double* dpart;      // [kMaxStreamRank][kComputeUnits]: per column group, per row group
   int* emax;                // per workgroup: largest exponent in its share of z
   unsigned* bar; int* abort; unsigned spin_limit;
   int P, Q, RW;             // row groups, column groups, rows per wave
 };
 
 // LDS of the resident form by tile shape; `shared` (8 x 512 floats) holds, at different times, the
-// per-wave staging of step A's row sums, the per-wave column sums of step C and the float32 copy
-// of z of step D.
+// per-wave staging of step A's row sums, the per-wave column sums of step C, and the sums of the
+// partial z and the float32 copy of z of step D.
 struct ResidentLds {
   size_t tile, ush, ustage, shared, small, svsh, uf, lut, ucode, vcode, total;
 };
@@ -1176,36 +1177,60 @@ __device__ __forceinline__ double wave_row_sums_staged(const float (&us)[8], flo
   return sum8(t);
 }
 
-// out[j] = scale_j * (sum over the workgroups of row j of a [kMaxStreamRank][kComputeUnits] table),
-// j < k: 32 lanes per row, all loads in flight at once
-__device__ __forceinline__ void all_share_sums(const double* table, int G, int k, const double* sig, double* out) {
+// Sum of the first `count` entries of row j = thread / 32 of a [kMaxStreamRank][kComputeUnits]
+// table, in two parts so that the load can be issued together with a step's other loads (a load
+// whose value is used at once costs a memory round trip of its own).  Up to 32 entries are one
+// load per lane; more (small matrices cut into many row groups) are loaded on the spot.
+__device__ __forceinline__ double share_load(const double* table, int count) {
   const int j = threadIdx.x / 32, part = threadIdx.x % 32;
-  double x[kComputeUnits / 32];
-#pragma unroll
-  for (int i = 0; i < kComputeUnits / 32; ++i) {
-    // every load is issued (a load under a condition would wait for the one before it)
-    const int o = part + 32 * i;
-    const double v = load_dev(table + (size_t)j * kComputeUnits + (o < G ? o : G - 1));
-    x[i] = (j < k && o < G) ? v : 0.0;
-  }
-  double t = 0.0;
-#pragma unroll
-  for (int i = 0; i < kComputeUnits / 32; ++i) t += x[i];
+  // issued whatever the index: a load under a condition is compiled to a branch and a wait
+  return load_dev(table + (size_t)j * kComputeUnits + (part < count ? part : count - 1));
+}
+// out[j] = sig[j] * sum, j < k
+__device__ __forceinline__ void share_sums(double first, const double* table, int count, int k, const double* sig,
+                                           double* out) {
+  const int j = threadIdx.x / 32, part = threadIdx.x % 32;
+  double t = part < count ? first : 0.0;
+  for (int o = part + 32; o < count; o += 32) t += load_dev(table + (size_t)j * kComputeUnits + o);
   t = sum32(t);
   if (part == 0 && j < k) out[j] = sig[j] * t;
 }
 
-// shares of (decoded code row j) . vec over [lo, hi): 32 lanes per stored rank j < k; the codes
-// of an entry's 16 ranks are adjacent
+// N partial sums `stride` apart, of which the first `count` are wanted (count >= 1): all issued
+template <int N, typename PT>
+__device__ __forceinline__ void load_partials(const PT* src, size_t stride, int first, int step, int count, PT* x) {
+#pragma unroll
+  for (int j = 0; j < N; ++j) {
+    const int i = first + (j < count ? j : count - 1) * step;
+    x[j] = __hip_atomic_load(src + (size_t)i * stride, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+
+// (decoded codes of rank j) . vec over `len` entries, for the ranks j < k that fall to this
+// workgroup (j = owner modulo owners), left in out[j][slot]: 32 lanes per rank; the codes of an
+// entry's 16 ranks are adjacent
 template <typename VT>
-__device__ __forceinline__ void dot_shares(const uint8_t* codes, const float* lut, const VT* vec, int lo, int hi,
-                                           int k, double* out) {
+__device__ __forceinline__ void dot_shares(const uint8_t* codes, const float* lut, const VT* vec, int len, int k,
+                                           int owners, int owner, int slot, double* out) {
   const int j = threadIdx.x / 32, part = threadIdx.x % 32;
+  const bool mine = j < k && j % owners == owner;
   double t = 0.0;
-  if (j < k)
-    for (int x = lo + part; x < hi; x += 32) t = fma((double)lut[codes[(size_t)x * kMaxStreamRank + j]], (double)vec[x], t);
+  if (mine) {
+    // four entries at a time: each costs two dependent LDS reads
+    double t4[4] = {0.0, 0.0, 0.0, 0.0};
+    for (int x0 = part; x0 < len; x0 += 128) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int x = x0 + 32 * i;
+        const int xc = x < len ? x : len - 1;
+        const double v = (double)lut[codes[(size_t)xc * kMaxStreamRank + j]] * (double)vec[xc];
+        t4[i] += x < len ? v : 0.0;
+      }
+    }
+    t = (t4[0] + t4[1]) + (t4[2] + t4[3]);
+  }
   t = sum32(t);
-  if (part == 0 && j < k) store_dev(out + (size_t)j * kComputeUnits + blockIdx.x, t);
+  if (part == 0 && mine) store_dev(out + (size_t)j * kComputeUnits + slot, t);
 }
 
 // sum_j coef[j] * (decoded code j of the 16 adjacent codes at `codes`), j < k
@@ -1236,6 +1261,7 @@ __global__ __launch_bounds__(kChainThreads) void resident_chain_kernel(ResidentA
   float* stage = reinterpret_cast<float*>(lds_raw + L.shared) + w * 512;
   float* zred = reinterpret_cast<float*>(lds_raw + L.shared);
   float* vsh = reinterpret_cast<float*>(lds_raw + L.shared);
+  double* zsumsh = reinterpret_cast<double*>(lds_raw + L.shared + 4096);   // 8 KB, next to vsh
   double* sc = reinterpret_cast<double*>(lds_raw + L.small);
   double* sd = sc + 16; double* sig = sc + 32; double* fin = sc + 48;
   int* esh = reinterpret_cast<int*>(sc + 64);
@@ -1339,34 +1365,34 @@ __global__ __launch_bounds__(kChainThreads) void resident_chain_kernel(ResidentA
       }
       grid_barrier(a.bar, ++phase, a.abort, a.spin_limit);
 
-      // ---- B: u of the row group
-      if (i > 0 && w == 0) {
-        int e = INT_MIN;
-#pragma unroll
-        for (int x = 0; x < kComputeUnits / kWave; ++x) {
-          const int o = lane + x * kWave;
-          const int v = __hip_atomic_load(a.emax + (o < G ? o : G - 1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          e = max(e, v);
-        }
-#pragma unroll
-        for (int o = 32; o >= 1; o >>= 1) e = max(e, __shfl_xor(e, o));
-        if (lane == 0) esh[0] = e;
-      }
+      // ---- B: u of the row group.  All loads of the step are issued before the first is used.
       double usum = 0.0;
-      if (tid < TR) {
-        const double* src = a.upart + (size_t)p * Q * TR + tid;
-        for (int q0 = 0; q0 < Q; q0 += 16) {
-          double x[16];
+      {
+        constexpr int kBatch = 8;
+        const double* src = a.upart + (size_t)p * Q * TR + (tid < TR ? tid : TR - 1);
+        double x[kBatch];
+        load_partials<kBatch>(src, TR, 0, 1, Q < kBatch ? Q : kBatch, x);
+        const double cs = share_load(a.cpart, Q);
+        if (i > 0 && w == 0) {
+          int e = INT_MIN;
 #pragma unroll
-          for (int j = 0; j < 16; ++j) {
-            const double v = load_dev(src + (size_t)(q0 + j < Q ? q0 + j : Q - 1) * TR);
-            x[j] = q0 + j < Q ? v : 0.0;
+          for (int x4 = 0; x4 < kComputeUnits / kWave; ++x4) {
+            const int o = lane + x4 * kWave;
+            e = max(e, __hip_atomic_load(a.emax + (o < G ? o : G - 1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
           }
 #pragma unroll
-          for (int j = 0; j < 16; ++j) usum += x[j];
+          for (int o = 32; o >= 1; o >>= 1) e = max(e, __shfl_xor(e, o));
+          if (lane == 0) esh[0] = e;
         }
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) usum += j < Q ? x[j] : 0.0;
+        for (int q0 = kBatch; q0 < Q; q0 += kBatch) {   // more column groups: further round trips
+          load_partials<kBatch>(src, TR, q0, 1, Q - q0 < kBatch ? Q - q0 : kBatch, x);
+#pragma unroll
+          for (int j = 0; j < kBatch; ++j) usum += q0 + j < Q ? x[j] : 0.0;
+        }
+        share_sums(cs, a.cpart, Q, k, sig, sc);
       }
-      all_share_sums(a.cpart, G, k, sig, sc);
       __syncthreads();
       double rs = 1.0;
       if (i > 0) {
@@ -1380,7 +1406,7 @@ __global__ __launch_bounds__(kChainThreads) void resident_chain_kernel(ResidentA
         uf[tid] = (float)t;
       }
       __syncthreads();
-      dot_shares(ucode, lut, ush, row_lo, row_hi, k, a.dpart);
+      dot_shares(ucode, lut, ush, TR, k, Q, q, p, a.dpart);
       if (last_app) {
         const double x = (tid >= row_lo && tid < row_hi) ? ush[tid] * ush[tid] : 0.0;
         const double t = wave_sum(x);
@@ -1448,24 +1474,45 @@ __global__ __launch_bounds__(kChainThreads) void resident_chain_kernel(ResidentA
       grid_barrier(a.bar, ++phase, a.abort, a.spin_limit);
 
       // ---- D: z of the column group, the next input
+      {
+        // two adjacent columns per load; with one sweep two threads share a pair and take every
+        // second row group each
+        constexpr int kPairs = TC / 2, H = T / kPairs;
+        const int cp = tid % kPairs, half = tid / kPairs;
+        const unsigned long long* src = reinterpret_cast<const unsigned long long*>(a.zpart + (size_t)q * TC + 2 * cp);
+        const size_t step = (size_t)Q * TC / 2;
+        const int cnt = (P - half + H - 1) / H;   // row groups half, half + H, ..
+        constexpr int kBatch = 16;
+        const double ds = share_load(a.dpart, P);
+        double z0 = 0.0, z1 = 0.0;
+        unsigned long long x[kBatch];
+        load_partials<kBatch>(src, step, half < P ? half : 0, H, cnt < 1 ? 1 : (cnt < kBatch ? cnt : kBatch), x);
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+          const bool live = j < cnt;
+          z0 += live ? (double)__uint_as_float((unsigned)x[j]) : 0.0;
+          z1 += live ? (double)__uint_as_float((unsigned)(x[j] >> 32)) : 0.0;
+        }
+        for (int i0 = kBatch; i0 < cnt; i0 += kBatch) {   // more row groups: further round trips
+          load_partials<kBatch>(src, step, half + i0 * H, H, cnt - i0 < kBatch ? cnt - i0 : kBatch, x);
+#pragma unroll
+          for (int j = 0; j < kBatch; ++j) {
+            const bool live = i0 + j < cnt;
+            z0 += live ? (double)__uint_as_float((unsigned)x[j]) : 0.0;
+            z1 += live ? (double)__uint_as_float((unsigned)(x[j] >> 32)) : 0.0;
+          }
+        }
+        share_sums(ds, a.dpart, P, k, sig, sd);
+        zsumsh[half * TC + 2 * cp] = z0;
+        zsumsh[half * TC + 2 * cp + 1] = z1;
+      }
+      __syncthreads();
       double zsum[NSW];
 #pragma unroll
       for (int s = 0; s < NSW; ++s) {
-        zsum[s] = 0.0;
-        const float* src = a.zpart + (size_t)q * TC + s * 512 + tid;
-        for (int p0 = 0; p0 < P; p0 += 32) {
-          float x[32];
-#pragma unroll
-          for (int j = 0; j < 32; ++j) {
-            const float v = load_dev(src + (size_t)(p0 + j < P ? p0 + j : P - 1) * Q * TC);
-            x[j] = p0 + j < P ? v : 0.f;
-          }
-#pragma unroll
-          for (int j = 0; j < 32; ++j) zsum[s] += (double)x[j];
-        }
+        zsum[s] = zsumsh[s * 512 + tid];
+        if (NSW == 1) zsum[s] += zsumsh[TC + s * 512 + tid];
       }
-      all_share_sums(a.dpart, G, k, sig, sd);
-      __syncthreads();
       int e = INT_MIN;
       double q2 = 0.0;
 #pragma unroll
@@ -1484,7 +1531,7 @@ __global__ __launch_bounds__(kChainThreads) void resident_chain_kernel(ResidentA
       }
       __syncthreads();
       if (!last_app) {
-        dot_shares(vcode, lut, vsh, col_lo, col_hi, k, a.cpart);
+        dot_shares(vcode, lut, vsh, TC, k, P, p, q, a.cpart);
 #pragma unroll
         for (int o = 32; o >= 1; o >>= 1) e = max(e, __shfl_xor(e, o));
         if (lane == 0) esh[1 + w] = e;
@@ -1535,7 +1582,7 @@ __global__ __launch_bounds__(kChainThreads) void resident_chain_kernel(ResidentA
       }
     }
     __syncthreads();
-    if (k + 1 < a.r) dot_shares(vcode, lut, vsh, col_lo, col_hi, k + 1, a.cpart);
+    if (k + 1 < a.r) dot_shares(vcode, lut, vsh, TC, k + 1, P, p, q, a.cpart);
     __syncthreads();   // vsh shares its memory with step A's sums
   }
 
