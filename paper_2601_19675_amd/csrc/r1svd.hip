@@ -1207,30 +1207,29 @@ __device__ __forceinline__ void load_partials(const PT* src, size_t stride, int 
 }
 
 // (decoded codes of rank j) . vec over `len` entries, for the ranks j < k that fall to this
-// workgroup (j = owner modulo owners), left in out[j][slot]: 32 lanes per rank; the codes of an
-// entry's 16 ranks are adjacent
+// workgroup (j = owner modulo owners), left in out[j][slot].  The whole workgroup works on one
+// rank at a time (an entry per thread, then a sum over the workgroup in a fixed order); the
+// codes of an entry's 16 ranks are adjacent.  Contains workgroup barriers; `scratch`: 8 doubles.
 template <typename VT>
 __device__ __forceinline__ void dot_shares(const uint8_t* codes, const float* lut, const VT* vec, int len, int k,
-                                           int owners, int owner, int slot, double* out) {
-  const int j = threadIdx.x / 32, part = threadIdx.x % 32;
-  const bool mine = j < k && j % owners == owner;
-  double t = 0.0;
-  if (mine) {
-    // four entries at a time: each costs two dependent LDS reads
-    double t4[4] = {0.0, 0.0, 0.0, 0.0};
-    for (int x0 = part; x0 < len; x0 += 128) {
+                                           int owners, int owner, int slot, double* out, double* scratch) {
+  const int tid = threadIdx.x;
+  for (int j = owner; j < k; j += owners) {
+    double t = 0.0;
+    for (int x = tid; x < len; x += kChainThreads)
+      t = fma((double)lut[codes[(size_t)x * kMaxStreamRank + j]], (double)vec[x], t);
+    t = sum32(t);
+    t += __shfl_xor(t, 32);
+    if ((tid & 63) == 0) scratch[tid >> 6] = t;
+    __syncthreads();
+    if (tid == 0) {
+      double total = 0.0;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int x = x0 + 32 * i;
-        const int xc = x < len ? x : len - 1;
-        const double v = (double)lut[codes[(size_t)xc * kMaxStreamRank + j]] * (double)vec[xc];
-        t4[i] += x < len ? v : 0.0;
-      }
+      for (int wv = 0; wv < kChainThreads / kWave; ++wv) total += scratch[wv];
+      store_dev(out + (size_t)j * kComputeUnits + slot, total);
     }
-    t = (t4[0] + t4[1]) + (t4[2] + t4[3]);
+    __syncthreads();
   }
-  t = sum32(t);
-  if (part == 0 && mine) store_dev(out + (size_t)j * kComputeUnits + slot, t);
 }
 
 // sum_j coef[j] * (decoded code j of the 16 adjacent codes at `codes`), j < k
@@ -1406,7 +1405,7 @@ __global__ __launch_bounds__(kChainThreads) void resident_chain_kernel(ResidentA
         uf[tid] = (float)t;
       }
       __syncthreads();
-      dot_shares(ucode, lut, ush, TR, k, Q, q, p, a.dpart);
+      dot_shares(ucode, lut, ush, TR, k, Q, q, p, a.dpart, fin);
       if (last_app) {
         const double x = (tid >= row_lo && tid < row_hi) ? ush[tid] * ush[tid] : 0.0;
         const double t = wave_sum(x);
@@ -1531,7 +1530,7 @@ __global__ __launch_bounds__(kChainThreads) void resident_chain_kernel(ResidentA
       }
       __syncthreads();
       if (!last_app) {
-        dot_shares(vcode, lut, vsh, TC, k, P, p, q, a.cpart);
+        dot_shares(vcode, lut, vsh, TC, k, P, p, q, a.cpart, fin);
 #pragma unroll
         for (int o = 32; o >= 1; o >>= 1) e = max(e, __shfl_xor(e, o));
         if (lane == 0) esh[1 + w] = e;
@@ -1582,7 +1581,7 @@ __global__ __launch_bounds__(kChainThreads) void resident_chain_kernel(ResidentA
       }
     }
     __syncthreads();
-    if (k + 1 < a.r) dot_shares(vcode, lut, vsh, TC, k + 1, P, p, q, a.cpart);
+    if (k + 1 < a.r) dot_shares(vcode, lut, vsh, TC, k + 1, P, p, q, a.cpart, fin);
     __syncthreads();   // vsh shares its memory with step A's sums
   }
 
