@@ -274,14 +274,19 @@ ptq_status ptq_activation_scale(const double* asum, int64_t tokens, int64_t n, d
  * R      m x n float32 output, ldr >= n, ldr % 4 == 0, 16-byte aligned.  May not alias W.
  * r, it  rank and number of power iterations (the paper uses 16 and 8); r = 0 gives R = W.
  * n % 4 == 0 and n <= 32768.
- * The running matrix is held in float32, every product and sum is float64 in a fixed
- * order: results are reproducible run to run.
+ * The running matrix W diag(s) - sum of the stored rank-one terms is held in float32 and
+ * rewritten at every rank, or -- for a bfloat16 W with n % 8 == 0, ldw % 8 == 0, 16-byte aligned,
+ * r <= 16, too large for the first case -- never formed: the products are taken from W as it
+ * is (kept on the chip if it fits there, else streamed) and the stored ranks are applied as
+ * corrections.  Sums across threads are float64 in a fixed order: results are reproducible
+ * run to run.
  * The loop runs as ONE cooperative launch where the device can hold it, its workgroups waiting
  * for each other's partial sums; a workgroup that waits longer than a fixed number of rounds
  * (about a second) gives up and makes all others give up: the call still completes, and every
  * entry of sigma is then the NaN pattern 0x7e00.  Two environment variables, read at every
- * call, exist for tests and comparisons: PTQ_R1SVD_LAUNCH = "rows" | "steps" selects a slower
- * form of the same loop, PTQ_R1SVD_SPIN_LIMIT = <rounds> sets that number of rounds.
+ * call, exist for tests and comparisons: PTQ_R1SVD_LAUNCH = "resident" | "stream" | "rows" |
+ * "steps" selects another form of the same loop than the one the shapes call for,
+ * PTQ_R1SVD_SPIN_LIMIT = <rounds> sets that number of rounds.
  * Workspace: PTQ_OP_SCALED_R1SVD (m, n).
  * Errors: PTQ_ERR_ARG, PTQ_ERR_SHAPE, PTQ_ERR_DTYPE, PTQ_ERR_WORKSPACE, PTQ_ERR_HIP.
  */
