@@ -1080,31 +1080,73 @@ __global__ __launch_bounds__(256) void narrow_scale_kernel(const double* __restr
   if (c < n) sf[c] = (float)s[c];
 }
 
+// ---- words that carry their own arrival flag ---------------------------------------------------
+// What workgroups of one launch hand to each other without a barrier in between is an 8-byte word:
+// the value in the low half, the number of the application it belongs to in the high half,
+// written with one device-coherent store.  A reader loads the words it needs and loads them again
+// until their high halves show the application it is waiting for: store, signal and load cost
+// one trip to memory instead of three.  A reader gives up after spin_limit rounds and raises
+// `abort`, which ends every later wait at once.
+__device__ __forceinline__ void store_tagged(unsigned long long* p, unsigned bits, unsigned tag) {
+  __hip_atomic_store(p, (unsigned long long)bits | ((unsigned long long)tag << 32), __ATOMIC_RELAXED,
+                     __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned long long load_tagged(const unsigned long long* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// One round of waiting for tagged words: false when the wait is to be abandoned.
+__device__ __forceinline__ bool keep_waiting(unsigned& spins, int* abort, unsigned spin_limit) {
+  if ((spins & 63u) == 63u && __hip_atomic_load(abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return false;
+  if (++spins > spin_limit) {
+    __hip_atomic_store(abort, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return false;
+  }
+  __builtin_amdgcn_s_sleep(1);
+  return true;
+}
+
+// 2^-e as a double for the exponent that travels with the data (INT_MIN: nothing to scale).
+__device__ __forceinline__ double unscale(int e) {
+  if (e == INT_MIN) return 1.0;
+  return scalbn(1.0, -(e > 126 ? 126 : (e < -126 ? -126 : e)));
+}
+
 // ---- the loop on a bfloat16 weight that fits the registers and LDS of the chip -----------------
 // The same products as the stream form, but the weight is read ONCE: the matrix is cut into
 // P x Q tiles (P Q <= 256), workgroup (p, q) keeps its tile for the whole loop -- 8 waves, a
 // band of rows per wave, the first RR rows of a band packed in registers (128 per thread), the
 // others in LDS -- and an application is
-//   A  partial u of the tile from v (the tile's columns)            -> upart, grid barrier
+//   A  partial u of the tile from v (the tile's columns)            -> upart
 //   B  u of the tile's rows = sum over the Q tiles of the row group - corrections
-//   C  partial z of the tile from u                                  -> zpart, grid barrier
+//   C  partial z of the tile from u                                  -> zpart
 //   D  z of the tile's columns = s o (sum over the P tiles of the column group) - corrections
 // so what crosses the chip is P n + Q m numbers per application instead of 256 n, and nothing
-// is streamed.  Every tile of a row group derives the same u, every tile of a column group the
-// same z (same loads, same order), so the small jobs are shared out: of the dot products with
-// the stored ranks tile (p, q) takes rank j = q (mod Q) for its row group and j = p (mod P) for
-// its column group; of the norms and the largest exponent it takes the q-th part of its rows
-// and the p-th part of its columns.  The power of two that keeps the vectors in range is
-// applied to u (A is linear).  7B-sized MLP projections (90 MB) just fit: 352 KB per compute unit.
+// is streamed.  There is no barrier inside an application: everything exchanged is a tagged
+// word (float32 partial sums; the float64 dot products as a high and a low float32), and two
+// buffers alternate.  A tile writes the words of application i + 2 only after it has seen those
+// of application i + 1 from everybody it exchanges with, and each of them published those after
+// it had read application i; for the dot products, which everybody reads, the same follows
+// through one more exchange (row group, then column group, reach every tile).  Only the norms
+// of a rank's last vectors meet at a grid barrier, once per rank.
+// Every tile of a row group derives the same u, every tile of a column group the same z (same
+// loads, same order), so the small jobs are shared out: of the dot products with the stored
+// ranks tile (p, q) takes rank j = q (mod Q) for its row group and j = p (mod P) for its column
+// group; of the norms it takes the q-th part of its rows and the p-th part of its columns.
+// The power of two that keeps the vectors in range travels with the partial u (the exponent of
+// the largest entry of the tile's columns of v; a row group sees all columns) and is applied
+// to u, A being linear.  7B-sized MLP projections (90 MB) just fit: 352 KB per compute unit.
+constexpr int kResidentRows = 512, kResidentCols = 1024;   // words per workgroup in upart, zpart
+constexpr size_t kShareWords = (size_t)kMaxStreamRank * kComputeUnits * 2;   // one buffer of cpart or dpart
+
 struct ResidentArgs {
   const uint16_t* W; int64_t ldw; int m, n;
   const float* sf; const float* S; int64_t lds; int r, it;
   uint8_t* U; uint8_t* V; uint16_t* sigma16;
-  double* upart;            // [workgroup][8 RW]
-  float* zpart;             // [workgroup][TC]
+  unsigned long long* upart;   // tagged [2][workgroup][kResidentRows]: partial u, then the exponent of the tile's v
+  unsigned long long* zpart;   // tagged [2][workgroup][kResidentCols]: partial z
+  unsigned long long* cpart;   // tagged [2][kMaxStreamRank][kComputeUnits][2]: (V_j . v) per column group
+  unsigned long long* dpart;   // tagged [2][kMaxStreamRank][kComputeUnits][2]: (U_j . u) per row group
   double* unrm2; double* normpart;   // per workgroup
-  double* cpart; double* dpart;      // [kMaxStreamRank][kComputeUnits]: per column group, per row group
-  int* emax;                // per workgroup: largest exponent in its share of z
   unsigned* bar; int* abort; unsigned spin_limit;
   int P, Q, RW;             // row groups, column groups, rows per wave
 };
@@ -1177,42 +1219,49 @@ __device__ __forceinline__ double wave_row_sums_staged(const float (&us)[8], flo
   return sum8(t);
 }
 
-// Sum of the first `count` entries of row j = thread / 32 of a [kMaxStreamRank][kComputeUnits]
-// table, in two parts so that the load can be issued together with a step's other loads (a load
-// whose value is used at once costs a memory round trip of its own).  Up to 32 entries are one
-// load per lane; more (small matrices cut into many row groups) are loaded on the spot.
-__device__ __forceinline__ double share_load(const double* table, int count) {
-  const int j = threadIdx.x / 32, part = threadIdx.x % 32;
-  // issued whatever the index: a load under a condition is compiled to a branch and a wait
-  return load_dev(table + (size_t)j * kComputeUnits + (part < count ? part : count - 1));
+// A float64 as two tagged words: the nearest float32 and the float32 nearest to what is left.
+__device__ __forceinline__ void store_tagged_pair(unsigned long long* p, double v, unsigned tag) {
+  const float hi = (float)v;
+  const float lo = (float)(v - (double)hi);
+  store_tagged(p, __float_as_uint(hi), tag);
+  store_tagged(p + 1, __float_as_uint(lo), tag);
 }
-// out[j] = sig[j] * sum, j < k
-__device__ __forceinline__ void share_sums(double first, const double* table, int count, int k, const double* sig,
-                                           double* out) {
+
+// Sum over the first `count` slots of row j = thread / 32 of a tagged [kMaxStreamRank]
+// [kComputeUnits][2] table, for the rows j < k; waits for the tag.  out[j] = sig[j] * sum.
+__device__ __forceinline__ void tagged_share_sums(const unsigned long long* table, int count, int k, unsigned tag,
+                                                  const double* sig, double* out, int* abort, unsigned spin_limit) {
+  if (k == 0) return;
   const int j = threadIdx.x / 32, part = threadIdx.x % 32;
-  double t = part < count ? first : 0.0;
-  for (int o = part + 32; o < count; o += 32) t += load_dev(table + (size_t)j * kComputeUnits + o);
+  const unsigned long long* row = table + (size_t)j * kComputeUnits * 2;
+  double t = 0.0;
+  unsigned spins = 0;
+  for (int o0 = 0; o0 < count; o0 += 32) {
+    const int o = o0 + part;
+    const bool want = j < k && o < count;
+    const unsigned long long* w2 = row + (size_t)(o < count ? o : count - 1) * 2;
+    unsigned long long hi, lo;
+    bool ready;
+    do {
+      hi = load_tagged(w2);
+      lo = load_tagged(w2 + 1);
+      ready = !want || ((unsigned)(hi >> 32) == tag && (unsigned)(lo >> 32) == tag);
+    } while (!ready && keep_waiting(spins, abort, spin_limit));
+    t += want ? (double)__uint_as_float((unsigned)hi) + (double)__uint_as_float((unsigned)lo) : 0.0;
+  }
   t = sum32(t);
   if (part == 0 && j < k) out[j] = sig[j] * t;
 }
 
-// N partial sums `stride` apart, of which the first `count` are wanted (count >= 1): all issued
-template <int N, typename PT>
-__device__ __forceinline__ void load_partials(const PT* src, size_t stride, int first, int step, int count, PT* x) {
-#pragma unroll
-  for (int j = 0; j < N; ++j) {
-    const int i = first + (j < count ? j : count - 1) * step;
-    x[j] = __hip_atomic_load(src + (size_t)i * stride, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  }
-}
-
 // (decoded codes of rank j) . vec over `len` entries, for the ranks j < k that fall to this
-// workgroup (j = owner modulo owners), left in out[j][slot].  The whole workgroup works on one
-// rank at a time (an entry per thread, then a sum over the workgroup in a fixed order); the
-// codes of an entry's 16 ranks are adjacent.  Contains workgroup barriers; `scratch`: 8 doubles.
+// workgroup (j = owner modulo owners), left in out[j][slot] as a tagged pair.  The whole
+// workgroup works on one rank at a time (an entry per thread, then a sum over the workgroup in
+// a fixed order); the codes of an entry's 16 ranks are adjacent.  Contains workgroup barriers;
+// `scratch`: 8 doubles.
 template <typename VT>
 __device__ __forceinline__ void dot_shares(const uint8_t* codes, const float* lut, const VT* vec, int len, int k,
-                                           int owners, int owner, int slot, double* out, double* scratch) {
+                                           int owners, int owner, int slot, unsigned long long* out, unsigned tag,
+                                           double* scratch) {
   const int tid = threadIdx.x;
   for (int j = owner; j < k; j += owners) {
     double t = 0.0;
@@ -1226,7 +1275,7 @@ __device__ __forceinline__ void dot_shares(const uint8_t* codes, const float* lu
       double total = 0.0;
 #pragma unroll
       for (int wv = 0; wv < kChainThreads / kWave; ++wv) total += scratch[wv];
-      store_dev(out + (size_t)j * kComputeUnits + slot, total);
+      store_tagged_pair(out + ((size_t)j * kComputeUnits + slot) * 2, total, tag);
     }
     __syncthreads();
   }
@@ -1260,7 +1309,6 @@ __global__ __launch_bounds__(kChainThreads) void resident_chain_kernel(ResidentA
   float* stage = reinterpret_cast<float*>(lds_raw + L.shared) + w * 512;
   float* zred = reinterpret_cast<float*>(lds_raw + L.shared);
   float* vsh = reinterpret_cast<float*>(lds_raw + L.shared);
-  double* zsumsh = reinterpret_cast<double*>(lds_raw + L.shared + 4096);   // 8 KB, next to vsh
   double* sc = reinterpret_cast<double*>(lds_raw + L.small);
   double* sd = sc + 16; double* sig = sc + 32; double* fin = sc + 48;
   int* esh = reinterpret_cast<int*>(sc + 64);
@@ -1303,11 +1351,19 @@ __global__ __launch_bounds__(kChainThreads) void resident_chain_kernel(ResidentA
   const int row_lo = (int)((int64_t)q * TR / Q), row_hi = (int)((int64_t)(q + 1) * TR / Q);
   const int col_lo = (int)((int64_t)p * TC / P), col_hi = (int)((int64_t)(p + 1) * TC / P);
   unsigned phase = 0;
+  unsigned app = 0;       // applications so far: the tag of what this one exchanges
+  int ecol = INT_MIN;     // exponent of the largest entry of this tile's columns of v (INT_MIN: do not scale)
 
   for (int k = 0; k < a.r; ++k) {
     double zcur[NSW];
     for (int i = 0; i <= a.it; ++i) {
       const bool last_app = i == a.it;
+      ++app;
+      unsigned long long* const up = a.upart + ((size_t)(app & 1u) * G + b) * kResidentRows;
+      unsigned long long* const zp = a.zpart + ((size_t)(app & 1u) * G + b) * kResidentCols;
+      const unsigned long long* const cin = a.cpart + (size_t)(app & 1u) * kShareWords;
+      unsigned long long* const dio = a.dpart + (size_t)(app & 1u) * kShareWords;
+      unsigned long long* const cout = a.cpart + (size_t)((app + 1) & 1u) * kShareWords;
       // ---- A: partial u of the tile
       {
         float sv[NSW][8];
@@ -1360,52 +1416,49 @@ __global__ __launch_bounds__(kChainThreads) void resident_chain_kernel(ResidentA
       __syncthreads();
       if (tid < TR) {
         const int wv = tid / RW, x = tid - wv * RW;
-        store_dev(a.upart + (size_t)b * TR + tid, ustage[(x >> 3) * 64 + wv * 8 + (x & 7)]);
+        store_tagged(up + tid, __float_as_uint((float)ustage[(x >> 3) * 64 + wv * 8 + (x & 7)]), app);
+      } else if (tid == TR) {
+        store_tagged(up + TR, (unsigned)ecol, app);
       }
-      grid_barrier(a.bar, ++phase, a.abort, a.spin_limit);
 
-      // ---- B: u of the row group.  All loads of the step are issued before the first is used.
+      // ---- B: u of the row group.  Thread t < TR adds up row t's partial sums, thread TR takes the
+      // largest of the exponents; all loads of a round are issued before the first is looked at.
       double usum = 0.0;
       {
-        constexpr int kBatch = 8;
-        const double* src = a.upart + (size_t)p * Q * TR + (tid < TR ? tid : TR - 1);
-        double x[kBatch];
-        load_partials<kBatch>(src, TR, 0, 1, Q < kBatch ? Q : kBatch, x);
-        const double cs = share_load(a.cpart, Q);
-        if (i > 0 && w == 0) {
-          int e = INT_MIN;
+        constexpr int kBatch = 12;
+        const unsigned long long* src = a.upart + ((size_t)(app & 1u) * G + (size_t)p * Q) * kResidentRows + (tid < TR ? tid : TR);
+        int e_in = INT_MIN;
+        unsigned spins = 0;
+        for (int q0 = 0; q0 < Q; q0 += kBatch) {
+          const int cnt = Q - q0 < kBatch ? Q - q0 : kBatch;
+          unsigned long long x[kBatch];
+          bool ready;
+          do {
+            ready = true;
 #pragma unroll
-          for (int x4 = 0; x4 < kComputeUnits / kWave; ++x4) {
-            const int o = lane + x4 * kWave;
-            e = max(e, __hip_atomic_load(a.emax + (o < G ? o : G - 1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+            for (int j = 0; j < kBatch; ++j) {
+              x[j] = load_tagged(src + (size_t)(q0 + (j < cnt ? j : cnt - 1)) * kResidentRows);
+              ready = ready && (unsigned)(x[j] >> 32) == app;
+            }
+          } while (!ready && keep_waiting(spins, a.abort, a.spin_limit));
+#pragma unroll
+          for (int j = 0; j < kBatch; ++j) {
+            usum += j < cnt ? (double)__uint_as_float((unsigned)x[j]) : 0.0;
+            e_in = max(e_in, j < cnt ? (int)(unsigned)x[j] : INT_MIN);
           }
-#pragma unroll
-          for (int o = 32; o >= 1; o >>= 1) e = max(e, __shfl_xor(e, o));
-          if (lane == 0) esh[0] = e;
         }
-#pragma unroll
-        for (int j = 0; j < kBatch; ++j) usum += j < Q ? x[j] : 0.0;
-        for (int q0 = kBatch; q0 < Q; q0 += kBatch) {   // more column groups: further round trips
-          load_partials<kBatch>(src, TR, q0, 1, Q - q0 < kBatch ? Q - q0 : kBatch, x);
-#pragma unroll
-          for (int j = 0; j < kBatch; ++j) usum += q0 + j < Q ? x[j] : 0.0;
-        }
-        share_sums(cs, a.cpart, Q, k, sig, sc);
+        if (tid == TR) esh[0] = e_in;
+        tagged_share_sums(cin, Q, k, app, sig, sc, a.abort, a.spin_limit);
       }
       __syncthreads();
-      double rs = 1.0;
-      if (i > 0) {
-        int e = esh[0];
-        e = e == INT_MIN ? 0 : (e > 126 ? 126 : (e < -126 ? -126 : e));
-        rs = scalbn(1.0, -e);
-      }
+      const double rs = unscale(esh[0]);
       if (tid < TR) {
         const double t = (usum - stored_ranks_dot(ucode + (size_t)tid * KR, lut, sc, k)) * rs;
         ush[tid] = t;
         uf[tid] = (float)t;
       }
       __syncthreads();
-      dot_shares(ucode, lut, ush, TR, k, Q, q, p, a.dpart, fin);
+      dot_shares(ucode, lut, ush, TR, k, Q, q, p, dio, app, fin);
       if (last_app) {
         const double x = (tid >= row_lo && tid < row_hi) ? ush[tid] * ush[tid] : 0.0;
         const double t = wave_sum(x);
@@ -1467,51 +1520,38 @@ __global__ __launch_bounds__(kChainThreads) void resident_chain_kernel(ResidentA
           double t = 0.0;
 #pragma unroll
           for (int wv = 0; wv < T / kWave; ++wv) t += (double)zred[wv * 512 + tid];
-          store_dev(a.zpart + (size_t)b * TC + s * 512 + tid, (float)t);
+          store_tagged(zp + s * 512 + tid, __float_as_uint((float)t), app);
         }
       }
-      grid_barrier(a.bar, ++phase, a.abort, a.spin_limit);
 
       // ---- D: z of the column group, the next input
+      double zsum[NSW];
       {
-        // two adjacent columns per load; with one sweep two threads share a pair and take every
-        // second row group each
-        constexpr int kPairs = TC / 2, H = T / kPairs;
-        const int cp = tid % kPairs, half = tid / kPairs;
-        const unsigned long long* src = reinterpret_cast<const unsigned long long*>(a.zpart + (size_t)q * TC + 2 * cp);
-        const size_t step = (size_t)Q * TC / 2;
-        const int cnt = (P - half + H - 1) / H;   // row groups half, half + H, ..
         constexpr int kBatch = 16;
-        const double ds = share_load(a.dpart, P);
-        double z0 = 0.0, z1 = 0.0;
-        unsigned long long x[kBatch];
-        load_partials<kBatch>(src, step, half < P ? half : 0, H, cnt < 1 ? 1 : (cnt < kBatch ? cnt : kBatch), x);
+        unsigned spins = 0;
 #pragma unroll
-        for (int j = 0; j < kBatch; ++j) {
-          const bool live = j < cnt;
-          z0 += live ? (double)__uint_as_float((unsigned)x[j]) : 0.0;
-          z1 += live ? (double)__uint_as_float((unsigned)(x[j] >> 32)) : 0.0;
-        }
-        for (int i0 = kBatch; i0 < cnt; i0 += kBatch) {   // more row groups: further round trips
-          load_partials<kBatch>(src, step, half + i0 * H, H, cnt - i0 < kBatch ? cnt - i0 : kBatch, x);
+        for (int s = 0; s < NSW; ++s) {
+          zsum[s] = 0.0;
+          const unsigned long long* src = a.zpart + ((size_t)(app & 1u) * G + q) * kResidentCols + s * 512 + tid;
+          for (int p0 = 0; p0 < P; p0 += kBatch) {
+            const int cnt = P - p0 < kBatch ? P - p0 : kBatch;
+            unsigned long long x[kBatch];
+            bool ready;
+            do {
+              ready = true;
 #pragma unroll
-          for (int j = 0; j < kBatch; ++j) {
-            const bool live = i0 + j < cnt;
-            z0 += live ? (double)__uint_as_float((unsigned)x[j]) : 0.0;
-            z1 += live ? (double)__uint_as_float((unsigned)(x[j] >> 32)) : 0.0;
+              for (int j = 0; j < kBatch; ++j) {
+                x[j] = load_tagged(src + (size_t)(p0 + (j < cnt ? j : cnt - 1)) * Q * kResidentCols);
+                ready = ready && (unsigned)(x[j] >> 32) == app;
+              }
+            } while (!ready && keep_waiting(spins, a.abort, a.spin_limit));
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) zsum[s] += j < cnt ? (double)__uint_as_float((unsigned)x[j]) : 0.0;
           }
         }
-        share_sums(ds, a.dpart, P, k, sig, sd);
-        zsumsh[half * TC + 2 * cp] = z0;
-        zsumsh[half * TC + 2 * cp + 1] = z1;
+        tagged_share_sums(dio, P, k, app, sig, sd, a.abort, a.spin_limit);
       }
       __syncthreads();
-      double zsum[NSW];
-#pragma unroll
-      for (int s = 0; s < NSW; ++s) {
-        zsum[s] = zsumsh[s * 512 + tid];
-        if (NSW == 1) zsum[s] += zsumsh[TC + s * 512 + tid];
-      }
       int e = INT_MIN;
       double q2 = 0.0;
 #pragma unroll
@@ -1523,25 +1563,21 @@ __global__ __launch_bounds__(kChainThreads) void resident_chain_kernel(ResidentA
         const float zf = (float)zz;
         vsh[cl] = zf;
         svsh[cl] = zf * sfc[s];
-        if (cl >= col_lo && cl < col_hi) {
-          if (zz != 0.0 && fabs(zz) < __builtin_inf()) e = max(e, ilogb(zz));
-          q2 = fma(zz, zz, q2);
-        }
+        if (zz != 0.0 && fabs(zz) < __builtin_inf()) e = max(e, ilogb(zz));
+        if (cl >= col_lo && cl < col_hi) q2 = fma(zz, zz, q2);
       }
       __syncthreads();
       if (!last_app) {
-        dot_shares(vcode, lut, vsh, TC, k, P, p, q, a.cpart, fin);
+        dot_shares(vcode, lut, vsh, TC, k, P, p, q, cout, app + 1, fin);
 #pragma unroll
         for (int o = 32; o >= 1; o >>= 1) e = max(e, __shfl_xor(e, o));
         if (lane == 0) esh[1 + w] = e;
         __syncthreads();
-        if (tid == 0) {
-          int em = INT_MIN;
+        ecol = INT_MIN;
 #pragma unroll
-          for (int wv = 0; wv < T / kWave; ++wv) em = max(em, esh[1 + wv]);
-          __hip_atomic_store(a.emax + b, em, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
+        for (int wv = 0; wv < T / kWave; ++wv) ecol = max(ecol, esh[1 + wv]);
       } else {
+        ecol = INT_MIN;   // the next rank starts from a sketch vector
         const double t = wave_sum(q2);
         if (lane == 0) fin[w] = t;
         __syncthreads();
@@ -1581,7 +1617,8 @@ __global__ __launch_bounds__(kChainThreads) void resident_chain_kernel(ResidentA
       }
     }
     __syncthreads();
-    if (k + 1 < a.r) dot_shares(vcode, lut, vsh, TC, k + 1, P, p, q, a.cpart, fin);
+    if (k + 1 < a.r)
+      dot_shares(vcode, lut, vsh, TC, k + 1, P, p, q, a.cpart + (size_t)((app + 1) & 1u) * kShareWords, app + 1, fin);
     __syncthreads();   // vsh shares its memory with step A's sums
   }
 
@@ -1634,30 +1671,6 @@ __global__ void tile_init_kernel(unsigned* words, int count, int* abort) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < count) words[i] = 0u;
   if (i == 0) *abort = 0;
-}
-
-__device__ __forceinline__ void store_tagged(unsigned long long* p, unsigned bits, unsigned tag) {
-  __hip_atomic_store(p, (unsigned long long)bits | ((unsigned long long)tag << 32), __ATOMIC_RELAXED,
-                     __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ unsigned long long load_tagged(const unsigned long long* p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-// One round of waiting for tagged words: false when the wait is to be abandoned.
-__device__ __forceinline__ bool keep_waiting(unsigned& spins, int* abort, unsigned spin_limit) {
-  if ((spins & 63u) == 63u && __hip_atomic_load(abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return false;
-  if (++spins > spin_limit) {
-    __hip_atomic_store(abort, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return false;
-  }
-  __builtin_amdgcn_s_sleep(1);
-  return true;
-}
-
-// 2^-e as a double for the exponent that travels with the data (INT_MIN: nothing to scale).
-__device__ __forceinline__ double unscale(int e) {
-  if (e == INT_MIN) return 1.0;
-  return scalbn(1.0, -(e > 126 ? 126 : (e < -126 ? -126 : e)));
 }
 
 // Sum of squares of an LDS array over the workgroup, fixed order; the same value in every thread.
@@ -1938,11 +1951,11 @@ constexpr size_t kTileWorkspaceBytes = 2 * kTilePartBytes + 2 * kTileNormBytes;
 constexpr int kMaxChainApps = 16384;   // applications (rank x iteration) one cooperative launch can hold
 constexpr size_t kChainVectorBytes = size_t{16} << 20;   // room for their float32 copies of z
 
-// resident form: partial u (at most 512 rows per tile, float64), partial z (at most 1024 columns,
-// float32) and the exponents
-constexpr size_t kResidentUpartBytes = (size_t)kComputeUnits * 512 * sizeof(double);
-constexpr size_t kResidentZpartBytes = (size_t)kComputeUnits * 1024 * sizeof(float);
-constexpr size_t kResidentWorkspaceBytes = kResidentUpartBytes + kResidentZpartBytes + kComputeUnits * sizeof(int);
+// resident form: two buffers each of tagged partial u, partial z and the two tables of dot products
+constexpr size_t kResidentUpartBytes = (size_t)2 * kComputeUnits * kResidentRows * sizeof(unsigned long long);
+constexpr size_t kResidentZpartBytes = (size_t)2 * kComputeUnits * kResidentCols * sizeof(unsigned long long);
+constexpr size_t kResidentShareBytes = (size_t)2 * kShareWords * sizeof(unsigned long long);
+constexpr size_t kResidentWorkspaceBytes = kResidentUpartBytes + kResidentZpartBytes + 2 * kResidentShareBytes;
 
 struct Layout {
   size_t A, zpart, z, z32, u, unrm2, normpart, ud, vd, scalars, barrier, expo, zapp, tile, sf, shares, resident, total;
@@ -2059,7 +2072,7 @@ inline ResidentPlan resident_plan(int64_t m, int64_t n) {
     int64_t P = kComputeUnits / Q;
     const int64_t rw = ceil_div(m, 8 * P);
     P = ceil_div(m, 8 * rw);
-    if (8 * rw > kChainThreads) continue;
+    if (8 * rw >= kResidentRows) continue;   // a row per thread, and the word after the rows
     const size_t lds = resident_lds(nsw, rr, (int)rw).total;
     if (lds > kResidentMaxLds) continue;
     if (!best.ok || rw * nsw < (int64_t)best.rw * best.nsw) best = {nsw, rr, (int)rw, (int)P, (int)Q, lds, true};
@@ -2184,11 +2197,15 @@ ptq_status r1svd_launch(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m, in
     const ResidentPlan plan = resident_plan(m, n);
     if (plan.ok && !mode_is("stream")) {
       char* rw = base + L.resident;
+      // tags of an earlier call must not be mistaken for this one's: the tagged words start at zero
+      const int words = (int)(kResidentWorkspaceBytes / sizeof(unsigned));
+      tile_init_kernel<<<(unsigned)ceil_div(words, 256), 256, 0, st>>>(reinterpret_cast<unsigned*>(rw), words, abort_flag);
       ResidentArgs ra{static_cast<const uint16_t*>(W), ldw, (int)m, (int)n, sf, S, lds, r, it, U, V, sigma16,
-                      reinterpret_cast<double*>(rw), reinterpret_cast<float*>(rw + kResidentUpartBytes),
-                      unrm2, normpart, shares, shares + (size_t)kMaxStreamRank * kComputeUnits,
-                      reinterpret_cast<int*>(rw + kResidentUpartBytes + kResidentZpartBytes),
-                      bar, abort_flag, spin_limit, plan.P, plan.Q, plan.rw};
+                      reinterpret_cast<unsigned long long*>(rw),
+                      reinterpret_cast<unsigned long long*>(rw + kResidentUpartBytes),
+                      reinterpret_cast<unsigned long long*>(rw + kResidentUpartBytes + kResidentZpartBytes),
+                      reinterpret_cast<unsigned long long*>(rw + kResidentUpartBytes + kResidentZpartBytes + kResidentShareBytes),
+                      unrm2, normpart, bar, abort_flag, spin_limit, plan.P, plan.Q, plan.rw};
       launched = plan.nsw == 1 ? launch_resident<1, 32>(ra, plan, st) : launch_resident<2, 16>(ra, plan, st);
     }
     if (!launched) {
