@@ -141,6 +141,23 @@ def r1svd_timings(ptq, W, X, m, n, t, rank=16, it=8, reps=5):
     r_ms = timed(lambda: ptq.ptq_scaled_r1svd(W, s, S, it, U, V, sg, R, ws))
     apps = rank * (it + 1)
     xbytes = float(t) * n * X.element_size()
+
+    # the same loop on the two MLP projection shapes of the 7B model this layer comes from (random bfloat16
+    # weights, log-normal scale): too large for the tile form, kept on the chip as bfloat16 instead
+    mlp = {}
+    for (mm, nn) in ((11008, 4096), (4096, 11008)):
+        W2 = (torch.randn((mm, nn), generator=g, device=dev, dtype=torch.float32) * 0.02).to(torch.bfloat16)
+        s2 = torch.exp(torch.randn(nn, generator=g, device=dev, dtype=torch.float32)).double()
+        S2 = torch.randn((rank, nn), generator=g, device=dev, dtype=torch.float32)
+        U2 = torch.empty((rank, mm), dtype=torch.uint8, device=dev)
+        V2 = torch.empty((rank, nn), dtype=torch.uint8, device=dev)
+        R2 = torch.empty((mm, nn), dtype=torch.float32, device=dev)
+        ws2 = torch.empty(ptq.ptq_workspace_bytes(binding.OP_SCALED_R1SVD, mm, nn), dtype=torch.uint8, device=dev)
+        ms2 = timed(lambda: ptq.ptq_scaled_r1svd(W2, s2, S2, it, U2, V2, sg, R2, ws2))
+        mlp[f"{mm}x{nn}"] = {"ms": ms2, "us_per_application": 1e3 * ms2 / apps,
+                             "equivalent_GBps_of_unfused_gemvs": rank * (2 * it + 2) * 4.0 * mm * nn / ms2 / 1e6}
+        del W2, R2, ws2
+    ptq.ptq_scaled_r1svd(W, s, S, it, U, V, sg, R, ws)   # sg again holds this layer's sigma
     return {
         "rank": rank, "iterations": it,
         "activation_scale": {"ms": a_ms, "algorithmic_GBps": xbytes / a_ms / 1e6,
@@ -149,6 +166,7 @@ def r1svd_timings(ptq, W, X, m, n, t, rank=16, it=8, reps=5):
                    "matrix_bytes_f32": 4.0 * m * n,
                    # what a pass-per-product implementation would stream: (2 it + 2) reads of A per rank
                    "equivalent_GBps_of_unfused_gemvs": rank * (2 * it + 2) * 4.0 * m * n / r_ms / 1e6},
+        "sketch_mlp_shapes": mlp,
         "sigma_first": [float(x) for x in sg[:4].float().cpu()],
         "total_ms": a_ms + r_ms,
     }
