@@ -260,14 +260,14 @@ def test_r1svd_sigma_beyond_fp16_range(launch_mode):
     _check(W.astype(np.float64), np.ones(n), S, 3, got)
 
 
-@pytest.mark.parametrize("mode", ["single", "rows"])
+@pytest.mark.parametrize("mode", ["single", "resident", "stream", "rows"])
 def test_r1svd_gives_up_cleanly_when_the_wait_limit_is_reached(mode, monkeypatch):
     # a wait limit of zero rounds: the first workgroup that finds a partial sum not there yet raises the
     # abort flag, everybody stops waiting, the kernel runs to its end on whatever it has and marks every
     # sigma as NaN; the next ordinary call is unaffected
-    Ws, W64, s, S = _case(1024, 1024, "f32", 1300, 3)
-    if mode == "rows":
-        monkeypatch.setenv("PTQ_R1SVD_LAUNCH", "rows")
+    Ws, W64, s, S = _case(1024, 1024, "bf16" if mode in ("resident", "stream") else "f32", 1300, 3)
+    if mode != "single":
+        monkeypatch.setenv("PTQ_R1SVD_LAUNCH", mode)
     monkeypatch.setenv("PTQ_R1SVD_SPIN_LIMIT", "0")
     bad = _run_gpu(to_device(Ws), s, S, 2)
     assert np.all(np.isnan(bad[2]))
