@@ -3,20 +3,30 @@
 //
 // One rank costs  y = (A A^T)^it A v,  p = A^T y.  Written as  y = A (A^T A)^it v  this is
 // it + 1 applications of "u = A v, z = A^T u" to the same matrix, and both products of one
-// application can be taken from ONE pass over A: a workgroup owns a block of R complete rows,
-// keeps them in registers, finishes its R entries of u = A v (a reduction inside the
-// workgroup), and then multiplies the same registers by those entries to get its share of
-// z = A^T u, which it writes as a partial vector.  A second small kernel adds the partial
-// vectors in a fixed order.  So a rank reads A  it + 1  times instead of  2 it + 2  times,
-// every sum has a fixed order (results are reproducible), and the chain is bound by the rate
-// at which A (float32, rewritten once per rank by the deflation) streams from memory.
+// application can be taken from ONE pass over A.  So a rank reads A  it + 1  times instead of
+// 2 it + 2  times, and every sum has a fixed order (results are reproducible).
 //
-// Arithmetic: A and the vector v of an application are float32, and so are the products and
-// the short sums a thread forms from its own 4 * sweeps columns (for u) or its R rows (for z);
-// everything that is added across threads, workgroups or row blocks is float64, as are the
-// norms and the values that get rounded to e4m3 / fp16.  That keeps the noise at the level the
-// float32 storage of A sets anyway.  Vectors grow by sigma_1^2 per application; v is z times a
-// power of two (exact) taken from the size of z, so the printed formula is evaluated as it stands.
+// The loop exists in five forms, chosen by shape and type (r1svd_launch):
+//   tile      A (float32) in the registers of 256 workgroups, a 256 x 256 tile each, for the whole
+//             loop; partial sums travel as tagged words, no barrier inside an application
+//   resident  a bfloat16 W too large for that: W itself stays on the chip (registers + LDS) in
+//             P x Q tiles and A = W diag(s) - stored rank-one terms is never formed; tagged words
+//   stream    a bfloat16 W too large for the chip: the same implicit products, row blocks of W
+//             streamed from memory in every application, grid barriers
+//   rows      any other type: row blocks of the float32 A, deflated in place, streamed; one launch
+//   steps     the same row blocks as one launch per application and per partial sum, when the
+//             device cannot hold a cooperative launch
+// In the row-block forms a workgroup owns R complete rows, keeps them in registers, finishes its
+// R entries of u = A v (a reduction inside the workgroup) and multiplies the same registers by
+// those entries to get its share of z = A^T u, which it writes as a partial vector.
+//
+// Arithmetic: the matrix and the vector v of an application are float32 (bfloat16 weights are
+// exact in it), and so are the products and the short sums a thread forms from its own columns
+// (for u) or rows (for z); everything that is added across threads, workgroups or row blocks is
+// float64, as are the norms and the values that get rounded to e4m3 / fp16.  That keeps the noise
+// at the level the float32 storage of A sets anyway.  Vectors grow by sigma_1^2 per application;
+// v is z times a power of two (exact) taken from the size of z, so the printed formula is
+// evaluated as it stands.
 #include "common.h"
 
 #include <climits>
