@@ -1042,7 +1042,7 @@ __global__ __launch_bounds__(kChainThreads) void stream_chain_kernel(StreamArgs 
 }
 
 // R = W - (sum_k sigma_k U_k V_k^T) diag(s)^-1 from the stored factors (Algorithm 1; float64
-// arithmetic, one rounding): what the stream form hands to the quantizer.  One workgroup per
+// arithmetic, one rounding): what the resident and stream forms hand to the quantizer.  One workgroup per
 // 4 rows x 1024 columns.
 __global__ __launch_bounds__(256) void stream_residual_kernel(const uint16_t* __restrict__ W, int64_t ldw, int m,
                                                              int n, int r, const uint8_t* __restrict__ U,
@@ -1051,6 +1051,8 @@ __global__ __launch_bounds__(256) void stream_residual_kernel(const uint16_t* __
                                                              const double* __restrict__ s, float* __restrict__ Rout,
                                                              int64_t ldr) {
   __shared__ double su[4][kMaxStreamRank];
+  __shared__ double lut[256];   // decoded e4m3 codes: a table read instead of the arithmetic, 64 times per thread
+  lut[threadIdx.x] = e4m3_decode((uint8_t)threadIdx.x);
   const int nb = (n + 1023) / 1024;
   const int c = ((int)(blockIdx.x % nb) * 256 + threadIdx.x) * 4;
   const int row0 = (int)(blockIdx.x / nb) * 4;
@@ -1065,14 +1067,14 @@ __global__ __launch_bounds__(256) void stream_residual_kernel(const uint16_t* __
     const unsigned codes = *reinterpret_cast<const unsigned*>(V + (int64_t)k * n + c);
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      const double v = e4m3_decode((uint8_t)(codes >> (8 * q)));
+      const double v = lut[(codes >> (8 * q)) & 0xffu];
 #pragma unroll
       for (int i = 0; i < 4; ++i) low[i][q] = fma(su[i][k], v, low[i][q]);
     }
   }
-  double sc4[4];
+  double sc4[4];   // 1 / s: one division per column, not per entry (the result is rounded to float32 anyway)
 #pragma unroll
-  for (int q = 0; q < 4; ++q) sc4[q] = s[c + q];
+  for (int q = 0; q < 4; ++q) sc4[q] = 1.0 / s[c + q];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     if (row0 + i >= m) break;
@@ -1080,7 +1082,7 @@ __global__ __launch_bounds__(256) void stream_residual_kernel(const uint16_t* __
     const double w4[4] = {(double)bf16_lo(wv.x), (double)bf16_hi(wv.x), (double)bf16_lo(wv.y), (double)bf16_hi(wv.y)};
     float o[4];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) o[q] = (float)(w4[q] - low[i][q] / sc4[q]);
+    for (int q = 0; q < 4; ++q) o[q] = (float)(w4[q] - low[i][q] * sc4[q]);
     *reinterpret_cast<float4*>(Rout + (int64_t)(row0 + i) * ldr + c) = make_float4(o[0], o[1], o[2], o[3]);
   }
 }
