@@ -1147,6 +1147,8 @@ __device__ __forceinline__ double unscale(int e) {
 // The power of two that keeps the vectors in range travels with the partial u (the exponent of
 // the largest entry of the tile's columns of v; a row group sees all columns) and is applied
 // to u, A being linear.  7B-sized MLP projections (90 MB) just fit: 352 KB per compute unit.
+// Of a larger weight the rows of a band that fit neither registers nor LDS are re-read from
+// memory, eight at a time, in step A and again in step C.
 constexpr int kResidentRows = 512, kResidentCols = 1024;   // words per workgroup in upart, zpart
 constexpr size_t kShareWords = (size_t)kMaxStreamRank * kComputeUnits * 2;   // one buffer of cpart or dpart
 
@@ -1160,7 +1162,7 @@ struct ResidentArgs {
   unsigned long long* dpart;   // tagged [2][kMaxStreamRank][kComputeUnits][2]: (U_j . u) per row group
   double* unrm2; double* normpart;   // per workgroup
   unsigned* bar; int* abort; unsigned spin_limit;
-  int P, Q, RW;             // row groups, column groups, rows per wave
+  int P, Q, RW, RL;         // row groups, column groups, rows per wave, of which in LDS
 };
 
 // LDS of the resident form by tile shape; `shared` (8 x 512 floats) holds, at different times, the
@@ -1169,9 +1171,9 @@ struct ResidentArgs {
 struct ResidentLds {
   size_t tile, ush, ustage, shared, small, svsh, uf, lut, ucode, vcode, total;
 };
-__host__ __device__ inline ResidentLds resident_lds(int nsw, int rr, int rw) {
-  const int tc = nsw * 512, tr = 8 * rw, rl = rw > rr ? rw - rr : 0;
-  const int chunks = rr / 8 + (rl + 7) / 8;
+__host__ __device__ inline ResidentLds resident_lds(int nsw, int rr, int rw, int rl) {
+  const int tc = nsw * 512, tr = 8 * rw;
+  const int chunks = rr / 8 + (rw > rr ? (rw - rr + 7) / 8 : 0);
   ResidentLds L{};
   size_t off = 0;
   auto take = [&](size_t bytes) { const size_t at = off; off += (bytes + 15) & ~size_t{15}; return at; };
@@ -1313,8 +1315,9 @@ __global__ __launch_bounds__(kChainThreads) void resident_chain_kernel(ResidentA
   extern __shared__ __align__(16) unsigned char lds_raw[];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, b = blockIdx.x, G = gridDim.x;
   const int p = b / a.Q, q = b % a.Q, P = a.P, Q = a.Q;
-  const int m = a.m, n = a.n, RW = a.RW, TR = 8 * RW, RL = RW > RR ? RW - RR : 0;
-  const ResidentLds L = resident_lds(NSW, RR, RW);
+  const int m = a.m, n = a.n, RW = a.RW, TR = 8 * RW, RL = a.RL;
+  const int RG = RW - RR - RL > 0 ? RW - RR - RL : 0;   // rows of a band that fit neither: read from memory in A and in C
+  const ResidentLds L = resident_lds(NSW, RR, RW, RL);
   uint4* tile = reinterpret_cast<uint4*>(lds_raw + L.tile);
   double* ush = reinterpret_cast<double*>(lds_raw + L.ush);
   double* ustage = reinterpret_cast<double*>(lds_raw + L.ustage);
@@ -1349,6 +1352,20 @@ __global__ __launch_bounds__(kChainThreads) void resident_chain_kernel(ResidentA
       if (row < m && col < n) x = *reinterpret_cast<const uint4*>(a.W + (int64_t)row * a.ldw + col);
       tile[(size_t)(w * RL + rl) * (TC / 8) + s * 64 + lane] = x;
     }
+  // kStreamRows rows of the wave's band from memory, from row r0 on; all loads are issued before the
+  // first is used (rows past the band or the matrix are fetched from a valid row and zeroed)
+  constexpr int kStreamRows = 8 / NSW;
+  auto streamed_rows = [&](uint4 (&g4)[kStreamRows][NSW], int r0) {
+#pragma unroll
+    for (int x = 0; x < kStreamRows; ++x)
+#pragma unroll
+      for (int s = 0; s < NSW; ++s) {
+        const int row = p * TR + w * RW + r0 + x, col = q * TC + s * 512 + lane * 8;
+        const bool live = r0 + x < RW && row < m && col < n;
+        const uint4 v = *reinterpret_cast<const uint4*>(a.W + (int64_t)(row < m ? row : m - 1) * a.ldw + (col < n ? col : 0));
+        g4[x][s] = live ? v : make_uint4(0u, 0u, 0u, 0u);
+      }
+  };
   if (tid < 256) lut[tid] = (float)e4m3_decode((uint8_t)tid);
   for (int x = tid; x < TR + RR; x += T) uf[x] = 0.f;
   float sfc[NSW];
@@ -1404,7 +1421,7 @@ __global__ __launch_bounds__(kChainThreads) void resident_chain_kernel(ResidentA
             if ((lane & 7) == 0) ustage[c8 * 64 + w * 8 + (lane >> 3)] = t;
           }
         }
-        for (int c8 = RR / 8; c8 * 8 < RW; ++c8) {
+        for (int c8 = RR / 8; c8 * 8 < RR + RL; ++c8) {
           float us[8];
 #pragma unroll
           for (int x = 0; x < 8; ++x) {
@@ -1419,6 +1436,29 @@ __global__ __launch_bounds__(kChainThreads) void resident_chain_kernel(ResidentA
                 for (int c = 0; c < 4; ++c)
                   us[x] = fmaf(bf16_hi(wd[c]), sv[s][2 * c + 1], fmaf(bf16_lo(wd[c]), sv[s][2 * c], us[x]));
               }
+            }
+          }
+          const double t = wave_row_sums_staged(us, stage);
+          if ((lane & 7) == 0) ustage[c8 * 64 + w * 8 + (lane >> 3)] = t;
+        }
+        // rows beyond registers and LDS (RR + RL is then a multiple of 8): eight at a time from memory
+        for (int c8 = (RR + RL) / 8; c8 * 8 < RW && RG > 0; ++c8) {
+          float us[8];
+#pragma unroll
+          for (int x0 = 0; x0 < 8; x0 += kStreamRows) {
+            uint4 g4[kStreamRows][NSW];
+            streamed_rows(g4, c8 * 8 + x0);
+#pragma unroll
+            for (int x = 0; x < kStreamRows; ++x) {
+              float t = 0.f;
+#pragma unroll
+              for (int s = 0; s < NSW; ++s) {
+                const unsigned wd[4] = {g4[x][s].x, g4[x][s].y, g4[x][s].z, g4[x][s].w};
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                  t = fmaf(bf16_hi(wd[c]), sv[s][2 * c + 1], fmaf(bf16_lo(wd[c]), sv[s][2 * c], t));
+              }
+              us[x0 + x] = t;
             }
           }
           const double t = wave_row_sums_staged(us, stage);
@@ -1520,6 +1560,23 @@ __global__ __launch_bounds__(kChainThreads) void resident_chain_kernel(ResidentA
             for (int c = 0; c < 4; ++c) {
               zt[s][2 * c] = fmaf(bf16_lo(wd[c]), ufv, zt[s][2 * c]);
               zt[s][2 * c + 1] = fmaf(bf16_hi(wd[c]), ufv, zt[s][2 * c + 1]);
+            }
+          }
+        }
+        for (int r0 = RR + RL; r0 < RW; r0 += kStreamRows) {
+          uint4 g4[kStreamRows][NSW];
+          streamed_rows(g4, r0);
+#pragma unroll
+          for (int x = 0; x < kStreamRows; ++x) {
+            const float ufv = r0 + x < RW ? uf[w * RW + r0 + x] : 0.f;
+#pragma unroll
+            for (int s = 0; s < NSW; ++s) {
+              const unsigned wd[4] = {g4[x][s].x, g4[x][s].y, g4[x][s].z, g4[x][s].w};
+#pragma unroll
+              for (int c = 0; c < 4; ++c) {
+                zt[s][2 * c] = fmaf(bf16_lo(wd[c]), ufv, zt[s][2 * c]);
+                zt[s][2 * c + 1] = fmaf(bf16_hi(wd[c]), ufv, zt[s][2 * c + 1]);
+              }
             }
           }
         }
@@ -2074,9 +2131,10 @@ bool launch_stream(StreamArgs& a, hipStream_t st) {
 
 // Tile shape of the resident form: column sweeps per tile (512 columns each), rows per wave, groups.
 constexpr size_t kResidentMaxLds = 160 * 1024;
-struct ResidentPlan { int nsw, rr, rw, P, Q; size_t lds; bool ok; };
+struct ResidentPlan { int nsw, rr, rw, rl, P, Q; size_t lds; bool ok; };
 inline ResidentPlan resident_plan(int64_t m, int64_t n) {
   ResidentPlan best{};
+  int64_t best_cost = 0;
   for (int nsw = 1; nsw <= 2; ++nsw) {
     const int rr = 32 / nsw;
     const int64_t Q = ceil_div(n, (int64_t)512 * nsw);
@@ -2085,9 +2143,21 @@ inline ResidentPlan resident_plan(int64_t m, int64_t n) {
     const int64_t rw = ceil_div(m, 8 * P);
     P = ceil_div(m, 8 * rw);
     if (8 * rw >= kResidentRows) continue;   // a row per thread, and the word after the rows
-    const size_t lds = resident_lds(nsw, rr, (int)rw).total;
-    if (lds > kResidentMaxLds) continue;
-    if (!best.ok || rw * nsw < (int64_t)best.rw * best.nsw) best = {nsw, rr, (int)rw, (int)P, (int)Q, lds, true};
+    // rows of a band: rr in registers, as many of the others as LDS holds, the rest re-read from
+    // memory twice per application (in whole groups of 8, so LDS rows are then a multiple of 8)
+    const size_t fixed = resident_lds(nsw, rr, (int)rw, 0).total;
+    if (fixed > kResidentMaxLds) continue;
+    const int64_t row_bytes = (int64_t)8 * 512 * nsw * 2;
+    int64_t rl = rw > rr ? rw - rr : 0;
+    const int64_t room = (int64_t)(kResidentMaxLds - fixed) / row_bytes;
+    if (rl > room) rl = room / 8 * 8;
+    const int64_t rg = rw - rr - rl > 0 ? rw - rr - rl : 0;
+    if (rg * 4 > rw * 3) continue;           // mostly streamed: the stream form is the better fit
+    const int64_t cost = (rw + 2 * rg) * nsw;   // a streamed row costs about three resident ones
+    if (!best.ok || cost < best_cost) {
+      best = {nsw, rr, (int)rw, (int)rl, (int)P, (int)Q, resident_lds(nsw, rr, (int)rw, (int)rl).total, true};
+      best_cost = cost;
+    }
   }
   return best;
 }
@@ -2217,7 +2287,7 @@ ptq_status r1svd_launch(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m, in
                       reinterpret_cast<unsigned long long*>(rw + kResidentUpartBytes),
                       reinterpret_cast<unsigned long long*>(rw + kResidentUpartBytes + kResidentZpartBytes),
                       reinterpret_cast<unsigned long long*>(rw + kResidentUpartBytes + kResidentZpartBytes + kResidentShareBytes),
-                      unrm2, normpart, bar, abort_flag, spin_limit, plan.P, plan.Q, plan.rw};
+                      unrm2, normpart, bar, abort_flag, spin_limit, plan.P, plan.Q, plan.rw, plan.rl};
       launched = plan.nsw == 1 ? launch_resident<1, 32>(ra, plan, st) : launch_resident<2, 16>(ra, plan, st);
     }
     if (!launched) {

@@ -248,6 +248,21 @@ def test_r1svd_full_size_mlp_projection(capsys):
               f"followed {ref['followed']} near-ties, sigma {ref['sigma'][:3]}...]", flush=True)
 
 
+def test_r1svd_resident_form_with_rows_left_in_memory(capsys):
+    """An 8B-sized MLP up projection (14336 x 4096, 117 MB as bfloat16) is more than registers and LDS
+    hold: 16 of a wave's 56 rows are re-read from memory in both products of every application."""
+    spec = wl.LayerSpec("up_proj", 14336, 4096, 2048, x_sigma=1.0, layer_id=17)
+    r, it = 4, 2
+    Ws = wl.gen_weight_with_low_rank_part(spec, rank=3)
+    W64 = wl.to_f64(Ws)
+    S = wl.gen_sketch_vectors(spec, r)
+    s = ro.activation_scale(wl.channel_scales(spec) * np.sqrt(2.0 / np.pi))
+    got = _run_gpu(to_device(Ws), s, S, it)
+    ref = _check(W64, s, S, it, got)
+    with capsys.disabled():
+        print(f"  [r1svd 14336x4096 r=4 it=2: followed {ref['followed']} near-ties, sigma {ref['sigma']}]", flush=True)
+
+
 def test_r1svd_sigma_beyond_fp16_range(launch_mode):
     rng = np.random.default_rng(31)
     m, n = 64, 256
