@@ -104,6 +104,8 @@ def test_r1svd_matches_oracle(dtype, m, n, r, it, launch_mode):
     (9, 12296, 3, 2),      # four sweeps
     (1031, 64, 4, 4),      # a prime number of rows over 256 workgroups, 4 column blocks
     (12000, 520, 3, 2),    # resident: two column groups, 128 row groups, rows of a band in registers and LDS
+    (40, 72, 1, 0),        # one rank, no power iteration
+    (520, 1032, 2, 0),     # two ranks without power iteration: the correction enters at once
 ])
 @pytest.mark.parametrize("form", ["resident", "stream"])
 def test_r1svd_bfloat16_forms_shapes(m, n, r, it, form, monkeypatch):
