@@ -127,19 +127,16 @@ __device__ __forceinline__ float fp16_bits_to_float(uint16_t h) {
   return (h & 0x8000) ? -mag : mag;
 }
 
-__global__ __launch_bounds__(256) void narrow_kernel(const double* __restrict__ in, int64_t count,
-                                                     float* __restrict__ out) {
-  const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (e < count) out[e] = (float)in[e];
-}
-
-// one workgroup per (token, rank)
+// one workgroup per (token, rank); the first also clears the counters of the product that follows
 template <int DT>
 __global__ __launch_bounds__(256) void low_rank_coeff_kernel(const void* __restrict__ X, int64_t ldx, int n,
                                                              const uint8_t* __restrict__ V,
                                                              const uint16_t* __restrict__ sigma,
                                                              const double* __restrict__ s, int r,
-                                                             float* __restrict__ y) {
+                                                             float* __restrict__ y, unsigned* __restrict__ done,
+                                                             int counters) {
+  if (blockIdx.x == 0)
+    for (int i = threadIdx.x; i < counters; i += 256) done[i] = 0u;
   const int t = blockIdx.x / r, k = blockIdx.x - t * r;
   double acc = 0.0;
   for (int j = threadIdx.x; j < n; j += 256)
@@ -164,6 +161,7 @@ struct ForwardArgs {
   const uint8_t* U;         // r x m, e4m3
   int r;
   float* partial;           // splits x B x m
+  unsigned* done;           // one counter per block of 256 rows: zero on entry, left at zero
   float* O;                 // tokens x m
   int64_t ldo;
 };
@@ -234,39 +232,54 @@ __global__ __launch_bounds__(256) void forward_partial_kernel(ForwardArgs a) {
 #pragma unroll
     for (int t = 0; t < B; ++t) acc[t] = fmaf(sc, fmaf(-z, xsum[t][k], raw[t]), acc[t]);
   }
+  // The partial sums go out device-coherently; the workgroup that counts itself last for its
+  // block of rows adds the column runs in order, adds the low-rank part and writes the output:
+  //   O[t][row] = sum over the column runs + sum_k U[k][row] y[t][k]
   if (live) {
 #pragma unroll
-    for (int t = 0; t < B; ++t) a.partial[((int64_t)blockIdx.y * B + t) * m + row] = acc[t];
+    for (int t = 0; t < B; ++t)
+      __hip_atomic_store(a.partial + ((int64_t)blockIdx.y * B + t) * m + row, acc[t], __ATOMIC_RELAXED,
+                         __HIP_MEMORY_SCOPE_AGENT);
   }
-}
-
-// O[t][row] = sum over the column runs, in order, + sum_k U[k][row] y[t][k]
-template <int B>
-__global__ __launch_bounds__(64) void forward_finish_kernel(ForwardArgs a, int splits) {
-  const int row = blockIdx.x * 64 + threadIdx.x;
-  if (row >= a.m) return;
-  float acc[B];
+  __shared__ int last;
+  __builtin_amdgcn_s_waitcnt(0);   // every wave's stores acknowledged before the workgroup is counted
+  __syncthreads();
+  const int splits = gridDim.y;
+  if (tid == 0) last = atomicAdd(a.done + blockIdx.x, 1u) + 1u == (unsigned)splits;
+  __syncthreads();
+  if (!last) return;
+  if (tid == 0) __hip_atomic_store(a.done + blockIdx.x, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (!live) return;
+  float out[B];
 #pragma unroll
-  for (int t = 0; t < B; ++t) acc[t] = 0.f;
+  for (int t = 0; t < B; ++t) out[t] = 0.f;
   for (int sp0 = 0; sp0 < splits; sp0 += 8) {   // eight loads in flight per token, added in order
     float v[8][B];
 #pragma unroll
     for (int k = 0; k < 8; ++k)
 #pragma unroll
-      for (int t = 0; t < B; ++t)
-        v[k][t] = sp0 + k < splits ? a.partial[((int64_t)(sp0 + k) * B + t) * a.m + row] : 0.f;
+      for (int t = 0; t < B; ++t) {
+        const int sp = sp0 + k < splits ? sp0 + k : splits - 1;   // issued whatever sp: no branch, no wait
+        v[k][t] = __hip_atomic_load(a.partial + ((int64_t)sp * B + t) * m + row, __ATOMIC_RELAXED,
+                                    __HIP_MEMORY_SCOPE_AGENT);
+      }
 #pragma unroll
     for (int k = 0; k < 8; ++k)
 #pragma unroll
-      for (int t = 0; t < B; ++t) acc[t] += v[k][t];
+      for (int t = 0; t < B; ++t) out[t] += sp0 + k < splits ? v[k][t] : 0.f;
   }
   for (int k = 0; k < a.r; ++k) {
-    const float u = e4m3_to_float(a.U[(int64_t)k * a.m + row]);
+    const float u = e4m3_to_float(a.U[(int64_t)k * m + row]);
 #pragma unroll
-    for (int t = 0; t < B; ++t) acc[t] = fmaf(u, a.y[(int64_t)t * a.r + k], acc[t]);
+    for (int t = 0; t < B; ++t) out[t] = fmaf(u, a.y[(int64_t)t * a.r + k], out[t]);
   }
 #pragma unroll
-  for (int t = 0; t < B; ++t) a.O[(int64_t)t * a.ldo + row] = acc[t];
+  for (int t = 0; t < B; ++t) a.O[(int64_t)t * a.ldo + row] = out[t];
+}
+
+__global__ void clear_counters_kernel(unsigned* done, int count) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < count) done[i] = 0u;
 }
 
 template <int BITS, int B>
@@ -274,7 +287,6 @@ void launch_forward_b(const ForwardArgs& a, hipStream_t st) {
   const int splits = (int)ceil_div(a.n / kChunk, kFwdRun);
   dim3 g((unsigned)ceil_div(a.m, 256), (unsigned)splits);
   forward_partial_kernel<BITS, B><<<g, 256, 0, st>>>(a);
-  forward_finish_kernel<B><<<(unsigned)ceil_div(a.m, 64), 64, 0, st>>>(a, splits);
 }
 
 // four, two or one token per pass over the codes
@@ -337,9 +349,12 @@ static size_t forward_partial_bytes(int64_t m, int64_t n) {
   return align_up((size_t)ceil_div(n / kChunk, kFwdRun) * 4 * (size_t)m * sizeof(float), 256);
 }
 
+static size_t forward_counter_bytes(int64_t m) { return align_up((size_t)ceil_div(m, 256) * sizeof(unsigned), 256); }
+
 size_t linear_forward_workspace_bytes(int64_t tokens, int64_t m, int64_t n, int64_t r) {
-  return align_up((size_t)tokens * n * sizeof(double), 256) + align_up((size_t)tokens * n * sizeof(float), 256) +
-         align_up((size_t)tokens * (r > 0 ? r : 1) * sizeof(float), 256) + forward_partial_bytes(m, n);
+  return align_up((size_t)tokens * n * sizeof(float), 256) +
+         align_up((size_t)tokens * (r > 0 ? r : 1) * sizeof(float), 256) + forward_partial_bytes(m, n) +
+         forward_counter_bytes(m);
 }
 
 ptq_status linear_forward_launch(const void* X, ptq_dtype xdt, int64_t ldx, int64_t tokens, int64_t m, int64_t n,
@@ -348,25 +363,27 @@ ptq_status linear_forward_launch(const void* X, ptq_dtype xdt, int64_t ldx, int6
                                  const uint8_t* V, const uint16_t* sigma, int r, const double* s, float* O,
                                  int64_t ldo, void* ws, hipStream_t st) {
   char* base = static_cast<char*>(ws);
-  double* xt64 = reinterpret_cast<double*>(base);
-  float* xt = reinterpret_cast<float*>(base + align_up((size_t)tokens * n * sizeof(double), 256));
+  float* xt = reinterpret_cast<float*>(base);
   float* y = reinterpret_cast<float*>(reinterpret_cast<char*>(xt) + align_up((size_t)tokens * n * sizeof(float), 256));
   float* partial = reinterpret_cast<float*>(reinterpret_cast<char*>(y) +
                                             align_up((size_t)tokens * (r > 0 ? r : 1) * sizeof(float), 256));
+  unsigned* done = reinterpret_cast<unsigned*>(reinterpret_cast<char*>(partial) + forward_partial_bytes(m, n));
   // X~ = X P Q: the rows of X go through the same transform as the rows of the residual
-  ptq_status rc = lopro_rotate_weight_launch(X, xdt, ldx, tokens, n, perm, b_I, b_H, xt64, n, st);
+  ptq_status rc = lopro_rotate_input_launch(X, xdt, ldx, tokens, n, perm, b_I, b_H, xt, n, st);
   if (rc != PTQ_OK) return rc;
-  narrow_kernel<<<(unsigned)ceil_div(tokens * n, 256), 256, 0, st>>>(xt64, tokens * n, xt);
+  const int counters = (int)ceil_div(m, 256);
   if (r > 0) {
     const unsigned g = (unsigned)(tokens * r);
     switch (xdt) {
-      case PTQ_F32: low_rank_coeff_kernel<PTQ_F32><<<g, 256, 0, st>>>(X, ldx, (int)n, V, sigma, s, r, y); break;
-      case PTQ_BF16: low_rank_coeff_kernel<PTQ_BF16><<<g, 256, 0, st>>>(X, ldx, (int)n, V, sigma, s, r, y); break;
-      case PTQ_F64: low_rank_coeff_kernel<PTQ_F64><<<g, 256, 0, st>>>(X, ldx, (int)n, V, sigma, s, r, y); break;
+      case PTQ_F32: low_rank_coeff_kernel<PTQ_F32><<<g, 256, 0, st>>>(X, ldx, (int)n, V, sigma, s, r, y, done, counters); break;
+      case PTQ_BF16: low_rank_coeff_kernel<PTQ_BF16><<<g, 256, 0, st>>>(X, ldx, (int)n, V, sigma, s, r, y, done, counters); break;
+      case PTQ_F64: low_rank_coeff_kernel<PTQ_F64><<<g, 256, 0, st>>>(X, ldx, (int)n, V, sigma, s, r, y, done, counters); break;
       default: return PTQ_ERR_DTYPE;
     }
+  } else {
+    clear_counters_kernel<<<(unsigned)ceil_div(counters, 256), 256, 0, st>>>(done, counters);
   }
-  ForwardArgs a{packed, scales, zeros, (int)m, (int)n, group, xt, y, U, r, partial, O, ldo};
+  ForwardArgs a{packed, scales, zeros, (int)m, (int)n, group, xt, y, U, r, partial, done, O, ldo};
   switch (bits) {
     case 2: launch_forward<2>(a, (int)tokens, st); break;
     case 3: launch_forward<3>(a, (int)tokens, st); break;

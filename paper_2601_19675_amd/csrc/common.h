@@ -99,6 +99,10 @@ ptq_status lopro_order_launch(const void* R, ptq_dtype rdt, int64_t ldr, int64_t
 ptq_status lopro_rotate_weight_launch(const void* R, ptq_dtype rdt, int64_t ldr, int64_t m, int64_t n,
                                       const int32_t* perm, int b_I, int b_H, double* Rout, int64_t ldo,
                                       hipStream_t s);
+// the same transform on the rows of X, written as float32: the input of the stored layer's product
+ptq_status lopro_rotate_input_launch(const void* X, ptq_dtype xdt, int64_t ldx, int64_t tokens, int64_t n,
+                                     const int32_t* perm, int b_I, int b_H, float* Xout, int64_t ldo,
+                                     hipStream_t st);
 ptq_status lopro_unrotate_weight_launch(const double* Rq, int64_t ldq, int64_t m, int64_t n,
                                         const int32_t* perm, int b_I, int b_H, double* Wout, int64_t ldo,
                                         hipStream_t s);

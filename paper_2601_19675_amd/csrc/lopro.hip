@@ -101,11 +101,13 @@ __global__ __launch_bounds__(256) void rank_kernel(const double* __restrict__ ke
 // One workgroup per row; the row is staged in LDS in its storage type (MODE 0) resp. as float64
 // (MODE 1).  row_perm (MODE 0 only, may be null) picks the source row.
 // (256 threads, or 1024 when the staged row is so large that only one workgroup fits a CU.)
-template <int DT, int MODE>
+// OT: float64, or (MODE 0 only) float32 for activations on their way into the stored layer.
+template <int DT, int MODE, typename OT>
 __global__ __launch_bounds__(1024) void row_rotate_kernel(const void* __restrict__ in, int64_t ldi, int n,
                                                          const int32_t* __restrict__ perm,
                                                          const int32_t* __restrict__ row_perm, int b_I, int b_H,
-                                                         double* __restrict__ out, int64_t ldo) {
+                                                         OT* __restrict__ out, int64_t ldo) {
+  static_assert(MODE == 0 || sizeof(OT) == sizeof(double), "the scatter form writes float64");
   extern __shared__ __attribute__((aligned(16))) char rowbuf[];
   using ST = typename StoredType<DT>::type;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -139,9 +141,13 @@ __global__ __launch_bounds__(1024) void row_rotate_kernel(const void* __restrict
         for (int i = 0; i < 4; ++i) v[i] *= scale;
       }
       if (c < ce) {
-        double* o = out + (int64_t)row * ldo + c;
-        *reinterpret_cast<double2*>(o) = double2{v[0], v[1]};
-        *reinterpret_cast<double2*>(o + 2) = double2{v[2], v[3]};
+        OT* o = out + (int64_t)row * ldo + c;
+        if constexpr (sizeof(OT) == sizeof(double)) {
+          *reinterpret_cast<double2*>(o) = double2{v[0], v[1]};
+          *reinterpret_cast<double2*>(o + 2) = double2{v[2], v[3]};
+        } else {
+          *reinterpret_cast<float4*>(o) = make_float4((float)v[0], (float)v[1], (float)v[2], (float)v[3]);
+        }
       }
     }
   } else {
@@ -175,7 +181,7 @@ __global__ __launch_bounds__(1024) void row_rotate_kernel(const void* __restrict
       }
     }
     __syncthreads();
-    for (int c = tid; c < n; c += nthr) out[(int64_t)row * ldo + c] = buf[c];
+    for (int c = tid; c < n; c += nthr) out[(int64_t)row * ldo + c] = (OT)buf[c];
   }
 }
 
@@ -260,16 +266,16 @@ __global__ __launch_bounds__(512) void col_rotate_kernel(double* __restrict__ A,
 
 size_t stored_size(ptq_dtype dt) { return dt == PTQ_BF16 ? 2 : (dt == PTQ_F32 ? 4 : 8); }
 
-template <int MODE>
+template <int MODE, typename OT>
 ptq_status launch_row_rotate(const void* in, ptq_dtype dt, int64_t ldi, int64_t rows, int64_t n,
-                             const int32_t* perm, const int32_t* row_perm, int b_I, int b_H, double* out,
+                             const int32_t* perm, const int32_t* row_perm, int b_I, int b_H, OT* out,
                              int64_t ldo, hipStream_t st) {
   const size_t lds = (size_t)n * (MODE == 0 ? stored_size(dt) : sizeof(double));
   if (lds > 160 * 1024) return PTQ_ERR_SHAPE;
 #define PTQ_ROW_CASE(DT)                                                                                   \
   {                                                                                                        \
-    if (!lds_opt_in<row_rotate_kernel<DT, MODE>>(160 * 1024)) return PTQ_ERR_HIP;                          \
-    row_rotate_kernel<DT, MODE><<<(unsigned)rows, lds > 40 * 1024 ? 1024 : 256, lds, st>>>(                \
+    if (!lds_opt_in<row_rotate_kernel<DT, MODE, OT>>(160 * 1024)) return PTQ_ERR_HIP;                          \
+    row_rotate_kernel<DT, MODE, OT><<<(unsigned)rows, lds > 40 * 1024 ? 1024 : 256, lds, st>>>(                \
         in, ldi, (int)n, perm, row_perm, b_I, b_H, out, ldo);                                              \
   }
   switch (dt) {
@@ -314,13 +320,19 @@ ptq_status lopro_order_launch(const void* R, ptq_dtype rdt, int64_t ldr, int64_t
 ptq_status lopro_rotate_weight_launch(const void* R, ptq_dtype rdt, int64_t ldr, int64_t m, int64_t n,
                                       const int32_t* perm, int b_I, int b_H, double* Rout, int64_t ldo,
                                       hipStream_t st) {
-  return launch_row_rotate<0>(R, rdt, ldr, m, n, perm, nullptr, b_I, b_H, Rout, ldo, st);
+  return launch_row_rotate<0, double>(R, rdt, ldr, m, n, perm, nullptr, b_I, b_H, Rout, ldo, st);
+}
+
+ptq_status lopro_rotate_input_launch(const void* X, ptq_dtype xdt, int64_t ldx, int64_t tokens, int64_t n,
+                                     const int32_t* perm, int b_I, int b_H, float* Xout, int64_t ldo,
+                                     hipStream_t st) {
+  return launch_row_rotate<0, float>(X, xdt, ldx, tokens, n, perm, nullptr, b_I, b_H, Xout, ldo, st);
 }
 
 ptq_status lopro_unrotate_weight_launch(const double* Rq, int64_t ldq, int64_t m, int64_t n,
                                         const int32_t* perm, int b_I, int b_H, double* Wout, int64_t ldo,
                                         hipStream_t st) {
-  return launch_row_rotate<1>(Rq, PTQ_F64, ldq, m, n, perm, nullptr, b_I, b_H, Wout, ldo, st);
+  return launch_row_rotate<1, double>(Rq, PTQ_F64, ldq, m, n, perm, nullptr, b_I, b_H, Wout, ldo, st);
 }
 
 ptq_status lopro_rotate_hessian_launch(const double* H, int64_t ldh, int64_t n, const int32_t* perm, int b_I,
@@ -329,7 +341,7 @@ ptq_status lopro_rotate_hessian_launch(const double* H, int64_t ldh, int64_t n, 
   dim3 gs((unsigned)ceil_div(n, 32), (unsigned)ceil_div(n, 32));
   symmetrize_kernel<<<gs, 256, 0, st>>>(H, ldh, (int)n, Hs);
   // rows: Hout[r, :] = (row perm[r] of H, columns gathered by perm) rotated
-  ptq_status rc = launch_row_rotate<0>(Hs, PTQ_F64, n, n, n, perm, perm, b_I, b_H, Hout, ldo, st);
+  ptq_status rc = launch_row_rotate<0, double>(Hs, PTQ_F64, n, n, n, perm, perm, b_I, b_H, Hout, ldo, st);
   if (rc != PTQ_OK) return rc;
   // columns: H' = Q^T (that)
   if (n > b_I) {
