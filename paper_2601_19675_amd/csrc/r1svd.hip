@@ -259,6 +259,67 @@ __device__ __forceinline__ void wave_row_sums(const float (&us)[R], double* red)
   }
 }
 
+// Lane exchanges inside a row of 16 lanes by data-parallel primitives (no LDS traffic): after the
+// four steps every lane of a row holds the sum over the row, added in a fixed order.
+template <int CTRL>
+__device__ __forceinline__ double dpp_move(double v) {
+  const unsigned long long bits = __double_as_longlong(v);
+  const int lo = __builtin_amdgcn_update_dpp(0, (int)(unsigned)bits, CTRL, 0xf, 0xf, false);
+  const int hi = __builtin_amdgcn_update_dpp(0, (int)(unsigned)(bits >> 32), CTRL, 0xf, 0xf, false);
+  return __longlong_as_double((long long)(((unsigned long long)(unsigned)hi << 32) | (unsigned)lo));
+}
+constexpr int kDppSwapPairs = 0xB1;      // quad_perm [1, 0, 3, 2]
+constexpr int kDppSwapHalfQuads = 0x4E;  // quad_perm [2, 3, 0, 1]
+constexpr int kDppHalfMirror = 0x141;    // lane i of 8 <- lane 7 - i
+constexpr int kDppMirror = 0x140;        // lane i of 16 <- lane 15 - i
+__device__ __forceinline__ double sum8(double t) {
+  t += dpp_move<kDppSwapPairs>(t);
+  t += dpp_move<kDppSwapHalfQuads>(t);
+  t += dpp_move<kDppHalfMirror>(t);
+  return t;
+}
+__device__ __forceinline__ double sum32(double t) {
+  t = sum8(t);
+  t += dpp_move<kDppMirror>(t);
+  t += __shfl_xor(t, 16);
+  return t;
+}
+
+// Sums over the 64 lanes of a wave of 8 per-lane values, in float64: the values go through
+// `stage` (8 x 64 floats of this wave's own), 8 lanes add up a row (each 8 values, then among
+// themselves).  Every lane returns the sum of row lane / 8.
+__device__ __forceinline__ double wave_row_sums_staged(const float (&us)[8], float* stage) {
+  const int lane = threadIdx.x & 63;
+  __builtin_amdgcn_wave_barrier();   // the reads of the previous call precede these writes
+#pragma unroll
+  for (int x = 0; x < 8; ++x) stage[x * 64 + lane] = us[x];
+  __builtin_amdgcn_wave_barrier();   // a wave's LDS accesses complete in order
+  const float4 v0 = *reinterpret_cast<const float4*>(stage + (lane >> 3) * 64 + (lane & 7) * 8);
+  const float4 v1 = *reinterpret_cast<const float4*>(stage + (lane >> 3) * 64 + (lane & 7) * 8 + 4);
+  const double t = (((double)v0.x + (double)v0.y) + ((double)v0.z + (double)v0.w)) +
+                   (((double)v1.x + (double)v1.y) + ((double)v1.z + (double)v1.w));
+  return sum8(t);
+}
+
+// R per-lane values summed over the wave into red[wave * R + row]: through the staging area in
+// chunks of 8 rows (4 rows are padded to 8), fewer rows by the exchange above.
+template <int R>
+__device__ __forceinline__ void wave_row_sums_into(const float (&us)[R], double* red, float* stage) {
+  if constexpr (R % 8 == 0 || R == 4) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int h = 0; h < (R + 7) / 8; ++h) {
+      float part[8];
+#pragma unroll
+      for (int x = 0; x < 8; ++x) part[x] = h * 8 + x < R ? us[h * 8 + x] : 0.f;
+      const double t = wave_row_sums_staged(part, stage);
+      if ((lane & 7) == 0 && h * 8 + (lane >> 3) < R) red[wave * R + h * 8 + (lane >> 3)] = t;
+    }
+  } else {
+    wave_row_sums<R>(us, red);
+  }
+}
+
 // A block of R rows of A in the registers of a workgroup of T threads: a thread owns 4 adjacent
 // columns in each of NS sweeps of 4 T columns.
 // COH: the vectors come from other workgroups of the same launch (see load_dev).
@@ -306,9 +367,9 @@ struct RowBlock {
   // u = (block) v for the R rows, left in ush[0..R) (and in u_out, if not null); then
   // zacc += (block)^T u.  v is vin times the power of two rs.
   // Returns the sum of squares of the R entries of u (valid in thread 0).
-  // red: T/64 x R doubles, ush: R doubles of LDS.  Contains two workgroup barriers.
+  // red: T/64 x R doubles, ush: R doubles, stage: T/64 x 512 floats of LDS.  Contains two workgroup barriers.
   __device__ __forceinline__ double apply(const float* vin, float rs, int m, int n, int row0, double* u_out,
-                                          double (&zacc)[NS][4], double* red, double* ush) {
+                                          double (&zacc)[NS][4], double* red, double* ush, float* stage) {
     constexpr int kWaves = T / kWave;
     const int tid = threadIdx.x;
     float us[R];
@@ -324,7 +385,7 @@ struct RowBlock {
       for (int i = 0; i < R; ++i)
         us[i] = fmaf(w[s][i][3], v.w, fmaf(w[s][i][2], v.z, fmaf(w[s][i][1], v.y, fmaf(w[s][i][0], v.x, us[i]))));
     }
-    wave_row_sums<R>(us, red);
+    wave_row_sums_into<R>(us, red, stage + (tid >> 6) * 512);
     __syncthreads();
     if (tid < R) {
       double t = 0.0;
@@ -377,6 +438,7 @@ template <int T, int NS, int R, bool DEFLATE>
 __global__ __launch_bounds__(T) void pass_kernel(PassArgs a) {
   __shared__ double red[T / kWave * R];
   __shared__ double ush[R];
+  __shared__ float stage[T / kWave * 512];
   double zacc[NS][4];
 #pragma unroll
   for (int s = 0; s < NS; ++s)
@@ -396,7 +458,7 @@ __global__ __launch_bounds__(T) void pass_kernel(PassArgs a) {
     asm volatile("" : "+s"(vin), "+s"(vd));
     RowBlock<T, NS, R> blk;
     blk.load(a.A, a.m, a.n, tile * R, DEFLATE, DEFLATE ? *a.sigma : 0.0, a.ud, vd);
-    unrm2 += blk.apply(vin, rs, a.m, a.n, tile * R, a.u, zacc, red, ush);
+    unrm2 += blk.apply(vin, rs, a.m, a.n, tile * R, a.u, zacc, red, ush, stage);
   }
   if (threadIdx.x == 0) a.unrm2[blockIdx.x] = unrm2;
   store_partial<T, NS>(zacc, a.zpart, a.n, blockIdx.x, gridDim.x);
@@ -597,6 +659,7 @@ __global__ __launch_bounds__(kChainThreads) void chain_kernel(ChainArgs a) {
   __shared__ double red[T / kWave * R];
   __shared__ double ush[R];
   __shared__ double sred[kGroups][kReduceCols];
+  __shared__ float stage[T / kWave * 512];
   __shared__ double fin[T / kWave];
   const int tid = threadIdx.x, b = blockIdx.x, G = gridDim.x;
   const int m = a.m, n = a.n;
@@ -631,7 +694,7 @@ __global__ __launch_bounds__(kChainThreads) void chain_kernel(ChainArgs a) {
         asm volatile("" : "+s"(vin), "+s"(vd));
         RowBlock<T, NS, R, true> blk;
         blk.load(a.A, m, n, tile * R, i == 0 && k > 0, sg_prev, a.ud, vd);
-        unrm2 += blk.apply(vin, rs, m, n, tile * R, a.u, zacc, red, ush);
+        unrm2 += blk.apply(vin, rs, m, n, tile * R, a.u, zacc, red, ush, stage);
       }
       store_partial<T, NS, true>(zacc, a.zpart, n, b, G);
       if (tid == 0) store_dev(a.unrm2 + b, unrm2);
@@ -846,6 +909,7 @@ __global__ __launch_bounds__(kChainThreads) void stream_chain_kernel(StreamArgs 
   __shared__ double fin[kWaves];
   __shared__ double sc[KR], sd[KR], sig[KR];
   __shared__ double cacc[KR][kReduceCols];
+  __shared__ float stage[kWaves * 512];   // per wave: 8 rows x 64 lanes on their way to the row sums
   float* Uown = own;
   float* Vown = own + (size_t)KR * a.rows_own;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, b = blockIdx.x, G = gridDim.x;
@@ -885,7 +949,7 @@ __global__ __launch_bounds__(kChainThreads) void stream_chain_kernel(StreamArgs 
         blk.load(a.W, a.ldw, n, row0, r1);
         float us[R];
         blk.times_vector(vin, sf, rs, n, us);
-        wave_row_sums<R>(us, red);
+        wave_row_sums_into<R>(us, red, stage + wave * 512);
         __syncthreads();
         if (tid < R) {
           double t = 0.0;
@@ -1189,48 +1253,6 @@ __host__ __device__ inline ResidentLds resident_lds(int nsw, int rr, int rw, int
   L.vcode = take((size_t)kMaxStreamRank * tc);
   L.total = off;
   return L;
-}
-
-// Lane exchanges inside a row of 16 lanes by data-parallel primitives (no LDS traffic): after the
-// four steps every lane of a row holds the sum over the row, added in a fixed order.
-template <int CTRL>
-__device__ __forceinline__ double dpp_move(double v) {
-  const unsigned long long bits = __double_as_longlong(v);
-  const int lo = __builtin_amdgcn_update_dpp(0, (int)(unsigned)bits, CTRL, 0xf, 0xf, false);
-  const int hi = __builtin_amdgcn_update_dpp(0, (int)(unsigned)(bits >> 32), CTRL, 0xf, 0xf, false);
-  return __longlong_as_double((long long)(((unsigned long long)(unsigned)hi << 32) | (unsigned)lo));
-}
-constexpr int kDppSwapPairs = 0xB1;      // quad_perm [1, 0, 3, 2]
-constexpr int kDppSwapHalfQuads = 0x4E;  // quad_perm [2, 3, 0, 1]
-constexpr int kDppHalfMirror = 0x141;    // lane i of 8 <- lane 7 - i
-constexpr int kDppMirror = 0x140;        // lane i of 16 <- lane 15 - i
-__device__ __forceinline__ double sum8(double t) {
-  t += dpp_move<kDppSwapPairs>(t);
-  t += dpp_move<kDppSwapHalfQuads>(t);
-  t += dpp_move<kDppHalfMirror>(t);
-  return t;
-}
-__device__ __forceinline__ double sum32(double t) {
-  t = sum8(t);
-  t += dpp_move<kDppMirror>(t);
-  t += __shfl_xor(t, 16);
-  return t;
-}
-
-// Sums over the 64 lanes of a wave of 8 per-lane values, in float64: the values go through
-// `stage` (8 x 64 floats of this wave's own), 8 lanes add up a row (each 8 values, then among
-// themselves).  Every lane returns the sum of row lane / 8.
-__device__ __forceinline__ double wave_row_sums_staged(const float (&us)[8], float* stage) {
-  const int lane = threadIdx.x & 63;
-  __builtin_amdgcn_wave_barrier();   // the reads of the previous call precede these writes
-#pragma unroll
-  for (int x = 0; x < 8; ++x) stage[x * 64 + lane] = us[x];
-  __builtin_amdgcn_wave_barrier();   // a wave's LDS accesses complete in order
-  const float4 v0 = *reinterpret_cast<const float4*>(stage + (lane >> 3) * 64 + (lane & 7) * 8);
-  const float4 v1 = *reinterpret_cast<const float4*>(stage + (lane >> 3) * 64 + (lane & 7) * 8 + 4);
-  const double t = (((double)v0.x + (double)v0.y) + ((double)v0.z + (double)v0.w)) +
-                   (((double)v1.x + (double)v1.y) + ((double)v1.z + (double)v1.w));
-  return sum8(t);
 }
 
 // A float64 as two tagged words: the nearest float32 and the float32 nearest to what is left.
