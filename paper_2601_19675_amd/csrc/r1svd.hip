@@ -1816,6 +1816,7 @@ __global__ __launch_bounds__(512) void tile_chain_kernel(TileArgs a) {
   __shared__ float vsh[kTile];          // ... as the float32 vector the products use
   __shared__ double ush[kTile];         // this row of tiles' piece of u, scaled
   __shared__ float red2[kWaves][kTile];
+  __shared__ float stage[kWaves * 512];   // per wave: 8 rows x 64 lanes on their way to the row sums
   __shared__ double udsh[kTile], vdsh[kTile];
   __shared__ double tmp[2 * kTile];
   __shared__ double fin[kWaves];
@@ -1867,30 +1868,18 @@ __global__ __launch_bounds__(512) void tile_chain_kernel(TileArgs a) {
       {
         const float4 v = *reinterpret_cast<const float4*>(&vsh[lane * 4]);
 #pragma unroll
-        for (int h = 0; h < kRowsPerWave / 16; ++h) {
-          double us[16];
+        for (int h = 0; h < kRowsPerWave / 8; ++h) {
+          float us[8];
 #pragma unroll
-          for (int j = 0; j < 16; ++j) {
-            const float* wr = wt[h * 16 + j];
-            us[j] = (double)fmaf(wr[3], v.w, fmaf(wr[2], v.z, fmaf(wr[1], v.y, wr[0] * v.x)));
+          for (int j = 0; j < 8; ++j) {
+            const float* wr = wt[h * 8 + j];
+            us[j] = fmaf(wr[3], v.w, fmaf(wr[2], v.z, fmaf(wr[1], v.y, wr[0] * v.x)));
           }
-          int width = 32;
-#pragma unroll
-          for (int cnt = 16; cnt > 1; cnt >>= 1, width >>= 1) {
-            const bool upper = (lane & width) != 0;
-#pragma unroll
-            for (int j = 0; j < cnt / 2; ++j) {
-              const double send = upper ? us[j] : us[j + cnt / 2];
-              const double keep = upper ? us[j + cnt / 2] : us[j];
-              us[j] = keep + __shfl_xor(send, width);
-            }
-          }
-          us[0] += __shfl_xor(us[0], 2);
-          us[0] += __shfl_xor(us[0], 1);
-          if ((lane & 3) == 0)
+          const double t = wave_row_sums_staged(us, stage + w * 512);
+          if ((lane & 7) == 0)
             store_tagged(a.upart + (int64_t)buf * part_stride + ((int64_t)p * Q + q) * kTilePart + w * kRowsPerWave +
-                             h * 16 + (lane >> 2),
-                         __float_as_uint((float)us[0]), tag);
+                             h * 8 + (lane >> 3),
+                         __float_as_uint((float)t), tag);
         }
         if (tid == 0)
           store_tagged(a.upart + (int64_t)buf * part_stride + ((int64_t)p * Q + q) * kTilePart + kTile,
