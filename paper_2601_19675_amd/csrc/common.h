@@ -64,6 +64,22 @@ inline bool lds_opt_in(int bytes) {
   return true;
 }
 
+// Lane exchanges inside a row of 16 lanes by data-parallel primitives: register moves, no trip
+// through the LDS crossbar (which a shuffle of a float64 makes twice).  Applied in this order --
+// pairs, half quads, half mirror, mirror -- with an associative, commutative operation after
+// each, every lane ends up with the result over 2, 4, 8, 16 lanes.
+template <int CTRL>
+__device__ __forceinline__ double dpp_move(double v) {
+  const unsigned long long bits = __double_as_longlong(v);
+  const int lo = __builtin_amdgcn_update_dpp(0, (int)(unsigned)bits, CTRL, 0xf, 0xf, false);
+  const int hi = __builtin_amdgcn_update_dpp(0, (int)(unsigned)(bits >> 32), CTRL, 0xf, 0xf, false);
+  return __longlong_as_double((long long)(((unsigned long long)(unsigned)hi << 32) | (unsigned)lo));
+}
+constexpr int kDppSwapPairs = 0xB1;      // quad_perm [1, 0, 3, 2]
+constexpr int kDppSwapHalfQuads = 0x4E;  // quad_perm [2, 3, 0, 1]
+constexpr int kDppHalfMirror = 0x141;    // lane i of 8 <- lane 7 - i
+constexpr int kDppMirror = 0x140;        // lane i of 16 <- lane 15 - i
+
 #define PTQ_HIP_CHECK_LAUNCH()                         \
   do {                                                 \
     if (hipGetLastError() != hipSuccess) return PTQ_ERR_HIP; \

@@ -198,11 +198,11 @@ __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
           lo = fmin(lo, v);
           hi = fmax(hi, v);
         }
-#pragma unroll
-        for (int x = 8; x > 0; x >>= 1) {
-          lo = fmin(lo, __shfl_xor(lo, x));
-          hi = fmax(hi, __shfl_xor(hi, x));
-        }
+        // over the row's 16 lanes (min and max do not depend on the order)
+        lo = fmin(lo, dpp_move<kDppSwapPairs>(lo));         hi = fmax(hi, dpp_move<kDppSwapPairs>(hi));
+        lo = fmin(lo, dpp_move<kDppSwapHalfQuads>(lo));     hi = fmax(hi, dpp_move<kDppSwapHalfQuads>(hi));
+        lo = fmin(lo, dpp_move<kDppHalfMirror>(lo));        hi = fmax(hi, dpp_move<kDppHalfMirror>(hi));
+        lo = fmin(lo, dpp_move<kDppMirror>(lo));            hi = fmax(hi, dpp_move<kDppMirror>(hi));
         if (sub == 0) {
           gmin[r] = lo;
           gmax[r] = hi;

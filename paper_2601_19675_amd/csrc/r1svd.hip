@@ -259,19 +259,7 @@ __device__ __forceinline__ void wave_row_sums(const float (&us)[R], double* red)
   }
 }
 
-// Lane exchanges inside a row of 16 lanes by data-parallel primitives (no LDS traffic): after the
-// four steps every lane of a row holds the sum over the row, added in a fixed order.
-template <int CTRL>
-__device__ __forceinline__ double dpp_move(double v) {
-  const unsigned long long bits = __double_as_longlong(v);
-  const int lo = __builtin_amdgcn_update_dpp(0, (int)(unsigned)bits, CTRL, 0xf, 0xf, false);
-  const int hi = __builtin_amdgcn_update_dpp(0, (int)(unsigned)(bits >> 32), CTRL, 0xf, 0xf, false);
-  return __longlong_as_double((long long)(((unsigned long long)(unsigned)hi << 32) | (unsigned)lo));
-}
-constexpr int kDppSwapPairs = 0xB1;      // quad_perm [1, 0, 3, 2]
-constexpr int kDppSwapHalfQuads = 0x4E;  // quad_perm [2, 3, 0, 1]
-constexpr int kDppHalfMirror = 0x141;    // lane i of 8 <- lane 7 - i
-constexpr int kDppMirror = 0x140;        // lane i of 16 <- lane 15 - i
+// Sums over 8 and over 32 adjacent lanes by the lane exchanges of common.h, added in a fixed order.
 __device__ __forceinline__ double sum8(double t) {
   t += dpp_move<kDppSwapPairs>(t);
   t += dpp_move<kDppSwapHalfQuads>(t);
