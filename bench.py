@@ -173,7 +173,7 @@ def r1svd_timings(ptq, W, X, m, n, t, rank=16, it=8, reps=5):
 
 
 def forward_timings(ptq, codes, scales, zeros, m, n, bits, group, rank=16, reps=20):
-    """The stored layer applied to 1 and to 4 tokens in the rotated-input form (packed codes of the step just
+    """The stored layer applied to 1, 4, 16 and 64 tokens in the rotated-input form (packed codes of the step just
     run, a random permutation, random rank-16 e4m3 factors): bound by the packed codes streaming from memory."""
     import torch
     from paper_2601_19675_amd import binding
@@ -191,7 +191,7 @@ def forward_timings(ptq, codes, scales, zeros, m, n, bits, group, rank=16, reps=
     s = torch.ones(n, dtype=torch.float64, device=dev)
     out = {"bits": bits, "group": group, "rank": rank, "packed_bytes": packed.numel() * 4}
     nbytes = packed.numel() * 4 + scales.numel() * 4 + zeros.numel() + rank * (m + n)
-    for tokens in (1, 4):
+    for tokens in (1, 4, 16, 64):
         X = torch.randn((tokens, n), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
         O = torch.empty((tokens, m), dtype=torch.float32, device=dev)
         ws = torch.empty(ptq.ptq_workspace_bytes(binding.OP_LINEAR_FORWARD, m, n, tokens, rank), dtype=torch.uint8,

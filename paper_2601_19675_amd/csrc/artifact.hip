@@ -282,6 +282,196 @@ __global__ void clear_counters_kernel(unsigned* done, int count) {
   if (i < count) done[i] = 0u;
 }
 
+// ---- many tokens: the same sums on the matrix cores ------------------------------------------
+// With 8 or more tokens the row-per-lane kernel above is bound by feeding the same x to all lanes.
+// Here a wave takes 32 rows and up to 32 tokens and accumulates  raw[row][t] = sum_j code_j x_tj
+// with the float32 32 x 32 x 2 MFMA (full float32 products and sums): lane l supplies the code of
+// row l % 32 for the column of parity l / 32 -- both halves of the wave load the same packed
+// words and extract alternate codes, so nothing is transposed -- and x[t = l % 32] of that
+// column from LDS.  At the end of a quantization group (or of the run of 8 chunks) the 16
+// accumulators of a lane get  scale (raw - zero sum_j x_tj)  for their rows and start again.
+// grid: (row blocks of 128, runs of kFwdRun chunks), 4 waves; partial sums and the finish as above.
+constexpr int kMfmaTokens = 32, kMfmaRows = 128;
+
+template <int BITS>
+__global__ __launch_bounds__(256) void forward_mfma_kernel(ForwardArgs a, int tokens) {
+  __shared__ float xs[kFwdRun * kChunk][kMfmaTokens + 1];   // [column of the run][token]; the odd pitch spreads the transposing stores over the banks
+  __shared__ float xsum[kFwdRun][kMfmaTokens];
+  __shared__ float gsc[kFwdRun][kMfmaRows], gz[kFwdRun][kMfmaRows];
+  __shared__ int last;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int m = a.m, n = a.n, chunks = n / kChunk;
+  const int c0 = blockIdx.y * kFwdRun;
+  const int nc = min(kFwdRun, chunks - c0);
+  const int row = blockIdx.x * kMfmaRows + w * 32 + (lane & 31);   // the row whose codes this lane supplies
+  const int parity = lane >> 5;
+  const bool live = row < m;
+
+  Words<BITS> wd[kFwdRun];
+#pragma unroll
+  for (int k = 0; k < kFwdRun; ++k) {
+#pragma unroll
+    for (int q = 0; q < BITS; ++q) wd[k].w[q] = 0u;
+    if (live && k < nc) wd[k] = *reinterpret_cast<const Words<BITS>*>(a.packed + ((int64_t)(c0 + k) * m + row) * BITS);
+  }
+  // x of the run, transposed to [column][token] (zeros past the last token and the last chunk):
+  // eight 16-byte loads per thread, all requested before the first is stored
+  {
+    constexpr int kQuads = kFwdRun * kChunk / 4;   // per token
+    float4 v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int e = tid + 256 * i, t = e / kQuads, c = 4 * (e - t * kQuads);
+      const bool ok = t < tokens && c < nc * kChunk;
+      const float4 x = *reinterpret_cast<const float4*>(a.xt + (int64_t)(t < tokens ? t : 0) * n + c0 * kChunk +
+                                                         (c < nc * kChunk ? c : 0));
+      v[i] = ok ? x : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int e = tid + 256 * i, t = e / kQuads, c = 4 * (e - t * kQuads);
+      xs[c][t] = v[i].x; xs[c + 1][t] = v[i].y; xs[c + 2][t] = v[i].z; xs[c + 3][t] = v[i].w;
+    }
+  }
+  // scale and zero of each chunk's group for the block's 128 rows
+  for (int e = tid; e < kFwdRun * kMfmaRows; e += 256) {
+    const int k = e / kMfmaRows, rl = e - k * kMfmaRows;
+    const int orow = blockIdx.x * kMfmaRows + rl;
+    const bool ok = k < nc && orow < m;
+    const int g = ((c0 + (k < nc ? k : 0)) * kChunk) / a.group;
+    gsc[k][rl] = ok ? a.scales[(int64_t)g * m + orow] : 0.f;
+    gz[k][rl] = ok ? (float)a.zeros[(int64_t)g * m + orow] : 0.f;
+  }
+  __syncthreads();
+  {
+    const int k = tid >> 5, t = tid & 31;   // 8 chunks x 32 tokens = 256 threads
+    float sum = 0.f;
+    for (int j = 0; j < kChunk; ++j) sum += xs[k * kChunk + j][t];
+    xsum[k][t] = sum;
+  }
+  __syncthreads();
+
+  // accumulator r of a lane is row (r / 4) * 8 + (lane / 32) * 4 + r % 4 of the wave's 32, token lane % 32
+  const int t_out = lane & 31;
+  f32x16 acc, total;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) { acc[r] = 0.f; total[r] = 0.f; }
+  float xsg = 0.f;
+#pragma unroll
+  for (int k = 0; k < kFwdRun; ++k) {
+    if (k >= nc) break;
+#pragma unroll
+    for (int i = 0; i < kChunk / 2; ++i) {
+      const uint32_t ce = chunk_code<BITS>(wd[k].w, 2 * i), co = chunk_code<BITS>(wd[k].w, 2 * i + 1);
+      const float cf = (float)(parity ? co : ce);
+      const float x = xs[k * kChunk + 2 * i + parity][t_out];
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(cf, x, acc, 0, 0, 0);
+    }
+    xsg += xsum[k][t_out];
+    const int col_end = (c0 + k + 1) * kChunk;
+    if (col_end % a.group == 0 || k == nc - 1) {   // the group ends here, or the run does
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int rl = w * 32 + (r >> 2) * 8 + parity * 4 + (r & 3);
+        total[r] = fmaf(gsc[k][rl], fmaf(-gz[k][rl], xsg, acc[r]), total[r]);
+        acc[r] = 0.f;
+      }
+      xsg = 0.f;
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int orow = blockIdx.x * kMfmaRows + w * 32 + (r >> 2) * 8 + parity * 4 + (r & 3);
+    if (orow < m && t_out < tokens)
+      __hip_atomic_store(a.partial + ((int64_t)blockIdx.y * kMfmaTokens + t_out) * m + orow, total[r], __ATOMIC_RELAXED,
+                         __HIP_MEMORY_SCOPE_AGENT);
+  }
+  __builtin_amdgcn_s_waitcnt(0);   // every wave's stores acknowledged before the workgroup is counted
+  __syncthreads();
+  const int splits = gridDim.y;
+  if (tid == 0) last = atomicAdd(a.done + blockIdx.x, 1u) + 1u == (unsigned)splits;
+  __syncthreads();
+  if (!last) return;
+  if (tid == 0) __hip_atomic_store(a.done + blockIdx.x, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  // finish.  With m a multiple of 4 the partial sums are read as ordinary 16-byte loads (four rows
+  // of one token and run) after an acquire fence, which drops whatever older copies of these
+  // lines this compute die may hold; the producers stored them device-coherently.
+  if ((m & 3) == 0) {
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    const int q4 = tid & 31;                                  // four rows
+    const int frow4 = blockIdx.x * kMfmaRows + 4 * q4;
+    if (frow4 >= m) return;
+    for (int t = tid >> 5; t < tokens; t += 8) {
+      float out[4] = {0.f, 0.f, 0.f, 0.f};
+      for (int sp0 = 0; sp0 < splits; sp0 += 16) {
+        float4 v[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+          const int sp = sp0 + k < splits ? sp0 + k : splits - 1;   // issued whatever sp: no branch, no wait
+          v[k] = *reinterpret_cast<const float4*>(a.partial + ((int64_t)sp * kMfmaTokens + t) * m + frow4);
+        }
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+          const bool on = sp0 + k < splits;
+          out[0] += on ? v[k].x : 0.f; out[1] += on ? v[k].y : 0.f;
+          out[2] += on ? v[k].z : 0.f; out[3] += on ? v[k].w : 0.f;
+        }
+      }
+      for (int k = 0; k < a.r; ++k) {
+        const float yk = a.y[(int64_t)t * a.r + k];
+        const uint32_t u4 = *reinterpret_cast<const uint32_t*>(a.U + (int64_t)k * m + frow4);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) out[j] = fmaf(e4m3_to_float((uint8_t)(u4 >> (8 * j))), yk, out[j]);
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) a.O[(int64_t)t * a.ldo + frow4 + j] = out[j];
+    }
+    return;
+  }
+  // finish: thread = (row of the block, half of the tokens), eight tokens at a time with the partial
+  // sums of sixteen column runs requested together (each round of requests is a trip to memory)
+  const int frow = blockIdx.x * kMfmaRows + (tid & (kMfmaRows - 1));
+  if (frow >= m) return;
+  const int t_begin = (tid / kMfmaRows) * 16;
+  for (int t0 = t_begin; t0 < t_begin + 16 && t0 < tokens; t0 += 8) {
+    float out[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) out[t] = 0.f;
+    for (int sp0 = 0; sp0 < splits; sp0 += 16) {
+      float v[16][8];
+#pragma unroll
+      for (int k = 0; k < 16; ++k)
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+          const int sp = sp0 + k < splits ? sp0 + k : splits - 1;   // issued whatever sp: no branch, no wait
+          const int tt = t0 + t < tokens ? t0 + t : tokens - 1;
+          v[k][t] = __hip_atomic_load(a.partial + ((int64_t)sp * kMfmaTokens + tt) * m + frow, __ATOMIC_RELAXED,
+                                      __HIP_MEMORY_SCOPE_AGENT);
+        }
+#pragma unroll
+      for (int k = 0; k < 16; ++k)
+#pragma unroll
+        for (int t = 0; t < 8; ++t) out[t] += sp0 + k < splits ? v[k][t] : 0.f;
+    }
+    for (int k = 0; k < a.r; ++k) {
+      const float u = e4m3_to_float(a.U[(int64_t)k * m + frow]);
+#pragma unroll
+      for (int t = 0; t < 8; ++t)
+        if (t0 + t < tokens) out[t] = fmaf(u, a.y[(int64_t)(t0 + t) * a.r + k], out[t]);
+    }
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+      if (t0 + t < tokens) a.O[(int64_t)(t0 + t) * a.ldo + frow] = out[t];
+  }
+}
+
+template <int BITS>
+void launch_forward_mfma(const ForwardArgs& a, int tokens, hipStream_t st) {
+  const int splits = (int)ceil_div(a.n / kChunk, kFwdRun);
+  dim3 g((unsigned)ceil_div(a.m, kMfmaRows), (unsigned)splits);
+  forward_mfma_kernel<BITS><<<g, 256, 0, st>>>(a, tokens);
+}
+
 template <int BITS, int B>
 void launch_forward_b(const ForwardArgs& a, hipStream_t st) {
   const int splits = (int)ceil_div(a.n / kChunk, kFwdRun);
@@ -289,7 +479,8 @@ void launch_forward_b(const ForwardArgs& a, hipStream_t st) {
   forward_partial_kernel<BITS, B><<<g, 256, 0, st>>>(a);
 }
 
-// four, two or one token per pass over the codes
+// up to 32 tokens per pass over the codes on the matrix cores while 8 or more are left, then
+// four, two or one token per pass
 template <int BITS>
 void launch_forward(const ForwardArgs& a, int tokens, hipStream_t st) {
   ForwardArgs b = a;
@@ -297,7 +488,8 @@ void launch_forward(const ForwardArgs& a, int tokens, hipStream_t st) {
   while (done < tokens) {
     const int left = tokens - done;
     int step;
-    if (left >= 4) { step = 4; launch_forward_b<BITS, 4>(b, st); }
+    if (left >= 8) { step = left < kMfmaTokens ? left : kMfmaTokens; launch_forward_mfma<BITS>(b, step, st); }
+    else if (left >= 4) { step = 4; launch_forward_b<BITS, 4>(b, st); }
     else if (left >= 2) { step = 2; launch_forward_b<BITS, 2>(b, st); }
     else { step = 1; launch_forward_b<BITS, 1>(b, st); }
     done += step;
@@ -346,10 +538,10 @@ ptq_status unpack_dequant_launch(const uint32_t* packed, int64_t m, int64_t n, i
 }
 
 static size_t forward_partial_bytes(int64_t m, int64_t n) {
-  return align_up((size_t)ceil_div(n / kChunk, kFwdRun) * 4 * (size_t)m * sizeof(float), 256);
+  return align_up((size_t)ceil_div(n / kChunk, kFwdRun) * kMfmaTokens * (size_t)m * sizeof(float), 256);
 }
 
-static size_t forward_counter_bytes(int64_t m) { return align_up((size_t)ceil_div(m, 256) * sizeof(unsigned), 256); }
+static size_t forward_counter_bytes(int64_t m) { return align_up((size_t)ceil_div(m, kMfmaRows) * sizeof(unsigned), 256); }
 
 size_t linear_forward_workspace_bytes(int64_t tokens, int64_t m, int64_t n, int64_t r) {
   return align_up((size_t)tokens * n * sizeof(float), 256) +
@@ -371,7 +563,7 @@ ptq_status linear_forward_launch(const void* X, ptq_dtype xdt, int64_t ldx, int6
   // X~ = X P Q: the rows of X go through the same transform as the rows of the residual
   ptq_status rc = lopro_rotate_input_launch(X, xdt, ldx, tokens, n, perm, b_I, b_H, xt, n, st);
   if (rc != PTQ_OK) return rc;
-  const int counters = (int)ceil_div(m, 256);
+  const int counters = (int)ceil_div(m, kMfmaRows);   // one per 128 rows (matrix-core passes) or per 256 (the others)
   if (r > 0) {
     const unsigned g = (unsigned)(tokens * r);
     switch (xdt) {

@@ -121,12 +121,26 @@ def _check_forward(X64, got, packed, codes, scales, zeros, perm, Uc, Vc, sigma, 
 
 @pytest.mark.parametrize("bits,tokens,dtype,r", [(2, 1, torch.float32, 4), (3, 3, torch.bfloat16, 5),
                                                  (4, 7, torch.float32, 16), (8, 2, torch.float64, 0),
-                                                 (3, 4, torch.float32, 70)])
+                                                 (3, 4, torch.float32, 70), (4, 29, torch.bfloat16, 16),
+                                                 (2, 16, torch.float32, 3)])
 def test_forward_matches_oracle(bits, tokens, dtype, r):
     rng = np.random.default_rng(bits * 10 + tokens)
     m, n, group, bI, bH = 77, 1024, 64, 256, 128
     layer = _random_layer(rng, m, n, r, bits, group)
     X_t = _dev(rng.standard_normal((tokens, n))).to(dtype)
+    X64 = X_t.to(torch.float64).cpu().numpy()
+    got, packed = _forward(X_t, *layer, bits, group, bI, bH)
+    _check_forward(X64, got, packed, *layer, bits, group, bI, bH)
+
+
+@pytest.mark.parametrize("bits,tokens,m,group", [(4, 19, 256, 128), (3, 32, 132, 32), (2, 45, 64, 512)])
+def test_forward_many_tokens_on_the_matrix_cores(bits, tokens, m, group):
+    """Eight or more tokens go through the float32 MFMA kernel, up to 32 per pass; groups of one chunk,
+    of four, and longer than a workgroup's run of columns; m a multiple of 4 (wide loads in the finish)."""
+    rng = np.random.default_rng(1000 + tokens)
+    n, bI, bH, r = 1024, 256, 128, 6
+    layer = _random_layer(rng, m, n, r, bits, group)
+    X_t = _dev(rng.standard_normal((tokens, n)).astype(np.float32))
     X64 = X_t.to(torch.float64).cpu().numpy()
     got, packed = _forward(X_t, *layer, bits, group, bI, bH)
     _check_forward(X64, got, packed, *layer, bits, group, bI, bH)
