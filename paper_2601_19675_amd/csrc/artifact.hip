@@ -290,7 +290,7 @@ __global__ void clear_counters_kernel(unsigned* done, int count) {
 // words and extract alternate codes, so nothing is transposed -- and x[t = l % 32] of that
 // column from LDS.  At the end of a quantization group (or of the run of 8 chunks) the 16
 // accumulators of a lane get  scale (raw - zero sum_j x_tj)  for their rows and start again.
-// grid: (row blocks of 128, runs of kFwdRun chunks), 4 waves; partial sums and the finish as above.
+// grid: (row blocks of 128, runs of kFwdRun chunks), 4 waves; the partial sums are added by the kernel below.
 constexpr int kMfmaTokens = 32, kMfmaRows = 128;
 
 template <int BITS>
@@ -298,7 +298,6 @@ __global__ __launch_bounds__(256) void forward_mfma_kernel(ForwardArgs a, int to
   __shared__ float xs[kFwdRun * kChunk][kMfmaTokens + 1];   // [column of the run][token]; the odd pitch spreads the transposing stores over the banks
   __shared__ float xsum[kFwdRun][kMfmaTokens];
   __shared__ float gsc[kFwdRun][kMfmaRows], gz[kFwdRun][kMfmaRows];
-  __shared__ int last;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int m = a.m, n = a.n, chunks = n / kChunk;
   const int c0 = blockIdx.y * kFwdRun;
@@ -382,87 +381,43 @@ __global__ __launch_bounds__(256) void forward_mfma_kernel(ForwardArgs a, int to
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
     const int orow = blockIdx.x * kMfmaRows + w * 32 + (r >> 2) * 8 + parity * 4 + (r & 3);
-    if (orow < m && t_out < tokens)
-      __hip_atomic_store(a.partial + ((int64_t)blockIdx.y * kMfmaTokens + t_out) * m + orow, total[r], __ATOMIC_RELAXED,
-                         __HIP_MEMORY_SCOPE_AGENT);
+    if (orow < m && t_out < tokens) a.partial[((int64_t)blockIdx.y * kMfmaTokens + t_out) * m + orow] = total[r];
   }
-  __builtin_amdgcn_s_waitcnt(0);   // every wave's stores acknowledged before the workgroup is counted
-  __syncthreads();
-  const int splits = gridDim.y;
-  if (tid == 0) last = atomicAdd(a.done + blockIdx.x, 1u) + 1u == (unsigned)splits;
-  __syncthreads();
-  if (!last) return;
-  if (tid == 0) __hip_atomic_store(a.done + blockIdx.x, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  // finish.  With m a multiple of 4 the partial sums are read as ordinary 16-byte loads (four rows
-  // of one token and run) after an acquire fence, which drops whatever older copies of these
-  // lines this compute die may hold; the producers stored them device-coherently.
-  if ((m & 3) == 0) {
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-    const int q4 = tid & 31;                                  // four rows
-    const int frow4 = blockIdx.x * kMfmaRows + 4 * q4;
-    if (frow4 >= m) return;
-    for (int t = tid >> 5; t < tokens; t += 8) {
-      float out[4] = {0.f, 0.f, 0.f, 0.f};
-      for (int sp0 = 0; sp0 < splits; sp0 += 16) {
-        float4 v[16];
+}
+
+// O[t][row] = sum over the column runs, in order, + sum_k U[k][row] y[t][k] for the matrix-core
+// passes: with up to 32 tokens the sums are enough work for a launch of their own over the whole
+// chip (done by the last workgroup of each row block they took longer than the products).
+// grid: (rows / 256, groups of four tokens)
+__global__ __launch_bounds__(256) void forward_mfma_finish_kernel(ForwardArgs a, int tokens, int splits) {
+  const int row = blockIdx.x * 256 + threadIdx.x;
+  const int t0 = blockIdx.y * 4;
+  if (row >= a.m) return;
+  float out[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int sp0 = 0; sp0 < splits; sp0 += 16) {
+    float v[16][4];
 #pragma unroll
-        for (int k = 0; k < 16; ++k) {
-          const int sp = sp0 + k < splits ? sp0 + k : splits - 1;   // issued whatever sp: no branch, no wait
-          v[k] = *reinterpret_cast<const float4*>(a.partial + ((int64_t)sp * kMfmaTokens + t) * m + frow4);
-        }
+    for (int k = 0; k < 16; ++k)
 #pragma unroll
-        for (int k = 0; k < 16; ++k) {
-          const bool on = sp0 + k < splits;
-          out[0] += on ? v[k].x : 0.f; out[1] += on ? v[k].y : 0.f;
-          out[2] += on ? v[k].z : 0.f; out[3] += on ? v[k].w : 0.f;
-        }
-      }
-      for (int k = 0; k < a.r; ++k) {
-        const float yk = a.y[(int64_t)t * a.r + k];
-        const uint32_t u4 = *reinterpret_cast<const uint32_t*>(a.U + (int64_t)k * m + frow4);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) out[j] = fmaf(e4m3_to_float((uint8_t)(u4 >> (8 * j))), yk, out[j]);
+      for (int t = 0; t < 4; ++t) {
+        const int sp = sp0 + k < splits ? sp0 + k : splits - 1;   // issued whatever sp: no branch, no wait
+        const int tt = t0 + t < tokens ? t0 + t : tokens - 1;
+        v[k][t] = a.partial[((int64_t)sp * kMfmaTokens + tt) * a.m + row];
       }
 #pragma unroll
-      for (int j = 0; j < 4; ++j) a.O[(int64_t)t * a.ldo + frow4 + j] = out[j];
-    }
-    return;
+    for (int k = 0; k < 16; ++k)
+#pragma unroll
+      for (int t = 0; t < 4; ++t) out[t] += sp0 + k < splits ? v[k][t] : 0.f;
   }
-  // finish: thread = (row of the block, half of the tokens), eight tokens at a time with the partial
-  // sums of sixteen column runs requested together (each round of requests is a trip to memory)
-  const int frow = blockIdx.x * kMfmaRows + (tid & (kMfmaRows - 1));
-  if (frow >= m) return;
-  const int t_begin = (tid / kMfmaRows) * 16;
-  for (int t0 = t_begin; t0 < t_begin + 16 && t0 < tokens; t0 += 8) {
-    float out[8];
+  for (int k = 0; k < a.r; ++k) {
+    const float u = e4m3_to_float(a.U[(int64_t)k * a.m + row]);
 #pragma unroll
-    for (int t = 0; t < 8; ++t) out[t] = 0.f;
-    for (int sp0 = 0; sp0 < splits; sp0 += 16) {
-      float v[16][8];
-#pragma unroll
-      for (int k = 0; k < 16; ++k)
-#pragma unroll
-        for (int t = 0; t < 8; ++t) {
-          const int sp = sp0 + k < splits ? sp0 + k : splits - 1;   // issued whatever sp: no branch, no wait
-          const int tt = t0 + t < tokens ? t0 + t : tokens - 1;
-          v[k][t] = __hip_atomic_load(a.partial + ((int64_t)sp * kMfmaTokens + tt) * m + frow, __ATOMIC_RELAXED,
-                                      __HIP_MEMORY_SCOPE_AGENT);
-        }
-#pragma unroll
-      for (int k = 0; k < 16; ++k)
-#pragma unroll
-        for (int t = 0; t < 8; ++t) out[t] += sp0 + k < splits ? v[k][t] : 0.f;
-    }
-    for (int k = 0; k < a.r; ++k) {
-      const float u = e4m3_to_float(a.U[(int64_t)k * m + frow]);
-#pragma unroll
-      for (int t = 0; t < 8; ++t)
-        if (t0 + t < tokens) out[t] = fmaf(u, a.y[(int64_t)(t0 + t) * a.r + k], out[t]);
-    }
-#pragma unroll
-    for (int t = 0; t < 8; ++t)
-      if (t0 + t < tokens) a.O[(int64_t)(t0 + t) * a.ldo + frow] = out[t];
+    for (int t = 0; t < 4; ++t)
+      if (t0 + t < tokens) out[t] = fmaf(u, a.y[(int64_t)(t0 + t) * a.r + k], out[t]);
   }
+#pragma unroll
+  for (int t = 0; t < 4; ++t)
+    if (t0 + t < tokens) a.O[(int64_t)(t0 + t) * a.ldo + row] = out[t];
 }
 
 template <int BITS>
@@ -470,6 +425,8 @@ void launch_forward_mfma(const ForwardArgs& a, int tokens, hipStream_t st) {
   const int splits = (int)ceil_div(a.n / kChunk, kFwdRun);
   dim3 g((unsigned)ceil_div(a.m, kMfmaRows), (unsigned)splits);
   forward_mfma_kernel<BITS><<<g, 256, 0, st>>>(a, tokens);
+  dim3 gf((unsigned)ceil_div(a.m, 256), (unsigned)ceil_div(tokens, 4));
+  forward_mfma_finish_kernel<<<gf, 256, 0, st>>>(a, tokens, splits);
 }
 
 template <int BITS, int B>
@@ -541,7 +498,7 @@ static size_t forward_partial_bytes(int64_t m, int64_t n) {
   return align_up((size_t)ceil_div(n / kChunk, kFwdRun) * kMfmaTokens * (size_t)m * sizeof(float), 256);
 }
 
-static size_t forward_counter_bytes(int64_t m) { return align_up((size_t)ceil_div(m, kMfmaRows) * sizeof(unsigned), 256); }
+static size_t forward_counter_bytes(int64_t m) { return align_up((size_t)ceil_div(m, 256) * sizeof(unsigned), 256); }
 
 size_t linear_forward_workspace_bytes(int64_t tokens, int64_t m, int64_t n, int64_t r) {
   return align_up((size_t)tokens * n * sizeof(float), 256) +
@@ -563,7 +520,7 @@ ptq_status linear_forward_launch(const void* X, ptq_dtype xdt, int64_t ldx, int6
   // X~ = X P Q: the rows of X go through the same transform as the rows of the residual
   ptq_status rc = lopro_rotate_input_launch(X, xdt, ldx, tokens, n, perm, b_I, b_H, xt, n, st);
   if (rc != PTQ_OK) return rc;
-  const int counters = (int)ceil_div(m, kMfmaRows);   // one per 128 rows (matrix-core passes) or per 256 (the others)
+  const int counters = (int)ceil_div(m, 256);
   if (r > 0) {
     const unsigned g = (unsigned)(tokens * r);
     switch (xdt) {
