@@ -330,6 +330,11 @@ __global__ __launch_bounds__(256) void forward_mfma_kernel(ForwardArgs a, int to
     for (int i = 0; i < 8; ++i) {
       const int e = tid + 256 * i, t = e / kQuads, c = 4 * (e - t * kQuads);
       xs[c][t] = v[i].x; xs[c + 1][t] = v[i].y; xs[c + 2][t] = v[i].z; xs[c + 3][t] = v[i].w;
+      float sum = (v[i].x + v[i].y) + (v[i].z + v[i].w);   // eight consecutive lanes hold one chunk of a token
+      sum += __shfl_xor(sum, 1);
+      sum += __shfl_xor(sum, 2);
+      sum += __shfl_xor(sum, 4);
+      if ((c & (kChunk - 1)) == 0) xsum[c / kChunk][t] = sum;
     }
   }
   // scale and zero of each chunk's group for the block's 128 rows
@@ -342,13 +347,6 @@ __global__ __launch_bounds__(256) void forward_mfma_kernel(ForwardArgs a, int to
     gz[k][rl] = ok ? (float)a.zeros[(int64_t)g * m + orow] : 0.f;
   }
   __syncthreads();
-  {
-    const int k = tid >> 5, t = tid & 31;   // 8 chunks x 32 tokens = 256 threads
-    float sum = 0.f;
-    for (int j = 0; j < kChunk; ++j) sum += xs[k * kChunk + j][t];
-    xsum[k][t] = sum;
-  }
-  __syncthreads();
 
   // accumulator r of a lane is row (r / 4) * 8 + (lane / 32) * 4 + r % 4 of the wave's 32, token lane % 32
   const int t_out = lane & 31;
@@ -359,12 +357,14 @@ __global__ __launch_bounds__(256) void forward_mfma_kernel(ForwardArgs a, int to
 #pragma unroll
   for (int k = 0; k < kFwdRun; ++k) {
     if (k >= nc) break;
+    float xv[kChunk / 2];   // the chunk's x values first: one LDS latency per chunk, not per MFMA
+#pragma unroll
+    for (int i = 0; i < kChunk / 2; ++i) xv[i] = xs[k * kChunk + 2 * i + parity][t_out];
 #pragma unroll
     for (int i = 0; i < kChunk / 2; ++i) {
       const uint32_t ce = chunk_code<BITS>(wd[k].w, 2 * i), co = chunk_code<BITS>(wd[k].w, 2 * i + 1);
       const float cf = (float)(parity ? co : ce);
-      const float x = xs[k * kChunk + 2 * i + parity][t_out];
-      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(cf, x, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(cf, xv[i], acc, 0, 0, 0);
     }
     xsg += xsum[k][t_out];
     const int col_end = (c0 + k + 1) * kChunk;
