@@ -116,6 +116,18 @@ def test_r1svd_bfloat16_forms_shapes(m, n, r, it, form, monkeypatch):
     _check(W64, s, S, it, got)
 
 
+@pytest.mark.parametrize("form", ["resident", "stream"])
+def test_r1svd_bfloat16_forms_read_a_strided_weight(form, monkeypatch):
+    """The weight as a view into a wider buffer (row pitch n + 64): the forms that never copy W must follow it."""
+    monkeypatch.setenv("PTQ_R1SVD_LAUNCH", form)
+    m, n, r, it = 150, 1024, 4, 2
+    Ws, W64, s, S = _case(m, n, "bf16", 955, r)
+    Wbig = torch.full((m, n + 64), 7.0, dtype=torch.bfloat16, device="cuda")
+    Wbig[:, :n] = to_device(Ws)
+    got = _run_gpu(Wbig[:, :n], s, S, it)
+    _check(W64, s, S, it, got)
+
+
 def test_r1svd_float64_weight_and_strided_views():
     m, n, r = 40, 512, 3
     Ws, W64, s, S = _case(m, n, "f32", 950, r)
