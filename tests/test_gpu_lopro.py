@@ -162,6 +162,52 @@ def test_solve_in_the_rotated_basis_end_to_end():
     print(f"rel layer error rotated solve {float(e_orig[0]):.5f} (oracle {rel_ref:.5f})")
 
 
+def test_activation_order_is_the_permuted_solve_without_rotation():
+    """The activation-order variant of the column solve (columns taken by falling diag(H)) needs no code
+    of its own: a row of ones as the "residual" makes the key diag(H), and b_I = n leaves no rotated
+    block, so order / permute W and H / solve / permute back is that variant.  Checked against the oracle
+    solving the explicitly permuted problem."""
+    m, n, bits, group, block = 40, 512, 4, 128, 128
+    Ws, W64, H = _layer(m, n, 2048, "bf16", 905)
+    Wd, Hd = to_device(Ws), _dev(H)
+    perm = torch.empty(n, dtype=torch.int32, device="cuda")
+    ptq.ptq_lopro_column_order(torch.ones((1, n), dtype=torch.float32, device="cuda"), Hd, perm)
+    pg = perm.cpu().numpy().astype(np.int64)
+    d = np.diag(H)
+    assert np.all(np.diff(d[pg]) <= 0) and sorted(pg.tolist()) == list(range(n))
+    Wp = torch.empty((m, n), dtype=torch.float64, device="cuda")
+    Hp = torch.empty((n, n), dtype=torch.float64, device="cuda")
+    ptq.ptq_lopro_rotate_weight(Wd, perm, n, 256, Wp)
+    ptq.ptq_lopro_rotate_hessian(Hd, perm, n, 256, Hp)
+    assert np.array_equal(Wp.cpu().numpy(), W64[:, pg])
+    assert np.array_equal(Hp.cpu().numpy(), H[np.ix_(pg, pg)])
+    U = torch.empty((n, n), dtype=torch.float64, device="cuda")
+    dead = torch.empty(n, dtype=torch.uint8, device="cuda")
+    info = torch.empty(2, dtype=torch.int32, device="cuda")
+    ptq.ptq_damped_cholesky_inv(Hp, 0.01, U, dead, info)
+    codes = torch.empty((m, n), dtype=torch.uint8, device="cuda")
+    scales = torch.empty((m, n // group), dtype=torch.float32, device="cuda")
+    zeros = torch.empty((m, n // group), dtype=torch.uint8, device="cuda")
+    Wq = torch.empty((m, n), dtype=torch.float64, device="cuda")
+    ptq.ptq_quantize_layer(Wp, U, dead, bits, group, block, codes, scales, zeros, Wq, None)
+    back = torch.empty_like(Wq)
+    ptq.ptq_lopro_unrotate_weight(Wq, perm, n, 256, back)
+    err = torch.zeros(3, dtype=torch.float64, device="cuda")
+    ptq.ptq_layer_error(Wd, back, Hd, err)
+    # the oracle on the permuted operands
+    Hdm, dm = orc.damp(H[np.ix_(pg, pg)], 0.01)
+    out = orc.quantize_layer(W64[:, pg], orc.inverse_cholesky_upper(Hdm), bits, group, dead=dm)
+    rep = compare_quantization(Wp.cpu().numpy(), U.cpu().numpy(), bits, group, None, codes.cpu().numpy(),
+                               scales.cpu().numpy(), zeros.cpu().numpy())
+    assert rep["unflagged"] == 0, rep["details"][:3]
+    ref_back = np.empty_like(out["Wq"])
+    ref_back[:, pg] = out["Wq"]
+    rel_ref = orc.layer_error(W64, ref_back, H)[0]
+    assert abs(float(err[0]) - rel_ref) <= 1e-4
+    # codes come back to their own columns
+    assert np.array_equal(back.cpu().numpy()[:, pg], Wq.cpu().numpy())
+
+
 def test_full_size_rotation_sampled(capsys):
     # the C2 layer's own size (4096 x 4096 bf16, b_I = b_H = 256): rows of R' and entries of H' sampled
     # against the definition (the dense oracle at n = 4096 would take minutes)
