@@ -121,7 +121,7 @@ def group_grid(wg: np.ndarray, maxq: int):
 
 def quantize_layer(W: np.ndarray, U: np.ndarray, bits: int, group: int,
                    dead: np.ndarray | None = None, forced: dict | None = None,
-                   want_pre: bool = False):
+                   want_pre: bool = False, static_groups: bool = False):
     """Greedy column-sequential quantization of the rows of W (m x n).
 
     For column j (Sec. 2, item (a): quantize a column, compensate the later
@@ -130,7 +130,9 @@ def quantize_layer(W: np.ndarray, U: np.ndarray, bits: int, group: int,
               e    = (w_j - q) / U_jj
               w_k -= e * U_jk      for every k > j.
     The grid of a group is taken from the row's current values when j reaches
-    the first column of that group.
+    the first column of that group, or -- `static_groups`, an option of the
+    quantizer the paper names in that item -- from the row's values as they
+    were handed over, before any compensation.
 
     `forced` (used by the parity protocol for near-ties) maps
     ("code", r, j) / ("zero", r, k) / ("scale", r, k) to the value to take
@@ -148,6 +150,7 @@ def quantize_layer(W: np.ndarray, U: np.ndarray, bits: int, group: int,
     ng = n // group
     if dead is not None:
         W[:, np.asarray(dead, dtype=bool)] = 0.0
+    W_given = W.copy()
     forced = forced or {}
     f_code, f_zero, f_scale = {}, {}, {}
     for (kind, r, idx), v in forced.items():
@@ -165,7 +168,7 @@ def quantize_layer(W: np.ndarray, U: np.ndarray, bits: int, group: int,
     for j in range(n):
         if j % group == 0:
             k = j // group
-            scale, zero, ps, pz, xmin = group_grid(W[:, j:j + group], int(maxq))
+            scale, zero, ps, pz, xmin = group_grid((W_given if static_groups else W)[:, j:j + group], int(maxq))
             if k in f_scale:
                 for r, v in f_scale[k]:
                     scale[r] = float(np.float32(v))

@@ -330,3 +330,57 @@ def test_trace_identity_and_permutation_covariance():
     assert abs(rel - rel3) < 1e-12
     Hu = np.triu(H) + 123.0 * np.tril(np.ones((n, n)), -1)
     assert np.array_equal(orc.symmetrize_from_upper(Hu), np.triu(H) + np.triu(H, 1).T)
+
+
+# ---------------------------------------------------------- static groups
+def test_static_groups_grids_are_those_of_the_given_weights():
+    """With static groups every scale and zero is the round-to-nearest grid of the weights as handed
+    over: independent of the Hessian, and equal to the textbook min / max grid written out by hand."""
+    rng = np.random.default_rng(410)
+    m, n, bits, group = 6, 64, 3, 16
+    W = rng.standard_normal((m, n)) * 0.02
+    W[:, 3] *= 12
+    maxq = 2 ** bits - 1
+    outs = []
+    for seed in (1, 2):
+        H, _ = _spd(n, np.random.default_rng(seed))
+        Hd, _ = orc.damp(H, 0.01)
+        outs.append(orc.quantize_layer(W, orc.inverse_cholesky_upper(Hd), bits, group, static_groups=True))
+    assert np.array_equal(outs[0]["scales"], outs[1]["scales"]) and np.array_equal(outs[0]["zeros"], outs[1]["zeros"])
+    assert not np.array_equal(outs[0]["codes"], outs[1]["codes"])      # the codes do feel the Hessian
+    for r in range(m):
+        for k in range(n // group):
+            g = W[r, k * group:(k + 1) * group]
+            lo, hi = min(0.0, g.min()), max(0.0, g.max())
+            s = float(np.float32((hi - lo) / maxq))
+            assert outs[0]["scales"][r, k] == np.float32(s) and outs[0]["zeros"][r, k] == round(-lo / s)
+    # the grids of the ordinary solve move with the compensation (first group aside)
+    dyn = orc.quantize_layer(W, orc.inverse_cholesky_upper(orc.damp(_spd(n, np.random.default_rng(1))[0], 0.01)[0]),
+                             bits, group)
+    assert np.array_equal(dyn["scales"][:, 0], outs[0]["scales"][:, 0])
+    assert not np.array_equal(dyn["scales"][:, 1:], outs[0]["scales"][:, 1:])
+
+
+def test_static_groups_keep_the_identities_of_the_solve():
+    """Where the grid comes from does not touch the compensation: (W - Wq) = E U and sum e^2 =
+    tr(D H_d D^T) still hold, a diagonal Hessian still gives round-to-nearest, and weights on the grid
+    are still recovered exactly."""
+    rng = np.random.default_rng(411)
+    m, n, bits, group = 5, 48, 4, 16
+    H, _ = _spd(n, rng)
+    Hd, _ = orc.damp(H, 0.01)
+    U = orc.inverse_cholesky_upper(Hd)
+    W = rng.standard_normal((m, n)) * 0.02
+    out = orc.quantize_layer(W, U, bits, group, static_groups=True)
+    D = W - out["Wq"]
+    assert np.allclose(D, out["E"] @ U, rtol=0, atol=1e-12 * np.abs(W).max())
+    assert np.allclose(np.einsum("ij,ij->i", D @ Hd, D), out["row_err2"], rtol=1e-9, atol=0)
+    assert np.allclose(out["Wq"], orc.dequantize(out["codes"], out["scales"], out["zeros"], group))
+    Udiag = orc.inverse_cholesky_upper(np.diag(rng.uniform(0.5, 50.0, n)))
+    a = orc.quantize_layer(W, Udiag, bits, group, static_groups=True)
+    b = orc.quantize_layer(W, Udiag, bits, group)
+    assert all(np.array_equal(a[k], b[k]) for k in ("codes", "scales", "zeros"))
+    rtn = orc.round_to_nearest(W, bits, group)
+    on_grid = orc.dequantize(rtn["codes"], rtn["scales"], rtn["zeros"], group)
+    c = orc.quantize_layer(on_grid, U, bits, group, static_groups=True)
+    assert np.array_equal(c["Wq"], on_grid)
