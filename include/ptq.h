@@ -154,6 +154,22 @@ ptq_status ptq_quantize_layer(const void* W, ptq_dtype wdt, int64_t ldw, int64_t
                               ptq_stream stream);
 
 /*
+ * The same solve with STATIC GROUPS, an option of the quantizer the paper builds on (Sec. 2,
+ * item (a): compensation-based methods, GPTQ): the scale and zero of every (row, group) are
+ * taken from W as it is handed over (dead columns counting as zeros), before any compensation,
+ * instead of from the row's updated values when the walk reaches the group.  Arguments, layouts,
+ * workspace and errors as for ptq_quantize_layer.  (Its other option, taking the columns in the
+ * order of falling diag(H), needs no entry point: ptq_lopro_column_order on a 1 x n matrix of
+ * ones gives that order, and the permutation calls with b_I = n apply it without rotating.)
+ */
+ptq_status ptq_quantize_layer_static_groups(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m,
+                                            int64_t n, const double* U, int64_t ldu,
+                                            const uint8_t* dead_mask, int bits, int group, int block,
+                                            uint8_t* codes, float* scales, uint8_t* zeros, double* Wq,
+                                            double* row_err2, void* ws, size_t ws_bytes,
+                                            ptq_stream stream);
+
+/*
  * Relative layer error under the proxy-Hessian loss (Sec. 2, Eq. 1):
  *
  *   num = tr((W - Wq) H (W - Wq)^T),  den = tr(W H W^T),  rel = sqrt(num / den)

@@ -52,9 +52,10 @@ def load_library() -> ctypes.CDLL:
     lib.ptq_hessian_accumulate.argtypes = [vp, i64, vp, c.c_int, i64, i64, i64, vp, sz, vp]
     lib.ptq_damped_cholesky_inv.restype = c.c_int
     lib.ptq_damped_cholesky_inv.argtypes = [vp, i64, i64, c.c_double, vp, i64, vp, vp, vp, sz, vp]
-    lib.ptq_quantize_layer.restype = c.c_int
-    lib.ptq_quantize_layer.argtypes = [vp, c.c_int, i64, i64, i64, vp, i64, vp, c.c_int, c.c_int,
-                                       c.c_int, vp, vp, vp, vp, vp, vp, sz, vp]
+    for fn in (lib.ptq_quantize_layer, lib.ptq_quantize_layer_static_groups):
+        fn.restype = c.c_int
+        fn.argtypes = [vp, c.c_int, i64, i64, i64, vp, i64, vp, c.c_int, c.c_int, c.c_int, vp, vp, vp, vp, vp, vp,
+                       sz, vp]
     lib.ptq_layer_error.restype = c.c_int
     lib.ptq_layer_error.argtypes = [vp, c.c_int, i64, vp, i64, i64, vp, i64, vp, vp, sz, vp]
     lib.ptq_lopro_column_order.restype = c.c_int
@@ -159,7 +160,8 @@ def ptq_damped_cholesky_inv(H: torch.Tensor, damp: float, U: torch.Tensor,
 def ptq_quantize_layer(W: torch.Tensor, U: torch.Tensor, dead_mask: torch.Tensor | None, bits: int,
                        group: int, block: int, codes: torch.Tensor, scales: torch.Tensor,
                        zeros: torch.Tensor, Wq: torch.Tensor | None = None,
-                       row_err2: torch.Tensor | None = None, ws: torch.Tensor | None = None) -> None:
+                       row_err2: torch.Tensor | None = None, ws: torch.Tensor | None = None,
+                       _entry: str = "ptq_quantize_layer") -> None:
     """Column-sequential quantize + compensate of W (m x n) with factor U."""
     _check_dev(W, U, dead_mask, codes, scales, zeros, Wq, row_err2)
     m, n = W.shape
@@ -171,12 +173,21 @@ def ptq_quantize_layer(W: torch.Tensor, U: torch.Tensor, dead_mask: torch.Tensor
     assert Wq is None or (Wq.dtype == torch.float64 and Wq.is_contiguous() and Wq.shape == (m, n))
     assert row_err2 is None or (row_err2.dtype == torch.float64 and row_err2.numel() >= m)
     ws = _ws(ws, ptq_workspace_bytes(OP_QUANTIZE, m, n), W)
-    rc = load_library().ptq_quantize_layer(W.data_ptr(), _dtype_code(W), W.stride(0), m, n, U.data_ptr(),
-                                           U.stride(0), _ptr(dead_mask), bits, group, block,
-                                           codes.data_ptr(), scales.data_ptr(), zeros.data_ptr(), _ptr(Wq),
-                                           _ptr(row_err2), ws.data_ptr(), ws.numel(), _stream())
+    rc = getattr(load_library(), _entry)(W.data_ptr(), _dtype_code(W), W.stride(0), m, n, U.data_ptr(),
+                                         U.stride(0), _ptr(dead_mask), bits, group, block,
+                                         codes.data_ptr(), scales.data_ptr(), zeros.data_ptr(), _ptr(Wq),
+                                         _ptr(row_err2), ws.data_ptr(), ws.numel(), _stream())
     if rc:
-        raise PtqError(rc, "ptq_quantize_layer")
+        raise PtqError(rc, _entry)
+
+
+def ptq_quantize_layer_static_groups(W: torch.Tensor, U: torch.Tensor, dead_mask: torch.Tensor | None, bits: int,
+                                     group: int, block: int, codes: torch.Tensor, scales: torch.Tensor,
+                                     zeros: torch.Tensor, Wq: torch.Tensor | None = None,
+                                     row_err2: torch.Tensor | None = None, ws: torch.Tensor | None = None) -> None:
+    """The same solve with every group's grid taken from W as given, before any compensation."""
+    ptq_quantize_layer(W, U, dead_mask, bits, group, block, codes, scales, zeros, Wq, row_err2, ws,
+                       _entry="ptq_quantize_layer_static_groups")
 
 
 def ptq_layer_error(W: torch.Tensor, Wq: torch.Tensor, H: torch.Tensor, out: torch.Tensor,

@@ -99,7 +99,7 @@ size_t quantize_workspace_bytes(int64_t m, int64_t n);
 ptq_status quantize_launch(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m, int64_t n,
                            const double* U, int64_t ldu, const uint8_t* dead_mask, int bits, int group,
                            int block, uint8_t* codes, float* scales, uint8_t* zeros, double* Wq,
-                           double* row_err2, void* ws, size_t ws_bytes, hipStream_t s);
+                           double* row_err2, int static_groups, void* ws, size_t ws_bytes, hipStream_t s);
 
 size_t layer_error_workspace_bytes(int64_t m, int64_t n);
 ptq_status layer_error_launch(const void* W, ptq_dtype wdt, int64_t ldw, const double* Wq, int64_t m,

@@ -77,10 +77,10 @@ ptq_status ptq_damped_cholesky_inv(const double* H, int64_t ldh, int64_t n, doub
                          static_cast<hipStream_t>(stream));
 }
 
-ptq_status ptq_quantize_layer(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m, int64_t n,
-                              const double* U, int64_t ldu, const uint8_t* dead_mask, int bits, int group,
-                              int block, uint8_t* codes, float* scales, uint8_t* zeros, double* Wq,
-                              double* row_err2, void* ws, size_t ws_bytes, ptq_stream stream) {
+static ptq_status quantize_checked(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m, int64_t n, const double* U,
+                                   int64_t ldu, const uint8_t* dead_mask, int bits, int group, int block,
+                                   uint8_t* codes, float* scales, uint8_t* zeros, double* Wq, double* row_err2,
+                                   int static_groups, void* ws, size_t ws_bytes, ptq_stream stream) {
   if (bits < 2 || bits > 8) return PTQ_ERR_ARG;
   if (!dtype_ok(wdt)) return PTQ_ERR_DTYPE;
   if (m < 0 || n < 0 || ldw < n || ldu < n || m > INT32_MAX / 2 || n > INT32_MAX / 2) return PTQ_ERR_SHAPE;
@@ -93,7 +93,24 @@ ptq_status ptq_quantize_layer(const void* W, ptq_dtype wdt, int64_t ldw, int64_t
   if (!W || !U || !codes || !scales || !zeros) return PTQ_ERR_ARG;
   if (ws_bad(ws, ws_bytes, quantize_workspace_bytes(m, n))) return PTQ_ERR_WORKSPACE;
   return quantize_launch(W, wdt, ldw, m, n, U, ldu, dead_mask, bits, group, block, codes, scales, zeros,
-                         Wq, row_err2, ws, ws_bytes, static_cast<hipStream_t>(stream));
+                         Wq, row_err2, static_groups, ws, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+ptq_status ptq_quantize_layer(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m, int64_t n,
+                              const double* U, int64_t ldu, const uint8_t* dead_mask, int bits, int group,
+                              int block, uint8_t* codes, float* scales, uint8_t* zeros, double* Wq,
+                              double* row_err2, void* ws, size_t ws_bytes, ptq_stream stream) {
+  return quantize_checked(W, wdt, ldw, m, n, U, ldu, dead_mask, bits, group, block, codes, scales, zeros, Wq,
+                          row_err2, 0, ws, ws_bytes, stream);
+}
+
+ptq_status ptq_quantize_layer_static_groups(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m, int64_t n,
+                                            const double* U, int64_t ldu, const uint8_t* dead_mask, int bits,
+                                            int group, int block, uint8_t* codes, float* scales, uint8_t* zeros,
+                                            double* Wq, double* row_err2, void* ws, size_t ws_bytes,
+                                            ptq_stream stream) {
+  return quantize_checked(W, wdt, ldw, m, n, U, ldu, dead_mask, bits, group, block, codes, scales, zeros, Wq,
+                          row_err2, 1, ws, ws_bytes, stream);
 }
 
 ptq_status ptq_layer_error(const void* W, ptq_dtype wdt, int64_t ldw, const double* Wq, int64_t m,

@@ -44,6 +44,7 @@ struct QuantArgs {
   uint8_t* zeros;
   double* Wq;
   double* row_err2;
+  int static_groups;   // scales / zeros hold the grids already (taken from the given weights): use, do not derive
 };
 
 // NT = number of 16-column tiles the kernel is instantiated for (>= bw / 16).
@@ -188,7 +189,7 @@ __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
       for (int kk = 0; kk < 4; ++kk)
         ub[q][kk] = U[(int64_t)(gcol + 4 * kk + (lane >> 4)) * a.ldu + a.i1 + 16 * tc + (lane & 15)];
     }
-    if (gstart) {
+    if (gstart && !a.static_groups) {
       // min / max of the group's current values: 16 lanes per row (first four waves)
       if (tid < 256) {
         const int r = tid >> 4, sub = tid & 15;
@@ -213,7 +214,14 @@ __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
     if (tid < kRows) {
       const int r = tid;
       const bool rlive = row0 + r < a.m;
-      if (gstart) {
+      if (gstart && a.static_groups) {
+        const int64_t at = (int64_t)(rlive ? row0 + r : 0) * ng + gcol / a.group;
+        scale = (double)a.scales[at];
+        rscale = 1.0 / scale;
+        zero = (double)a.zeros[at];
+        klo = -zero;
+        khi = maxq - zero;
+      } else if (gstart) {
         double lo = gmin[r], hi = gmax[r];
         if (lo == hi) {
           lo = -1.0;
@@ -320,6 +328,32 @@ ptq_status run_blocks(QuantArgs a, int block, hipStream_t st) {
 
 }  // namespace
 
+// Static groups: the grid of every (row, group) from the weights as given (dead columns count as
+// zeros), by the same arithmetic as the column walk uses at a group start.  One thread each.
+template <int DT>
+__global__ __launch_bounds__(256) void static_grid_kernel(const void* __restrict__ W, int64_t ldw, int m, int n,
+                                                          const uint8_t* __restrict__ dead, int bits, int group,
+                                                          float* __restrict__ scales, uint8_t* __restrict__ zeros) {
+  const int ng = n / group;
+  const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (e >= (int64_t)m * ng) return;
+  const int r = (int)(e / ng), k = (int)(e - (int64_t)r * ng);
+  const double maxq = (double)((1 << bits) - 1);
+  double lo = 0.0, hi = 0.0;
+  for (int c = k * group; c < (k + 1) * group; ++c) {
+    const double v = (dead && dead[c]) ? 0.0 : load_as_f64<DT>(W, (int64_t)r * ldw + c);
+    lo = fmin(lo, v);
+    hi = fmax(hi, v);
+  }
+  if (lo == hi) {
+    lo = -1.0;
+    hi = 1.0;
+  }
+  const float sf = (float)((hi - lo) / maxq);
+  scales[e] = sf;
+  zeros[e] = (uint8_t)rint(-lo / (double)sf);
+}
+
 size_t quantize_workspace_bytes(int64_t m, int64_t n) {
   const int64_t mpad = ceil_div(m, kRows) * kRows;
   return align_up((size_t)n * (size_t)mpad * sizeof(double), 256) + align_up((size_t)n * sizeof(double), 256);
@@ -328,7 +362,7 @@ size_t quantize_workspace_bytes(int64_t m, int64_t n) {
 ptq_status quantize_launch(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m, int64_t n,
                            const double* U, int64_t ldu, const uint8_t* dead_mask, int bits, int group,
                            int block, uint8_t* codes, float* scales, uint8_t* zeros, double* Wq,
-                           double* row_err2, void* ws, size_t ws_bytes, hipStream_t st) {
+                           double* row_err2, int static_groups, void* ws, size_t ws_bytes, hipStream_t st) {
   if (m == 0 || n == 0) return PTQ_OK;
   if (ws_bytes < quantize_workspace_bytes(m, n)) return PTQ_ERR_WORKSPACE;
   // a group wider than the block makes the grid depend on columns beyond the
@@ -356,6 +390,16 @@ ptq_status quantize_launch(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m,
   a.zeros = zeros;
   a.Wq = Wq;
   a.row_err2 = row_err2;
+  a.static_groups = static_groups;
+  if (static_groups) {
+    const unsigned gg = (unsigned)ceil_div(m * (n / group), 256);
+    switch (wdt) {
+      case PTQ_F32: static_grid_kernel<PTQ_F32><<<gg, 256, 0, st>>>(W, ldw, (int)m, (int)n, dead_mask, bits, group, scales, zeros); break;
+      case PTQ_BF16: static_grid_kernel<PTQ_BF16><<<gg, 256, 0, st>>>(W, ldw, (int)m, (int)n, dead_mask, bits, group, scales, zeros); break;
+      case PTQ_F64: static_grid_kernel<PTQ_F64><<<gg, 256, 0, st>>>(W, ldw, (int)m, (int)n, dead_mask, bits, group, scales, zeros); break;
+      default: return PTQ_ERR_DTYPE;
+    }
+  }
   inv_diag_kernel<<<(unsigned)ceil_div(n, 256), 256, 0, st>>>(U, ldu, (int)n, const_cast<double*>(a.invd));
   PTQ_HIP_CHECK_LAUNCH();
   ptq_status rc;

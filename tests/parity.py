@@ -64,11 +64,11 @@ def _alt_round(x):
 
 
 def compare_quantization(W64, U, bits, group, dead, g_codes, g_scales, g_zeros, tol=1e-5,
-                         max_forced_per_row=64):
+                         max_forced_per_row=64, static_groups=False):
     """Runs the protocol over all rows of W64.  Returns a report dict."""
     maxq = float(2 ** bits - 1)
     m, n = W64.shape
-    base = orc.quantize_layer(W64, U, bits, group, dead=dead, want_pre=True)
+    base = orc.quantize_layer(W64, U, bits, group, dead=dead, want_pre=True, static_groups=static_groups)
     rep = dict(rows=m, exact_rows=0, flagged_codes=0, flagged_zeros=0, flagged_scales=0,
                unflagged=0, max_scale_margin_ulp=0.0, details=[], oracle=base)
     for r in range(m):
@@ -117,7 +117,8 @@ def compare_quantization(W64, U, bits, group, dead, g_codes, g_scales, g_zeros, 
                 rep["details"].append((r, kind, idx))
                 break
             forced[(kind, 0, idx)] = val
-            cur = orc.quantize_layer(W64[r:r + 1], U, bits, group, dead=dead, forced=forced, want_pre=True)
+            cur = orc.quantize_layer(W64[r:r + 1], U, bits, group, dead=dead, forced=forced, want_pre=True,
+                                     static_groups=static_groups)
         else:
             rep["unflagged"] += 1
             rep["details"].append((r, "too many forced decisions", -1))

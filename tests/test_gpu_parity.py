@@ -44,7 +44,7 @@ def _gpu_factor(H_np, damp, n=None):
     return U.cpu().numpy(), dead.cpu().numpy().astype(bool), info.cpu().numpy()
 
 
-def _gpu_quantize(Ws, U_np, bits, group, block, dead=None, want_wq=True):
+def _gpu_quantize(Ws, U_np, bits, group, block, dead=None, want_wq=True, static_groups=False):
     W = to_device(Ws)
     m, n = W.shape
     U = torch.from_numpy(np.ascontiguousarray(U_np)).cuda()
@@ -54,7 +54,8 @@ def _gpu_quantize(Ws, U_np, bits, group, block, dead=None, want_wq=True):
     Wq = torch.full((m, n), float("nan"), dtype=torch.float64, device="cuda") if want_wq else None
     err2 = torch.full((m,), float("nan"), dtype=torch.float64, device="cuda")
     dm = None if dead is None else torch.from_numpy(dead.astype(np.uint8)).cuda()
-    ptq.ptq_quantize_layer(W, U, dm, bits, group, block, codes, scales, zeros, Wq, err2)
+    solve = ptq.ptq_quantize_layer_static_groups if static_groups else ptq.ptq_quantize_layer
+    solve(W, U, dm, bits, group, block, codes, scales, zeros, Wq, err2)
     torch.cuda.synchronize()
     return dict(codes=codes.cpu().numpy(), scales=scales.cpu().numpy(), zeros=zeros.cpu().numpy(),
                 Wq=None if Wq is None else Wq.cpu().numpy(), row_err2=err2.cpu().numpy())
@@ -210,6 +211,29 @@ def test_quantize_matches_oracle(case, correlated):
         assert np.allclose(g["Wq"], o["Wq"], rtol=0, atol=0)
         assert np.allclose(g["row_err2"], o["row_err2"], rtol=1e-9, atol=1e-30)
     assert np.array_equal(g["Wq"], orc.dequantize(g["codes"], g["scales"], g["zeros"], group))
+
+
+@pytest.mark.parametrize("case", [CASES[1], CASES[2], CASES[4], CASES[5]], ids=lambda c: c[0])
+def test_quantize_with_static_groups_matches_oracle(case):
+    """Every group's grid from the weights as given: same protocol as the ordinary solve."""
+    name, dtype, m, n, t, bits, group, block = case
+    Ws, X = _layer(name, dtype, m, n, t, True, 800 + len(name))
+    U = orc.inverse_cholesky_upper(orc.damp(orc.hessian(X), 0.01)[0])
+    dead = np.zeros(n, dtype=bool)
+    dead[[3, n // 2]] = True          # dead columns count as zeros in the grids too
+    g = _gpu_quantize(Ws, U, bits, group, block, dead=dead, static_groups=True)
+    W64 = wl.to_f64(Ws)
+    rep = compare_quantization(W64, U, bits, group, dead, g["codes"], g["scales"], g["zeros"], static_groups=True)
+    assert rep["unflagged"] == 0, rep["details"][:5]
+    assert rep["flagged_codes"] + rep["flagged_zeros"] + rep["flagged_scales"] <= 2
+    # the grids are those of round-to-nearest on the given weights, whatever the Hessian did to the codes
+    Wz = W64.copy()
+    Wz[:, dead] = 0.0
+    rtn = orc.round_to_nearest(Wz, bits, group)
+    assert np.array_equal(g["scales"], rtn["scales"]) and np.array_equal(g["zeros"], rtn["zeros"])
+    assert np.array_equal(g["Wq"], orc.dequantize(g["codes"], g["scales"], g["zeros"], group))
+    dyn = _gpu_quantize(Ws, U, bits, group, block, dead=dead)
+    assert not np.array_equal(dyn["scales"], g["scales"])
 
 
 def test_quantize_block_size_changes_nothing():
