@@ -11,17 +11,30 @@ LLAMA2_7B = [(4096, 4096)] * 4 + [(11008, 4096)] * 2 + [(4096, 11008)]
 LLAMA2_13B = [(5120, 5120)] * 4 + [(13824, 5120)] * 2 + [(5120, 13824)]
 
 
+def _printed_bit_widths():
+    """tests/golden/average_bits.txt: the values the paper prints, with where it prints them."""
+    import os
+    rows = []
+    with open(os.path.join(os.path.dirname(__file__), "golden", "average_bits.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                model, bits, what, value = line.split()
+                rows.append((model, int(bits), what, float(value)))
+    return rows
+
+
 def test_eq12_reproduces_the_papers_bit_widths():
-    # the average-bit appendix: rank 16, fp8 factors cost "approximately 0.05 bits" on a 7B model and
-    # "0.04 bits" on a 13B model -- the two low-rank terms of Eq. 12, averaged over the linear layers
-    for shapes, want in ((LLAMA2_7B, 0.05), (LLAMA2_13B, 0.04)):
-        low_rank = (ao.model_average_bits(shapes, 2, 16, 128, 16, 8, terms=4)
-                    - ao.model_average_bits(shapes, 2, 16, 128, 16, 8, terms=2))
-        assert round(low_rank, 2) == want
-    # the result tables list LoPRo at 2.17 and 3.17 bits (group 128, 16-bit scales, rank 16, fp8):
-    # Eq. 12 without the two terms the paper calls negligible
-    assert round(ao.model_average_bits(LLAMA2_7B, 2, 16, 128, 16, 8, terms=4), 2) == 2.17
-    assert round(ao.model_average_bits(LLAMA2_7B, 3, 16, 128, 16, 8, terms=4), 2) == 3.17
+    shapes = {"llama2-7b": LLAMA2_7B, "llama2-13b": LLAMA2_13B}
+    rows = _printed_bit_widths()
+    assert len(rows) == 4
+    for model, bits, what, want in rows:
+        # rank 16, fp8 factors, group 128, 16-bit scales; "terms=4" is Eq. 12 without the two terms the
+        # paper calls negligible, "terms=2" without the low-rank terms as well
+        full = ao.model_average_bits(shapes[model], bits, 16, 128, 16, 8, terms=4)
+        if what == "low_rank":
+            assert round(full - ao.model_average_bits(shapes[model], bits, 16, 128, 16, 8, terms=2), 2) == want
+        else:
+            assert round(full, 2) == want
     # and those two terms are indeed small: under a hundredth of a bit
     assert ao.model_average_bits(LLAMA2_7B, 2, 16, 128, 16, 8) - ao.model_average_bits(
         LLAMA2_7B, 2, 16, 128, 16, 8, terms=4) < 0.01
