@@ -4,7 +4,9 @@
 A step is one pass of the whole hot path over one synthetic layer:
 Hessian accumulation -> damped Cholesky factor of the inverse -> blocked
 column quantization -> layer error, with all inputs resident in HBM.
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: metric / value / unit (columns quantized per second for the whole step),
+ms_per_step and the per-call times, the Hessian rate, a "roofline" object for the dominant
+kernel and a "cpu_baseline" object (the oracle timed on a sample of the same layer).
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C2] [--no-cpu-baseline]
 """
