@@ -157,10 +157,11 @@ def test_forward_without_rotation_or_low_rank_is_a_plain_dequantized_product():
     assert np.allclose(got, ref, rtol=0, atol=_gamma(n) * np.max(np.abs(ref)) * 100)
 
 
-def test_forward_full_size_attention_projection(capsys):
+@pytest.mark.parametrize("tokens", [4, 45])   # 45 = a matrix-core pass of 32, one of 13: both kernels at full size
+def test_forward_full_size_attention_projection(tokens):
     rng = np.random.default_rng(99)
     m = n = 4096
-    bits, group, bI, bH, r, tokens = 3, 128, 256, 256, 16, 4
+    bits, group, bI, bH, r = 3, 128, 256, 256, 16
     layer = _random_layer(rng, m, n, r, bits, group)
     X_t = _dev(rng.standard_normal((tokens, n)).astype(np.float32)).to(torch.bfloat16)
     got, packed = _forward(X_t, *layer, bits, group, bI, bH)
