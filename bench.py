@@ -70,6 +70,36 @@ def cpu_baseline(cfg, spec, seed):
     }
 
 
+def single_block_us_per_column(ptq, bits, group, reps=30):
+    """Time per column of the column walk where the call holds nothing else: 16 rows (one workgroup)
+    and a layer that is a single block, so that there is no lazy update; a 256-column call minus a
+    128-column call removes the launch.  It contains the walk, the in-block pushes and the block's
+    set-up and outputs, so it is an upper estimate of the walk's share.  Microseconds per column."""
+    import torch
+    gen = torch.Generator(device="cuda").manual_seed(7)
+    times = {}
+    for n in (128, 256):
+        W = torch.randn((16, n), device="cuda", generator=gen) * 0.02
+        U = torch.triu(torch.randn((n, n), dtype=torch.float64, device="cuda", generator=gen) * 0.01, 1)
+        U += torch.eye(n, dtype=torch.float64, device="cuda")
+        g = min(group, n)
+        codes = torch.empty((16, n), dtype=torch.uint8, device="cuda")
+        scales = torch.empty((16, n // g), dtype=torch.float32, device="cuda")
+        zeros = torch.empty((16, n // g), dtype=torch.uint8, device="cuda")
+        ws = torch.empty(max(256, ptq.ptq_workspace_bytes(2, 16, n, 0, n)), dtype=torch.uint8, device="cuda")
+        runs = []
+        for k in range(reps + 3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            ptq.ptq_quantize_layer(W, U, None, bits, g, n, codes, scales, zeros, None, None, ws)
+            e1.record()
+            torch.cuda.synchronize()
+            if k >= 3:
+                runs.append(e0.elapsed_time(e1))
+        times[n] = sorted(runs)[len(runs) // 2]
+    return 1e3 * (times[256] - times[128]) / 128.0
+
+
 def lopro_timings(ptq, W, H, m, n, ws, b_I=256, b_H=256, reps=10):
     """LoPRo's pre-conditioning kernels on the benchmark layer: all memory-bound; GB/s are algorithmic
     bytes (each operand read once, each result written once) over the event-bracketed call."""
@@ -350,6 +380,9 @@ def main():
         "solve_columns_per_s": n / ((f_ms + q_ms) * 1e-3),
         "quantize_columns_per_s": n / (q_ms * 1e-3),
         "quantize_tflops_f64": float(m) * n * n / (q_ms * 1e-3) / 1e12,
+        # W in, codes + Wq out, the upper triangle of U, the grids: what the column walk has to move
+        "quantize_algorithmic_gbps": (float(m) * n * (W.element_size() + 1 + 8) + 4.0 * n * n
+                                      + 5.0 * m * n / cfg.group) / (q_ms * 1e-3) / 1e9,
         "rel_layer_error": rel,
         "roofline": {
             "kernel": "ptq_hessian_accumulate (Hessian MFMA kernel + partial-tile reduction)",
@@ -359,6 +392,13 @@ def main():
             "algorithmic_flops_per_launch": syrk_flops, "algorithmic_bytes_per_launch": 2.0 * t * n,
         },
     }
+    # the solve against its floors (bytes at the HBM rate, flops at the float64 peak), and what its
+    # serial part costs: n columns at the per-column time of a call that is nothing but the walk
+    q_bytes = float(m) * n * (W.element_size() + 1 + 8) + 4.0 * n * n + 5.0 * m * n / cfg.group
+    t_col_us = single_block_us_per_column(ptq, cfg.bits, cfg.group)
+    floors = {"hbm_ms": q_bytes / (HBM_GBPS * 1e9) * 1e3, "f64_ms": float(m) * n * n / (PEAK_F64_TFLOPS * 1e12) * 1e3}
+    result["quantize_floors"] = dict(floors, frac_of_largest_floor=max(floors.values()) / q_ms,
+                                     single_block_us_per_column=t_col_us, walk_ms_upper_estimate=n * t_col_us * 1e-3)
     if args.lopro:
         result["lopro"] = lopro_timings(ptq, W, H, m, n, ws)
     if args.r1svd:

@@ -361,7 +361,8 @@ ptq_status ptq_unpack_dequantize(const uint32_t* packed, int64_t m, int64_t n, i
  *        ptq_scaled_r1svd; r = 0 applies the residual alone (U, V, sigma, s may be NULL).
  * X~ and the low-rank coefficients are formed in float64 and rounded to float32; the products
  * with the codes accumulate in float32.  tokens <= 4096 (meant for a handful: the call reads
- * the packed codes once per four tokens).
+ * the packed codes once per pass, and a pass takes up to 32 tokens when there are eight or
+ * more of them, up to four otherwise).
  * Workspace: PTQ_OP_LINEAR_FORWARD with m, n, t = tokens and block = r.
  */
 ptq_status ptq_lopro_linear_forward(const void* X, ptq_dtype xdt, int64_t ldx, int64_t tokens, int64_t m,

@@ -66,7 +66,8 @@ __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
   double* P = lds;                                  // [4][16][bw]
   double* S = lds;                                  // [16][bw + 1]   (aliases P)
   double* Em = lds + 4 * kRows * a.bw;              // [16 k][16 rows]
-  double* Ud = Em + 256;                            // [2][16][16]
+  double* Qm = Em + 256;                            // [16 k][17]: the mini-block's dequantized values
+  double* Ud = Qm + 272;                            // [2][16][16]
   double* Id = Ud + 512;                            // [2][16]
   double* gmin = Id + 32;                           // [16]
   double* gmax = gmin + 16;                         // [16]
@@ -238,13 +239,32 @@ __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
           a.zeros[(int64_t)(row0 + r) * ng + gcol / a.group] = (uint8_t)zero;
         }
       }
-      double w[16];
+      // The walk is one dependent chain of float64 operations per column; everything that does not
+      // depend on it is taken out of its way: the reciprocal pivots and the entries of U that carry
+      // a column's error to the very next column sit in registers before it starts; the error's
+      // effect on the columns further on is applied one step later, next to the following column's
+      // chain, as independent operations that fill its latency (left to itself the compiler gathers
+      // them in front of each column as one more chain; the scheduling barrier keeps a step's
+      // instructions in their step); and the results go to LDS only -- other waves write them out.
+      double w[16], idr[16], sd[15], rp[16], rc[16];
+      const double* ud = Ud + buf * 256;
 #pragma unroll
       for (int j = 0; j < 16; ++j) w[j] = S[r * sp + c0 + j];
-      const double* ud = Ud + buf * 256;
-      const double* id = Id + buf * 16;
+#pragma unroll
+      for (int j = 0; j < 16; ++j) idr[j] = Id[buf * 16 + j];
+#pragma unroll
+      for (int j = 0; j < 15; ++j) sd[j] = ud[j * 16 + j + 1];
+      double ep = 0.0;
 #pragma unroll
       for (int j = 0; j < 16; ++j) {
+        // the rest of row j of U, for the next step
+#pragma unroll
+        for (int c = j + 2; c < 16; ++c) rc[c] = ud[j * 16 + c];
+        // column j - 1 onto the columns after this one: nothing below waits for these
+        if (j > 0) {
+#pragma unroll
+          for (int c = j + 1; c < 16; ++c) w[c] = fma(-ep, rp[c], w[c]);
+        }
         // x = w / scale, correctly rounded from the reciprocal (one Newton step
         // on the quotient), so that exact ties round as a true division would
         const double q0 = w[j] * rscale;
@@ -253,14 +273,16 @@ __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
         // k = code - zero, clamped; scale * k is exact (24-bit x 9-bit), so one
         // fma gives w - q with the same single rounding as the subtraction
         const double k = fmin(fmax(rint(x), klo), khi);
-        const double e = fma(-scale, k, w[j]) * id[j];
-#pragma unroll
-        for (int c = j + 1; c < 16; ++c) w[c] = fma(-e, ud[j * 16 + c], w[c]);
+        const double e = fma(-scale, k, w[j]) * idr[j];
+        if (j < 15) w[j + 1] = fma(-e, sd[j], w[j + 1]);
         err2 = fma(e, e, err2);
         Ct[r * a.bw + c0 + j] = (uint8_t)(k + zero);
         Em[j * kRows + r] = e;
-        a.errT[(int64_t)(gcol + j) * a.mpad + row0 + r] = e;
-        if (a.Wq && rlive) a.Wq[(int64_t)(row0 + r) * a.n + gcol + j] = scale * k;
+        Qm[j * 17 + r] = scale * k;
+        ep = e;
+#pragma unroll
+        for (int c = j + 2; c < 16; ++c) rp[c] = rc[c];
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
     __syncthreads();
@@ -275,9 +297,20 @@ __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
           const double av = Em[(4 * kk + (lane >> 4)) * kRows + (lane & 15)];
           d = __builtin_amdgcn_mfma_f64_16x16x4f64(av, ub[q][kk], d, 0, 0, 0);
         }
+        double sv[4];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) S[(4 * r + (lane >> 4)) * sp + 16 * t + (lane & 15)] -= d[r];
+        for (int r = 0; r < 4; ++r) sv[r] = S[(4 * r + (lane >> 4)) * sp + 16 * t + (lane & 15)];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) S[(4 * r + (lane >> 4)) * sp + 16 * t + (lane & 15)] = sv[r] - d[r];
       }
+    }
+    // the mini-block's errors (for the later blocks) and dequantized values leave through the
+    // upper four waves, 128 contiguous bytes per 16 lanes
+    if (tid >= 256) {
+      const int e = tid - 256;
+      a.errT[(int64_t)(gcol + (e >> 4)) * a.mpad + row0 + (e & 15)] = Em[e];
+      const int r = e >> 4, j = e & 15;
+      if (a.Wq && row0 + r < a.m) a.Wq[(int64_t)(row0 + r) * a.n + gcol + j] = Qm[j * 17 + r];
     }
     if (mb + 1 < nt) {
       if (tid < 256) Ud[(buf ^ 1) * 256 + tid] = ud_next;
@@ -300,7 +333,7 @@ __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
 }
 
 size_t block_lds_bytes(int bw) {
-  return (size_t)(4 * kRows * bw + 256 + 512 + 32 + 32) * sizeof(double) + (size_t)kRows * bw;
+  return (size_t)(4 * kRows * bw + 256 + 272 + 512 + 32 + 32) * sizeof(double) + (size_t)kRows * bw;
 }
 
 template <int DT, int NT>
