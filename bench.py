@@ -370,7 +370,7 @@ def main():
         "metric": "layer-solve columns quantized/sec + Hessian TFLOP/s (% MFMA peak), 1 GPU",
         "value": n / (ms * 1e-3), "unit": "columns/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16,f64" if spec.dtype == "bf16" else "f64", "data": "synthetic (device-drawn activations)" if args.device_x else "synthetic",
+        "vs_baseline": None, "dtype": "bf16,f32,f64" if spec.dtype == "bf16" else "f32,f64", "data": "synthetic (device-drawn activations)" if args.device_x else "synthetic",
         "config": {"workload": f"{args.config}:{spec.name} W {m}x{n} {spec.dtype}, X {t}x{n} {spec.dtype}, "
                                f"{cfg.bits}-bit asym group {cfg.group} block {cfg.block} damp {damp}"},
         "phases_ms": {"hessian": h_ms, "factor": f_ms, "quantize": q_ms, "layer_error": e_ms},

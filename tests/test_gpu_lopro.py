@@ -144,8 +144,9 @@ def test_solve_in_the_rotated_basis_end_to_end():
     ptq.ptq_layer_error(Rr, Wq, Hr, e_rot)
     ptq.ptq_layer_error(Wd, back, Hd, e_orig)
     assert info.cpu().tolist() == [0, 0]
-    # Eq. 8: the same loss in either basis
-    assert abs(float(e_rot[0]) - float(e_orig[0])) <= 1e-9
+    # Eq. 8: the same loss in either basis (the rotated operands are float64, the layer's own weights
+    # are stored narrower and take the float32 form of the sum)
+    assert abs(float(e_rot[0]) - float(e_orig[0])) <= 1e-7
     # stage-wise parity of the solve on the rotated operands (the oracle is fed the GPU's R' and U)
     rep = compare_quantization(Rr.cpu().numpy(), U.cpu().numpy(), bits, group, None, codes.cpu().numpy(),
                                scales.cpu().numpy(), zeros.cpu().numpy())
