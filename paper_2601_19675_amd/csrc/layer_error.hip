@@ -9,12 +9,15 @@
 // single-workgroup kernel adds the tile sums in index order.
 //
 // Two forms of the same sum.  Weights stored in float64 take the float64 MFMA GEMM.  Weights
-// stored in float32 or bfloat16 take the float32 one: D, W and Hu are rounded to float32 once
-// (W in bfloat16 is exact), products and the running sums over k are float32 on the matrix
-// cores, and everything from the tile's sum_ij A_ij T_ij on is float64.  The roundings are
-// unbiased and independent, so they average out over the m n terms of the trace: measured
-// against the float64 definition the two traces differ by a few parts in 10^8.
+// stored in float32 or bfloat16 take the bfloat16-split one: D, W and Hu are rounded to float32
+// once (W in bfloat16 is exact) and kept as three bfloat16 pieces each, the piece products and
+// the running sums over k are float32 on the matrix cores, and everything from the tile's
+// sum_ij A_ij T_ij on is float64.  The roundings are unbiased and independent, so they average
+// out over the m n terms of the trace: measured against the float64 definition the two traces
+// differ by a few parts in 10^9.
 #include "dgemm.h"
+
+#include <type_traits>
 
 namespace ptq {
 namespace {
@@ -79,89 +82,130 @@ __global__ __launch_bounds__(256, 3) void quad_form_kernel(ErrArgs a) {   // thr
     a.partial[((int64_t)z * nrt + rt) * gridDim.y + ct] = red[0];
 }
 
-// ---------------------------------------------------------------- float32 matrix-core form
-constexpr int kT = 128;          // tile edge: four waves, 64 x 64 each (2 x 2 tiles of the 32 x 32 x 2 MFMA)
-constexpr int kBK = 16;          // k-tile
-constexpr int kPitch = kT + 32;  // LDS pitch: the two k rows of a fragment read fall on the two bank halves
+// ---------------------------------------------------------------- bfloat16-split form
+constexpr int kT = 128;         // tile edge: four waves, 64 x 64 each (2 x 2 tiles of the 32 x 32 x 16 MFMA)
 
-struct Err32Args {
-  const float* A32;  // [2][mp][np]: D = W - Wq, then W; zero outside m x n
-  const float* Hu;   // [np][np]: Hu; zero below the diagonal and outside n x n
-  int mp, np;        // m, n rounded up to the tile edge
-  double* partial;   // [2][tiles]
+// A float32 number is exactly the sum of three bfloat16 numbers (8 + 8 + 8 significant bits, each
+// remainder taken after rounding to nearest), and the product of two bfloat16 numbers is exact in
+// float32.  So A Hu in float32 is the sum of the piece products A_a Hu_b; the six with a + b <= 2
+// carry everything down to 2^-24 of a term, the other three are below the rounding of a float32
+// product.  They run on the bfloat16 32 x 32 x 16 MFMA (sixteen times the float32 rate per
+// instruction), accumulate in float32, smallest pieces first.  W stored in bfloat16 is one piece.
+constexpr int kSK = 32;        // k-tile of the split form
+constexpr int kSP = kSK + 8;   // LDS pitch in elements: 80-byte rows keep the 16-byte fragment reads apart
+
+__device__ __forceinline__ uint16_t bf16_rne(float x) {
+  uint32_t u = __float_as_uint(x);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float bf16_val(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+__device__ __forceinline__ void split3(float x, uint16_t (&p)[3]) {
+  p[0] = bf16_rne(x);
+  float r = x - bf16_val(p[0]);
+  p[1] = bf16_rne(r);
+  r -= bf16_val(p[1]);
+  p[2] = bf16_rne(r);
+}
+
+struct SplitArgs {
+  const uint16_t* A;   // [pieces][mp][np]: D = W - Wq or W as bfloat16 pieces; zero outside m x n
+  const uint16_t* HuT; // [3][np (j)][np (k)]: Hu transposed, as pieces; zero for k > j and outside n x n
+  int mp, np;
+  double* partial;     // [tiles] of this quadratic form
 };
 
+// D and W as bfloat16 pieces, four consecutive k per thread
 template <int DT>
-__global__ __launch_bounds__(256) void narrow_kernel(const void* __restrict__ W, int64_t ldw,
-                                                     const double* __restrict__ Wq, int m, int n, int mp, int np,
-                                                     float* __restrict__ A32) {
-  const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;   // four consecutive k
+__global__ __launch_bounds__(256) void split_weights_kernel(const void* __restrict__ W, int64_t ldw,
+                                                            const double* __restrict__ Wq, int m, int n, int mp, int np,
+                                                            uint16_t* __restrict__ Dp, uint16_t* __restrict__ Wp) {
+  const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (q >= (int64_t)mp * np / 4) return;
   const int i = (int)(q / (np / 4)), k0 = (int)(q - (int64_t)i * (np / 4)) * 4;
-  float d[4], w[4];
+  uint16_t d[4][3], w[4][3];
 #pragma unroll
   for (int c = 0; c < 4; ++c) {
     const bool ok = i < m && k0 + c < n;
     const double wv = ok ? load_as_f64<DT>(W, (int64_t)i * ldw + k0 + c) : 0.0;
     const double qv = ok ? Wq[(int64_t)i * n + k0 + c] : 0.0;
-    d[c] = (float)(wv - qv);
-    w[c] = (float)wv;
+    split3((float)(wv - qv), d[c]);
+    split3((float)wv, w[c]);
   }
-  float* o = A32 + (int64_t)i * np + k0;
-  *reinterpret_cast<float4*>(o) = float4{d[0], d[1], d[2], d[3]};
-  *reinterpret_cast<float4*>(o + (int64_t)mp * np) = float4{w[0], w[1], w[2], w[3]};
+  const int64_t plane = (int64_t)mp * np, at = (int64_t)i * np + k0;
+#pragma unroll
+  for (int p = 0; p < 3; ++p) {
+    *reinterpret_cast<ushort4*>(Dp + p * plane + at) = ushort4{d[0][p], d[1][p], d[2][p], d[3][p]};
+    if (DT != PTQ_BF16 || p == 0)
+      *reinterpret_cast<ushort4*>(Wp + p * plane + at) = ushort4{w[0][p], w[1][p], w[2][p], w[3][p]};
+  }
 }
 
-__global__ __launch_bounds__(256) void hu_kernel(const double* __restrict__ H, int64_t ldh, int n, int np,
-                                                 float* __restrict__ Hu) {
-  const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;   // four consecutive j
-  if (q >= (int64_t)np * np / 4) return;
-  const int k = (int)(q / (np / 4)), j0 = (int)(q - (int64_t)k * (np / 4)) * 4;
-  float v[4];
+// Hu transposed, as pieces: 32 x 32 tiles through LDS so that both the reads of H and the writes run along rows
+__global__ __launch_bounds__(256) void split_hu_kernel(const double* __restrict__ H, int64_t ldh, int n, int np,
+                                                       uint16_t* __restrict__ HuT) {
+  __shared__ uint16_t t[3][32][33];
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  const int j0 = blockIdx.x * 32, k0 = blockIdx.y * 32;
 #pragma unroll
-  for (int c = 0; c < 4; ++c) {
-    const int j = j0 + c;
+  for (int rr = 0; rr < 4; ++rr) {
+    const int k = k0 + ty + 8 * rr, j = j0 + tx;
     const bool ok = k < n && j < n && k <= j;
     const double h = ok ? H[(int64_t)k * ldh + j] : 0.0;
-    v[c] = (float)(k == j ? h : 2.0 * h);
+    uint16_t p[3];
+    split3((float)(k == j ? h : 2.0 * h), p);
+#pragma unroll
+    for (int q = 0; q < 3; ++q) t[q][ty + 8 * rr][tx] = p[q];
   }
-  *reinterpret_cast<float4*>(Hu + (int64_t)k * np + j0) = float4{v[0], v[1], v[2], v[3]};
+  __syncthreads();
+  const int64_t plane = (int64_t)np * np;
+#pragma unroll
+  for (int rr = 0; rr < 4; ++rr) {
+    const int j = j0 + ty + 8 * rr, k = k0 + tx;
+#pragma unroll
+    for (int q = 0; q < 3; ++q) HuT[q * plane + (int64_t)j * np + k] = t[q][tx][ty + 8 * rr];
+  }
 }
 
-__global__ __launch_bounds__(256, 2) void quad_form32_kernel(Err32Args a) {
-  __shared__ float As[2][kBK][kPitch];   // [stage][k][i]
-  __shared__ float Bs[2][kBK][kPitch];   // [stage][k][j]
+template <int NA>
+__global__ __launch_bounds__(256) void quad_form_split_kernel(SplitArgs a) {
+  extern __shared__ uint16_t sm[];   // [2 stages][NA + 3 pieces][128 rows][kSP]
   __shared__ double red[4];
-  // column tiles have k ranges proportional to their index: the widest are dispatched first
-  // (blockIdx.y is the slow grid index), the two quadratic forms share blockIdx.x
-  const int nrt = gridDim.x >> 1;
-  const int z = blockIdx.x / nrt;
-  const int rt = blockIdx.x - z * nrt;
-  const int ct = gridDim.y - 1 - blockIdx.y;
+  constexpr int NP = NA + 3;
+  constexpr int kPiece = kT * kSP, kStage = NP * kPiece;
+  // the widest column tiles first (blockIdx.y is the slow grid index)
+  const int rt = blockIdx.x, ct = gridDim.y - 1 - blockIdx.y;
   const int i0 = rt * kT, j0 = ct * kT;
-  const int kend = j0 + kT;   // below it Hu is zero; a multiple of the k-tile
-  const float* __restrict__ A = a.A32 + ((int64_t)z * a.mp + i0) * a.np;
-  const float* __restrict__ B = a.Hu + j0;
+  const int kend = j0 + kT;   // beyond it Hu is zero; a multiple of the k-tile
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
+  const int64_t planeA = (int64_t)a.mp * a.np, planeB = (int64_t)a.np * a.np;
 
-  // global -> registers -> LDS: a thread brings 8 consecutive k of one row of A and 8 consecutive j of one row of Hu
-  const int ar = tid >> 1, ak = (tid & 1) * 8;
-  const int bk = tid >> 4, bj = (tid & 15) * 8;
-  const float* ap = A + (int64_t)ar * a.np + ak;
-  const float* bp = B + (int64_t)bk * a.np + bj;
-  float4 ra0, ra1, rb0, rb1;
-  auto fetch = [&](int k0) {
-    ra0 = *reinterpret_cast<const float4*>(ap + k0);
-    ra1 = *reinterpret_cast<const float4*>(ap + k0 + 4);
-    rb0 = *reinterpret_cast<const float4*>(bp + (int64_t)k0 * a.np);
-    rb1 = *reinterpret_cast<const float4*>(bp + (int64_t)k0 * a.np + 4);
+  // a piece's 128 x 32 tile is 512 chunks of 16 bytes: two per thread.  Two register sets: a tile's
+  // loads are issued three k-tiles ahead and have two whole k-tiles of MFMAs to arrive (one k-tile
+  // of the bfloat16 MFMA is too short to cover the latency of a load from L2)
+  const int lr = tid >> 2, lk = (tid & 3) * 8;
+  const uint16_t* ga = a.A + (int64_t)(i0 + lr) * a.np + lk;
+  const uint16_t* gb = a.HuT + (int64_t)(j0 + lr) * a.np + lk;
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // a native vector: stays in registers
+  u32x4 reg[2][NP][2];
+  auto fetch = [&](auto set, int k0) {
+    constexpr int S = decltype(set)::value;
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+      const uint16_t* g = p < NA ? ga + p * planeA : gb + (p - NA) * planeB;
+      reg[S][p][0] = *reinterpret_cast<const u32x4*>(g + k0);
+      reg[S][p][1] = *reinterpret_cast<const u32x4*>(g + (int64_t)64 * a.np + k0);
+    }
   };
-  auto stash = [&](int s) {
-    As[s][ak + 0][ar] = ra0.x; As[s][ak + 1][ar] = ra0.y; As[s][ak + 2][ar] = ra0.z; As[s][ak + 3][ar] = ra0.w;
-    As[s][ak + 4][ar] = ra1.x; As[s][ak + 5][ar] = ra1.y; As[s][ak + 6][ar] = ra1.z; As[s][ak + 7][ar] = ra1.w;
-    *reinterpret_cast<float4*>(&Bs[s][bk][bj]) = rb0;
-    *reinterpret_cast<float4*>(&Bs[s][bk][bj + 4]) = rb1;
+  auto stash = [&](auto set, int stage) {
+    constexpr int S = decltype(set)::value;
+    uint16_t* st = sm + stage * kStage;
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+      *reinterpret_cast<u32x4*>(st + p * kPiece + lr * kSP + lk) = reg[S][p][0];
+      *reinterpret_cast<u32x4*>(st + p * kPiece + (lr + 64) * kSP + lk) = reg[S][p][1];
+    }
   };
 
   f32x16 acc[2][2];
@@ -172,33 +216,57 @@ __global__ __launch_bounds__(256, 2) void quad_form32_kernel(Err32Args a) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[tm][tn][r] = 0.f;
 
-  fetch(0);
-  stash(0);
-  if (kBK < kend) fetch(kBK);
-  __syncthreads();
-  int cur = 0;
-  for (int k0 = 0; k0 < kend; k0 += kBK) {
-    // next k-tile: registers -> the other stage; the one after: issue its loads
-    if (k0 + kBK < kend) stash(cur ^ 1);
-    if (k0 + 2 * kBK < kend) fetch(k0 + 2 * kBK);
-    // operand fragments: lane l holds A(i = l % 32, k = l / 32) and B(k = l / 32, j = l % 32)
+  // the products of the k-tile in LDS stage `stage`
+  auto products = [&](int stage) {
+    const uint16_t* st = sm + stage * kStage;
+    // fragment of a 32-row strip: lane l holds row l % 32, k = 8 (l / 32) .. + 7 of the 16-wide k-step
 #pragma unroll
-    for (int ks = 0; ks < kBK / 2; ++ks) {
-      const int kr = 2 * ks + (lane >> 5);
-      float av[2], bv[2];
+    for (int ks = 0; ks < kSK / 16; ++ks) {
+      bf16x8 fa[NA][2], fb[3][2];
+      const int fo = (lane & 31) * kSP + ks * 16 + (lane >> 5) * 8;
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
-        av[t] = As[cur][kr][wm * 64 + t * 32 + (lane & 31)];
-        bv[t] = Bs[cur][kr][wn * 64 + t * 32 + (lane & 31)];
+#pragma unroll
+        for (int p = 0; p < NA; ++p)
+          fa[p][t] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(st + p * kPiece + (wm * 64 + t * 32) * kSP + fo));
+#pragma unroll
+        for (int p = 0; p < 3; ++p)
+          fb[p][t] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(st + (NA + p) * kPiece + (wn * 64 + t * 32) * kSP + fo));
       }
 #pragma unroll
-      for (int tm = 0; tm < 2; ++tm)
+      for (int order = 2; order >= 0; --order)
 #pragma unroll
-        for (int tn = 0; tn < 2; ++tn)
-          acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[tm], bv[tn], acc[tm][tn], 0, 0, 0);
+        for (int pa = 0; pa < NA; ++pa) {
+          const int pb = order - pa;
+          if (pb < 0 || pb > 2) continue;
+#pragma unroll
+          for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+            for (int tn = 0; tn < 2; ++tn)
+              acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[pa][tm], fb[pb][tn], acc[tm][tn], 0, 0, 0);
+        }
     }
-    __syncthreads();   // stage cur free for the tile after next, stage cur ^ 1 complete
-    cur ^= 1;
+  };
+  using Set0 = std::integral_constant<int, 0>;
+  using Set1 = std::integral_constant<int, 1>;
+
+  // kend is a multiple of 128: an even number (at least four) of k-tiles
+  fetch(Set0{}, 0);
+  fetch(Set1{}, kSK);
+  stash(Set0{}, 0);
+  fetch(Set0{}, 2 * kSK);
+  __syncthreads();
+  for (int k0 = 0; k0 < kend; k0 += 2 * kSK) {
+    // tile k0 sits in stage 0; tile k0 + 32 goes from set 1 to stage 1, set 1 then takes tile k0 + 96
+    stash(Set1{}, 1);
+    if (k0 + 3 * kSK < kend) fetch(Set1{}, k0 + 3 * kSK);
+    products(0);
+    __syncthreads();
+    // tile k0 + 32 sits in stage 1; tile k0 + 64 goes from set 0 to stage 0, set 0 then takes tile k0 + 128
+    if (k0 + 2 * kSK < kend) stash(Set0{}, 0);
+    if (k0 + 4 * kSK < kend) fetch(Set0{}, k0 + 4 * kSK);
+    products(1);
+    __syncthreads();
   }
 
   // sum_ij A_ij T_ij of the tile in float64; accumulator r of a lane is row (r / 4) * 8 + (lane / 32) * 4 + r % 4,
@@ -212,13 +280,17 @@ __global__ __launch_bounds__(256, 2) void quad_form32_kernel(Err32Args a) {
       for (int r = 0; r < 16; ++r) {
         const int i = wm * 64 + tm * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
         const int j = wn * 64 + tn * 32 + (lane & 31);
-        s = fma((double)acc[tm][tn][r], (double)A[(int64_t)i * a.np + j0 + j], s);
+        const int64_t at = (int64_t)(i0 + i) * a.np + j0 + j;
+        double v = (double)bf16_val(a.A[at]);
+#pragma unroll
+        for (int p = 1; p < NA; ++p) v += (double)bf16_val(a.A[p * planeA + at]);
+        s = fma((double)acc[tm][tn][r], v, s);
       }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
   if (lane == 0) red[wave] = s;
   __syncthreads();
-  if (tid == 0) a.partial[((int64_t)z * nrt + rt) * gridDim.y + ct] = (red[0] + red[1]) + (red[2] + red[3]);
+  if (tid == 0) a.partial[(int64_t)rt * gridDim.y + ct] = (red[0] + red[1]) + (red[2] + red[3]);
 }
 
 __global__ __launch_bounds__(256) void finish_kernel(const double* __restrict__ partial, int tiles,
@@ -256,39 +328,53 @@ static size_t bytes_f64_form(int64_t m, int64_t n) {
   return partial_bytes(m, n) + align_up(2 * (size_t)m * (size_t)n * sizeof(double), 256);
 }
 
-static size_t partial32_bytes(int64_t mp, int64_t np) {
+static size_t partial_split_bytes(int64_t mp, int64_t np) {
   return align_up(2 * (size_t)(mp / kT) * (size_t)(np / kT) * sizeof(double), 256);
 }
 
-static size_t bytes_f32_form(int64_t m, int64_t n) {
+static size_t pieces_bytes(int64_t rows, int64_t cols) {
+  return align_up(3 * (size_t)rows * (size_t)cols * sizeof(uint16_t), 256);
+}
+
+static size_t bytes_split_form(int64_t m, int64_t n) {
   const int64_t mp = ceil_div(m, kT) * kT, np = ceil_div(n, kT) * kT;
-  return partial32_bytes(mp, np) + align_up(2 * (size_t)mp * (size_t)np * sizeof(float), 256) +
-         align_up((size_t)np * (size_t)np * sizeof(float), 256);
+  return partial_split_bytes(mp, np) + 2 * pieces_bytes(mp, np) + pieces_bytes(np, np);
 }
 
 // the caller asks before it says which storage type W has: enough for either form
 size_t layer_error_workspace_bytes(int64_t m, int64_t n) {
-  const size_t a = bytes_f64_form(m, n), b = bytes_f32_form(m, n);
+  const size_t a = bytes_f64_form(m, n), b = bytes_split_form(m, n);
   return a > b ? a : b;
 }
 
-static ptq_status launch_f32_form(const void* W, ptq_dtype wdt, int64_t ldw, const double* Wq, int64_t m, int64_t n,
-                                  const double* H, int64_t ldh, double* out, void* ws, hipStream_t st) {
+template <int NA>
+static bool launch_split(const SplitArgs& a, hipStream_t st) {
+  const int lds = 2 * (NA + 3) * kT * kSP * (int)sizeof(uint16_t);
+  if (!lds_opt_in<quad_form_split_kernel<NA>>(2 * 6 * kT * kSP * (int)sizeof(uint16_t))) return false;
+  quad_form_split_kernel<NA><<<dim3((unsigned)(a.mp / kT), (unsigned)(a.np / kT)), 256, lds, st>>>(a);
+  return true;
+}
+
+static ptq_status launch_split_form(const void* W, ptq_dtype wdt, int64_t ldw, const double* Wq, int64_t m, int64_t n,
+                                    const double* H, int64_t ldh, double* out, void* ws, hipStream_t st) {
   const int64_t mp = ceil_div(m, kT) * kT, np = ceil_div(n, kT) * kT;
-  double* partial = static_cast<double*>(ws);
-  float* A32 = reinterpret_cast<float*>(static_cast<char*>(ws) + partial32_bytes(mp, np));
-  float* Hu = reinterpret_cast<float*>(reinterpret_cast<char*>(A32) +
-                                       align_up(2 * (size_t)mp * (size_t)np * sizeof(float), 256));
-  const unsigned ga = (unsigned)ceil_div(mp * np / 4, 256), gh = (unsigned)ceil_div(np * np / 4, 256);
+  char* base = static_cast<char*>(ws);
+  double* partial = reinterpret_cast<double*>(base);
+  uint16_t* Dp = reinterpret_cast<uint16_t*>(base + partial_split_bytes(mp, np));
+  uint16_t* Wp = reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(Dp) + pieces_bytes(mp, np));
+  uint16_t* HuT = reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(Wp) + pieces_bytes(mp, np));
+  const unsigned ga = (unsigned)ceil_div(mp * np / 4, 256);
   if (wdt == PTQ_F32)
-    narrow_kernel<PTQ_F32><<<ga, 256, 0, st>>>(W, ldw, Wq, (int)m, (int)n, (int)mp, (int)np, A32);
+    split_weights_kernel<PTQ_F32><<<ga, 256, 0, st>>>(W, ldw, Wq, (int)m, (int)n, (int)mp, (int)np, Dp, Wp);
   else
-    narrow_kernel<PTQ_BF16><<<ga, 256, 0, st>>>(W, ldw, Wq, (int)m, (int)n, (int)mp, (int)np, A32);
-  hu_kernel<<<gh, 256, 0, st>>>(H, ldh, (int)n, (int)np, Hu);
-  Err32Args a{A32, Hu, (int)mp, (int)np, partial};
-  dim3 g(2 * (unsigned)(mp / kT), (unsigned)(np / kT));
-  quad_form32_kernel<<<g, 256, 0, st>>>(a);
-  finish_kernel<<<1, 256, 0, st>>>(partial, (int)(g.x / 2 * g.y), out);
+    split_weights_kernel<PTQ_BF16><<<ga, 256, 0, st>>>(W, ldw, Wq, (int)m, (int)n, (int)mp, (int)np, Dp, Wp);
+  split_hu_kernel<<<dim3((unsigned)(np / 32), (unsigned)(np / 32)), 256, 0, st>>>(H, ldh, (int)n, (int)np, HuT);
+  const int tiles = (int)((mp / kT) * (np / kT));
+  SplitArgs num{Dp, HuT, (int)mp, (int)np, partial};
+  SplitArgs den{Wp, HuT, (int)mp, (int)np, partial + tiles};
+  if (!launch_split<3>(num, st)) return PTQ_ERR_HIP;
+  if (!(wdt == PTQ_BF16 ? launch_split<1>(den, st) : launch_split<3>(den, st))) return PTQ_ERR_HIP;
+  finish_kernel<<<1, 256, 0, st>>>(partial, tiles, out);
   PTQ_HIP_CHECK_LAUNCH();
   return PTQ_OK;
 }
@@ -297,7 +383,7 @@ ptq_status layer_error_launch(const void* W, ptq_dtype wdt, int64_t ldw, const d
                               int64_t n, const double* H, int64_t ldh, double* out, void* ws,
                               size_t ws_bytes, hipStream_t st) {
   if (ws_bytes < layer_error_workspace_bytes(m, n)) return PTQ_ERR_WORKSPACE;
-  if (wdt == PTQ_F32 || wdt == PTQ_BF16) return launch_f32_form(W, wdt, ldw, Wq, m, n, H, ldh, out, ws, st);
+  if (wdt == PTQ_F32 || wdt == PTQ_BF16) return launch_split_form(W, wdt, ldw, Wq, m, n, H, ldh, out, ws, st);
   if (wdt != PTQ_F64) return PTQ_ERR_DTYPE;
   double* partial = static_cast<double*>(ws);
   double* A2 = reinterpret_cast<double*>(static_cast<char*>(ws) + partial_bytes(m, n));

@@ -118,7 +118,7 @@ def stagewise(capsys, spec, bits, group, block, damps, t_test, n_rows=48, seed=w
         rel, num, den = g.error(Hdev)
         r0, n0, d0 = orc.layer_error(W64, Wq, Href)
         say(capsys, f"  damp {damp}: rel layer error gpu {rel:.6f} oracle {r0:.6f}")
-        # bfloat16 weights: float32 products on the matrix cores, float64 from the tile sums on
+        # bfloat16 weights: float32 sums of exact piece products on the matrix cores, float64 from the tile sums on
         assert abs(rel - r0) <= 1e-4 and abs(num - n0) <= 3e-7 * n0 and abs(den - d0) <= 3e-7 * d0
     del g
     torch.cuda.empty_cache()

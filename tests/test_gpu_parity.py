@@ -317,9 +317,10 @@ def test_layer_error_matches_oracle(dtype, m, n):
     ptq.ptq_layer_error(to_device(Ws), torch.from_numpy(Wq).cuda(), torch.from_numpy(Hin).cuda(), out)
     rel, num, den = out.cpu().numpy()
     r0, n0, d0 = orc.layer_error(W64, Wq, H)
-    # float64 weights: float64 throughout.  float32 / bfloat16 weights: D, W and H rounded to float32 and
-    # float32 products and sums over k on the matrix cores -- four roundings of 2^-24 per term at worst
-    # (that worst case is the 1 x 1 layer), far less once m n terms average them out
+    # float64 weights: float64 throughout.  float32 / bfloat16 weights: D, W and H rounded to float32,
+    # products (from bfloat16 pieces, complete to 2^-24) and sums over k in float32 on the matrix cores --
+    # four roundings of 2^-24 per term at worst (that worst case is the 1 x 1 layer), far less once
+    # m n terms average them out
     tol = 1e-10 if dtype == "f64" else 3e-7
     assert abs(rel - r0) <= 1e-4 and abs(rel - r0) <= tol
     assert abs(num - n0) <= tol * n0 and abs(den - d0) <= tol * d0
