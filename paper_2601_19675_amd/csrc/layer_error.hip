@@ -109,10 +109,11 @@ __device__ __forceinline__ void split3(float x, uint16_t (&p)[3]) {
 }
 
 struct SplitArgs {
-  const uint16_t* A;   // [pieces][mp][np]: D = W - Wq or W as bfloat16 pieces; zero outside m x n
+  const uint16_t* D;   // [3][mp][np]: D = W - Wq as bfloat16 pieces; zero outside m x n
+  const uint16_t* W;   // [1 or 3][mp][np]: W likewise
   const uint16_t* HuT; // [3][np (j)][np (k)]: Hu transposed, as pieces; zero for k > j and outside n x n
   int mp, np;
-  double* partial;     // [tiles] of this quadratic form
+  double* partial;     // [2][tiles]: the tile sums of tr(D H D^T), then those of tr(W H W^T)
 };
 
 // D and W as bfloat16 pieces, four consecutive k per thread
@@ -167,16 +168,18 @@ __global__ __launch_bounds__(256) void split_hu_kernel(const double* __restrict_
   }
 }
 
-template <int NA>
+// ND pieces of D and NW pieces of W against the three pieces of Hu: both traces in one pass over Hu when
+// the pieces fit LDS together (<3, 1>: W stored in bfloat16), else one trace per launch (<3, 0>, <0, 3>)
+template <int ND, int NW>
 __global__ __launch_bounds__(256) void quad_form_split_kernel(SplitArgs a) {
-  extern __shared__ uint16_t sm[];   // [2 stages][NA + 3 pieces][128 rows][kSP]
-  __shared__ double red[4];
-  constexpr int NP = NA + 3;
+  extern __shared__ uint16_t sm[];   // [2 stages][ND + NW + 3 pieces][128 rows][kSP]
+  __shared__ double red[2][4];
+  constexpr int NA = ND + NW, NP = NA + 3;
   constexpr int kPiece = kT * kSP, kStage = NP * kPiece;
   // the widest column tiles first (blockIdx.y is the slow grid index)
   const int rt = blockIdx.x, ct = gridDim.y - 1 - blockIdx.y;
   const int i0 = rt * kT, j0 = ct * kT;
-  const int kend = j0 + kT;   // beyond it Hu is zero; a multiple of the k-tile
+  const int kend = j0 + kT;   // beyond it Hu is zero; a multiple of 128
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   const int64_t planeA = (int64_t)a.mp * a.np, planeB = (int64_t)a.np * a.np;
@@ -185,7 +188,7 @@ __global__ __launch_bounds__(256) void quad_form_split_kernel(SplitArgs a) {
   // loads are issued three k-tiles ahead and have two whole k-tiles of MFMAs to arrive (one k-tile
   // of the bfloat16 MFMA is too short to cover the latency of a load from L2)
   const int lr = tid >> 2, lk = (tid & 3) * 8;
-  const uint16_t* ga = a.A + (int64_t)(i0 + lr) * a.np + lk;
+  const int64_t arow = (int64_t)(i0 + lr) * a.np + lk;
   const uint16_t* gb = a.HuT + (int64_t)(j0 + lr) * a.np + lk;
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // a native vector: stays in registers
   u32x4 reg[2][NP][2];
@@ -193,7 +196,7 @@ __global__ __launch_bounds__(256) void quad_form_split_kernel(SplitArgs a) {
     constexpr int S = decltype(set)::value;
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
-      const uint16_t* g = p < NA ? ga + p * planeA : gb + (p - NA) * planeB;
+      const uint16_t* g = p < ND ? a.D + p * planeA + arow : (p < NA ? a.W + (p - ND) * planeA + arow : gb + (p - NA) * planeB);
       reg[S][p][0] = *reinterpret_cast<const u32x4*>(g + k0);
       reg[S][p][1] = *reinterpret_cast<const u32x4*>(g + (int64_t)64 * a.np + k0);
     }
@@ -208,13 +211,16 @@ __global__ __launch_bounds__(256) void quad_form_split_kernel(SplitArgs a) {
     }
   };
 
-  f32x16 acc[2][2];
+  constexpr int kForms = (ND > 0) + (NW > 0);
+  f32x16 acc[kForms][2][2];
 #pragma unroll
-  for (int tm = 0; tm < 2; ++tm)
+  for (int f = 0; f < kForms; ++f)
 #pragma unroll
-    for (int tn = 0; tn < 2; ++tn)
+    for (int tm = 0; tm < 2; ++tm)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[tm][tn][r] = 0.f;
+      for (int tn = 0; tn < 2; ++tn)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[f][tm][tn][r] = 0.f;
 
   // the products of the k-tile in LDS stage `stage`
   auto products = [&](int stage) {
@@ -233,17 +239,20 @@ __global__ __launch_bounds__(256) void quad_form_split_kernel(SplitArgs a) {
         for (int p = 0; p < 3; ++p)
           fb[p][t] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(st + (NA + p) * kPiece + (wn * 64 + t * 32) * kSP + fo));
       }
+      // piece pa of an operand with piece pb of Hu for pa + pb <= 2, the smallest products first
 #pragma unroll
       for (int order = 2; order >= 0; --order)
 #pragma unroll
-        for (int pa = 0; pa < NA; ++pa) {
+        for (int p = 0; p < NA; ++p) {
+          const int f = (ND > 0 && p >= ND) ? 1 : 0;   // which trace the piece belongs to
+          const int pa = p < ND ? p : p - ND;
           const int pb = order - pa;
           if (pb < 0 || pb > 2) continue;
 #pragma unroll
           for (int tm = 0; tm < 2; ++tm)
 #pragma unroll
             for (int tn = 0; tn < 2; ++tn)
-              acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[pa][tm], fb[pb][tn], acc[tm][tn], 0, 0, 0);
+              acc[f][tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[p][tm], fb[pb][tn], acc[f][tm][tn], 0, 0, 0);
         }
     }
   };
@@ -271,26 +280,39 @@ __global__ __launch_bounds__(256) void quad_form_split_kernel(SplitArgs a) {
 
   // sum_ij A_ij T_ij of the tile in float64; accumulator r of a lane is row (r / 4) * 8 + (lane / 32) * 4 + r % 4,
   // column lane % 32 of its 32 x 32 tile; rows and columns beyond m x n hold zeros
-  double s = 0.0;
+  double s[kForms];
 #pragma unroll
-  for (int tm = 0; tm < 2; ++tm)
+  for (int f = 0; f < kForms; ++f) {
+    const bool is_w = (ND == 0) || f == 1;
+    const uint16_t* P = is_w ? a.W : a.D;
+    const int np_ = is_w ? NW : ND;
+    s[f] = 0.0;
 #pragma unroll
-    for (int tn = 0; tn < 2; ++tn)
+    for (int tm = 0; tm < 2; ++tm)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int i = wm * 64 + tm * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-        const int j = wn * 64 + tn * 32 + (lane & 31);
-        const int64_t at = (int64_t)(i0 + i) * a.np + j0 + j;
-        double v = (double)bf16_val(a.A[at]);
+      for (int tn = 0; tn < 2; ++tn)
 #pragma unroll
-        for (int p = 1; p < NA; ++p) v += (double)bf16_val(a.A[p * planeA + at]);
-        s = fma((double)acc[tm][tn][r], v, s);
-      }
+        for (int r = 0; r < 16; ++r) {
+          const int i = wm * 64 + tm * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+          const int j = wn * 64 + tn * 32 + (lane & 31);
+          const int64_t at = (int64_t)(i0 + i) * a.np + j0 + j;
+          double v = (double)bf16_val(P[at]);
+          for (int p = 1; p < np_; ++p) v += (double)bf16_val(P[p * planeA + at]);
+          s[f] = fma((double)acc[f][tm][tn][r], v, s[f]);
+        }
 #pragma unroll
-  for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
-  if (lane == 0) red[wave] = s;
+    for (int off = 32; off > 0; off >>= 1) s[f] += __shfl_xor(s[f], off);
+    if (lane == 0) red[f][wave] = s[f];
+  }
   __syncthreads();
-  if (tid == 0) a.partial[(int64_t)rt * gridDim.y + ct] = (red[0] + red[1]) + (red[2] + red[3]);
+  if (tid == 0) {
+    const int64_t tile = (int64_t)rt * gridDim.y + ct, tiles = (int64_t)gridDim.x * gridDim.y;
+#pragma unroll
+    for (int f = 0; f < kForms; ++f) {
+      const bool is_w = (ND == 0) || f == 1;
+      a.partial[(is_w ? tiles : 0) + tile] = (red[f][0] + red[f][1]) + (red[f][2] + red[f][3]);
+    }
+  }
 }
 
 __global__ __launch_bounds__(256) void finish_kernel(const double* __restrict__ partial, int tiles,
@@ -347,11 +369,11 @@ size_t layer_error_workspace_bytes(int64_t m, int64_t n) {
   return a > b ? a : b;
 }
 
-template <int NA>
+template <int ND, int NW>
 static bool launch_split(const SplitArgs& a, hipStream_t st) {
-  const int lds = 2 * (NA + 3) * kT * kSP * (int)sizeof(uint16_t);
-  if (!lds_opt_in<quad_form_split_kernel<NA>>(2 * 6 * kT * kSP * (int)sizeof(uint16_t))) return false;
-  quad_form_split_kernel<NA><<<dim3((unsigned)(a.mp / kT), (unsigned)(a.np / kT)), 256, lds, st>>>(a);
+  const int lds = 2 * (ND + NW + 3) * kT * kSP * (int)sizeof(uint16_t);
+  if (!lds_opt_in<quad_form_split_kernel<ND, NW>>(2 * 7 * kT * kSP * (int)sizeof(uint16_t))) return false;
+  quad_form_split_kernel<ND, NW><<<dim3((unsigned)(a.mp / kT), (unsigned)(a.np / kT)), 256, lds, st>>>(a);
   return true;
 }
 
@@ -370,10 +392,12 @@ static ptq_status launch_split_form(const void* W, ptq_dtype wdt, int64_t ldw, c
     split_weights_kernel<PTQ_BF16><<<ga, 256, 0, st>>>(W, ldw, Wq, (int)m, (int)n, (int)mp, (int)np, Dp, Wp);
   split_hu_kernel<<<dim3((unsigned)(np / 32), (unsigned)(np / 32)), 256, 0, st>>>(H, ldh, (int)n, (int)np, HuT);
   const int tiles = (int)((mp / kT) * (np / kT));
-  SplitArgs num{Dp, HuT, (int)mp, (int)np, partial};
-  SplitArgs den{Wp, HuT, (int)mp, (int)np, partial + tiles};
-  if (!launch_split<3>(num, st)) return PTQ_ERR_HIP;
-  if (!(wdt == PTQ_BF16 ? launch_split<1>(den, st) : launch_split<3>(den, st))) return PTQ_ERR_HIP;
+  SplitArgs a{Dp, Wp, HuT, (int)mp, (int)np, partial};
+  if (wdt == PTQ_BF16) {
+    if (!launch_split<3, 1>(a, st)) return PTQ_ERR_HIP;
+  } else {
+    if (!launch_split<3, 0>(a, st) || !launch_split<0, 3>(a, st)) return PTQ_ERR_HIP;
+  }
   finish_kernel<<<1, 256, 0, st>>>(partial, tiles, out);
   PTQ_HIP_CHECK_LAUNCH();
   return PTQ_OK;
