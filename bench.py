@@ -76,6 +76,8 @@ def single_block_us_per_column(ptq, bits, group, reps=30):
     128-column call removes the launch.  It contains the walk, the in-block pushes and the block's
     set-up and outputs, so it is an upper estimate of the walk's share.  Microseconds per column."""
     import torch
+
+    from paper_2601_19675_amd import binding
     gen = torch.Generator(device="cuda").manual_seed(7)
     times = {}
     for n in (128, 256):
@@ -86,7 +88,7 @@ def single_block_us_per_column(ptq, bits, group, reps=30):
         codes = torch.empty((16, n), dtype=torch.uint8, device="cuda")
         scales = torch.empty((16, n // g), dtype=torch.float32, device="cuda")
         zeros = torch.empty((16, n // g), dtype=torch.uint8, device="cuda")
-        ws = torch.empty(max(256, ptq.ptq_workspace_bytes(2, 16, n, 0, n)), dtype=torch.uint8, device="cuda")
+        ws = torch.empty(max(256, ptq.ptq_workspace_bytes(binding.OP_QUANTIZE, 16, n, 0, n)), dtype=torch.uint8, device="cuda")
         runs = []
         for k in range(reps + 3):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
