@@ -74,7 +74,7 @@ class GpuLayer:
         return self.out.cpu().numpy()
 
 
-def stagewise(capsys, spec, bits, group, block, damps, t_test, n_rows=48, seed=wl.BASE_SEED):
+def stagewise(capsys, spec, bits, group, block, damps, t_test, n_rows=48, seed=wl.BASE_SEED, static_too=False):
     """Every stage on the GPU at the layer's full m x n, each fed the oracle's
     upstream result computed from the first t_test tokens."""
     m, n = spec.m, spec.n
@@ -120,13 +120,26 @@ def stagewise(capsys, spec, bits, group, block, damps, t_test, n_rows=48, seed=w
         say(capsys, f"  damp {damp}: rel layer error gpu {rel:.6f} oracle {r0:.6f}")
         # bfloat16 weights: float32 sums of exact piece products on the matrix cores, float64 from the tile sums on
         assert abs(rel - r0) <= 1e-4 and abs(num - n0) <= 3e-7 * n0 and abs(den - d0) <= 3e-7 * d0
+    if static_too:
+        # the static-groups variant of the solve at the same size and launch shape, with the last factor
+        ptq.ptq_quantize_layer_static_groups(g.W, Udev, None, bits, group, block, g.codes, g.scales, g.zeros, g.Wq,
+                                             g.err2)
+        torch.cuda.synchronize()
+        codes, scales, zeros = g.codes.cpu().numpy(), g.scales.cpu().numpy(), g.zeros.cpu().numpy()
+        rep = compare_quantization(W64[rows], Uref, bits, group, None, codes[rows], scales[rows], zeros[rows],
+                                   static_groups=True)
+        say(capsys, f"  static groups: sampled rows exact {rep['exact_rows']}/{n_rows}, flagged c/z/s "
+                    f"{rep['flagged_codes']}/{rep['flagged_zeros']}/{rep['flagged_scales']}, unflagged {rep['unflagged']}")
+        assert rep["unflagged"] == 0, rep["details"][:5]
+        assert rep["flagged_codes"] + rep["flagged_zeros"] + rep["flagged_scales"] <= 2
+        assert np.array_equal(g.Wq.cpu().numpy(), orc.dequantize(codes, scales, zeros, group))
     del g
     torch.cuda.empty_cache()
 
 
 def test_config2_attention_projection_stagewise(capsys):
     cfg = wl.CONFIGS["C2"]
-    stagewise(capsys, cfg.layers[0], cfg.bits, cfg.group, cfg.block, cfg.damps, t_test=8192)
+    stagewise(capsys, cfg.layers[0], cfg.bits, cfg.group, cfg.block, cfg.damps, t_test=8192, static_too=True)
 
 
 def test_config4_two_bit_damp_sweep(capsys):
