@@ -394,6 +394,20 @@ def main():
             "algorithmic_flops_per_launch": syrk_flops, "algorithmic_bytes_per_launch": 2.0 * t * n,
         },
     }
+    # the other three calls against the peak of the unit that bounds them (algorithmic flops of the call
+    # over its event-bracketed time; the layer error counts the piece products it executes on the bf16 MFMA)
+    f_flops = 2.0 / 3.0 * float(n) ** 3
+    q_flops = float(m) * n * n
+    pieces = 9.0 if spec.dtype == "bf16" else 12.0
+    e_flops = pieces * m * n * (n + 128.0)
+    result["rooflines_other_calls"] = [
+        {"call": "ptq_damped_cholesky_inv", "bound": "mfma", "dtype": "f64", "achieved": f_flops / (f_ms * 1e-3) / 1e12,
+         "peak": PEAK_F64_TFLOPS, "unit": "TFLOP/s", "frac": f_flops / (f_ms * 1e-3) / 1e12 / PEAK_F64_TFLOPS},
+        {"call": "ptq_quantize_layer", "bound": "mfma", "dtype": "f64", "achieved": q_flops / (q_ms * 1e-3) / 1e12,
+         "peak": PEAK_F64_TFLOPS, "unit": "TFLOP/s", "frac": q_flops / (q_ms * 1e-3) / 1e12 / PEAK_F64_TFLOPS},
+        {"call": "ptq_layer_error", "bound": "mfma", "dtype": "bf16", "achieved": e_flops / (e_ms * 1e-3) / 1e12,
+         "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": e_flops / (e_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS},
+    ]
     # the solve against its floors (bytes at the HBM rate, flops at the float64 peak), and what its
     # serial part costs: n columns at the per-column time of a call that is nothing but the walk
     q_bytes = float(m) * n * (W.element_size() + 1 + 8) + 4.0 * n * n + 5.0 * m * n / cfg.group
