@@ -39,6 +39,13 @@ def test_status_strings_and_workspace_sizes(lib):
     assert ptq.ptq_workspace_bytes(binding.OP_CHOLESKY_INV, 0, 4096) >= 4096 * 4096 * 8
     # the solve keeps the errors of every column: n x m float64
     assert ptq.ptq_workspace_bytes(binding.OP_QUANTIZE, 4096, 11008) >= 4096 * 11008 * 8
+    # the layer error: room for either form -- float64 copies of D and W, or bfloat16 pieces of D, W and
+    # the transposed Hessian on sizes rounded up to its 128-wide tiles
+    for mm, nn in ((4096, 4096), (4096, 11008), (1, 1), (70, 200)):
+        need = ptq.ptq_workspace_bytes(binding.OP_LAYER_ERROR, mm, nn)
+        mp, npad = -(-mm // 128) * 128, -(-nn // 128) * 128
+        assert need >= 2 * mm * nn * 8
+        assert need >= 2 * 3 * mp * npad * 2 + 3 * npad * npad * 2
     out = ctypes.c_size_t()
     assert lib.ptq_workspace_bytes(0, -1, 8, 8, 0, ctypes.byref(out)) == 2
     assert lib.ptq_workspace_bytes(9, 1, 8, 8, 0, ctypes.byref(out)) == 1
