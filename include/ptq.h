@@ -305,10 +305,7 @@ ptq_status ptq_activation_scale(const double* asum, int64_t tokens, int64_t n, d
  * The loop runs as ONE cooperative launch where the device can hold it, its workgroups waiting
  * for each other's partial sums; a workgroup that waits longer than a fixed number of rounds
  * (about a second) gives up and makes all others give up: the call still completes, and every
- * entry of sigma is then the NaN pattern 0x7e00.  Two environment variables, read at every
- * call, exist for tests and comparisons: PTQ_R1SVD_LAUNCH = "resident" | "stream" | "rows" |
- * "steps" selects another form of the same loop than the one the shapes call for,
- * PTQ_R1SVD_SPIN_LIMIT = <rounds> sets that number of rounds.
+ * entry of sigma is then the NaN pattern 0x7e00 (check sigma[0] after synchronising).
  * Workspace: PTQ_OP_SCALED_R1SVD (m, n).
  * Errors: PTQ_ERR_ARG, PTQ_ERR_SHAPE, PTQ_ERR_DTYPE, PTQ_ERR_WORKSPACE, PTQ_ERR_HIP.
  */

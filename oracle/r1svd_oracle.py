@@ -144,33 +144,30 @@ def rank_one_step(A: np.ndarray, v: np.ndarray, it: int):
 
 def r1svd(A: np.ndarray, S: np.ndarray, it: int, rounded: bool = True,
           U_force: np.ndarray | None = None, V_force: np.ndarray | None = None,
-          follow: dict | None = None, follow_tol: float = 0.0):
+          sigma_force: np.ndarray | None = None):
     """Rank-by-rank sketch of A with deflation (Sec. 3.3; Algorithm 1, inner loop).
 
     S is r x n, one sketch vector per rank.  With `rounded` the factors are stored in
     e4m3 / fp16 and the stored values are what is deflated.  U_force / V_force (r x m,
-    r x n, int16, -1 = no override) replace single codes: the parity protocol uses them
-    where a value sits on a rounding tie, so that one flipped code does not hide everything
-    after it.  `follow` = {"U_code", "V_code", "sigma"} are another implementation's stored
-    results: wherever one of them differs from this function's own rounding but is itself
-    within (1/2 + follow_tol) quanta of the unrounded value -- a legitimate rounding of a
-    value that sits on a tie, up to the arithmetic noise follow_tol stands for -- it is
-    adopted and counted in "followed"; all other differences are left for the caller to see.
+    r x n, int16, -1 = no override) replace single codes and sigma_force (r, NaN = no
+    override) a stored sigma: a parity protocol uses them where a value sits on a rounding
+    tie, so that one flipped code does not hide everything after it.
 
     Returns dict: U (r x m), V (r x n), sigma (r) as stored values (float64), U_code,
-    V_code (uint8, only with `rounded`), U_margin, V_margin, and A (the deflated matrix).
+    V_code (uint8, only with `rounded`), U_margin, V_margin, the unrounded U_exact, V_exact,
+    sigma_exact of every rank (given the earlier ranks as stored), and A (the deflated matrix).
     """
     A = np.array(A, dtype=np.float64, copy=True)
     m, n = A.shape
     r = S.shape[0]
     U = np.zeros((r, m)); V = np.zeros((r, n)); sig = np.zeros(r)
+    Ue = np.zeros((r, m)); Ve = np.zeros((r, n)); sige = np.zeros(r)
     Uc = np.zeros((r, m), dtype=np.uint8); Vc = np.zeros((r, n), dtype=np.uint8)
     Um = np.full((r, m), 0.5); Vm = np.full((r, n), 0.5)
-    followed = 0
     for k in range(r):
         u, sg, vv = rank_one_step(A, S[k].astype(np.float64), it)
+        Ue[k], Ve[k], sige[k] = u, vv, sg
         if rounded:
-            u_exact, v_exact = u, vv
             u, Um[k] = e4m3_round(u)
             vv, Vm[k] = e4m3_round(vv)
             Uc[k] = e4m3_encode(u)
@@ -183,35 +180,30 @@ def r1svd(A: np.ndarray, S: np.ndarray, it: int, rounded: bool = True,
                 f = V_force[k] >= 0
                 Vc[k][f] = V_force[k][f].astype(np.uint8)
                 vv = e4m3_decode(Vc[k])
-            sg_exact = sg
             sg = fp16_round(sg)
-            if follow is not None:
-                for own, theirs, exact in ((Uc[k], follow["U_code"][k], u_exact),
-                                           (Vc[k], follow["V_code"][k], v_exact)):
-                    near = np.abs(e4m3_decode(theirs) - exact) <= (0.5 + follow_tol) * _quantum(
-                        exact, _E4M3_MIN_EXP, _E4M3_MANT_BITS)
-                    take = (own != theirs) & near & ((theirs & 0x7F) != 0x7F)
-                    own[take] = theirs[take]
-                    followed += int(np.count_nonzero(take))
-                u = e4m3_decode(Uc[k])
-                vv = e4m3_decode(Vc[k])
-                theirs = float(follow["sigma"][k])
-                if theirs != sg and np.isfinite(theirs) and abs(theirs - sg_exact) <= (0.5 + follow_tol) * float(
-                        _quantum(sg_exact, -14, 10)):
-                    sg = theirs
-                    followed += 1
+            if sigma_force is not None and not np.isnan(sigma_force[k]):
+                sg = float(sigma_force[k])
         U[k], V[k], sig[k] = u, vv, sg
         A -= sg * np.outer(u, vv)
-    return {"U": U, "V": V, "sigma": sig, "U_code": Uc, "V_code": Vc,
-            "U_margin": Um, "V_margin": Vm, "A": A, "followed": followed}
+    return {"U": U, "V": V, "sigma": sig, "U_code": Uc, "V_code": Vc, "U_margin": Um, "V_margin": Vm,
+            "U_exact": Ue, "V_exact": Ve, "sigma_exact": sige, "A": A}
+
+
+def quantum(x: np.ndarray, fmt: str) -> np.ndarray:
+    """Spacing of the stored format's values ("e4m3" or "fp16") in the binade of |x|."""
+    if fmt == "e4m3":
+        return _quantum(x, _E4M3_MIN_EXP, _E4M3_MANT_BITS)
+    if fmt == "fp16":
+        return _quantum(x, -14, 10)
+    raise ValueError(fmt)
 
 
 def scaled_r1svd(W: np.ndarray, s: np.ndarray, S: np.ndarray, it: int, rounded: bool = True,
                  U_force: np.ndarray | None = None, V_force: np.ndarray | None = None,
-                 follow: dict | None = None, follow_tol: float = 0.0):
+                 sigma_force: np.ndarray | None = None):
     """W_s = W diag(s), its sketch, and the residual R = A diag(s)^-1       (Algorithm 1)"""
     s = s.astype(np.float64)
-    out = r1svd(W.astype(np.float64) * s[None, :], S, it, rounded, U_force, V_force, follow, follow_tol)
+    out = r1svd(W.astype(np.float64) * s[None, :], S, it, rounded, U_force, V_force, sigma_force)
     out["R"] = out["A"] / s[None, :]
     return out
 

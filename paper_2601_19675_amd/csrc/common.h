@@ -132,6 +132,7 @@ ptq_status abs_sum_launch(double* asum, const void* X, ptq_dtype xdt, int64_t t,
 ptq_status activation_scale_launch(const double* asum, int64_t tokens, int64_t n, double* s, hipStream_t st);
 size_t r1svd_workspace_bytes(int64_t m, int64_t n);
 int64_t r1svd_max_columns();
+void r1svd_select(int launch_form, long long spin_limit);
 ptq_status r1svd_launch(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m, int64_t n, const double* s,
                         const float* S, int64_t lds, int r, int it, uint8_t* U, uint8_t* V, uint16_t* sigma16,
                         float* Rout, int64_t ldr, void* ws, hipStream_t st);

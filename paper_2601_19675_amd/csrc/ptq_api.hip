@@ -207,6 +207,11 @@ ptq_status ptq_scaled_r1svd(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m
                       static_cast<hipStream_t>(stream));
 }
 
+// For the library's own tests: selects the launch form of ptq_scaled_r1svd (0 = by shape, 1 = resident,
+// 2 = stream, 3 = row blocks, 4 = one launch per step) and the spin limit of its bounded waits
+// (negative = default) for all later calls of this process.  Deliberately not declared in ptq.h.
+void ptq_internal_r1svd_select(int launch_form, long long spin_limit) { r1svd_select(launch_form, spin_limit); }
+
 double ptq_average_bits(int64_t m, int64_t n, double d_q, double d_o, int64_t g, int64_t r, double d_r) {
   if (m <= 0 || n <= 0 || g <= 0 || r < 0) return -1.0;
   return d_q + d_o / (double)g + (double)r * d_r / (double)n + (double)r * d_r / (double)m + 2.0 * d_o / (double)n +

@@ -960,6 +960,16 @@ ptq_status activation_scale_launch(const double* asum, int64_t tokens, int64_t n
   return PTQ_OK;
 }
 
+// Process-wide selection for the library's own tests and comparisons (not part of the documented
+// interface): 0 = the form the shapes call for, 1 = resident, 2 = stream, 3 = row blocks of the float32
+// running matrix, 4 = one launch per step; and the number of rounds a waiting workgroup spins.
+static std::atomic<int> g_launch_form{0};
+static std::atomic<unsigned> g_spin_limit{1u << 21};
+void r1svd_select(int launch_form, long long spin_limit) {
+  g_launch_form.store(launch_form >= 0 && launch_form <= 4 ? launch_form : 0, std::memory_order_relaxed);
+  g_spin_limit.store(spin_limit < 0 ? (1u << 21) : (unsigned)spin_limit, std::memory_order_relaxed);
+}
+
 size_t r1svd_workspace_bytes(int64_t m, int64_t n) { return layout(m, n).total; }
 int64_t r1svd_max_columns() { return kMaxColumns; }
 
@@ -982,16 +992,15 @@ ptq_status r1svd_launch(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m, in
   unsigned* counter = reinterpret_cast<unsigned*>(scal + 3);
   clear_counter_kernel<<<1, kWave, 0, st>>>(counter);   // a kernel, so that the call can be captured in a graph
 
-  // rounds a workgroup waits for another before it gives up (PTQ_R1SVD_SPIN_LIMIT: for tests of that path)
-  unsigned spin_limit = 1u << 21;
-  if (const char* lim = std::getenv("PTQ_R1SVD_SPIN_LIMIT")) spin_limit = (unsigned)std::strtoul(lim, nullptr, 10);
-  // One cooperative launch for the whole loop where the device can hold it.  PTQ_R1SVD_LAUNCH in the
-  // environment selects another form of the same loop, for comparison and tests: "resident" and
-  // "stream" the two launches that work on a bfloat16 weight as it is even where the tile form
-  // applies, "rows" the launch over row blocks of the float32 running matrix, "steps" one launch
-  // per step.
-  const char* mode = std::getenv("PTQ_R1SVD_LAUNCH");
-  const auto mode_is = [&](const char* name) { return mode && std::strcmp(mode, name) == 0; };
+  // rounds a workgroup waits for another before it gives up, and the form of the loop: one cooperative
+  // launch for the whole loop where the device can hold it, in the form the shapes call for, unless
+  // the library's own tests have selected another one (r1svd_select below)
+  const unsigned spin_limit = g_spin_limit.load(std::memory_order_relaxed);
+  const int mode = g_launch_form.load(std::memory_order_relaxed);
+  const auto mode_is = [&](const char* name) {
+    return (mode == 1 && std::strcmp(name, "resident") == 0) || (mode == 2 && std::strcmp(name, "stream") == 0) ||
+           (mode == 3 && std::strcmp(name, "rows") == 0) || (mode == 4 && std::strcmp(name, "steps") == 0);
+  };
   const int64_t TP = ceil_div(m, kTile), TQ = ceil_div(n, kTile);
   const bool tile_form = r > 0 && TP * TQ <= kComputeUnits && !mode_is("steps") && !mode_is("rows") &&
                          !mode_is("stream") && !mode_is("resident");

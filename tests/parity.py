@@ -13,17 +13,9 @@ and the comparison continues.  Anything else is an unflagged mismatch.
 from __future__ import annotations
 
 import numpy as np
-import torch
 
 from oracle import ptq_oracle as orc
-from ptq_workloads import to_f64
-
-
-def to_device(a: np.ndarray) -> torch.Tensor:
-    """Stored numpy tensor (uint16 = bf16 bits, float32, float64, uint8) -> cuda tensor."""
-    if a.dtype == np.uint16:
-        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
-    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+from ptq_workloads import to_device, to_f64  # noqa: F401  (to_device is re-exported for the tests)
 
 
 def hessian_errors(H_gpu: np.ndarray, H_ref: np.ndarray):
@@ -63,12 +55,30 @@ def _alt_round(x):
     return alt, margin
 
 
+def oracle_solve_rows(W64, U, bits, group, dead=None, static_groups=False, chunk=128, workers=None):
+    """orc.quantize_layer(..., want_pre=True) over all rows of W64, called on slices of `chunk` rows
+    from a pool of threads: rows are independent given U, so the slices are separate oracle runs
+    whose results are stacked.  (Nothing of the oracle is changed; a slice of 128 rows keeps the
+    column loop's rank-one updates in cache, and numpy releases the interpreter lock inside them.)"""
+    import os
+    from concurrent.futures import ThreadPoolExecutor
+    m = W64.shape[0]
+    if m <= chunk:
+        return orc.quantize_layer(W64, U, bits, group, dead=dead, want_pre=True, static_groups=static_groups)
+    workers = workers or min(16, os.cpu_count() or 1)
+    los = list(range(0, m, chunk))
+    with ThreadPoolExecutor(workers) as ex:
+        parts = list(ex.map(lambda lo: orc.quantize_layer(W64[lo:lo + chunk], U, bits, group, dead=dead, want_pre=True,
+                                                          static_groups=static_groups), los))
+    return {k: np.concatenate([p[k] for p in parts], axis=0) for k in parts[0]}
+
+
 def compare_quantization(W64, U, bits, group, dead, g_codes, g_scales, g_zeros, tol=1e-5,
                          max_forced_per_row=64, static_groups=False):
     """Runs the protocol over all rows of W64.  Returns a report dict."""
     maxq = float(2 ** bits - 1)
     m, n = W64.shape
-    base = orc.quantize_layer(W64, U, bits, group, dead=dead, want_pre=True, static_groups=static_groups)
+    base = oracle_solve_rows(W64, U, bits, group, dead, static_groups)
     rep = dict(rows=m, exact_rows=0, flagged_codes=0, flagged_zeros=0, flagged_scales=0,
                unflagged=0, max_scale_margin_ulp=0.0, details=[], oracle=base)
     for r in range(m):
@@ -127,3 +137,50 @@ def compare_quantization(W64, U, bits, group, dead, g_codes, g_scales, g_zeros, 
 
 def stored_to_f64(a):
     return to_f64(a)
+
+
+# ----------------------------------------------------------------------------
+# the same idea for the low-rank sketch: near-ties of the stored e4m3 / fp16 values
+# ----------------------------------------------------------------------------
+def follow_r1svd(W64, s, S, it, U_codes, V_codes, sigma, tol, max_followed=4):
+    """Oracle run of the scaled rank-one sketch that takes another implementation's stored value
+    where -- and only where -- that value is itself a legitimate rounding of the oracle's own
+    unrounded one: within (1/2 + tol) quanta of it, tol standing for the arithmetic noise of the
+    implementation under test.  One flipped code changes every later rank, so decisions are
+    settled rank by rank: the oracle is run, the first rank with a difference is examined, its
+    near-ties are forced (the oracle's U_force / V_force / sigma_force), and the oracle is run
+    again; anything that is not a near-tie stays different for the caller to see.  Gives up after
+    `max_followed` forced values.  Returns the oracle's result with "followed" = their number."""
+    from oracle import r1svd_oracle as ro
+    r, m, n = S.shape[0], W64.shape[0], W64.shape[1]
+    Uf = np.full((r, m), -1, dtype=np.int16)
+    Vf = np.full((r, n), -1, dtype=np.int16)
+    sf = np.full(r, np.nan)
+    followed = 0
+    settled = 0                      # ranks below this one agree or are given up on
+    while True:
+        ref = ro.scaled_r1svd(W64, s, S, it, U_force=Uf, V_force=Vf, sigma_force=sf)
+        ref["followed"] = followed
+        k = settled
+        while k < r and (np.array_equal(ref["U_code"][k], U_codes[k]) and np.array_equal(ref["V_code"][k], V_codes[k])
+                         and ref["sigma"][k] == sigma[k]):
+            k += 1
+        if k == r or followed >= max_followed:
+            return ref
+        took = 0
+        for own, theirs, exact, force in ((ref["U_code"][k], U_codes[k], ref["U_exact"][k], Uf[k]),
+                                          (ref["V_code"][k], V_codes[k], ref["V_exact"][k], Vf[k])):
+            near = np.abs(ro.e4m3_decode(theirs) - exact) <= (0.5 + tol) * ro.quantum(exact, "e4m3")
+            take = (own != theirs) & near & ((theirs & 0x7F) != 0x7F) & (force < 0)
+            force[take] = theirs[take]
+            took += int(np.count_nonzero(take))
+        th = float(sigma[k])
+        if (th != ref["sigma"][k] and np.isfinite(th) and np.isnan(sf[k]) and
+                abs(th - ref["sigma_exact"][k]) <= (0.5 + tol) * float(ro.quantum(ref["sigma_exact"][k], "fp16"))):
+            sf[k] = th
+            took += 1
+        followed += took
+        if took == 0:
+            settled = k + 1          # a real difference in rank k: leave it, look no further in this rank
+            if settled == r:
+                return ref

@@ -11,7 +11,7 @@ import ptq_workloads as wl
 from oracle import lopro_oracle as lo
 from oracle import ptq_oracle as orc
 from oracle import r1svd_oracle as ro
-from parity import compare_quantization, to_device
+from parity import compare_quantization, follow_r1svd, to_device
 
 pytestmark = pytest.mark.gpu
 
@@ -77,9 +77,7 @@ def test_one_layer_through_every_stage(bits, capsys):
 
     # ---- each stage against its oracle, fed the GPU's upstream results ---------------------------
     assert np.allclose(s_g, ro.activation_scale(ro.mean_abs_activation(X64)), rtol=1e-12)
-    ref = ro.scaled_r1svd(W64, s_g, S.astype(np.float64), it,
-                          follow={"U_code": U8.cpu().numpy(), "V_code": V8.cpu().numpy(), "sigma": out["sigma"]},
-                          follow_tol=2e-3)
+    ref = follow_r1svd(W64, s_g, S.astype(np.float64), it, U8.cpu().numpy(), V8.cpu().numpy(), out["sigma"], 2e-3)
     assert np.array_equal(ref["U_code"], U8.cpu().numpy()) and np.array_equal(ref["V_code"], V8.cpu().numpy())
     assert np.array_equal(ref["sigma"], out["sigma"]) and ref["followed"] <= 2
     Hg = orc.symmetrize_from_upper(H.cpu().numpy())

@@ -14,7 +14,7 @@ import torch
 import paper_2601_19675_amd as ptq
 import ptq_workloads as wl
 from oracle import r1svd_oracle as ro
-from parity import to_device
+from parity import follow_r1svd, to_device
 
 pytestmark = pytest.mark.gpu
 
@@ -29,13 +29,30 @@ def launch_mode(request, monkeypatch):
     """The loop runs as one cooperative launch -- over tiles where the matrix fits the chip's registers
     (default), over a bfloat16 weight used as it is, kept on the chip in two-dimensional tiles ("resident")
     or streamed in row blocks ("stream"; other types take the next form), or over row blocks of the
-    float32 running matrix ("rows") -- or as one launch per step ("steps"); the library reads
-    PTQ_R1SVD_LAUNCH at every call.  All forms are held to the oracle."""
-    if request.param == "single":
-        monkeypatch.delenv("PTQ_R1SVD_LAUNCH", raising=False)
-    else:
-        monkeypatch.setenv("PTQ_R1SVD_LAUNCH", request.param)
-    return request.param
+    float32 running matrix ("rows") -- or as one launch per step ("steps"); the library's selector for
+    its own tests picks the form.  All forms are held to the oracle."""
+    _select(request.param)
+    yield request.param
+    _select("single")
+
+
+_FORMS = {"single": 0, "resident": 1, "stream": 2, "rows": 3, "steps": 4}
+
+
+def _select(form="single", spin_limit=-1):
+    """The launch form and the spin limit of the bounded waits for all later calls (an exported
+    function of the library that its header deliberately does not declare)."""
+    import ctypes
+    fn = ptq.load_library().ptq_internal_r1svd_select
+    fn.restype = None
+    fn.argtypes = [ctypes.c_int, ctypes.c_longlong]
+    fn(_FORMS[form], spin_limit)
+
+
+@pytest.fixture
+def form_selector():
+    yield _select
+    _select("single")
 
 
 def _dev(a, dtype=None):
@@ -56,15 +73,14 @@ def _run_gpu(Wd, s, S, it):
             R.cpu().numpy().astype(np.float64))
 
 
-def _check(W64, s, S, it, got, max_followed_frac=1e-3):
+def _check(W64, s, S, it, got, max_followed=4):
     Ug, Vg, sg, Rg = got
     r = S.shape[0]
-    ref = ro.scaled_r1svd(W64, s, S.astype(np.float64), it,
-                          follow={"U_code": Ug, "V_code": Vg, "sigma": sg}, follow_tol=FOLLOW_TOL)
+    ref = follow_r1svd(W64, s, S.astype(np.float64), it, Ug, Vg, sg, FOLLOW_TOL, max_followed)
     assert np.array_equal(Ug, ref["U_code"]), f"U codes differ at {np.argwhere(Ug != ref['U_code'])[:5]}"
     assert np.array_equal(Vg, ref["V_code"]), f"V codes differ at {np.argwhere(Vg != ref['V_code'])[:5]}"
     assert np.array_equal(sg, ref["sigma"]), (sg, ref["sigma"])
-    assert ref["followed"] <= max(2, max_followed_frac * (Ug.size + Vg.size)), ref["followed"]
+    assert ref["followed"] <= max_followed, ref["followed"]
     # every float32 rounding of the running matrix costs 2^-24 of the entry's magnitude, which
     # is bounded by |W_s| + sum_k |sigma_k U_k V_k|; r + 1 of them, plus the final division
     bound = np.abs(W64 * s[None, :]) + np.abs(ref["U"]).T @ (np.abs(ref["V"]) * ref["sigma"][:, None])
@@ -108,18 +124,18 @@ def test_r1svd_matches_oracle(dtype, m, n, r, it, launch_mode):
     (520, 1032, 2, 0),     # two ranks without power iteration: the correction enters at once
 ])
 @pytest.mark.parametrize("form", ["resident", "stream"])
-def test_r1svd_bfloat16_forms_shapes(m, n, r, it, form, monkeypatch):
+def test_r1svd_bfloat16_forms_shapes(m, n, r, it, form, form_selector):
     """The forms that use the bfloat16 weight as it is and apply the stored ranks as corrections."""
-    monkeypatch.setenv("PTQ_R1SVD_LAUNCH", form)
+    form_selector(form)
     Ws, W64, s, S = _case(m, n, "bf16", 930 + n, r)
     got = _run_gpu(to_device(Ws), s, S, it)
     _check(W64, s, S, it, got)
 
 
 @pytest.mark.parametrize("form", ["resident", "stream"])
-def test_r1svd_bfloat16_forms_read_a_strided_weight(form, monkeypatch):
+def test_r1svd_bfloat16_forms_read_a_strided_weight(form, form_selector):
     """The weight as a view into a wider buffer (row pitch n + 64): the forms that never copy W must follow it."""
-    monkeypatch.setenv("PTQ_R1SVD_LAUNCH", form)
+    form_selector(form)
     m, n, r, it = 150, 1024, 4, 2
     Ws, W64, s, S = _case(m, n, "bf16", 955, r)
     Wbig = torch.full((m, n + 64), 7.0, dtype=torch.bfloat16, device="cuda")
@@ -290,17 +306,15 @@ def test_r1svd_sigma_beyond_fp16_range(launch_mode):
 
 
 @pytest.mark.parametrize("mode", ["single", "resident", "stream", "rows"])
-def test_r1svd_gives_up_cleanly_when_the_wait_limit_is_reached(mode, monkeypatch):
+def test_r1svd_gives_up_cleanly_when_the_wait_limit_is_reached(mode, form_selector):
     # a wait limit of zero rounds: the first workgroup that finds a partial sum not there yet raises the
     # abort flag, everybody stops waiting, the kernel runs to its end on whatever it has and marks every
     # sigma as NaN; the next ordinary call is unaffected
     Ws, W64, s, S = _case(1024, 1024, "bf16" if mode in ("resident", "stream") else "f32", 1300, 3)
-    if mode != "single":
-        monkeypatch.setenv("PTQ_R1SVD_LAUNCH", mode)
-    monkeypatch.setenv("PTQ_R1SVD_SPIN_LIMIT", "0")
+    form_selector(mode, 0)
     bad = _run_gpu(to_device(Ws), s, S, 2)
     assert np.all(np.isnan(bad[2]))
-    monkeypatch.delenv("PTQ_R1SVD_SPIN_LIMIT")
+    form_selector(mode)
     good = _run_gpu(to_device(Ws), s, S, 2)
     _check(W64, s, S, 2, good)
 

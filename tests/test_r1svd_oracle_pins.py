@@ -220,12 +220,17 @@ def test_forced_codes_replace_single_entries():
     assert np.array_equal(none["A"], base["A"])
 
 
-def test_follow_adopts_only_legitimate_roundings():
+def test_follow_protocol_adopts_only_legitimate_roundings():
+    """The near-tie rule of the parity protocol (tests/parity.py), exercised on the CPU with a made-up
+    'other implementation': the oracle's own results with one code moved to its neighbour."""
+    from parity import follow_r1svd
     rng = np.random.default_rng(26)
     A = rng.standard_normal((16, 12))
     S = rng.standard_normal((2, 12))
+    one = np.ones(12)
     base = ro.r1svd(A, S, 2)
     exact = ro.r1svd(A, S, 2, rounded=False)
+    assert np.array_equal(base["U_exact"][0], exact["U"][0])      # rank 0 sees the same matrix either way
     # the other neighbour of the entry closest to a tie is adopted with a tolerance above its
     # margin, and refused with a tolerance below it; a far-off code is never adopted
     i = int(np.argmin(base["U_margin"][0]))
@@ -236,17 +241,22 @@ def test_follow_adopts_only_legitimate_roundings():
     other = own + q if x > own else own - q
     theirs = {"U_code": base["U_code"].copy(), "V_code": base["V_code"].copy(), "sigma": base["sigma"].copy()}
     theirs["U_code"][0, i] = ro.e4m3_encode(np.array([other]))[0]
-    yes = ro.r1svd(A, S, 2, follow=theirs, follow_tol=mg * 1.01 + 1e-12)
+    yes = follow_r1svd(A, one, S, 2, theirs["U_code"], theirs["V_code"], theirs["sigma"], mg * 1.01 + 1e-12)
     assert yes["followed"] >= 1 and yes["U_code"][0, i] == theirs["U_code"][0, i]
-    no = ro.r1svd(A, S, 2, follow=theirs, follow_tol=mg * 0.5)
-    assert no["U_code"][0, i] == base["U_code"][0, i]
+    no = follow_r1svd(A, one, S, 2, theirs["U_code"], theirs["V_code"], theirs["sigma"], mg * 0.5)
+    assert no["U_code"][0, i] == base["U_code"][0, i] and no["followed"] == 0
     far = {k: v.copy() for k, v in theirs.items()}
     far["U_code"][0, i] = base["U_code"][0, i] ^ 0x20
-    assert ro.r1svd(A, S, 2, follow=far, follow_tol=0.01)["U_code"][0, i] == base["U_code"][0, i]
+    assert follow_r1svd(A, one, S, 2, far["U_code"], far["V_code"], far["sigma"], 0.01)["U_code"][0, i] == \
+        base["U_code"][0, i]
     # following one's own results changes nothing
-    same = ro.r1svd(A, S, 2, follow={"U_code": base["U_code"], "V_code": base["V_code"], "sigma": base["sigma"]},
-                    follow_tol=0.01)
+    same = follow_r1svd(A, one, S, 2, base["U_code"], base["V_code"], base["sigma"], 0.01)
     assert same["followed"] == 0 and np.array_equal(same["A"], base["A"])
+    # a forced sigma is what gets deflated
+    sf = np.array([np.nan, base["sigma"][1] * 1.5])
+    forced = ro.r1svd(A, S, 2, sigma_force=sf)
+    assert forced["sigma"][0] == base["sigma"][0] and forced["sigma"][1] == sf[1]
+    assert np.allclose(forced["A"], base["A"] - (sf[1] - base["sigma"][1]) * np.outer(base["U"][1], base["V"][1]))
 
 
 def test_sigma_beyond_fp16_saturates_and_later_ranks_take_the_rest():
