@@ -384,3 +384,40 @@ def test_static_groups_keep_the_identities_of_the_solve():
     on_grid = orc.dequantize(rtn["codes"], rtn["scales"], rtn["zeros"], group)
     c = orc.quantize_layer(on_grid, U, bits, group, static_groups=True)
     assert np.array_equal(c["Wq"], on_grid)
+
+
+def test_dynamic_grid_is_taken_when_the_walk_enters_the_group_hand_worked():
+    """Pins WHEN a group's grid is taken: from the row's values after every earlier column's error
+    has been pushed onto them and before the group's own first column is quantized.  Worked by hand:
+    2 bits (codes 0..3), groups of 2, four columns, U = I except U[1,3] = 4 (the last column of the
+    first group pushes onto the second group) and U[2,3] = 8 (the second group's first column pushes
+    onto its second).
+
+    row 0: w = (3, 1.25, 1.5, 7)
+      group 0: range [0, 3], scale 1, zero 0.  col 0: code 3, e = 0.  col 1: 1.25 -> code 1, q = 1,
+               e = 0.25, so w3 = 7 - 0.25 * 4 = 6.
+      group 1, taken now: values (1.5, 6) -> range [0, 6], scale 2, zero 0.
+               col 2: 0.75 -> code 1, q = 2, e = -0.5, so w3 = 6 + 0.5 * 8 = 10.
+               col 3: 10 / 2 = 5 -> clamped to code 3, q = 6, e = 4.
+      (from the weights as given the scale would be 7/3; taken one column later, after col 2's
+       push, 10/3.)
+    row 1: w = (-3, -1.25, -0.5, -7)
+      group 0: range [-3, 0], scale 1, zero 3.  col 0: code 0, e = 0.  col 1: -1.25 -> -1 + 3 = 2,
+               q = -1, e = -0.25, so w3 = -7 + 0.25 * 4 = -6.
+      group 1, taken now: values (-0.5, -6) -> range [-6, 0], scale 2, zero 3.
+               col 2: -0.25 -> rounds to -0 -> code 3, q = 0, e = -0.5, so w3 = -6 + 0.5 * 8 = -2.
+               col 3: -2 / 2 = -1 -> code 2, q = -2, e = 0.
+    """
+    W = np.array([[3.0, 1.25, 1.5, 7.0], [-3.0, -1.25, -0.5, -7.0]])
+    U = np.eye(4)
+    U[1, 3] = 4.0
+    U[2, 3] = 8.0
+    out = orc.quantize_layer(W, U, 2, 2)
+    assert out["scales"].tolist() == [[1.0, 2.0], [1.0, 2.0]]
+    assert out["zeros"].tolist() == [[0, 0], [3, 3]]
+    assert out["codes"].tolist() == [[3, 1, 1, 3], [0, 2, 3, 2]]
+    assert out["Wq"].tolist() == [[3.0, 1.0, 2.0, 6.0], [-3.0, -1.0, 0.0, -2.0]]
+    assert out["E"].tolist() == [[0.0, 0.25, -0.5, 4.0], [0.0, -0.25, -0.5, 0.0]]
+    # the static-groups option is the other timing: grids of the weights as given
+    st = orc.quantize_layer(W, U, 2, 2, static_groups=True)
+    assert st["scales"][:, 1].tolist() == [float(np.float32(7.0 / 3.0))] * 2
