@@ -8,7 +8,12 @@ Prints ONE JSON line: metric / value / unit (columns quantized per second for th
 ms_per_step and the per-call times, the Hessian rate, a "roofline" object for the dominant
 kernel and a "cpu_baseline" object (the oracle timed on a sample of the same layer).
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C2] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C3 --layer 1] [--no-cpu-baseline]
+
+Default workload: the 4096 x 11008 down projection of the MLP pair (the widest single layer of
+the 7B shape, the one the metric's columns/s is quoted on).  --config C2 / C4 / C1 and --layer
+select the other layers; --config C5 times the seven linears of a decoder block back to back in
+one timed region.
 """
 from __future__ import annotations
 
@@ -26,47 +31,100 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_F64_TFLOPS = 78.6      # MI355X float64 (vector and matrix)
 HBM_GBPS = 8000.0
 
-# HBM bytes per launch of the dominant kernel (Hessian main kernel), from two rocprofv3 --pmc
-# runs of this file (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter reads
-# for a plain 1 GiB device copy (--copy-calibration): FETCH_SIZE reads 524288 per GiB read
-# (factor 2 KiB per count), WRITE_SIZE 1048576 per GiB written (1 KiB per count).
-# See profiles/hessian_C2_hbm_traffic.txt.  None for workloads that were not profiled.
+# HBM bytes per launch of the dominant kernel (Hessian main kernel).  NOT measured by this run:
+# copied from two separate rocprofv3 --pmc runs of this file (FETCH_SIZE, then WRITE_SIZE), each
+# scaled by what the same counter reads for a plain 1 GiB device copy (--copy-calibration):
+# FETCH_SIZE reads 524288 per GiB read (factor 2 KiB per count), WRITE_SIZE 1048576 per GiB written
+# (1 KiB per count).  The profile file that holds the run is named beside the number; None for
+# workloads that were not profiled.
 MEASURED_TRAFFIC_BYTES = {
-    "C2:attn_proj": 3.655e6 * 2048 + 5.222e5 * 1024,
+    "C2:attn_proj": (3.655e6 * 2048 + 5.222e5 * 1024, "profiles/hessian_C2_hbm_traffic.txt"),
 }
 
 
-def cpu_baseline(cfg, spec, seed):
-    """The oracle, as it stands, on a bounded sample of the same layer; scaled to columns/s."""
+def log(msg):
+    print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
+
+
+def host_cpu_info():
+    """(logical CPUs the OS shows, CPUs this process may run on, physical cores from /proc/cpuinfo or None)."""
+    logical = os.cpu_count() or 1
+    try:
+        usable = len(os.sched_getaffinity(0))
+    except AttributeError:
+        usable = logical
+    physical = None
+    try:
+        cores = set()
+        phys = core = None
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("physical id"):
+                phys = line.split(":")[1].strip()
+            elif line.startswith("core id"):
+                core = line.split(":")[1].strip()
+            elif not line.strip():
+                if phys is not None and core is not None:
+                    cores.add((phys, core))
+                phys = core = None
+        physical = len(cores) or None
+    except OSError:
+        pass
+    return logical, usable, physical
+
+
+def cpu_baseline(cfg, spec, seed, full_factor=True):
+    """The oracle, as it stands, on a bounded sample of the same layer: the Hessian over a prefix of
+    the tokens, the factor of the layer's full n x n matrix (or, with full_factor False, of its leading
+    4096 x 4096 block, scaled by the cube of the size ratio), the solve and the error on the first rows.
+    Each stage is timed on its own; the stage times are scaled linearly in tokens / rows to the full
+    layer and added.  Reported in the metric's unit, columns per second for the whole step."""
     import numpy as np
     from threadpoolctl import threadpool_info
 
     import ptq_workloads as wl
     from oracle import ptq_oracle as orc
 
-    t_s = min(spec.t, 4096)
-    rows_s = min(spec.m, 64)
+    t_s = min(spec.t, 16384)
+    rows_s = min(spec.m, 256)
     Ws = wl.gen_weight(spec, seed)
     X64 = wl.to_f64(wl.gen_activations(spec, seed, 0, t_s))
     W64 = wl.to_f64(Ws)[:rows_s]
     t0 = time.perf_counter()
     H = orc.hessian(X64)
     t1 = time.perf_counter()
-    Hd, dead = orc.damp(H, cfg.damps[0])
-    U = orc.inverse_cholesky_upper(Hd)
+    log(f"cpu baseline: oracle Hessian over {t_s} tokens {t1 - t0:.1f} s")
+    nf = spec.n if (full_factor or spec.n <= 4096) else 4096
+    Hd, dead = orc.damp(H[:nf, :nf], cfg.damps[0])
+    Uf = orc.inverse_cholesky_upper(Hd)
     t2 = time.perf_counter()
+    log(f"cpu baseline: oracle factor of {nf} x {nf} {t2 - t1:.1f} s")
+    factor_s = (t2 - t1) * (spec.n / nf) ** 3
+    if nf == spec.n:
+        U = Uf
+    else:  # the solve needs some upper factor of the right size: the sampled one, extended by the identity
+        U = np.eye(spec.n)
+        U[:nf, :nf] = Uf
+        dead = np.zeros(spec.n, dtype=bool)
     out = orc.quantize_layer(W64, U, cfg.bits, cfg.group, dead=dead)
     t3 = time.perf_counter()
+    log(f"cpu baseline: oracle solve of {rows_s} rows {t3 - t2:.1f} s")
     orc.layer_error(W64, out["Wq"], H)
     t4 = time.perf_counter()
-    est = ((t1 - t0) * spec.t / t_s + (t2 - t1) + (t3 - t2) * spec.m / rows_s + (t4 - t3) * spec.m / rows_s)
+    est = (t1 - t0) * spec.t / t_s + factor_s + (t3 - t2) * spec.m / rows_s + (t4 - t3) * spec.m / rows_s
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    logical, usable, physical = host_cpu_info()
     return {
-        "value": spec.n / est, "unit": "columns/s", "cores": int(threads), "kind": "oracle",
-        "sample": (f"{t_s} of {spec.t} tokens for H, full {spec.n}x{spec.n} factor, {rows_s} of {spec.m} rows "
-                   f"for solve and error; times scaled linearly to the full layer "
-                   f"(H {t1 - t0:.2f}s, factor {t2 - t1:.2f}s, solve {t3 - t2:.2f}s, error {t4 - t3:.2f}s measured)"),
+        "value": spec.n / est, "unit": "columns/s", "cores": int(min(threads, usable)), "kind": "oracle",
+        "sample": (f"{t_s} of {spec.t} tokens for H, "
+                   + (f"the full {spec.n}x{spec.n} factor" if nf == spec.n else
+                      f"the factor of the leading {nf}x{nf} block scaled by ({spec.n}/{nf})^3")
+                   + f", {rows_s} of {spec.m} rows for solve and error; stage times scaled linearly in tokens / rows "
+                     f"to the full layer and added (measured: H {t1 - t0:.2f}s, factor {t2 - t1:.2f}s, "
+                     f"solve {t3 - t2:.2f}s, error {t4 - t3:.2f}s)"),
         "est_seconds_full_layer": est,
+        "measured_seconds": {"hessian": t1 - t0, "factor": t2 - t1, "solve": t3 - t2, "layer_error": t4 - t3},
+        "blas_threads": int(threads), "host_logical_cpus": logical, "host_usable_cpus": usable,
+        "host_physical_cores": physical,
     }
 
 
@@ -245,14 +303,153 @@ def forward_timings(ptq, codes, scales, zeros, m, n, bits, group, rank=16, reps=
     return out
 
 
+class LayerRun:
+    """Device buffers of one layer and one pass of the whole path over them."""
+
+    def __init__(self, ptq, wl, cfg, spec, device_x=False):
+        import torch
+        self.ptq, self.cfg, self.spec = ptq, cfg, spec
+        m, n, t = spec.m, spec.n, spec.t
+        self.m, self.n, self.t = m, n, t
+        self.damp = cfg.damps[0]
+        dev = "cuda"
+        self.W = wl.to_device(wl.gen_weight(spec, cfg.seed))
+        self.X = torch.empty((t, n), dtype=torch.bfloat16 if spec.dtype == "bf16" else torch.float32, device=dev)
+        step_t = 32768
+        if device_x:
+            gen = torch.Generator(device=dev).manual_seed(cfg.seed + spec.layer_id)
+            if spec.x_kind == "student_t":
+                ch_scale = torch.ones(n, device=dev)
+            else:
+                ch_scale = torch.exp(spec.x_sigma * torch.randn(n, device=dev, generator=gen))
+            for lo in range(0, t, step_t):
+                z = torch.randn((min(t, lo + step_t) - lo, n), device=dev, generator=gen)
+                if spec.x_kind == "student_t":
+                    chi = sum(torch.randn(z.shape, device=dev, generator=gen).square_() for _ in range(3)) / 3.0
+                    z = z / chi.sqrt_()
+                self.X[lo:lo + step_t] = (z * ch_scale).to(self.X.dtype)
+            del z
+        else:
+            for lo in range(0, t, step_t):          # generate on the host in slabs, upload
+                self.X[lo:lo + step_t] = wl.to_device(wl.gen_activations(spec, cfg.seed, lo, min(t, lo + step_t)))
+        self.H = torch.zeros((n, n), dtype=torch.float64, device=dev)
+        self.U = torch.empty((n, n), dtype=torch.float64, device=dev)
+        self.dead = torch.empty((n,), dtype=torch.uint8, device=dev)
+        self.info = torch.empty((2,), dtype=torch.int32, device=dev)
+        self.codes = torch.empty((m, n), dtype=torch.uint8, device=dev)
+        self.scales = torch.empty((m, n // cfg.group), dtype=torch.float32, device=dev)
+        self.zeros = torch.empty((m, n // cfg.group), dtype=torch.uint8, device=dev)
+        self.Wq = torch.empty((m, n), dtype=torch.float64, device=dev)
+        self.err2 = torch.empty((m,), dtype=torch.float64, device=dev)
+        self.out = torch.zeros(3, dtype=torch.float64, device=dev)
+        self.ws_bytes = max(ptq.ptq_workspace_bytes(op, m, n, t, cfg.block) for op in range(6))
+        self.ws = None
+
+    def step(self, ev=None):
+        ptq, cfg = self.ptq, self.cfg
+        self.H.zero_()
+        if ev: ev[0].record()
+        ptq.ptq_hessian_accumulate(self.H, self.X, self.ws)
+        if ev: ev[1].record()
+        ptq.ptq_damped_cholesky_inv(self.H, self.damp, self.U, self.dead, self.info, self.ws)
+        if ev: ev[2].record()
+        ptq.ptq_quantize_layer(self.W, self.U, self.dead, cfg.bits, cfg.group, cfg.block, self.codes, self.scales,
+                               self.zeros, self.Wq, self.err2, self.ws)
+        if ev: ev[3].record()
+        ptq.ptq_layer_error(self.W, self.Wq, self.H, self.out, self.ws)
+        if ev: ev[4].record()
+
+    def label(self, name):
+        s, c = self.spec, self.cfg
+        return (f"{name}:{s.name} W {s.m}x{s.n} {s.dtype}, X {s.t}x{s.n} {s.dtype}, "
+                f"{c.bits}-bit asym group {c.group} block {c.block} damp {self.damp}")
+
+
+def time_layers(layers, steps, warmup):
+    """W untimed passes, then exactly `steps` timed passes over all the layers, one after the other on
+    the current stream; returns (ms per pass by the host clock around synchronised ends, per-layer
+    per-call event times in ms averaged over the passes)."""
+    import torch
+    n_ev = 5
+    events = [[[torch.cuda.Event(enable_timing=True) for _ in range(n_ev)] for _ in layers] for _ in range(steps)]
+    for _ in range(warmup):
+        for L in layers:
+            L.step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(steps):
+        for i, L in enumerate(layers):
+            L.step(events[k][i])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    for L in layers:
+        assert L.info.cpu().tolist() == [0, 0], "factorization failed"
+    phases = [[sum(events[k][i][j].elapsed_time(events[k][i][j + 1]) for k in range(steps)) / steps
+               for j in range(n_ev - 1)] for i in range(len(layers))]
+    return 1e3 * elapsed / steps, phases
+
+
+def layer_numbers(L, phase):
+    """Rates of one layer's four calls from their event-bracketed times."""
+    m, n, t, cfg, spec = L.m, L.n, L.t, L.cfg, L.spec
+    h_ms, f_ms, q_ms, e_ms = phase
+    syrk_flops = float(t) * n * (n + 1)           # algorithmic: upper triangle incl. diagonal
+    h_tflops = syrk_flops / (h_ms * 1e-3) / 1e12
+    f_flops = 2.0 / 3.0 * float(n) ** 3
+    q_flops = float(m) * n * n
+    pieces = 9.0 if spec.dtype == "bf16" else 12.0
+    e_exec = pieces * m * n * (n + 128.0)         # piece products the kernel executes on the bf16 MFMA
+    e_alg = 2.0 * m * n * (n + 128.0)             # the two traces of the method itself
+    peak_f64 = PEAK_F64_TFLOPS
+    return {
+        "phases_ms": {"hessian": h_ms, "factor": f_ms, "quantize": q_ms, "layer_error": e_ms},
+        "hessian_tflops_syrk": h_tflops,
+        "hessian_tflops_full_square": 2.0 * t * n * n / (h_ms * 1e-3) / 1e12,
+        "hessian_pct_mfma_peak": 100.0 * h_tflops / PEAK_BF16_TFLOPS,
+        "solve_columns_per_s": n / ((f_ms + q_ms) * 1e-3),
+        "quantize_columns_per_s": n / (q_ms * 1e-3),
+        "quantize_tflops_f64": q_flops / (q_ms * 1e-3) / 1e12,
+        # W in, codes + Wq out, the upper triangle of U, the grids: what the column walk has to move
+        "quantize_algorithmic_gbps": (float(m) * n * (L.W.element_size() + 1 + 8) + 4.0 * n * n
+                                      + 5.0 * m * n / cfg.group) / (q_ms * 1e-3) / 1e9,
+        "syrk_flops": syrk_flops,
+        # the other three calls against the peak of the unit that bounds them: algorithmic flops of the call over
+        # its event-bracketed time; for the layer error both the method's own two traces and the bf16 piece
+        # products the kernel executes to form them at float32 precision
+        "rooflines_other_calls": [
+            {"call": "ptq_damped_cholesky_inv", "bound": "mfma", "dtype": "f64",
+             "achieved": f_flops / (f_ms * 1e-3) / 1e12, "peak": peak_f64, "unit": "TFLOP/s",
+             "frac": f_flops / (f_ms * 1e-3) / 1e12 / peak_f64},
+            {"call": "ptq_quantize_layer", "bound": "mfma", "dtype": "f64",
+             "achieved": q_flops / (q_ms * 1e-3) / 1e12, "peak": peak_f64, "unit": "TFLOP/s",
+             "frac": q_flops / (q_ms * 1e-3) / 1e12 / peak_f64},
+            {"call": "ptq_layer_error", "bound": "mfma", "dtype": "bf16",
+             "achieved": e_alg / (e_ms * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+             "frac": e_alg / (e_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+             "flops_counted": "algorithmic: the two traces, 2 m n (n + 128)",
+             "executed_piece_products_tflops": e_exec / (e_ms * 1e-3) / 1e12,
+             "executed_frac": e_exec / (e_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS},
+        ],
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", default="C2")
-    ap.add_argument("--layer", type=int, default=0)
+    ap.add_argument("--config", default="C3", help="C1..C4: one layer of that configuration (see --layer); "
+                    "C5: the seven linears of a decoder block as one timed region")
+    ap.add_argument("--layer", type=int, default=None,
+                    help="index of the layer inside the configuration (default: the last one, which for C3 is the "
+                         "4096 x 11008 down projection)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-baseline-factor-sample", action="store_true",
+                    help="time the oracle's factor on the leading 4096 x 4096 block and scale by the cube of the size "
+                         "ratio instead of factoring the layer's full matrix (n = 11008: about a minute and a half)")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the short extra timing of the 4096 x 4096 attention projection (C2) that the default "
+                         "run reports under \"other_workloads\"")
     ap.add_argument("--lopro", action="store_true",
                     help="also time LoPRo's pre-conditioning of the same layer (column order, rotation of W and H, "
                          "way back; b_I = b_H = 256) and report it under \"lopro\"; the step itself is unchanged")
@@ -264,7 +461,7 @@ def main():
                          "rank-16 low-rank part) and report it under \"forward\"")
     ap.add_argument("--device-x", action="store_true",
                     help="draw the activations on the GPU (same distribution family, torch generator) instead of "
-                         "the seeded host generator: for timing the widest layers, whose host generation takes minutes")
+                         "the seeded host generator")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run plain 1 GiB device copies and exit (reference reading for the "
                          "FETCH_SIZE / WRITE_SIZE counters under rocprofv3 --pmc)")
@@ -278,9 +475,6 @@ def main():
 
     import paper_2601_19675_amd as ptq
     import ptq_workloads as wl
-
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
-    from parity import to_device
 
     if not os.path.exists(ptq.lib_path()):
         from paper_2601_19675_amd import build
@@ -298,132 +492,88 @@ def main():
         return
 
     cfg = wl.CONFIGS[args.config]
-    spec = cfg.layers[args.layer]
-    m, n, t = spec.m, spec.n, spec.t
-    damp = cfg.damps[0]
-    W = to_device(wl.gen_weight(spec, cfg.seed))
-    X = torch.empty((t, n), dtype=torch.bfloat16 if spec.dtype == "bf16" else torch.float32, device="cuda")
-    step_t = 32768
-    if args.device_x:
-        gen = torch.Generator(device="cuda").manual_seed(cfg.seed)
-        if spec.x_kind == "student_t":
-            ch_scale = torch.ones(n, device="cuda")
-        else:
-            ch_scale = torch.exp(spec.x_sigma * torch.randn(n, device="cuda", generator=gen))
-        for lo in range(0, t, step_t):
-            z = torch.randn((min(t, lo + step_t) - lo, n), device="cuda", generator=gen)
-            if spec.x_kind == "student_t":
-                chi = sum(torch.randn_like(z).square_() for _ in range(3)) / 3.0
-                z = z / chi.sqrt_()
-            X[lo:lo + step_t] = (z * ch_scale).to(X.dtype)
-        del z
-    else:
-        for lo in range(0, t, step_t):          # generate on the host in slabs, upload
-            X[lo:lo + step_t] = to_device(wl.gen_activations(spec, cfg.seed, lo, min(t, lo + step_t)))
-
-    dev = "cuda"
-    H = torch.zeros((n, n), dtype=torch.float64, device=dev)
-    U = torch.empty((n, n), dtype=torch.float64, device=dev)
-    dead = torch.empty((n,), dtype=torch.uint8, device=dev)
-    info = torch.empty((2,), dtype=torch.int32, device=dev)
-    codes = torch.empty((m, n), dtype=torch.uint8, device=dev)
-    scales = torch.empty((m, n // cfg.group), dtype=torch.float32, device=dev)
-    zeros = torch.empty((m, n // cfg.group), dtype=torch.uint8, device=dev)
-    Wq = torch.empty((m, n), dtype=torch.float64, device=dev)
-    err2 = torch.empty((m,), dtype=torch.float64, device=dev)
-    out = torch.zeros(3, dtype=torch.float64, device=dev)
-    ws_bytes = max(ptq.ptq_workspace_bytes(op, m, n, t, cfg.block) for op in range(6))
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
-
-    n_ev = 5
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(n_ev)] for _ in range(args.steps)]
-
-    def step(ev=None):
-        H.zero_()
-        if ev: ev[0].record()
-        ptq.ptq_hessian_accumulate(H, X, ws)
-        if ev: ev[1].record()
-        ptq.ptq_damped_cholesky_inv(H, damp, U, dead, info, ws)
-        if ev: ev[2].record()
-        ptq.ptq_quantize_layer(W, U, dead, cfg.bits, cfg.group, cfg.block, codes, scales, zeros, Wq, err2, ws)
-        if ev: ev[3].record()
-        ptq.ptq_layer_error(W, Wq, H, out, ws)
-        if ev: ev[4].record()
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for k in range(args.steps):
-        step(events[k])
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    assert info.cpu().tolist() == [0, 0], "factorization failed"
-
-    ms = 1e3 * elapsed / args.steps
-    phase = [sum(events[k][i].elapsed_time(events[k][i + 1]) for k in range(args.steps)) / args.steps
-             for i in range(n_ev - 1)]
-    h_ms, f_ms, q_ms, e_ms = phase
-    syrk_flops = float(t) * n * (n + 1)           # algorithmic: upper triangle incl. diagonal
-    h_tflops = syrk_flops / (h_ms * 1e-3) / 1e12
-    rel = float(out[0])
+    block_mode = args.config == "C5" and args.layer is None
+    specs = list(cfg.layers) if block_mode else [cfg.layers[args.layer if args.layer is not None else -1]]
+    layers = []
+    for spec in specs:
+        log(f"generating inputs of {spec.name} {spec.m}x{spec.n}, X {spec.t}x{spec.n}")
+        layers.append(LayerRun(ptq, wl, cfg, spec, args.device_x))
+    ws = torch.empty(max(L.ws_bytes for L in layers), dtype=torch.uint8, device="cuda")
+    for L in layers:
+        L.ws = ws
+    log("timing")
+    ms, phases = time_layers(layers, args.steps, args.warmup)
+    total_cols = sum(L.n for L in layers)
+    # the layer whose Hessian call is the longest carries the roofline object (a block: the down projection)
+    dom = max(range(len(layers)), key=lambda i: phases[i][0])
+    L, spec = layers[dom], layers[dom].spec
+    m, n, t = L.m, L.n, L.t
+    nums = layer_numbers(L, phases[dom])
+    h_ms, f_ms, q_ms, e_ms = phases[dom]
+    traffic = MEASURED_TRAFFIC_BYTES.get(f"{args.config}:{spec.name}", (None, None))
 
     result = {
         "metric": "layer-solve columns quantized/sec + Hessian TFLOP/s (% MFMA peak), 1 GPU",
-        "value": n / (ms * 1e-3), "unit": "columns/s", "n_gpus": 1, "steps": args.steps,
+        "value": total_cols / (ms * 1e-3), "unit": "columns/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16,f32,f64" if spec.dtype == "bf16" else "f32,f64", "data": "synthetic (device-drawn activations)" if args.device_x else "synthetic",
-        "config": {"workload": f"{args.config}:{spec.name} W {m}x{n} {spec.dtype}, X {t}x{n} {spec.dtype}, "
-                               f"{cfg.bits}-bit asym group {cfg.group} block {cfg.block} damp {damp}"},
-        "phases_ms": {"hessian": h_ms, "factor": f_ms, "quantize": q_ms, "layer_error": e_ms},
-        "hessian_tflops_syrk": h_tflops,
-        "hessian_tflops_full_square": 2.0 * t * n * n / (h_ms * 1e-3) / 1e12,
-        "hessian_pct_mfma_peak": 100.0 * h_tflops / PEAK_BF16_TFLOPS,
-        "solve_columns_per_s": n / ((f_ms + q_ms) * 1e-3),
-        "quantize_columns_per_s": n / (q_ms * 1e-3),
-        "quantize_tflops_f64": float(m) * n * n / (q_ms * 1e-3) / 1e12,
-        # W in, codes + Wq out, the upper triangle of U, the grids: what the column walk has to move
-        "quantize_algorithmic_gbps": (float(m) * n * (W.element_size() + 1 + 8) + 4.0 * n * n
-                                      + 5.0 * m * n / cfg.group) / (q_ms * 1e-3) / 1e9,
-        "rel_layer_error": rel,
-        "roofline": {
-            "kernel": "ptq_hessian_accumulate (Hessian MFMA kernel + partial-tile reduction)",
-            "bound": "mfma", "achieved": h_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-            "frac": h_tflops / PEAK_BF16_TFLOPS,
-            "traffic": MEASURED_TRAFFIC_BYTES.get(f"{args.config}:{spec.name}"),
-            "algorithmic_flops_per_launch": syrk_flops, "algorithmic_bytes_per_launch": 2.0 * t * n,
-        },
+        "vs_baseline": None, "dtype": "bf16,f32,f64" if spec.dtype == "bf16" else "f32,f64",
+        "data": "synthetic (device-drawn activations)" if args.device_x else "synthetic",
+        "config": {"workload": (f"C5: decoder block, 7 linears back to back ({total_cols} columns; each layer its own "
+                                f"X {t} tokens), {cfg.bits}-bit asym group {cfg.group} block {cfg.block} damp {L.damp}"
+                                if block_mode else L.label(args.config))},
     }
-    # the other three calls against the peak of the unit that bounds them (algorithmic flops of the call
-    # over its event-bracketed time; the layer error counts the piece products it executes on the bf16 MFMA)
-    f_flops = 2.0 / 3.0 * float(n) ** 3
-    q_flops = float(m) * n * n
-    pieces = 9.0 if spec.dtype == "bf16" else 12.0
-    e_flops = pieces * m * n * (n + 128.0)
-    result["rooflines_other_calls"] = [
-        {"call": "ptq_damped_cholesky_inv", "bound": "mfma", "dtype": "f64", "achieved": f_flops / (f_ms * 1e-3) / 1e12,
-         "peak": PEAK_F64_TFLOPS, "unit": "TFLOP/s", "frac": f_flops / (f_ms * 1e-3) / 1e12 / PEAK_F64_TFLOPS},
-        {"call": "ptq_quantize_layer", "bound": "mfma", "dtype": "f64", "achieved": q_flops / (q_ms * 1e-3) / 1e12,
-         "peak": PEAK_F64_TFLOPS, "unit": "TFLOP/s", "frac": q_flops / (q_ms * 1e-3) / 1e12 / PEAK_F64_TFLOPS},
-        {"call": "ptq_layer_error", "bound": "mfma", "dtype": "bf16", "achieved": e_flops / (e_ms * 1e-3) / 1e12,
-         "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": e_flops / (e_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS},
-    ]
+    for k in ("phases_ms", "hessian_tflops_syrk", "hessian_tflops_full_square", "hessian_pct_mfma_peak",
+              "solve_columns_per_s", "quantize_columns_per_s", "quantize_tflops_f64", "quantize_algorithmic_gbps"):
+        result[k] = nums[k]
+    result["rel_layer_error"] = float(L.out[0])
+    result["roofline"] = {
+        "kernel": "ptq_hessian_accumulate (Hessian MFMA kernel + partial-tile reduction)"
+                  + (f" of {spec.name} {m}x{n}" if block_mode else ""),
+        "bound": "mfma", "achieved": nums["hessian_tflops_syrk"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+        "frac": nums["hessian_tflops_syrk"] / PEAK_BF16_TFLOPS,
+        "traffic": traffic[0], "traffic_source": traffic[1],
+        "algorithmic_flops_per_launch": nums["syrk_flops"], "algorithmic_bytes_per_launch": 2.0 * t * n,
+    }
+    result["rooflines_other_calls"] = nums["rooflines_other_calls"]
+    if block_mode:
+        result["layers"] = [dict(name=Li.spec.name, m=Li.m, n=Li.n, rel_layer_error=float(Li.out[0]),
+                                 **{k: v for k, v in layer_numbers(Li, ph).items()
+                                    if k in ("phases_ms", "hessian_pct_mfma_peak", "solve_columns_per_s")})
+                            for Li, ph in zip(layers, phases)]
     # the solve against its floors (bytes at the HBM rate, flops at the float64 peak), and what its
     # serial part costs: n columns at the per-column time of a call that is nothing but the walk
-    q_bytes = float(m) * n * (W.element_size() + 1 + 8) + 4.0 * n * n + 5.0 * m * n / cfg.group
+    q_bytes = float(m) * n * (L.W.element_size() + 1 + 8) + 4.0 * n * n + 5.0 * m * n / cfg.group
     t_col_us = single_block_us_per_column(ptq, cfg.bits, cfg.group)
     floors = {"hbm_ms": q_bytes / (HBM_GBPS * 1e9) * 1e3, "f64_ms": float(m) * n * n / (PEAK_F64_TFLOPS * 1e12) * 1e3}
     result["quantize_floors"] = dict(floors, frac_of_largest_floor=max(floors.values()) / q_ms,
                                      single_block_us_per_column=t_col_us, walk_ms_upper_estimate=n * t_col_us * 1e-3)
     if args.lopro:
-        result["lopro"] = lopro_timings(ptq, W, H, m, n, ws)
+        result["lopro"] = lopro_timings(ptq, L.W, L.H, m, n, ws)
     if args.r1svd:
-        result["r1svd"] = r1svd_timings(ptq, W, X, m, n, t)
+        result["r1svd"] = r1svd_timings(ptq, L.W, L.X, m, n, t)
     if args.forward:
-        result["forward"] = forward_timings(ptq, codes, scales, zeros, m, n, cfg.bits, cfg.group)
+        result["forward"] = forward_timings(ptq, L.codes, L.scales, L.zeros, m, n, cfg.bits, cfg.group)
+    main_is_headline = (args.config == "C3" and not block_mode and spec.name == "down_proj")
+    del layers, L, ws
+    torch.cuda.empty_cache()
+    if main_is_headline and not args.no_other_workloads:
+        # the 4096 x 4096 attention projection (second configuration), a few passes, for comparison across runs
+        cfg2 = wl.CONFIGS["C2"]
+        log("generating inputs of C2 attn_proj for the extra timing")
+        L2 = LayerRun(ptq, wl, cfg2, cfg2.layers[0], args.device_x)
+        L2.ws = torch.empty(L2.ws_bytes, dtype=torch.uint8, device="cuda")
+        ms2, ph2 = time_layers([L2], max(3, args.steps // 2), 2)
+        n2 = layer_numbers(L2, ph2[0])
+        result["other_workloads"] = {L2.label("C2"): {
+            "ms_per_step": ms2, "columns_per_s": L2.n / (ms2 * 1e-3), "phases_ms": n2["phases_ms"],
+            "hessian_pct_mfma_peak": n2["hessian_pct_mfma_peak"], "solve_columns_per_s": n2["solve_columns_per_s"],
+            "quantize_tflops_f64": n2["quantize_tflops_f64"]}}
+        del L2
+        torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(cfg, spec, cfg.seed)
-    print(json.dumps(result))
+        log("cpu baseline (oracle on the host cores)")
+        result["cpu_baseline"] = cpu_baseline(cfg, spec, cfg.seed, full_factor=not args.cpu_baseline_factor_sample)
+    print(json.dumps(result), flush=True)
 
 
 if __name__ == "__main__":

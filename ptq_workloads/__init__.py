@@ -59,6 +59,15 @@ def to_f64(a: np.ndarray) -> np.ndarray:
     return a.astype(np.float64)
 
 
+def to_device(a: np.ndarray):
+    """Stored numpy tensor (uint16 = bfloat16 bits, float32, float64, uint8) -> torch tensor on the
+    current GPU holding the same bits (uint16 becomes torch.bfloat16)."""
+    import torch
+    if a.dtype == np.uint16:
+        return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
 def store(a64: np.ndarray, dtype: str) -> np.ndarray:
     if dtype == "f32":
         return a64.astype(np.float32)
