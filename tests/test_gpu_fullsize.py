@@ -22,7 +22,7 @@ import torch
 import paper_2601_19675_amd as ptq
 import ptq_workloads as wl
 from oracle import ptq_oracle as orc
-from parity import compare_quantization, hessian_errors, to_device
+from parity import compare_quantization, hessian_errors, oracle_solve_rows, to_device
 
 pytestmark = pytest.mark.gpu
 
@@ -74,9 +74,25 @@ class GpuLayer:
         return self.out.cpu().numpy()
 
 
-def stagewise(capsys, spec, bits, group, block, damps, t_test, n_rows=48, seed=wl.BASE_SEED, static_too=False):
+def sample_rows(m, n_rows, seed):
+    """Rows to hold against the oracle: a random sample, plus one whole aligned run of 48 rows and the
+    last 48 rows of the layer, so that every position inside a workgroup's row tile (16, 32 or 48 rows)
+    and the layer's last, possibly partial, tile occur."""
+    rng = np.random.default_rng(seed)
+    rows = set(rng.choice(m, min(m, n_rows), replace=False).tolist())
+    if m > 96:
+        lo = 48 * int(rng.integers(0, m // 48 - 1))
+        rows.update(range(lo, lo + 48))
+        rows.update(range(m - 48, m))
+    rows.update((0, m - 1))
+    return np.array(sorted(rows))
+
+
+def stagewise(capsys, spec, bits, group, block, damps, t_test, n_rows=48, seed=wl.BASE_SEED, static_too=False,
+              all_rows_damp=None):
     """Every stage on the GPU at the layer's full m x n, each fed the oracle's
-    upstream result computed from the first t_test tokens."""
+    upstream result computed from the first t_test tokens.  The column solve is compared on a
+    sample of rows (see sample_rows), or on every row for the damping value `all_rows_damp`."""
     m, n = spec.m, spec.n
     sub = wl.scaled(spec, t=t_test)
     Ws, Xs = wl.gen_weight(sub, seed), wl.gen_activations(sub, seed)
@@ -88,10 +104,9 @@ def stagewise(capsys, spec, bits, group, block, damps, t_test, n_rows=48, seed=w
     fro, ent = hessian_errors(g.H.cpu().numpy(), Href)
     assert fro <= 1e-5 and ent <= 1e-5, (fro, ent)
     Hdev = torch.from_numpy(np.triu(Href)).cuda()
-    rng = np.random.default_rng(n + m + bits)
-    rows = np.sort(rng.choice(m, n_rows, replace=False))
-    rows[0], rows[-1] = 0, m - 1
+    some_rows = sample_rows(m, n_rows, n + m + bits)
     for damp in damps:
+        rows = np.arange(m) if damp == all_rows_damp else some_rows
         Hd, dead = orc.damp(Href, damp)
         Uref = orc.inverse_cholesky_upper(Hd)
         say(capsys, f"  damp {damp}: oracle factor done")
@@ -102,7 +117,7 @@ def stagewise(capsys, spec, bits, group, block, damps, t_test, n_rows=48, seed=w
         g.quantize(bits, block, U=Udev)
         codes, scales, zeros = g.codes.cpu().numpy(), g.scales.cpu().numpy(), g.zeros.cpu().numpy()
         rep = compare_quantization(W64[rows], Uref, bits, group, None, codes[rows], scales[rows], zeros[rows])
-        say(capsys, f"  damp {damp}: H err {fro:.1e}, U err {du:.1e}, sampled rows exact {rep['exact_rows']}/{n_rows}, "
+        say(capsys, f"  damp {damp}: H err {fro:.1e}, U err {du:.1e}, compared rows exact {rep['exact_rows']}/{len(rows)}, "
                     f"flagged c/z/s {rep['flagged_codes']}/{rep['flagged_zeros']}/{rep['flagged_scales']}, "
                     f"unflagged {rep['unflagged']}")
         assert rep["unflagged"] == 0, rep["details"][:5]
@@ -126,9 +141,10 @@ def stagewise(capsys, spec, bits, group, block, damps, t_test, n_rows=48, seed=w
                                              g.err2)
         torch.cuda.synchronize()
         codes, scales, zeros = g.codes.cpu().numpy(), g.scales.cpu().numpy(), g.zeros.cpu().numpy()
+        rows = some_rows
         rep = compare_quantization(W64[rows], Uref, bits, group, None, codes[rows], scales[rows], zeros[rows],
                                    static_groups=True)
-        say(capsys, f"  static groups: sampled rows exact {rep['exact_rows']}/{n_rows}, flagged c/z/s "
+        say(capsys, f"  static groups: compared rows exact {rep['exact_rows']}/{len(rows)}, flagged c/z/s "
                     f"{rep['flagged_codes']}/{rep['flagged_zeros']}/{rep['flagged_scales']}, unflagged {rep['unflagged']}")
         assert rep["unflagged"] == 0, rep["details"][:5]
         assert rep["flagged_codes"] + rep["flagged_zeros"] + rep["flagged_scales"] <= 2
@@ -143,28 +159,33 @@ def test_config2_attention_projection_stagewise(capsys):
 
 
 def test_config4_two_bit_damp_sweep(capsys):
+    """2-bit codes, groups of 64, blocks of 256, three damping values; every one of the 4096 rows is held
+    against the oracle at damp 0.01, a sample at the other two."""
     cfg = wl.CONFIGS["C4"]
-    stagewise(capsys, cfg.layers[0], cfg.bits, cfg.group, cfg.block, cfg.damps, t_test=8192)
+    stagewise(capsys, cfg.layers[0], cfg.bits, cfg.group, cfg.block, cfg.damps, t_test=8192, n_rows=128,
+              all_rows_damp=0.01)
 
 
-def test_config3_up_proj_stagewise(capsys):
+def test_config3_up_proj_stagewise_all_rows(capsys):
+    """3-bit codes of the 11008 x 4096 up projection: every row against the oracle."""
     cfg = wl.CONFIGS["C3"]
-    stagewise(capsys, cfg.layers[0], cfg.bits, cfg.group, cfg.block, cfg.damps, t_test=8192)
+    stagewise(capsys, cfg.layers[0], cfg.bits, cfg.group, cfg.block, cfg.damps, t_test=8192,
+              all_rows_damp=cfg.damps[0])
 
 
 def test_config3_down_proj_stagewise(capsys):
     cfg = wl.CONFIGS["C3"]
-    stagewise(capsys, cfg.layers[1], cfg.bits, cfg.group, cfg.block, cfg.damps, t_test=12288, n_rows=24)
+    stagewise(capsys, cfg.layers[1], cfg.bits, cfg.group, cfg.block, cfg.damps, t_test=12288, n_rows=160)
 
 
 def test_config5_decoder_block(capsys):
-    """The seven linears one after another.  The six with 4096 input channels
-    go through the stage-wise protocol; down_proj (whose shape the test above
-    covers against the oracle) runs the whole GPU chain and is checked through
-    the identities that hold at any size."""
+    """The seven linears one after another, each through the stage-wise protocol (the down projection with
+    the oracle's 11008 x 11008 factor), and the down projection once more as the whole GPU chain, checked
+    through the identities that hold at any size."""
     cfg = wl.CONFIGS["C5"]
     for spec in cfg.layers[:6]:
-        stagewise(capsys, spec, cfg.bits, cfg.group, cfg.block, cfg.damps, t_test=4096, n_rows=16)
+        stagewise(capsys, spec, cfg.bits, cfg.group, cfg.block, cfg.damps, t_test=4096, n_rows=64)
+    stagewise(capsys, cfg.layers[6], cfg.bits, cfg.group, cfg.block, cfg.damps, t_test=12288, n_rows=96)
     spec = wl.scaled(cfg.layers[6], t=16384)
     Ws, Xs = wl.gen_weight(spec), wl.gen_activations(spec)
     g = GpuLayer(Ws, spec.n, cfg.group)
@@ -186,6 +207,35 @@ def test_config5_decoder_block(capsys):
     lhs = np.einsum("ij,ij->i", D @ Hd, D)
     assert np.allclose(lhs, g.err2.cpu().numpy(), rtol=1e-7, atol=0)
     assert 0 < rel < 1
+
+
+def test_hessian_headline_shape_long_float32_runs(capsys):
+    """The 4096 x 11008 down projection's Hessian the way bench.py issues it: for layers this wide a
+    workgroup sums up to 65536 tokens in float32 before the float64 reduction.  First exactly one such
+    run (65536 tokens in one call), then all 262144 heavy-tailed tokens in one call, each against the
+    directly computed float64 Gram matrix of 48 sampled channels."""
+    spec = wl.CONFIGS["C3"].layers[1]
+    Xs = wl.gen_activations(spec)
+    say(capsys, f"generated X {spec.t} x {spec.n}")
+    X = to_device(Xs)
+    ch = np.sort(np.random.default_rng(2).choice(spec.n, 48, replace=False))
+    ch[0], ch[-1] = 0, spec.n - 1
+    Xc = wl.to_f64(np.ascontiguousarray(Xs[:, ch]))
+    del Xs
+    H = torch.zeros((spec.n, spec.n), dtype=torch.float64, device="cuda")
+    idx = torch.from_numpy(ch).cuda()
+    for tokens in (65536, spec.t):
+        H.zero_()
+        ptq.ptq_hessian_accumulate(H, X[:tokens])
+        torch.cuda.synchronize()
+        Hs = H[idx][:, idx].cpu().numpy()
+        Gref = Xc[:tokens].T @ Xc[:tokens]
+        fro, ent = hessian_errors(Hs, Gref)
+        say(capsys, f"H of {tokens} tokens x {spec.n} channels, 48 sampled channels: frobenius {fro:.2e}, "
+                    f"scaled entry-wise {ent:.2e}")
+        assert fro <= 1e-5 and ent <= 1e-5
+    del X, H
+    torch.cuda.empty_cache()
 
 
 def test_hessian_all_tokens_sampled_channels(capsys):
@@ -236,9 +286,16 @@ def test_config2_end_to_end_all_tokens(capsys):
     du = np.max(np.abs(g.U.cpu().numpy() - Uref)) / np.max(np.abs(Uref))
     say(capsys, f"oracle factor done; H err {fro:.1e}/{ent:.1e}, U (from GPU H) vs oracle U {du:.1e}")
     assert du <= 1e-5
-    o = orc.quantize_layer(W64, Uref, cfg.bits, cfg.group)
+    o = oracle_solve_rows(W64, Uref, cfg.bits, cfg.group)
     rel_ref = orc.layer_error(W64, o["Wq"], Href)[0]
     codes = g.codes.cpu().numpy()
+    # with the factor the GPU itself produced, the solve meets the bit-exact bar on every row
+    rep = compare_quantization(W64, g.U.cpu().numpy(), cfg.bits, cfg.group, g.dead.cpu().numpy().astype(bool), codes,
+                               g.scales.cpu().numpy(), g.zeros.cpu().numpy())
+    say(capsys, f"solve with the GPU's own factor vs oracle on it: rows exact {rep['exact_rows']}/{spec.m}, flagged c/z/s "
+                f"{rep['flagged_codes']}/{rep['flagged_zeros']}/{rep['flagged_scales']}, unflagged {rep['unflagged']}")
+    assert rep["unflagged"] == 0, rep["details"][:5]
+    assert rep["flagged_codes"] + rep["flagged_zeros"] + rep["flagged_scales"] <= 4
     agree = float(np.mean(codes == o["codes"]))
     rows_same = int(np.sum(np.all(codes == o["codes"], axis=1)))
     # the GPU's own quantized weights judged by the oracle's error routine and Hessian
