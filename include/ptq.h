@@ -375,6 +375,27 @@ ptq_status ptq_lopro_linear_forward(const void* X, ptq_dtype xdt, int64_t ldx, i
                                     int r, const double* s, float* O, int64_t ldo, void* ws,
                                     size_t ws_bytes, ptq_stream stream);
 
+/*
+ * ptq_lopro_linear_forward for callers that cannot allocate device memory or pass a workspace
+ * along: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, results and errors as ptq_lopro_linear_forward, without the workspace: the
+ * scratch memory (rotated input, low-rank coefficients, partial sums, row-block counters) is a
+ * fixed array of ptq_lopro_linear_forward_static_limit() bytes (32 MiB) that is part of the
+ * library's device code, one copy per GPU, held until the process ends.  The call allocates and
+ * frees nothing.  A problem whose PTQ_OP_LINEAR_FORWARD workspace size exceeds the limit is
+ * refused with PTQ_ERR_WORKSPACE (the limit covers, e.g., 11008 x 4096 and 4096 x 11008 layers
+ * with up to 64 tokens).  All calls on one GPU share that GPU's array: calls that overlap on one
+ * GPU (different streams, or different host threads) race and must be serialised by the caller;
+ * calls on different GPUs are independent.  What has to start at zero is cleared by the call's
+ * own kernels on `stream`.
+ */
+size_t ptq_lopro_linear_forward_static_limit(void);
+ptq_status ptq_lopro_linear_forward_static(const void* X, ptq_dtype xdt, int64_t ldx, int64_t tokens, int64_t m,
+                                           int64_t n, const uint32_t* packed, int bits, const float* scales_t,
+                                           const uint8_t* zeros_t, int group, const int32_t* perm, int b_I,
+                                           int b_H, const uint8_t* U, const uint8_t* V, const uint16_t* sigma,
+                                           int r, const double* s, float* O, int64_t ldo, ptq_stream stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -79,6 +79,10 @@ def load_library() -> ctypes.CDLL:
     lib.ptq_lopro_linear_forward.restype = c.c_int
     lib.ptq_lopro_linear_forward.argtypes = [vp, c.c_int, i64, i64, i64, i64, vp, c.c_int, vp, vp, c.c_int, vp,
                                              c.c_int, c.c_int, vp, vp, vp, c.c_int, vp, vp, i64, vp, sz, vp]
+    lib.ptq_lopro_linear_forward_static.restype = c.c_int
+    lib.ptq_lopro_linear_forward_static.argtypes = lib.ptq_lopro_linear_forward.argtypes[:21] + [vp]
+    lib.ptq_lopro_linear_forward_static_limit.restype = sz
+    lib.ptq_lopro_linear_forward_static_limit.argtypes = []
     lib.ptq_scaled_r1svd.restype = c.c_int
     lib.ptq_scaled_r1svd.argtypes = [vp, c.c_int, i64, i64, i64, vp, vp, i64, c.c_int, c.c_int, vp, vp, vp, vp,
                                      i64, vp, sz, vp]
@@ -349,7 +353,8 @@ def ptq_unpack_dequantize(packed: torch.Tensor, n: int, bits: int, scales_t: tor
 def ptq_lopro_linear_forward(X: torch.Tensor, packed: torch.Tensor, bits: int, scales_t: torch.Tensor,
                              zeros_t: torch.Tensor, group: int, perm: torch.Tensor, b_I: int, b_H: int,
                              U: torch.Tensor | None, V: torch.Tensor | None, sigma: torch.Tensor | None,
-                             s: torch.Tensor | None, O: torch.Tensor, ws: torch.Tensor | None = None) -> None:
+                             s: torch.Tensor | None, O: torch.Tensor, ws: torch.Tensor | None = None,
+                             _static: bool = False) -> None:
     """O (float32 tokens x m) <- the stored layer applied to X (tokens x n) in the rotated-input form;
     scales_t / zeros_t are the group-major grids ptq_pack_codes writes."""
     scales, zeros = scales_t, zeros_t
@@ -368,10 +373,26 @@ def ptq_lopro_linear_forward(X: torch.Tensor, packed: torch.Tensor, bits: int, s
         assert sigma.dtype == torch.float16 and sigma.is_contiguous() and sigma.numel() == r
         assert s.dtype == torch.float64 and s.is_contiguous() and s.numel() == n
     assert O.dtype == torch.float32 and O.stride(1) == 1 and O.shape == (tokens, m)
+    args = (X.data_ptr(), _dtype_code(X), X.stride(0), tokens, m, n, packed.data_ptr(), bits, scales.data_ptr(),
+            zeros.data_ptr(), group, perm.data_ptr(), b_I, b_H, _ptr(U), _ptr(V), _ptr(sigma), r, _ptr(s),
+            O.data_ptr(), O.stride(0))
+    if _static:
+        rc = load_library().ptq_lopro_linear_forward_static(*args, _stream())
+        if rc:
+            raise PtqError(rc, "ptq_lopro_linear_forward_static")
+        return
     ws = _ws(ws, ptq_workspace_bytes(OP_LINEAR_FORWARD, m, n, tokens, r), X)
-    rc = load_library().ptq_lopro_linear_forward(
-        X.data_ptr(), _dtype_code(X), X.stride(0), tokens, m, n, packed.data_ptr(), bits, scales.data_ptr(),
-        zeros.data_ptr(), group, perm.data_ptr(), b_I, b_H, _ptr(U), _ptr(V), _ptr(sigma), r, _ptr(s),
-        O.data_ptr(), O.stride(0), ws.data_ptr(), ws.numel(), _stream())
+    rc = load_library().ptq_lopro_linear_forward(*args, ws.data_ptr(), ws.numel(), _stream())
     if rc:
         raise PtqError(rc, "ptq_lopro_linear_forward")
+
+
+def ptq_lopro_linear_forward_static(X, packed, bits, scales_t, zeros_t, group, perm, b_I, b_H, U, V, sigma, s,
+                                    O) -> None:
+    """The same call on the library's own per-GPU scratch array: nothing is allocated, no workspace is passed."""
+    ptq_lopro_linear_forward(X, packed, bits, scales_t, zeros_t, group, perm, b_I, b_H, U, V, sigma, s, O,
+                             _static=True)
+
+
+def ptq_lopro_linear_forward_static_limit() -> int:
+    return int(load_library().ptq_lopro_linear_forward_static_limit())

@@ -500,6 +500,30 @@ static size_t forward_partial_bytes(int64_t m, int64_t n) {
 
 static size_t forward_counter_bytes(int64_t m) { return align_up((size_t)ceil_div(m, 256) * sizeof(unsigned), 256); }
 
+// ---- scratch for callers that cannot allocate -----------------------------------------------
+// One array per GPU, part of the library's code object: the device memory the forward call needs
+// beyond its inputs and outputs (the rotated input, the low-rank coefficients, the partial sums of
+// the column runs and the row-block counters).  Its name is a host-side stand-in, not a device
+// address: the address on the current device comes from hipGetSymbolAddress, once per device.
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+size_t linear_forward_static_scratch_bytes() { return kStaticScratchBytes; }
+
+ptq_status linear_forward_static_scratch(void** ptr) {
+  constexpr int kMaxDevices = 64;
+  static std::atomic<void*> per_device[kMaxDevices];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return PTQ_ERR_HIP;
+  void* p = per_device[dev].load(std::memory_order_acquire);
+  if (!p) {
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return PTQ_ERR_HIP;
+    per_device[dev].store(p, std::memory_order_release);   // every thread gets the same address: no race
+  }
+  *ptr = p;
+  return PTQ_OK;
+}
+
 size_t linear_forward_workspace_bytes(int64_t tokens, int64_t m, int64_t n, int64_t r) {
   return align_up((size_t)tokens * n * sizeof(float), 256) +
          align_up((size_t)tokens * (r > 0 ? r : 1) * sizeof(float), 256) + forward_partial_bytes(m, n) +

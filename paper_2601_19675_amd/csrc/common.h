@@ -145,6 +145,9 @@ ptq_status unpack_dequant_launch(const uint32_t* packed, int64_t m, int64_t n, i
 ptq_status pack_grids_launch(const float* scales, const uint8_t* zeros, int64_t m, int64_t ng, float* scales_t,
                              uint8_t* zeros_t, hipStream_t st);
 size_t linear_forward_workspace_bytes(int64_t tokens, int64_t m, int64_t n, int64_t r);
+// the per-GPU static scratch of ptq_lopro_linear_forward_static: its size, and its address on the current device
+size_t linear_forward_static_scratch_bytes();
+ptq_status linear_forward_static_scratch(void** ptr);
 ptq_status linear_forward_launch(const void* X, ptq_dtype xdt, int64_t ldx, int64_t tokens, int64_t m, int64_t n,
                                  const uint32_t* packed, int bits, const float* scales, const uint8_t* zeros,
                                  int group, const int32_t* perm, int b_I, int b_H, const uint8_t* U,

@@ -246,11 +246,11 @@ ptq_status ptq_unpack_dequantize(const uint32_t* packed, int64_t m, int64_t n, i
   return unpack_dequant_launch(packed, m, n, bits, scales, zeros, group, Wq, ldq, static_cast<hipStream_t>(stream));
 }
 
-ptq_status ptq_lopro_linear_forward(const void* X, ptq_dtype xdt, int64_t ldx, int64_t tokens, int64_t m, int64_t n,
-                                    const uint32_t* packed, int bits, const float* scales, const uint8_t* zeros,
-                                    int group, const int32_t* perm, int b_I, int b_H, const uint8_t* U,
-                                    const uint8_t* V, const uint16_t* sigma, int r, const double* s, float* O,
-                                    int64_t ldo, void* ws, size_t ws_bytes, ptq_stream stream) {
+static ptq_status linear_forward_args(const void* X, ptq_dtype xdt, int64_t ldx, int64_t tokens, int64_t m, int64_t n,
+                                      const uint32_t* packed, int bits, const float* scales, const uint8_t* zeros,
+                                      int group, const int32_t* perm, int b_I, int b_H, const uint8_t* U,
+                                      const uint8_t* V, const uint16_t* sigma, int r, const double* s, float* O,
+                                      int64_t ldo) {
   if (!dtype_ok(xdt)) return PTQ_ERR_DTYPE;
   if (bits != 2 && bits != 3 && bits != 4 && bits != 8) return PTQ_ERR_ARG;
   if (tokens < 0 || tokens > 4096 || m <= 0 || n <= 0 || n % 32 != 0 || group <= 0 || group % 32 != 0 ||
@@ -262,7 +262,37 @@ ptq_status ptq_lopro_linear_forward(const void* X, ptq_dtype xdt, int64_t ldx, i
   if (!X || !packed || !scales || !zeros || !perm || !O || misaligned(perm, 16) || misaligned(packed, 16))
     return PTQ_ERR_ARG;
   if (r > 0 && (!U || !V || !sigma || !s)) return PTQ_ERR_ARG;
+  return PTQ_OK;
+}
+
+ptq_status ptq_lopro_linear_forward(const void* X, ptq_dtype xdt, int64_t ldx, int64_t tokens, int64_t m, int64_t n,
+                                    const uint32_t* packed, int bits, const float* scales, const uint8_t* zeros,
+                                    int group, const int32_t* perm, int b_I, int b_H, const uint8_t* U,
+                                    const uint8_t* V, const uint16_t* sigma, int r, const double* s, float* O,
+                                    int64_t ldo, void* ws, size_t ws_bytes, ptq_stream stream) {
+  const ptq_status rc = linear_forward_args(X, xdt, ldx, tokens, m, n, packed, bits, scales, zeros, group, perm, b_I,
+                                            b_H, U, V, sigma, r, s, O, ldo);
+  if (rc != PTQ_OK || tokens == 0) return rc;
   if (ws_bad(ws, ws_bytes, linear_forward_workspace_bytes(tokens, m, n, r))) return PTQ_ERR_WORKSPACE;
+  return linear_forward_launch(X, xdt, ldx, tokens, m, n, packed, bits, scales, zeros, group, perm, b_I, b_H, U, V,
+                               sigma, r, s, O, ldo, ws, static_cast<hipStream_t>(stream));
+}
+
+size_t ptq_lopro_linear_forward_static_limit(void) { return linear_forward_static_scratch_bytes(); }
+
+ptq_status ptq_lopro_linear_forward_static(const void* X, ptq_dtype xdt, int64_t ldx, int64_t tokens, int64_t m,
+                                           int64_t n, const uint32_t* packed, int bits, const float* scales,
+                                           const uint8_t* zeros, int group, const int32_t* perm, int b_I, int b_H,
+                                           const uint8_t* U, const uint8_t* V, const uint16_t* sigma, int r,
+                                           const double* s, float* O, int64_t ldo, ptq_stream stream) {
+  const ptq_status rc = linear_forward_args(X, xdt, ldx, tokens, m, n, packed, bits, scales, zeros, group, perm, b_I,
+                                            b_H, U, V, sigma, r, s, O, ldo);
+  if (rc != PTQ_OK || tokens == 0) return rc;
+  // sizes beyond the static array are refused, never trimmed
+  if (linear_forward_workspace_bytes(tokens, m, n, r) > linear_forward_static_scratch_bytes()) return PTQ_ERR_WORKSPACE;
+  void* ws = nullptr;
+  const ptq_status sc = linear_forward_static_scratch(&ws);
+  if (sc != PTQ_OK) return sc;
   return linear_forward_launch(X, xdt, ldx, tokens, m, n, packed, bits, scales, zeros, group, perm, b_I, b_H, U, V,
                                sigma, r, s, O, ldo, ws, static_cast<hipStream_t>(stream));
 }

@@ -188,3 +188,14 @@ def test_stored_form_argument_errors_and_average_bits(lib):
     assert call(perm=None) == 1
     assert call(ws=None, bytes=0) == 4
     assert call(tok=0) == 0
+    # the form on the library's own scratch array: the same checks, and sizes beyond the array are refused
+    def call_static(**kw):
+        a = list(ok)
+        for k, v in kw.items():
+            a[names.index(k)] = v
+        return lib.ptq_lopro_linear_forward_static(*(a[:21] + [None]))
+    assert call_static(dt=9) == 3 and call_static(bits=5) == 1 and call_static(grp=48) == 2
+    assert call_static(U=None) == 1 and call_static(tok=0) == 0
+    assert lib.ptq_lopro_linear_forward_static_limit() == 32 << 20
+    assert ptq.ptq_workspace_bytes(binding.OP_LINEAR_FORWARD, 16384, 16384, 8, 4) > 32 << 20
+    assert call_static(m=16384, n=16384, ldx=16384, ldo=16384, tok=8) == 4
