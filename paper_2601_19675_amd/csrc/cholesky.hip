@@ -523,21 +523,37 @@ __device__ __forceinline__ void node_gemm_tile(const Op& op, int lin, int gx, in
   op.krange(i0, i1, j0, j1, kb, ke);
   f64x4 acc[TM][TN];
   dgemm_zero(acc);
-  dgemm_mainloop<TM, TN, Op::A_KFAST, Op::B_KFAST>(acc, op.a(i0), DgemmIdentity{}, op.b(j0), DgemmIdentity{},
-                                                   i1 - i0, j1 - j0, kb, ke, smem);
+  // a tile with no ragged edge takes the software-pipelined loop (same sums in the same order)
+  // (its buffer loads address a tile's footprint with 32-bit byte offsets)
+  const DView va = op.a(i0), vb = op.b(j0);
+  const int64_t spana = ((int64_t)T::BM * abs(va.so) + (int64_t)(ke - kb) * abs(va.sk)) * 8;
+  const int64_t spanb = ((int64_t)T::BN * abs(vb.so) + (int64_t)(ke - kb) * abs(vb.sk)) * 8;
+  const bool full = (i1 - i0 == T::BM) && (j1 - j0 == T::BN) && ke > kb && ((ke - kb) % kGemmBK == 0) &&
+                    spana < ((int64_t)1 << 31) && spanb < ((int64_t)1 << 31);
+  bool done = false;
+  if constexpr (TM * TN >= 4) {
+    if (full) {
+      dgemm_mainloop_pipelined<TM, TN, Op::A_KFAST, Op::B_KFAST>(acc, va, vb, kb, ke, smem);
+      done = true;
+    }
+  }
+  if (!done)
+    dgemm_mainloop<TM, TN, Op::A_KFAST, Op::B_KFAST>(acc, va, DgemmIdentity{}, vb, DgemmIdentity{}, i1 - i0, j1 - j0,
+                                                     kb, ke, smem);
   dgemm_foreach(acc, [&](int i, int j, double v) { op.store(i0 + i, j0 + j, v); });
 }
 
-// (64 x 128 tiles: three workgroups per CU fit in LDS, so the registers are capped for three)
+// (64 x 64 tiles: three workgroups per CU, so the registers are capped for three; the 128 x 128 tile
+// keeps 128 accumulator registers and two sets of staging registers and runs one or two per CU)
 template <int TM, int TN, class Op>
-__global__ __launch_bounds__(256, (TM * TN >= 8) ? 3 : 1) void node_gemm_kernel(Op op, int gx, int gy) {
+__global__ __launch_bounds__(256, (TM * TN == 4) ? 3 : 1) void node_gemm_kernel(Op op, int gx, int gy) {
   extern __shared__ double smem[];
   node_gemm_tile<TM, TN>(op, blockIdx.x, gx, gy, smem);
 }
 
 // Two independent steps in one launch: workgroups [0, n1) take the tiles of the first.
 template <int TM, int TN, class Op1, class Op2>
-__global__ __launch_bounds__(256, (TM * TN >= 8) ? 3 : 1) void node_gemm2_kernel(Op1 op1, Op2 op2, int n1, int gx1, int gy1, int gx2, int gy2) {
+__global__ __launch_bounds__(256, (TM * TN == 4) ? 3 : 1) void node_gemm2_kernel(Op1 op1, Op2 op2, int n1, int gx1, int gy1, int gx2, int gy2) {
   extern __shared__ double smem[];
   const int b = blockIdx.x;
   if (b < n1)
@@ -570,19 +586,20 @@ bool launch_tiles2(const Op1& op1, int M1, int N1, const Op2& op2, int M2, int N
   return true;
 }
 
-// Tile shape by problem size, as measured: 64 x 128 once there are enough tiles to fill the
-// chip several times over; up to a 2048-wide node 32 x 32 tiles (many small workgroups per CU
-// hide the load latency of the short k loops better than few large ones); 64 x 64 between.
+// Tile shape by problem size, as measured: 128 x 128 once there are enough tiles to fill the
+// chip twice over; up to about a 1500-wide node 32 x 32 tiles (there the k loops are short and
+// bound by the latency of their loads, whatever the tile: many small workgroups hide it best);
+// 64 x 64 between.
 inline int tile_class(int M, int N) {
-  if (ceil_div(M, 64) * ceil_div(N, 128) >= 1024) return 2;
-  if (ceil_div(M, 64) * ceil_div(N, 64) <= 1024) return 0;
+  if (ceil_div(M, 128) * ceil_div(N, 128) >= 512) return 2;
+  if (ceil_div(M, 64) * ceil_div(N, 64) <= 512) return 0;
   return 1;
 }
 
 template <class Op>
 bool launch_node(const Op& op, int M, int N, hipStream_t st) {
   switch (tile_class(M, N)) {
-    case 2: return launch_tiles<2, 4, Op>(op, M, N, st);
+    case 2: return launch_tiles<4, 4, Op>(op, M, N, st);
     case 1: return launch_tiles<2, 2, Op>(op, M, N, st);
     default: return launch_tiles<1, 1, Op>(op, M, N, st);
   }
@@ -592,7 +609,7 @@ template <class Op1, class Op2>
 bool launch_node2(const Op1& op1, int M1, int N1, const Op2& op2, int M2, int N2, hipStream_t st) {
   const int c1 = tile_class(M1, N1), c2 = tile_class(M2, N2);
   switch (c1 < c2 ? c1 : c2) {
-    case 2: return launch_tiles2<2, 4, Op1, Op2>(op1, M1, N1, op2, M2, N2, st);
+    case 2: return launch_tiles2<4, 4, Op1, Op2>(op1, M1, N1, op2, M2, N2, st);
     case 1: return launch_tiles2<2, 2, Op1, Op2>(op1, M1, N1, op2, M2, N2, st);
     default: return launch_tiles2<1, 1, Op1, Op2>(op1, M1, N1, op2, M2, N2, st);
   }

@@ -16,6 +16,8 @@
 // per k-tile, loads for tile t+2 are issued before the MFMAs of tile t, and
 // LDS is double-buffered so that there is one barrier per k-tile.
 #pragma once
+#include <type_traits>
+
 #include "common.h"
 
 namespace ptq {
@@ -169,6 +171,165 @@ __device__ __forceinline__ void dgemm_mainloop(f64x4 (&acc)[TM][TN], DView A, FA
     }
     __syncthreads();  // stage cur free for the tile after next, stage cur^1 complete
     cur ^= 1;
+  }
+}
+
+// ---- the same product for a tile that lies fully inside its operands, software-pipelined ----
+// The loop above spends a quarter of its time outside the matrix pipe: per k-tile every wave first
+// parks the next tile in LDS and requests the one after (address arithmetic, masks, sixteen loads and
+// sixteen LDS stores in a row) and only then starts its MFMAs, and with one to three waves per SIMD
+// nothing else fills that gap.  Here a tile with no ragged edge (all rows and columns valid, k range a
+// multiple of the k-tile) takes a loop whose body is one scheduling region in which those
+// instructions sit BETWEEN the MFMAs: operands come through buffer loads whose per-thread offsets
+// never change (the k-tile advances in a scalar offset, so there is no address arithmetic), go to
+// one of two register sets, and are written to the other LDS stage one k-tile later, a load or a
+// store after every MFMA or two.  Summation order per output element is that of the loop above.
+typedef __attribute__((__vector_size__(2 * sizeof(int)))) int dgemm_i32x2;
+
+template <int I, int MM, int NV, int NW>
+__device__ __forceinline__ void dgemm_sched_step() {
+  // MM MFMAs; after MFMA I one buffer load while I < NV and one LDS store while I < NW
+  if constexpr (I < MM) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    if constexpr (I < NV) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+    if constexpr (I < NW) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+    dgemm_sched_step<I + 1, MM, NV, NW>();
+  }
+}
+
+template <int TM, int TN, bool A_KFAST, bool B_KFAST>
+__device__ __forceinline__ void dgemm_mainloop_pipelined(f64x4 (&acc)[TM][TN], DView A, DView B, int kbeg, int kend,
+                                                         double* smem) {
+  using T = DgemmTile<TM, TN>;
+  constexpr int EA = T::EA, EB = T::EB, E = EA + EB, MM = TM * TN;
+  static_assert(E <= 2 * MM, "loads of a k-tile are spread over the MFMAs of its first two k-steps");
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int K = kend - kbeg;
+  const int ntile = K / kGemmBK;
+  if (ntile <= 0) return;
+
+  // buffer resources based at the lowest address the tile touches (strides may be negative)
+  const int64_t loa = (A.so < 0 ? (int64_t)(T::BM - 1) * A.so : 0) + (A.sk < 0 ? (int64_t)(K - 1) * A.sk : 0);
+  const int64_t lob = (B.so < 0 ? (int64_t)(T::BN - 1) * B.so : 0) + (B.sk < 0 ? (int64_t)(K - 1) * B.sk : 0);
+  const __amdgpu_buffer_rsrc_t ra_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<double*>(A.p + (int64_t)kbeg * A.sk + loa), 0, (int)0xFFFFFFFFu, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rb_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<double*>(B.p + (int64_t)kbeg * B.sk + lob), 0, (int)0xFFFFFFFFu, 0x00020000);
+  int voa[EA], vob[EB], lda[EA], ldb[EB];
+#pragma unroll
+  for (int p = 0; p < EA; ++p) {
+    const int e = tid + 256 * p;
+    const int i = A_KFAST ? e / kGemmBK : e % T::BM;
+    const int k = A_KFAST ? e % kGemmBK : e / T::BM;
+    voa[p] = (i * A.so + k * A.sk - (A.so < 0 ? (T::BM - 1) * A.so : 0) - (A.sk < 0 ? (kGemmBK - 1) * A.sk : 0)) * 8;
+    lda[p] = k * T::PA + i;
+  }
+#pragma unroll
+  for (int p = 0; p < EB; ++p) {
+    const int e = tid + 256 * p;
+    const int j = B_KFAST ? e / kGemmBK : e % T::BN;
+    const int k = B_KFAST ? e % kGemmBK : e / T::BN;
+    vob[p] = (j * B.so + k * B.sk - (B.so < 0 ? (T::BN - 1) * B.so : 0) - (B.sk < 0 ? (kGemmBK - 1) * B.sk : 0)) * 8;
+    ldb[p] = kGemmBK * T::PA + k * T::PB + j;
+  }
+  // scalar byte offset of the k-tile about to be requested
+  int soa = (A.sk < 0 ? -(K - kGemmBK) * A.sk : 0) * 8, sob = (B.sk < 0 ? -(K - kGemmBK) * B.sk : 0) * 8;
+  const int stepa = kGemmBK * A.sk * 8, stepb = kGemmBK * B.sk * 8;
+
+  double ra[2][EA], rb[2][EB];
+  auto request = [&](int set) {
+#pragma unroll
+    for (int p = 0; p < EA; ++p)
+      ra[set][p] = __builtin_bit_cast(double, __builtin_amdgcn_raw_buffer_load_b64(ra_rsrc, voa[p], soa, 0));
+#pragma unroll
+    for (int p = 0; p < EB; ++p)
+      rb[set][p] = __builtin_bit_cast(double, __builtin_amdgcn_raw_buffer_load_b64(rb_rsrc, vob[p], sob, 0));
+    soa += stepa;
+    sob += stepb;
+  };
+  auto park = [&](int set, int stage, int from, int to) {   // elements [from, to) of the E a thread holds
+    double* st = smem + stage * T::kStageDoubles;
+#pragma unroll
+    for (int q = 0; q < E; ++q) {
+      if (q >= from && q < to) {
+        if (q < EA) st[lda[q]] = ra[set][q];
+        else st[ldb[q - EA]] = rb[set][q - EA];
+      }
+    }
+  };
+
+  // P: LDS stage that holds the current k-tile (= register set the tile after next is requested into)
+  auto body = [&](auto p_, auto load_, auto store_) {
+    constexpr int P = decltype(p_)::value;
+    constexpr bool LOAD = decltype(load_)::value, STORE = decltype(store_)::value;
+    const double* sa = smem + P * T::kStageDoubles;
+    const double* sb = sa + kGemmBK * T::PA;
+    if constexpr (LOAD) request(P);
+    double a[2][TM], b[2][TN];
+    auto frags = [&](int kk, int slot) {
+      const int kr = kk + (lane >> 4);
+#pragma unroll
+      for (int tm = 0; tm < TM; ++tm) a[slot][tm] = sa[kr * T::PA + wm * 16 * TM + tm * 16 + (lane & 15)];
+#pragma unroll
+      for (int tn = 0; tn < TN; ++tn) b[slot][tn] = sb[kr * T::PB + wn * 16 * TN + tn * 16 + (lane & 15)];
+    };
+    frags(0, 0);
+#pragma unroll
+    for (int kk = 0; kk < kGemmBK; kk += 4) {
+      const int slot = (kk >> 2) & 1;
+      if (kk + 4 < kGemmBK) frags(kk + 4, slot ^ 1);
+#pragma unroll
+      for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)
+          acc[tm][tn] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[slot][tm], b[slot][tn], acc[tm][tn], 0, 0, 0);
+      if constexpr (STORE) {
+        if (kk == 8) park(P ^ 1, P ^ 1, 0, E / 2);
+        if (kk == 12) park(P ^ 1, P ^ 1, E / 2, E);
+      }
+    }
+    // the order the scheduler is asked for: per k-step the fragment reads of the next one, then its MFMAs
+    // with one request after each in the first two k-steps and one LDS store after each in the last two
+    constexpr int NV0 = !LOAD ? 0 : (E < MM ? E : MM), NV1 = !LOAD ? 0 : E - NV0;
+    constexpr int NW2 = !STORE ? 0 : E / 2, NW3 = !STORE ? 0 : E - E / 2;
+    __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);
+    dgemm_sched_step<0, MM, NV0, 0>();
+    __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);
+    dgemm_sched_step<0, MM, NV1, 0>();
+    __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);
+    dgemm_sched_step<0, MM, 0, NW2>();
+    dgemm_sched_step<0, MM, 0, NW3>();
+    __syncthreads();
+  };
+  using std::integral_constant;
+  using I0 = integral_constant<int, 0>;
+  using I1 = integral_constant<int, 1>;
+  using Yes = integral_constant<bool, true>;
+  using No = integral_constant<bool, false>;
+
+  // prologue: tile 0 into stage 0, tile 1 on its way into register set 1
+  request(0);
+  park(0, 0, 0, E);
+  if (ntile > 1) request(1);
+  __syncthreads();
+  int t = 0;
+  for (; t + 3 < ntile; t += 2) {
+    body(I0{}, Yes{}, Yes{});
+    body(I1{}, Yes{}, Yes{});
+  }
+  const int rest = ntile - t;
+  if (rest == 3) {
+    body(I0{}, Yes{}, Yes{});
+    body(I1{}, No{}, Yes{});
+    body(I0{}, No{}, No{});
+  } else if (rest == 2) {
+    body(I0{}, No{}, Yes{});
+    body(I1{}, No{}, No{});
+  } else {
+    body(I0{}, No{}, No{});
   }
 }
 

@@ -19,13 +19,19 @@
 namespace ptq {
 namespace {
 
-constexpr int kRows = 16;       // rows per workgroup
+constexpr int kRowTile = 16;    // rows of one MFMA M-tile; a workgroup owns MT of them (MT = 1, 2 or 3)
+constexpr int kRowAlign = 96;   // the error matrix is padded to a multiple of every workgroup height
 constexpr int kThreads = 512;   // eight waves: one wave per SIMD cannot keep the float64 matrix pipe busy
 constexpr int kWaves = kThreads / 64;
 
 __global__ void inv_diag_kernel(const double* __restrict__ U, int64_t ldu, int n, double* invd) {
   const int j = blockIdx.x * blockDim.x + threadIdx.x;
   if (j < n) invd[j] = 1.0 / U[(int64_t)j * ldu + j];
+}
+
+// doubles of the LDS region that first holds the partial sums of the lazy update and then the state tile
+__host__ __device__ constexpr int state_doubles(int mt, int bw) {
+  return mt == 1 ? 4 * kRowTile * bw : kRowTile * mt * (bw + 1);
 }
 
 struct QuantArgs {
@@ -47,10 +53,15 @@ struct QuantArgs {
   int static_groups;   // scales / zeros hold the grids already (taken from the given weights): use, do not derive
 };
 
-// NT = number of 16-column tiles the kernel is instantiated for (>= bw / 16).
-template <int DT, int NT>
+// NT = number of 16-column tiles the kernel is instantiated for (>= bw / 16); MT = row tiles of 16
+// rows per workgroup.  With 256 compute units a layer of up to 4096 rows gives every unit one row
+// tile (MT = 1); taller layers take two or three tiles per workgroup, so that one pass over the
+// panel of U serves up to 48 rows and the serial column walk (one lane per row, one wave whatever
+// the height) is shared by them.
+template <int DT, int NT, int MT>
 __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
   extern __shared__ double lds[];
+  constexpr int kRows = kRowTile * MT;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
@@ -63,75 +74,135 @@ __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
   // LDS carve-up: partial sums of four waves at a time (reused as the state tile),
   // the mini-block errors, the mini-block's 16 x 16 diagonal block of U and its
   // reciprocal pivots (double-buffered), group min / max, and the code tile.
-  double* P = lds;                                  // [4][16][bw]
-  double* S = lds;                                  // [16][bw + 1]   (aliases P)
-  double* Em = lds + 4 * kRows * a.bw;              // [16 k][16 rows]
-  double* Qm = Em + 256;                            // [16 k][17]: the mini-block's dequantized values
-  double* Ud = Qm + 272;                            // [2][16][16]
+  double* P = lds;                                  // MT = 1: [4][16][bw]; else [rows][bw]
+  double* S = lds;                                  // [rows][bw + 1]   (aliases P)
+  double* Em = lds + state_doubles(MT, a.bw);       // [16 k][rows]
+  double* Qm = Em + 16 * kRows;                     // [16 k][rows + 1]: the mini-block's dequantized values
+  double* Ud = Qm + 16 * (kRows + 1);               // [2][16][16]
   double* Id = Ud + 512;                            // [2][16]
-  double* gmin = Id + 32;                           // [16]
-  double* gmax = gmin + 16;                         // [16]
-  uint8_t* Ct = reinterpret_cast<uint8_t*>(gmax + 16);  // [16][bw]
+  double* gmin = Id + 32;                           // [rows]
+  double* gmax = gmin + kRows;                      // [rows]
+  uint8_t* Ct = reinterpret_cast<uint8_t*>(gmax + kRows);  // [rows][bw]
 
+  if constexpr (MT == 1) {
   // ---- phase 1: acc = E[rows, 0:i1] * U[0:i1, block], k split over the waves,
-  //      operands of the next kDepth steps in flight while the MFMAs run
-  f64x4 acc[NT];
+    //      operands of the next kDepth steps in flight while the MFMAs run
+    f64x4 acc[NT];
 #pragma unroll
-  for (int t = 0; t < NT; ++t) acc[t] = f64x4{0.0, 0.0, 0.0, 0.0};
-  {
-    constexpr int kDepth = (NT >= 16) ? 2 : 4;
-    const int kl = lane >> 4, cl = lane & 15;
-    const double* ep = a.errT + (int64_t)(4 * wave + kl) * a.mpad + row0 + cl;
-    const double* up = U + (int64_t)(4 * wave + kl) * a.ldu + a.i1 + cl;
-    int coff[NT];  // tiles beyond the block re-read its last tile (result unused)
+    for (int t = 0; t < NT; ++t) acc[t] = f64x4{0.0, 0.0, 0.0, 0.0};
+    {
+      constexpr int kDepth = (NT >= 16) ? 2 : 4;
+      const int kl = lane >> 4, cl = lane & 15;
+      const double* ep = a.errT + (int64_t)(4 * wave + kl) * a.mpad + row0 + cl;
+      const double* up = U + (int64_t)(4 * wave + kl) * a.ldu + a.i1 + cl;
+      int coff[NT];  // tiles beyond the block re-read its last tile (result unused)
 #pragma unroll
-    for (int t = 0; t < NT; ++t) coff[t] = 16 * (t < nt ? t : nt - 1);
-    const int niter = (a.i1 - 4 * wave + 4 * kWaves - 1) / (4 * kWaves);  // k = 32 it + 4 wave + kl < i1 (a multiple of 16)
-    double av[kDepth], bv[kDepth][NT];
-    auto issue = [&](int slot, int it) {
-      av[slot] = ep[(int64_t)it * (4 * kWaves) * a.mpad];
-      const double* u = up + (int64_t)it * (4 * kWaves) * a.ldu;
+      for (int t = 0; t < NT; ++t) coff[t] = 16 * (t < nt ? t : nt - 1);
+      const int niter = (a.i1 - 4 * wave + 4 * kWaves - 1) / (4 * kWaves);  // k = 32 it + 4 wave + kl < i1 (a multiple of 16)
+      double av[kDepth], bv[kDepth][NT];
+      auto issue = [&](int slot, int it) {
+        av[slot] = ep[(int64_t)it * (4 * kWaves) * a.mpad];
+        const double* u = up + (int64_t)it * (4 * kWaves) * a.ldu;
 #pragma unroll
-      for (int t = 0; t < NT; ++t) bv[slot][t] = u[coff[t]];
-    };
+        for (int t = 0; t < NT; ++t) bv[slot][t] = u[coff[t]];
+      };
 #pragma unroll
-    for (int d = 0; d < kDepth; ++d)
-      if (d < niter) issue(d, d);
-    for (int it = 0; it < niter; it += kDepth) {
+      for (int d = 0; d < kDepth; ++d)
+        if (d < niter) issue(d, d);
+      for (int it = 0; it < niter; it += kDepth) {
 #pragma unroll
-      for (int d = 0; d < kDepth; ++d) {
-        if (it + d < niter) {
+        for (int d = 0; d < kDepth; ++d) {
+          if (it + d < niter) {
 #pragma unroll
-          for (int t = 0; t < NT; ++t)
-            acc[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[d], bv[d][t], acc[t], 0, 0, 0);
-          if (it + d + kDepth < niter) issue(d, it + d + kDepth);
+            for (int t = 0; t < NT; ++t)
+              acc[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[d], bv[d][t], acc[t], 0, 0, 0);
+            if (it + d + kDepth < niter) issue(d, it + d + kDepth);
+          }
         }
       }
     }
-  }
-  // the eight partial sums are folded in two rounds through four LDS slots
-  if (wave >= 4) {
+    // the eight partial sums are folded in two rounds through four LDS slots
+    if (wave >= 4) {
 #pragma unroll
-    for (int t = 0; t < NT; ++t)
-      if (t < nt) {
+      for (int t = 0; t < NT; ++t)
+        if (t < nt) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
-          P[((wave - 4) * kRows + 4 * r + (lane >> 4)) * a.bw + 16 * t + (lane & 15)] = acc[t][r];
-      }
-  }
-  __syncthreads();
-  if (wave < 4) {
+          for (int r = 0; r < 4; ++r)
+            P[((wave - 4) * kRows + 4 * r + (lane >> 4)) * a.bw + 16 * t + (lane & 15)] = acc[t][r];
+        }
+    }
+    __syncthreads();
+    if (wave < 4) {
 #pragma unroll
-    for (int t = 0; t < NT; ++t)
-      if (t < nt) {
+      for (int t = 0; t < NT; ++t)
+        if (t < nt) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
-          P[(wave * kRows + 4 * r + (lane >> 4)) * a.bw + 16 * t + (lane & 15)] += acc[t][r];
-      }
-  }
-  __syncthreads();
+          for (int r = 0; r < 4; ++r)
+            P[(wave * kRows + 4 * r + (lane >> 4)) * a.bw + 16 * t + (lane & 15)] += acc[t][r];
+        }
+    }
+    __syncthreads();
 
-  // ---- state tile S = W - (p0 + p1 + p2 + p3), dead channels read as zero
+  } else {
+    // ---- phase 1, several row tiles: a wave owns column tiles (wave, wave + 8, ...) and runs over all k
+    //      itself -- no partial sums to fold; the operand of U is fetched once for all MT row tiles, the
+    //      rows of E (the same for every wave) come out of the cache after the first wave's fetch
+    constexpr int TPW = (NT + kWaves - 1) / kWaves;
+    constexpr int kDepth = 4;
+    f64x4 acc[MT][TPW];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int q = 0; q < TPW; ++q) acc[mt][q] = f64x4{0.0, 0.0, 0.0, 0.0};
+    if (wave < nt) {
+      const int kl = lane >> 4, cl = lane & 15;
+      const double* ep = a.errT + (int64_t)kl * a.mpad + row0 + cl;
+      int coff[TPW];  // tiles beyond the block re-read a valid tile (result unused)
+#pragma unroll
+      for (int q = 0; q < TPW; ++q) coff[q] = 16 * ((wave + kWaves * q) < nt ? wave + kWaves * q : wave);
+      const double* up = U + (int64_t)kl * a.ldu + a.i1 + cl;
+      const int niter = a.i1 >> 2;   // i1 is a multiple of 16
+      double av[kDepth][MT], bv[kDepth][TPW];
+      auto issue = [&](int slot, int it) {
+        const double* e = ep + (int64_t)it * 4 * a.mpad;
+        const double* u = up + (int64_t)it * 4 * a.ldu;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) av[slot][mt] = e[kRowTile * mt];
+#pragma unroll
+        for (int q = 0; q < TPW; ++q) bv[slot][q] = u[coff[q]];
+      };
+#pragma unroll
+      for (int d = 0; d < kDepth; ++d)
+        if (d < niter) issue(d, d);
+      for (int it = 0; it < niter; it += kDepth) {
+#pragma unroll
+        for (int d = 0; d < kDepth; ++d) {
+          if (it + d < niter) {
+#pragma unroll
+            for (int q = 0; q < TPW; ++q)
+#pragma unroll
+              for (int mt = 0; mt < MT; ++mt)
+                acc[mt][q] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[d][mt], bv[d][q], acc[mt][q], 0, 0, 0);
+            if (it + d + kDepth < niter) issue(d, it + d + kDepth);
+          }
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < TPW; ++q) {
+        const int t = wave + kWaves * q;
+        if (t < nt) {
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+              P[(kRowTile * mt + 4 * r + (lane >> 4)) * a.bw + 16 * t + (lane & 15)] = acc[mt][q][r];
+        }
+      }
+    }
+    __syncthreads();
+  }
+
+  // ---- state tile S = W - (sum of the partial sums), dead channels read as zero
   {
     constexpr int NP = (kRows * 16 * NT + kThreads - 1) / kThreads;
     double sv[NP];
@@ -144,9 +215,13 @@ __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
         double w = 0.0;
         if (row0 + r < a.m && !(a.dead && a.dead[a.i1 + c]))
           w = load_as_f64<DT>(a.W, (int64_t)(row0 + r) * a.ldw + a.i1 + c);
-        const double s01 = P[(0 * kRows + r) * a.bw + c] + P[(1 * kRows + r) * a.bw + c];
-        const double s23 = P[(2 * kRows + r) * a.bw + c] + P[(3 * kRows + r) * a.bw + c];
-        sv[p] = w - (s01 + s23);
+        if constexpr (MT == 1) {
+          const double s01 = P[(0 * kRows + r) * a.bw + c] + P[(1 * kRows + r) * a.bw + c];
+          const double s23 = P[(2 * kRows + r) * a.bw + c] + P[(3 * kRows + r) * a.bw + c];
+          sv[p] = w - (s01 + s23);
+        } else {
+          sv[p] = w - P[r * a.bw + c];
+        }
       }
     }
     __syncthreads();
@@ -191,23 +266,26 @@ __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
         ub[q][kk] = U[(int64_t)(gcol + 4 * kk + (lane >> 4)) * a.ldu + a.i1 + 16 * tc + (lane & 15)];
     }
     if (gstart && !a.static_groups) {
-      // min / max of the group's current values: 16 lanes per row (first four waves)
+      // min / max of the group's current values: 16 lanes per row, 16 rows per pass of the first four waves
       if (tid < 256) {
-        const int r = tid >> 4, sub = tid & 15;
-        double lo = 0.0, hi = 0.0;
-        for (int c = sub; c < a.group; c += 16) {
-          const double v = S[r * sp + c0 + c];
-          lo = fmin(lo, v);
-          hi = fmax(hi, v);
-        }
-        // over the row's 16 lanes (min and max do not depend on the order)
-        lo = fmin(lo, dpp_move<kDppSwapPairs>(lo));         hi = fmax(hi, dpp_move<kDppSwapPairs>(hi));
-        lo = fmin(lo, dpp_move<kDppSwapHalfQuads>(lo));     hi = fmax(hi, dpp_move<kDppSwapHalfQuads>(hi));
-        lo = fmin(lo, dpp_move<kDppHalfMirror>(lo));        hi = fmax(hi, dpp_move<kDppHalfMirror>(hi));
-        lo = fmin(lo, dpp_move<kDppMirror>(lo));            hi = fmax(hi, dpp_move<kDppMirror>(hi));
-        if (sub == 0) {
-          gmin[r] = lo;
-          gmax[r] = hi;
+#pragma unroll
+        for (int pass = 0; pass < MT; ++pass) {
+          const int r = kRowTile * pass + (tid >> 4), sub = tid & 15;
+          double lo = 0.0, hi = 0.0;
+          for (int c = sub; c < a.group; c += 16) {
+            const double v = S[r * sp + c0 + c];
+            lo = fmin(lo, v);
+            hi = fmax(hi, v);
+          }
+          // over the row's 16 lanes (min and max do not depend on the order)
+          lo = fmin(lo, dpp_move<kDppSwapPairs>(lo));         hi = fmax(hi, dpp_move<kDppSwapPairs>(hi));
+          lo = fmin(lo, dpp_move<kDppSwapHalfQuads>(lo));     hi = fmax(hi, dpp_move<kDppSwapHalfQuads>(hi));
+          lo = fmin(lo, dpp_move<kDppHalfMirror>(lo));        hi = fmax(hi, dpp_move<kDppHalfMirror>(hi));
+          lo = fmin(lo, dpp_move<kDppMirror>(lo));            hi = fmax(hi, dpp_move<kDppMirror>(hi));
+          if (sub == 0) {
+            gmin[r] = lo;
+            gmax[r] = hi;
+          }
         }
       }
       __syncthreads();
@@ -278,7 +356,7 @@ __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
         err2 = fma(e, e, err2);
         Ct[r * a.bw + c0 + j] = (uint8_t)(k + zero);
         Em[j * kRows + r] = e;
-        Qm[j * 17 + r] = scale * k;
+        Qm[j * (kRows + 1) + r] = scale * k;
         ep = e;
 #pragma unroll
         for (int c = j + 2; c < 16; ++c) rp[c] = rc[c];
@@ -291,26 +369,33 @@ __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
     for (int q = 0; q < kUpd; ++q) {
       const int t = mb + 1 + wave + kWaves * q;
       if (t < nt) {
-        f64x4 d = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-          const double av = Em[(4 * kk + (lane >> 4)) * kRows + (lane & 15)];
-          d = __builtin_amdgcn_mfma_f64_16x16x4f64(av, ub[q][kk], d, 0, 0, 0);
+        for (int mt = 0; mt < MT; ++mt) {
+          f64x4 d = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+          for (int kk = 0; kk < 4; ++kk) {
+            const double av = Em[(4 * kk + (lane >> 4)) * kRows + kRowTile * mt + (lane & 15)];
+            d = __builtin_amdgcn_mfma_f64_16x16x4f64(av, ub[q][kk], d, 0, 0, 0);
+          }
+          double sv[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) sv[r] = S[(kRowTile * mt + 4 * r + (lane >> 4)) * sp + 16 * t + (lane & 15)];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) S[(kRowTile * mt + 4 * r + (lane >> 4)) * sp + 16 * t + (lane & 15)] = sv[r] - d[r];
         }
-        double sv[4];
-#pragma unroll
-        for (int r = 0; r < 4; ++r) sv[r] = S[(4 * r + (lane >> 4)) * sp + 16 * t + (lane & 15)];
-#pragma unroll
-        for (int r = 0; r < 4; ++r) S[(4 * r + (lane >> 4)) * sp + 16 * t + (lane & 15)] = sv[r] - d[r];
       }
     }
     // the mini-block's errors (for the later blocks) and dequantized values leave through the
     // upper four waves, 128 contiguous bytes per 16 lanes
     if (tid >= 256) {
-      const int e = tid - 256;
-      a.errT[(int64_t)(gcol + (e >> 4)) * a.mpad + row0 + (e & 15)] = Em[e];
-      const int r = e >> 4, j = e & 15;
-      if (a.Wq && row0 + r < a.m) a.Wq[(int64_t)(row0 + r) * a.n + gcol + j] = Qm[j * 17 + r];
+#pragma unroll
+      for (int pass = 0; pass < MT; ++pass) {
+        const int e = tid - 256 + 256 * pass;          // Em is [16 k][rows]: e = k * rows + row
+        const int k = e / kRows, rr = e - k * kRows;
+        a.errT[(int64_t)(gcol + k) * a.mpad + row0 + rr] = Em[e];
+        const int r = e >> 4, j = e & 15;
+        if (a.Wq && row0 + r < a.m) a.Wq[(int64_t)(row0 + r) * a.n + gcol + j] = Qm[j * (kRows + 1) + r];
+      }
     }
     if (mb + 1 < nt) {
       if (tid < 256) Ud[(buf ^ 1) * 256 + tid] = ud_next;
@@ -332,31 +417,51 @@ __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
   }
 }
 
-size_t block_lds_bytes(int bw) {
-  return (size_t)(4 * kRows * bw + 256 + 272 + 512 + 32 + 32) * sizeof(double) + (size_t)kRows * bw;
+size_t block_lds_bytes(int mt, int bw) {
+  const int rows = kRowTile * mt;
+  return (size_t)(state_doubles(mt, bw) + 16 * rows + 16 * (rows + 1) + 512 + 32 + 2 * rows) * sizeof(double) +
+         (size_t)rows * bw;
 }
 
-template <int DT, int NT>
+template <int DT, int NT, int MT>
 ptq_status launch_block(const QuantArgs& a, hipStream_t st) {
-  if (!lds_opt_in<quant_block_kernel<DT, NT>>((int)block_lds_bytes(16 * NT))) return PTQ_ERR_HIP;
-  quant_block_kernel<DT, NT><<<a.mpad / kRows, kThreads, block_lds_bytes(a.bw), st>>>(a);
+  if (!lds_opt_in<quant_block_kernel<DT, NT, MT>>((int)block_lds_bytes(MT, 16 * NT))) return PTQ_ERR_HIP;
+  const unsigned wgs = (unsigned)ceil_div(a.m, kRowTile * MT);
+  quant_block_kernel<DT, NT, MT><<<wgs, kThreads, block_lds_bytes(MT, a.bw), st>>>(a);
   return PTQ_OK;
 }
 
-template <int DT>
+template <int DT, int MT>
 ptq_status run_blocks(QuantArgs a, int block, hipStream_t st) {
   for (int i1 = 0; i1 < a.n; i1 += block) {
     a.i1 = i1;
     a.bw = (a.n - i1 < block) ? a.n - i1 : block;
     const int nt = a.bw / 16;
     ptq_status rc;
-    if (nt <= 2) rc = launch_block<DT, 2>(a, st);
-    else if (nt <= 4) rc = launch_block<DT, 4>(a, st);
-    else if (nt <= 8) rc = launch_block<DT, 8>(a, st);
-    else rc = launch_block<DT, 16>(a, st);
+    if (nt <= 2) rc = launch_block<DT, 2, MT>(a, st);
+    else if (nt <= 4) rc = launch_block<DT, 4, MT>(a, st);
+    else if (nt <= 8) rc = launch_block<DT, 8, MT>(a, st);
+    else rc = launch_block<DT, 16, MT>(a, st);
     if (rc != PTQ_OK) return rc;
   }
   return PTQ_OK;
+}
+
+// Row tiles per workgroup: one while the layer's row tiles fit the chip's 256 compute units (with a
+// little slack), else as many (up to 3) as bring the workgroup count back to about one per unit.
+int row_tiles_per_workgroup(int64_t m) {
+  const int64_t tiles = ceil_div(m, kRowTile);
+  if (tiles <= 288) return 1;
+  return tiles <= 576 ? 2 : 3;
+}
+
+template <int DT>
+ptq_status run_blocks_any(const QuantArgs& a, int block, hipStream_t st) {
+  switch (row_tiles_per_workgroup(a.m)) {
+    case 1: return run_blocks<DT, 1>(a, block, st);
+    case 2: return run_blocks<DT, 2>(a, block, st);
+    default: return run_blocks<DT, 3>(a, block, st);
+  }
 }
 
 }  // namespace
@@ -388,7 +493,7 @@ __global__ __launch_bounds__(256) void static_grid_kernel(const void* __restrict
 }
 
 size_t quantize_workspace_bytes(int64_t m, int64_t n) {
-  const int64_t mpad = ceil_div(m, kRows) * kRows;
+  const int64_t mpad = ceil_div(m, kRowAlign) * kRowAlign;
   return align_up((size_t)n * (size_t)mpad * sizeof(double), 256) + align_up((size_t)n * sizeof(double), 256);
 }
 
@@ -407,7 +512,7 @@ ptq_status quantize_launch(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m,
   a.ldw = ldw;
   a.m = (int)m;
   a.n = (int)n;
-  a.mpad = (int)(ceil_div(m, kRows) * kRows);
+  a.mpad = (int)(ceil_div(m, kRowAlign) * kRowAlign);
   a.U = U;
   a.ldu = ldu;
   a.dead = dead_mask;
@@ -437,9 +542,9 @@ ptq_status quantize_launch(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m,
   PTQ_HIP_CHECK_LAUNCH();
   ptq_status rc;
   switch (wdt) {
-    case PTQ_F32: rc = run_blocks<PTQ_F32>(a, block, st); break;
-    case PTQ_BF16: rc = run_blocks<PTQ_BF16>(a, block, st); break;
-    case PTQ_F64: rc = run_blocks<PTQ_F64>(a, block, st); break;
+    case PTQ_F32: rc = run_blocks_any<PTQ_F32>(a, block, st); break;
+    case PTQ_BF16: rc = run_blocks_any<PTQ_BF16>(a, block, st); break;
+    case PTQ_F64: rc = run_blocks_any<PTQ_F64>(a, block, st); break;
     default: return PTQ_ERR_DTYPE;
   }
   if (rc != PTQ_OK) return rc;

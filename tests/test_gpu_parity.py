@@ -175,6 +175,10 @@ CASES = [
     ("block_tail", "f32", 40, 384, 1000, 4, 128, 256),
     ("group_wider_than_block", "bf16", 24, 512, 1300, 3, 128, 64),
     ("tiny", "f32", 1, 16, 40, 4, 16, 16),
+    # tall layers: two and three 16-row tiles per workgroup, with a ragged last workgroup
+    ("tall_two_row_tiles", "bf16", 4700, 256, 700, 3, 128, 128),
+    ("tall_three_row_tiles", "bf16", 9300, 192, 600, 4, 64, 64),
+    ("tall_three_row_tiles_b256", "f32", 9237, 320, 900, 2, 64, 256),
 ]
 
 
