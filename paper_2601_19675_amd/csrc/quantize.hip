@@ -93,32 +93,74 @@ __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
     {
       constexpr int kDepth = (NT >= 16) ? 2 : 4;
       const int kl = lane >> 4, cl = lane & 15;
-      const double* ep = a.errT + (int64_t)(4 * wave + kl) * a.mpad + row0 + cl;
-      const double* up = U + (int64_t)(4 * wave + kl) * a.ldu + a.i1 + cl;
+      const int wv = __builtin_amdgcn_readfirstlane(wave);   // uniform: scalar loop control
       int coff[NT];  // tiles beyond the block re-read its last tile (result unused)
 #pragma unroll
       for (int t = 0; t < NT; ++t) coff[t] = 16 * (t < nt ? t : nt - 1);
-      const int niter = (a.i1 - 4 * wave + 4 * kWaves - 1) / (4 * kWaves);  // k = 32 it + 4 wave + kl < i1 (a multiple of 16)
+      const int niter = (a.i1 - 4 * wv + 4 * kWaves - 1) / (4 * kWaves);  // k = 32 it + 4 wave + kl < i1 (a multiple of 16)
       double av[kDepth], bv[kDepth][NT];
-      auto issue = [&](int slot, int it) {
-        av[slot] = ep[(int64_t)it * (4 * kWaves) * a.mpad];
-        const double* u = up + (int64_t)it * (4 * kWaves) * a.ldu;
+      auto mfmas = [&](int d) {
 #pragma unroll
-        for (int t = 0; t < NT; ++t) bv[slot][t] = u[coff[t]];
+        for (int t = 0; t < NT; ++t)
+          acc[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[d], bv[d][t], acc[t], 0, 0, 0);
       };
+      // The loop: slot d's MFMAs, then the request for the step kDepth later into the same slot.  In the
+      // steady state there is no branch between the first request and the last iteration, every slot is
+      // valid and has a successor, and the requests are buffer loads whose per-lane offsets never change
+      // (the step advances in a scalar offset: no address arithmetic between the MFMAs).
+      auto run = [&](auto issue) {
+        int it = 0;
+        if (niter >= 2 * kDepth) {
 #pragma unroll
-      for (int d = 0; d < kDepth; ++d)
-        if (d < niter) issue(d, d);
-      for (int it = 0; it < niter; it += kDepth) {
+          for (int d = 0; d < kDepth; ++d) issue(d, d);
+          for (; it + 2 * kDepth <= niter; it += kDepth) {
 #pragma unroll
-        for (int d = 0; d < kDepth; ++d) {
-          if (it + d < niter) {
+            for (int d = 0; d < kDepth; ++d) {
+              mfmas(d);
+              issue(d, it + d + kDepth);
+            }
+          }
+        } else {
 #pragma unroll
-            for (int t = 0; t < NT; ++t)
-              acc[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[d], bv[d][t], acc[t], 0, 0, 0);
-            if (it + d + kDepth < niter) issue(d, it + d + kDepth);
+          for (int d = 0; d < kDepth; ++d)
+            if (d < niter) issue(d, d);
+        }
+        for (; it < niter; it += kDepth) {
+#pragma unroll
+          for (int d = 0; d < kDepth; ++d) {
+            if (it + d < niter) {
+              mfmas(d);
+              if (it + d + kDepth < niter) issue(d, it + d + kDepth);
+            }
           }
         }
+      };
+      const bool offsets32 = (int64_t)a.n * a.ldu * 8 < ((int64_t)1 << 31) && (int64_t)a.n * a.mpad * 8 < ((int64_t)1 << 31);
+      if (offsets32) {
+        const __amdgpu_buffer_rsrc_t re = __builtin_amdgcn_make_buffer_rsrc(const_cast<double*>(a.errT + row0), 0,
+                                                                            (int)0xFFFFFFFFu, 0x00020000);
+        const __amdgpu_buffer_rsrc_t ru = __builtin_amdgcn_make_buffer_rsrc(const_cast<double*>(U + a.i1), 0,
+                                                                            (int)0xFFFFFFFFu, 0x00020000);
+        const int ve = ((4 * wv + kl) * a.mpad + cl) * 8;
+        int vu[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) vu[t] = ((4 * wv + kl) * (int)a.ldu + cl + coff[t]) * 8;
+        const int se = 4 * kWaves * a.mpad * 8, su = 4 * kWaves * (int)a.ldu * 8;
+        run([&](int slot, int it) {
+          av[slot] = __builtin_bit_cast(double, __builtin_amdgcn_raw_buffer_load_b64(re, ve, it * se, 0));
+#pragma unroll
+          for (int t = 0; t < NT; ++t)
+            bv[slot][t] = __builtin_bit_cast(double, __builtin_amdgcn_raw_buffer_load_b64(ru, vu[t], it * su, 0));
+        });
+      } else {
+        const double* ep = a.errT + (int64_t)(4 * wv + kl) * a.mpad + row0 + cl;
+        const double* up = U + (int64_t)(4 * wv + kl) * a.ldu + a.i1 + cl;
+        run([&](int slot, int it) {
+          av[slot] = ep[(int64_t)it * (4 * kWaves) * a.mpad];
+          const double* u = up + (int64_t)it * (4 * kWaves) * a.ldu;
+#pragma unroll
+          for (int t = 0; t < NT; ++t) bv[slot][t] = u[coff[t]];
+        });
       }
     }
     // the eight partial sums are folded in two rounds through four LDS slots
@@ -154,38 +196,79 @@ __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
       for (int q = 0; q < TPW; ++q) acc[mt][q] = f64x4{0.0, 0.0, 0.0, 0.0};
-    if (wave < nt) {
+    const int wv = __builtin_amdgcn_readfirstlane(wave);   // uniform: scalar loop control
+    if (wv < nt) {
       const int kl = lane >> 4, cl = lane & 15;
-      const double* ep = a.errT + (int64_t)kl * a.mpad + row0 + cl;
       int coff[TPW];  // tiles beyond the block re-read a valid tile (result unused)
 #pragma unroll
-      for (int q = 0; q < TPW; ++q) coff[q] = 16 * ((wave + kWaves * q) < nt ? wave + kWaves * q : wave);
-      const double* up = U + (int64_t)kl * a.ldu + a.i1 + cl;
+      for (int q = 0; q < TPW; ++q) coff[q] = 16 * ((wv + kWaves * q) < nt ? wv + kWaves * q : wv);
       const int niter = a.i1 >> 2;   // i1 is a multiple of 16
       double av[kDepth][MT], bv[kDepth][TPW];
-      auto issue = [&](int slot, int it) {
-        const double* e = ep + (int64_t)it * 4 * a.mpad;
-        const double* u = up + (int64_t)it * 4 * a.ldu;
+      auto mfmas = [&](int d) {
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) av[slot][mt] = e[kRowTile * mt];
+        for (int q = 0; q < TPW; ++q)
 #pragma unroll
-        for (int q = 0; q < TPW; ++q) bv[slot][q] = u[coff[q]];
+          for (int mt = 0; mt < MT; ++mt)
+            acc[mt][q] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[d][mt], bv[d][q], acc[mt][q], 0, 0, 0);
       };
+      auto run = [&](auto issue) {   // branch-free steady state, as in the one-tile form
+        int it = 0;
+        if (niter >= 2 * kDepth) {
 #pragma unroll
-      for (int d = 0; d < kDepth; ++d)
-        if (d < niter) issue(d, d);
-      for (int it = 0; it < niter; it += kDepth) {
+          for (int d = 0; d < kDepth; ++d) issue(d, d);
+          for (; it + 2 * kDepth <= niter; it += kDepth) {
 #pragma unroll
-        for (int d = 0; d < kDepth; ++d) {
-          if (it + d < niter) {
+            for (int d = 0; d < kDepth; ++d) {
+              mfmas(d);
+              issue(d, it + d + kDepth);
+            }
+          }
+        } else {
 #pragma unroll
-            for (int q = 0; q < TPW; ++q)
+          for (int d = 0; d < kDepth; ++d)
+            if (d < niter) issue(d, d);
+        }
+        for (; it < niter; it += kDepth) {
 #pragma unroll
-              for (int mt = 0; mt < MT; ++mt)
-                acc[mt][q] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[d][mt], bv[d][q], acc[mt][q], 0, 0, 0);
-            if (it + d + kDepth < niter) issue(d, it + d + kDepth);
+          for (int d = 0; d < kDepth; ++d) {
+            if (it + d < niter) {
+              mfmas(d);
+              if (it + d + kDepth < niter) issue(d, it + d + kDepth);
+            }
           }
         }
+      };
+      const bool offsets32 = (int64_t)a.n * a.ldu * 8 < ((int64_t)1 << 31) && (int64_t)a.n * a.mpad * 8 < ((int64_t)1 << 31);
+      if (offsets32) {
+        const __amdgpu_buffer_rsrc_t re = __builtin_amdgcn_make_buffer_rsrc(const_cast<double*>(a.errT + row0), 0,
+                                                                            (int)0xFFFFFFFFu, 0x00020000);
+        const __amdgpu_buffer_rsrc_t ru = __builtin_amdgcn_make_buffer_rsrc(const_cast<double*>(U + a.i1), 0,
+                                                                            (int)0xFFFFFFFFu, 0x00020000);
+        int ve[MT], vu[TPW];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) ve[mt] = (kl * a.mpad + cl + kRowTile * mt) * 8;
+#pragma unroll
+        for (int q = 0; q < TPW; ++q) vu[q] = (kl * (int)a.ldu + cl + coff[q]) * 8;
+        const int se = 4 * a.mpad * 8, su = 4 * (int)a.ldu * 8;
+        run([&](int slot, int it) {
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt)
+            av[slot][mt] = __builtin_bit_cast(double, __builtin_amdgcn_raw_buffer_load_b64(re, ve[mt], it * se, 0));
+#pragma unroll
+          for (int q = 0; q < TPW; ++q)
+            bv[slot][q] = __builtin_bit_cast(double, __builtin_amdgcn_raw_buffer_load_b64(ru, vu[q], it * su, 0));
+        });
+      } else {
+        const double* ep = a.errT + (int64_t)kl * a.mpad + row0 + cl;
+        const double* up = U + (int64_t)kl * a.ldu + a.i1 + cl;
+        run([&](int slot, int it) {
+          const double* e = ep + (int64_t)it * 4 * a.mpad;
+          const double* u = up + (int64_t)it * 4 * a.ldu;
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) av[slot][mt] = e[kRowTile * mt];
+#pragma unroll
+          for (int q = 0; q < TPW; ++q) bv[slot][q] = u[coff[q]];
+        });
       }
 #pragma unroll
       for (int q = 0; q < TPW; ++q) {
