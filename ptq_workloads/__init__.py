@@ -35,6 +35,7 @@ _TENSOR_SCALE = 3
 _TENSOR_OUTLIER = 4
 _TENSOR_SKETCH = 5
 _TENSOR_LOWRANK = 6
+_TENSOR_CODEBOOK = 7
 
 
 # ----------------------------------------------------------------------------
@@ -194,6 +195,21 @@ def gen_sketch_vectors(spec: LayerSpec, r: int, seed: int = BASE_SEED) -> np.nda
     drawn here so that every implementation under test sees the same ones."""
     rng = _rng(seed, spec.layer_id, _TENSOR_SKETCH)
     return rng.standard_normal((r, spec.n), dtype=np.float32)
+
+
+def gen_codebook(W64: np.ndarray, entries: int, dim: int, spec: LayerSpec, seed: int = BASE_SEED) -> np.ndarray:
+    """entries x dim float32 codebook drawn at random for a vector quantizer: distinct pieces of
+    `dim` consecutive columns (starting at a multiple of dim) of the given weight matrix, picked
+    uniformly -- a random, untrained codebook in the weights' own units."""
+    rng = _rng(seed, spec.layer_id, _TENSOR_CODEBOOK)
+    m, n = W64.shape
+    pieces = np.ascontiguousarray(W64[:, : (n // dim) * dim]).reshape(-1, dim)
+    pick = rng.choice(pieces.shape[0], size=min(entries, pieces.shape[0]), replace=False)
+    cb = pieces[pick].astype(np.float32)
+    if cb.shape[0] < entries:   # a layer smaller than the codebook: fill up with Gaussian entries of the same spread
+        extra = rng.standard_normal((entries - cb.shape[0], dim)) * float(np.std(pieces))
+        cb = np.vstack([cb, extra.astype(np.float32)])
+    return cb
 
 
 def channel_scales(spec: LayerSpec, seed: int = BASE_SEED) -> np.ndarray:
