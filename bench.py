@@ -264,6 +264,34 @@ def r1svd_timings(ptq, W, X, m, n, t, rank=16, it=8, reps=5):
     }
 
 
+def vq_timings(ptq, wl, L, reps=5):
+    """The vector-quantized form of the solve on the benchmark layer with the factor of the step just run, in the
+    paper's two settings (4-D vectors with 256 entries = 2 bits per weight, 2-D vectors with 64 entries = 3 bits);
+    the codebook is drawn at random from the layer's own weights.  Float64 throughout: the lazy update is the
+    scalar solve's, so the same m n^2 flop count applies."""
+    import torch
+    out = {}
+    W64 = L.W.double().cpu().numpy()
+    for K, d in ((256, 4), (64, 2)):
+        C = torch.from_numpy(wl.gen_codebook(W64, K, d, L.spec, L.cfg.seed)).cuda()
+        idx = torch.empty((L.m, L.n // d), dtype=torch.uint8, device="cuda")
+        f = lambda: ptq.ptq_quantize_layer_vq(L.W, L.U, L.dead, C, L.cfg.block, idx, L.Wq, L.err2, L.ws)
+        f()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            f()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        ptq.ptq_layer_error(L.W, L.Wq, L.H, L.out, L.ws)
+        torch.cuda.synchronize()
+        out[f"{K}_entries_x_{d}"] = {"ms": ms, "columns_per_s": L.n / (ms * 1e-3),
+                                      "tflops_f64": float(L.m) * L.n * L.n / (ms * 1e-3) / 1e12,
+                                      "rel_layer_error": float(L.out[0])}
+    return out
+
+
 def forward_timings(ptq, codes, scales, zeros, m, n, bits, group, rank=16, reps=20):
     """The stored layer applied to 1, 4, 16 and 64 tokens in the rotated-input form (packed codes of the step just
     run, a random permutation, random rank-16 e4m3 factors): bound by the packed codes streaming from memory."""
@@ -459,6 +487,9 @@ def main():
     ap.add_argument("--forward", action="store_true",
                     help="also time the stored layer applied to 1 and 4 tokens (packed codes, rotated input, "
                          "rank-16 low-rank part) and report it under \"forward\"")
+    ap.add_argument("--vq", action="store_true",
+                    help="also time the vector-quantized form of the solve (256 entries x 4 and 64 entries x 2) on the "
+                         "same layer and factor and report it under \"vq\"")
     ap.add_argument("--device-x", action="store_true",
                     help="draw the activations on the GPU (same distribution family, torch generator) instead of "
                          "the seeded host generator")
@@ -553,6 +584,8 @@ def main():
         result["r1svd"] = r1svd_timings(ptq, L.W, L.X, m, n, t)
     if args.forward:
         result["forward"] = forward_timings(ptq, L.codes, L.scales, L.zeros, m, n, cfg.bits, cfg.group)
+    if args.vq:
+        result["vq"] = vq_timings(ptq, wl, L)
     main_is_headline = (args.config == "C3" and not block_mode and spec.name == "down_proj")
     del layers, L, ws
     torch.cuda.empty_cache()

@@ -170,6 +170,30 @@ ptq_status ptq_quantize_layer_static_groups(const void* W, ptq_dtype wdt, int64_
                                             ptq_stream stream);
 
 /*
+ * The same solve with a VECTOR quantizer (the paper's second variant; implementation-details
+ * appendix: a randomly drawn, untrained codebook, no block-wise scaling, vectors of 4 weights at
+ * 2 bits per weight and of 2 weights at 3 bits per weight; assignment by the proxy-Hessian loss,
+ * Sec. 3.2, Eq. 8; Algorithm 1, quantization step).  A vector is `dim` consecutive columns of a row
+ * starting at a multiple of dim.  For every row and group g = columns [j, j + dim), j = g dim, with w
+ * the row's current (compensated) values and T = U[j:j+dim, j:j+dim]:
+ *
+ *   loss(c)  = sum_i e_i^2,   e = (w - c) T^-1   (the errors of the group's columns, one after the other)
+ *   index_g  = the entry of the codebook with the smallest loss (the lowest index among equal ones)
+ *   w_k     -= sum_i e_i U[j+i][k]    for all later columns k
+ *
+ * codebook   entries x dim float32, row-major, in the weights' own units; one codebook for the layer,
+ *            drawn by the caller.  1 <= entries <= 256; dim is 1, 2 or 4; n % dim == 0.
+ * indices    m x (n / dim) uint8 output, row-major.
+ * Wq         m x n float64 output (ld = n) or NULL: the assigned entries.   row_err2  m float64 or NULL.
+ * W, U, dead_mask, block (a multiple of 16, at most 256), workspace (PTQ_OP_QUANTIZE) and errors as for
+ * ptq_quantize_layer.  All arithmetic is float64.
+ */
+ptq_status ptq_quantize_layer_vq(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m, int64_t n,
+                                 const double* U, int64_t ldu, const uint8_t* dead_mask, const float* codebook,
+                                 int entries, int dim, int block, uint8_t* indices, double* Wq,
+                                 double* row_err2, void* ws, size_t ws_bytes, ptq_stream stream);
+
+/*
  * Relative layer error under the proxy-Hessian loss (Sec. 2, Eq. 1):
  *
  *   num = tr((W - Wq) H (W - Wq)^T),  den = tr(W H W^T),  rel = sqrt(num / den)

@@ -56,6 +56,9 @@ def load_library() -> ctypes.CDLL:
         fn.restype = c.c_int
         fn.argtypes = [vp, c.c_int, i64, i64, i64, vp, i64, vp, c.c_int, c.c_int, c.c_int, vp, vp, vp, vp, vp, vp,
                        sz, vp]
+    lib.ptq_quantize_layer_vq.restype = c.c_int
+    lib.ptq_quantize_layer_vq.argtypes = [vp, c.c_int, i64, i64, i64, vp, i64, vp, vp, c.c_int, c.c_int, c.c_int, vp, vp,
+                                          vp, vp, sz, vp]
     lib.ptq_layer_error.restype = c.c_int
     lib.ptq_layer_error.argtypes = [vp, c.c_int, i64, vp, i64, i64, vp, i64, vp, vp, sz, vp]
     lib.ptq_lopro_column_order.restype = c.c_int
@@ -192,6 +195,28 @@ def ptq_quantize_layer_static_groups(W: torch.Tensor, U: torch.Tensor, dead_mask
     """The same solve with every group's grid taken from W as given, before any compensation."""
     ptq_quantize_layer(W, U, dead_mask, bits, group, block, codes, scales, zeros, Wq, row_err2, ws,
                        _entry="ptq_quantize_layer_static_groups")
+
+
+def ptq_quantize_layer_vq(W: torch.Tensor, U: torch.Tensor, dead_mask: torch.Tensor | None, codebook: torch.Tensor,
+                          block: int, indices: torch.Tensor, Wq: torch.Tensor | None = None,
+                          row_err2: torch.Tensor | None = None, ws: torch.Tensor | None = None) -> None:
+    """The column solve with a vector quantizer: codebook (float32 entries x dim), indices (uint8 m x n/dim)."""
+    _check_dev(W, U, dead_mask, codebook, indices, Wq, row_err2)
+    m, n = W.shape
+    entries, dim = codebook.shape
+    assert W.stride(1) == 1 and U.stride(1) == 1 and U.dtype == torch.float64
+    assert codebook.dtype == torch.float32 and codebook.is_contiguous()
+    if dim > 0 and n % dim == 0:
+        assert indices.dtype == torch.uint8 and indices.is_contiguous() and indices.shape == (m, n // dim)
+    assert Wq is None or (Wq.dtype == torch.float64 and Wq.is_contiguous() and Wq.shape == (m, n))
+    assert row_err2 is None or (row_err2.dtype == torch.float64 and row_err2.numel() >= m)
+    ws = _ws(ws, ptq_workspace_bytes(OP_QUANTIZE, m, n), W)
+    rc = load_library().ptq_quantize_layer_vq(W.data_ptr(), _dtype_code(W), W.stride(0), m, n, U.data_ptr(), U.stride(0),
+                                              _ptr(dead_mask), codebook.data_ptr(), entries, dim, block,
+                                              indices.data_ptr(), _ptr(Wq), _ptr(row_err2), ws.data_ptr(), ws.numel(),
+                                              _stream())
+    if rc:
+        raise PtqError(rc, "ptq_quantize_layer_vq")
 
 
 def ptq_layer_error(W: torch.Tensor, Wq: torch.Tensor, H: torch.Tensor, out: torch.Tensor,

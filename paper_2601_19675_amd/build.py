@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libptq.so")
-SOURCES = ["ptq_api.hip", "hessian.hip", "cholesky.hip", "quantize.hip", "layer_error.hip", "lopro.hip", "r1svd.hip", "r1svd_bf16.hip", "artifact.hip"]
+SOURCES = ["ptq_api.hip", "hessian.hip", "cholesky.hip", "quantize.hip", "vq.hip", "layer_error.hip", "lopro.hip", "r1svd.hip", "r1svd_bf16.hip", "artifact.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-result",
     # packed-FP32 instructions are kept out of every kernel

@@ -101,6 +101,11 @@ ptq_status quantize_launch(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m,
                            int block, uint8_t* codes, float* scales, uint8_t* zeros, double* Wq,
                            double* row_err2, int static_groups, void* ws, size_t ws_bytes, hipStream_t s);
 
+ptq_status quantize_vq_launch(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m, int64_t n, const double* U,
+                              int64_t ldu, const uint8_t* dead_mask, const float* codebook, int entries, int dim,
+                              int block, uint8_t* indices, double* Wq, double* row_err2, void* ws, size_t ws_bytes,
+                              hipStream_t s);
+
 size_t layer_error_workspace_bytes(int64_t m, int64_t n);
 ptq_status layer_error_launch(const void* W, ptq_dtype wdt, int64_t ldw, const double* Wq, int64_t m,
                               int64_t n, const double* H, int64_t ldh, double* out, void* ws,

@@ -113,6 +113,21 @@ ptq_status ptq_quantize_layer_static_groups(const void* W, ptq_dtype wdt, int64_
                           row_err2, 1, ws, ws_bytes, stream);
 }
 
+ptq_status ptq_quantize_layer_vq(const void* W, ptq_dtype wdt, int64_t ldw, int64_t m, int64_t n, const double* U,
+                                 int64_t ldu, const uint8_t* dead_mask, const float* codebook, int entries, int dim,
+                                 int block, uint8_t* indices, double* Wq, double* row_err2, void* ws,
+                                 size_t ws_bytes, ptq_stream stream) {
+  if (entries < 1 || entries > 256 || (dim != 1 && dim != 2 && dim != 4)) return PTQ_ERR_ARG;
+  if (!dtype_ok(wdt)) return PTQ_ERR_DTYPE;
+  if (m < 0 || n < 0 || ldw < n || ldu < n || m > INT32_MAX / 2 || n > INT32_MAX / 2) return PTQ_ERR_SHAPE;
+  if (n % dim != 0 || block <= 0 || block % 16 != 0 || block > 256) return PTQ_ERR_SHAPE;
+  if (m == 0 || n == 0) return PTQ_OK;
+  if (!W || !U || !codebook || !indices) return PTQ_ERR_ARG;
+  if (ws_bad(ws, ws_bytes, quantize_workspace_bytes(m, n))) return PTQ_ERR_WORKSPACE;
+  return quantize_vq_launch(W, wdt, ldw, m, n, U, ldu, dead_mask, codebook, entries, dim, block, indices, Wq,
+                            row_err2, ws, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
 ptq_status ptq_layer_error(const void* W, ptq_dtype wdt, int64_t ldw, const double* Wq, int64_t m,
                            int64_t n, const double* H, int64_t ldh, double* out, void* ws,
                            size_t ws_bytes, ptq_stream stream) {

@@ -184,3 +184,50 @@ def follow_r1svd(W64, s, S, it, U_codes, V_codes, sigma, tol, max_followed=4):
             settled = k + 1          # a real difference in rank k: leave it, look no further in this rank
             if settled == r:
                 return ref
+
+
+# ----------------------------------------------------------------------------
+# the vector-quantized solve: near-ties of the assignment
+# ----------------------------------------------------------------------------
+def compare_vq(W64, U, codebook, dead, g_indices, tol=1e-5, max_forced_per_row=16):
+    """The protocol of compare_quantization for the vector quantizer.  A group's decision is the entry
+    with the smallest loss; the boundary between two entries is where their losses are equal, and a
+    point at distance delta (in units of the entries' separation, both measured through T^-1) from it
+    has a loss difference of 2 delta |(c_a - c_b) T^-1|^2.  At the first group where the GPU's index
+    differs from the oracle's, the difference is accepted when the oracle's own losses put the point
+    within `tol` of that boundary; the GPU's index is then forced and the row solved again."""
+    from oracle import vq_oracle as vqo
+    C = np.asarray(codebook, dtype=np.float64)
+    d = C.shape[1]
+    m = W64.shape[0]
+    base = vqo.quantize_layer_vq(W64, U, C, dead=dead, want_margins=True)
+    rep = dict(rows=m, exact_rows=0, flagged=0, unflagged=0, details=[], oracle=base, max_margin=0.0)
+    for r in range(m):
+        if np.array_equal(base["indices"][r], g_indices[r]):
+            rep["exact_rows"] += 1
+            continue
+        cur = {k: v[r:r + 1] for k, v in base.items()}
+        forced = {}
+        for _ in range(max_forced_per_row):
+            diff = np.nonzero(cur["indices"][0] != g_indices[r])[0]
+            if diff.size == 0:
+                break
+            g = int(diff[0])
+            j = g * d
+            T = U[j:j + d, j:j + d]
+            losses = vqo.group_losses(cur["pre_w"][0, j:j + d], C, T)
+            ko, kg = int(cur["indices"][0, g]), int(g_indices[r, g])
+            sep = float(np.sum(vqo.group_errors(C[kg][None, :], C[ko], T) ** 2))
+            margin = (losses[kg] - losses[ko]) / (2.0 * sep) if sep > 0 else 0.0
+            if kg >= C.shape[0] or margin > tol or (sep == 0.0 and kg > ko):
+                rep["unflagged"] += 1
+                rep["details"].append((r, g, ko, kg, float(margin)))
+                break
+            rep["flagged"] += 1
+            rep["max_margin"] = max(rep["max_margin"], float(margin))
+            forced[(0, g)] = kg
+            cur = vqo.quantize_layer_vq(W64[r:r + 1], U, C, dead=dead, forced=forced, want_margins=True)
+        else:
+            rep["unflagged"] += 1
+            rep["details"].append((r, -1, -1, -1, 0.0))
+    return rep

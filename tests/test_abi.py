@@ -168,6 +168,13 @@ def test_stored_form_argument_errors_and_average_bits(lib):
     assert lib.ptq_unpack_dequantize(p, 4, 64, 4, p, p, 48, p, 64, None) == 2   # n % group
     assert lib.ptq_unpack_dequantize(p, 4, 64, 4, p, p, 32, p, 32, None) == 2   # ldq < n
     assert lib.ptq_unpack_dequantize(p, 4, 64, 4, None, p, 32, p, 64, None) == 1
+    # vector quantizer:          W dt ldw m  n   U ldu dead cb  K   d blk idx Wq e2 ws bytes
+    vq = lambda **kw: lib.ptq_quantize_layer_vq(*[kw.get(k, v) for k, v in dict(
+        W=p, dt=1, ldw=64, m=8, n=64, U=p, ldu=64, dead=None, cb=p, K=256, d=4, blk=64, idx=p, Wq=None, e2=None, ws=p,
+        bytes=big, st=None).items()])
+    assert vq(K=0) == 1 and vq(K=257) == 1 and vq(d=3) == 1 and vq(dt=7) == 3
+    assert vq(n=62, ldw=62, ldu=62) == 2 and vq(blk=40) == 2 and vq(blk=512) == 2 and vq(ldu=32) == 2
+    assert vq(cb=None) == 1 and vq(idx=None) == 1 and vq(ws=None, bytes=0) == 4 and vq(m=0) == 0
     # forward:                  X  dt ldx tok m  n    packed bits sc z  grp perm bI  bH  U  V  sg r  s  O  ldo ws bytes
     ok = [p, 0, 256, 2, 8, 256, p, 4, p, p, 64, p, 128, 128, p, p, p, 4, p, p, 8, p, big, None]
     names = ["X", "dt", "ldx", "tok", "m", "n", "packed", "bits", "sc", "z", "grp", "perm", "bI", "bH", "U", "V",
