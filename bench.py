@@ -292,6 +292,65 @@ def vq_timings(ptq, wl, L, reps=5):
     return out
 
 
+def mfma_control(ptq, L):
+    """What the matrix cores sustain on this chip, beside the Hessian kernel: (1) a register-only MFMA loop
+    (nothing else issued: no loads, no LDS) in bfloat16 and float64, with benign operands and with random
+    operand bits, each for tens of milliseconds, with the shader clock read inside the kernel (cycle counter
+    over the constant-rate counter); (2) the Hessian kernel itself on the benchmark layer's activations and
+    on small-integer activations of the same shape (fewer bits toggling in the multipliers)."""
+    import ctypes
+    import torch
+    from paper_2601_19675_amd import build as b
+    lib = ctypes.CDLL(b.PROBE_LIB)
+    lib.ptq_probe_mfma.restype = ctypes.c_double
+    lib.ptq_probe_mfma.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
+                                   ctypes.c_void_p, ctypes.c_void_p]
+    blocks = 2048
+    outb = torch.empty(blocks * 256, dtype=torch.float32, device="cuda")
+    clk = torch.zeros(2, dtype=torch.int64, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    res = {"register_only_loops": []}
+    for kind, name, iters, peak in ((0, "bf16 32x32x16", 9000, PEAK_BF16_TFLOPS), (1, "f64 16x16x4", 36000, PEAK_F64_TFLOPS)):
+        for rnd in (0, 1):
+            lib.ptq_probe_mfma(kind, rnd, 200, blocks, outb.data_ptr(), clk.data_ptr(), st)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            flops = lib.ptq_probe_mfma(kind, rnd, iters, blocks, outb.data_ptr(), clk.data_ptr(), st)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1)
+            c = clk.cpu().tolist()
+            res["register_only_loops"].append({
+                "mfma": name, "operands": "random bits" if rnd else "benign", "ms": ms,
+                "tflops": flops / ms / 1e9, "frac_of_peak": flops / ms / 1e9 / peak,
+                "shader_clock_ghz": c[1] / (c[0] / 100e6) / 1e9 if c[0] else None})
+    # the Hessian kernel: real activations, then small integers in the same buffer
+    def hess_ms(X, reps=3):
+        ptq.ptq_hessian_accumulate(L.H, X, L.ws)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            ptq.ptq_hessian_accumulate(L.H, X, L.ws)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+    syrk = float(L.t) * L.n * (L.n + 1)
+    real_ms = hess_ms(L.X)
+    gen = torch.Generator(device="cuda").manual_seed(3)
+    for lo in range(0, L.t, 32768):
+        hi = min(L.t, lo + 32768)
+        L.X[lo:hi] = torch.randint(-2, 3, (hi - lo, L.n), device="cuda", generator=gen, dtype=torch.int8).to(L.X.dtype)
+    small_ms = hess_ms(L.X)
+    res["hessian_kernel"] = {
+        "shape": f"X {L.t}x{L.n}",
+        "real_activations": {"ms": real_ms, "tflops_syrk": syrk / real_ms / 1e9, "frac_of_peak": syrk / real_ms / 1e9 / PEAK_BF16_TFLOPS},
+        "small_integer_activations": {"ms": small_ms, "tflops_syrk": syrk / small_ms / 1e9,
+                                      "frac_of_peak": syrk / small_ms / 1e9 / PEAK_BF16_TFLOPS}}
+    return res
+
+
 def forward_timings(ptq, codes, scales, zeros, m, n, bits, group, rank=16, reps=20):
     """The stored layer applied to 1, 4, 16 and 64 tokens in the rotated-input form (packed codes of the step just
     run, a random permutation, random rank-16 e4m3 factors): bound by the packed codes streaming from memory."""
@@ -487,6 +546,10 @@ def main():
     ap.add_argument("--forward", action="store_true",
                     help="also time the stored layer applied to 1 and 4 tokens (packed codes, rotated input, "
                          "rank-16 low-rank part) and report it under \"forward\"")
+    ap.add_argument("--mfma-control", action="store_true",
+                    help="also run the controls behind the Hessian roofline: register-only MFMA loops (bfloat16 and "
+                         "float64, benign and random operand bits, shader clock read in the kernel) and the Hessian "
+                         "kernel on small-integer activations; reported under \"mfma_control\" (overwrites X: runs last)")
     ap.add_argument("--vq", action="store_true",
                     help="also time the vector-quantized form of the solve (256 entries x 4 and 64 entries x 2) on the "
                          "same layer and factor and report it under \"vq\"")
@@ -586,6 +649,8 @@ def main():
         result["forward"] = forward_timings(ptq, L.codes, L.scales, L.zeros, m, n, cfg.bits, cfg.group)
     if args.vq:
         result["vq"] = vq_timings(ptq, wl, L)
+    if args.mfma_control:
+        result["mfma_control"] = mfma_control(ptq, L)
     main_is_headline = (args.config == "C3" and not block_mode and spec.name == "down_proj")
     del layers, L, ws
     torch.cuda.empty_cache()

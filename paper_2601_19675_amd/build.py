@@ -9,6 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libptq.so")
+PROBE_LIB = os.path.join(HERE, "libptq_probe.so")   # diagnostics for bench.py --mfma-control, not part of the product
 SOURCES = ["ptq_api.hip", "hessian.hip", "cholesky.hip", "quantize.hip", "vq.hip", "layer_error.hip", "lopro.hip", "r1svd.hip", "r1svd_bf16.hip", "artifact.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-result",
@@ -52,6 +53,11 @@ def build(verbose: bool = True) -> str:
                        capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")
+    # the register-only MFMA probe, a library of its own
+    r = subprocess.run([hipcc, *[f for f in FLAGS if f != "-Wall"], "-shared", os.path.join(CSRC, "probe_mfma.hip"), "-o",
+                        PROBE_LIB], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"probe library failed:\n{r.stdout}\n{r.stderr}")
     if verbose:
         print(f"built {LIB}")
     return LIB

@@ -135,6 +135,20 @@ __device__ __forceinline__ void dgemm_mainloop(f64x4 (&acc)[TM][TN], DView A, FA
     }
   };
 
+  // A tile with fewer than four MFMAs per k-step would run them as one dependent chain (an MFMA's
+  // result is ready only three instruction times later): the k-steps of a k-tile then go to NS
+  // separate accumulator sets, added up at the end.
+  constexpr int NS = (TM * TN >= 4) ? 1 : 4 / (TM * TN);
+  f64x4 part[NS][TM][TN];
+  if constexpr (NS > 1) {
+#pragma unroll
+    for (int q = 0; q < NS; ++q)
+#pragma unroll
+      for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) part[q][tm][tn] = f64x4{0.0, 0.0, 0.0, 0.0};
+  }
+
   fetch(kbeg);
   stash(kbeg, smem);
   if (kbeg + kGemmBK < kend) fetch(kbeg + kGemmBK);
@@ -164,13 +178,32 @@ __device__ __forceinline__ void dgemm_mainloop(f64x4 (&acc)[TM][TN], DView A, FA
 #pragma unroll
       for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
-        for (int tn = 0; tn < TN; ++tn)
-          acc[tm][tn] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[slot][tm], b[slot][tn], acc[tm][tn], 0, 0, 0);
+        for (int tn = 0; tn < TN; ++tn) {
+          if constexpr (NS == 1)
+            acc[tm][tn] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[slot][tm], b[slot][tn], acc[tm][tn], 0, 0, 0);
+          else
+            part[(kk >> 2) % NS][tm][tn] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[slot][tm], b[slot][tn],
+                                                                                part[(kk >> 2) % NS][tm][tn], 0, 0, 0);
+        }
       __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);   // the reads of the next k-step first
       __builtin_amdgcn_sched_group_barrier(0x008, TM * TN, 0);   // then this k-step's MFMAs
     }
     __syncthreads();  // stage cur free for the tile after next, stage cur^1 complete
     cur ^= 1;
+  }
+  if constexpr (NS > 1) {
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+      for (int tn = 0; tn < TN; ++tn) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          double sum = part[0][tm][tn][r];
+#pragma unroll
+          for (int q = 1; q < NS; ++q) sum += part[q][tm][tn][r];
+          acc[tm][tn][r] += sum;
+        }
+      }
   }
 }
 

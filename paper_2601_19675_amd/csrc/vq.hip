@@ -9,7 +9,7 @@
 // sum_i e_i^2 with e = (w - c) T^-1 taken by forward substitution (the errors the scalar walk would
 // make column by column); the entry with the smallest loss is assigned, the lowest index among exactly
 // equal ones.  Half a wave works for one row: a lane keeps K / 32 entries in registers for the whole
-// kernel, evaluates their losses, and the 32 lanes agree on the minimum by exchanging (loss, index)
+// walk, evaluates their losses, and the 32 lanes agree on the minimum by exchanging (loss, index)
 // pairs; every lane then knows the group's errors and applies them to the later columns of the
 // mini-block itself, so the eight waves walk their two rows each without a barrier between groups.
 #include "common.h"
@@ -80,16 +80,6 @@ __global__ __launch_bounds__(kThreads) void vq_block_kernel(VqArgs a) {
   double* Ud = Qm + 272;                            // [2][16][16] diagonal block of U
   double* Id = Ud + 512;                            // [2][16] reciprocal pivots
   uint8_t* It = reinterpret_cast<uint8_t*>(Id + 32);  // [16][bw / D] indices of the block
-
-  // this lane's codebook entries: k = l32 + 32 s, for the whole kernel
-  const int l32 = lane & 31;
-  double cb[kSlots][D];
-#pragma unroll
-  for (int s = 0; s < kSlots; ++s) {
-    const int k = l32 + 32 * s;
-#pragma unroll
-    for (int i = 0; i < D; ++i) cb[s][i] = k < a.K ? (double)a.codebook[k * D + i] : 0.0;
-  }
 
   // ---- phase 1: acc = E[rows, 0:i1] * U[0:i1, block], k split over the waves
   f64x4 acc[NT];
@@ -183,6 +173,16 @@ __global__ __launch_bounds__(kThreads) void vq_block_kernel(VqArgs a) {
   __syncthreads();
 
   // ---- phase 2: 16-column mini-blocks; half a wave walks one row
+  // this lane's codebook entries, k = l32 + 32 s, in registers from here on (after the lazy update, whose
+  // accumulators need the room)
+  const int l32 = lane & 31;
+  double cb[kSlots][D];
+#pragma unroll
+  for (int s = 0; s < kSlots; ++s) {
+    const int k = l32 + 32 * s;
+#pragma unroll
+    for (int i = 0; i < D; ++i) cb[s][i] = k < a.K ? (double)a.codebook[k * D + i] : 0.0;
+  }
   const int r = 2 * wave + (lane >> 5);   // the row of this half-wave
   double err2 = 0.0;
   constexpr int kUpd = (NT + kWaves - 1) / kWaves;
