@@ -22,6 +22,9 @@
 // unused) upper triangle of the work matrix, L21 X11 in the dead G21 block.
 #include "dgemm.h"
 
+#include <atomic>
+#include <mutex>
+
 namespace ptq {
 namespace {
 
@@ -546,9 +549,11 @@ __device__ __forceinline__ void node_gemm_tile(const Op& op, int lin, int gx, in
 // (64 x 64 tiles: three workgroups per CU, so the registers are capped for three; the 128 x 128 tile
 // keeps 128 accumulator registers and two sets of staging registers and runs one or two per CU)
 template <int TM, int TN, class Op>
-__global__ __launch_bounds__(256, (TM * TN == 4) ? 3 : 1) void node_gemm_kernel(Op op, int gx, int gy) {
+__global__ __launch_bounds__(256, (TM * TN == 4) ? 3 : 1) void node_gemm_kernel(Op op, int gx, int gy, int total) {
   extern __shared__ double smem[];
-  node_gemm_tile<TM, TN>(op, blockIdx.x, gx, gy, smem);
+  // one tile per workgroup, or, launched with fewer workgroups than tiles, a stride over the tile list
+  // (both tile loops end with a barrier, so the LDS stages are free when the next tile starts)
+  for (int lin = blockIdx.x; lin < total; lin += gridDim.x) node_gemm_tile<TM, TN>(op, lin, gx, gy, smem);
 }
 
 // Two independent steps in one launch: workgroups [0, n1) take the tiles of the first.
@@ -562,14 +567,17 @@ __global__ __launch_bounds__(256, (TM * TN == 4) ? 3 : 1) void node_gemm2_kernel
     node_gemm_tile<TM, TN>(op2, b - n1, gx2, gy2, smem);
 }
 
+// max_wgs > 0 caps the number of workgroups (the tiles are then taken in a stride): used for work that
+// runs beside the critical chain on a second stream and must leave compute units free for it
 template <int TM, int TN, class Op>
-bool launch_tiles(const Op& op, int M, int N, hipStream_t st) {
+bool launch_tiles(const Op& op, int M, int N, hipStream_t st, int max_wgs = 0) {
   using T = DgemmTile<TM, TN>;
   constexpr int lds = T::kSmemDoubles * (int)sizeof(double);
   if (!lds_opt_in<node_gemm_kernel<TM, TN, Op>>(lds)) return false;
   const int gx = (int)ceil_div(N, T::BN), gy = (int)ceil_div(M, T::BM);
-  const int nwg = Op::LOWER_ONLY ? lower_tiles<TM, TN>(gx, gy) : gx * gy;
-  node_gemm_kernel<TM, TN, Op><<<(unsigned)nwg, 256, lds, st>>>(op, gx, gy);
+  const int total = Op::LOWER_ONLY ? lower_tiles<TM, TN>(gx, gy) : gx * gy;
+  const int nwg = (max_wgs > 0 && max_wgs < total) ? max_wgs : total;
+  node_gemm_kernel<TM, TN, Op><<<(unsigned)nwg, 256, lds, st>>>(op, gx, gy, total);
   return true;
 }
 
@@ -597,11 +605,11 @@ inline int tile_class(int M, int N) {
 }
 
 template <class Op>
-bool launch_node(const Op& op, int M, int N, hipStream_t st) {
+bool launch_node(const Op& op, int M, int N, hipStream_t st, int max_cus = 0) {
   switch (tile_class(M, N)) {
-    case 2: return launch_tiles<4, 4, Op>(op, M, N, st);
-    case 1: return launch_tiles<2, 2, Op>(op, M, N, st);
-    default: return launch_tiles<1, 1, Op>(op, M, N, st);
+    case 2: return launch_tiles<4, 4, Op>(op, M, N, st, max_cus);          // one workgroup per compute unit
+    case 1: return launch_tiles<2, 2, Op>(op, M, N, st, 3 * max_cus);      // three
+    default: return launch_tiles<1, 1, Op>(op, M, N, st, 4 * max_cus);
   }
 }
 
@@ -615,7 +623,47 @@ bool launch_node2(const Op1& op1, int M1, int N1, const Op2& op2, int M2, int N2
   }
 }
 
-bool recurse(double* G, double* U, int ldu, int n, int o, int s, int32_t* info, hipStream_t st) {
+// ---- a second stream for work that is off the critical chain ---------------------------------
+// After the trailing update of a node the chain  leaf -> panel -> update -> leaf ...  of its second
+// half is a sequence of small, latency-bound launches that leaves most of the chip idle, while
+// T = L21 X11  of the node (a quarter of its flops) is needed only by the node's last step.  For the
+// largest nodes (128 x 128 tiles) T therefore runs on a helper stream, forked after the update and
+// joined before  X21 = -X22 T,  with at most kSideCus workgroups, so that the launches of the chain
+// always find free compute units (measured at n = 11008: 128 gives the shortest total; 256 gains
+// nothing, 64 makes T the longer path).  Smaller nodes gain nothing (measured) and keep T in the
+// update's launch.  One helper stream and a few events per device, created on first use and kept
+// for the life of the process (default priority).
+constexpr int kSideCus = 128;
+constexpr int kMaxDepth = 12;
+struct Side {
+  std::mutex lock;   // the events are reused call after call: one caller at a time enqueues a factor
+  hipStream_t stream = nullptr;
+  hipEvent_t fork[kMaxDepth], join[kMaxDepth];
+  bool ok = false;
+};
+
+Side* side_for_device() {
+  constexpr int kMaxDevices = 64;
+  static Side sides[kMaxDevices];
+  static std::atomic<int> state[kMaxDevices];   // 0 = untried, 1 = being set up, 2 = ready, 3 = unavailable
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  int expected = 0;
+  if (state[dev].compare_exchange_strong(expected, 1)) {
+    Side& sd = sides[dev];
+    bool ok = hipStreamCreateWithFlags(&sd.stream, hipStreamNonBlocking) == hipSuccess;
+    for (int d = 0; ok && d < kMaxDepth; ++d)
+      ok = hipEventCreateWithFlags(&sd.fork[d], hipEventDisableTiming) == hipSuccess &&
+           hipEventCreateWithFlags(&sd.join[d], hipEventDisableTiming) == hipSuccess;
+    sd.ok = ok;
+    state[dev].store(ok ? 2 : 3, std::memory_order_release);
+  }
+  while (state[dev].load(std::memory_order_acquire) == 1) {
+  }
+  return state[dev].load(std::memory_order_acquire) == 2 ? &sides[dev] : nullptr;
+}
+
+bool recurse(double* G, double* U, int ldu, int n, int o, int s, int32_t* info, hipStream_t st, Side* side, int depth) {
   if (s <= kLeaf) {
     leaf_kernel<<<1, 256, kLeafLdsBytes, st>>>(G, n, o, s, U, ldu, info);
     return true;
@@ -624,10 +672,23 @@ bool recurse(double* G, double* U, int ldu, int n, int o, int s, int32_t* info, 
   const int s1 = (nb / 2) * kLeaf;
   const int s2 = s - s1;
   Node nd{G, U, ldu, n, o, s1, s2};
+  if (!recurse(G, U, ldu, n, o, s1, info, st, side, depth + 1) || !launch_node(OpPanel{nd}, s2, s1, st)) return false;
   // the trailing update and T = L21 X11 both need only L21 and touch different blocks
-  return recurse(G, U, ldu, n, o, s1, info, st) && launch_node(OpPanel{nd}, s2, s1, st) &&
-         launch_node2(OpSyrk{nd}, s2, s2, OpT{nd}, s2, s1, st) && recurse(G, U, ldu, n, o + s1, s2, info, st) &&
-         launch_node(OpX21{nd}, s2, s1, st);
+  if (side && depth < kMaxDepth && tile_class(s2, s1) == 2) {
+    // a large node: the trailing update first, with the whole chip; then T beside the chain of the
+    // second half (fork after the update, join before X21)
+    if (!launch_node(OpSyrk{nd}, s2, s2, st)) return false;
+    if (hipEventRecord(side->fork[depth], st) != hipSuccess ||
+        hipStreamWaitEvent(side->stream, side->fork[depth], 0) != hipSuccess)
+      return false;
+    if (!launch_node(OpT{nd}, s2, s1, side->stream, kSideCus)) return false;
+    if (hipEventRecord(side->join[depth], side->stream) != hipSuccess) return false;
+    if (!recurse(G, U, ldu, n, o + s1, s2, info, st, side, depth + 1)) return false;
+    if (hipStreamWaitEvent(st, side->join[depth], 0) != hipSuccess) return false;
+    return launch_node(OpX21{nd}, s2, s1, st);
+  }
+  return launch_node2(OpSyrk{nd}, s2, s2, OpT{nd}, s2, s1, st) &&
+         recurse(G, U, ldu, n, o + s1, s2, info, st, side, depth + 1) && launch_node(OpX21{nd}, s2, s1, st);
 }
 
 }  // namespace
@@ -650,7 +711,17 @@ ptq_status cholesky_launch(const double* H, int64_t ldh, int64_t n, double damp,
   dim3 g((unsigned)ceil_div(n, 256), (unsigned)n);
   build_work_kernel<<<g, 256, 0, st>>>(H, ldh, (int)n, scal, G, U, ldu);
   PTQ_HIP_CHECK_LAUNCH();
-  if (!recurse(G, U, (int)ldu, (int)n, 0, (int)n, info, st)) return PTQ_ERR_HIP;
+  // the helper stream only where a node is large enough to use it (the top node is the largest)
+  const int top1 = (int)(ceil_div(n, kLeaf) / 2) * kLeaf;
+  Side* side = (n > kLeaf && tile_class((int)n - top1, top1) == 2) ? side_for_device() : nullptr;
+  bool ok;
+  if (side) {
+    std::lock_guard<std::mutex> hold(side->lock);
+    ok = recurse(G, U, (int)ldu, (int)n, 0, (int)n, info, st, side, 0);
+  } else {
+    ok = recurse(G, U, (int)ldu, (int)n, 0, (int)n, info, st, nullptr, 0);
+  }
+  if (!ok) return PTQ_ERR_HIP;
   PTQ_HIP_CHECK_LAUNCH();
   return PTQ_OK;
 }
