@@ -302,21 +302,26 @@ def mfma_control(ptq, L):
     import torch
     from paper_2601_19675_amd import build as b
     lib = ctypes.CDLL(b.PROBE_LIB)
-    lib.ptq_probe_mfma.restype = ctypes.c_double
-    lib.ptq_probe_mfma.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
-                                   ctypes.c_void_p, ctypes.c_void_p]
+    for fn in (lib.ptq_probe_mfma, lib.ptq_probe_mfma_vgpr):
+        fn.restype = ctypes.c_double
+        fn.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
+                       ctypes.c_void_p]
     blocks = 2048
     outb = torch.empty(blocks * 256, dtype=torch.float32, device="cuda")
     clk = torch.zeros(2, dtype=torch.int64, device="cuda")
     st = torch.cuda.current_stream().cuda_stream
     res = {"register_only_loops": []}
-    for kind, name, iters, peak in ((0, "bf16 32x32x16", 9000, PEAK_BF16_TFLOPS), (1, "f64 16x16x4", 36000, PEAK_F64_TFLOPS)):
+    # (accumulators in AGPRs is how the bf16 Hessian kernel is compiled, in VGPRs how the float64 kernels are)
+    for kind, name, iters, peak, probe in (
+            (0, "bf16 32x32x16, accumulators in AGPRs", 9000, PEAK_BF16_TFLOPS, lib.ptq_probe_mfma),
+            (1, "f64 16x16x4, accumulators in AGPRs", 36000, PEAK_F64_TFLOPS, lib.ptq_probe_mfma),
+            (1, "f64 16x16x4, accumulators in VGPRs", 36000, PEAK_F64_TFLOPS, lib.ptq_probe_mfma_vgpr)):
         for rnd in (0, 1):
-            lib.ptq_probe_mfma(kind, rnd, 200, blocks, outb.data_ptr(), clk.data_ptr(), st)
+            probe(kind, rnd, 200, blocks, outb.data_ptr(), clk.data_ptr(), st)
             torch.cuda.synchronize()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
-            flops = lib.ptq_probe_mfma(kind, rnd, iters, blocks, outb.data_ptr(), clk.data_ptr(), st)
+            flops = probe(kind, rnd, iters, blocks, outb.data_ptr(), clk.data_ptr(), st)
             e1.record()
             torch.cuda.synchronize()
             ms = e0.elapsed_time(e1)

@@ -30,6 +30,43 @@ def _hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
+def check_dpp_wait_states(asm_text: str) -> int:
+    """The leaf kernel of cholesky.hip issues DPP instructions from inline assembly, where the compiler
+    does not count wait states: a DPP read needs two (two instructions, or s_nop) after a vector
+    instruction wrote the register it reads.  The source keeps that distance by construction; this walks
+    the generated assembly and raises if the compiler has put something closer (a copy into an
+    accumulator, say).  Returns the number of DPP instructions seen."""
+    import re
+
+    def regs(tok):
+        m = re.match(r"v\[(\d+):(\d+)\]", tok)
+        if m:
+            return set(range(int(m.group(1)), int(m.group(2)) + 1))
+        m = re.match(r"v(\d+)$", tok)
+        return {int(m.group(1))} if m else set()
+
+    lines = [l.strip() for l in asm_text.splitlines()]
+    lines = [l for l in lines if l and not l.startswith((";", ".")) and not l.endswith(":")]
+    seen = 0
+    for i, l in enumerate(lines):
+        if "row_newbcast" not in l:
+            continue
+        seen += 1
+        src0 = regs(l.split(None, 1)[1].split(",")[1].split()[0])
+        waited, k = 0, i - 1
+        while waited < 2 and k >= 0:
+            p = lines[k]
+            m = re.match(r"s_nop (\d+)", p)
+            if m:
+                waited += int(m.group(1)) + 1
+            else:
+                if p.startswith("v_") and regs(p.split(None, 1)[1].split(",")[0].split()[0]) & src0:
+                    raise RuntimeError(f"DPP read too close to the write of its source:\n  {p}\n  {l}")
+                waited += 1
+            k -= 1
+    return seen
+
+
 def build(verbose: bool = True) -> str:
     """Compiles every source (always, also when a library is already there) and links."""
     hipcc = _hipcc()
@@ -47,15 +84,34 @@ def build(verbose: bool = True) -> str:
             print("\n".join(errs), file=sys.stderr)
         return obj
 
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
+    def check_leaf_assembly():
+        cmd = [hipcc, *[f for f in FLAGS if f not in ("-fPIC", "-Wall")], *VGPR_FORM, "-S", "--cuda-device-only",
+               os.path.join(CSRC, "cholesky.hip"), "-o", "-"]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"hipcc -S failed for cholesky.hip:\n{r.stderr}")
+        if check_dpp_wait_states(r.stdout) == 0:
+            raise RuntimeError("cholesky.hip: no DPP instruction found in the generated assembly (check out of date?)")
+
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES) + 1)) as ex:
+        checked = ex.submit(check_leaf_assembly)
         objs = list(ex.map(compile_one, SOURCES))
+        checked.result()
     r = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs],
                        capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")
-    # the register-only MFMA probe, a library of its own
-    r = subprocess.run([hipcc, *[f for f in FLAGS if f != "-Wall"], "-shared", os.path.join(CSRC, "probe_mfma.hip"), "-o",
-                        PROBE_LIB], capture_output=True, text=True)
+    # the register-only MFMA probe, a library of its own: one source, compiled in both accumulator forms
+    probe_objs = []
+    for tag, extra in (("agpr", []), ("vgpr", ["-DPTQ_PROBE_VGPR_FORM", *VGPR_FORM])):
+        obj = os.path.join(CSRC, f"probe_mfma_{tag}.o")
+        r = subprocess.run([hipcc, *[f for f in FLAGS if f != "-Wall"], *extra, "-c", os.path.join(CSRC, "probe_mfma.hip"),
+                            "-o", obj], capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"probe library failed:\n{r.stdout}\n{r.stderr}")
+        probe_objs.append(obj)
+    r = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", PROBE_LIB, *probe_objs],
+                       capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"probe library failed:\n{r.stdout}\n{r.stderr}")
     if verbose:

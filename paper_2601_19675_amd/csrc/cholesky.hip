@@ -78,321 +78,407 @@ __global__ __launch_bounds__(256) void build_work_kernel(const double* __restric
 }
 
 // ---- leaf: X = inverse of the Cholesky factor of G[o:o+s, o:o+s], s <= 128 ---
-// The block lives in LDS and is processed in 16 x 16 sub-blocks, right-looking.  Factoring a
-// diagonal sub-block and inverting its factor is a chain of dependent operations that one
-// wave does in registers (lane = row, pivots and multipliers passed around with v_readlane,
-// no barriers); everything else is 16x16x4 float64 MFMA work on sub-blocks.  The chain is the
-// critical path, so the steps are skewed: while wave 0 factors diagonal block d+1 (after
-// applying step d's update to it itself), the other waves apply the rest of step d's trailing
-// update and pre-compute row d+1 of the inverse.
+// The block lives in LDS and is processed in 16 x 16 sub-blocks, right-looking, by eight waves.
+// The critical path is the chain of 128 pivots, so the pivots of block column d (a 16-column
+// panel with all rows below it) are the only work that waits for anything:
 //
-//   P1(d)  all waves   L_id = G_id X_dd^T  (i > d);   X_dj = -X_dd T_dj  (j < d)
-//   P2(d)  wave 0      G_{d+1,d+1} -= L_{d+1,d} L_{d+1,d}^T ;  factor + invert it -> X_{d+1,d+1}
-//          waves 1-3   G_ij -= L_id L_jd^T  (i >= j > d, all but (d+1,d+1));
-//                      T_{d+1,j} = sum_{k=j..d} L_{d+1,k} X_kj  (j <= d)
+//   A(d)  waves 0-3   panel d: factor the diagonal sub-block, invert its factor (X_dd) and form
+//                     L_id for every i > d
+//         waves 4-7   G_ij -= L_{i,d-1} L_{j,d-1}^T  for i >= j > d                    ("R(d-1)")
+//                     T_ij += L_{i,d-2} X_{d-2,j}  for i > d-2, j <= d-2             ("C(d-2)")
+//   B(d)  all waves   G_{i,d+1} -= L_id L_{d+1,d}^T  for i > d     (what panel d+1 waits for)
+//                     X_{d-1,j} = -X_{d-1,d-1} T_{d-1,j}  for j < d-1               ("F(d-1)")
+//
+// and after the last panel  A': C(nb-2);  B': F(nb-1).  The off-diagonal part of the inverse
+// therefore trails the factorization by two steps and is off the chain except for this tail.
+//
+// The panel: each of the four waves holds the 16 x 16 diagonal sub-block, one column per lane
+// and replicated in its four rows of 16 lanes (register k = row k), plus a sixteenth of the rows
+// below it (seven registers).  Eliminating pivot j is then  v -= bcast_j(v) * (D(j,c) / D(j,j))
+// on every register, where bcast_j hands lane j's value to its row of 16 lanes (DPP
+// row_newbcast, no LDS, no scalar round trip) and D(j,c) is the lane's own register j (the
+// trailing block is kept symmetric): one multiply-add per register and pivot, all columns at
+// once.  The columns stay unscaled until the end, so the chain per pivot is one broadcast, one
+// reciprocal square root (hardware estimate + two Newton steps), two multiplications and the
+// multiply-add of the next pivot's row.  The column operations that turn D into L, applied to
+// the rows of the identity, give L^-T: four more registers per wave and the inverse of the
+// diagonal factor needs no pass of its own.
 //
 // X_ij (i > j) and before it T_ij are parked in the unused upper sub-block (j, i); the
-// inverses of the diagonal sub-blocks have their own array.
-__device__ __forceinline__ double lane_bcast(double v, int src) {
-  const int lo = __builtin_amdgcn_readlane(__double2loint(v), src);
-  const int hi = __builtin_amdgcn_readlane(__double2hiint(v), src);
-  return __hiloint2double(hi, lo);
+// inverses of the diagonal sub-blocks have a strip of their own.
+constexpr int kLeafThreads = 512;
+constexpr int kLeafP = kLeaf + 1;   // pitch of the LDS block
+// LDS: the block [128][129]; the inverses of the diagonal sub-blocks side by side in a strip [16][129] of
+// the same pitch; a dump slot per thread of the panel waves [256]
+constexpr size_t kLeafLdsBytes = (size_t)(kLeaf * kLeafP + 16 * kLeafP + 256) * sizeof(double);
+
+// The DPP forms below are written as assembly because the compiler neither folds a 64-bit DPP move
+// into the multiply-add nor sees these instructions when it counts wait states: a DPP read needs two
+// wait states (two instructions, or s_nop 1) after a vector write of the register it reads.  Every
+// instruction of a wave costs an issue slot of four cycles, an s_nop included, so the statements
+// below carry none: the caller keeps the distance.  Each multiply-add reads, through DPP, only the
+// accumulator it updates, which in the panel was last written a whole pivot earlier; the one read
+// that follows its producer closely (the broadcast of the next pivot) is placed two multiply-adds
+// after it.  (That the compiler puts no copy of an accumulator in front of a statement is checked
+// on the generated assembly when the library is built.)
+template <int J>
+__device__ __forceinline__ double row_bcast(double v) {
+  double p;
+  asm volatile("v_mov_b64_dpp %0, %1 row_newbcast:%2 row_mask:0xf bank_mask:0xf" : "=v"(p) : "v"(v), "n"(J));
+  return p;
+}
+template <int J>
+__device__ __forceinline__ void fmac_bcast1(double nc, double& a) {
+  asm volatile("v_fmac_f64_dpp %0, %0, %1 row_newbcast:%2 row_mask:0xf bank_mask:0xf" : "+v"(a) : "v"(nc), "n"(J));
+}
+// (the same, naming a value that must exist before it: the statements keep their order, so whatever
+// computes `before` cannot sink below this one, and unlike an in-out operand it costs no wait state)
+template <int J>
+__device__ __forceinline__ void fmac_bcast1_after(double nc, double& a, double before) {
+  asm volatile("v_fmac_f64_dpp %0, %0, %1 row_newbcast:%2 row_mask:0xf bank_mask:0xf"
+               : "+v"(a)
+               : "v"(nc), "n"(J), "v"(before));
+}
+// r[LO .. HI) += bcast_J(r) * nc
+template <int J, int LO, int HI, int N>
+__device__ __forceinline__ void fmac_bcast_range(double nc, double (&r)[N]) {
+  if constexpr (LO < HI) {
+    fmac_bcast1<J>(nc, r[LO]);
+    fmac_bcast_range<J, LO + 1, HI>(nc, r);
+  }
 }
 
-constexpr int kLeafP = kLeaf + 1;   // pitch of the LDS block
-constexpr int kXdP = 17;            // pitch of a stored 16 x 16 diagonal inverse
-constexpr size_t kLeafLdsBytes = (size_t)(kLeaf * kLeafP + (kLeaf / 16) * 16 * kXdP) * sizeof(double);
+constexpr int kPanelWaves = 2;                               // waves that factor the panel (each on a SIMD of its own)
+static_assert(kPanelWaves == 2, "the work split below gives waves 2, 3, 6, 7 the products and 4, 5 the stores");
+constexpr int kPanelSlots = 4 * kPanelWaves;                 // rows of 16 lanes among them
+constexpr int kRowsPerBlock = 16 / kPanelSlots;              // rows of each sub-block that one of them holds
+constexpr int kPanelRows = (kLeaf / 16 - 1) * kRowsPerBlock; // registers for the rows below the diagonal sub-block
+constexpr int kIdentityRows = 16 / kPanelWaves;              // rows of the identity per wave: i = kPanelWaves m + wave
 
-__global__ __launch_bounds__(256) void leaf_kernel(const double* __restrict__ G, int n, int o, int s,
-                                                   double* __restrict__ U, int64_t ldu, int32_t* info) {
+// The registers of a panel wave: the diagonal sub-block, its share of the rows below, and its four
+// rows of the identity that the same column operations turn into the inverse of the factor.
+struct PanelRegs {
+  double Dg[16], A[kPanelRows], E[kIdentityRows];
+};
+// The I-th of the multiply-adds of pivot J that nothing waits for: rows J+2 .. 15 of the diagonal
+// sub-block, then the rows below it, then the identity rows that can be non-zero in column J (row
+// kPanelWaves m + wave is zero left of its own column, so m <= J / kPanelWaves).
+template <int J, int I>
+__device__ __forceinline__ void panel_pending(double nc, PanelRegs& R, double before) {
+  constexpr int nd = 14 - J, ne = J / kPanelWaves + 1;
+  if constexpr (I < nd)
+    fmac_bcast1_after<J>(nc, R.Dg[J + 2 + I], before);
+  else if constexpr (I < nd + kPanelRows)
+    fmac_bcast1_after<J>(nc, R.A[I - nd], before);
+  else if constexpr (I < nd + kPanelRows + ne)
+    fmac_bcast1_after<J>(nc, R.E[I - nd - kPanelRows], before);
+  else
+    asm volatile("" : : "v"(before));
+}
+template <int J, int LO>
+__device__ __forceinline__ void panel_pending_from(double nc, PanelRegs& R) {
+  constexpr int nd = 14 - J, ne = J / kPanelWaves + 1;
+  if constexpr (LO < nd + kPanelRows + ne) {
+    panel_pending<J, LO>(nc, R, nc);
+    panel_pending_from<J, LO + 1>(nc, R);
+  }
+}
+
+// Stage J of the panel: the multiply-adds of pivot J (coefficients nc), written out interleaved with the
+// chain that leads to pivot J+1's coefficients -- broadcast of D(J+1,J+1), reciprocal square root,
+// r^2 D(J+1, c) -- one multiply-add in the shadow of each dependent operation.  The compiler does not know
+// what the assembly costs and would sort the two apart again, so each operation of the chain is fenced:
+// the multiply-add after it names its result (volatile statements keep their order, so the operation
+// cannot sink below the statement), and a scheduling barrier on either side keeps the scheduler from
+// moving it.  A pivot that is not positive makes r and everything after it non-finite; the caller finds
+// it in rl.
+#define PTQ_CHAIN(stmt, I, dep)                 \
+  __builtin_amdgcn_sched_barrier(0);            \
+  stmt;                                         \
+  __builtin_amdgcn_sched_barrier(0);            \
+  panel_pending<J, I>(nc, R, dep);
+
+template <int J>
+__device__ __forceinline__ void panel_stage(PanelRegs& R, double nc, double& rl, int c) {
+  if constexpr (J == 15) {
+    panel_pending_from<15, 0>(nc, R);
+  } else {
+    fmac_bcast1<J>(nc, R.Dg[J + 1]);  // the next pivot's row first
+    panel_pending<J, 0>(nc, R, nc);   // (two statements, always there: the wait states of the
+    panel_pending<J, 1>(nc, R, nc);   //  DPP read of the row just written)
+    static_assert(kPanelRows >= 2, "the broadcast needs two statements between it and its producer");
+    const double p = row_bcast<J + 1>(R.Dg[J + 1]);
+    PTQ_CHAIN(double r = __builtin_amdgcn_rsq(p), 2, r)
+    PTQ_CHAIN(const double h = -0.5 * p, 3, h)
+    PTQ_CHAIN(const double dm = (c > J + 1) ? R.Dg[J + 1] : 0.0, 4, dm)   // D(J+1, c) for the columns still to come
+    PTQ_CHAIN(double t = h * r, 5, t)
+    PTQ_CHAIN(double u = fma(t, r, 1.5), 6, u)
+    PTQ_CHAIN(r = r * u, 7, r)
+    PTQ_CHAIN(t = h * r, 8, t)
+    PTQ_CHAIN(u = fma(t, r, 1.5), 9, u)
+    PTQ_CHAIN(r = r * u, 10, r)
+    PTQ_CHAIN(const double rr = r * r, 11, rr)
+    PTQ_CHAIN(const double next = -(rr * dm), 12, next)
+    panel_pending_from<J, 13>(nc, R);
+    rl = (c == J + 1) ? r : rl;
+    panel_stage<J + 1>(R, next, rl, c);
+  }
+}
+#undef PTQ_CHAIN
+
+__global__ __launch_bounds__(kLeafThreads) void leaf_kernel(const double* __restrict__ G, int n, int o, int s,
+                                                            double* __restrict__ U, int64_t ldu, int32_t* info) {
   extern __shared__ double lds[];
-  double* S = lds;                      // [128][129]
-  double* XD = lds + kLeaf * kLeafP;    // [8][16][17] inverses of the diagonal sub-blocks
+  double* S = lds;                                    // [128][129]
+  double* XD = lds + kLeaf * kLeafP;                  // [16][129]: X_kk(i, j) at XD[i * 129 + 16 k + j]
+  double* DUMP = XD + 16 * kLeafP;                    // [256]
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: keeps the work-list arithmetic scalar
   const int nb = (s + 15) >> 4, sp = nb << 4;
   const int l16 = lane & 15, lq = lane >> 4;
 
-  // load the lower triangle: thread = (column j, row parity), all its loads in flight at once
+  // load the lower triangle: thread = (column j, row mod 4), all its loads in flight at once
   // (padding rows / columns beyond s: identity)
   {
     const int j = tid & 127, i0 = tid >> 7;
-    double v[kLeaf / 2];
+    double v[kLeaf / 4];
 #pragma unroll
-    for (int u = 0; u < kLeaf / 2; ++u) {
-      const int i = i0 + 2 * u;
+    for (int u = 0; u < kLeaf / 4; ++u) {
+      const int i = i0 + 4 * u;
       const bool ld = (i < s) & (j <= i);
       v[u] = ld ? G[(int64_t)(o + i) * n + o + j] : ((i == j) ? 1.0 : 0.0);
     }
 #pragma unroll
-    for (int u = 0; u < kLeaf / 2; ++u) {
-      const int i = i0 + 2 * u;
+    for (int u = 0; u < kLeaf / 4; ++u) {
+      const int i = i0 + 4 * u;
       if (i < sp && j < sp) S[i * kLeafP + j] = v[u];
     }
   }
   __syncthreads();
 
-  // Factor diagonal sub-block d and invert its factor, one wave, all 64 lanes.  The symmetric
-  // 16 x 16 block M sits in four registers per lane in the accumulator layout of the MFMA read
-  // through the symmetry: lane (lq, l16), register r holds M(l16, 4 r + lq).  Column group g
-  // (columns 4g .. 4g+3) is then register g, and that register is at once the A and the B
-  // fragment of the 16 x 4 panel, so the rank-4 update of the later column groups is one MFMA
-  // with no data movement.  Inside a group the pivots go one by one: the pivot column is
-  // handed to the other lane groups with two lane permutes.  With `update`, step d-1's
-  // contribution L_{d,d-1} L_{d,d-1}^T is taken off the block first.
-  // The inverse follows by block forward substitution with 4 x 4 blocks: the four diagonal
-  // 4 x 4 inverses are computed from broadcast entries, then per block row two MFMAs:
-  // X_h = D_h - Dinv_h (T_h),  T += L(:, h) X_h.
-  auto factor_diag = [&](int d, bool update) {
-    const int b0 = 16 * d;
-    double m[4];
+  // ---- the panel of block column d (waves 0-3).  Taken branches are what this wave can least afford
+  // (each costs tens of cycles of instruction fetch), hence addresses chosen by selection, not code by branch.
+  auto panel = [&](int d) {
+    const int b0 = 16 * d, c = l16;
+    const int below = nb - 1 - d;          // sub-blocks under the diagonal one
+    const int rr = 4 * wave + lq;          // this lane's row of 16 lanes among the panel's
+    PanelRegs R;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int c = 4 * r + lq;
-      const int hi = l16 > c ? l16 : c, lo = l16 > c ? c : l16;
-      m[r] = S[(b0 + hi) * kLeafP + b0 + lo];
-    }
-    if (update) {
-      f64x4 acc = {0.0, 0.0, 0.0, 0.0};
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        const double lv = S[(b0 + l16) * kLeafP + b0 - 16 + 4 * kk + lq];
-        acc = __builtin_amdgcn_mfma_f64_16x16x4f64(lv, lv, acc, 0, 0, 0);
-      }
-#pragma unroll
-      for (int r = 0; r < 4; ++r) m[r] -= acc[r];
-    }
-    auto lane_fetch = [&](double v, int src_lane) -> double {  // per-lane source (ds_bpermute)
-      const int lo = __builtin_amdgcn_ds_bpermute(src_lane << 2, __double2loint(v));
-      const int hi = __builtin_amdgcn_ds_bpermute(src_lane << 2, __double2hiint(v));
-      return __hiloint2double(hi, lo);
-    };
-    int bad = -1;
-    double rinv[16];
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const int j = 4 * g + k;
-        double p = lane_bcast(m[g], 16 * k + j);
-        if (!(p > 0.0)) {
-          if (bad < 0) bad = j;
-          p = 1.0;
-        }
-        // 1/sqrt(p) by two Newton steps on the hardware estimate, then one
-        // correction each for sqrt(p) and its reciprocal (no division, no sqrt call)
-        const double h = 0.5 * p;
-        double r = __builtin_amdgcn_rsq(p);
-        r = r * fma(-h * r, r, 1.5);
-        r = r * fma(-h * r, r, 1.5);
-        double sq = p * r;
-        sq = fma(fma(-sq, sq, p), 0.5 * r, sq);
-        r = fma(fma(-sq, r, 1.0), r, r);
-        rinv[j] = r;
-        const double colv = (l16 == j) ? sq : (l16 > j ? m[g] * r : 0.0);
-        m[g] = (lq == k) ? colv : m[g];
-        if (k < 3) {
-          const double cj = lane_fetch(m[g], 16 * k + l16);          // L(own row, j)
-          const double mu = lane_fetch(m[g], 16 * k + 4 * g + lq);   // L(own column, j)
-          m[g] = (lq > k) ? fma(-cj, mu, m[g]) : m[g];
-        }
-      }
-      if (g < 3) {
-        const f64x4 acc = __builtin_amdgcn_mfma_f64_16x16x4f64(m[g], m[g], f64x4{0.0, 0.0, 0.0, 0.0}, 0, 0, 0);
-#pragma unroll
-        for (int r = g + 1; r < 4; ++r) m[r] -= acc[r];
-      }
-    }
-    if (bad >= 0 && b0 + bad < s && lane == 0 && info[0] == PTQ_OK) {
-      info[0] = PTQ_ERR_NOT_SPD;
-      info[1] = n - 1 - (o + b0 + bad);
-    }
-    // diagonal 4 x 4 inverses: dA[h] = Dinv(:, 4h..4h+3) as an A fragment (lane (lq, l16) holds
-    // x_ab with a = l16 - 4h, b = lq), dD[h] the same block in the accumulator layout
-    double dA[4], dD[4];
-#pragma unroll
-    for (int h = 0; h < 4; ++h) {
-      const double l10 = lane_bcast(m[h], 4 * h + 1), l20 = lane_bcast(m[h], 4 * h + 2);
-      const double l30 = lane_bcast(m[h], 4 * h + 3), l21 = lane_bcast(m[h], 16 + 4 * h + 2);
-      const double l31 = lane_bcast(m[h], 16 + 4 * h + 3), l32 = lane_bcast(m[h], 32 + 4 * h + 3);
-      const double r0 = rinv[4 * h], r1 = rinv[4 * h + 1], r2 = rinv[4 * h + 2], r3 = rinv[4 * h + 3];
-      const double x10 = -r1 * (l10 * r0);
-      const double x21 = -r2 * (l21 * r1);
-      const double x32 = -r3 * (l32 * r2);
-      const double x20 = -r2 * fma(l21, x10, l20 * r0);
-      const double x31 = -r3 * fma(l32, x21, l31 * r1);
-      const double x30 = -r3 * fma(l32, x20, fma(l31, x10, l30 * r0));
-      const int a = l16 - 4 * h, bq = lq;
-      double v = 0.0;
-      v = (a == 0 && bq == 0) ? r0 : v;
-      v = (a == 1 && bq == 1) ? r1 : v;
-      v = (a == 2 && bq == 2) ? r2 : v;
-      v = (a == 3 && bq == 3) ? r3 : v;
-      v = (a == 1 && bq == 0) ? x10 : v;
-      v = (a == 2 && bq == 1) ? x21 : v;
-      v = (a == 3 && bq == 2) ? x32 : v;
-      v = (a == 2 && bq == 0) ? x20 : v;
-      v = (a == 3 && bq == 1) ? x31 : v;
-      v = (a == 3 && bq == 0) ? x30 : v;
-      dA[h] = v;
-      // accumulator layout: lane (lq = a', l16 = 4h + b') wants x_{a'b'}, held by lane (b', 4h + a')
-      const int bp = l16 - 4 * h;
-      const bool in = (bp >= 0) & (bp < 4);
-      const double t = lane_fetch(v, in ? 16 * bp + 4 * h + lq : lane);
-      dD[h] = in ? t : 0.0;
-    }
-    f64x4 T = {0.0, 0.0, 0.0, 0.0};
-    double X[4];
-#pragma unroll
-    for (int h = 0; h < 4; ++h) {
-      if (h > 0) {
-        const f64x4 o = __builtin_amdgcn_mfma_f64_16x16x4f64(dA[h], T[h], f64x4{0.0, 0.0, 0.0, 0.0}, 0, 0, 0);
-        X[h] = dD[h] - o[h];
-      } else {
-        X[h] = dD[h];
-      }
-      if (h < 3) T = __builtin_amdgcn_mfma_f64_16x16x4f64(m[h], X[h], T, 0, 0, 0);
+    for (int k = 0; k < 16; ++k) {
+      const int hi = k > c ? k : c, lo = k > c ? c : k;
+      R.Dg[k] = S[(b0 + hi) * kLeafP + b0 + lo];
     }
 #pragma unroll
-    for (int r = 0; r < 4; ++r) XD[(d * 16 + 4 * r + lq) * kXdP + l16] = X[r];
-  };
-  auto fragA = [&](const double* blk, int kk) { return blk[l16 * kLeafP + 4 * kk + lq]; };
-
-  if (wave == 0) factor_diag(0, false);
-  __syncthreads();
-
-  for (int d = 0; d < nb; ++d) {
-    const int b0 = 16 * d;
-    // ---- P1: column d of L below the diagonal, row d of the inverse left of it
+    for (int m = 0; m < kIdentityRows; ++m) {
+      R.E[m] = (c == kPanelWaves * m + wave) ? 1.0 : 0.0;
+      asm volatile("" : "+v"(R.E[m]));   // in a register of its own from here on, not copied into one at its first use
+    }
+    // rows that do not exist (t >= below) read some valid element and are never written back: what
+    // they hold stays in their own register
+    double* sub = S + (b0 + 16 + rr) * kLeafP + b0 + c;   // this lane's first element of the first sub-block below
+    double* own = S + (b0 + c) * kLeafP + b0 + c;
+    // register t: sub-block t / kRowsPerBlock, row (t % kRowsPerBlock) * kPanelSlots + rr of it
+    auto row_of = [](int t) { return ((t / kRowsPerBlock) * 16 + (t % kRowsPerBlock) * kPanelSlots) * kLeafP; };
+#pragma unroll
+    for (int t = 0; t < kPanelRows; ++t) R.A[t] = *((t < below * kRowsPerBlock) ? sub + row_of(t) : own);
+    // pivot 0's coefficients, then the sixteen stages
+    double rl;
     {
-      const int nB = nb - 1 - d, nItems = nB + d;
-      for (int q = wave; q < nItems; q += 4) {
-        f64x4 acc = {0.0, 0.0, 0.0, 0.0};
-        if (q < nB) {
-          const int ib = d + 1 + q;  // wave 0 gets ib = d + 1, which it needs first in P2
-#pragma unroll
-          for (int kk = 0; kk < 4; ++kk) {
-            const double av = fragA(S + (16 * ib) * kLeafP + b0, kk);
-            const double bv = XD[(d * 16 + l16) * kXdP + 4 * kk + lq];
-            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
-          }
-#pragma unroll
-          for (int r = 0; r < 4; ++r) S[(16 * ib + 4 * r + lq) * kLeafP + b0 + l16] = acc[r];
-        } else {
-          const int jb = q - nB;  // X_dj = -X_dd T_dj, in place in the parked block (jb, d)
-          double* blk = S + (16 * jb) * kLeafP + b0;
-#pragma unroll
-          for (int kk = 0; kk < 4; ++kk) {
-            const double av = -XD[(d * 16 + l16) * kXdP + 4 * kk + lq];
-            const double bv = blk[(4 * kk + lq) * kLeafP + l16];
-            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
-          }
-#pragma unroll
-          for (int r = 0; r < 4; ++r) blk[(4 * r + lq) * kLeafP + l16] = acc[r];
-        }
-      }
+      const double p = row_bcast<0>(R.Dg[0]);
+      const double h = -0.5 * p;
+      double r = __builtin_amdgcn_rsq(p);
+      r = r * fma(h * r, r, 1.5);
+      r = r * fma(h * r, r, 1.5);
+      rl = r;
+      const double nc = (c > 0) ? -((r * r) * R.Dg[0]) : 0.0;
+      panel_stage<0>(R, nc, rl, c);
     }
-    __syncthreads();
-    if (d + 1 >= nb) break;
-    // ---- P2
+    // scale column c by its reciprocal pivot; only now do the entries become those of L
+    // (rows that do not exist go to a dump slot of the lane's own)
+    double* dump = DUMP + tid;   // (tid < 64 kPanelWaves)
+#pragma unroll
+    for (int t = 0; t < kPanelRows; ++t) *((t < below * kRowsPerBlock) ? sub + row_of(t) : dump) = R.A[t] * rl;
+    // the same column operations applied to the identity give the inverse factor transposed:
+    // X_dd(c, i) = E_i(c) r_c, for this wave's rows i = kPanelWaves m + wave
+    if (lq == 0) {
+#pragma unroll
+      for (int m = 0; m < kIdentityRows; ++m) XD[c * kLeafP + b0 + kPanelWaves * m + wave] = R.E[m] * rl;
+    }
     if (wave == 0) {
-      factor_diag(d + 1, true);
-    } else {
-      // row d+1 of the inverse, longest sums first: T_{d+1,j} = sum_{k=j..d} L_{d+1,k} X_kj
-      // (two accumulators, so that consecutive k blocks do not wait for each other)
-      const int ib = d + 1;
-      for (int jb = wave - 1; jb <= d; jb += 3) {
-        f64x4 t0 = {0.0, 0.0, 0.0, 0.0}, t1 = {0.0, 0.0, 0.0, 0.0};
-        for (int k = jb; k <= d; k += 2) {
-          const bool two = k + 1 <= d;
-          const int k1 = two ? k + 1 : k;
-          double av0[4], bv0[4], av1[4], bv1[4];
+      if (lq == 0) {
+        // (rows above the diagonal get what the registers hold: nothing reads that triangle)
 #pragma unroll
-          for (int kk = 0; kk < 4; ++kk) {
-            av0[kk] = fragA(S + (16 * ib) * kLeafP + 16 * k, kk);
-            bv0[kk] = (k == jb) ? XD[(jb * 16 + 4 * kk + lq) * kXdP + l16]
-                                : S[(16 * jb + 4 * kk + lq) * kLeafP + 16 * k + l16];
-            av1[kk] = fragA(S + (16 * ib) * kLeafP + 16 * k1, kk);
-            bv1[kk] = S[(16 * jb + 4 * kk + lq) * kLeafP + 16 * k1 + l16];
-          }
-#pragma unroll
-          for (int kk = 0; kk < 4; ++kk) {
-            t0 = __builtin_amdgcn_mfma_f64_16x16x4f64(av0[kk], bv0[kk], t0, 0, 0, 0);
-            t1 = __builtin_amdgcn_mfma_f64_16x16x4f64(av1[kk], two ? bv1[kk] : 0.0, t1, 0, 0, 0);
-          }
-        }
-#pragma unroll
-        for (int r = 0; r < 4; ++r) S[(16 * jb + 4 * r + lq) * kLeafP + 16 * ib + l16] = t0[r] + t1[r];
+        for (int k = 0; k < 16; ++k) S[(b0 + k) * kLeafP + b0 + c] = R.Dg[k] * rl;
       }
-      // trailing sub-blocks (i2 >= j2 > d), triangular index 1 .. cnt-1 (index 0 = (d+1, d+1) is
-      // wave 0's), dealt round-robin after the d+1 sums above and processed two at a time
-      const int T = nb - 1 - d;
-      const int cnt = T * (T + 1) / 2;
-      int c0 = (wave - 1 - d) % 3;
-      if (c0 < 0) c0 += 3;
-      if (c0 == 0) c0 = 3;
-      // (ii, rem) = row / column of triangular index c, advanced incrementally (index += 3)
-      int ii = 0, rem = c0;
-      auto settle = [&]() {
-        while (rem > ii) {
-          rem -= ii + 1;
-          ++ii;
-        }
-      };
-      for (int c = c0; c < cnt; c += 6) {
-        const bool two = c + 3 < cnt;
-        settle();
-        const int ia = d + 1 + ii, ja = d + 1 + rem;
-        int ib2 = ia, jb2 = ja;
-        rem += 3;
-        if (two) {
-          settle();
-          ib2 = d + 1 + ii;
-          jb2 = d + 1 + rem;
-        }
-        rem += 3;
-        double a0[4], b0v[4], a1[4], b1[4], cur0[4], cur1[4];
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-          a0[kk] = fragA(S + (16 * ia) * kLeafP + b0, kk);
-          b0v[kk] = fragA(S + (16 * ja) * kLeafP + b0, kk);
-          a1[kk] = fragA(S + (16 * ib2) * kLeafP + b0, kk);
-          b1[kk] = fragA(S + (16 * jb2) * kLeafP + b0, kk);
-          cur0[kk] = S[(16 * ia + 4 * kk + lq) * kLeafP + 16 * ja + l16];
-          cur1[kk] = S[(16 * ib2 + 4 * kk + lq) * kLeafP + 16 * jb2 + l16];
-        }
-        f64x4 acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = {0.0, 0.0, 0.0, 0.0};
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-          acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64(a0[kk], b0v[kk], acc0, 0, 0, 0);
-          acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a1[kk], b1[kk], acc1, 0, 0, 0);
-        }
-#pragma unroll
-        for (int r = 0; r < 4; ++r) S[(16 * ia + 4 * r + lq) * kLeafP + 16 * ja + l16] = cur0[r] - acc0[r];
-        if (two) {
-#pragma unroll
-          for (int r = 0; r < 4; ++r) S[(16 * ib2 + 4 * r + lq) * kLeafP + 16 * jb2 + l16] = cur1[r] - acc1[r];
+      // the first pivot that was not positive: its reciprocal root is the first that is not a positive number
+      const unsigned long long notpos = __ballot(!(rl > 0.0 && rl < __builtin_huge_val())) & 0xffffull;
+      if (notpos != 0) {
+        const int bad = __builtin_ctzll(notpos);
+        if (b0 + bad < s && lane == 0 && info[0] == PTQ_OK) {
+          info[0] = PTQ_ERR_NOT_SPD;
+          info[1] = n - 1 - (o + b0 + bad);
         }
       }
     }
-    __syncthreads();
-  }
+  };
 
-  // X(i, j), i >= j, goes to U[n-1-(o+i)][n-1-(o+j)]: thread = (column j, row parity)
-  {
-    const int j = tid & 127, i0 = tid >> 7, jb = j >> 4;
-    double* urow = U + (int64_t)(n - 1 - o) * ldu + (n - 1 - (o + j));
-#pragma unroll 8
-    for (int u = 0; u < kLeaf / 2; ++u) {
-      const int i = i0 + 2 * u;
+  // ---- 16 x 16 x 16 sub-block products  C = (C or 0) +- A B,  one wave each, two at a time so that
+  // the MFMA chain of one fills the latency of the other.  All operands have the pitch of the block, so
+  // every fragment is one LDS read at an immediate offset from a per-item base, and the work loops
+  // contain no branch but their own.  (An odd item out is given twice: both copies have read before
+  // either writes, and they write the same.)
+  struct Item {
+    const double* a;   // A(i, k) = a[i * 129 + k]
+    const double* b;   // B(k, j) = b[k * 129 + j], or with BT  b[j * 129 + k]
+    double* c;         // C(i, j) = c[i * 129 + j]
+    bool fresh;        // C starts from zero
+  };
+  auto product2 = [&](auto bt, auto neg, const Item& x, const Item& y) {
+    constexpr bool BT = decltype(bt)::value, NEG = decltype(neg)::value;
+    const int oa = l16 * kLeafP + lq, ob = BT ? oa : lq * kLeafP + l16, oc = lq * kLeafP + l16;
+    const double *xa = x.a + oa, *xb = x.b + ob, *ya = y.a + oa, *yb = y.b + ob;
+    double *xc = x.c + oc, *yc = y.c + oc;
+    double ax[4], bx[4], ay[4], by[4];
+    f64x4 cx, cy;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      ax[kk] = xa[4 * kk];
+      bx[kk] = xb[BT ? 4 * kk : 4 * kk * kLeafP];
+      cx[kk] = xc[4 * kk * kLeafP];
+      ay[kk] = ya[4 * kk];
+      by[kk] = yb[BT ? 4 * kk : 4 * kk * kLeafP];
+      cy[kk] = yc[4 * kk * kLeafP];
+    }
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      cx[kk] = x.fresh ? 0.0 : cx[kk];
+      cy[kk] = y.fresh ? 0.0 : cy[kk];
+    }
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      cx = __builtin_amdgcn_mfma_f64_16x16x4f64(NEG ? -ax[kk] : ax[kk], bx[kk], cx, 0, 0, 0);
+      cy = __builtin_amdgcn_mfma_f64_16x16x4f64(NEG ? -ay[kk] : ay[kk], by[kk], cy, 0, 0, 0);
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) xc[4 * r * kLeafP] = cx[r];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) yc[4 * r * kLeafP] = cy[r];
+  };
+  // (one product alone: two accumulators, k steps 0,2 and 1,3, halve the dependent chain)
+  auto product1 = [&](auto bt, auto neg, const Item& x) {
+    constexpr bool BT = decltype(bt)::value, NEG = decltype(neg)::value;
+    const int oa = l16 * kLeafP + lq, ob = BT ? oa : lq * kLeafP + l16, oc = lq * kLeafP + l16;
+    const double *xa = x.a + oa, *xb = x.b + ob;
+    double* xc = x.c + oc;
+    double ax[4], bx[4];
+    f64x4 c0, c1 = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      ax[kk] = xa[4 * kk];
+      bx[kk] = xb[BT ? 4 * kk : 4 * kk * kLeafP];
+      c0[kk] = xc[4 * kk * kLeafP];
+    }
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) c0[kk] = x.fresh ? 0.0 : c0[kk];
+#pragma unroll
+    for (int kk = 0; kk < 4; kk += 2) {
+      c0 = __builtin_amdgcn_mfma_f64_16x16x4f64(NEG ? -ax[kk] : ax[kk], bx[kk], c0, 0, 0, 0);
+      c1 = __builtin_amdgcn_mfma_f64_16x16x4f64(NEG ? -ax[kk + 1] : ax[kk + 1], bx[kk + 1], c1, 0, 0, 0);
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) xc[4 * r * kLeafP] = c0[r] + c1[r];
+  };
+  using std::false_type;
+  using std::true_type;
+  auto uniform = [](int v) { return __builtin_amdgcn_readfirstlane(v); };
+  // G_ij -= L_ik L_jk^T
+  auto update_item = [&](int k, int i, int j) {
+    return Item{S + (16 * i) * kLeafP + 16 * k, S + (16 * j) * kLeafP + 16 * k, S + (16 * i) * kLeafP + 16 * j, false};
+  };
+  // X_kj = -X_kk T_kj, in place in the parked sub-block (j, k)
+  auto finish_item = [&](int k, int j) {
+    double* blk = S + (16 * j) * kLeafP + 16 * k;
+    return Item{XD + 16 * k, blk, blk, true};
+  };
+  // R(k): the trailing update with block column k of everything right of block column k+1 (that
+  // one is on the critical path and has a phase of its own): G_ij -= L_ik L_jk^T, i >= j >= k+2;
+  // dealt to `count` waves, this one is number `slot`
+  auto rest_of_update = [&](int k, int slot, int count) {
+    const int T = nb - 2 - k, items = T * (T + 1) / 2;
+    auto item = [&](int q) {
+      // item q is (ii, jj), ii >= jj, of the triangle in row order: q = ii (ii + 1) / 2 + jj
+      const int ii = uniform((int)((sqrtf((float)(8 * q + 1)) - 1.0f) * 0.5f));
+      return update_item(k, k + 2 + ii, k + 2 + q - ii * (ii + 1) / 2);
+    };
+    for (int q = slot; q < items; q += 2 * count)
+      product2(true_type{}, true_type{}, item(q), item(q + count < items ? q + count : q));
+  };
+  // C(k): T_ij (+)= L_ik X_kj for every i > k, j <= k (the first contribution, j == k, is X_kk's and
+  // starts the sum)
+  auto contributions = [&](int k, int slot, int count) {
+    const int cols = k + 1, items = (nb - 1 - k) * cols;
+    const float rcols = 1.0f / (float)cols;
+    auto item = [&](int q) {
+      const int qi = uniform((int)(((float)q + 0.5f) * rcols));   // q / cols (small integers: exact)
+      const int i = k + 1 + qi, j = q - qi * cols;
+      const bool first = (j == k);
+      return Item{S + (16 * i) * kLeafP + 16 * k, first ? XD + 16 * k : S + (16 * j) * kLeafP + 16 * k,
+                  S + (16 * j) * kLeafP + 16 * i, first};
+    };
+    for (int q = slot; q < items; q += 2 * count)
+      product2(false_type{}, false_type{}, item(q), item(q + count < items ? q + count : q));
+  };
+
+  // X(i, j), i >= j, goes to U[n-1-(o+i)][n-1-(o+j)].  Rows [r0, r1) of X by `threads` threads, this one
+  // being number t: thread = (column, row phase), a column's consecutive threads write consecutive addresses.
+  auto store_rows = [&](int r0, int r1, int t, int threads) {
+    const int j = t & 127, jb = j >> 4, step = threads >> 7;
+    double* ucol = U + (int64_t)(n - 1 - o) * ldu + (n - 1 - (o + j));
+    for (int i = r0 + (t >> 7); i < r1; i += step) {
       if (i < s && j <= i) {
         const int ib = i >> 4;
-        const double x = (ib == jb) ? XD[(ib * 16 + (i & 15)) * kXdP + (j & 15)]
+        const double x = (ib == jb) ? XD[(i & 15) * kLeafP + 16 * ib + (j & 15)]
                                     : S[(16 * jb + (i & 15)) * kLeafP + 16 * ib + (j & 15)];
-        urow[-(int64_t)i * ldu] = x;
+        ucol[-(int64_t)i * ldu] = x;
       }
     }
+  };
+
+  for (int d = 0; d <= nb; ++d) {
+    // ---- A(d)
+    if (d < nb) {
+      // (a workgroup's waves go to the four SIMDs in turn: waves 0 and 1 factor the panel, and the
+      //  waves that share their SIMDs, 4 and 5, stay out of their way)
+      if (wave < kPanelWaves) {
+        panel(d);
+      } else if ((wave & 3) >= kPanelWaves) {
+        const int slot = (wave & 3) - kPanelWaves + (4 - kPanelWaves) * (wave >> 2);   // 0 .. 2 (4 - kPanelWaves) - 1
+        constexpr int helpers = 2 * (4 - kPanelWaves);
+        if (d >= 1) rest_of_update(d - 1, slot, helpers);
+        if (d >= 2) contributions(d - 2, helpers - 1 - slot, helpers);   // (the wave with the fewest items above goes first)
+      } else if (d >= 2) {
+        // the waves that share the panel's SIMDs have little to do meanwhile: block row d-2 of X is
+        // final (its last step was F(d-2) in the phase before) and goes out to memory
+        store_rows(16 * (d - 2), 16 * (d - 1), tid - 256, 128);
+      }
+    } else if (nb >= 2) {
+      contributions(nb - 2, wave, 8);
+    }
+    __syncthreads();
+    // ---- B(d): one product per wave.  Block column d+1 gets its update with block column d (nb-1-d
+    // products), and F(d-1) its d-1: never more than eight together.
+    {
+      const int T = d < nb ? nb - 1 - d : 0, fin = d >= 2 ? d - 1 : 0;
+      if (wave < T)
+        product1(true_type{}, true_type{}, update_item(d, d + 1 + wave, d + 1));
+      else if (wave < T + fin)
+        product1(false_type{}, true_type{}, finish_item(d - 1, wave - T));
+    }
+    __syncthreads();
   }
+
+  // the last two block rows of X (the others went out along the way)
+  store_rows(nb >= 2 ? 16 * (nb - 2) : 0, sp, tid, kLeafThreads);
 }
 
 // ---- the four GEMM steps of one recursion node -------------------------------
@@ -548,12 +634,16 @@ __device__ __forceinline__ void node_gemm_tile(const Op& op, int lin, int gx, in
 
 // (64 x 64 tiles: three workgroups per CU, so the registers are capped for three; the 128 x 128 tile
 // keeps 128 accumulator registers and two sets of staging registers and runs one or two per CU)
-template <int TM, int TN, class Op>
+template <int TM, int TN, bool STRIDED, class Op>
 __global__ __launch_bounds__(256, (TM * TN == 4) ? 3 : 1) void node_gemm_kernel(Op op, int gx, int gy, int total) {
   extern __shared__ double smem[];
-  // one tile per workgroup, or, launched with fewer workgroups than tiles, a stride over the tile list
-  // (both tile loops end with a barrier, so the LDS stages are free when the next tile starts)
-  for (int lin = blockIdx.x; lin < total; lin += gridDim.x) node_gemm_tile<TM, TN>(op, lin, gx, gy, smem);
+  if constexpr (STRIDED) {
+    // fewer workgroups than tiles: a stride over the tile list (both tile loops end with a barrier,
+    // so the LDS stages are free when the next tile starts)
+    for (int lin = blockIdx.x; lin < total; lin += gridDim.x) node_gemm_tile<TM, TN>(op, lin, gx, gy, smem);
+  } else {
+    node_gemm_tile<TM, TN>(op, blockIdx.x, gx, gy, smem);
+  }
 }
 
 // Two independent steps in one launch: workgroups [0, n1) take the tiles of the first.
@@ -573,11 +663,15 @@ template <int TM, int TN, class Op>
 bool launch_tiles(const Op& op, int M, int N, hipStream_t st, int max_wgs = 0) {
   using T = DgemmTile<TM, TN>;
   constexpr int lds = T::kSmemDoubles * (int)sizeof(double);
-  if (!lds_opt_in<node_gemm_kernel<TM, TN, Op>>(lds)) return false;
   const int gx = (int)ceil_div(N, T::BN), gy = (int)ceil_div(M, T::BM);
   const int total = Op::LOWER_ONLY ? lower_tiles<TM, TN>(gx, gy) : gx * gy;
-  const int nwg = (max_wgs > 0 && max_wgs < total) ? max_wgs : total;
-  node_gemm_kernel<TM, TN, Op><<<(unsigned)nwg, 256, lds, st>>>(op, gx, gy, total);
+  if (max_wgs > 0 && max_wgs < total) {
+    if (!lds_opt_in<node_gemm_kernel<TM, TN, true, Op>>(lds)) return false;
+    node_gemm_kernel<TM, TN, true, Op><<<(unsigned)max_wgs, 256, lds, st>>>(op, gx, gy, total);
+  } else {
+    if (!lds_opt_in<node_gemm_kernel<TM, TN, false, Op>>(lds)) return false;
+    node_gemm_kernel<TM, TN, false, Op><<<(unsigned)total, 256, lds, st>>>(op, gx, gy, total);
+  }
   return true;
 }
 
@@ -665,7 +759,7 @@ Side* side_for_device() {
 
 bool recurse(double* G, double* U, int ldu, int n, int o, int s, int32_t* info, hipStream_t st, Side* side, int depth) {
   if (s <= kLeaf) {
-    leaf_kernel<<<1, 256, kLeafLdsBytes, st>>>(G, n, o, s, U, ldu, info);
+    leaf_kernel<<<1, kLeafThreads, kLeafLdsBytes, st>>>(G, n, o, s, U, ldu, info);
     return true;
   }
   const int nb = (int)ceil_div(s, kLeaf);

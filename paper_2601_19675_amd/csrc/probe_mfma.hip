@@ -4,9 +4,13 @@
 // the same few values) and with random operand bits (the data dependence of the power limit).
 // kind 0: bf16 32x32x16 (16 accumulator tiles per wave, the Hessian kernel's shape), kind 1: float64
 // 16x16x4 (8 accumulator tiles per wave).  One wave per SIMD, `blocks` workgroups of 256 threads.
+// The file is compiled twice: as it is (the compiler then keeps MFMA accumulators in AGPRs), exporting
+// ptq_probe_mfma, and with -DPTQ_PROBE_VGPR_FORM and the option that keeps them in ordinary VGPRs,
+// exporting ptq_probe_mfma_vgpr.  For float64 the two forms sustain different rates.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+namespace {
 typedef __attribute__((__vector_size__(4 * sizeof(double)))) double f64x4;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
@@ -91,10 +95,18 @@ __global__ __launch_bounds__(256) void probe_f64(float* out, long long* clk, int
   }
 }
 
+}  // namespace
+
+#ifdef PTQ_PROBE_VGPR_FORM
+#define PTQ_PROBE_ENTRY ptq_probe_mfma_vgpr
+#else
+#define PTQ_PROBE_ENTRY ptq_probe_mfma
+#endif
+
 extern "C" {
 // out: blocks * 256 floats, clk: 2 int64, both device memory of the caller.  Returns the number of
 // floating-point operations the launch executes (0 on a bad argument); enqueues on `stream`.
-double ptq_probe_mfma(int kind, int random_bits, int iters, int blocks, float* out, long long* clk, void* stream) {
+double PTQ_PROBE_ENTRY(int kind, int random_bits, int iters, int blocks, float* out, long long* clk, void* stream) {
   if (!out || !clk || iters <= 0 || blocks <= 0) return 0.0;
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (kind == 0) {
