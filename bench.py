@@ -39,6 +39,7 @@ HBM_GBPS = 8000.0
 # workloads that were not profiled.
 MEASURED_TRAFFIC_BYTES = {
     "C2:attn_proj": (3.655e6 * 2048 + 5.222e5 * 1024, "profiles/hessian_C2_hbm_traffic.txt"),
+    "C3:down_proj": (4.082e7 * 2048 + 1.002e6 * 1024, "profiles/hessian_C3_down_hbm_traffic.txt"),
 }
 
 
@@ -457,6 +458,34 @@ class LayerRun:
                 f"{c.bits}-bit asym group {c.group} block {c.block} damp {self.damp}")
 
 
+def calls_alone(L, reps):
+    """Each of the four calls of a step on its own, `reps` launches back to back (state left by the last
+    step): what the call costs when the chip has not just run another one.  The factor's chain of small
+    launches follows the shader clock, which is still low right after the Hessian kernel, so inside a step
+    it is slower than alone."""
+    import torch
+    ptq, cfg = L.ptq, L.cfg
+    calls = {
+        "hessian": lambda: ptq.ptq_hessian_accumulate(L.H, L.X, L.ws),
+        "factor": lambda: ptq.ptq_damped_cholesky_inv(L.H, L.damp, L.U, L.dead, L.info, L.ws),
+        "quantize": lambda: ptq.ptq_quantize_layer(L.W, L.U, L.dead, cfg.bits, cfg.group, cfg.block, L.codes, L.scales,
+                                                   L.zeros, L.Wq, L.err2, L.ws),
+        "layer_error": lambda: ptq.ptq_layer_error(L.W, L.Wq, L.H, L.out, L.ws),
+    }
+    out = {}
+    for name, fn in calls.items():
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        out[name] = e0.elapsed_time(e1) / reps
+    return out
+
+
 def time_layers(layers, steps, warmup):
     """W untimed passes, then exactly `steps` timed passes over all the layers, one after the other on
     the current stream; returns (ms per pass by the host clock around synchronised ends, per-layer
@@ -551,6 +580,8 @@ def main():
     ap.add_argument("--forward", action="store_true",
                     help="also time the stored layer applied to 1 and 4 tokens (packed codes, rotated input, "
                          "rank-16 low-rank part) and report it under \"forward\"")
+    ap.add_argument("--calls-alone", action="store_true",
+                    help="also time each of the four calls alone, back to back (phases_alone_ms)")
     ap.add_argument("--mfma-control", action="store_true",
                     help="also run the controls behind the Hessian roofline: register-only MFMA loops (bfloat16 and "
                          "float64, benign and random operand bits, shader clock read in the kernel) and the Hessian "
@@ -646,6 +677,8 @@ def main():
     floors = {"hbm_ms": q_bytes / (HBM_GBPS * 1e9) * 1e3, "f64_ms": float(m) * n * n / (PEAK_F64_TFLOPS * 1e12) * 1e3}
     result["quantize_floors"] = dict(floors, frac_of_largest_floor=max(floors.values()) / q_ms,
                                      single_block_us_per_column=t_col_us, walk_ms_upper_estimate=n * t_col_us * 1e-3)
+    if args.calls_alone:
+        result["phases_alone_ms"] = calls_alone(L, max(3, args.steps))
     if args.lopro:
         result["lopro"] = lopro_timings(ptq, L.W, L.H, m, n, ws)
     if args.r1svd:
