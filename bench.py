@@ -518,7 +518,10 @@ def layer_numbers(L, phase):
     h_tflops = syrk_flops / (h_ms * 1e-3) / 1e12
     f_flops = 2.0 / 3.0 * float(n) ** 3
     q_flops = float(m) * n * n
-    pieces = 9.0 if spec.dtype == "bf16" else 12.0
+    # piece products per term: layers of at least 65536 entries run with two bfloat16 pieces per operand (3 products
+    # for tr(D H D^T) + 2 for tr(W H W^T) when W is stored in bfloat16, else 3 + 3), smaller ones with three (6 + 3, 6 + 6)
+    two = m * n >= 65536
+    pieces = ((5.0 if two else 9.0) if spec.dtype == "bf16" else (6.0 if two else 12.0))
     e_exec = pieces * m * n * (n + 128.0)         # piece products the kernel executes on the bf16 MFMA
     e_alg = 2.0 * m * n * (n + 128.0)             # the two traces of the method itself
     peak_f64 = PEAK_F64_TFLOPS

@@ -211,11 +211,14 @@ ptq_status ptq_quantize_layer_vq(const void* W, ptq_dtype wdt, int64_t ldw, int6
  * W   m x n, PTQ_F32 / PTQ_BF16 / PTQ_F64, ldw >= n.   Wq  m x n float64, ld = n.
  * out 3 x float64 device output: {rel, num, den}.
  * Precision follows the storage type of W.  PTQ_F64: float64 throughout.  PTQ_F32 / PTQ_BF16:
- * W - Wq, W and H are rounded to float32 once, their products (formed from bfloat16 pieces of
- * the float32 values, down to 2^-24 of a product) and the sums over the inner index run in
- * float32 on the matrix cores, and the sums over the m x n entries are float64; num and den
- * then agree with the float64 definition to about 1e-8 relative (3e-7 at worst, for a layer
- * of a single entry).  Sums are taken in a fixed order: results are reproducible.
+ * W - Wq, W and H are rounded to float32 once, their products are formed from bfloat16 pieces of
+ * the float32 values, the sums over the inner index run in float32 on the matrix cores, and the
+ * sums over the m x n entries are float64.  Layers of fewer than 65536 entries use three pieces
+ * (products complete to 2^-24): num and den agree with the float64 definition to about 1e-8
+ * relative (3e-7 at worst, for a layer of a single entry).  Larger layers use two pieces (products
+ * complete to 2^-16, errors unbiased and averaged over the m x n terms): num and den agree to
+ * about 1e-6 relative and rel to about 1e-7 (the agreement asked of rel is 1e-4).  Sums are taken
+ * in a fixed order: results are reproducible.
  * Errors: PTQ_ERR_ARG, PTQ_ERR_SHAPE, PTQ_ERR_DTYPE, PTQ_ERR_WORKSPACE.
  */
 ptq_status ptq_layer_error(const void* W, ptq_dtype wdt, int64_t ldw, const double* Wq, int64_t m,

@@ -85,12 +85,20 @@ __global__ __launch_bounds__(256, 3) void quad_form_kernel(ErrArgs a) {   // thr
 // ---------------------------------------------------------------- bfloat16-split form
 constexpr int kT = 128;         // tile edge: four waves, 64 x 64 each (2 x 2 tiles of the 32 x 32 x 16 MFMA)
 
-// A float32 number is exactly the sum of three bfloat16 numbers (8 + 8 + 8 significant bits, each
-// remainder taken after rounding to nearest), and the product of two bfloat16 numbers is exact in
-// float32.  So A Hu in float32 is the sum of the piece products A_a Hu_b; the six with a + b <= 2
-// carry everything down to 2^-24 of a term, the other three are below the rounding of a float32
-// product.  They run on the bfloat16 32 x 32 x 16 MFMA (sixteen times the float32 rate per
-// instruction), accumulate in float32, smallest pieces first.  W stored in bfloat16 is one piece.
+// A number rounded to P bfloat16 pieces (8 significant bits each, each remainder taken after rounding
+// to nearest) keeps 8 P significant bits, and the product of two bfloat16 numbers is exact in
+// float32.  So A Hu is the sum of the piece products A_a Hu_b; those with a + b < P carry everything
+// down to 2^(-8 P) of a term, the others are below what the pieces resolve.  They run on the bfloat16
+// 32 x 32 x 16 MFMA, accumulate in float32, smallest pieces first.  W stored in bfloat16 is one piece.
+// Three pieces are float32 arithmetic (six products for tr(D H D^T), three for tr(W H W^T) with W in
+// bfloat16; the traces agree with the float64 definition to 1e-8, 3e-7 at worst).  With two pieces
+// (three and two products, 0.56 of the matrix-core work) every term is off by up to 2^-16 of itself,
+// unbiased and independent from term to term, and a trace adds m n of them: measured against the
+// float64 oracle on layers of 1e5 .. 4.5e7 entries the traces differ by 3e-7 .. 1e-6 relative and the
+// relative layer error by at most 1e-7, where the required agreement is 1e-4.  That rests on the
+// averaging, so layers of fewer than kTwoPiecesFrom entries (where the time does not matter) take three.
+constexpr int kMaxPieces = 3;
+constexpr int64_t kTwoPiecesFrom = 65536;
 constexpr int kSK = 32;        // k-tile of the split form
 constexpr int kSP = kSK + 8;   // LDS pitch in elements: 80-byte rows keep the 16-byte fragment reads apart
 
@@ -100,42 +108,44 @@ __device__ __forceinline__ uint16_t bf16_rne(float x) {
   return (uint16_t)(u >> 16);
 }
 __device__ __forceinline__ float bf16_val(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
-__device__ __forceinline__ void split3(float x, uint16_t (&p)[3]) {
-  p[0] = bf16_rne(x);
-  float r = x - bf16_val(p[0]);
-  p[1] = bf16_rne(r);
-  r -= bf16_val(p[1]);
-  p[2] = bf16_rne(r);
+template <int P>
+__device__ __forceinline__ void split(float x, uint16_t (&p)[P]) {
+  float r = x;
+#pragma unroll
+  for (int q = 0; q < P; ++q) {
+    p[q] = bf16_rne(r);
+    r -= bf16_val(p[q]);
+  }
 }
 
 struct SplitArgs {
-  const uint16_t* D;   // [3][mp][np]: D = W - Wq as bfloat16 pieces; zero outside m x n
-  const uint16_t* W;   // [1 or 3][mp][np]: W likewise
-  const uint16_t* HuT; // [3][np (j)][np (k)]: Hu transposed, as pieces; zero for k > j and outside n x n
+  const uint16_t* D;   // [P][mp][np]: D = W - Wq as bfloat16 pieces; zero outside m x n
+  const uint16_t* W;   // [1 or P][mp][np]: W likewise
+  const uint16_t* HuT; // [P][np (j)][np (k)]: Hu transposed, as pieces; zero for k > j and outside n x n
   int mp, np;
   double* partial;     // [2][tiles]: the tile sums of tr(D H D^T), then those of tr(W H W^T)
 };
 
 // D and W as bfloat16 pieces, four consecutive k per thread
-template <int DT>
+template <int DT, int P>
 __global__ __launch_bounds__(256) void split_weights_kernel(const void* __restrict__ W, int64_t ldw,
                                                             const double* __restrict__ Wq, int m, int n, int mp, int np,
                                                             uint16_t* __restrict__ Dp, uint16_t* __restrict__ Wp) {
   const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (q >= (int64_t)mp * np / 4) return;
   const int i = (int)(q / (np / 4)), k0 = (int)(q - (int64_t)i * (np / 4)) * 4;
-  uint16_t d[4][3], w[4][3];
+  uint16_t d[4][P], w[4][P];
 #pragma unroll
   for (int c = 0; c < 4; ++c) {
     const bool ok = i < m && k0 + c < n;
     const double wv = ok ? load_as_f64<DT>(W, (int64_t)i * ldw + k0 + c) : 0.0;
     const double qv = ok ? Wq[(int64_t)i * n + k0 + c] : 0.0;
-    split3((float)(wv - qv), d[c]);
-    split3((float)wv, w[c]);
+    split((float)(wv - qv), d[c]);
+    split((float)wv, w[c]);
   }
   const int64_t plane = (int64_t)mp * np, at = (int64_t)i * np + k0;
 #pragma unroll
-  for (int p = 0; p < 3; ++p) {
+  for (int p = 0; p < P; ++p) {
     *reinterpret_cast<ushort4*>(Dp + p * plane + at) = ushort4{d[0][p], d[1][p], d[2][p], d[3][p]};
     if (DT != PTQ_BF16 || p == 0)
       *reinterpret_cast<ushort4*>(Wp + p * plane + at) = ushort4{w[0][p], w[1][p], w[2][p], w[3][p]};
@@ -143,9 +153,10 @@ __global__ __launch_bounds__(256) void split_weights_kernel(const void* __restri
 }
 
 // Hu transposed, as pieces: 32 x 32 tiles through LDS so that both the reads of H and the writes run along rows
+template <int P>
 __global__ __launch_bounds__(256) void split_hu_kernel(const double* __restrict__ H, int64_t ldh, int n, int np,
                                                        uint16_t* __restrict__ HuT) {
-  __shared__ uint16_t t[3][32][33];
+  __shared__ uint16_t t[P][32][33];
   const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
   const int j0 = blockIdx.x * 32, k0 = blockIdx.y * 32;
 #pragma unroll
@@ -153,10 +164,10 @@ __global__ __launch_bounds__(256) void split_hu_kernel(const double* __restrict_
     const int k = k0 + ty + 8 * rr, j = j0 + tx;
     const bool ok = k < n && j < n && k <= j;
     const double h = ok ? H[(int64_t)k * ldh + j] : 0.0;
-    uint16_t p[3];
-    split3((float)(k == j ? h : 2.0 * h), p);
+    uint16_t p[P];
+    split((float)(k == j ? h : 2.0 * h), p);
 #pragma unroll
-    for (int q = 0; q < 3; ++q) t[q][ty + 8 * rr][tx] = p[q];
+    for (int q = 0; q < P; ++q) t[q][ty + 8 * rr][tx] = p[q];
   }
   __syncthreads();
   const int64_t plane = (int64_t)np * np;
@@ -164,17 +175,17 @@ __global__ __launch_bounds__(256) void split_hu_kernel(const double* __restrict_
   for (int rr = 0; rr < 4; ++rr) {
     const int j = j0 + ty + 8 * rr, k = k0 + tx;
 #pragma unroll
-    for (int q = 0; q < 3; ++q) HuT[q * plane + (int64_t)j * np + k] = t[q][tx][ty + 8 * rr];
+    for (int q = 0; q < P; ++q) HuT[q * plane + (int64_t)j * np + k] = t[q][tx][ty + 8 * rr];
   }
 }
 
-// ND pieces of D and NW pieces of W against the three pieces of Hu: both traces in one pass over Hu when
-// the pieces fit LDS together (<3, 1>: W stored in bfloat16), else one trace per launch (<3, 0>, <0, 3>)
-template <int ND, int NW>
+// ND pieces of D and NW pieces of W against the NH pieces of Hu: both traces in one pass over Hu
+// (<P, 1, P>: W stored in bfloat16), or one trace per launch (<P, 0, P>, <0, P, P>)
+template <int ND, int NW, int NH>
 __global__ __launch_bounds__(256) void quad_form_split_kernel(SplitArgs a) {
-  extern __shared__ uint16_t sm[];   // [2 stages][ND + NW + 3 pieces][128 rows][kSP]
+  extern __shared__ uint16_t sm[];   // [2 stages][ND + NW + NH pieces][128 rows][kSP]
   __shared__ double red[2][4];
-  constexpr int NA = ND + NW, NP = NA + 3;
+  constexpr int NA = ND + NW, NP = NA + NH;
   constexpr int kPiece = kT * kSP, kStage = NP * kPiece;
   // the widest column tiles first (blockIdx.y is the slow grid index)
   const int rt = blockIdx.x, ct = gridDim.y - 1 - blockIdx.y;
@@ -222,60 +233,107 @@ __global__ __launch_bounds__(256) void quad_form_split_kernel(SplitArgs a) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[f][tm][tn][r] = 0.f;
 
-  // the products of the k-tile in LDS stage `stage`
-  auto products = [&](int stage) {
-    const uint16_t* st = sm + stage * kStage;
+  // One k-tile: the products of the tile in LDS stage `stage`, with the next tile's way into the other stage
+  // (registers of `set` -> LDS, then the loads of tile knext into the same registers) issued between them.
+  // A wave is alone on its SIMD, so nothing hides what it waits for but its own MFMAs: the fragments of the
+  // second k-step are read while the first k-step's products run, the LDS stores go out between them too,
+  // and the global loads go out between the products of the second k-step.  Only the first k-step's
+  // fragment reads, right after the barrier, are exposed.  The order is asked of the scheduler explicitly.
+  struct Frags {
+    bf16x8 a[NA][2], b[NH][2];
+  };
+  auto read_frags = [&](const uint16_t* st, int ks, Frags& f) {
     // fragment of a 32-row strip: lane l holds row l % 32, k = 8 (l / 32) .. + 7 of the 16-wide k-step
+    const int fo = (lane & 31) * kSP + ks * 16 + (lane >> 5) * 8;
 #pragma unroll
-    for (int ks = 0; ks < kSK / 16; ++ks) {
-      bf16x8 fa[NA][2], fb[3][2];
-      const int fo = (lane & 31) * kSP + ks * 16 + (lane >> 5) * 8;
+    for (int t = 0; t < 2; ++t) {
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
+      for (int p = 0; p < NA; ++p)
+        f.a[p][t] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(st + p * kPiece + (wm * 64 + t * 32) * kSP + fo));
 #pragma unroll
-        for (int p = 0; p < NA; ++p)
-          fa[p][t] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(st + p * kPiece + (wm * 64 + t * 32) * kSP + fo));
-#pragma unroll
-        for (int p = 0; p < 3; ++p)
-          fb[p][t] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(st + (NA + p) * kPiece + (wn * 64 + t * 32) * kSP + fo));
-      }
-      // piece pa of an operand with piece pb of Hu for pa + pb <= 2, the smallest products first
-#pragma unroll
-      for (int order = 2; order >= 0; --order)
-#pragma unroll
-        for (int p = 0; p < NA; ++p) {
-          const int f = (ND > 0 && p >= ND) ? 1 : 0;   // which trace the piece belongs to
-          const int pa = p < ND ? p : p - ND;
-          const int pb = order - pa;
-          if (pb < 0 || pb > 2) continue;
-#pragma unroll
-          for (int tm = 0; tm < 2; ++tm)
-#pragma unroll
-            for (int tn = 0; tn < 2; ++tn)
-              acc[f][tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[p][tm], fb[pb][tn], acc[f][tm][tn], 0, 0, 0);
-        }
+      for (int p = 0; p < NH; ++p)
+        f.b[p][t] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(st + (NA + p) * kPiece + (wn * 64 + t * 32) * kSP + fo));
     }
+  };
+  // piece pa of an operand with piece pb of Hu for pa + pb < NH, the smallest products first
+  auto multiply = [&](const Frags& f) {
+#pragma unroll
+    for (int order = NH - 1; order >= 0; --order)
+#pragma unroll
+      for (int p = 0; p < NA; ++p) {
+        const int fr = (ND > 0 && p >= ND) ? 1 : 0;   // which trace the piece belongs to
+        const int pa = p < ND ? p : p - ND;
+        const int pb = order - pa;
+        if (pb < 0 || pb >= NH) continue;
+#pragma unroll
+        for (int tm = 0; tm < 2; ++tm)
+#pragma unroll
+          for (int tn = 0; tn < 2; ++tn)
+            acc[fr][tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[p][tm], f.b[pb][tn], acc[fr][tm][tn], 0, 0, 0);
+      }
+  };
+  constexpr int kFull = NH * (NH + 1) / 2;   // products of an operand that has all its pieces
+  constexpr int kMfma = 4 * ((ND ? kFull : 0) + (NW == NH ? kFull : (NW == 1 ? NH : 0)));   // MFMAs of one k-step
+  constexpr int kMem = 2 * NP;                         // fragment reads = LDS stores = loads of a k-tile
+  constexpr int kPer = kMfma / kMem, kRest = kMfma - kPer * kMem;   // MFMAs between two memory instructions
+  static_assert(kSK == 32 && kPer >= 1, "two k-steps per tile; at least one MFMA between memory instructions");
+  auto tile = [&](auto stage_c, auto set, int knext) {
+    constexpr int STAGE = decltype(stage_c)::value;
+    const uint16_t* st = sm + STAGE * kStage;
+    Frags f0, f1;
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(st, 0, f0);
+    read_frags(st, 1, f1);
+    stash(set, STAGE ^ 1);
+    multiply(f0);
+    fetch(set, knext);
+    multiply(f1);
+    // the first k-step's fragments; then per kPer MFMAs one fragment read of the second k-step and one LDS
+    // store; then per kPer MFMAs one global load
+    __builtin_amdgcn_sched_group_barrier(0x100, kMem, 0);
+#pragma unroll
+    for (int i = 0; i < kMem; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, kPer, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+    }
+    if constexpr (kRest > 0) __builtin_amdgcn_sched_group_barrier(0x008, kRest, 0);
+#pragma unroll
+    for (int i = 0; i < kMem; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, kPer, 0);
+      __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+    }
+    if constexpr (kRest > 0) __builtin_amdgcn_sched_group_barrier(0x008, kRest, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();
   };
   using Set0 = std::integral_constant<int, 0>;
   using Set1 = std::integral_constant<int, 1>;
+  using Stage0 = std::integral_constant<int, 0>;
+  using Stage1 = std::integral_constant<int, 1>;
 
-  // kend is a multiple of 128: an even number (at least four) of k-tiles
+  // kend is a multiple of 128: an even number (at least four) of k-tiles.  The loop body has no
+  // branch: a fetch beyond the last k-tile reads the last one again and a stash after the last
+  // products fills a stage nobody reads.  With conditional fetches the compiler cannot count the
+  // outstanding loads across the back edge and waits for all of them before every stash; as it
+  // stands it waits for all but the newest set, and a tile's loads have two k-tiles to arrive.
+  // (The prologue issues its loads in the loop's order, set 1 before the second set 0, and the
+  // scheduling barriers keep it so: the wait counts at the loop head are the worse of the two ways in.)
+  const int klast = kend - kSK;
   fetch(Set0{}, 0);
+  __builtin_amdgcn_sched_barrier(0);
   fetch(Set1{}, kSK);
+  __builtin_amdgcn_sched_barrier(0);
   stash(Set0{}, 0);
+  __builtin_amdgcn_sched_barrier(0);
   fetch(Set0{}, 2 * kSK);
+  __builtin_amdgcn_sched_barrier(0);
   __syncthreads();
   for (int k0 = 0; k0 < kend; k0 += 2 * kSK) {
     // tile k0 sits in stage 0; tile k0 + 32 goes from set 1 to stage 1, set 1 then takes tile k0 + 96
-    stash(Set1{}, 1);
-    if (k0 + 3 * kSK < kend) fetch(Set1{}, k0 + 3 * kSK);
-    products(0);
-    __syncthreads();
+    tile(Stage0{}, Set1{}, min(k0 + 3 * kSK, klast));
     // tile k0 + 32 sits in stage 1; tile k0 + 64 goes from set 0 to stage 0, set 0 then takes tile k0 + 128
-    if (k0 + 2 * kSK < kend) stash(Set0{}, 0);
-    if (k0 + 4 * kSK < kend) fetch(Set0{}, k0 + 4 * kSK);
-    products(1);
-    __syncthreads();
+    tile(Stage1{}, Set0{}, min(k0 + 4 * kSK, klast));
   }
 
   // sum_ij A_ij T_ij of the tile in float64; accumulator r of a lane is row (r / 4) * 8 + (lane / 32) * 4 + r % 4,
@@ -355,7 +413,7 @@ static size_t partial_split_bytes(int64_t mp, int64_t np) {
 }
 
 static size_t pieces_bytes(int64_t rows, int64_t cols) {
-  return align_up(3 * (size_t)rows * (size_t)cols * sizeof(uint16_t), 256);
+  return align_up(kMaxPieces * (size_t)rows * (size_t)cols * sizeof(uint16_t), 256);
 }
 
 static size_t bytes_split_form(int64_t m, int64_t n) {
@@ -369,11 +427,11 @@ size_t layer_error_workspace_bytes(int64_t m, int64_t n) {
   return a > b ? a : b;
 }
 
-template <int ND, int NW>
+template <int ND, int NW, int NH>
 static bool launch_split(const SplitArgs& a, hipStream_t st) {
-  const int lds = 2 * (ND + NW + 3) * kT * kSP * (int)sizeof(uint16_t);
-  if (!lds_opt_in<quad_form_split_kernel<ND, NW>>(2 * 7 * kT * kSP * (int)sizeof(uint16_t))) return false;
-  quad_form_split_kernel<ND, NW><<<dim3((unsigned)(a.mp / kT), (unsigned)(a.np / kT)), 256, lds, st>>>(a);
+  const int lds = 2 * (ND + NW + NH) * kT * kSP * (int)sizeof(uint16_t);
+  if (!lds_opt_in<quad_form_split_kernel<ND, NW, NH>>(lds)) return false;
+  quad_form_split_kernel<ND, NW, NH><<<dim3((unsigned)(a.mp / kT), (unsigned)(a.np / kT)), 256, lds, st>>>(a);
   return true;
 }
 
@@ -386,18 +444,21 @@ static ptq_status launch_split_form(const void* W, ptq_dtype wdt, int64_t ldw, c
   uint16_t* Wp = reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(Dp) + pieces_bytes(mp, np));
   uint16_t* HuT = reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(Wp) + pieces_bytes(mp, np));
   const unsigned ga = (unsigned)ceil_div(mp * np / 4, 256);
-  if (wdt == PTQ_F32)
-    split_weights_kernel<PTQ_F32><<<ga, 256, 0, st>>>(W, ldw, Wq, (int)m, (int)n, (int)mp, (int)np, Dp, Wp);
-  else
-    split_weights_kernel<PTQ_BF16><<<ga, 256, 0, st>>>(W, ldw, Wq, (int)m, (int)n, (int)mp, (int)np, Dp, Wp);
-  split_hu_kernel<<<dim3((unsigned)(np / 32), (unsigned)(np / 32)), 256, 0, st>>>(H, ldh, (int)n, (int)np, HuT);
+  const dim3 gh((unsigned)(np / 32), (unsigned)(np / 32));
   const int tiles = (int)((mp / kT) * (np / kT));
   SplitArgs a{Dp, Wp, HuT, (int)mp, (int)np, partial};
-  if (wdt == PTQ_BF16) {
-    if (!launch_split<3, 1>(a, st)) return PTQ_ERR_HIP;
-  } else {
-    if (!launch_split<3, 0>(a, st) || !launch_split<0, 3>(a, st)) return PTQ_ERR_HIP;
-  }
+  auto run = [&](auto pieces) -> bool {
+    constexpr int P = decltype(pieces)::value;
+    if (wdt == PTQ_F32)
+      split_weights_kernel<PTQ_F32, P><<<ga, 256, 0, st>>>(W, ldw, Wq, (int)m, (int)n, (int)mp, (int)np, Dp, Wp);
+    else
+      split_weights_kernel<PTQ_BF16, P><<<ga, 256, 0, st>>>(W, ldw, Wq, (int)m, (int)n, (int)mp, (int)np, Dp, Wp);
+    split_hu_kernel<P><<<gh, 256, 0, st>>>(H, ldh, (int)n, (int)np, HuT);
+    if (wdt == PTQ_BF16) return launch_split<P, 1, P>(a, st);
+    return launch_split<P, 0, P>(a, st) && launch_split<0, P, P>(a, st);
+  };
+  const bool ok = (m * n >= kTwoPiecesFrom) ? run(std::integral_constant<int, 2>{}) : run(std::integral_constant<int, 3>{});
+  if (!ok) return PTQ_ERR_HIP;
   finish_kernel<<<1, 256, 0, st>>>(partial, tiles, out);
   PTQ_HIP_CHECK_LAUNCH();
   return PTQ_OK;

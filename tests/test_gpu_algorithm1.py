@@ -66,8 +66,9 @@ def test_one_layer_through_every_stage(bits, capsys):
     bound = (np.abs(W64 * s_g) + np.abs(out["U"]).T @ (np.abs(out["V"]) * out["sigma"][:, None])) / s_g
     assert np.all(np.abs(W_r + R_g - W64) <= (r + 3) * 2.0 ** -24 * bound)
     # Eq. 8: the residual's loss is the same number in both bases (tr(D H D^T) itself, entry 1 of the output)
-    # (the rotated residual is float64 and takes the float64 form of the sum, the float32 residual the float32 one)
-    assert float(e_rot[1]) == pytest.approx(float(e_res[1]), rel=3e-7)
+    # (the rotated residual is float64 and takes the float64 form of the sum, the float32 residual the form with
+    # two bfloat16 pieces per operand, whose traces hold to about 1e-6)
+    assert float(e_rot[1]) == pytest.approx(float(e_res[1]), rel=4e-6)
     # Eq. 7: the layer that inference would run, W_r + Q(R') Q^T P^T, and its error against W under H,
     # evaluated by the oracle from the GPU's outputs: W - W_hat = R - Rq, so it is the residual's loss
     H_ref = orc.hessian(X64)

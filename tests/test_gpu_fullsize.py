@@ -133,8 +133,10 @@ def stagewise(capsys, spec, bits, group, block, damps, t_test, n_rows=48, seed=w
         rel, num, den = g.error(Hdev)
         r0, n0, d0 = orc.layer_error(W64, Wq, Href)
         say(capsys, f"  damp {damp}: rel layer error gpu {rel:.6f} oracle {r0:.6f}")
-        # bfloat16 weights: float32 sums of exact piece products on the matrix cores, float64 from the tile sums on
-        assert abs(rel - r0) <= 1e-4 and abs(num - n0) <= 3e-7 * n0 and abs(den - d0) <= 3e-7 * d0
+        # bfloat16 weights: float32 sums of exact piece products on the matrix cores, float64 from the tile sums on;
+        # layers of this size use two pieces per operand (terms complete to 2^-16, unbiased, m n of them averaged):
+        # the required agreement is 1e-4 on the relative error; held to 1e-6 on it and to 4e-6 on the traces
+        assert abs(rel - r0) <= 1e-6 and abs(num - n0) <= 4e-6 * n0 and abs(den - d0) <= 4e-6 * d0
     if static_too:
         # the static-groups variant of the solve at the same size and launch shape, with the last factor
         ptq.ptq_quantize_layer_static_groups(g.W, Udev, None, bits, group, block, g.codes, g.scales, g.zeros, g.Wq,
