@@ -304,12 +304,18 @@ __global__ __launch_bounds__(kLeafThreads) void leaf_kernel(const double* __rest
 #pragma unroll
       for (int m = 0; m < kIdentityRows; ++m) XD[c * kLeafP + b0 + kPanelWaves * m + wave] = R.E[m] * rl;
     }
-    if (wave == 0) {
-      if (lq == 0) {
-        // (rows above the diagonal get what the registers hold: nothing reads that triangle)
+    // the diagonal sub-block, which both waves hold: each writes half of its rows
+    // (rows above the diagonal get what the registers hold: nothing reads that triangle)
+    if (lq == 0) {
+      if (wave == 0) {
 #pragma unroll
-        for (int k = 0; k < 16; ++k) S[(b0 + k) * kLeafP + b0 + c] = R.Dg[k] * rl;
+        for (int k = 0; k < 8; ++k) S[(b0 + k) * kLeafP + b0 + c] = R.Dg[k] * rl;
+      } else {
+#pragma unroll
+        for (int k = 8; k < 16; ++k) S[(b0 + k) * kLeafP + b0 + c] = R.Dg[k] * rl;
       }
+    }
+    if (wave == 0) {
       // the first pivot that was not positive: its reciprocal root is the first that is not a positive number
       const unsigned long long notpos = __ballot(!(rl > 0.0 && rl < __builtin_huge_val())) & 0xffffull;
       if (notpos != 0) {
