@@ -7,7 +7,7 @@ bfloat16 piece.  Every rung below float64 moves the pre-rounding values by 1e-8 
 for bfloat16), which flips the float32 rounding of group scales and near-tie codes in a sizeable share of
 the rows -- flagged by the protocol at best, failures at worst -- where float64 flips none.  This test
 runs the first configuration (512 x 512, all rows); the same script on 256 sampled rows of the 4096 x 4096
-layers gave the table in the design notes."""
+layers and 128 rows of the 4096 x 11008 one gave the table in profiles/lazy_update_precision_ladder.txt."""
 import numpy as np
 import pytest
 
@@ -123,7 +123,7 @@ def test_only_float64_updates_reproduce_the_oracle_on_configuration_one():
     assert by["bf16"]["unflagged"] == spec.m      # one bfloat16 piece: every row fails outright
 
 
-if __name__ == "__main__":      # the table of the design notes: python tests/test_update_precision_ladder.py C2|C4|C3d
+if __name__ == "__main__":      # the full-size table: python tests/test_update_precision_ladder.py C2|C4|C3d
     import sys
     which = sys.argv[1]
     cfgname, layer, t_test, nrows = {"C2": ("C2", 0, 8192, 256), "C4": ("C4", 0, 8192, 256), "C3d": ("C3", 1, 12288, 128)}[which]
