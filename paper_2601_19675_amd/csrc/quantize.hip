@@ -90,6 +90,11 @@ __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
     f64x4 acc[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[t] = f64x4{0.0, 0.0, 0.0, 0.0};
+    // (pairs of tiles share 16-byte loads when the block is a whole number of pairs, an even ldu keeps
+    // them aligned, and the offsets fit the buffer form; see below)
+    const bool paired = (nt % 2 == 0) && (a.ldu % 2 == 0) &&
+                        (int64_t)a.n * a.ldu * 8 < ((int64_t)1 << 31) && (int64_t)a.n * a.mpad * 8 < ((int64_t)1 << 31);
+    auto column_of = [&](int t, int cl) { return paired ? 32 * (t >> 1) + 2 * cl + (t & 1) : 16 * t + cl; };
     {
       constexpr int kDepth = (NT >= 16) ? 2 : 4;
       const int kl = lane >> 4, cl = lane & 15;
@@ -142,16 +147,37 @@ __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
         const __amdgpu_buffer_rsrc_t ru = __builtin_amdgcn_make_buffer_rsrc(const_cast<double*>(U + a.i1), 0,
                                                                             (int)0xFFFFFFFFu, 0x00020000);
         const int ve = ((4 * wv + kl) * a.mpad + cl) * 8;
-        int vu[NT];
-#pragma unroll
-        for (int t = 0; t < NT; ++t) vu[t] = ((4 * wv + kl) * (int)a.ldu + cl + coff[t]) * 8;
         const int se = 4 * kWaves * a.mpad * 8, su = 4 * kWaves * (int)a.ldu * 8;
-        run([&](int slot, int it) {
-          av[slot] = __builtin_bit_cast(double, __builtin_amdgcn_raw_buffer_load_b64(re, ve, it * se, 0));
+        if (paired) {
+          // The address unit takes a wave's load in 16 steps of four lanes whatever the width, so 8-byte
+          // loads top out at 32 bytes per clock and compute unit -- less than the eight MFMAs of a k-step
+          // need.  A lane therefore fetches two neighbouring columns at once (16 bytes) and gives one to each
+          // of a pair of tiles: tile 2p + q works on columns 32 p + 2 cl + q.  The MFMA does not care which
+          // columns make up a tile; the partial sums go back to their columns through the same map.
+          int vu[NT / 2];
 #pragma unroll
-          for (int t = 0; t < NT; ++t)
-            bv[slot][t] = __builtin_bit_cast(double, __builtin_amdgcn_raw_buffer_load_b64(ru, vu[t], it * su, 0));
-        });
+          for (int p = 0; p < NT / 2; ++p) vu[p] = ((4 * wv + kl) * (int)a.ldu + 2 * cl + (coff[2 * p] & ~31)) * 8;
+          typedef double f64x2 __attribute__((ext_vector_type(2)));
+          run([&](int slot, int it) {
+            av[slot] = __builtin_bit_cast(double, __builtin_amdgcn_raw_buffer_load_b64(re, ve, it * se, 0));
+#pragma unroll
+            for (int p = 0; p < NT / 2; ++p) {
+              const f64x2 two = __builtin_bit_cast(f64x2, __builtin_amdgcn_raw_buffer_load_b128(ru, vu[p], it * su, 0));
+              bv[slot][2 * p] = two[0];
+              bv[slot][2 * p + 1] = two[1];
+            }
+          });
+        } else {
+          int vu[NT];
+#pragma unroll
+          for (int t = 0; t < NT; ++t) vu[t] = ((4 * wv + kl) * (int)a.ldu + cl + coff[t]) * 8;
+          run([&](int slot, int it) {
+            av[slot] = __builtin_bit_cast(double, __builtin_amdgcn_raw_buffer_load_b64(re, ve, it * se, 0));
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+              bv[slot][t] = __builtin_bit_cast(double, __builtin_amdgcn_raw_buffer_load_b64(ru, vu[t], it * su, 0));
+          });
+        }
       } else {
         const double* ep = a.errT + (int64_t)(4 * wv + kl) * a.mpad + row0 + cl;
         const double* up = U + (int64_t)(4 * wv + kl) * a.ldu + a.i1 + cl;
@@ -170,7 +196,7 @@ __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
         if (t < nt) {
 #pragma unroll
           for (int r = 0; r < 4; ++r)
-            P[((wave - 4) * kRows + 4 * r + (lane >> 4)) * a.bw + 16 * t + (lane & 15)] = acc[t][r];
+            P[((wave - 4) * kRows + 4 * r + (lane >> 4)) * a.bw + column_of(t, lane & 15)] = acc[t][r];
         }
     }
     __syncthreads();
@@ -180,39 +206,70 @@ __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
         if (t < nt) {
 #pragma unroll
           for (int r = 0; r < 4; ++r)
-            P[(wave * kRows + 4 * r + (lane >> 4)) * a.bw + 16 * t + (lane & 15)] += acc[t][r];
+            P[(wave * kRows + 4 * r + (lane >> 4)) * a.bw + column_of(t, lane & 15)] += acc[t][r];
         }
     }
     __syncthreads();
 
   } else {
-    // ---- phase 1, several row tiles: a wave owns column tiles (wave, wave + 8, ...) and runs over all k
-    //      itself -- no partial sums to fold; the operand of U is fetched once for all MT row tiles, the
-    //      rows of E (the same for every wave) come out of the cache after the first wave's fetch
-    constexpr int TPW = (NT + kWaves - 1) / kWaves;
-    constexpr int kDepth = 4;
-    f64x4 acc[MT][TPW];
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-      for (int q = 0; q < TPW; ++q) acc[mt][q] = f64x4{0.0, 0.0, 0.0, 0.0};
     const int wv = __builtin_amdgcn_readfirstlane(wave);   // uniform: scalar loop control
-    if (wv < nt) {
-      const int kl = lane >> 4, cl = lane & 15;
-      int coff[TPW];  // tiles beyond the block re-read a valid tile (result unused)
+    const bool paired = (nt % 2 == 0) && (a.ldu % 2 == 0) && (a.mpad % 2 == 0) &&
+                        (int64_t)a.n * a.ldu * 8 < ((int64_t)1 << 31) && (int64_t)a.n * a.mpad * 8 < ((int64_t)1 << 31);
+    if (paired) {
+      // ---- phase 1, several row tiles, 16-byte loads (see the one-tile form for why): the waves are two
+      //      groups that take alternate k-steps; inside a group a wave owns pairs of column tiles (a lane
+      //      fetches two neighbouring columns of U at once, tile 2p + q works on columns 32 p + 2 cl + q) for
+      //      all row tiles, and the first two row tiles are a pair as well (a lane fetches the errors of rows
+      //      2 cl and 2 cl + 1 at once: row tile 0 works on the even rows of the first 32, tile 1 on the odd
+      //      ones).  Three load instructions feed six MFMAs.  The two groups' sums meet in the state tile.
+      constexpr int PPW = (NT / 2 + 3) / 4;   // pairs of column tiles per wave
+      constexpr int kDepth = 4;
+      typedef double f64x2 __attribute__((ext_vector_type(2)));
+      const int grp = wv >> 2, w4 = wv & 3;
+      f64x4 acc[MT][2 * PPW];
 #pragma unroll
-      for (int q = 0; q < TPW; ++q) coff[q] = 16 * ((wv + kWaves * q) < nt ? wv + kWaves * q : wv);
-      const int niter = a.i1 >> 2;   // i1 is a multiple of 16
-      double av[kDepth][MT], bv[kDepth][TPW];
-      auto mfmas = [&](int d) {
+      for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-        for (int q = 0; q < TPW; ++q)
+        for (int q = 0; q < 2 * PPW; ++q) acc[mt][q] = f64x4{0.0, 0.0, 0.0, 0.0};
+      const bool active = 2 * w4 < nt;
+      if (active) {
+        const int kl = lane >> 4, cl = lane & 15;
+        const int steps = a.i1 >> 2;                    // i1 is a multiple of 16
+        const int niter = (steps - grp + 1) >> 1;       // this group's k-steps: grp, grp + 2, ...
+        double av[kDepth][MT], bv[kDepth][2 * PPW];
+        auto mfmas = [&](int d) {
 #pragma unroll
-          for (int mt = 0; mt < MT; ++mt)
-            acc[mt][q] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[d][mt], bv[d][q], acc[mt][q], 0, 0, 0);
-      };
-      auto run = [&](auto issue) {   // branch-free steady state, as in the one-tile form
-        int it = 0;
+          for (int q = 0; q < 2 * PPW; ++q)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+              acc[mt][q] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[d][mt], bv[d][q], acc[mt][q], 0, 0, 0);
+        };
+        const __amdgpu_buffer_rsrc_t re = __builtin_amdgcn_make_buffer_rsrc(const_cast<double*>(a.errT + row0), 0,
+                                                                            (int)0xFFFFFFFFu, 0x00020000);
+        const __amdgpu_buffer_rsrc_t ru = __builtin_amdgcn_make_buffer_rsrc(const_cast<double*>(U + a.i1), 0,
+                                                                            (int)0xFFFFFFFFu, 0x00020000);
+        const int ve01 = ((4 * grp + kl) * a.mpad + 2 * cl) * 8;          // rows 2 cl, 2 cl + 1
+        const int ve2 = ((4 * grp + kl) * a.mpad + 32 + cl) * 8;          // row 32 + cl (three row tiles)
+        int vu[PPW];
+#pragma unroll
+        for (int q = 0; q < PPW; ++q) {
+          const int pr = (2 * (w4 + 4 * q) < nt) ? w4 + 4 * q : w4;       // a pair beyond the block re-reads a valid one
+          vu[q] = ((4 * grp + kl) * (int)a.ldu + 32 * pr + 2 * cl) * 8;
+        }
+        const int se = 8 * a.mpad * 8, su = 8 * (int)a.ldu * 8;
+        auto issue = [&](int slot, int it) {
+          const f64x2 e01 = __builtin_bit_cast(f64x2, __builtin_amdgcn_raw_buffer_load_b128(re, ve01, it * se, 0));
+          av[slot][0] = e01[0];
+          av[slot][1] = e01[1];
+          if constexpr (MT == 3) av[slot][2] = __builtin_bit_cast(double, __builtin_amdgcn_raw_buffer_load_b64(re, ve2, it * se, 0));
+#pragma unroll
+          for (int q = 0; q < PPW; ++q) {
+            const f64x2 two = __builtin_bit_cast(f64x2, __builtin_amdgcn_raw_buffer_load_b128(ru, vu[q], it * su, 0));
+            bv[slot][2 * q] = two[0];
+            bv[slot][2 * q + 1] = two[1];
+          }
+        };
+        int it = 0;   // branch-free steady state, as in the one-tile form
         if (niter >= 2 * kDepth) {
 #pragma unroll
           for (int d = 0; d < kDepth; ++d) issue(d, d);
@@ -237,52 +294,130 @@ __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
             }
           }
         }
+      }
+      // row of accumulator element r of row tile mt, column of tile 2 pr + q2
+      auto put = [&](bool add) {
+        if (!active) return;
+#pragma unroll
+        for (int q = 0; q < 2 * PPW; ++q) {
+          const int pr = w4 + 4 * (q >> 1);
+          if (2 * pr < nt) {
+            const int col = 32 * pr + 2 * (lane & 15) + (q & 1);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+              for (int r = 0; r < 4; ++r) {
+                const int i = 4 * r + (lane >> 4);
+                const int row = mt < 2 ? 2 * i + mt : 32 + i;
+                double* at = P + row * a.bw + col;
+                *at = add ? *at + acc[mt][q][r] : acc[mt][q][r];
+              }
+          }
+        }
       };
-      const bool offsets32 = (int64_t)a.n * a.ldu * 8 < ((int64_t)1 << 31) && (int64_t)a.n * a.mpad * 8 < ((int64_t)1 << 31);
-      if (offsets32) {
-        const __amdgpu_buffer_rsrc_t re = __builtin_amdgcn_make_buffer_rsrc(const_cast<double*>(a.errT + row0), 0,
-                                                                            (int)0xFFFFFFFFu, 0x00020000);
-        const __amdgpu_buffer_rsrc_t ru = __builtin_amdgcn_make_buffer_rsrc(const_cast<double*>(U + a.i1), 0,
-                                                                            (int)0xFFFFFFFFu, 0x00020000);
-        int ve[MT], vu[TPW];
+      if (grp == 1) put(false);
+      __syncthreads();
+      if (grp == 0) put(true);
+      __syncthreads();
+    } else {
+      // ---- phase 1, several row tiles: a wave owns column tiles (wave, wave + 8, ...) and runs over all k
+      //      itself -- no partial sums to fold; the operand of U is fetched once for all MT row tiles, the
+      //      rows of E (the same for every wave) come out of the cache after the first wave's fetch
+      constexpr int TPW = (NT + kWaves - 1) / kWaves;
+      constexpr int kDepth = 4;
+      f64x4 acc[MT][TPW];
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) ve[mt] = (kl * a.mpad + cl + kRowTile * mt) * 8;
+      for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-        for (int q = 0; q < TPW; ++q) vu[q] = (kl * (int)a.ldu + cl + coff[q]) * 8;
-        const int se = 4 * a.mpad * 8, su = 4 * (int)a.ldu * 8;
-        run([&](int slot, int it) {
+        for (int q = 0; q < TPW; ++q) acc[mt][q] = f64x4{0.0, 0.0, 0.0, 0.0};
+      if (wv < nt) {
+        const int kl = lane >> 4, cl = lane & 15;
+        int coff[TPW];  // tiles beyond the block re-read a valid tile (result unused)
 #pragma unroll
-          for (int mt = 0; mt < MT; ++mt)
-            av[slot][mt] = __builtin_bit_cast(double, __builtin_amdgcn_raw_buffer_load_b64(re, ve[mt], it * se, 0));
+        for (int q = 0; q < TPW; ++q) coff[q] = 16 * ((wv + kWaves * q) < nt ? wv + kWaves * q : wv);
+        const int niter = a.i1 >> 2;   // i1 is a multiple of 16
+        double av[kDepth][MT], bv[kDepth][TPW];
+        auto mfmas = [&](int d) {
 #pragma unroll
           for (int q = 0; q < TPW; ++q)
-            bv[slot][q] = __builtin_bit_cast(double, __builtin_amdgcn_raw_buffer_load_b64(ru, vu[q], it * su, 0));
-        });
-      } else {
-        const double* ep = a.errT + (int64_t)kl * a.mpad + row0 + cl;
-        const double* up = U + (int64_t)kl * a.ldu + a.i1 + cl;
-        run([&](int slot, int it) {
-          const double* e = ep + (int64_t)it * 4 * a.mpad;
-          const double* u = up + (int64_t)it * 4 * a.ldu;
 #pragma unroll
-          for (int mt = 0; mt < MT; ++mt) av[slot][mt] = e[kRowTile * mt];
+            for (int mt = 0; mt < MT; ++mt)
+              acc[mt][q] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[d][mt], bv[d][q], acc[mt][q], 0, 0, 0);
+        };
+        auto run = [&](auto issue) {   // branch-free steady state, as in the one-tile form
+          int it = 0;
+          if (niter >= 2 * kDepth) {
 #pragma unroll
-          for (int q = 0; q < TPW; ++q) bv[slot][q] = u[coff[q]];
-        });
-      }
+            for (int d = 0; d < kDepth; ++d) issue(d, d);
+            for (; it + 2 * kDepth <= niter; it += kDepth) {
 #pragma unroll
-      for (int q = 0; q < TPW; ++q) {
-        const int t = wave + kWaves * q;
-        if (t < nt) {
+              for (int d = 0; d < kDepth; ++d) {
+                mfmas(d);
+                issue(d, it + d + kDepth);
+              }
+            }
+          } else {
 #pragma unroll
-          for (int mt = 0; mt < MT; ++mt)
+            for (int d = 0; d < kDepth; ++d)
+              if (d < niter) issue(d, d);
+          }
+          for (; it < niter; it += kDepth) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-              P[(kRowTile * mt + 4 * r + (lane >> 4)) * a.bw + 16 * t + (lane & 15)] = acc[mt][q][r];
+            for (int d = 0; d < kDepth; ++d) {
+              if (it + d < niter) {
+                mfmas(d);
+                if (it + d + kDepth < niter) issue(d, it + d + kDepth);
+              }
+            }
+          }
+        };
+        const bool offsets32 = (int64_t)a.n * a.ldu * 8 < ((int64_t)1 << 31) && (int64_t)a.n * a.mpad * 8 < ((int64_t)1 << 31);
+        if (offsets32) {
+          const __amdgpu_buffer_rsrc_t re = __builtin_amdgcn_make_buffer_rsrc(const_cast<double*>(a.errT + row0), 0,
+                                                                              (int)0xFFFFFFFFu, 0x00020000);
+          const __amdgpu_buffer_rsrc_t ru = __builtin_amdgcn_make_buffer_rsrc(const_cast<double*>(U + a.i1), 0,
+                                                                              (int)0xFFFFFFFFu, 0x00020000);
+          int ve[MT], vu[TPW];
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) ve[mt] = (kl * a.mpad + cl + kRowTile * mt) * 8;
+#pragma unroll
+          for (int q = 0; q < TPW; ++q) vu[q] = (kl * (int)a.ldu + cl + coff[q]) * 8;
+          const int se = 4 * a.mpad * 8, su = 4 * (int)a.ldu * 8;
+          run([&](int slot, int it) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+              av[slot][mt] = __builtin_bit_cast(double, __builtin_amdgcn_raw_buffer_load_b64(re, ve[mt], it * se, 0));
+#pragma unroll
+            for (int q = 0; q < TPW; ++q)
+              bv[slot][q] = __builtin_bit_cast(double, __builtin_amdgcn_raw_buffer_load_b64(ru, vu[q], it * su, 0));
+          });
+        } else {
+          const double* ep = a.errT + (int64_t)kl * a.mpad + row0 + cl;
+          const double* up = U + (int64_t)kl * a.ldu + a.i1 + cl;
+          run([&](int slot, int it) {
+            const double* e = ep + (int64_t)it * 4 * a.mpad;
+            const double* u = up + (int64_t)it * 4 * a.ldu;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) av[slot][mt] = e[kRowTile * mt];
+#pragma unroll
+            for (int q = 0; q < TPW; ++q) bv[slot][q] = u[coff[q]];
+          });
+        }
+#pragma unroll
+        for (int q = 0; q < TPW; ++q) {
+          const int t = wave + kWaves * q;
+          if (t < nt) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+              for (int r = 0; r < 4; ++r)
+                P[(kRowTile * mt + 4 * r + (lane >> 4)) * a.bw + 16 * t + (lane & 15)] = acc[mt][q][r];
+          }
         }
       }
+      __syncthreads();
+
     }
-    __syncthreads();
   }
 
   // ---- state tile S = W - (sum of the partial sums), dead channels read as zero

@@ -85,6 +85,9 @@ __global__ __launch_bounds__(kThreads) void vq_block_kernel(VqArgs a) {
   f64x4 acc[NT];
 #pragma unroll
   for (int t = 0; t < NT; ++t) acc[t] = f64x4{0.0, 0.0, 0.0, 0.0};
+  // 16-byte loads need 16-byte alignment here (plain loads): an even ldu and U itself aligned
+  const bool paired = (nt % 2 == 0) && (a.ldu % 2 == 0) && ((reinterpret_cast<uintptr_t>(U) & 15) == 0);
+  auto column_of = [&](int t, int cl) { return paired ? 32 * (t >> 1) + 2 * cl + (t & 1) : 16 * t + cl; };
   {
     constexpr int kDepth = (NT >= 16) ? 2 : 4;
     const int kl = lane >> 4, cl = lane & 15;
@@ -100,11 +103,25 @@ __global__ __launch_bounds__(kThreads) void vq_block_kernel(VqArgs a) {
     };
     const double* ep = a.errT + (int64_t)(4 * wv + kl) * a.mpad + row0 + cl;
     const double* up = U + (int64_t)(4 * wv + kl) * a.ldu + a.i1 + cl;
+    // (with a whole number of tile pairs a lane fetches two neighbouring columns of U at once, one for each
+    //  tile of a pair -- tile 2p + q then works on columns 32 p + 2 cl + q; see the scalar solve for why)
+    typedef double f64x2 __attribute__((ext_vector_type(2)));
+    const double* up2 = U + (int64_t)(4 * wv + kl) * a.ldu + a.i1 + 2 * cl;
     auto issue = [&](int slot, int it) {
       av[slot] = ep[(int64_t)it * (4 * kWaves) * a.mpad];
-      const double* u = up + (int64_t)it * (4 * kWaves) * a.ldu;
+      if (paired) {
+        const double* u = up2 + (int64_t)it * (4 * kWaves) * a.ldu;
 #pragma unroll
-      for (int t = 0; t < NT; ++t) bv[slot][t] = u[coff[t]];
+        for (int p = 0; p < NT / 2; ++p) {
+          const f64x2 two = *reinterpret_cast<const f64x2*>(u + (coff[2 * p] & ~31));
+          bv[slot][2 * p] = two[0];
+          bv[slot][2 * p + 1] = two[1];
+        }
+      } else {
+        const double* u = up + (int64_t)it * (4 * kWaves) * a.ldu;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) bv[slot][t] = u[coff[t]];
+      }
     };
 #pragma unroll
     for (int d = 0; d < kDepth; ++d)
@@ -125,7 +142,7 @@ __global__ __launch_bounds__(kThreads) void vq_block_kernel(VqArgs a) {
       if (t < nt) {
 #pragma unroll
         for (int r = 0; r < 4; ++r)
-          P[((wave - 4) * kRows + 4 * r + (lane >> 4)) * a.bw + 16 * t + (lane & 15)] = acc[t][r];
+          P[((wave - 4) * kRows + 4 * r + (lane >> 4)) * a.bw + column_of(t, lane & 15)] = acc[t][r];
       }
   }
   __syncthreads();
@@ -135,7 +152,7 @@ __global__ __launch_bounds__(kThreads) void vq_block_kernel(VqArgs a) {
       if (t < nt) {
 #pragma unroll
         for (int r = 0; r < 4; ++r)
-          P[(wave * kRows + 4 * r + (lane >> 4)) * a.bw + 16 * t + (lane & 15)] += acc[t][r];
+          P[(wave * kRows + 4 * r + (lane >> 4)) * a.bw + column_of(t, lane & 15)] += acc[t][r];
       }
   }
   __syncthreads();
