@@ -84,27 +84,32 @@ __device__ __forceinline__ void dgemm_mainloop(f64x4 (&acc)[TM][TN], DView A, FA
   }
   const int stepa = kGemmBK * A.sk, stepb = kGemmBK * B.sk;
 
-  double ra[T::EA], rb[T::EB];
-  // loads of the k-tile starting at k0 (its offsets are the current ones); only
-  // the last tile can stick out of [kbeg, kend): there the k index is clamped
-  auto fetch = [&](int k0) {
+  // Register sets for the k-tiles in flight.  The smallest tile has two loads per operand and thread and
+  // a k-tile of four MFMAs per wave: with one k-tile in flight every iteration waits out a whole memory
+  // latency (measured: 0.6 - 1.3 us per iteration where the MFMAs need 0.1), so it keeps four in flight.
+  constexpr int D = (TM * TN == 1) ? 4 : 1;
+  double ra[D][T::EA], rb[D][T::EB];
+  // loads of the next k-tile in line (tiles are fetched in rising order; its offsets are the current
+  // ones) into register set SET; only the last tile can stick out of [kbeg, kend): there the k index is clamped
+  auto fetch = [&](auto set, int k0) {
+    constexpr int SET = decltype(set)::value;
     if (k0 + kGemmBK <= kend) {
 #pragma unroll
-      for (int p = 0; p < T::EA; ++p) ra[p] = A.p[offa[p]];
+      for (int p = 0; p < T::EA; ++p) ra[SET][p] = A.p[offa[p]];
 #pragma unroll
-      for (int p = 0; p < T::EB; ++p) rb[p] = B.p[offb[p]];
+      for (int p = 0; p < T::EB; ++p) rb[SET][p] = B.p[offb[p]];
     } else {
 #pragma unroll
       for (int p = 0; p < T::EA; ++p) {
         const int k = A_KFAST ? (tid + 256 * p) % kGemmBK : (tid + 256 * p) / T::BM;
         const int over = k0 + k - (kend - 1);
-        ra[p] = A.p[offa[p] - (over > 0 ? over : 0) * A.sk];
+        ra[SET][p] = A.p[offa[p] - (over > 0 ? over : 0) * A.sk];
       }
 #pragma unroll
       for (int p = 0; p < T::EB; ++p) {
         const int k = B_KFAST ? (tid + 256 * p) % kGemmBK : (tid + 256 * p) / T::BN;
         const int over = k0 + k - (kend - 1);
-        rb[p] = B.p[offb[p] - (over > 0 ? over : 0) * B.sk];
+        rb[SET][p] = B.p[offb[p] - (over > 0 ? over : 0) * B.sk];
       }
     }
 #pragma unroll
@@ -112,7 +117,20 @@ __device__ __forceinline__ void dgemm_mainloop(f64x4 (&acc)[TM][TN], DView A, FA
 #pragma unroll
     for (int p = 0; p < T::EB; ++p) offb[p] += stepb;
   };
-  auto stash = [&](int k0, double* st) {
+  // the same for a tile known to lie inside [kbeg, kend): no branch
+  auto fetch_inner = [&](auto set) {
+    constexpr int SET = decltype(set)::value;
+#pragma unroll
+    for (int p = 0; p < T::EA; ++p) ra[SET][p] = A.p[offa[p]];
+#pragma unroll
+    for (int p = 0; p < T::EB; ++p) rb[SET][p] = B.p[offb[p]];
+#pragma unroll
+    for (int p = 0; p < T::EA; ++p) offa[p] += stepa;
+#pragma unroll
+    for (int p = 0; p < T::EB; ++p) offb[p] += stepb;
+  };
+  auto stash = [&](auto set, int k0, double* st) {
+    constexpr int SET = decltype(set)::value;
     double* sa = st;
     double* sb = st + kGemmBK * T::PA;
 #pragma unroll
@@ -121,7 +139,7 @@ __device__ __forceinline__ void dgemm_mainloop(f64x4 (&acc)[TM][TN], DView A, FA
       const int i = A_KFAST ? e / kGemmBK : e % T::BM;
       const int k = A_KFAST ? e % kGemmBK : e / T::BM;
       const bool ok = ((oka >> p) & 1u) && (k0 + k < kend);
-      const double v = fa(ra[p], i, k0 + k);
+      const double v = fa(ra[SET][p], i, k0 + k);
       sa[k * T::PA + i] = ok ? v : 0.0;
     }
 #pragma unroll
@@ -130,7 +148,7 @@ __device__ __forceinline__ void dgemm_mainloop(f64x4 (&acc)[TM][TN], DView A, FA
       const int j = B_KFAST ? e / kGemmBK : e % T::BN;
       const int k = B_KFAST ? e % kGemmBK : e / T::BN;
       const bool ok = ((okb >> p) & 1u) && (k0 + k < kend);
-      const double v = fb(rb[p], k0 + k, j);
+      const double v = fb(rb[SET][p], k0 + k, j);
       sb[k * T::PB + j] = ok ? v : 0.0;
     }
   };
@@ -148,18 +166,10 @@ __device__ __forceinline__ void dgemm_mainloop(f64x4 (&acc)[TM][TN], DView A, FA
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) part[q][tm][tn] = f64x4{0.0, 0.0, 0.0, 0.0};
   }
-
-  fetch(kbeg);
-  stash(kbeg, smem);
-  if (kbeg + kGemmBK < kend) fetch(kbeg + kGemmBK);
-  __syncthreads();
-  int cur = 0;
-  for (int k0 = kbeg; k0 < kend; k0 += kGemmBK) {
-    const double* sa = smem + cur * T::kStageDoubles;
+  // the MFMAs of the k-tile in LDS stage `stage`
+  auto compute = [&](int stage) {
+    const double* sa = smem + stage * T::kStageDoubles;
     const double* sb = sa + kGemmBK * T::PA;
-    // next tile: registers -> the other LDS stage; tile after next: issue loads
-    if (k0 + kGemmBK < kend) stash(k0 + kGemmBK, smem + (cur ^ 1) * T::kStageDoubles);
-    if (k0 + 2 * kGemmBK < kend) fetch(k0 + 2 * kGemmBK);
     // fragments of k-step kk+1 are read while the MFMAs of k-step kk run (two register sets):
     // with few waves per SIMD nothing else would cover the LDS latency
     double a[2][TM], b[2][TN];
@@ -188,9 +198,60 @@ __device__ __forceinline__ void dgemm_mainloop(f64x4 (&acc)[TM][TN], DView A, FA
       __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);   // the reads of the next k-step first
       __builtin_amdgcn_sched_group_barrier(0x008, TM * TN, 0);   // then this k-step's MFMAs
     }
-    __syncthreads();  // stage cur free for the tile after next, stage cur^1 complete
-    cur ^= 1;
+  };
+
+  // Tile t is computed from LDS stage t % 2 while tile t + 1 goes from register set (t + 1) % D to the
+  // other stage and tile t + 1 + D is requested into the set that has just been emptied.
+  const int ntile = (kend - kbeg + kGemmBK - 1) / kGemmBK, nfull = (kend - kbeg) / kGemmBK;
+  auto k_of = [&](int t) { return kbeg + t * kGemmBK; };
+  using std::integral_constant;
+  // prologue: tile 0 into stage 0, tiles 1 .. D requested
+  fetch(integral_constant<int, 0>{}, k_of(0));
+  stash(integral_constant<int, 0>{}, k_of(0), smem);
+  {
+    auto request = [&](auto dc) {
+      constexpr int d = decltype(dc)::value;   // tile d + 1 into set (d + 1) % D
+      if (d + 1 < ntile) fetch(integral_constant<int, (d + 1) % D>{}, k_of(d + 1));
+    };
+    request(integral_constant<int, 0>{});
+    if constexpr (D > 1) request(integral_constant<int, 1>{});
+    if constexpr (D > 2) request(integral_constant<int, 2>{});
+    if constexpr (D > 3) request(integral_constant<int, 3>{});
+    static_assert(D <= 4, "the prologue is written out for up to four sets");
   }
+  __syncthreads();
+  int t0 = 0;
+  // steady state, D iterations per round, no branch inside: every tile stashed and requested is a full one
+  // (the last request of a round is tile t0 + 2 D)
+  auto round = [&](auto inner) {
+    constexpr bool INNER = decltype(inner)::value;
+    auto iter = [&](auto dc) {
+      constexpr int d = decltype(dc)::value;
+      const int t = t0 + d;
+      using Set = integral_constant<int, (d + 1) % D>;
+      if constexpr (INNER) {
+        stash(Set{}, k_of(t + 1), smem + ((d + 1) & 1) * T::kStageDoubles);
+        fetch_inner(Set{});
+        compute(d & 1);
+        __syncthreads();
+      } else {
+        if (t < ntile) {
+          if (t + 1 < ntile) stash(Set{}, k_of(t + 1), smem + ((t + 1) & 1) * T::kStageDoubles);
+          if (t + 1 + D < ntile) fetch(Set{}, k_of(t + 1 + D));
+          compute(t & 1);
+          __syncthreads();
+        }
+      }
+    };
+    iter(integral_constant<int, 0>{});
+    if constexpr (D > 1) iter(integral_constant<int, 1>{});
+    if constexpr (D > 2) iter(integral_constant<int, 2>{});
+    if constexpr (D > 3) iter(integral_constant<int, 3>{});
+  };
+  if constexpr (D % 2 == 0) {   // (stage parity by d needs an even round)
+    for (; t0 + 2 * D < nfull; t0 += D) round(integral_constant<bool, true>{});
+  }
+  for (; t0 < ntile; t0 += D) round(integral_constant<bool, false>{});
   if constexpr (NS > 1) {
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm)
