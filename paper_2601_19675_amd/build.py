@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libptq.so")
 PROBE_LIB = os.path.join(HERE, "libptq_probe.so")   # diagnostics for bench.py --mfma-control, not part of the product
-SOURCES = ["ptq_api.hip", "hessian.hip", "cholesky.hip", "quantize.hip", "vq.hip", "layer_error.hip", "lopro.hip", "r1svd.hip", "r1svd_bf16.hip", "artifact.hip"]
+SOURCES = ["ptq_api.hip", "hessian.hip", "hessian_f32.hip", "cholesky.hip", "quantize.hip", "vq.hip", "layer_error.hip", "lopro.hip", "r1svd.hip", "r1svd_bf16.hip", "artifact.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-result",
     # packed-FP32 instructions are kept out of every kernel

@@ -90,6 +90,10 @@ size_t hessian_workspace_bytes(int64_t n, int64_t t);
 ptq_status hessian_launch(double* H, int64_t ldh, const void* X, ptq_dtype xdt, int64_t t, int64_t n,
                           int64_t ldx, void* ws, size_t ws_bytes, hipStream_t s);
 
+// main kernel of the float32 case (hessian_f32.hip): float64 partial tiles of 64 or 128 channels squared
+bool hessian_f32_partials_launch(const float* X, int64_t ldx, int64_t t, int n, int64_t tok0, int chunk, int ntb,
+                                 int tile, dim3 grid, double* partial, hipStream_t s);
+
 size_t cholesky_workspace_bytes(int64_t n);
 ptq_status cholesky_launch(const double* H, int64_t ldh, int64_t n, double damp, double* U,
                            int64_t ldu, uint8_t* dead_mask, int32_t* info, void* ws, size_t ws_bytes,

@@ -15,7 +15,8 @@
 // partial tile; a second kernel adds the partial tiles into H in float64 in a
 // fixed order, so the result is bit-reproducible from run to run.
 //
-// f32 path (small layers): float64 FMAs on a 64 x 64 tile, same partial scheme.
+// float32 activations: hessian_f32.hip (float64 matrix cores, 64 x 64 or 128 x 128 tiles), same
+// partial scheme with float64 partial tiles.
 #include <type_traits>
 
 #include "common.h"
@@ -30,7 +31,9 @@ constexpr int kMaxChunk = 8192;      // tokens summed in float32 before the floa
 constexpr int kMaxChunkBig = 20480;  // ... in the 256 x 256-tile kernel (fewer, larger partial tiles)
 constexpr int kMaxChunkHuge = 65536; // ... and once a split alone fills the chip several times over
 
-constexpr int kTile32 = 64;     // f32-path tile
+constexpr int kTile32 = 64;          // float32 activations: tile of narrow layers
+constexpr int kTile32Wide = 128;     // ... and from kWide32From channels on
+constexpr int64_t kWide32From = 1024;
 constexpr int kKT32 = 16;
 
 __device__ __forceinline__ void tile_from_linear(int lin, int ntb, int& I, int& J) {
@@ -422,51 +425,6 @@ __global__ __launch_bounds__(256) void hessian_bf16_big_kernel(const uint16_t* _
     big_tile<false>(X, ldx, t, n, tok0, chunk, I, J, split, out, hs);
 }
 
-// float32 activations: float64 FMAs, 64 x 64 tile, 4 x 4 outputs per thread.
-__global__ __launch_bounds__(256) void hessian_f32_kernel(const float* __restrict__ X, int64_t ldx,
-                                                          int64_t t, int n, int64_t tok0, int chunk,
-                                                          int ntb, double* __restrict__ partial) {
-  __shared__ double As[kKT32][kTile32 + 4];
-  __shared__ double Bs[kKT32][kTile32 + 4];
-  int I, J;
-  tile_from_linear(blockIdx.x, ntb, I, J);
-  const int tid = threadIdx.x;
-  const int ty = tid >> 4, tx = tid & 15;
-  const int64_t kbeg = tok0 + (int64_t)blockIdx.y * chunk;
-  const int64_t kend = (kbeg + chunk < t) ? kbeg + chunk : t;
-  double acc[4][4] = {};
-  for (int64_t k0 = kbeg; k0 < kend; k0 += kKT32) {
-    __syncthreads();
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      const int e = tid + 256 * p;
-      const int kk = e >> 6, c = e & 63;
-      const int64_t k = k0 + kk;
-      const int ca = I * kTile32 + c, cb = J * kTile32 + c;
-      As[kk][c] = (k < kend && ca < n) ? (double)X[k * ldx + ca] : 0.0;
-      Bs[kk][c] = (k < kend && cb < n) ? (double)X[k * ldx + cb] : 0.0;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int kk = 0; kk < kKT32; ++kk) {
-      double av[4], bv[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) av[i] = As[kk][ty * 4 + i];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) bv[j] = Bs[kk][tx * 4 + j];
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = fma(av[i], bv[j], acc[i][j]);
-    }
-  }
-  double* out = partial + ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * (kTile32 * kTile32);
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) out[(ty * 4 + i) * kTile32 + tx * 4 + j] = acc[i][j];
-}
-
 // H[upper] += sum over splits of the partial tiles, in float64, fixed order.  Four consecutive
 // elements of a tile row per thread (TILE is a multiple of 4, so they share the row).
 template <class PT, int TILE>
@@ -510,7 +468,7 @@ bool big_kernel_fits(int64_t ldx) {
 Plan make_plan(int64_t n, int64_t t, ptq_dtype dt, bool allow_big) {
   Plan p;
   const bool big = allow_big && (dt == PTQ_BF16) && n >= kBigFrom;
-  p.tile = (dt == PTQ_BF16) ? (big ? kBT : kTile) : kTile32;
+  p.tile = (dt == PTQ_BF16) ? (big ? kBT : kTile) : (n >= kWide32From ? kTile32Wide : kTile32);
   const int kt = (dt == PTQ_BF16) ? kKT : kKT32;
   p.ntb = (int)ceil_div(n, p.tile);
   p.ntiles = p.ntb * (p.ntb + 1) / 2;
@@ -580,10 +538,15 @@ ptq_status hessian_launch(double* H, int64_t ldh, const void* X, ptq_dtype xdt, 
       hessian_reduce_kernel<float, kTile><<<gr, 256, 0, st>>>(static_cast<const float*>(ws), ns, p.ntiles,
                                                               p.ntb, (int)n, H, ldh);
     } else {
-      hessian_f32_kernel<<<g, 256, 0, st>>>(static_cast<const float*>(X), ldx, t, (int)n, tok0, p.chunk,
-                                            p.ntb, static_cast<double*>(ws));
-      hessian_reduce_kernel<double, kTile32><<<gr, 256, 0, st>>>(static_cast<const double*>(ws), ns,
-                                                                 p.ntiles, p.ntb, (int)n, H, ldh);
+      if (!hessian_f32_partials_launch(static_cast<const float*>(X), ldx, t, (int)n, tok0, p.chunk, p.ntb, p.tile, g,
+                                       static_cast<double*>(ws), st))
+        return PTQ_ERR_HIP;
+      if (p.tile == kTile32Wide)
+        hessian_reduce_kernel<double, kTile32Wide><<<gr, 256, 0, st>>>(static_cast<const double*>(ws), ns,
+                                                                       p.ntiles, p.ntb, (int)n, H, ldh);
+      else
+        hessian_reduce_kernel<double, kTile32><<<gr, 256, 0, st>>>(static_cast<const double*>(ws), ns,
+                                                                   p.ntiles, p.ntb, (int)n, H, ldh);
     }
   }
   PTQ_HIP_CHECK_LAUNCH();

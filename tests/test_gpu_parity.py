@@ -73,6 +73,7 @@ def _correlated_x(rng, t, n, corr=0.8):
     ("bf16", 3000, 2304), ("bf16", 20000 + 5, 2056),      # wide layers: the 256 x 256-tile kernel
     ("bf16", 50, 2048), ("bf16", 1, 2048), ("bf16", 129, 2560),   # ... with fewer tokens than its LDS ring holds
     ("f32", 2048, 512), ("f32", 333, 70), ("f32", 5, 1),
+    ("f32", 1500, 1024), ("f32", 9000 + 3, 1300),          # from 1024 channels on: 128 x 128 tiles, here ragged, two chunks
 ])
 def test_hessian_matches_oracle(dtype, t, n):
     spec = wl.LayerSpec("h", 16, n, t, dtype=dtype, x_sigma=1.5, layer_id=900 + n)
