@@ -510,6 +510,48 @@ def time_layers(layers, steps, warmup):
     return 1e3 * elapsed / steps, phases
 
 
+def time_block_two_streams(layers, ws_hessian, steps, warmup):
+    """The block's layers with the Hessian calls on a stream of their own (both streams at the default
+    priority): layer k+1's Hessian runs beside factor, solve and layer error of layer k, whose chain of
+    small launches leaves most of the chip idle.  A layer's factor waits for its Hessian; a pass starts
+    only when the previous pass has ended (a block is timed as a unit, no overlap from block to block).
+    `ws_hessian`: a workspace of the Hessian calls' own, the other calls keep the layers' shared one.
+    Returns ms per pass by the host clock around synchronised ends."""
+    import torch
+    s_h, s_r = torch.cuda.Stream(), torch.cuda.Stream()
+    ready = [torch.cuda.Event() for _ in layers]
+    block_done = torch.cuda.Event()
+
+    def one_pass():
+        s_h.wait_event(block_done)
+        for L, ev in zip(layers, ready):
+            with torch.cuda.stream(s_h):
+                L.H.zero_()
+                L.ptq.ptq_hessian_accumulate(L.H, L.X, ws_hessian)
+                ev.record(s_h)
+            with torch.cuda.stream(s_r):
+                s_r.wait_event(ev)
+                L.ptq.ptq_damped_cholesky_inv(L.H, L.damp, L.U, L.dead, L.info, L.ws)
+                L.ptq.ptq_quantize_layer(L.W, L.U, L.dead, L.cfg.bits, L.cfg.group, L.cfg.block, L.codes, L.scales,
+                                         L.zeros, L.Wq, L.err2, L.ws)
+                L.ptq.ptq_layer_error(L.W, L.Wq, L.H, L.out, L.ws)
+        block_done.record(s_r)
+
+    torch.cuda.synchronize()
+    block_done.record(s_r)
+    for _ in range(warmup):
+        one_pass()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        one_pass()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    for L in layers:
+        assert L.info.cpu().tolist() == [0, 0], "factorization failed"
+    return 1e3 * elapsed / steps
+
+
 def layer_numbers(L, phase):
     """Rates of one layer's four calls from their event-bracketed times."""
     m, n, t, cfg, spec = L.m, L.n, L.t, L.cfg, L.spec
@@ -585,6 +627,9 @@ def main():
                          "rank-16 low-rank part) and report it under \"forward\"")
     ap.add_argument("--calls-alone", action="store_true",
                     help="also time each of the four calls alone, back to back (phases_alone_ms)")
+    ap.add_argument("--one-stream", action="store_true",
+                    help="with --config C5: only the one-stream passes (by default the block is then timed again with "
+                         "the Hessian calls on a second stream, and that time is the reported one)")
     ap.add_argument("--mfma-control", action="store_true",
                     help="also run the controls behind the Hessian roofline: register-only MFMA loops (bfloat16 and "
                          "float64, benign and random operand bits, shader clock read in the kernel) and the Hessian "
@@ -636,6 +681,16 @@ def main():
         L.ws = ws
     log("timing")
     ms, phases = time_layers(layers, args.steps, args.warmup)
+    ms_one_stream = None
+    if block_mode and not args.one_stream:
+        # the same passes again with the Hessian calls on a second stream; the per-call times above are from
+        # the one-stream passes, where calls do not overlap
+        one_stream_out = [float(Li.out[0]) for Li in layers]
+        ws_h = torch.empty(max(ptq.ptq_workspace_bytes(0, Li.m, Li.n, Li.t, cfg.block) for Li in layers),
+                           dtype=torch.uint8, device="cuda")
+        ms_one_stream, ms = ms, time_block_two_streams(layers, ws_h, args.steps, args.warmup)
+        assert [float(Li.out[0]) for Li in layers] == one_stream_out, "the two-stream pass changed a result"
+        del ws_h
     total_cols = sum(L.n for L in layers)
     # the layer whose Hessian call is the longest carries the roofline object (a block: the down projection)
     dom = max(range(len(layers)), key=lambda i: phases[i][0])
@@ -669,6 +724,9 @@ def main():
     }
     result["rooflines_other_calls"] = nums["rooflines_other_calls"]
     if block_mode:
+        result["streams"] = 1 if ms_one_stream is None else 2
+        if ms_one_stream is not None:
+            result["ms_per_step_one_stream"] = ms_one_stream
         result["layers"] = [dict(name=Li.spec.name, m=Li.m, n=Li.n, rel_layer_error=float(Li.out[0]),
                                  **{k: v for k, v in layer_numbers(Li, ph).items()
                                     if k in ("phases_ms", "hessian_pct_mfma_peak", "solve_columns_per_s")})

@@ -18,7 +18,7 @@
  *     ptq_workspace_bytes() returns; the library allocates no device memory,
  *     keeps no data between calls and never frees anything.  (What it does keep,
  *     per device and for the life of the process: kernel attributes it has set,
- *     and one helper stream with a few events that ptq_damped_cholesky_inv
+ *     and two helper streams with a few events that ptq_damped_cholesky_inv
  *     creates on its first call for a wide factor (from about 5800 columns).)
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
  *     default stream) and the call returns without waiting for it.
@@ -113,7 +113,7 @@ ptq_status ptq_hessian_accumulate(double* H, int64_t ldh, const void* X, ptq_dty
  *            {PTQ_ERR_NOT_SPD, j} when the pivot of column j (in the order of
  *            elimination, j counted in H's own indexing) was not positive;
  *            U is then undefined.
- * For the largest factors one step of a node's work runs on the library's helper stream
+ * For the largest factors two parts of a node's work run on the library's two helper streams
  * beside the rest (forked from and joined back into `stream` with events, so to the caller the
  * call is ordered on `stream` like any other, also under stream capture); calls from several
  * host threads on one device are serialised on a lock while they enqueue.

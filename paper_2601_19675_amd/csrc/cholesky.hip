@@ -23,6 +23,7 @@
 #include "dgemm.h"
 
 #include <atomic>
+#include <functional>
 #include <mutex>
 
 namespace ptq {
@@ -495,30 +496,33 @@ struct Node {
   double* U;      // output, X reversed: X(i, j) = U[n-1-i][n-1-j]
   int ldu;
   int n, o, s1, s2;
+  int r;          // first row of the second block: o + s1, except for the early part of a panel or an update
+                  // (see recurse), whose k range [o, o + s1) ends before the second block begins
   __device__ __forceinline__ const double* g(int i, int j) const { return G + (int64_t)i * n + j; }
   __device__ __forceinline__ const double* x(int i, int j) const {
     return U + (int64_t)(n - 1 - i) * ldu + (n - 1 - j);
   }
 };
 
-// L21 = G21 X11^T, stored transposed in the mirror block of G.
+// L21 = G21 X11^T, stored transposed in the mirror block of G; columns [c0, s1) of it.
 struct OpPanel {
   static constexpr bool A_KFAST = true, B_KFAST = true;
   static constexpr int K_ORDER = +2;  // k range grows with the column tile: last column tile first
   static constexpr bool LOWER_ONLY = false;
   Node nd;
+  int c0;
   __device__ int M() const { return nd.s2; }
-  __device__ int N() const { return nd.s1; }
+  __device__ int N() const { return nd.s1 - c0; }
   __device__ bool active(int, int, int, int) const { return true; }
-  __device__ void krange(int, int, int, int j1, int& kb, int& ke) const { kb = 0; ke = min(nd.s1, j1); }
-  __device__ DView a(int i0) const { return DView{nd.g(nd.o + nd.s1 + i0, nd.o), nd.n, 1}; }
-  __device__ DView b(int j0) const { return DView{nd.x(nd.o + j0, nd.o), -nd.ldu, -1}; }  // X11(j, k)
+  __device__ void krange(int, int, int, int j1, int& kb, int& ke) const { kb = 0; ke = min(nd.s1, c0 + j1); }
+  __device__ DView a(int i0) const { return DView{nd.g(nd.r + i0, nd.o), nd.n, 1}; }
+  __device__ DView b(int j0) const { return DView{nd.x(nd.o + c0 + j0, nd.o), -nd.ldu, -1}; }  // X11(j, k)
   __device__ void store(int i, int j, double v) const {
-    if (i < nd.s2 && j < nd.s1) nd.G[(int64_t)(nd.o + j) * nd.n + nd.o + nd.s1 + i] = v;
+    if (i < nd.s2 && j < nd.s1 - c0) nd.G[(int64_t)(nd.o + c0 + j) * nd.n + nd.r + i] = v;
   }
 };
 
-// G22 -= L21 L21^T on the lower triangle.
+// G22 -= L21 L21^T on the lower triangle (k over the node's columns [o, o + s1)).
 struct OpSyrk {
   static constexpr bool A_KFAST = false, B_KFAST = false;
   static constexpr int K_ORDER = 0;   // every active tile has the full k range
@@ -528,10 +532,10 @@ struct OpSyrk {
   __device__ int N() const { return nd.s2; }
   __device__ bool active(int, int i1, int j0, int) const { return i1 > j0; }
   __device__ void krange(int, int, int, int, int& kb, int& ke) const { kb = 0; ke = nd.s1; }
-  __device__ DView a(int i0) const { return DView{nd.g(nd.o, nd.o + nd.s1 + i0), 1, nd.n}; }  // L21(i, k)
-  __device__ DView b(int j0) const { return DView{nd.g(nd.o, nd.o + nd.s1 + j0), 1, nd.n}; }  // L21(j, k)
+  __device__ DView a(int i0) const { return DView{nd.g(nd.o, nd.r + i0), 1, nd.n}; }  // L21(i, k)
+  __device__ DView b(int j0) const { return DView{nd.g(nd.o, nd.r + j0), 1, nd.n}; }  // L21(j, k)
   __device__ void store(int i, int j, double v) const {
-    if (i < nd.s2 && j <= i) nd.G[(int64_t)(nd.o + nd.s1 + i) * nd.n + nd.o + nd.s1 + j] -= v;
+    if (i < nd.s2 && j <= i) nd.G[(int64_t)(nd.r + i) * nd.n + nd.r + j] -= v;
   }
 };
 
@@ -611,6 +615,11 @@ __device__ __forceinline__ void node_gemm_tile(const Op& op, int lin, int gx, in
     bj = lin - q * gx;
     bi = Op::K_ORDER > 0 ? gy - 1 - q : q;
   }
+  // the tile is the same for every lane; said explicitly, because a buffer descriptor that the compiler takes for
+  // lane-dependent is loaded through a loop over its distinct values around every request of the k loop
+  // (the lower-triangle search above ended up so in the 128 x 128-tile update)
+  bi = __builtin_amdgcn_readfirstlane(bi);
+  bj = __builtin_amdgcn_readfirstlane(bj);
   const int i0 = bi * T::BM, j0 = bj * T::BN;
   const int i1 = min(i0 + T::BM, op.M()), j1 = min(j0 + T::BN, op.N());
   if (!op.active(i0, i1, j0, j1)) return;
@@ -723,22 +732,33 @@ bool launch_node2(const Op1& op1, int M1, int N1, const Op2& op2, int M2, int N2
   }
 }
 
-// ---- a second stream for work that is off the critical chain ---------------------------------
-// After the trailing update of a node the chain  leaf -> panel -> update -> leaf ...  of its second
-// half is a sequence of small, latency-bound launches that leaves most of the chip idle, while
-// T = L21 X11  of the node (a quarter of its flops) is needed only by the node's last step.  For the
-// largest nodes (128 x 128 tiles) T therefore runs on a helper stream, forked after the update and
-// joined before  X21 = -X22 T,  with at most kSideCus workgroups, so that the launches of the chain
-// always find free compute units (measured at n = 11008: 128 gives the shortest total; 256 gains
-// nothing, 64 makes T the longer path).  Smaller nodes gain nothing (measured) and keep T in the
-// update's launch.  One helper stream and a few events per device, created on first use and kept
-// for the life of the process (default priority).
+// ---- helper streams for work that is off the critical chain -----------------------------------
+// The chain  leaf -> panel -> update -> leaf ...  of a half of a node is a sequence of small,
+// latency-bound launches that leaves most of the chip idle.  For the largest nodes (128 x 128 tiles)
+// two pieces of the node's own work run beside those chains, each on a stream of its own with a cap
+// on its workgroups, so that the chain's launches always find free compute units:
+//  * beside the chain of the SECOND half:  T = L21 X11  (a quarter of the node's flops), which is
+//    needed only by the node's last step -- forked after the trailing update, joined before
+//    X21 = -X22 T  (cap kSideCus; measured at n = 11008: 128 gives the shortest total, 256 gains
+//    nothing, 64 makes T the longer path);
+//  * beside the second half of the FIRST half's recursion:  the early part of the node's panel and
+//    update.  Once the first half A = [o, o + sA) of the first child is inverted, the columns
+//    [0, sA) of L21 = G21 X11^T are computable (X11 is lower triangular: they need X_A only), and so
+//    is their share  G22 -= L21[:, :sA] L21[:, :sA]^T  of the update.  The child signals that point
+//    (`on_first_half`), the early part runs on its stream, and after the child the node finishes
+//    the panel (columns [sA, s1)) and the update (k in [sA, s1)) on the caller's stream (cap
+//    kEarlyCus; n = 11008: 18.0 ms without, 17.9 / 17.4 / 17.5 / 17.6 ms with 128 / 160 / 192 / 224;
+//    n = 8192: 9.49 without, 9.04 / 8.95 with 128 / 192).
+// Smaller nodes gain nothing (measured) and keep one stream, with T in the update's launch.  The
+// streams and a few events per device are created on first use and kept for the life of the
+// process (default priority).
 constexpr int kSideCus = 128;
+constexpr int kEarlyCus = 192;
 constexpr int kMaxDepth = 12;
 struct Side {
   std::mutex lock;   // the events are reused call after call: one caller at a time enqueues a factor
-  hipStream_t stream = nullptr;
-  hipEvent_t fork[kMaxDepth], join[kMaxDepth];
+  hipStream_t stream = nullptr, early_stream = nullptr;
+  hipEvent_t fork[kMaxDepth], join[kMaxDepth], early_fork[kMaxDepth], early_join[kMaxDepth];
   bool ok = false;
 };
 
@@ -751,10 +771,13 @@ Side* side_for_device() {
   int expected = 0;
   if (state[dev].compare_exchange_strong(expected, 1)) {
     Side& sd = sides[dev];
-    bool ok = hipStreamCreateWithFlags(&sd.stream, hipStreamNonBlocking) == hipSuccess;
+    bool ok = hipStreamCreateWithFlags(&sd.stream, hipStreamNonBlocking) == hipSuccess &&
+              hipStreamCreateWithFlags(&sd.early_stream, hipStreamNonBlocking) == hipSuccess;
     for (int d = 0; ok && d < kMaxDepth; ++d)
       ok = hipEventCreateWithFlags(&sd.fork[d], hipEventDisableTiming) == hipSuccess &&
-           hipEventCreateWithFlags(&sd.join[d], hipEventDisableTiming) == hipSuccess;
+           hipEventCreateWithFlags(&sd.join[d], hipEventDisableTiming) == hipSuccess &&
+           hipEventCreateWithFlags(&sd.early_fork[d], hipEventDisableTiming) == hipSuccess &&
+           hipEventCreateWithFlags(&sd.early_join[d], hipEventDisableTiming) == hipSuccess;
     sd.ok = ok;
     state[dev].store(ok ? 2 : 3, std::memory_order_release);
   }
@@ -763,21 +786,42 @@ Side* side_for_device() {
   return state[dev].load(std::memory_order_acquire) == 2 ? &sides[dev] : nullptr;
 }
 
-bool recurse(double* G, double* U, int ldu, int n, int o, int s, int32_t* info, hipStream_t st, Side* side, int depth) {
+inline int first_part(int s) { return ((int)ceil_div(s, kLeaf) / 2) * kLeaf; }
+
+// `on_first_half`, if given, is called (on the host) right after the launches that invert the first half of
+// this block have been enqueued on st.
+bool recurse(double* G, double* U, int ldu, int n, int o, int s, int32_t* info, hipStream_t st, Side* side, int depth,
+             const std::function<bool()>* on_first_half = nullptr) {
   if (s <= kLeaf) {
     leaf_kernel<<<1, kLeafThreads, kLeafLdsBytes, st>>>(G, n, o, s, U, ldu, info);
     return true;
   }
-  const int nb = (int)ceil_div(s, kLeaf);
-  const int s1 = (nb / 2) * kLeaf;
+  const int s1 = first_part(s);
   const int s2 = s - s1;
-  Node nd{G, U, ldu, n, o, s1, s2};
-  if (!recurse(G, U, ldu, n, o, s1, info, st, side, depth + 1) || !launch_node(OpPanel{nd}, s2, s1, st)) return false;
-  // the trailing update and T = L21 X11 both need only L21 and touch different blocks
+  const Node nd{G, U, ldu, n, o, s1, s2, o + s1};
   if (side && depth < kMaxDepth && tile_class(s2, s1) == 2) {
-    // a large node: the trailing update first, with the whole chip; then T beside the chain of the
-    // second half (fork after the update, join before X21)
-    if (!launch_node(OpSyrk{nd}, s2, s2, st)) return false;
+    // a large node.  Early part: beside the second half of the first child's recursion
+    const int sA = s1 > kLeaf ? first_part(s1) : 0;
+    const bool early = sA > 0 && tile_class(s2, sA) == 2;
+    const std::function<bool()> start_early = [&]() -> bool {
+      const Node part{G, U, ldu, n, o, sA, s2, o + s1};
+      return hipEventRecord(side->early_fork[depth], st) == hipSuccess &&
+             hipStreamWaitEvent(side->early_stream, side->early_fork[depth], 0) == hipSuccess &&
+             launch_node(OpPanel{part, 0}, s2, sA, side->early_stream, kEarlyCus) &&
+             launch_node(OpSyrk{part}, s2, s2, side->early_stream, kEarlyCus) &&
+             hipEventRecord(side->early_join[depth], side->early_stream) == hipSuccess;
+    };
+    if (!recurse(G, U, ldu, n, o, s1, info, st, side, depth + 1, early ? &start_early : nullptr)) return false;
+    if (on_first_half && !(*on_first_half)()) return false;
+    if (early) {
+      const Node rest{G, U, ldu, n, o + sA, s1 - sA, s2, o + s1};
+      if (hipStreamWaitEvent(st, side->early_join[depth], 0) != hipSuccess ||
+          !launch_node(OpPanel{nd, sA}, s2, s1 - sA, st) || !launch_node(OpSyrk{rest}, s2, s2, st))
+        return false;
+    } else if (!launch_node(OpPanel{nd, 0}, s2, s1, st) || !launch_node(OpSyrk{nd}, s2, s2, st)) {
+      return false;
+    }
+    // T beside the chain of the second half (fork after the update, join before X21)
     if (hipEventRecord(side->fork[depth], st) != hipSuccess ||
         hipStreamWaitEvent(side->stream, side->fork[depth], 0) != hipSuccess)
       return false;
@@ -787,7 +831,10 @@ bool recurse(double* G, double* U, int ldu, int n, int o, int s, int32_t* info, 
     if (hipStreamWaitEvent(st, side->join[depth], 0) != hipSuccess) return false;
     return launch_node(OpX21{nd}, s2, s1, st);
   }
-  return launch_node2(OpSyrk{nd}, s2, s2, OpT{nd}, s2, s1, st) &&
+  if (!recurse(G, U, ldu, n, o, s1, info, st, side, depth + 1)) return false;
+  if (on_first_half && !(*on_first_half)()) return false;
+  // the trailing update and T = L21 X11 both need only L21 and touch different blocks
+  return launch_node(OpPanel{nd, 0}, s2, s1, st) && launch_node2(OpSyrk{nd}, s2, s2, OpT{nd}, s2, s1, st) &&
          recurse(G, U, ldu, n, o + s1, s2, info, st, side, depth + 1) && launch_node(OpX21{nd}, s2, s1, st);
 }
 
@@ -812,7 +859,7 @@ ptq_status cholesky_launch(const double* H, int64_t ldh, int64_t n, double damp,
   build_work_kernel<<<g, 256, 0, st>>>(H, ldh, (int)n, scal, G, U, ldu);
   PTQ_HIP_CHECK_LAUNCH();
   // the helper stream only where a node is large enough to use it (the top node is the largest)
-  const int top1 = (int)(ceil_div(n, kLeaf) / 2) * kLeaf;
+  const int top1 = first_part((int)n);
   Side* side = (n > kLeaf && tile_class((int)n - top1, top1) == 2) ? side_for_device() : nullptr;
   bool ok;
   if (side) {
