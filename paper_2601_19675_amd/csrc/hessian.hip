@@ -18,6 +18,7 @@
 // float32 activations: hessian_f32.hip (float64 matrix cores, 64 x 64 or 128 x 128 tiles), same
 // partial scheme with float64 partial tiles.
 #include <type_traits>
+#include <utility>
 
 #include "common.h"
 
@@ -187,12 +188,32 @@ __device__ __forceinline__ void dma16(i32x4 rsrc, uint32_t voff, uint32_t ldsadd
   asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(ldsaddr), "v"(voff), "s"(rsrc)
                : "memory", "m0");
 }
+
+// The same with the LDS address as a scalar base plus a compile-time offset: one scalar instruction per request
+// instead of an add into a temporary and a move.
+template <uint32_t OFFSET>
+__device__ __forceinline__ void dma16_at(i32x4 rsrc, uint32_t voff, uint32_t ldsbase) {
+  asm volatile("s_add_u32 m0, %0, %3\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(ldsbase), "v"(voff), "s"(rsrc),
+               "n"(OFFSET)
+               : "memory", "m0", "scc");
+}
+
 #pragma clang diagnostic pop
 
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
   // s_waitcnt vmcnt(N); the other counters at their maximum (no wait)
   __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0f70);
+}
+
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>)
+template <class F, int... Is>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, Is...>) {
+  (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
 
 template <bool diag>
@@ -224,13 +245,13 @@ __device__ __forceinline__ void big_tile(const uint16_t* __restrict__ X, int64_t
 
     // descriptor over the chunk's tokens (uniform, kept in scalar registers)
     const uint64_t gb0 = (uint64_t)(X + kbeg * ldx);
-    const i32x4 rs = {(int)__builtin_amdgcn_readfirstlane((uint32_t)gb0),
-                      (int)__builtin_amdgcn_readfirstlane((uint32_t)(gb0 >> 32)),
-                      (int)__builtin_amdgcn_readfirstlane((uint32_t)(len * ldx * 2)),  // bytes, < 2^32 (host)
-                      0x00020000};
-    const uint32_t stage_step = (uint32_t)(kBKS * ldx * 2);
+    i32x4 rs = {(int)__builtin_amdgcn_readfirstlane((uint32_t)gb0),
+                (int)__builtin_amdgcn_readfirstlane((uint32_t)(gb0 >> 32)),
+                (int)__builtin_amdgcn_readfirstlane((uint32_t)(len * ldx * 2)),  // bytes, < 2^32 (host)
+                0x00020000};
+    const uint32_t stage_step = __builtin_amdgcn_readfirstlane((uint32_t)(kBKS * ldx * 2));
 
-    // per-lane byte offsets of the four DMA instructions of a part; they advance by a stage
+    // per-lane byte offsets of the four DMA instructions of a part, inside a stage (the descriptor advances)
     uint32_t voA[4], voB[4];
     {
       const int pos = lane & 31;
@@ -269,12 +290,17 @@ __device__ __forceinline__ void big_tile(const uint16_t* __restrict__ X, int64_t
       if (q < 4) dma16(rs, voA[q], dst + q * 4096);
       else dma16(rs, voB[q - 4], dst + kBPart + (q - 4) * 4096);
     };
+    // One stage on: the descriptor moves (base up, extent down, never below zero -- past the end of the chunk every
+    // lane is out of range and delivers zeros), the per-lane offsets stay.  Scalar work, where advancing the
+    // eight per-lane offsets costs the wave eight vector instructions per stage.
     auto dma_advance = [&]() {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        voA[i] += stage_step;
-        voB[i] += stage_step;
-      }
+      const uint64_t base = (((uint64_t)(uint32_t)rs[1] << 32) | (uint32_t)rs[0]) + stage_step;
+      const uint32_t extent = (uint32_t)rs[2];
+      // (readfirstlane: the compiler forms the saturating difference in a vector register, and the descriptor
+      // operand of the requests has to be scalar)
+      rs[0] = (int)__builtin_amdgcn_readfirstlane((uint32_t)base);
+      rs[1] = (int)__builtin_amdgcn_readfirstlane((uint32_t)(base >> 32));
+      rs[2] = (int)__builtin_amdgcn_readfirstlane(extent > stage_step ? extent - stage_step : 0u);
     };
     // 16 MFMAs on (fa, fb) while the next fragments (na, nb) are read at `so`.  L/2 DMA
     // instructions, q0 onwards, go between the four groups of four MFMAs: issued in one
@@ -324,8 +350,61 @@ __device__ __forceinline__ void big_tile(const uint16_t* __restrict__ X, int64_t
     // those DMA instructions is spread over the second half of iteration s, the rest over the
     // first half of iteration s + 1.  In issue order the requests outstanding at the barrier are
     // those of stages s+1, s+2, s+3, and stage s+1 is the one that must have landed.
+    // The same half with the ring slot known at compile time: SO (LDS offset of the tokens to read) folds into the
+    // immediate offset of the LDS reads -- from a second set of per-lane addresses, 64 KB further on, for the upper
+    // two slots, since the immediate has 16 bits -- and DST (slot being refilled) into the immediate of the request's
+    // scalar add.  With a run-time slot every pair of reads and every request needs an add of its own, and this
+    // loop is bound by what a wave issues besides its MFMAs.
+    uint32_t hiA[4], hiB[4];
+#pragma unroll
+    for (int T = 0; T < 4; ++T) {
+      hiA[T] = adA[T] + 65536u;
+      hiB[T] = adB[T] + 65536u;
+      // (opaque to the compiler, or it forms them again before every use instead of keeping eight registers)
+      asm volatile("" : "+v"(hiA[T]), "+v"(hiB[T]));
+    }
+    const uint32_t wbase = lbase + wave * 1024;
+    auto half_at = [&](auto role, auto so_, auto q0_, auto dst_, const bf16x8 (&fa)[4], const bf16x8 (&fb)[4],
+                       bf16x8 (&na)[4], bf16x8 (&nb)[4]) {
+      constexpr int ROLE = decltype(role)::value;
+      constexpr uint32_t SO = decltype(so_)::value, DST = decltype(dst_)::value;
+      constexpr int Q0 = decltype(q0_)::value;
+      constexpr bool HI = SO >= 65536u;
+      constexpr uint32_t so = HI ? SO - 65536u : SO;
+      static_for<4>([&](auto g_) {
+        constexpr int g = decltype(g_)::value;
+        if constexpr (ROLE != 2) {
+          na[g] = read_one(so + (HI ? hiA[g] : adA[g]));
+          nb[g] = read_one(so + (HI ? hiB[g] : adB[g]));
+#pragma unroll
+          for (int b = (ROLE == 1 ? g : 0); b < 4; ++b)
+            acc[g][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[g], fb[b], acc[g][b], 0, 0, 0);
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+          __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);  // DS read
+          if (ROLE == 0 || g < 3) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+          if (ROLE == 0 || g < 2) __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (L == 8 || (g & 1)) {
+          constexpr int q = (L == 8) ? Q0 + g : Q0 + (g >> 1);
+          if constexpr (q < 4) dma16_at<DST + q * 4096>(rs, voA[q], wbase);
+          else dma16_at<DST + kBPart + (q - 4) * 4096>(rs, voB[q - 4], wbase);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      });
+    };
+
+    // Iteration s: tokens 0..15 of stage s | barrier | tokens 16..31.  At the barrier every wave
+    // has finished reading stage s, so its slot is refilled with stage s + 4: the first half of
+    // those DMA instructions is spread over the second half of iteration s, the rest over the
+    // first half of iteration s + 1.  In issue order the requests outstanding at the barrier are
+    // those of stages s+1, s+2, s+3, and stage s+1 is the one that must have landed.
+    // Four iterations per trip of the loop, one per ring slot; what is left over (the number of stages
+    // is not a multiple of four) takes the form with a run-time slot.
     auto main_loop = [&](auto role) {
       constexpr int ROLE = decltype(role)::value;
+      using std::integral_constant;
       bf16x8 fa0[4], fb0[4], fa1[4], fb1[4];
       if (ROLE != 2) {
 #pragma unroll
@@ -334,7 +413,28 @@ __device__ __forceinline__ void big_tile(const uint16_t* __restrict__ X, int64_t
           fb0[T] = read_one(adB[T]);
         }
       }
-      for (int s = 0; s < nstage; ++s) {
+      auto iteration_at = [&](auto slot_) {
+        constexpr uint32_t SLOT = decltype(slot_)::value;
+        constexpr uint32_t slot_off = SLOT * kBStage, pend_off = ((SLOT + kBRing - 1) & (kBRing - 1)) * kBStage,
+                           next_off = ((SLOT + 1) & (kBRing - 1)) * kBStage;
+        half_at(role, integral_constant<uint32_t, slot_off + 16 * kBRow>{}, integral_constant<int, L / 2>{},
+                integral_constant<uint32_t, pend_off>{}, fa0, fb0, fa1, fb1);
+        dma_advance();
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        wait_vmcnt<2 * L>();
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        half_at(role, integral_constant<uint32_t, next_off>{}, integral_constant<int, 0>{},
+                integral_constant<uint32_t, slot_off>{}, fa1, fb1, fa0, fb0);
+      };
+      int s = 0;
+      for (; s + kBRing <= nstage; s += kBRing) {
+        iteration_at(integral_constant<uint32_t, 0>{});
+        iteration_at(integral_constant<uint32_t, 1>{});
+        iteration_at(integral_constant<uint32_t, 2>{});
+        iteration_at(integral_constant<uint32_t, 3>{});
+      }
+      for (; s < nstage; ++s) {
         const uint32_t slot_off = (s & (kBRing - 1)) * kBStage;
         const uint32_t pend_off = ((s + kBRing - 1) & (kBRing - 1)) * kBStage;
         const uint32_t next_off = ((s + 1) & (kBRing - 1)) * kBStage;
