@@ -59,8 +59,7 @@ struct QuantArgs {
 // panel of U serves up to 48 rows and the serial column walk (one lane per row, one wave whatever
 // the height) is shared by them.
 template <int DT, int NT, int MT>
-__global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
-  extern __shared__ double lds[];
+__device__ __forceinline__ void quant_block(const QuantArgs& a, double* lds) {
   constexpr int kRows = kRowTile * MT;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -635,6 +634,36 @@ __global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
   }
 }
 
+template <int DT, int NT, int MT>
+__global__ __launch_bounds__(kThreads) void quant_block_kernel(QuantArgs a) {
+  extern __shared__ double lds[];
+  quant_block<DT, NT, MT>(a, lds);
+}
+
+// All blocks of a layer in one launch: a workgroup's rows depend on no other workgroup's, so it walks the blocks at
+// its own pace (a launch per block makes every workgroup wait for the slowest one of every block).  What a block
+// leaves in global memory for the next ones -- its errors, the running row sums -- is written and read by the same
+// workgroup, hence the same compute unit and cache: a workgroup barrier between blocks orders it.
+template <int DT, int NT, int MT>
+__global__ __launch_bounds__(kThreads) void quant_layer_kernel(QuantArgs a, int block) {
+  extern __shared__ double lds[];
+  for (int i1 = 0; i1 < a.n; i1 += block) {
+    QuantArgs b = a;
+    b.i1 = i1;
+    b.bw = (a.n - i1 < block) ? a.n - i1 : block;
+    // With several row tiles the arguments are made opaque per block: what the compiler would otherwise compute
+    // once for all blocks and keep -- per-lane offsets into U, the errors, the outputs -- costs more registers than
+    // the kernel has (measured, 8192 x 4096: 3.09 ms opaque, 3.24 not, 3.38 with a launch per block).  With one row
+    // tile keeping them pays (4096 x 11008: 9.93 ms against 10.52 opaque and 10.19 with a launch per block).
+    if constexpr (MT > 1) {
+      asm volatile("" : "+s"(b.U), "+s"(b.errT), "+s"(b.W), "+s"(b.Wq), "+s"(b.codes), "+s"(b.mpad), "+s"(b.n));
+      asm volatile("" : "+s"(b.invd), "+s"(b.dead), "+s"(b.scales), "+s"(b.zeros), "+s"(b.ldu), "+s"(b.ldw), "+s"(b.m));
+    }
+    quant_block<DT, NT, MT>(b, lds);
+    __syncthreads();
+  }
+}
+
 size_t block_lds_bytes(int mt, int bw) {
   const int rows = kRowTile * mt;
   return (size_t)(state_doubles(mt, bw) + 16 * rows + 16 * (rows + 1) + 512 + 32 + 2 * rows) * sizeof(double) +
@@ -649,8 +678,24 @@ ptq_status launch_block(const QuantArgs& a, hipStream_t st) {
   return PTQ_OK;
 }
 
+template <int DT, int NT, int MT>
+ptq_status launch_layer(const QuantArgs& a, int block, hipStream_t st) {
+  const unsigned wgs = (unsigned)ceil_div(a.m, kRowTile * MT);
+  if (!lds_opt_in<quant_layer_kernel<DT, NT, MT>>((int)block_lds_bytes(MT, 16 * NT))) return PTQ_ERR_HIP;
+  quant_layer_kernel<DT, NT, MT><<<wgs, kThreads, block_lds_bytes(MT, block), st>>>(a, block);
+  return PTQ_OK;
+}
+
 template <int DT, int MT>
 ptq_status run_blocks(QuantArgs a, int block, hipStream_t st) {
+  // one launch for the layer; blocks wider than 128 columns (the 16-tile instantiation is short of registers as it
+  // is) keep a launch per block
+  if (block <= 128) {
+    const int nt = block / 16;
+    if (nt <= 2) return launch_layer<DT, 2, MT>(a, block, st);
+    if (nt <= 4) return launch_layer<DT, 4, MT>(a, block, st);
+    return launch_layer<DT, 8, MT>(a, block, st);
+  }
   for (int i1 = 0; i1 < a.n; i1 += block) {
     a.i1 = i1;
     a.bw = (a.n - i1 < block) ? a.n - i1 : block;
