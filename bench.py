@@ -39,7 +39,7 @@ HBM_GBPS = 8000.0
 # workloads that were not profiled.
 MEASURED_TRAFFIC_BYTES = {
     "C2:attn_proj": (3.483e6 * 2048 + 5.222e5 * 1024, "profiles/hessian_C2_hbm_traffic.txt"),
-    "C3:down_proj": (3.491e7 * 2048 + 1.050e6 * 1024, "profiles/hessian_C3_down_hbm_traffic.txt"),
+    "C3:down_proj": (3.565e7 * 2048 + 1.050e6 * 1024, "profiles/hessian_C3_down_hbm_traffic.txt"),
 }
 
 
